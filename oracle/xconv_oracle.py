@@ -1,0 +1,217 @@
+"""ctypes front end of the CPU oracle (oracle/xconv_oracle.c).
+
+TEST INFRASTRUCTURE ONLY.  Only tests/, __graft_entry__.smoke() and the
+cpu_baseline leg of bench.py may import this module.  It holds no arithmetic of
+its own: every function marshals numpy arrays into the C routine of the same
+name, where the paper's formulas are written out (Sec. 3 Eq. (2), (3), (5),
+(6); Algorithm 1).
+
+Array conventions: float32 inputs whose values are already representable in
+the storage type; gradients come back as float64.
+dtype codes: 0 fp32, 1 bf16, 2 fp16.  dist codes: 0 Rademacher, 1 Gaussian.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_LIB = None
+
+F32, BF16, F16 = 0, 1, 2
+RADEMACHER, GAUSSIAN = 0, 1
+
+_c_f32p = ctypes.POINTER(ctypes.c_float)
+_c_f64p = ctypes.POINTER(ctypes.c_double)
+_c_i32p = ctypes.POINTER(ctypes.c_int32)
+
+
+def lib():
+    global _LIB
+    if _LIB is None:
+        path = _build.LIB
+        if not os.path.exists(path) or os.path.getmtime(path) < os.path.getmtime(_build.SRC):
+            _build.build(force=True)
+        L = ctypes.CDLL(path)
+        L.xo_splitmix64.restype = ctypes.c_uint64
+        L.xo_splitmix64.argtypes = [ctypes.POINTER(ctypes.c_uint64)]
+        L.xo_stream_word.restype = ctypes.c_uint64
+        L.xo_stream_word.argtypes = [ctypes.c_uint64, ctypes.c_uint64]
+        L.xo_probe_matrix.restype = ctypes.c_int
+        L.xo_probe_matrix.argtypes = [ctypes.c_int, ctypes.c_uint64, ctypes.c_int, ctypes.c_int, _c_f32p]
+        L.xo_round_storage.restype = ctypes.c_double
+        L.xo_round_storage.argtypes = [ctypes.c_double, ctypes.c_int]
+        L.xo_probe_fwd.restype = None
+        L.xo_probe_fwd.argtypes = [_c_f32p, _c_f32p, _c_f32p] + [ctypes.c_int] * 6
+        L.xo_correlate.restype = None
+        L.xo_correlate.argtypes = [_c_f32p, _c_f32p, _c_f64p] + [ctypes.c_int] * 11
+        L.xo_dw_exact.restype = None
+        L.xo_dw_exact.argtypes = [_c_f32p, _c_f32p, _c_f64p] + [ctypes.c_int] * 11
+        L.xo_expand.restype = None
+        L.xo_expand.argtypes = [_c_f64p, _c_f32p, _c_f64p] + [ctypes.c_int] * 5
+        L.xo_dw_from_xt.restype = None
+        L.xo_dw_from_xt.argtypes = [_c_f32p, _c_f32p, _c_f32p, _c_f64p] + [ctypes.c_int] * 12
+        L.xo_dw_estimate.restype = None
+        L.xo_dw_estimate.argtypes = [_c_f32p, _c_f32p, _c_f32p, _c_f64p] + [ctypes.c_int] * 13
+        L.xo_dw_from_xt_at.restype = None
+        L.xo_dw_from_xt_at.argtypes = [_c_f32p, _c_f32p, _c_f32p, _c_i32p, ctypes.c_int, _c_f64p] + [ctypes.c_int] * 12
+        L.xo_dw_exact_at.restype = None
+        L.xo_dw_exact_at.argtypes = [_c_f32p, _c_f32p, _c_i32p, ctypes.c_int, _c_f64p] + [ctypes.c_int] * 11
+        L.xo_conv_fwd.restype = None
+        L.xo_conv_fwd.argtypes = [_c_f32p, _c_f64p, _c_f64p] + [ctypes.c_int] * 11
+        _LIB = L
+    return _LIB
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a, a.ctypes.data_as(_c_f32p)
+
+
+def _f64(a):
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    return a, a.ctypes.data_as(_c_f64p)
+
+
+def out_extent(n, k, stride, pad):
+    span = n + 2 * pad - k
+    return 0 if span < 0 else span // stride + 1
+
+
+def splitmix64_stream(state, count):
+    st = ctypes.c_uint64(state)
+    return [int(lib().xo_splitmix64(ctypes.byref(st))) for _ in range(count)]
+
+
+def stream_word(seed, ctr):
+    return int(lib().xo_stream_word(ctypes.c_uint64(seed), ctypes.c_uint64(ctr)))
+
+
+def probe_matrix(dist, seed, C_in, r):
+    Z = np.empty((C_in, r), dtype=np.float32)
+    rc = lib().xo_probe_matrix(dist, ctypes.c_uint64(seed), C_in, r, Z.ctypes.data_as(_c_f32p))
+    if rc != 0:
+        raise ValueError("unknown probe distribution %r" % (dist,))
+    return Z
+
+
+def round_storage(v, dtype):
+    return float(lib().xo_round_storage(float(v), dtype))
+
+
+def probe_fwd(X, Z, dtype=F32):
+    X, Xp = _f32(X)
+    Z, Zp = _f32(Z)
+    B, C_in, H, W = X.shape
+    r = Z.shape[1]
+    assert Z.shape[0] == C_in
+    Xt = np.empty((B, r, H, W), dtype=np.float32)
+    lib().xo_probe_fwd(Xp, Zp, Xt.ctypes.data_as(_c_f32p), B, C_in, H, W, r, dtype)
+    return Xt
+
+
+def correlate(dY, A, kH, kW, stride=(1, 1), pad=(0, 0)):
+    dY, dYp = _f32(dY)
+    A, Ap = _f32(A)
+    B, C_out, Ho, Wo = dY.shape
+    _, Q, H, W = A.shape
+    assert Ho == out_extent(H, kH, stride[0], pad[0]) and Wo == out_extent(W, kW, stride[1], pad[1])
+    G = np.empty((C_out, Q, kH, kW), dtype=np.float64)
+    lib().xo_correlate(dYp, Ap, G.ctypes.data_as(_c_f64p), B, C_out, Q, H, W,
+                       kH, kW, stride[0], stride[1], pad[0], pad[1])
+    return G
+
+
+def dw_exact(dY, X, kH, kW, stride=(1, 1), pad=(0, 0)):
+    dY, dYp = _f32(dY)
+    X, Xp = _f32(X)
+    B, C_out, Ho, Wo = dY.shape
+    _, C_in, H, W = X.shape
+    assert Ho == out_extent(H, kH, stride[0], pad[0]) and Wo == out_extent(W, kW, stride[1], pad[1])
+    dW = np.empty((C_out, C_in, kH, kW), dtype=np.float64)
+    lib().xo_dw_exact(dYp, Xp, dW.ctypes.data_as(_c_f64p), B, C_in, C_out, H, W,
+                      kH, kW, stride[0], stride[1], pad[0], pad[1])
+    return dW
+
+
+def expand(G, Z):
+    G, Gp = _f64(G)
+    Z, Zp = _f32(Z)
+    C_out, r, kH, kW = G.shape
+    C_in = Z.shape[0]
+    assert Z.shape[1] == r
+    dW = np.empty((C_out, C_in, kH, kW), dtype=np.float64)
+    lib().xo_expand(Gp, Zp, dW.ctypes.data_as(_c_f64p), C_out, C_in, r, kH, kW)
+    return dW
+
+
+def dw_from_xt(dY, Xt, Z, kH, kW, stride=(1, 1), pad=(0, 0)):
+    dY, dYp = _f32(dY)
+    Xt, Xtp = _f32(Xt)
+    Z, Zp = _f32(Z)
+    B, C_out, Ho, Wo = dY.shape
+    _, r, H, W = Xt.shape
+    C_in = Z.shape[0]
+    assert Z.shape[1] == r
+    assert Ho == out_extent(H, kH, stride[0], pad[0]) and Wo == out_extent(W, kW, stride[1], pad[1])
+    dW = np.empty((C_out, C_in, kH, kW), dtype=np.float64)
+    lib().xo_dw_from_xt(dYp, Xtp, Zp, dW.ctypes.data_as(_c_f64p), B, C_in, C_out, H, W, r,
+                        kH, kW, stride[0], stride[1], pad[0], pad[1])
+    return dW
+
+
+def dw_estimate(dY, X, Z, kH, kW, stride=(1, 1), pad=(0, 0), dtype=F32):
+    dY, dYp = _f32(dY)
+    X, Xp = _f32(X)
+    Z, Zp = _f32(Z)
+    B, C_out, Ho, Wo = dY.shape
+    _, C_in, H, W = X.shape
+    r = Z.shape[1]
+    assert Z.shape[0] == C_in
+    assert Ho == out_extent(H, kH, stride[0], pad[0]) and Wo == out_extent(W, kW, stride[1], pad[1])
+    dW = np.empty((C_out, C_in, kH, kW), dtype=np.float64)
+    lib().xo_dw_estimate(dYp, Xp, Zp, dW.ctypes.data_as(_c_f64p), B, C_in, C_out, H, W, r,
+                         kH, kW, stride[0], stride[1], pad[0], pad[1], dtype)
+    return dW
+
+
+def dw_from_xt_at(dY, Xt, Z, idx, kH, kW, stride=(1, 1), pad=(0, 0)):
+    dY, dYp = _f32(dY)
+    Xt, Xtp = _f32(Xt)
+    Z, Zp = _f32(Z)
+    idx = np.ascontiguousarray(idx, dtype=np.int32).reshape(-1, 4)
+    B, C_out, Ho, Wo = dY.shape
+    _, r, H, W = Xt.shape
+    C_in = Z.shape[0]
+    out = np.empty(idx.shape[0], dtype=np.float64)
+    lib().xo_dw_from_xt_at(dYp, Xtp, Zp, idx.ctypes.data_as(_c_i32p), idx.shape[0],
+                           out.ctypes.data_as(_c_f64p), B, C_in, C_out, H, W, r,
+                           kH, kW, stride[0], stride[1], pad[0], pad[1])
+    return out
+
+
+def dw_exact_at(dY, X, idx, kH, kW, stride=(1, 1), pad=(0, 0)):
+    dY, dYp = _f32(dY)
+    X, Xp = _f32(X)
+    idx = np.ascontiguousarray(idx, dtype=np.int32).reshape(-1, 4)
+    B, C_out, Ho, Wo = dY.shape
+    _, C_in, H, W = X.shape
+    out = np.empty(idx.shape[0], dtype=np.float64)
+    lib().xo_dw_exact_at(dYp, Xp, idx.ctypes.data_as(_c_i32p), idx.shape[0],
+                         out.ctypes.data_as(_c_f64p), B, C_in, C_out, H, W,
+                         kH, kW, stride[0], stride[1], pad[0], pad[1])
+    return out
+
+
+def conv_fwd(X, Wt, stride=(1, 1), pad=(0, 0)):
+    X, Xp = _f32(X)
+    Wt, Wp = _f64(Wt)
+    B, C_in, H, W = X.shape
+    C_out, _, kH, kW = Wt.shape
+    Ho = out_extent(H, kH, stride[0], pad[0])
+    Wo = out_extent(W, kW, stride[1], pad[1])
+    Y = np.empty((B, C_out, Ho, Wo), dtype=np.float64)
+    lib().xo_conv_fwd(Xp, Wp, Y.ctypes.data_as(_c_f64p), B, C_in, C_out, H, W,
+                      kH, kW, stride[0], stride[1], pad[0], pad[1])
+    return Y

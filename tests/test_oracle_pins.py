@@ -1,0 +1,416 @@
+"""Pins for the CPU oracle: every routine in oracle/xconv_oracle.c is checked
+against something other than itself -- published generator outputs, library
+routines (numpy float16, torch bfloat16, torch conv2d and its autograd), brute
+force written independently here, closed forms and the statistical statements
+of the paper (Sec. 3 Eq. (2), (3), (5), (6); Proposition 1; Algorithm 1).
+CPU only.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import xconv_oracle as xo
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _read_numbers(name):
+    rows = []
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                rows.append([int(t) for t in line.split()])
+    return rows
+
+
+# --------------------------------------------------------------------------
+# generator
+# --------------------------------------------------------------------------
+def test_splitmix64_published_vector():
+    want = [row[0] for row in _read_numbers("splitmix64_seed1234567.txt")]
+    assert xo.splitmix64_stream(1234567, len(want)) == want
+
+
+def test_stream_word_is_the_counter_form_of_splitmix64():
+    # word ctr of seed's stream == (ctr+1)-th output of SplitMix64 started at
+    # the first output of SplitMix64(seed)
+    for seed in (0, 1, 3001, 2**63 + 12345):
+        key = xo.splitmix64_stream(seed, 1)[0]
+        stream = xo.splitmix64_stream(key, 6)
+        assert [xo.stream_word(seed, c) for c in range(6)] == stream
+
+
+def test_rademacher_entries_and_balance():
+    Z = xo.probe_matrix(xo.RADEMACHER, 3001, 256, 64)
+    assert set(np.unique(Z)) == {-1.0, 1.0}
+    n = Z.size
+    assert abs(Z.sum()) < 4.0 * np.sqrt(n)
+    assert np.all(np.abs(Z.sum(axis=0)) < 4.5 * np.sqrt(Z.shape[0]))
+    assert np.all(np.abs(Z.sum(axis=1)) < 4.5 * np.sqrt(Z.shape[1]))
+    # top bit of the stream word decides the sign
+    for (c, j) in [(0, 0), (3, 5), (255, 63)]:
+        w = xo.stream_word(3001, c * 64 + j)
+        assert Z[c, j] == (-1.0 if (w >> 63) else 1.0)
+
+
+def test_gaussian_moments():
+    Z = xo.probe_matrix(xo.GAUSSIAN, 3002, 512, 256).astype(np.float64)
+    n = Z.size
+    assert abs(Z.mean()) < 4.0 / np.sqrt(n)
+    assert abs(Z.var() - 1.0) < 4.0 * np.sqrt(2.0 / n)
+    kurt = np.mean(Z ** 4)
+    assert abs(kurt - 3.0) < 4.0 * np.sqrt(96.0 / n)
+    assert abs(np.mean(Z ** 3)) < 4.0 * np.sqrt(15.0 / n)
+    # Box-Muller from the two stream words, redone here in numpy double
+    for (c, j) in [(0, 0), (17, 3), (511, 255)]:
+        idx = c * 256 + j
+        u1 = ((xo.stream_word(3002, 2 * idx) >> 11) + 1) * 2.0 ** -53
+        u2 = (xo.stream_word(3002, 2 * idx + 1) >> 11) * 2.0 ** -53
+        g = np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
+        assert abs(Z[c, j] - g) <= 2e-7 * max(1.0, abs(g))
+
+
+@pytest.mark.parametrize("dist", [xo.RADEMACHER, xo.GAUSSIAN])
+def test_probe_second_moment_is_identity(dist):
+    # E[z z^T] = I (Eq. (3)): Z Z^T / r -> I as r grows, off-diagonals ~ 1/sqrt(r)
+    C = 16
+    for r, tol in ((1024, 0.2), (16384, 0.05)):
+        Z = xo.probe_matrix(dist, 77, C, r).astype(np.float64)
+        G = Z @ Z.T / r
+        assert np.max(np.abs(G - np.eye(C))) < tol
+
+
+def test_probe_matrix_seed_behaviour():
+    a = xo.probe_matrix(xo.GAUSSIAN, 5, 32, 8)
+    b = xo.probe_matrix(xo.GAUSSIAN, 5, 32, 8)
+    c = xo.probe_matrix(xo.GAUSSIAN, 6, 32, 8)
+    assert np.array_equal(a, b)
+    assert not np.array_equal(a, c)
+    assert abs(np.corrcoef(a.ravel(), c.ravel())[0, 1]) < 0.3
+    with pytest.raises(ValueError):
+        xo.probe_matrix(9, 5, 4, 4)
+
+
+# --------------------------------------------------------------------------
+# storage rounding
+# --------------------------------------------------------------------------
+def test_round_storage_matches_library_conversions():
+    rng = np.random.default_rng(0)
+    vals = np.concatenate([
+        rng.standard_normal(2000) * 10.0 ** rng.integers(-9, 5, 2000),
+        np.array([0.0, -0.0, 1.0, 1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, 65504.0, 65519.9, 65520.0,
+                  6e-8, 2.98e-8, 2.99e-8, 5.96e-8, 1e-40, 3.3895e38, 3.4e38, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8]),
+    ])
+    for v in vals:
+        f32 = np.float32(v)
+        # the oracle rounds double sums directly; use doubles that are floats so
+        # the library conversion (float -> 16 bit) rounds the same number
+        v = float(f32)
+        got16 = xo.round_storage(v, xo.F16)
+        with np.errstate(over="ignore"):
+            want16 = float(np.float32(v).astype(np.float16))
+        assert got16 == want16 or (np.isnan(got16) and np.isnan(want16)), (v, got16, want16)
+        gotb = xo.round_storage(v, xo.BF16)
+        wantb = float(torch.tensor(v, dtype=torch.float32).to(torch.bfloat16).to(torch.float32))
+        assert gotb == wantb, (v, gotb, wantb)
+        assert xo.round_storage(v, xo.F32) == v
+
+
+# --------------------------------------------------------------------------
+# exact gradient, Eq. (2)/(5)
+# --------------------------------------------------------------------------
+def _brute_conv(X, Wt, stride, pad):
+    """Textbook direct convolution (gather form), written here independently."""
+    B, C_in, H, W = X.shape
+    C_out, _, kH, kW = Wt.shape
+    Ho = (H + 2 * pad[0] - kH) // stride[0] + 1
+    Wo = (W + 2 * pad[1] - kW) // stride[1] + 1
+    Xp = np.zeros((B, C_in, H + 2 * pad[0], W + 2 * pad[1]))
+    Xp[:, :, pad[0]:pad[0] + H, pad[1]:pad[1] + W] = X
+    Y = np.zeros((B, C_out, Ho, Wo))
+    for b, m, oy, ox in itertools.product(range(B), range(C_out), range(Ho), range(Wo)):
+        patch = Xp[b, :, oy * stride[0]:oy * stride[0] + kH, ox * stride[1]:ox * stride[1] + kW]
+        Y[b, m, oy, ox] = np.sum(patch * Wt[m])
+    return Y
+
+
+TINY = [
+    # B, C_in, C_out, H, W, kH, kW, stride, pad
+    (2, 3, 2, 6, 5, 3, 3, (1, 1), (1, 1)),
+    (2, 2, 3, 6, 6, 3, 3, (2, 2), (1, 1)),
+    (1, 3, 3, 5, 6, 1, 1, (1, 1), (0, 0)),
+    (2, 2, 2, 6, 6, 3, 3, (1, 1), (0, 0)),
+    (1, 2, 2, 7, 6, 3, 2, (2, 1), (1, 0)),
+    (2, 1, 2, 5, 5, 5, 5, (1, 1), (2, 2)),
+]
+
+
+@pytest.mark.parametrize("case", TINY)
+def test_conv_fwd_against_brute_force_and_torch(case):
+    B, C_in, C_out, H, W, kH, kW, stride, pad = case
+    rng = np.random.default_rng(1)
+    X = rng.standard_normal((B, C_in, H, W)).astype(np.float32)
+    Wt = rng.standard_normal((C_out, C_in, kH, kW))
+    Y = xo.conv_fwd(X, Wt, stride, pad)
+    assert np.allclose(Y, _brute_conv(X.astype(np.float64), Wt, stride, pad), atol=1e-12)
+    Yt = F.conv2d(torch.from_numpy(X).double(), torch.from_numpy(Wt), stride=stride, padding=pad).numpy()
+    assert np.allclose(Y, Yt, atol=1e-12)
+
+
+@pytest.mark.parametrize("case", TINY)
+def test_dw_exact_unit_weight_brute_force(case):
+    # dW[m,n,ky,kx] = <dY, conv(X, E_{m,n,ky,kx})> for every unit weight
+    B, C_in, C_out, H, W, kH, kW, stride, pad = case
+    rng = np.random.default_rng(2)
+    X = rng.standard_normal((B, C_in, H, W)).astype(np.float32)
+    Ho, Wo = xo.out_extent(H, kH, stride[0], pad[0]), xo.out_extent(W, kW, stride[1], pad[1])
+    dY = rng.standard_normal((B, C_out, Ho, Wo)).astype(np.float32)
+    dW = xo.dw_exact(dY, X, kH, kW, stride, pad)
+    for m, n, ky, kx in itertools.product(range(C_out), range(C_in), range(kH), range(kW)):
+        E = np.zeros((C_out, C_in, kH, kW))
+        E[m, n, ky, kx] = 1.0
+        want = np.sum(dY.astype(np.float64) * _brute_conv(X.astype(np.float64), E, stride, pad))
+        assert abs(dW[m, n, ky, kx] - want) < 1e-10
+
+
+@pytest.mark.parametrize("case", TINY + [(3, 5, 4, 9, 11, 3, 3, (2, 2), (1, 1)), (2, 4, 6, 12, 12, 3, 3, (1, 1), (1, 1))])
+def test_dw_exact_against_torch_autograd(case):
+    B, C_in, C_out, H, W, kH, kW, stride, pad = case
+    rng = np.random.default_rng(3)
+    X = rng.standard_normal((B, C_in, H, W)).astype(np.float32)
+    Ho, Wo = xo.out_extent(H, kH, stride[0], pad[0]), xo.out_extent(W, kW, stride[1], pad[1])
+    dY = rng.standard_normal((B, C_out, Ho, Wo)).astype(np.float32)
+    w = torch.zeros((C_out, C_in, kH, kW), dtype=torch.float64, requires_grad=True)
+    y = F.conv2d(torch.from_numpy(X).double(), w, stride=stride, padding=pad)
+    y.backward(torch.from_numpy(dY).double())
+    assert np.allclose(xo.dw_exact(dY, X, kH, kW, stride, pad), w.grad.numpy(), atol=1e-10)
+
+
+def test_dw_exact_adjoint_identity():
+    rng = np.random.default_rng(4)
+    B, C_in, C_out, H, W, k = 3, 4, 5, 10, 9, 3
+    for stride, pad in (((1, 1), (1, 1)), ((2, 2), (1, 1)), ((1, 2), (0, 1))):
+        X = rng.standard_normal((B, C_in, H, W)).astype(np.float32)
+        Wt = rng.standard_normal((C_out, C_in, k, k))
+        Y = xo.conv_fwd(X, Wt, stride, pad)
+        dY = rng.standard_normal(Y.shape).astype(np.float32)
+        lhs = np.sum(dY.astype(np.float64) * Y)
+        rhs = np.sum(xo.dw_exact(dY, X, k, k, stride, pad) * Wt)
+        assert abs(lhs - rhs) < 1e-9 * max(1.0, abs(lhs))
+
+
+def test_dw_exact_special_cases():
+    rng = np.random.default_rng(5)
+    # k = 1: the gradient is the plain matrix product  sum_{b,p} dY[b,m,p] X[b,n,p]
+    B, C_in, C_out, H, W = 3, 5, 4, 6, 7
+    X = rng.standard_normal((B, C_in, H, W)).astype(np.float32)
+    dY = rng.standard_normal((B, C_out, H, W)).astype(np.float32)
+    want = np.einsum("bmp,bnp->mn", dY.reshape(B, C_out, -1).astype(np.float64), X.reshape(B, C_in, -1).astype(np.float64))
+    assert np.allclose(xo.dw_exact(dY, X, 1, 1)[:, :, 0, 0], want, atol=1e-10)
+    # a single bright input pixel: dW is a flipped, shifted copy of dY around it
+    X = np.zeros((1, 1, 7, 7), dtype=np.float32)
+    X[0, 0, 3, 4] = 2.0
+    dY = rng.standard_normal((1, 1, 7, 7)).astype(np.float32)
+    dW = xo.dw_exact(dY, X, 3, 3, (1, 1), (1, 1))
+    for ky, kx in itertools.product(range(3), range(3)):
+        # input pixel (3,4) is seen by output pixel (3 - ky + 1, 4 - kx + 1)
+        assert abs(dW[0, 0, ky, kx] - 2.0 * dY[0, 0, 3 - ky + 1, 4 - kx + 1]) < 1e-12
+
+
+# --------------------------------------------------------------------------
+# probe, correlation, expansion: Algorithm 1 / Eq. (6)
+# --------------------------------------------------------------------------
+def test_probe_fwd_is_a_channel_contraction():
+    rng = np.random.default_rng(6)
+    X = rng.standard_normal((3, 7, 5, 6)).astype(np.float32)
+    Z = rng.standard_normal((7, 4)).astype(np.float32)
+    Xt = xo.probe_fwd(X, Z, xo.F32)
+    want = np.einsum("nj,bnyx->bjyx", Z.astype(np.float64), X.astype(np.float64))
+    assert Xt.shape == (3, 4, 5, 6)
+    assert np.array_equal(Xt, want.astype(np.float32))
+    # 16-bit storage: one rounding of the exact sum
+    Xh = xo.probe_fwd(X, Z, xo.F16)
+    assert np.array_equal(Xh, want.astype(np.float32).astype(np.float16).astype(np.float32)) or \
+        np.max(np.abs(Xh - want)) <= 2.0 ** -11 * np.max(np.abs(want)) * 1.0001
+    Xb = xo.probe_fwd(X, Z, xo.BF16)
+    assert np.max(np.abs(Xb - want) / np.maximum(np.abs(want), 1e-30)) <= 2.0 ** -8
+    assert np.array_equal(Xb.view(np.uint32) & 0xFFFF, np.zeros(Xb.shape, dtype=np.uint32))
+
+
+CLOSED_FORM_CASES = [
+    # B, C_in, C_out, H, W, k, stride, pad, r, dist
+    (3, 8, 5, 9, 10, 3, 1, 1, 4, xo.GAUSSIAN),
+    (2, 6, 7, 11, 9, 3, 2, 1, 3, xo.RADEMACHER),
+    (2, 5, 3, 8, 8, 1, 1, 0, 2, xo.GAUSSIAN),
+    (2, 4, 4, 9, 9, 5, 1, 2, 6, xo.RADEMACHER),
+    (2, 4, 3, 10, 7, 3, 1, 0, 5, xo.GAUSSIAN),
+]
+
+
+@pytest.mark.parametrize("case", CLOSED_FORM_CASES)
+def test_estimate_closed_form(case):
+    # For a fixed Z the estimator is linear in X, so
+    #   dW_est[m,n,:,:] = sum_n' (Z Z^T / r)[n,n'] dW_exact[m,n',:,:]
+    # (Eq. (6) with the probes restricted to channels).  The right-hand side is
+    # built from the torch-pinned exact gradient and numpy alone.
+    B, C_in, C_out, H, W, k, st, p, r, dist = case
+    rng = np.random.default_rng(7)
+    X = rng.standard_normal((B, C_in, H, W)).astype(np.float32)
+    Ho, Wo = xo.out_extent(H, k, st, p), xo.out_extent(W, k, st, p)
+    dY = rng.standard_normal((B, C_out, Ho, Wo)).astype(np.float32)
+    Z = xo.probe_matrix(dist, 11, C_in, r)
+    est = xo.dw_estimate(dY, X, Z, k, k, (st, st), (p, p), xo.F32)
+    w = torch.zeros((C_out, C_in, k, k), dtype=torch.float64, requires_grad=True)
+    F.conv2d(torch.from_numpy(X).double(), w, stride=st, padding=p).backward(torch.from_numpy(dY).double())
+    G = Z.astype(np.float64) @ Z.astype(np.float64).T / r
+    want = np.einsum("nq,mqyx->mnyx", G, w.grad.numpy())
+    # fp32 storage of the probed activations is the only rounding
+    assert np.max(np.abs(est - want)) <= 2e-6 * np.max(np.abs(want))
+
+
+def test_estimate_steps_compose():
+    rng = np.random.default_rng(8)
+    B, C_in, C_out, H, W, k, r = 2, 6, 4, 8, 8, 3, 3
+    X = rng.standard_normal((B, C_in, H, W)).astype(np.float32)
+    dY = rng.standard_normal((B, C_out, H, W)).astype(np.float32)
+    Z = xo.probe_matrix(xo.GAUSSIAN, 1, C_in, r)
+    Xt = xo.probe_fwd(X, Z, xo.F32)
+    G = xo.correlate(dY, Xt, k, k, (1, 1), (1, 1))
+    # correlation pinned by torch: it is the exact gradient w.r.t. an r-channel input
+    w = torch.zeros((C_out, r, k, k), dtype=torch.float64, requires_grad=True)
+    F.conv2d(torch.from_numpy(Xt).double(), w, padding=1).backward(torch.from_numpy(dY).double())
+    assert np.allclose(G, w.grad.numpy(), atol=1e-10)
+    # expansion pinned by einsum
+    want = np.einsum("nj,mjyx->mnyx", Z.astype(np.float64), G) / r
+    assert np.allclose(xo.expand(G, Z), want, atol=1e-12)
+    assert np.allclose(xo.dw_from_xt(dY, Xt, Z, k, k, (1, 1), (1, 1)), want, atol=1e-12)
+    assert np.allclose(xo.dw_estimate(dY, X, Z, k, k, (1, 1), (1, 1), xo.F32), want, atol=1e-12)
+    # sampled entries are the same numbers
+    idx = np.array([[0, 0, 0, 0], [3, 5, 2, 1], [1, 2, 1, 1], [2, 4, 0, 2]], dtype=np.int32)
+    got = xo.dw_from_xt_at(dY, Xt, Z, idx, k, k, (1, 1), (1, 1))
+    assert np.allclose(got, [want[tuple(i)] for i in idx], atol=1e-12)
+    ex = xo.dw_exact(dY, X, k, k, (1, 1), (1, 1))
+    got = xo.dw_exact_at(dY, X, idx, k, k, (1, 1), (1, 1))
+    assert np.allclose(got, [ex[tuple(i)] for i in idx], atol=1e-12)
+
+
+def _sylvester_hadamard(n):
+    Hm = np.array([[1.0]])
+    while Hm.shape[0] < n:
+        Hm = np.block([[Hm, Hm], [Hm, -Hm]])
+    return Hm
+
+
+@pytest.mark.parametrize("stride,pad", [(1, 1), (2, 1)])
+def test_full_rank_orthogonal_probe_recovers_exact_gradient(stride, pad):
+    # r = C_in with Z Z^T = r I: the estimate is the exact gradient (Sec. 2:
+    # raising the probing rank recovers the exact gradient).
+    rng = np.random.default_rng(9)
+    B, C_in, C_out, H, W, k = 2, 8, 5, 10, 10, 3
+    X = rng.standard_normal((B, C_in, H, W)).astype(np.float32)
+    Ho = xo.out_extent(H, k, stride, pad)
+    dY = rng.standard_normal((B, C_out, Ho, Ho)).astype(np.float32)
+    exact = xo.dw_exact(dY, X, k, k, (stride, stride), (pad, pad))
+    for Z in (_sylvester_hadamard(C_in), np.sqrt(C_in) * np.eye(C_in)):
+        Z = Z.astype(np.float32)
+        est = xo.dw_estimate(dY, X, Z, k, k, (stride, stride), (pad, pad), xo.F32)
+        assert np.max(np.abs(est - exact)) <= 3e-6 * np.max(np.abs(exact))
+    # a random full-rank Rademacher probe is NOT exact
+    Zr = xo.probe_matrix(xo.RADEMACHER, 1, C_in, C_in)
+    est = xo.dw_estimate(dY, X, Zr, k, k, (stride, stride), (pad, pad), xo.F32)
+    assert np.max(np.abs(est - exact)) > 1e-2 * np.max(np.abs(exact))
+
+
+def _layer(seed, B=2, C_in=8, C_out=4, H=8, W=8):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((B, C_in, H, W)).astype(np.float32)
+    dY = rng.standard_normal((B, C_out, H, W)).astype(np.float32)
+    return X, dY
+
+
+@pytest.mark.parametrize("dist", [xo.RADEMACHER, xo.GAUSSIAN])
+def test_unbiasedness_rate(dist):
+    # Eq. (3): the estimator is unbiased, so the mean over S independent seeds
+    # approaches the exact gradient like 1/sqrt(S).
+    X, dY = _layer(10)
+    C_in, r = X.shape[1], 2
+    exact = xo.dw_exact(dY, X, 3, 3, (1, 1), (1, 1))
+    Xc = X  # the probe output is linear in X; fp32 storage rounding is far below the noise
+    S_list = [16, 64, 256, 1024]
+    errs = []
+    acc = np.zeros_like(exact)
+    done = 0
+    for S in S_list:
+        while done < S:
+            Z = xo.probe_matrix(dist, 100000 + done, C_in, r)
+            acc += xo.dw_estimate(dY, Xc, Z, 3, 3, (1, 1), (1, 1), xo.F32)
+            done += 1
+        errs.append(np.linalg.norm(acc / S - exact) / np.linalg.norm(exact))
+    slope = np.polyfit(np.log(S_list), np.log(errs), 1)[0]
+    assert -0.65 < slope < -0.35, (slope, errs)
+    assert errs[-1] < 0.12, errs
+
+
+@pytest.mark.parametrize("dist", [xo.RADEMACHER, xo.GAUSSIAN])
+def test_estimator_variance_formula(dist):
+    # From Eq. (3) with unit-variance entries: per entry, with w = dW_exact[m,:,ky,kx],
+    #   Var = (|w|^2 + w_n^2)/r  (Gaussian),   (|w|^2 - w_n^2)/r  (Rademacher).
+    X, dY = _layer(11, C_in=6, C_out=3, H=6, W=6)
+    C_in, r, S = 6, 3, 3000
+    exact = xo.dw_exact(dY, X, 3, 3, (1, 1), (1, 1))
+    sq = np.zeros_like(exact)
+    for s in range(S):
+        Z = xo.probe_matrix(dist, 500000 + s, C_in, r)
+        d = xo.dw_estimate(dY, X, Z, 3, 3, (1, 1), (1, 1), xo.F32) - exact
+        sq += d * d
+    var = sq / S
+    norm2 = np.sum(exact ** 2, axis=1, keepdims=True)
+    sign = 1.0 if dist == xo.GAUSSIAN else -1.0
+    want = (norm2 + sign * exact ** 2) / r
+    ratio = var.sum() / want.sum()
+    assert 0.93 < ratio < 1.07, ratio
+    # entrywise within Monte-Carlo scatter
+    assert np.all(var < 1.35 * want + 1e-12) and np.all(var > 0.7 * want - 1e-12)
+
+
+def test_error_decays_like_inverse_sqrt_r():
+    # Proposition 1, large-r regime: error ~ |A|_F / sqrt(r)
+    X, dY = _layer(12, C_in=64, C_out=4, H=6, W=6)
+    exact = xo.dw_exact(dY, X, 3, 3, (1, 1), (1, 1))
+    rs = [2, 4, 8, 16, 32]
+    errs = []
+    for r in rs:
+        e = 0.0
+        for s in range(24):
+            Z = xo.probe_matrix(xo.GAUSSIAN, 900000 + 100 * r + s, 64, r)
+            e += np.linalg.norm(xo.dw_estimate(dY, X, Z, 3, 3, (1, 1), (1, 1), xo.F32) - exact) ** 2
+        errs.append(np.sqrt(e / 24))
+    slope = np.polyfit(np.log(rs), np.log(errs), 1)[0]
+    assert -0.6 < slope < -0.4, (slope, errs)
+
+
+def test_sixteen_bit_storage_effect_is_small():
+    # Storing the probed activations in 16 bits perturbs the estimate far less
+    # than the 2e-2 parity budget of the 16-bit paths.
+    rng = np.random.default_rng(13)
+    B, C_in, C_out, H, W, r = 4, 16, 8, 12, 12, 4
+    X = np.maximum(rng.standard_normal((B, C_in, H, W)), 0).astype(np.float16).astype(np.float32)
+    dY = (0.1 * rng.standard_normal((B, C_out, H, W))).astype(np.float16).astype(np.float32)
+    Z = xo.probe_matrix(xo.RADEMACHER, 3, C_in, r)
+    e32 = xo.dw_estimate(dY, X, Z, 3, 3, (1, 1), (1, 1), xo.F32)
+    e16 = xo.dw_estimate(dY, X, Z, 3, 3, (1, 1), (1, 1), xo.F16)
+    eb = xo.dw_estimate(dY, X, Z, 3, 3, (1, 1), (1, 1), xo.BF16)
+    scale = np.max(np.abs(e32))
+    assert 0 < np.max(np.abs(e16 - e32)) < 2e-3 * scale
+    assert 0 < np.max(np.abs(eb - e32)) < 1e-2 * scale
+
+
+def test_paper_memory_ratio_table():
+    # Sec. 4.1: N*C_in/r = 2^(14-gamma) for N = 1024, C_in = 16, r = 2^gamma
+    for gamma, ratio in _read_numbers("paper_memory_ratio.txt"):
+        assert 1024 * 16 // (2 ** gamma) == ratio == 2 ** (14 - gamma)
