@@ -1,0 +1,144 @@
+/*
+ * xconv.h -- C ABI of the MI355X (gfx950) XConv weight-gradient library.
+ *
+ * The library implements the low-memory stochastic weight gradient of a 2-D
+ * convolutional layer (Algorithm 1 of the paper) with probing vectors that act
+ * on the channel axis:
+ *
+ *   forward   Xt[b,j,y,x] = sum_n Z[n,j] X[b,n,y,x]                 (Alg. 1 fwd step 3; Eq. (6) step (i))
+ *   backward  G[m,j,ky,kx] = sum_{b,oy,ox} dY[b,m,oy,ox] Xt[b,j,oy*sh+ky-ph, ox*sw+kx-pw]
+ *                                                                    (Alg. 1 bwd step 3 and the shift of step 4)
+ *             dW[m,n,ky,kx] = (1/r) sum_j Z[n,j] G[m,j,ky,kx]        (Alg. 1 bwd step 4; Eq. (6) step (iii))
+ *   exact     dW[m,n,ky,kx] = sum_{b,oy,ox} dY[b,m,oy,ox] X[b,n,oy*sh+ky-ph, ox*sw+kx-pw]
+ *                                                                    (Eq. (2) / Eq. (5))
+ *
+ * Z is [C_in, r] with i.i.d. unit-variance entries (E[z z^T] = I, Eq. (3)); taps
+ * outside the image contribute zero (zero padding, cross-correlation, dilation
+ * 1, groups 1).  H' = floor((H + 2*pad_h - kH)/stride_h) + 1, W' likewise.
+ *
+ * Conventions for every entry point
+ *   - "_dev" pointers are device (HBM) addresses on the current HIP device,
+ *     "_host" pointers are host addresses.  All buffers are owned and allocated
+ *     by the caller; the library allocates no device memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Device work is enqueued on it and the call returns without waiting.
+ *   - Return value: an xconv_status.  Arguments are validated on the host before
+ *     anything is enqueued; on a non-zero status nothing was launched (except
+ *     XCONV_EHIP, which reports a failed launch).  Nothing aborts or throws.
+ *   - dW is overwritten, never accumulated into.
+ */
+#ifndef XCONV_H
+#define XCONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    XCONV_OK = 0,
+    XCONV_EINVAL = 1,       /* null pointer, non-positive extent, empty output, bad enum   */
+    XCONV_EUNSUPPORTED = 2, /* valid but not implemented (see xconv_check_desc)             */
+    XCONV_EWORKSPACE = 3,   /* ws_bytes smaller than xconv_workspace_bytes()                */
+    XCONV_EHIP = 4          /* the HIP runtime reported an error while enqueuing            */
+} xconv_status;
+
+typedef enum { XCONV_F32 = 0, XCONV_BF16 = 1, XCONV_F16 = 2 } xconv_dtype;   /* storage of X, dY, Xt; sums and dW are fp32 */
+typedef enum { XCONV_NCHW = 0, XCONV_NHWC = 1 } xconv_layout;                /* of X and dY                                 */
+typedef enum { XCONV_RADEMACHER = 0, XCONV_GAUSSIAN = 1, XCONV_USER_Z = 2 } xconv_probe;
+typedef enum { XCONV_OP_PROBE = 0, XCONV_OP_ESTIMATE = 1, XCONV_OP_EXACT = 2 } xconv_op;
+
+/* Problem statement of one layer (Algorithm 1: X, dY, the seed s and r; the
+ * layer arguments in/out channels, kernel, stride, padding). */
+typedef struct xconv_desc {
+    int32_t B, C_in, C_out, H, W;            /* input extent                                         */
+    int32_t kH, kW;                          /* kernel extent                                        */
+    int32_t stride_h, stride_w, pad_h, pad_w;
+    int32_t r;                               /* number of probing vectors, >= 1                      */
+    int32_t dtype;                           /* xconv_dtype                                          */
+    int32_t layout;                          /* xconv_layout                                         */
+    int32_t probe;                           /* xconv_probe: how Z is obtained when no Z is passed   */
+    int32_t reserved;                        /* must be 0                                            */
+    uint64_t seed;                           /* Algorithm 1's s: same value in forward and backward  */
+} xconv_desc;
+
+/* Host-only validation.  XCONV_EINVAL: null desc, an extent < 1, stride < 1,
+ * pad < 0, r < 1, H' or W' < 1, unknown enum, reserved != 0.
+ * XCONV_EUNSUPPORTED: layout NHWC; r > 1024; C_in or C_out > 65536; kH*kW > 49;
+ * an extent whose tensors exceed 2^31-1 elements per image plane. */
+xconv_status xconv_check_desc(const xconv_desc *desc);
+
+/* Bytes of the stored probe output Xt.  Its layout is the library's own
+ * ([B, H, W, r rounded up to 16] in the storage dtype); callers treat it as
+ * opaque and keep it between forward and backward.  0 for an invalid desc. */
+size_t xconv_xt_bytes(const xconv_desc *desc);
+
+/* Bytes of device scratch the given op (xconv_op) needs in `ws_dev`.  The
+ * scratch holds Z when it is regenerated from the seed, the split partial sums
+ * of the correlation and, for the exact gradient, a channels-last copy of X.
+ * 0 for an invalid desc. */
+size_t xconv_workspace_bytes(const xconv_desc *desc, int op);
+
+/* Z[s] on the host: fills Z_host[C_in*r] (row-major [C_in][r], fp32) with the
+ * probing matrix that `desc->probe` and `desc->seed` define (Alg. 1 fwd step 2
+ * / bwd step 2).  Rademacher: +1/-1 from the top bit of word c*r+j of the
+ * SplitMix64 stream of the seed.  Gaussian: Box-Muller in double on words
+ * 2(c*r+j), 2(c*r+j)+1, rounded to fp32.  XCONV_EINVAL for XCONV_USER_Z. */
+xconv_status xconv_probe_matrix(const xconv_desc *desc, float *Z_host);
+
+/* The same matrix generated on the device into Z_dev[C_in*r] (fp32). */
+xconv_status xconv_probe_matrix_dev(const xconv_desc *desc, float *Z_dev, void *stream);
+
+/* Forward probe (Alg. 1 fwd step 3).  X_dev: [B,C_in,H,W] in desc->dtype.
+ * Xt_dev: xconv_xt_bytes() bytes, written once.  Z_dev: [C_in,r] fp32 or NULL;
+ * NULL regenerates Z from (probe, seed) into the workspace (XCONV_USER_Z then
+ * is XCONV_EINVAL).  Sums are fp32; Xt is rounded once (nearest even) to
+ * desc->dtype.  ws_dev may be NULL when Z_dev is given. */
+xconv_status xconv_probe_fwd(const xconv_desc *desc, const void *X_dev, void *Xt_dev,
+                             const float *Z_dev, void *ws_dev, size_t ws_bytes, void *stream);
+
+/* Backward estimate (Alg. 1 bwd steps 1-4).  dY_dev: [B,C_out,H',W'] in
+ * desc->dtype.  Xt_dev: as written by xconv_probe_fwd for the same desc.
+ * Z_dev: as above (must be the Z used in the forward).  dW_dev:
+ * [C_out,C_in,kH,kW] fp32, overwritten.  The result is deterministic for given
+ * inputs (fixed-order two-pass reduction, no atomics). */
+xconv_status xconv_dw_estimate(const xconv_desc *desc, const void *dY_dev, const void *Xt_dev,
+                               const float *Z_dev, float *dW_dev,
+                               void *ws_dev, size_t ws_bytes, void *stream);
+
+/* Exact weight gradient (Eq. (2)/(5)), for comparison with the estimate: same
+ * correlation kernel with the C_in real channels in place of the r probed
+ * ones.  X_dev: [B,C_in,H,W]; dW_dev: [C_out,C_in,kH,kW] fp32, overwritten.
+ * desc->r, probe and seed are ignored (r must still be >= 1). */
+xconv_status xconv_dw_exact(const xconv_desc *desc, const void *dY_dev, const void *X_dev,
+                            float *dW_dev, void *ws_dev, size_t ws_bytes, void *stream);
+
+/* Launch plan of the correlation kernel for op XCONV_OP_ESTIMATE or
+ * XCONV_OP_EXACT, for reports and tests (host only).  Fills out[0..15] with
+ * K-splits S, steps NS, rows per step RB, columns per step CW, waves along
+ * output channels WM, along probe columns WJ, along the k-steps WK, workgroup
+ * tile M_WG, J_WG, LDS bytes, tiles NTM, NTJ, offset groups NOG, column stride
+ * CS, dY vector chunks per row NCHR, 0. */
+xconv_status xconv_plan_info(const xconv_desc *desc, int op, int32_t *out);
+
+/* Test helper: writes the stored Xt as plain fp32 [B,r,H,W] into out_dev. */
+xconv_status xconv_xt_unpack(const xconv_desc *desc, const void *Xt_dev, float *out_dev, void *stream);
+
+/* Per-kernel timing with HIP events recorded on the launch stream.  While
+ * enabled, every kernel the library enqueues is bracketed by two events.
+ * xconv_prof_collect synchronises those events, writes up to `max` records
+ * (kernel id, milliseconds) in launch order, returns how many it wrote and
+ * clears the list.  Kernel ids: see xconv_prof_kernel_name.  Not thread safe;
+ * meant for the benchmark, off by default. */
+void xconv_prof_enable(int on);
+int xconv_prof_collect(int32_t *kernel_ids, float *ms, int max);
+const char *xconv_prof_kernel_name(int kernel_id);
+
+const char *xconv_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* XCONV_H */

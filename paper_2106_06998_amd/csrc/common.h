@@ -1,0 +1,111 @@
+// Internal definitions shared by the HIP translation units of libxconv.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/xconv.h"
+
+namespace xc {
+
+constexpr int kThreads = 256;  // every kernel runs 4 wavefronts of 64 lanes per workgroup
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+enum KernelId {
+    K_GEN_Z = 0,
+    K_PROBE = 1,
+    K_PROBE_GENERIC = 2,
+    K_CORR = 3,
+    K_REDUCE_EXPAND = 4,
+    K_TO_NHWC = 5,
+    K_UNPACK = 6,
+    K_COUNT = 7
+};
+
+__host__ __device__ inline int round_up(int a, int b) { return (a + b - 1) / b * b; }
+__host__ __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// ---- storage-type conversions (device) ------------------------------------
+__device__ inline uint16_t f32_to_bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ inline uint16_t f32_to_f16_rne(float f)
+{
+    _Float16 h = (_Float16)f;  // v_cvt_f16_f32: round to nearest even
+    return __builtin_bit_cast(uint16_t, h);
+}
+__device__ inline float bf16_to_f32(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+__device__ inline float f16_to_f32(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
+
+template <int DT> __device__ inline uint16_t f32_to_st16(float f)
+{
+    if constexpr (DT == XCONV_BF16) return f32_to_bf16_rne(f);
+    else return f32_to_f16_rne(f);
+}
+template <int DT> __device__ inline float st16_to_f32(uint16_t h)
+{
+    if constexpr (DT == XCONV_BF16) return bf16_to_f32(h);
+    else return f16_to_f32(h);
+}
+
+// 16x16x32 MFMA on eight 16-bit values per lane (passed as the raw 16 bytes).
+template <int DT> __device__ inline f32x4 mfma16(const uint4 &a, const uint4 &b, f32x4 c)
+{
+    if constexpr (DT == XCONV_BF16)
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+
+// In-register transpose of an 8 (rows q) x 2*NW (16-bit columns) block held as
+// rows[q][w] (two columns per 32-bit word) into per-column vectors: column t
+// gets the eight row values packed in q order.
+template <int NW> __device__ inline void transpose_rows8(const uint32_t (&rows)[8][NW], uint4 (&cols)[2 * NW])
+{
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        // even column: low halves of each row pair; odd column: high halves
+        // (plain shifts and masks; the compiler folds each into one byte-permute)
+        cols[2 * w].x = (rows[0][w] & 0xffffu) | (rows[1][w] << 16);
+        cols[2 * w].y = (rows[2][w] & 0xffffu) | (rows[3][w] << 16);
+        cols[2 * w].z = (rows[4][w] & 0xffffu) | (rows[5][w] << 16);
+        cols[2 * w].w = (rows[6][w] & 0xffffu) | (rows[7][w] << 16);
+        cols[2 * w + 1].x = (rows[0][w] >> 16) | (rows[1][w] & 0xffff0000u);
+        cols[2 * w + 1].y = (rows[2][w] >> 16) | (rows[3][w] & 0xffff0000u);
+        cols[2 * w + 1].z = (rows[4][w] >> 16) | (rows[5][w] & 0xffff0000u);
+        cols[2 * w + 1].w = (rows[6][w] >> 16) | (rows[7][w] & 0xffff0000u);
+    }
+}
+
+// ---- launch plan of the correlation kernel (host fills, kernel reads) ------
+struct CorrParams {
+    const void *dY;    // [B, C_out, Ho, Wo] storage dtype
+    const void *A;     // channels-last activation-like tensor [B, H, W, CS] storage dtype (Xt, or X for the exact path)
+    float *part;       // [S, K2, JP, MP] fp32 partial sums
+    int B, C_out, H, W, Ho, Wo;
+    int kH, kW, sh, sw, ph, pw;
+    int CS;            // channel stride of A (multiple of 16)
+    int NBG;           // batch groups (BI images each)
+    int RB, CW, CWp;   // output rows and columns per step; CWp = CW rounded up to 4
+    int NSTRIP, NBAND; // steps per batch group = NSTRIP * NBAND
+    int NR, NOLD, NNEW;  // rows of A per step: NR = (RB-1)*sh + kH; NOLD kept from the previous step, NNEW loaded
+    int BWc;           // columns of A staged per row = (CWp-1)*sw + kW
+    int WM, WJ, WK;    // wave arrangement inside a workgroup (product 4)
+    int M_WG, J_WG;    // workgroup tile: output channels and probe columns
+    int ASTR, BSTR;    // LDS strides (units) per pixel slot / per staged column
+    int NCHR;          // vector chunks of dY staged per row and output channel
+    int NTM, NTJ;      // tiles along C_out and along the probe columns
+    int S, NS;         // K-splits and total steps
+    int K2, NOG;       // kernel offsets and offset groups of <= 9
+    int MP, JP;        // padded extents of the partial buffer
+    int dy_vec;        // 1: dY planes allow aligned 16-byte loads
+    int a_units, b_units;  // LDS units of the two staging tiles
+};
+
+}  // namespace xc

@@ -1,0 +1,595 @@
+// Offset-wise correlation of the residual with a channels-last activation-like
+// tensor (Algorithm 1, backward step 3 combined with the shift of step 4):
+//
+//   G[m,j,ky,kx] = sum_{b,oy,ox} dY[b,m,oy,ox] * A[b, oy*sh+ky-ph, ox*sw+kx-pw, j]
+//
+// and the final reduction + left multiplication with Z/r (backward step 4,
+// Eq. (6) step (iii)).  With A = Xt this is the XConv estimate, with A = X in
+// channels-last form it is the exact gradient of Eq. (2)/(5).
+//
+// Shape of the work: an implicit GEMM with M = C_out, N = (columns of A) x kH*kW
+// and a very long reduction K = B*Ho*Wo.  Only a handful of output tiles exist,
+// so the reduction is split over workgroups (deterministic two-pass reduction:
+// partial tiles to scratch, then reduce_expand_kernel).
+//
+// Mapping to the matrix cores.  The reduction index is (image, pixel); the MFMA
+// needs several consecutive k per lane for the 16-bit types, and the +-1 pixel
+// shifts of the kernel offsets would break the alignment of any vector taken
+// along x or y.  The kernel therefore packs the *batch*: for 16-bit storage one
+// LDS unit is the 8 values of 8 consecutive images at one (pixel, channel), so a
+// kernel offset or a stride only changes which unit a lane reads.  dY (NCHW) and
+// A (channels-last) are both brought into that form while they are staged into
+// LDS, by an 8x8 transpose in registers.  For fp32 storage the MFMA takes one k
+// per lane and a unit is a single float of a single image.
+//
+// One MFMA k-step covers 4 pixel slots (lane group g = lane/16 takes slot g):
+//   A operand  lane (m = lane%16, g):  dY unit of pixel slot g, output channel m
+//   B operand  lane (j = lane%16, g):  A  unit of the shifted pixel, column j
+//   D          16x16 tile of G for one kernel offset
+// A wave owns MT*16 output channels x 16 columns x up to 9 offsets (MT*9
+// accumulator tiles) and walks over pixels; a workgroup is WM x WJ x WK waves
+// (output channels x columns x a split of the k-steps).
+//
+// Staging.  A step is RB output rows x CW output columns of BI images.  The rows
+// of A it needs live in an LDS ring, so consecutive steps of one image reload
+// only the new rows.  Global loads for step t+1 are issued into registers before
+// the MFMA loop of step t and written to LDS after it.
+#include <type_traits>
+
+#include "common.h"
+#include "launch.h"
+
+namespace xc {
+
+constexpr int kMaxOff = 9;
+
+struct StepPos {
+    int bg, oy0, x0;
+};
+
+__device__ inline StepPos decode_step(const CorrParams &P, int t)
+{
+    StepPos s;
+    const int band = t % P.NBAND;
+    t /= P.NBAND;
+    const int strip = t % P.NSTRIP;
+    s.bg = t / P.NSTRIP;
+    s.oy0 = band * P.RB;
+    s.x0 = strip * P.CW;
+    return s;
+}
+
+template <int DT, int MT, int NA, int NB>
+__global__ __launch_bounds__(kThreads) void corr_kernel(const CorrParams P)
+{
+    constexpr bool F32 = (DT == XCONV_F32);
+    constexpr int BI = F32 ? 1 : 8;   // images per LDS unit
+    constexpr int EPV = F32 ? 4 : 8;  // elements per 16-byte global vector
+    using unit_t = typename std::conditional<F32, float, uint4>::type;
+    using elem_t = typename std::conditional<F32, float, uint16_t>::type;
+
+    extern __shared__ uint4 lds_raw[];
+    unit_t *lds_a = reinterpret_cast<unit_t *>(lds_raw);
+    unit_t *lds_b = lds_a + P.a_units;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int jl = lane & 15, g = lane >> 4;
+    const int wm = wave % P.WM, wj = (wave / P.WM) % P.WJ, wk = wave / (P.WM * P.WJ);
+
+    const int tm = blockIdx.y % P.NTM, tj = blockIdx.y / P.NTM;
+    const int m0 = tm * P.M_WG;   // first output channel of the workgroup tile
+    const int jb = tj * P.J_WG;   // first column of A of the workgroup tile
+    const int o_first = blockIdx.z * kMaxOff;
+    const int noff = (P.K2 - o_first) < kMaxOff ? (P.K2 - o_first) : kMaxOff;
+
+    const int HoWo = P.Ho * P.Wo;
+    const elem_t *dY = static_cast<const elem_t *>(P.dY);
+    const elem_t *Ag = static_cast<const elem_t *>(P.A);
+
+    // my share of the steps
+    const int t_begin = (int)(((long long)P.NS * blockIdx.x) / P.S);
+    const int t_end = (int)(((long long)P.NS * (blockIdx.x + 1)) / P.S);
+
+    // ---- per-thread staging tasks, decoded once -------------------------------
+    // dY task: (rb, ml, cc) = output row in the band, channel in the tile, vector chunk in the row
+    const int ntask_a = P.RB * P.M_WG * P.NCHR;
+    int a_dec[NA];
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+        const int task = tid + i * kThreads;
+        const int cc = task % P.NCHR;
+        const int ml = (task / P.NCHR) % P.M_WG;
+        const int rb = task / (P.NCHR * P.M_WG);
+        a_dec[i] = (task < ntask_a) ? ((rb << 22) | (ml << 8) | cc) : -1;
+    }
+    // A task: (rr, c, jc) = row among the rows to load, staged column, vector of EPV channels
+    const int JC = P.J_WG / EPV;
+    const int ntask_b = P.NNEW * P.BWc * JC;
+    int b_dec[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        const int task = tid + i * kThreads;
+        const int jc = task % JC;
+        const int c = (task / JC) % P.BWc;
+        const int rr = task / (JC * P.BWc);
+        b_dec[i] = (task < ntask_b) ? ((rr << 22) | (c << 6) | jc) : -1;
+    }
+
+    uint4 ra[NA][BI];
+    uint4 rbv[NB][BI];
+
+    // ---- dY: global -> registers ----------------------------------------------
+    auto a_load = [&](int step) {
+        const StepPos sp = decode_step(P, step);
+#pragma unroll
+        for (int i = 0; i < NA; ++i) {
+            if (a_dec[i] < 0) continue;
+            const int rb = a_dec[i] >> 22, ml = (a_dec[i] >> 8) & 0x3fff, cc = a_dec[i] & 0xff;
+            const int oy = sp.oy0 + rb;
+            const int f0 = oy * P.Wo + sp.x0;
+            const int chunk = f0 / EPV + cc;
+            const int m = m0 + ml;
+            const bool ok = (oy < P.Ho) && (m < P.C_out);
+#pragma unroll
+            for (int img = 0; img < BI; ++img) {
+                const int b = sp.bg * BI + img;
+                uint4 v = uint4{0u, 0u, 0u, 0u};
+                if (ok && b < P.B) {
+                    const elem_t *src = dY + ((size_t)b * P.C_out + m) * HoWo + (size_t)chunk * EPV;
+                    if (P.dy_vec) {
+                        if (chunk * EPV < HoWo) v = *reinterpret_cast<const uint4 *>(src);
+                    } else {
+                        uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+                        for (int e = 0; e < EPV; ++e) {
+                            if (chunk * EPV + e < HoWo) {
+                                if constexpr (F32) w[e] = __float_as_uint(src[e]);
+                                else w[e >> 1] |= (uint32_t)src[e] << (16 * (e & 1));
+                            }
+                        }
+                        v = uint4{w[0], w[1], w[2], w[3]};
+                    }
+                }
+                ra[i][img] = v;
+            }
+        }
+    };
+
+    // ---- dY: registers -> LDS (every pixel slot of the step is written) --------
+    auto a_store = [&](int step) {
+        const StepPos sp = decode_step(P, step);
+        const int cw_eff = (P.Wo - sp.x0) < P.CW ? (P.Wo - sp.x0) : P.CW;
+#pragma unroll
+        for (int i = 0; i < NA; ++i) {
+            if (a_dec[i] < 0) continue;
+            const int rb = a_dec[i] >> 22, ml = (a_dec[i] >> 8) & 0x3fff, cc = a_dec[i] & 0xff;
+            const int f0 = (sp.oy0 + rb) * P.Wo + sp.x0;
+            const int chunk = f0 / EPV + cc;
+            const int xs0 = chunk * EPV - f0;  // slot of the chunk's first pixel (may be negative)
+            unit_t *dst = lds_a + (size_t)(rb * P.CWp) * P.ASTR + ml;
+            if constexpr (F32) {
+                const uint32_t w[4] = {ra[i][0].x, ra[i][0].y, ra[i][0].z, ra[i][0].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int xs = xs0 + e;
+                    if (xs >= 0 && xs < P.CWp) dst[xs * P.ASTR] = (xs < cw_eff) ? __uint_as_float(w[e]) : 0.0f;
+                }
+            } else {
+                uint32_t rows[8][4];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) { rows[q][0] = ra[i][q].x; rows[q][1] = ra[i][q].y; rows[q][2] = ra[i][q].z; rows[q][3] = ra[i][q].w; }
+                uint4 cols[8];
+                transpose_rows8<4>(rows, cols);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int xs = xs0 + e;
+                    if (xs >= 0 && xs < P.CWp) dst[xs * P.ASTR] = (xs < cw_eff) ? cols[e] : uint4{0u, 0u, 0u, 0u};
+                }
+            }
+        }
+    };
+
+    // ---- A rows: global -> registers.  Rows are in padded coordinates (iy + ph).
+    auto b_load_task = [&](const StepPos &sp, int row_first, int rr, int c, int jc, uint4 (&dst)[BI]) {
+        const int iy = row_first + rr - P.ph;
+        const int ix = sp.x0 * P.sw - P.pw + c;
+        const bool ok = iy >= 0 && iy < P.H && ix >= 0 && ix < P.W;
+#pragma unroll
+        for (int img = 0; img < BI; ++img) {
+            const int b = sp.bg * BI + img;
+            uint4 v = uint4{0u, 0u, 0u, 0u};
+            if (ok && b < P.B) v = *reinterpret_cast<const uint4 *>(Ag + (((size_t)b * P.H + iy) * P.W + ix) * P.CS + jb + jc * EPV);
+            dst[img] = v;
+        }
+    };
+    auto b_store_task = [&](int row_first, int rr, int c, int jc, const uint4 (&src)[BI]) {
+        const int slot = (row_first + rr) % P.NR;
+        if constexpr (F32) {
+            float *dst = lds_b + (size_t)(slot * P.BWc + c) * P.BSTR + jc * 4;
+            *reinterpret_cast<uint4 *>(dst) = src[0];
+        } else {
+            uint32_t rows[8][4];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) { rows[q][0] = src[q].x; rows[q][1] = src[q].y; rows[q][2] = src[q].z; rows[q][3] = src[q].w; }
+            uint4 cols[8];
+            transpose_rows8<4>(rows, cols);
+            uint4 *dst = lds_b + (size_t)(slot * P.BWc + c) * P.BSTR + jc * 9;  // 9 units per 8 columns: bank spreading
+#pragma unroll
+            for (int e = 0; e < 8; ++e) dst[e] = cols[e];
+        }
+    };
+    // rows the step loads in steady state: [oy0*sh + NOLD, oy0*sh + NR)
+    auto b_load = [&](int step) {
+        const StepPos sp = decode_step(P, step);
+        const int row_first = sp.oy0 * P.sh + P.NOLD;
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            if (b_dec[i] < 0) continue;
+            b_load_task(sp, row_first, b_dec[i] >> 22, (b_dec[i] >> 6) & 0xffff, b_dec[i] & 0x3f, rbv[i]);
+        }
+    };
+    auto b_store = [&](int step) {
+        const StepPos sp = decode_step(P, step);
+        const int row_first = sp.oy0 * P.sh + P.NOLD;
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            if (b_dec[i] < 0) continue;
+            b_store_task(row_first, b_dec[i] >> 22, (b_dec[i] >> 6) & 0xffff, b_dec[i] & 0x3f, rbv[i]);
+        }
+    };
+    // rows [oy0*sh, oy0*sh + NOLD) that a step normally inherits from its predecessor
+    auto b_fill_old = [&](int step) {
+        const StepPos sp = decode_step(P, step);
+        const int row_first = sp.oy0 * P.sh;
+        const int ntask = P.NOLD * P.BWc * JC;
+        for (int task = tid; task < ntask; task += kThreads) {
+            const int jc = task % JC, c = (task / JC) % P.BWc, rr = task / (JC * P.BWc);
+            uint4 tmp[BI];
+            b_load_task(sp, row_first, rr, c, jc, tmp);
+            b_store_task(row_first, rr, c, jc, tmp);
+        }
+    };
+
+    // ---- accumulators -----------------------------------------------------------
+    f32x4 acc[MT][kMaxOff];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int o = 0; o < kMaxOff; ++o) acc[mt][o] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    int off_ky[kMaxOff], off_kx[kMaxOff];
+#pragma unroll
+    for (int o = 0; o < kMaxOff; ++o) {
+        const int oo = (o < noff) ? (o_first + o) : o_first;
+        off_ky[o] = oo / P.kW;
+        off_kx[o] = oo % P.kW;
+    }
+
+    const int NKS = (P.RB * P.CWp) >> 2;  // k-steps (4 pixel slots each) per step
+    const int a_lane = g * P.ASTR + (wm * MT) * 16 + jl;
+    const int b_lane = F32 ? (g * P.sw * P.BSTR + wj * 16 + jl) : (g * P.sw * P.BSTR + wj * 18 + jl + (jl >> 3));
+
+    if (t_begin < t_end) {
+        a_load(t_begin);
+        b_load(t_begin);
+    }
+    int prev_bg = -1, prev_x0 = -1, prev_oy0 = -1;
+    for (int step = t_begin; step < t_end; ++step) {
+        const StepPos sp = decode_step(P, step);
+        __syncthreads();  // everyone is done reading the tiles of the previous step
+        const bool fresh = !(sp.bg == prev_bg && sp.x0 == prev_x0 && sp.oy0 == prev_oy0 + P.RB);
+        if (fresh && P.NOLD > 0) b_fill_old(step);
+        a_store(step);
+        b_store(step);
+        prev_bg = sp.bg; prev_x0 = sp.x0; prev_oy0 = sp.oy0;
+        __syncthreads();
+        if (step + 1 < t_end) {
+            a_load(step + 1);
+            b_load(step + 1);
+        }
+
+        for (int ks = wk; ks < NKS; ks += P.WK) {
+            const int p0 = ks << 2;
+            const int rb = p0 / P.CWp;
+            const int xs0 = p0 - rb * P.CWp;
+            unit_t af[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) af[mt] = lds_a[(size_t)p0 * P.ASTR + a_lane + mt * 16];
+            const int rowp = (sp.oy0 + rb) * P.sh;
+#pragma unroll
+            for (int o = 0; o < kMaxOff; ++o) {
+                if (o < noff) {
+                    const int slot = (rowp + off_ky[o]) % P.NR;
+                    const int col = xs0 * P.sw + off_kx[o];
+                    const unit_t bf = lds_b[(size_t)(slot * P.BWc + col) * P.BSTR + b_lane];
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        if constexpr (F32) acc[mt][o] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[mt], bf, acc[mt][o], 0, 0, 0);
+                        else acc[mt][o] = mfma16<DT>(af[mt], bf, acc[mt][o]);
+                    }
+                }
+            }
+        }
+    }
+
+    // ---- reduce the WK k-split waves through LDS, then write the partial tile --
+    // One buffer per (wm, wj) group; waves wk = 1..WK-1 hand their tiles to wave
+    // wk = 0 one after the other, so the summation order is fixed.
+    f32x4 *red = reinterpret_cast<f32x4 *>(lds_raw) + ((size_t)(wm + P.WM * wj) * MT * kMaxOff) * 64 + lane;
+    for (int k = 1; k < P.WK; ++k) {
+        __syncthreads();
+        if (wk == k) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int o = 0; o < kMaxOff; ++o) red[(mt * kMaxOff + o) * 64] = acc[mt][o];
+        }
+        __syncthreads();
+        if (wk == 0) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int o = 0; o < kMaxOff; ++o) acc[mt][o] += red[(mt * kMaxOff + o) * 64];
+        }
+    }
+    if (wk == 0) {
+        // D tile: lane (jl, g) holds rows 4g..4g+3 (output channels) of column jl
+        const int jcol = jb + wj * 16 + jl;
+#pragma unroll
+        for (int o = 0; o < kMaxOff; ++o) {
+            if (o < noff) {
+                float *dst = P.part + (((size_t)blockIdx.x * P.K2 + (o_first + o)) * P.JP + jcol) * P.MP + m0 + (wm * MT) * 16 + 4 * g;
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) *reinterpret_cast<f32x4 *>(dst + mt * 16) = acc[mt][o];
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Second pass: sum the S partial tiles in a fixed order and either expand through
+// Z/r (Algorithm 1 backward step 4) or, on the exact path, just transpose into
+// dW[m,n,ky,kx].  One workgroup per (kernel offset, 16 output channels).
+// ---------------------------------------------------------------------------
+constexpr int kRedJ = 1024;
+
+__global__ __launch_bounds__(kThreads) void reduce_expand_kernel(const float *__restrict__ part, const float *__restrict__ Z,
+                                                                 float *__restrict__ dW, int S, int K2, int JP, int MP,
+                                                                 int C_out, int C_in, int r, int Q)
+{
+    __shared__ float T[kRedJ][16];
+    const int o = blockIdx.x, mb = blockIdx.y * 16;
+    const int tid = threadIdx.x, mm = tid & 15, tl = tid >> 4;
+    const int m = mb + mm;
+    for (int jbase = 0; jbase < Q; jbase += kRedJ) {
+        const int jn = (Q - jbase) < kRedJ ? (Q - jbase) : kRedJ;
+        __syncthreads();
+        for (int j = tl; j < jn; j += 16) {
+            float s = 0.f;
+            const float *src = part + ((size_t)o * JP + jbase + j) * MP + mb + mm;
+            for (int k = 0; k < S; ++k) s += src[(size_t)k * K2 * JP * MP];
+            T[j][mm] = s;
+        }
+        __syncthreads();
+        if (Z != nullptr) {
+            // Q == r <= kRedJ: a single pass
+            const float inv_r = 1.0f / (float)r;
+            for (int n = tl; n < C_in; n += 16) {
+                float s = 0.f;
+                const float *zn = Z + (size_t)n * r;
+                for (int j = 0; j < jn; ++j) s = fmaf(zn[j], T[j][mm], s);
+                if (m < C_out) dW[((size_t)m * C_in + n) * K2 + o] = s * inv_r;
+            }
+        } else {
+            for (int j = tl; j < jn; j += 16)
+                if (m < C_out) dW[((size_t)m * C_in + jbase + j) * K2 + o] = T[j][mm];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host: launch plan
+// ---------------------------------------------------------------------------
+static int env_int(const char *name, int dflt)
+{
+    const char *v = getenv(name);
+    return (v && *v) ? atoi(v) : dflt;
+}
+
+static const size_t kLdsLimit = 160 * 1024;
+
+
+static void fill_geometry(CorrParams &P, int dtype, int RB, int CW)
+{
+    const bool f32 = dtype == XCONV_F32;
+    const int EPV = f32 ? 4 : 8;
+    P.RB = RB;
+    P.CW = CW;
+    P.CWp = round_up(CW, 4);
+    P.NSTRIP = ceil_div(P.Wo, CW);
+    P.NBAND = ceil_div(P.Ho, RB);
+    P.NR = (RB - 1) * P.sh + P.kH;
+    P.NOLD = P.kH > P.sh ? P.kH - P.sh : 0;
+    P.NNEW = P.NR - P.NOLD;
+    P.BWc = (P.CWp - 1) * P.sw + P.kW;
+    // vector chunks of EPV pixels that can intersect a row segment of CWp slots,
+    // over all alignments of the segment start (periodic in the row and strip index)
+    int nch = 1;
+    for (int oy = 0; oy < P.Ho && oy < 8; ++oy)
+        for (int s = 0; s < P.NSTRIP && s < 8; ++s) {
+            const int f0 = oy * P.Wo + s * CW;
+            const int need = ceil_div(f0 % EPV + P.CWp, EPV);
+            if (need > nch) nch = need;
+        }
+    P.NCHR = nch;
+    if (f32) {
+        // strides chosen so that the four lane groups of a k-step hit different banks
+        P.ASTR = P.M_WG + (80 - P.M_WG % 64) % 64;
+        P.BSTR = P.J_WG + (80 - P.J_WG % 64) % 64;
+    } else {
+        P.ASTR = P.M_WG + 1;
+        P.BSTR = P.J_WG / 8 * 9;
+    }
+    P.a_units = round_up(RB * P.CWp * P.ASTR, 4);
+    P.b_units = P.NR * P.BWc * P.BSTR;
+    P.NS = P.NBG * P.NSTRIP * P.NBAND;
+}
+
+static size_t lds_bytes_of(const CorrParams &P, int dtype, int MT)
+{
+    const size_t unit = dtype == XCONV_F32 ? 4 : 16;
+    const size_t stage = ((size_t)P.a_units + P.b_units) * unit;
+    const size_t red = P.WK > 1 ? (size_t)P.WM * P.WJ * MT * kMaxOff * 64 * 16 : 0;
+    return stage > red ? stage : red;
+}
+
+static int corr_mt(int C_out) { return C_out > 16 ? 4 : 1; }
+
+static bool geometry_fits(const CorrParams &P, int dtype, int MT)
+{
+    const bool f32 = dtype == XCONV_F32;
+    const int EPV = f32 ? 4 : 8;
+    const int na_max = f32 ? 8 : 2, nb_max = f32 ? 4 : 2;
+    if (lds_bytes_of(P, dtype, MT) > kLdsLimit) return false;
+    if (P.RB * P.M_WG * P.NCHR > kThreads * na_max) return false;
+    if (P.NNEW * P.BWc * (P.J_WG / EPV) > kThreads * nb_max) return false;
+    if (P.NCHR > 255 || P.BWc > 65535 || P.M_WG > 16383 || P.RB > 255) return false;
+    return true;
+}
+
+bool plan_corr(CorrParams &P, int dtype, int B, int C_out, int H, int W, int kH, int kW, int sh, int sw, int ph, int pw,
+               int CS, bool dy_aligned)
+{
+    const bool f32 = dtype == XCONV_F32;
+    const int BI = f32 ? 1 : 8, EPV = f32 ? 4 : 8;
+    P.B = B; P.C_out = C_out; P.H = H; P.W = W;
+    P.kH = kH; P.kW = kW; P.sh = sh; P.sw = sw; P.ph = ph; P.pw = pw;
+    P.Ho = (H + 2 * ph - kH) / sh + 1;
+    P.Wo = (W + 2 * pw - kW) / sw + 1;
+    P.CS = CS;
+    P.NBG = ceil_div(B, BI);
+    P.K2 = kH * kW;
+    P.NOG = ceil_div(P.K2, kMaxOff);
+    P.dy_vec = (dy_aligned && ((long long)P.Ho * P.Wo) % EPV == 0) ? 1 : 0;
+
+    const int MT = corr_mt(C_out);
+    const int nwm = ceil_div(C_out, 16 * MT), nwj = CS / 16;
+    // waves along the A columns share dY through LDS, so prefer them; WJ must divide the column tiles
+    int WJ = env_int("XCONV_CORR_WJ", 0);
+    if (WJ != 1 && WJ != 2 && WJ != 4) WJ = (nwj % 4 == 0) ? 4 : (nwj % 2 == 0) ? 2 : 1;
+    if (nwj % WJ != 0) WJ = 1;
+    int WM = env_int("XCONV_CORR_WM", 0);
+    if (WM != 1 && WM != 2 && WM != 4) WM = nwm >= 4 ? 4 : nwm >= 2 ? 2 : 1;
+    while (WM * WJ > 4) WM >>= 1;
+    P.WM = WM; P.WJ = WJ; P.WK = 4 / (WM * WJ);
+    P.M_WG = WM * MT * 16;
+    P.J_WG = WJ * 16;
+    P.NTM = ceil_div(C_out, P.M_WG);
+    P.NTJ = CS / P.J_WG;
+    P.MP = P.NTM * P.M_WG;
+    P.JP = CS;
+
+    // Step shape: the widest strip that fits, then the tallest band under the slot cap.
+    const int slots_cap = env_int("XCONV_CORR_SLOTS", f32 ? 128 : 64);
+    int bestRB = env_int("XCONV_CORR_RB", 0), bestCW = env_int("XCONV_CORR_CW", 0);
+    if (bestRB <= 0 || bestCW <= 0) {
+        bestRB = bestCW = 0;
+        int prevCW = -1;
+        for (int nstrip = 1; nstrip <= P.Wo && bestRB == 0; nstrip = nstrip < 4 ? nstrip + 1 : nstrip + nstrip / 2) {
+            int CW = nstrip == 1 ? P.Wo : round_up(ceil_div(P.Wo, nstrip), 4);
+            if (CW > P.Wo) CW = P.Wo;
+            if (CW == prevCW) continue;
+            prevCW = CW;
+            if (round_up(CW, 4) > slots_cap && CW > 4) continue;
+            long long best_score = -1;
+            for (int RB = 1; RB <= P.Ho && RB <= 32; ++RB) {
+                fill_geometry(P, dtype, RB, CW);
+                if (RB > 1 && RB * P.CWp > slots_cap) break;
+                if (!geometry_fits(P, dtype, MT)) break;
+                const long long useful = (long long)P.Ho * P.Wo;
+                const long long padded = (long long)P.NBAND * RB * P.NSTRIP * P.CWp;
+                const long long score = (long long)RB * P.CWp * 1000 * useful / padded;
+                if (score > best_score) { best_score = score; bestRB = RB; bestCW = CW; }
+            }
+        }
+        if (bestRB == 0) {  // last resort: one row, four columns
+            bestRB = 1;
+            bestCW = P.Wo < 4 ? P.Wo : 4;
+        }
+    }
+    fill_geometry(P, dtype, bestRB, bestCW);
+    if (!geometry_fits(P, dtype, MT)) return false;
+
+    // K-split: fill the 256 compute units (two workgroups each when LDS allows)
+    const size_t lds = lds_bytes_of(P, dtype, MT);
+    const int per_cu = env_int("XCONV_CORR_WGS_PER_CU", lds <= 72 * 1024 ? 2 : 1);
+    const int ny = P.NTM * P.NTJ * P.NOG;
+    int target = env_int("XCONV_CORR_SPLITS", 0);
+    if (target <= 0) {
+        target = (256 * per_cu) / ny;
+        if (target < 1) target = 1;
+        if (target > P.NS) target = P.NS;
+        // prefer a split count that divides the steps evenly
+        int bestS = target;
+        double best_eff = 0.0;
+        for (int S = target; S >= 1 && S >= target * 3 / 4; --S) {
+            const double eff = (double)P.NS / ((double)S * ceil_div(P.NS, S)) * ((double)S / target);
+            if (eff > best_eff + 1e-9) { best_eff = eff; bestS = S; }
+        }
+        target = bestS;
+    }
+    if (target > P.NS) target = P.NS;
+    if (target < 1) target = 1;
+    P.S = target;
+    return true;
+}
+
+size_t corr_lds_bytes(int dtype, const CorrParams &P) { return lds_bytes_of(P, dtype, corr_mt(P.C_out)); }
+
+size_t corr_partial_bytes(const CorrParams &P) { return (size_t)P.S * P.K2 * P.JP * P.MP * sizeof(float); }
+
+template <int DT, int MT, int NA, int NB> static hipError_t launch_corr_cfg(const CorrParams &P, size_t lds, hipStream_t st)
+{
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(corr_kernel<DT, MT, NA, NB>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL((corr_kernel<DT, MT, NA, NB>), dim3(P.S, P.NTM * P.NTJ, P.NOG), dim3(kThreads), lds, st, P);
+    return hipGetLastError();
+}
+
+template <int DT, int MT> static hipError_t launch_corr_16(const CorrParams &P, size_t lds, hipStream_t st)
+{
+    const int na = ceil_div(P.RB * P.M_WG * P.NCHR, kThreads), nb = ceil_div(P.NNEW * P.BWc * (P.J_WG / 8), kThreads);
+    if (na <= 1 && nb <= 1) return launch_corr_cfg<DT, MT, 1, 1>(P, lds, st);
+    if (na <= 1) return launch_corr_cfg<DT, MT, 1, 2>(P, lds, st);
+    if (nb <= 1) return launch_corr_cfg<DT, MT, 2, 1>(P, lds, st);
+    return launch_corr_cfg<DT, MT, 2, 2>(P, lds, st);
+}
+
+hipError_t launch_corr(int dtype, const CorrParams &P, hipStream_t st)
+{
+    const int MT = corr_mt(P.C_out);
+    const size_t lds = lds_bytes_of(P, dtype, MT);
+    if (dtype == XCONV_F32) {
+        if (MT == 4) return launch_corr_cfg<XCONV_F32, 4, 8, 4>(P, lds, st);
+        return launch_corr_cfg<XCONV_F32, 1, 8, 4>(P, lds, st);
+    }
+    if (dtype == XCONV_BF16) {
+        if (MT == 4) return launch_corr_16<XCONV_BF16, 4>(P, lds, st);
+        return launch_corr_16<XCONV_BF16, 1>(P, lds, st);
+    }
+    if (MT == 4) return launch_corr_16<XCONV_F16, 4>(P, lds, st);
+    return launch_corr_16<XCONV_F16, 1>(P, lds, st);
+}
+
+hipError_t launch_reduce_expand(const CorrParams &P, const float *Z, float *dW, int C_in, int r, hipStream_t st)
+{
+    const int Q = Z ? r : C_in;
+    hipLaunchKernelGGL(reduce_expand_kernel, dim3(P.K2, ceil_div(P.C_out, 16)), dim3(kThreads), 0, st, P.part, Z, dW, P.S, P.K2,
+                       P.JP, P.MP, P.C_out, C_in, r, Q);
+    return hipGetLastError();
+}
+
+}  // namespace xc

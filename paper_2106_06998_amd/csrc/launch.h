@@ -1,0 +1,31 @@
+// Host-side launch wrappers implemented next to their kernels.
+#pragma once
+#include "common.h"
+
+namespace xc {
+
+// probe_kernels.hip
+void host_probe_matrix(int dist, uint64_t seed, int n, float *Z);
+hipError_t launch_gen_z(float *Z, int n, int dist, uint64_t seed, hipStream_t st);
+bool probe_fast_path_ok(int dtype, int C_in, int HW);
+hipError_t launch_probe(int dtype, const void *X, const float *Z, void *Xt, int B, int C_in, int HW, int r, int CS,
+                        bool z_exact16, hipStream_t st);
+hipError_t launch_probe_generic(int dtype, const void *X, const float *Z, void *Xt, int B, int C_in, int HW, int r, int CS,
+                                hipStream_t st);
+hipError_t launch_unpack(int dtype, const void *Xt, float *out, int B, int HW, int r, int CS, hipStream_t st);
+hipError_t launch_to_nhwc(int dtype, const void *X, void *out, int B, int C, int HW, int CS, hipStream_t st);
+
+// corr_kernels.hip
+// Fills every field of P except the three pointers.  Q is the number of
+// probe/activation columns that carry data (r, or C_in on the exact path), CS
+// their padded stride.  Returns false when no launch shape fits the device.
+bool plan_corr(CorrParams &P, int dtype, int B, int C_out, int H, int W, int kH, int kW, int sh, int sw, int ph, int pw,
+               int CS, bool dy_aligned);
+size_t corr_partial_bytes(const CorrParams &P);
+size_t corr_lds_bytes(int dtype, const CorrParams &P);
+hipError_t launch_corr(int dtype, const CorrParams &P, hipStream_t st);
+// dW[m,n,o] = scale * sum_j Zn[n,j] * sum_s part[s,o,j,m]   (Z != nullptr)
+// dW[m,n,o] = sum_s part[s,o,n,m]                            (Z == nullptr)
+hipError_t launch_reduce_expand(const CorrParams &P, const float *Z, float *dW, int C_in, int r, hipStream_t st);
+
+}  // namespace xc

@@ -1,0 +1,447 @@
+// Probe-side kernels: regeneration of Z[s] from the seed, the forward channel
+// probe Xt = Z^T X (Algorithm 1, forward step 3; Eq. (6) step (i) restricted to
+// the channel axis), and the layout helpers around it.
+//
+// The probe is a skinny contraction: per image it is the product
+//   Xt_b^T [r x HW] = Z^T [r x C_in] * X_b [C_in x HW],
+// read C_in*HW, write r*HW, so it is bound by HBM bandwidth.  It still runs on
+// the matrix cores: at 16-bit storage its arithmetic intensity is above what the
+// vector ALUs deliver at HBM speed.  X is read straight from global memory into
+// the MFMA B operand (pixels are the MFMA columns, so NCHW rows load coalesced),
+// Z^T lives in LDS already arranged as A-operand fragments, and the rows of each
+// 16-row MFMA tile are assigned to probe indices so that a lane ends up holding
+// consecutive probe columns of one pixel, which makes the channels-last store a
+// run of 16-byte vectors.
+#include "common.h"
+#include "launch.h"
+
+namespace xc {
+
+// ---------------------------------------------------------------------------
+// Z[s]: SplitMix64 in counter form.  Word ctr of the stream of `seed` is
+// fin(key + gamma*(ctr+1)) with key = fin(seed + gamma).
+// ---------------------------------------------------------------------------
+__host__ __device__ inline uint64_t mix_fin(uint64_t z)
+{
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+__host__ __device__ inline uint64_t stream_word(uint64_t key, uint64_t ctr)
+{
+    return mix_fin(key + 0x9E3779B97F4A7C15ull * (ctr + 1ull));
+}
+__host__ __device__ inline float probe_entry(int dist, uint64_t key, uint64_t idx)
+{
+    if (dist == XCONV_RADEMACHER) return (stream_word(key, idx) >> 63) ? -1.0f : 1.0f;
+    // Box-Muller in double on two 53-bit uniforms, u1 in (0,1], u2 in [0,1)
+    const double u1 = ((double)(stream_word(key, 2ull * idx) >> 11) + 1.0) * 0x1.0p-53;
+    const double u2 = (double)(stream_word(key, 2ull * idx + 1ull) >> 11) * 0x1.0p-53;
+    return (float)(sqrt(-2.0 * log(u1)) * cos(6.283185307179586476925 * u2));
+}
+
+void host_probe_matrix(int dist, uint64_t seed, int n, float *Z)
+{
+    const uint64_t key = mix_fin(seed + 0x9E3779B97F4A7C15ull);
+    for (int i = 0; i < n; ++i) Z[i] = probe_entry(dist, key, (uint64_t)i);
+}
+
+__global__ __launch_bounds__(kThreads) void gen_z_kernel(float *__restrict__ Z, int n, int dist, uint64_t seed)
+{
+    const int i = blockIdx.x * kThreads + threadIdx.x;
+    if (i >= n) return;
+    const uint64_t key = mix_fin(seed + 0x9E3779B97F4A7C15ull);
+    Z[i] = probe_entry(dist, key, (uint64_t)i);
+}
+
+// Row i of MFMA tile jt holds probe column j0 + jmap: lane group g = i/4 then
+// owns the 4*JT consecutive columns g*4*JT .. (g+1)*4*JT-1 of the 16*JT block.
+__device__ inline int jmap(int jt, int i, int JT) { return (i >> 2) * (4 * JT) + jt * 4 + (i & 3); }
+
+// ---------------------------------------------------------------------------
+// fp32 probe.  v_mfma_f32_16x16x4_f32: A = Z^T tile (16 probe rows x 4
+// channels), B = X tile (4 channels x 16 pixel columns).  Each lane loads four
+// consecutive pixels (16 bytes) of one channel; MFMA t uses element t, so MFMA
+// column n stands for pixel 4n+t of the wave's 64-pixel tile.
+// ---------------------------------------------------------------------------
+template <int JT>
+__global__ __launch_bounds__(kThreads) void probe_f32_kernel(const float *__restrict__ X, const float *__restrict__ Z,
+                                                             float *__restrict__ Xt, int C_in, int HW, int r, int CS,
+                                                             int j0, long long ngroups, int ntiles)
+{
+    extern __shared__ float zs[];  // [KQ][JT][64] A-operand fragments
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int KQ = (C_in + 3) >> 2;
+    for (int e = tid; e < KQ * JT * 64; e += kThreads) {
+        const int l = e & 63, jt = (e >> 6) % JT, kq = (e >> 6) / JT;
+        const int c = kq * 4 + (l >> 4);
+        const int j = j0 + jmap(jt, l & 15, JT);
+        zs[e] = (c < C_in && j < r) ? Z[(size_t)c * r + j] : 0.0f;
+    }
+    __syncthreads();
+
+    const int n = lane & 15, g = lane >> 4;
+    for (int tile = blockIdx.x * 4 + wave; tile < ntiles; tile += gridDim.x * 4) {
+        const long long pg = (long long)tile * 16 + n;
+        const bool valid = pg < ngroups;
+        const long long flat = pg * 4;
+        const int b = valid ? (int)(flat / HW) : 0;
+        const int p = valid ? (int)(flat % HW) : 0;
+        const float *xb = X + (size_t)b * C_in * HW + p;
+        f32x4 acc[JT][4];
+#pragma unroll
+        for (int jt = 0; jt < JT; ++jt)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) acc[jt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+        for (int c0 = 0; c0 < C_in; c0 += 16) {
+            float4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int c = c0 + 4 * u + g;
+                v[u] = (valid && c < C_in) ? *reinterpret_cast<const float4 *>(xb + (size_t)c * HW) : float4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int kq = (c0 >> 2) + u;
+                if (kq < KQ) {
+#pragma unroll
+                    for (int jt = 0; jt < JT; ++jt) {
+                        const float a = zs[(kq * JT + jt) * 64 + lane];
+                        acc[jt][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, v[u].x, acc[jt][0], 0, 0, 0);
+                        acc[jt][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, v[u].y, acc[jt][1], 0, 0, 0);
+                        acc[jt][2] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, v[u].z, acc[jt][2], 0, 0, 0);
+                        acc[jt][3] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, v[u].w, acc[jt][3], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        if (valid) {
+            // lane (n, g) holds rows 4g..4g+3 of every tile = probe columns j0 + g*4*JT + jt*4 + v
+            float *out = Xt + (size_t)flat * CS + j0 + g * (4 * JT);
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int jt = 0; jt < JT; ++jt)
+                    *reinterpret_cast<f32x4 *>(out + (size_t)t * CS + jt * 4) = acc[jt][t];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// 16-bit probe.  v_mfma_f32_16x16x32_{f16,bf16}: a lane supplies 8 consecutive
+// k (channels) of one row/column.  In NCHW the 8 channels of a pixel are HW
+// elements apart, so each lane loads PT consecutive pixels from 8 channel rows
+// and transposes the 8 x PT block in registers; MFMA t then uses pixel t of
+// every lane.  SPLIT: Z is not exactly representable in the storage type
+// (Gaussian or user Z), so it is used as hi + lo (two MFMAs); +-1 needs one.
+// ---------------------------------------------------------------------------
+template <int DT, int JT, int PT, bool SPLIT>
+__global__ __launch_bounds__(kThreads) void probe_16_kernel(const uint16_t *__restrict__ X, const float *__restrict__ Z,
+                                                            uint16_t *__restrict__ Xt, int C_in, int HW, int r, int CS,
+                                                            int j0, long long ngroups, int ntiles)
+{
+    extern __shared__ uint4 zf[];  // [SPLIT?2:1][KK][JT][64] A-operand fragments
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int KK = (C_in + 31) >> 5;
+    const int nfrag = KK * JT * 64;
+    for (int e = tid; e < nfrag; e += kThreads) {
+        const int l = e & 63, jt = (e >> 6) % JT, kk = (e >> 6) / JT;
+        const int j = j0 + jmap(jt, l & 15, JT);
+        uint32_t hi[4], lo[4];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int c = kk * 32 + 8 * (l >> 4) + q;
+            const float z = (c < C_in && j < r) ? Z[(size_t)c * r + j] : 0.0f;
+            const uint16_t h = f32_to_st16<DT>(z);
+            const uint16_t w = f32_to_st16<DT>(z - st16_to_f32<DT>(h));
+            if (q & 1) { hi[q >> 1] |= (uint32_t)h << 16; lo[q >> 1] |= (uint32_t)w << 16; }
+            else       { hi[q >> 1] = h; lo[q >> 1] = w; }
+        }
+        zf[e] = uint4{hi[0], hi[1], hi[2], hi[3]};
+        if (SPLIT) zf[nfrag + e] = uint4{lo[0], lo[1], lo[2], lo[3]};
+    }
+    __syncthreads();
+
+    constexpr int NW = PT / 2;
+    const int n = lane & 15, g = lane >> 4;
+    for (int tile = blockIdx.x * 4 + wave; tile < ntiles; tile += gridDim.x * 4) {
+        const long long pg = (long long)tile * 16 + n;
+        const bool valid = pg < ngroups;
+        const long long flat = pg * PT;
+        const int b = valid ? (int)(flat / HW) : 0;
+        const int p = valid ? (int)(flat % HW) : 0;
+        const uint16_t *xb = X + (size_t)b * C_in * HW + p;
+        f32x4 acc[JT][PT];
+#pragma unroll
+        for (int jt = 0; jt < JT; ++jt)
+#pragma unroll
+            for (int t = 0; t < PT; ++t) acc[jt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+        for (int kk = 0; kk < KK; ++kk) {
+            uint32_t rows[8][NW];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int c = kk * 32 + 8 * g + q;
+                const bool ok = valid && c < C_in;
+                if constexpr (PT == 8) {
+                    const uint4 v = ok ? *reinterpret_cast<const uint4 *>(xb + (size_t)c * HW) : uint4{0, 0, 0, 0};
+                    rows[q][0] = v.x; rows[q][1] = v.y; rows[q][2] = v.z; rows[q][3] = v.w;
+                } else {
+                    const uint2 v = ok ? *reinterpret_cast<const uint2 *>(xb + (size_t)c * HW) : uint2{0, 0};
+                    rows[q][0] = v.x; rows[q][1] = v.y;
+                }
+            }
+            uint4 cols[PT];
+            transpose_rows8<NW>(rows, cols);
+#pragma unroll
+            for (int jt = 0; jt < JT; ++jt) {
+                const uint4 ah = zf[(kk * JT + jt) * 64 + lane];
+#pragma unroll
+                for (int t = 0; t < PT; ++t) acc[jt][t] = mfma16<DT>(ah, cols[t], acc[jt][t]);
+                if constexpr (SPLIT) {
+                    const uint4 al = zf[nfrag + (kk * JT + jt) * 64 + lane];
+#pragma unroll
+                    for (int t = 0; t < PT; ++t) acc[jt][t] = mfma16<DT>(al, cols[t], acc[jt][t]);
+                }
+            }
+        }
+        if (valid) {
+            uint16_t *out = Xt + (size_t)flat * CS + j0 + g * (4 * JT);
+#pragma unroll
+            for (int t = 0; t < PT; ++t)
+#pragma unroll
+                for (int jt = 0; jt < JT; ++jt) {
+                    uint2 w;
+                    w.x = (uint32_t)f32_to_st16<DT>(acc[jt][t][0]) | ((uint32_t)f32_to_st16<DT>(acc[jt][t][1]) << 16);
+                    w.y = (uint32_t)f32_to_st16<DT>(acc[jt][t][2]) | ((uint32_t)f32_to_st16<DT>(acc[jt][t][3]) << 16);
+                    *reinterpret_cast<uint2 *>(out + (size_t)t * CS + jt * 4) = w;
+                }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Any-shape probe on the vector ALUs (used when image planes are not a
+// multiple of the vector width, so the MFMA path's aligned loads do not apply).
+// One thread per (pixel, block of 16 probe columns).
+// ---------------------------------------------------------------------------
+template <int DT>
+__global__ __launch_bounds__(kThreads) void probe_generic_kernel(const void *__restrict__ Xv, const float *__restrict__ Z,
+                                                                 void *__restrict__ Xtv, int C_in, int HW, int r, int CS,
+                                                                 long long npix)
+{
+    const long long flat = (long long)blockIdx.x * kThreads + threadIdx.x;
+    if (flat >= npix) return;
+    const int jb = blockIdx.y * 16;
+    const int b = (int)(flat / HW), p = (int)(flat % HW);
+    float acc[16];
+#pragma unroll
+    for (int jj = 0; jj < 16; ++jj) acc[jj] = 0.f;
+    for (int c = 0; c < C_in; ++c) {
+        const size_t xi = ((size_t)b * C_in + c) * HW + p;
+        float x;
+        if constexpr (DT == XCONV_F32) x = static_cast<const float *>(Xv)[xi];
+        else x = st16_to_f32<DT>(static_cast<const uint16_t *>(Xv)[xi]);
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) {
+            const int j = jb + jj;
+            const float z = (j < r) ? Z[(size_t)c * r + j] : 0.f;
+            acc[jj] = fmaf(z, x, acc[jj]);
+        }
+    }
+    const size_t oi = (size_t)flat * CS + jb;
+#pragma unroll
+    for (int jj = 0; jj < 16; ++jj) {
+        if constexpr (DT == XCONV_F32) static_cast<float *>(Xtv)[oi + jj] = acc[jj];
+        else static_cast<uint16_t *>(Xtv)[oi + jj] = f32_to_st16<DT>(acc[jj]);
+    }
+}
+
+// Stored Xt [B, HW, CS] -> plain fp32 [B, r, HW] (test helper).
+template <int DT>
+__global__ __launch_bounds__(kThreads) void unpack_kernel(const void *__restrict__ Xtv, float *__restrict__ out, int HW, int r,
+                                                          int CS, long long total)
+{
+    const long long i = (long long)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= total) return;
+    const int p = (int)(i % HW);
+    const long long bj = i / HW;
+    const int j = (int)(bj % r);
+    const long long b = bj / r;
+    const size_t src = ((size_t)b * HW + p) * CS + j;
+    if constexpr (DT == XCONV_F32) out[i] = static_cast<const float *>(Xtv)[src];
+    else out[i] = st16_to_f32<DT>(static_cast<const uint16_t *>(Xtv)[src]);
+}
+
+// X [B, C, HW] -> channels-last [B, HW, CS] with zero columns C..CS-1 (input of
+// the correlation kernel on the exact-gradient path).  32x32 tiles through LDS.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void to_nhwc_kernel(const T *__restrict__ X, T *__restrict__ out, int C, int HW, int CS)
+{
+    __shared__ T tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+    const int p0 = blockIdx.x * 32, c0 = blockIdx.y * 32, b = blockIdx.z;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int c = c0 + ty + 8 * k, p = p0 + tx;
+        tile[ty + 8 * k][tx] = (c < C && p < HW) ? X[((size_t)b * C + c) * HW + p] : T(0);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int p = p0 + ty + 8 * k, c = c0 + tx;
+        if (p < HW && c < CS) out[((size_t)b * HW + p) * CS + c] = tile[tx][ty + 8 * k];
+    }
+}
+
+// ---------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------
+hipError_t launch_gen_z(float *Z, int n, int dist, uint64_t seed, hipStream_t st)
+{
+    hipLaunchKernelGGL(gen_z_kernel, dim3(ceil_div(n, kThreads)), dim3(kThreads), 0, st, Z, n, dist, seed);
+    return hipGetLastError();
+}
+
+template <typename K> static hipError_t set_lds(K kernel, size_t bytes)
+{
+    if (bytes <= 64 * 1024) return hipSuccess;
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+static int probe_grid(int ntiles)
+{
+    // 4 tiles (one per wave) per workgroup pass; cap the grid so that the
+    // per-workgroup Z staging is amortised over several tiles on large inputs.
+    const int want = ceil_div(ntiles, 4);
+    return want < 2048 ? want : 2048;
+}
+
+template <int JT>
+static hipError_t launch_probe_f32_jt(const float *X, const float *Z, float *Xt, int C_in, int HW, int r, int CS, int j0,
+                                      long long npix, hipStream_t st)
+{
+    const long long ngroups = npix / 4;
+    const int ntiles = (int)((ngroups + 15) / 16);
+    const size_t lds = (size_t)ceil_div(C_in, 4) * JT * 64 * sizeof(float);
+    hipError_t e = set_lds(probe_f32_kernel<JT>, lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(probe_f32_kernel<JT>, dim3(probe_grid(ntiles)), dim3(kThreads), lds, st, X, Z, Xt, C_in, HW, r, CS, j0,
+                       ngroups, ntiles);
+    return hipGetLastError();
+}
+
+template <int DT, int JT, int PT, bool SPLIT>
+static hipError_t launch_probe_16_cfg(const uint16_t *X, const float *Z, uint16_t *Xt, int C_in, int HW, int r, int CS, int j0,
+                                      long long npix, hipStream_t st)
+{
+    const long long ngroups = npix / PT;
+    const int ntiles = (int)((ngroups + 15) / 16);
+    const size_t lds = (size_t)(SPLIT ? 2 : 1) * ceil_div(C_in, 32) * JT * 64 * sizeof(uint4);
+    hipError_t e = set_lds(probe_16_kernel<DT, JT, PT, SPLIT>, lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((probe_16_kernel<DT, JT, PT, SPLIT>), dim3(probe_grid(ntiles)), dim3(kThreads), lds, st, X, Z, Xt, C_in,
+                       HW, r, CS, j0, ngroups, ntiles);
+    return hipGetLastError();
+}
+
+template <int DT, int JT>
+static hipError_t launch_probe_16_jt(const uint16_t *X, const float *Z, uint16_t *Xt, int C_in, int HW, int r, int CS, int j0,
+                                     long long npix, bool split, hipStream_t st)
+{
+    // 8 pixels per lane when the accumulators stay small, 4 for wide probe blocks
+    const bool pt8 = (JT <= 2) && (HW % 8 == 0);
+    if (pt8) {
+        if (split) return launch_probe_16_cfg<DT, JT, 8, true>(X, Z, Xt, C_in, HW, r, CS, j0, npix, st);
+        return launch_probe_16_cfg<DT, JT, 8, false>(X, Z, Xt, C_in, HW, r, CS, j0, npix, st);
+    }
+    if (split) return launch_probe_16_cfg<DT, JT, 4, true>(X, Z, Xt, C_in, HW, r, CS, j0, npix, st);
+    return launch_probe_16_cfg<DT, JT, 4, false>(X, Z, Xt, C_in, HW, r, CS, j0, npix, st);
+}
+
+bool probe_fast_path_ok(int dtype, int C_in, int HW)
+{
+    // aligned vector loads of 4 pixels (16 bytes fp32, 8 bytes 16-bit) per channel row;
+    // LDS for the Z fragments (worst case JT = 4, split) must fit
+    if (HW % 4 != 0) return false;
+    const size_t lds = dtype == XCONV_F32 ? (size_t)ceil_div(C_in, 4) * 4 * 64 * 4 : (size_t)2 * ceil_div(C_in, 32) * 4 * 64 * 16;
+    return lds <= 128 * 1024;
+}
+
+hipError_t launch_probe(int dtype, const void *X, const float *Z, void *Xt, int B, int C_in, int HW, int r, int CS,
+                        bool z_exact16, hipStream_t st)
+{
+    const long long npix = (long long)B * HW;
+    const int ntj = CS / 16;
+    hipError_t e = hipSuccess;
+    for (int t0 = 0; t0 < ntj && e == hipSuccess; t0 += 4) {
+        const int jt = (ntj - t0) < 4 ? (ntj - t0) : 4;
+        const int j0 = t0 * 16;
+        if (dtype == XCONV_F32) {
+            const float *x = static_cast<const float *>(X);
+            float *o = static_cast<float *>(Xt);
+            switch (jt) {
+            case 1: e = launch_probe_f32_jt<1>(x, Z, o, C_in, HW, r, CS, j0, npix, st); break;
+            case 2: e = launch_probe_f32_jt<2>(x, Z, o, C_in, HW, r, CS, j0, npix, st); break;
+            case 3: e = launch_probe_f32_jt<3>(x, Z, o, C_in, HW, r, CS, j0, npix, st); break;
+            default: e = launch_probe_f32_jt<4>(x, Z, o, C_in, HW, r, CS, j0, npix, st); break;
+            }
+        } else {
+            const uint16_t *x = static_cast<const uint16_t *>(X);
+            uint16_t *o = static_cast<uint16_t *>(Xt);
+            const bool split = !z_exact16;
+#define XC_P16(DT)                                                                                        \
+    switch (jt) {                                                                                         \
+    case 1: e = launch_probe_16_jt<DT, 1>(x, Z, o, C_in, HW, r, CS, j0, npix, split, st); break;          \
+    case 2: e = launch_probe_16_jt<DT, 2>(x, Z, o, C_in, HW, r, CS, j0, npix, split, st); break;          \
+    case 3: e = launch_probe_16_jt<DT, 3>(x, Z, o, C_in, HW, r, CS, j0, npix, split, st); break;          \
+    default: e = launch_probe_16_jt<DT, 4>(x, Z, o, C_in, HW, r, CS, j0, npix, split, st); break;         \
+    }
+            if (dtype == XCONV_BF16) { XC_P16(XCONV_BF16) } else { XC_P16(XCONV_F16) }
+#undef XC_P16
+        }
+    }
+    return e;
+}
+
+hipError_t launch_probe_generic(int dtype, const void *X, const float *Z, void *Xt, int B, int C_in, int HW, int r, int CS,
+                                hipStream_t st)
+{
+    const long long npix = (long long)B * HW;
+    dim3 grid((unsigned)((npix + kThreads - 1) / kThreads), CS / 16);
+    if (dtype == XCONV_F32)
+        hipLaunchKernelGGL(probe_generic_kernel<XCONV_F32>, grid, dim3(kThreads), 0, st, X, Z, Xt, C_in, HW, r, CS, npix);
+    else if (dtype == XCONV_BF16)
+        hipLaunchKernelGGL(probe_generic_kernel<XCONV_BF16>, grid, dim3(kThreads), 0, st, X, Z, Xt, C_in, HW, r, CS, npix);
+    else
+        hipLaunchKernelGGL(probe_generic_kernel<XCONV_F16>, grid, dim3(kThreads), 0, st, X, Z, Xt, C_in, HW, r, CS, npix);
+    return hipGetLastError();
+}
+
+hipError_t launch_unpack(int dtype, const void *Xt, float *out, int B, int HW, int r, int CS, hipStream_t st)
+{
+    const long long total = (long long)B * r * HW;
+    dim3 grid((unsigned)((total + kThreads - 1) / kThreads));
+    if (dtype == XCONV_F32)
+        hipLaunchKernelGGL(unpack_kernel<XCONV_F32>, grid, dim3(kThreads), 0, st, Xt, out, HW, r, CS, total);
+    else if (dtype == XCONV_BF16)
+        hipLaunchKernelGGL(unpack_kernel<XCONV_BF16>, grid, dim3(kThreads), 0, st, Xt, out, HW, r, CS, total);
+    else
+        hipLaunchKernelGGL(unpack_kernel<XCONV_F16>, grid, dim3(kThreads), 0, st, Xt, out, HW, r, CS, total);
+    return hipGetLastError();
+}
+
+hipError_t launch_to_nhwc(int dtype, const void *X, void *out, int B, int C, int HW, int CS, hipStream_t st)
+{
+    dim3 grid(ceil_div(HW, 32), ceil_div(CS, 32), B);
+    if (dtype == XCONV_F32)
+        hipLaunchKernelGGL(to_nhwc_kernel<float>, grid, dim3(kThreads), 0, st, static_cast<const float *>(X),
+                           static_cast<float *>(out), C, HW, CS);
+    else
+        hipLaunchKernelGGL(to_nhwc_kernel<uint16_t>, grid, dim3(kThreads), 0, st, static_cast<const uint16_t *>(X),
+                           static_cast<uint16_t *>(out), C, HW, CS);
+    return hipGetLastError();
+}
+
+}  // namespace xc

@@ -1,0 +1,329 @@
+// C ABI of libxconv: argument validation, scratch layout, kernel sequencing and
+// the optional per-kernel event timing.  Declarations and their contracts are
+// in include/xconv.h.
+#include <mutex>
+#include <vector>
+
+#include "common.h"
+#include "launch.h"
+
+using namespace xc;
+
+namespace {
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t elem_bytes(int dtype) { return dtype == XCONV_F32 ? 4 : 2; }
+inline int out_extent(int in, int k, int stride, int pad)
+{
+    const int span = in + 2 * pad - k;
+    return span < 0 ? 0 : span / stride + 1;
+}
+
+// ---- event timing ----------------------------------------------------------
+struct ProfRec {
+    int id;
+    hipEvent_t a, b;
+};
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof;
+std::mutex g_prof_mu;
+
+struct ProfScope {
+    hipStream_t st;
+    int slot = -1;
+    ProfScope(int id, hipStream_t s) : st(s)
+    {
+        if (!g_prof_on) return;
+        ProfRec r{id, nullptr, nullptr};
+        if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
+        (void)hipEventRecord(r.a, st);
+        std::lock_guard<std::mutex> lk(g_prof_mu);
+        g_prof.push_back(r);
+        slot = (int)g_prof.size() - 1;
+    }
+    ~ProfScope()
+    {
+        if (slot < 0) return;
+        std::lock_guard<std::mutex> lk(g_prof_mu);
+        (void)hipEventRecord(g_prof[slot].b, st);
+    }
+};
+
+#define XC_LAUNCH(id, st, expr)               \
+    do {                                      \
+        ProfScope _ps((id), (st));            \
+        hipError_t _e = (expr);               \
+        if (_e != hipSuccess) return XCONV_EHIP; \
+    } while (0)
+
+// ---- plans -------------------------------------------------------------------
+struct PlanKey {
+    int v[14];
+    bool operator==(const PlanKey &o) const
+    {
+        for (int i = 0; i < 14; ++i)
+            if (v[i] != o.v[i]) return false;
+        return true;
+    }
+};
+struct PlanEntry {
+    PlanKey key;
+    CorrParams P;
+    bool ok;
+};
+std::mutex g_plan_mu;
+std::vector<PlanEntry> g_plans;
+
+bool get_plan(CorrParams &P, int dtype, int B, int C_out, int H, int W, int kH, int kW, int sh, int sw, int ph, int pw, int CS,
+              bool dy_aligned)
+{
+    PlanKey k{{dtype, B, C_out, H, W, kH, kW, sh, sw, ph, pw, CS, dy_aligned ? 1 : 0, 0}};
+    {
+        std::lock_guard<std::mutex> lk(g_plan_mu);
+        for (const PlanEntry &e : g_plans)
+            if (e.key == k) {
+                P = e.P;
+                return e.ok;
+            }
+    }
+    PlanEntry e;
+    e.key = k;
+    e.P = CorrParams{};
+    e.ok = plan_corr(e.P, dtype, B, C_out, H, W, kH, kW, sh, sw, ph, pw, CS, dy_aligned);
+    P = e.P;
+    std::lock_guard<std::mutex> lk(g_plan_mu);
+    if (g_plans.size() >= 64) g_plans.erase(g_plans.begin());
+    g_plans.push_back(e);
+    return e.ok;
+}
+
+size_t z_bytes(const xconv_desc *d) { return align_up((size_t)d->C_in * d->r * sizeof(float), 256); }
+
+}  // namespace
+
+extern "C" {
+
+xconv_status xconv_check_desc(const xconv_desc *d)
+{
+    if (!d) return XCONV_EINVAL;
+    if (d->B < 1 || d->C_in < 1 || d->C_out < 1 || d->H < 1 || d->W < 1) return XCONV_EINVAL;
+    if (d->kH < 1 || d->kW < 1 || d->stride_h < 1 || d->stride_w < 1 || d->pad_h < 0 || d->pad_w < 0) return XCONV_EINVAL;
+    if (d->r < 1 || d->reserved != 0) return XCONV_EINVAL;
+    if (d->dtype < XCONV_F32 || d->dtype > XCONV_F16) return XCONV_EINVAL;
+    if (d->layout < XCONV_NCHW || d->layout > XCONV_NHWC) return XCONV_EINVAL;
+    if (d->probe < XCONV_RADEMACHER || d->probe > XCONV_USER_Z) return XCONV_EINVAL;
+    if (out_extent(d->H, d->kH, d->stride_h, d->pad_h) < 1 || out_extent(d->W, d->kW, d->stride_w, d->pad_w) < 1) return XCONV_EINVAL;
+    if (d->layout != XCONV_NCHW) return XCONV_EUNSUPPORTED;
+    if (d->r > 1024 || d->C_in > 65536 || d->C_out > 65536 || (long long)d->kH * d->kW > 49) return XCONV_EUNSUPPORTED;
+    if ((long long)d->H * d->W > 0x7fffffffLL / 8 || (long long)(d->H + 2 * d->pad_h) * (d->W + 2 * d->pad_w) > 0x7fffffffLL / 8)
+        return XCONV_EUNSUPPORTED;
+    if (d->pad_h > 4096 || d->pad_w > 4096 || d->stride_h > 4096 || d->stride_w > 4096) return XCONV_EUNSUPPORTED;
+    return XCONV_OK;
+}
+
+size_t xconv_xt_bytes(const xconv_desc *d)
+{
+    if (xconv_check_desc(d) != XCONV_OK) return 0;
+    return (size_t)d->B * d->H * d->W * round_up(d->r, 16) * elem_bytes(d->dtype);
+}
+
+size_t xconv_workspace_bytes(const xconv_desc *d, int op)
+{
+    if (xconv_check_desc(d) != XCONV_OK) return 0;
+    if (op == XCONV_OP_PROBE) return z_bytes(d);
+    CorrParams P;
+    if (op == XCONV_OP_ESTIMATE) {
+        if (!get_plan(P, d->dtype, d->B, d->C_out, d->H, d->W, d->kH, d->kW, d->stride_h, d->stride_w, d->pad_h, d->pad_w,
+                      round_up(d->r, 16), true))
+            return 0;
+        return z_bytes(d) + align_up(corr_partial_bytes(P), 256);
+    }
+    if (op == XCONV_OP_EXACT) {
+        const int CSx = round_up(d->C_in, 16);
+        if (!get_plan(P, d->dtype, d->B, d->C_out, d->H, d->W, d->kH, d->kW, d->stride_h, d->stride_w, d->pad_h, d->pad_w, CSx, true))
+            return 0;
+        return align_up((size_t)d->B * d->H * d->W * CSx * elem_bytes(d->dtype), 256) + align_up(corr_partial_bytes(P), 256);
+    }
+    return 0;
+}
+
+xconv_status xconv_probe_matrix(const xconv_desc *d, float *Z_host)
+{
+    xconv_status s = xconv_check_desc(d);
+    if (s != XCONV_OK) return s;
+    if (!Z_host || d->probe == XCONV_USER_Z) return XCONV_EINVAL;
+    host_probe_matrix(d->probe, d->seed, d->C_in * d->r, Z_host);
+    return XCONV_OK;
+}
+
+xconv_status xconv_probe_matrix_dev(const xconv_desc *d, float *Z_dev, void *stream)
+{
+    xconv_status s = xconv_check_desc(d);
+    if (s != XCONV_OK) return s;
+    if (!Z_dev || d->probe == XCONV_USER_Z) return XCONV_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    XC_LAUNCH(K_GEN_Z, st, launch_gen_z(Z_dev, d->C_in * d->r, d->probe, d->seed, st));
+    return XCONV_OK;
+}
+
+xconv_status xconv_probe_fwd(const xconv_desc *d, const void *X_dev, void *Xt_dev, const float *Z_dev, void *ws_dev,
+                             size_t ws_bytes, void *stream)
+{
+    xconv_status s = xconv_check_desc(d);
+    if (s != XCONV_OK) return s;
+    if (!X_dev || !Xt_dev) return XCONV_EINVAL;
+    if (!aligned16(Xt_dev) || (reinterpret_cast<uintptr_t>(X_dev) & (elem_bytes(d->dtype) - 1)) != 0) return XCONV_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int CS = round_up(d->r, 16), HW = d->H * d->W;
+    const float *Z = Z_dev;
+    if (!Z) {
+        if (d->probe == XCONV_USER_Z) return XCONV_EINVAL;
+        if (!ws_dev || !aligned16(ws_dev)) return XCONV_EINVAL;
+        if (ws_bytes < z_bytes(d)) return XCONV_EWORKSPACE;
+        float *zw = static_cast<float *>(ws_dev);
+        XC_LAUNCH(K_GEN_Z, st, launch_gen_z(zw, d->C_in * d->r, d->probe, d->seed, st));
+        Z = zw;
+    }
+    const bool z_exact16 = d->probe == XCONV_RADEMACHER;
+    if (probe_fast_path_ok(d->dtype, d->C_in, HW) && aligned16(X_dev)) {
+        XC_LAUNCH(K_PROBE, st, launch_probe(d->dtype, X_dev, Z, Xt_dev, d->B, d->C_in, HW, d->r, CS, z_exact16, st));
+    } else {
+        XC_LAUNCH(K_PROBE_GENERIC, st, launch_probe_generic(d->dtype, X_dev, Z, Xt_dev, d->B, d->C_in, HW, d->r, CS, st));
+    }
+    return XCONV_OK;
+}
+
+xconv_status xconv_dw_estimate(const xconv_desc *d, const void *dY_dev, const void *Xt_dev, const float *Z_dev, float *dW_dev,
+                               void *ws_dev, size_t ws_bytes, void *stream)
+{
+    xconv_status s = xconv_check_desc(d);
+    if (s != XCONV_OK) return s;
+    if (!dY_dev || !Xt_dev || !dW_dev || !ws_dev) return XCONV_EINVAL;
+    if (!aligned16(Xt_dev) || !aligned16(ws_dev) || (reinterpret_cast<uintptr_t>(dW_dev) & 3u) != 0) return XCONV_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(dY_dev) & (elem_bytes(d->dtype) - 1)) != 0) return XCONV_EINVAL;
+    if (!Z_dev && d->probe == XCONV_USER_Z) return XCONV_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int CS = round_up(d->r, 16);
+    CorrParams P;
+    if (!get_plan(P, d->dtype, d->B, d->C_out, d->H, d->W, d->kH, d->kW, d->stride_h, d->stride_w, d->pad_h, d->pad_w, CS,
+                  aligned16(dY_dev)))
+        return XCONV_EUNSUPPORTED;
+    const size_t zb = z_bytes(d);
+    if (ws_bytes < zb + align_up(corr_partial_bytes(P), 256)) return XCONV_EWORKSPACE;
+    const float *Z = Z_dev;
+    if (!Z) {
+        float *zw = static_cast<float *>(ws_dev);
+        XC_LAUNCH(K_GEN_Z, st, launch_gen_z(zw, d->C_in * d->r, d->probe, d->seed, st));
+        Z = zw;
+    }
+    P.dY = dY_dev;
+    P.A = Xt_dev;
+    P.part = reinterpret_cast<float *>(static_cast<char *>(ws_dev) + zb);
+    XC_LAUNCH(K_CORR, st, launch_corr(d->dtype, P, st));
+    XC_LAUNCH(K_REDUCE_EXPAND, st, launch_reduce_expand(P, Z, dW_dev, d->C_in, d->r, st));
+    return XCONV_OK;
+}
+
+xconv_status xconv_dw_exact(const xconv_desc *d, const void *dY_dev, const void *X_dev, float *dW_dev, void *ws_dev,
+                            size_t ws_bytes, void *stream)
+{
+    xconv_status s = xconv_check_desc(d);
+    if (s != XCONV_OK) return s;
+    if (!dY_dev || !X_dev || !dW_dev || !ws_dev) return XCONV_EINVAL;
+    if (!aligned16(ws_dev) || (reinterpret_cast<uintptr_t>(dW_dev) & 3u) != 0) return XCONV_EINVAL;
+    const size_t eb = elem_bytes(d->dtype);
+    if ((reinterpret_cast<uintptr_t>(dY_dev) & (eb - 1)) != 0 || (reinterpret_cast<uintptr_t>(X_dev) & (eb - 1)) != 0) return XCONV_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int CSx = round_up(d->C_in, 16), HW = d->H * d->W;
+    CorrParams P;
+    if (!get_plan(P, d->dtype, d->B, d->C_out, d->H, d->W, d->kH, d->kW, d->stride_h, d->stride_w, d->pad_h, d->pad_w, CSx,
+                  aligned16(dY_dev)))
+        return XCONV_EUNSUPPORTED;
+    const size_t xb = align_up((size_t)d->B * HW * CSx * eb, 256);
+    if (ws_bytes < xb + align_up(corr_partial_bytes(P), 256)) return XCONV_EWORKSPACE;
+    XC_LAUNCH(K_TO_NHWC, st, launch_to_nhwc(d->dtype, X_dev, ws_dev, d->B, d->C_in, HW, CSx, st));
+    P.dY = dY_dev;
+    P.A = ws_dev;
+    P.part = reinterpret_cast<float *>(static_cast<char *>(ws_dev) + xb);
+    XC_LAUNCH(K_CORR, st, launch_corr(d->dtype, P, st));
+    XC_LAUNCH(K_REDUCE_EXPAND, st, launch_reduce_expand(P, nullptr, dW_dev, d->C_in, d->r, st));
+    return XCONV_OK;
+}
+
+xconv_status xconv_plan_info(const xconv_desc *d, int op, int32_t *out)
+{
+    xconv_status s = xconv_check_desc(d);
+    if (s != XCONV_OK) return s;
+    if (!out || (op != XCONV_OP_ESTIMATE && op != XCONV_OP_EXACT)) return XCONV_EINVAL;
+    const int CS = round_up(op == XCONV_OP_ESTIMATE ? d->r : d->C_in, 16);
+    CorrParams P;
+    if (!get_plan(P, d->dtype, d->B, d->C_out, d->H, d->W, d->kH, d->kW, d->stride_h, d->stride_w, d->pad_h, d->pad_w, CS, true))
+        return XCONV_EUNSUPPORTED;
+    const int32_t v[16] = {P.S, P.NS, P.RB, P.CW, P.WM, P.WJ, P.WK, P.M_WG, P.J_WG, (int32_t)corr_lds_bytes(d->dtype, P),
+                           P.NTM, P.NTJ, P.NOG, P.CS, P.NCHR, 0};
+    for (int i = 0; i < 16; ++i) out[i] = v[i];
+    return XCONV_OK;
+}
+
+xconv_status xconv_xt_unpack(const xconv_desc *d, const void *Xt_dev, float *out_dev, void *stream)
+{
+    xconv_status s = xconv_check_desc(d);
+    if (s != XCONV_OK) return s;
+    if (!Xt_dev || !out_dev) return XCONV_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    XC_LAUNCH(K_UNPACK, st, launch_unpack(d->dtype, Xt_dev, out_dev, d->B, d->H * d->W, d->r, round_up(d->r, 16), st));
+    return XCONV_OK;
+}
+
+void xconv_prof_enable(int on)
+{
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    g_prof_on = on != 0;
+}
+
+int xconv_prof_collect(int32_t *kernel_ids, float *ms, int max)
+{
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    int n = 0;
+    for (ProfRec &r : g_prof) {
+        float t = 0.f;
+        if (hipEventSynchronize(r.b) == hipSuccess && hipEventElapsedTime(&t, r.a, r.b) == hipSuccess && n < max) {
+            if (kernel_ids) kernel_ids[n] = r.id;
+            if (ms) ms[n] = t;
+            ++n;
+        }
+        (void)hipEventDestroy(r.a);
+        (void)hipEventDestroy(r.b);
+    }
+    g_prof.clear();
+    return n;
+}
+
+const char *xconv_prof_kernel_name(int id)
+{
+    switch (id) {
+    case K_GEN_Z: return "gen_z_kernel";
+    case K_PROBE: return "probe_kernel";
+    case K_PROBE_GENERIC: return "probe_generic_kernel";
+    case K_CORR: return "corr_kernel";
+    case K_REDUCE_EXPAND: return "reduce_expand_kernel";
+    case K_TO_NHWC: return "to_nhwc_kernel";
+    case K_UNPACK: return "unpack_kernel";
+    default: return "unknown";
+    }
+}
+
+const char *xconv_status_string(int status)
+{
+    switch (status) {
+    case XCONV_OK: return "ok";
+    case XCONV_EINVAL: return "invalid argument";
+    case XCONV_EUNSUPPORTED: return "unsupported configuration";
+    case XCONV_EWORKSPACE: return "workspace too small";
+    case XCONV_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,295 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU
+oracle on identical seeded inputs and the same Z.
+
+Tolerances (relative to the largest magnitude of the oracle's result):
+fp32 storage 1e-4, bf16/fp16 storage 2e-2 for the gradients.  The stored probe
+output is compared element by element: fp32 to 2e-6 of the largest value,
+16-bit storage to one unit in the last place of the storage type (the oracle
+rounds the exact sum once, the kernel rounds an fp32 sum once).
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import xconv_oracle as xo
+from paper_2106_06998_amd import binding as xb
+from paper_2106_06998_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+ODT = {"f32": xo.F32, "bf16": xo.BF16, "f16": xo.F16}
+OPROBE = {"rademacher": xo.RADEMACHER, "gaussian": xo.GAUSSIAN}
+GRAD_TOL = {"f32": 1e-4, "bf16": 2e-2, "f16": 2e-2}
+ULP = {"bf16": 2.0 ** -8, "f16": 2.0 ** -11}     # half a unit in the last place, relative
+
+
+def say(msg):
+    print("[gpu-case] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+def rel_max(got, want):
+    return float(np.max(np.abs(got - want)) / max(np.max(np.abs(want)), 1e-300))
+
+
+def run_probe(cfg, X, Z=None, seed_path=False):
+    """Returns (Xt buffer, unpacked Xt as numpy [B,r,H,W])."""
+    d = xb.desc_from_config(cfg)
+    Xd = xb.to_device(X, cfg.dtype, DEV)
+    Xt = xb.alloc_xt(d, DEV)
+    Xt.fill_(0x7f)                                  # poison: every byte must be overwritten
+    if seed_path:
+        ws = xb.alloc_ws(d, xb.XCONV_OP_PROBE, DEV)
+        xb.xconv_probe_fwd(d, Xd, Xt, None, ws)
+    else:
+        Zd = torch.from_numpy(np.ascontiguousarray(Z, dtype=np.float32)).to(DEV)
+        xb.xconv_probe_fwd(d, Xd, Xt, Zd, None)
+    out = torch.empty((cfg.B, cfg.r, cfg.H, cfg.W), dtype=torch.float32, device=DEV)
+    xb.xconv_xt_unpack(d, Xt, out)
+    torch.cuda.synchronize()
+    return d, Xt, out.cpu().numpy()
+
+
+def run_estimate(cfg, d, dY, Xt, Z=None):
+    dYd = xb.to_device(dY, cfg.dtype, DEV)
+    ws = xb.alloc_ws(d, xb.XCONV_OP_ESTIMATE, DEV)
+    dW = torch.full((cfg.C_out, cfg.C_in, cfg.k, cfg.k), float("nan"), dtype=torch.float32, device=DEV)
+    Zd = None if Z is None else torch.from_numpy(np.ascontiguousarray(Z, dtype=np.float32)).to(DEV)
+    xb.xconv_dw_estimate(d, dYd, Xt, Zd, dW, ws)
+    torch.cuda.synchronize()
+    return dW.cpu().numpy().astype(np.float64)
+
+
+def run_exact(cfg, d, dY, X):
+    dYd = xb.to_device(dY, cfg.dtype, DEV)
+    Xd = xb.to_device(X, cfg.dtype, DEV)
+    ws = xb.alloc_ws(d, xb.XCONV_OP_EXACT, DEV)
+    dW = torch.full((cfg.C_out, cfg.C_in, cfg.k, cfg.k), float("nan"), dtype=torch.float32, device=DEV)
+    xb.xconv_dw_exact(d, dYd, Xd, dW, ws)
+    torch.cuda.synchronize()
+    return dW.cpu().numpy().astype(np.float64)
+
+
+def check_probe_output(cfg, got, want):
+    assert got.shape == want.shape
+    scale = np.max(np.abs(want))
+    if cfg.dtype == "f32":
+        assert np.max(np.abs(got - want)) <= 2e-6 * scale, rel_max(got, want)
+    else:
+        # one rounding each of sums that differ by fp32 accumulation error: allow a unit in the last place
+        tol = 2.0 * ULP[cfg.dtype] * np.maximum(np.abs(want), 2.0 ** -14) + 1e-6 * scale
+        bad = np.abs(got - want) > tol
+        assert not bad.any(), (int(bad.sum()), rel_max(got, want))
+        assert np.mean(got == want) > 0.97
+
+
+def full_parity(cfg, seed_path=False, check_exact=True):
+    say("%s %s B%d C%d->%d %dx%d k%d s%d p%d r%d %s seed_path=%s" % (
+        cfg.name, cfg.dtype, cfg.B, cfg.C_in, cfg.C_out, cfg.H, cfg.W, cfg.k, cfg.stride, cfg.pad, cfg.r, cfg.probe, seed_path))
+    X, dY = synth.make_layer(cfg)
+    Z = xo.probe_matrix(OPROBE[cfg.probe], cfg.seeds[2], cfg.C_in, cfg.r)
+    st, pd = (cfg.stride, cfg.stride), (cfg.pad, cfg.pad)
+    Xt_o = xo.probe_fwd(X, Z, ODT[cfg.dtype])
+    d, Xt, Xt_g = run_probe(cfg, X, Z, seed_path)
+    check_probe_output(cfg, Xt_g, Xt_o)
+    want = xo.dw_from_xt(dY, Xt_o, Z, cfg.k, cfg.k, st, pd)
+    got = run_estimate(cfg, d, dY, Xt, None if seed_path else Z)
+    assert np.all(np.isfinite(got))
+    err = rel_max(got, want)
+    assert err <= GRAD_TOL[cfg.dtype], err
+    if check_exact:
+        want_x = xo.dw_exact(dY, X, cfg.k, cfg.k, st, pd)
+        got_x = run_exact(cfg, d, dY, X)
+        errx = rel_max(got_x, want_x)
+        assert errx <= GRAD_TOL[cfg.dtype], errx
+    return err
+
+
+# ---------------------------------------------------------------------------
+# generator on the device
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("probe", ["rademacher", "gaussian"])
+def test_device_probe_matrix_matches_host_and_oracle(probe):
+    for seed, C_in, r in ((3001, 16, 8), (3005, 256, 64), (77, 33, 5)):
+        say("probe_matrix_dev %s seed=%d %dx%d" % (probe, seed, C_in, r))
+        d = xb.make_desc(1, C_in, 1, 8, 8, 3, 1, 1, r, "f32", probe, seed)
+        Zd = torch.empty((C_in, r), dtype=torch.float32, device=DEV)
+        xb.xconv_probe_matrix_dev(d, Zd)
+        torch.cuda.synchronize()
+        Zg = Zd.cpu().numpy()
+        Zh = xb.xconv_probe_matrix(d)
+        Zo = xo.probe_matrix(OPROBE[probe], seed, C_in, r)
+        if probe == "rademacher":
+            assert np.array_equal(Zg, Zo) and np.array_equal(Zh, Zo)
+        else:
+            assert np.max(np.abs(Zg - Zo)) <= 2.4e-7 * np.max(np.abs(Zo))
+            assert np.mean(Zg == Zo) > 0.98
+
+
+# ---------------------------------------------------------------------------
+# reduced copies of the five benchmark layers: several tiles and ragged tails
+# ---------------------------------------------------------------------------
+SMALL = [
+    synth.CONFIGS["C1"],
+    synth.small_variant(synth.CONFIGS["C2"], B=5, H=20, W=24, name="C2-small"),
+    synth.small_variant(synth.CONFIGS["C3"], B=11, H=22, W=26, C_in=72, C_out=136, name="C3-small"),
+    synth.small_variant(synth.CONFIGS["C4"], B=2, H=40, W=300, name="C4-small"),
+    synth.small_variant(synth.CONFIGS["C5"], B=18, H=12, W=12, C_in=96, C_out=80, name="C5-small"),
+]
+
+
+@pytest.mark.parametrize("cfg", SMALL, ids=[c.name for c in SMALL])
+def test_small_layers_explicit_z(cfg):
+    full_parity(cfg, seed_path=False)
+
+
+@pytest.mark.parametrize("cfg", [SMALL[1], SMALL[4]], ids=["C2-small", "C5-small"])
+def test_small_layers_seed_path(cfg):
+    # Z regenerated on the device from the seed in forward and backward (Algorithm 1)
+    full_parity(cfg, seed_path=True, check_exact=False)
+
+
+EDGE = [
+    # name, B, C_in, C_out, H, W, k, stride, pad, r, probe, dtype
+    ("odd-plane-f32", 3, 5, 7, 9, 11, 3, 1, 1, 3, "gaussian", "f32"),          # planes not a multiple of the vector width
+    ("odd-plane-f16", 9, 5, 7, 9, 11, 3, 1, 1, 3, "rademacher", "f16"),
+    ("odd-plane-bf16", 3, 20, 18, 7, 9, 3, 2, 1, 20, "rademacher", "bf16"),
+    ("k1-f32", 4, 24, 40, 12, 12, 1, 1, 0, 8, "gaussian", "f32"),
+    ("k1-s2-f16", 8, 32, 32, 12, 12, 1, 2, 0, 16, "rademacher", "f16"),
+    ("k5-f32", 2, 8, 20, 16, 16, 5, 1, 2, 4, "rademacher", "f32"),             # 25 offsets: three offset groups
+    ("k5-bf16", 8, 16, 16, 12, 12, 5, 1, 2, 16, "rademacher", "bf16"),
+    ("nopad-f32", 2, 16, 16, 14, 18, 3, 1, 0, 8, "gaussian", "f32"),
+    ("rect-k-f16", 8, 16, 24, 13, 16, (3, 2), (2, 1), (1, 0), 8, "rademacher", "f16"),
+    ("gauss-f16", 8, 64, 32, 8, 8, 3, 1, 1, 24, "gaussian", "f16"),            # Z not representable in 16 bits: hi+lo probe
+    ("gauss-bf16", 16, 40, 32, 8, 8, 3, 1, 1, 48, "gaussian", "bf16"),
+    ("r-wide-f32", 2, 96, 16, 8, 8, 3, 1, 1, 80, "rademacher", "f32"),         # r > 64: two probe column blocks
+    ("r-wide-f16", 8, 96, 16, 8, 8, 3, 1, 1, 80, "rademacher", "f16"),
+    ("b1-f16", 1, 16, 16, 8, 8, 3, 1, 1, 4, "rademacher", "f16"),              # a single image in a group of 8
+    ("one-pixel-out", 2, 4, 4, 3, 3, 3, 1, 0, 2, "gaussian", "f32"),
+    ("wide-f32", 1, 8, 8, 6, 700, 3, 1, 1, 4, "rademacher", "f32"),            # several column strips
+    ("wide-f16", 8, 16, 16, 4, 260, 3, 1, 1, 16, "rademacher", "f16"),
+    ("big-cout-f32", 1, 8, 300, 8, 8, 3, 1, 1, 8, "rademacher", "f32"),
+]
+
+
+def _edge_cfg(e):
+    name, B, C_in, C_out, H, W, k, stride, pad, r, probe, dtype = e
+    return name, B, C_in, C_out, H, W, k, stride, pad, r, probe, dtype
+
+
+@pytest.mark.parametrize("e", EDGE, ids=[e[0] for e in EDGE])
+def test_edge_shapes(e):
+    name, B, C_in, C_out, H, W, k, stride, pad, r, probe, dtype = e
+    kH, kW = (k, k) if isinstance(k, int) else k
+    sh, sw = (stride, stride) if isinstance(stride, int) else stride
+    ph, pw = (pad, pad) if isinstance(pad, int) else pad
+    say("edge %s" % name)
+    Ho, Wo = xo.out_extent(H, kH, sh, ph), xo.out_extent(W, kW, sw, pw)
+    X = synth.draw((B, C_in, H, W), 11, "relu_normal", 1.0, dtype)
+    dY = synth.draw((B, C_out, Ho, Wo), 12, "normal", 1e-2, dtype)
+    Z = xo.probe_matrix(OPROBE[probe], 13, C_in, r)
+    d = xb.make_desc(B, C_in, C_out, H, W, (kH, kW), (sh, sw), (ph, pw), r, dtype, probe, 13)
+    Xd, dYd = xb.to_device(X, dtype, DEV), xb.to_device(dY, dtype, DEV)
+    Zd = torch.from_numpy(Z).to(DEV)
+    Xt = xb.alloc_xt(d, DEV)
+    Xt.fill_(0x7f)
+    xb.xconv_probe_fwd(d, Xd, Xt, Zd, None)
+    unp = torch.empty((B, r, H, W), dtype=torch.float32, device=DEV)
+    xb.xconv_xt_unpack(d, Xt, unp)
+    dW = torch.full((C_out, C_in, kH, kW), float("nan"), dtype=torch.float32, device=DEV)
+    xb.xconv_dw_estimate(d, dYd, Xt, Zd, dW, xb.alloc_ws(d, xb.XCONV_OP_ESTIMATE, DEV))
+    dWx = torch.full((C_out, C_in, kH, kW), float("nan"), dtype=torch.float32, device=DEV)
+    xb.xconv_dw_exact(d, dYd, Xd, dWx, xb.alloc_ws(d, xb.XCONV_OP_EXACT, DEV))
+    torch.cuda.synchronize()
+
+    class C:  # minimal stand-in for check_probe_output
+        pass
+    C.dtype = dtype
+    Xt_o = xo.probe_fwd(X, Z, ODT[dtype])
+    check_probe_output(C, unp.cpu().numpy(), Xt_o)
+    want = xo.dw_from_xt(dY, Xt_o, Z, kH, kW, (sh, sw), (ph, pw))
+    assert rel_max(dW.cpu().numpy().astype(np.float64), want) <= GRAD_TOL[dtype]
+    want_x = xo.dw_exact(dY, X, kH, kW, (sh, sw), (ph, pw))
+    assert rel_max(dWx.cpu().numpy().astype(np.float64), want_x) <= GRAD_TOL[dtype]
+
+
+def test_full_rank_hadamard_probe_gives_exact_gradient_on_gpu():
+    # r = C_in and Z Z^T = r I: the estimate equals the exact gradient
+    say("hadamard invariant")
+    B, C, H, W = 4, 16, 12, 12
+    Hm = np.array([[1.0]])
+    while Hm.shape[0] < C:
+        Hm = np.block([[Hm, Hm], [Hm, -Hm]])
+    Z = Hm.astype(np.float32)
+    X = synth.draw((B, C, H, W), 21, "normal", 1.0, "f32")
+    dY = synth.draw((B, 24, H, W), 22, "normal", 1.0, "f32")
+    d = xb.make_desc(B, C, 24, H, W, 3, 1, 1, C, "f32", "user", 0)
+    Xd, dYd, Zd = xb.to_device(X, "f32", DEV), xb.to_device(dY, "f32", DEV), torch.from_numpy(Z).to(DEV)
+    Xt = xb.alloc_xt(d, DEV)
+    xb.xconv_probe_fwd(d, Xd, Xt, Zd, None)
+    dW = torch.empty((24, C, 3, 3), dtype=torch.float32, device=DEV)
+    xb.xconv_dw_estimate(d, dYd, Xt, Zd, dW, xb.alloc_ws(d, xb.XCONV_OP_ESTIMATE, DEV))
+    torch.cuda.synchronize()
+    exact = xo.dw_exact(dY, X, 3, 3, (1, 1), (1, 1))
+    assert rel_max(dW.cpu().numpy().astype(np.float64), exact) <= 1e-5
+
+
+def test_estimate_is_deterministic_and_overwrites():
+    say("determinism")
+    cfg = SMALL[1]
+    X, dY = synth.make_layer(cfg)
+    Z = xo.probe_matrix(OPROBE[cfg.probe], cfg.seeds[2], cfg.C_in, cfg.r)
+    d, Xt, _ = run_probe(cfg, X, Z)
+    a = run_estimate(cfg, d, dY, Xt, Z)
+    b = run_estimate(cfg, d, dY, Xt, Z)
+    assert np.array_equal(a, b)
+
+
+# ---------------------------------------------------------------------------
+# the five layers at full size, in the launch configuration the bench times
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("name", ["C1", "C2"])
+def test_full_size_complete(name):
+    full_parity(synth.CONFIGS[name], seed_path=True, check_exact=(name == "C1"))
+
+
+@pytest.mark.parametrize("name", ["C3", "C4", "C5"])
+def test_full_size_sampled(name):
+    # The oracle computes the probe output in full and the gradient at sampled
+    # entries (each one a sum over all B*H'*W' pixels and all r probes).
+    cfg = synth.CONFIGS[name]
+    say("%s full size, sampled entries" % name)
+    X, dY = synth.make_layer(cfg)
+    Z = xo.probe_matrix(OPROBE[cfg.probe], cfg.seeds[2], cfg.C_in, cfg.r)
+    st, pd = (cfg.stride, cfg.stride), (cfg.pad, cfg.pad)
+    d, Xt, Xt_g = run_probe(cfg, X, None, seed_path=True)
+    got = run_estimate(cfg, d, dY, Xt, None)
+    got_x = run_exact(cfg, d, dY, X) if name == "C5" else None
+    assert np.all(np.isfinite(got))
+    say("%s oracle probe" % name)
+    Xt_o = xo.probe_fwd(X, Z, ODT[cfg.dtype])
+    check_probe_output(cfg, Xt_g, Xt_o)
+    rng = np.random.default_rng(5)
+    n = 48
+    idx = np.stack([rng.integers(0, cfg.C_out, n), rng.integers(0, cfg.C_in, n),
+                    rng.integers(0, cfg.k, n), rng.integers(0, cfg.k, n)], axis=1).astype(np.int32)
+    idx[0] = (0, 0, 0, 0)
+    idx[1] = (cfg.C_out - 1, cfg.C_in - 1, cfg.k - 1, cfg.k - 1)
+    say("%s oracle samples" % name)
+    want = xo.dw_from_xt_at(dY, Xt_o, Z, idx, cfg.k, cfg.k, st, pd)
+    g = np.array([got[tuple(i)] for i in idx])
+    scale = np.max(np.abs(got))          # the largest entry of the full result bounds the oracle's largest sampled one
+    assert np.max(np.abs(want)) <= 1.05 * scale
+    assert np.max(np.abs(g - want)) <= GRAD_TOL[cfg.dtype] * np.max(np.abs(want)), (np.max(np.abs(g - want)), np.max(np.abs(want)))
+    if got_x is not None:
+        wx = xo.dw_exact_at(dY, X, idx, cfg.k, cfg.k, st, pd)
+        gx = np.array([got_x[tuple(i)] for i in idx])
+        assert np.max(np.abs(gx - wx)) <= GRAD_TOL[cfg.dtype] * np.max(np.abs(wx))
+    # property that holds at any size: the estimate is the exact gradient mixed by Z Z^T / r
+    if got_x is not None:
+        G = Z.astype(np.float64) @ Z.astype(np.float64).T / cfg.r
+        mixed = np.einsum("nq,mqyx->mnyx", G, got_x)
+        assert rel_max(got, mixed) <= 2 * GRAD_TOL[cfg.dtype]

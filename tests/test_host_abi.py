@@ -1,0 +1,137 @@
+"""Host-side checks of the C-ABI library: it loads, exports every entry point
+the header declares, validates descriptors and reports sizes without touching
+a GPU, and its host probe generator agrees with the oracle's.  CPU only."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import xconv_oracle as xo
+from paper_2106_06998_amd import binding as xb
+from paper_2106_06998_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "xconv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(xconv_[a-z0-9_]+)\s*\(", text))
+    assert {"xconv_probe_fwd", "xconv_dw_estimate", "xconv_dw_exact"} <= names
+    L = xb.lib()
+    for n in sorted(names):
+        assert hasattr(L, n), n
+
+
+def test_desc_struct_layout_matches_header():
+    assert ctypes.sizeof(xb.xconv_desc) == 16 * 4 + 8
+    assert xb.xconv_desc.seed.offset == 64
+
+
+def _good():
+    return xb.make_desc(4, 16, 16, 32, 32, 3, 1, 1, 8, "f32", "rademacher", 3001)
+
+
+def test_check_desc_statuses():
+    assert xb.xconv_check_desc(_good()) == xb.XCONV_OK
+    assert xb.lib().xconv_check_desc(None) == xb.XCONV_EINVAL
+    for field, val in (("B", 0), ("C_in", -1), ("C_out", 0), ("H", 0), ("W", 0), ("kH", 0), ("kW", 0),
+                       ("stride_h", 0), ("stride_w", 0), ("pad_h", -1), ("pad_w", -1), ("r", 0),
+                       ("dtype", 3), ("dtype", -1), ("layout", 2), ("probe", 3), ("reserved", 1)):
+        d = _good()
+        setattr(d, field, val)
+        assert xb.xconv_check_desc(d) == xb.XCONV_EINVAL, field
+    d = _good()
+    d.kH = d.kW = 40            # kernel larger than the padded image: empty output
+    assert xb.xconv_check_desc(d) == xb.XCONV_EINVAL
+    for field, val in (("layout", xb.XCONV_NHWC), ("r", 1025), ("C_in", 70000), ("C_out", 70000)):
+        d = _good()
+        setattr(d, field, val)
+        assert xb.xconv_check_desc(d) == xb.XCONV_EUNSUPPORTED, field
+    d = xb.make_desc(1, 1, 1, 64, 64, 8, 1, 0, 1)     # 64 kernel offsets
+    assert xb.xconv_check_desc(d) == xb.XCONV_EUNSUPPORTED
+    assert "unsupported" in xb.xconv_status_string(xb.XCONV_EUNSUPPORTED)
+    assert xb.xconv_status_string(0) == "ok"
+
+
+def test_sizes():
+    d = _good()
+    assert xb.xconv_xt_bytes(d) == 4 * 32 * 32 * 16 * 4          # r = 8 is stored padded to 16 columns
+    d16 = xb.make_desc(256, 256, 256, 28, 28, 3, 1, 1, 64, "f16")
+    assert xb.xconv_xt_bytes(d16) == 256 * 28 * 28 * 64 * 2
+    assert xb.xconv_workspace_bytes(d, xb.XCONV_OP_PROBE) >= 16 * 8 * 4
+    west = xb.xconv_workspace_bytes(d, xb.XCONV_OP_ESTIMATE)
+    wex = xb.xconv_workspace_bytes(d, xb.XCONV_OP_EXACT)
+    assert west > 16 * 8 * 4 and wex > 4 * 32 * 32 * 16 * 4
+    bad = _good()
+    bad.r = 0
+    assert xb.xconv_xt_bytes(bad) == 0 and xb.xconv_workspace_bytes(bad, 1) == 0
+    assert xb.xconv_workspace_bytes(d, 7) == 0
+    # every benchmark layer gets a plan and a modest scratch size
+    for cfg in synth.CONFIGS.values():
+        dd = xb.desc_from_config(cfg)
+        assert xb.xconv_check_desc(dd) == xb.XCONV_OK
+        w = xb.xconv_workspace_bytes(dd, xb.XCONV_OP_ESTIMATE)
+        assert 0 < w < 256 * 2 ** 20, (cfg.name, w)
+        assert xb.xconv_workspace_bytes(dd, xb.XCONV_OP_EXACT) > 0
+
+
+@pytest.mark.parametrize("probe,code", [("rademacher", xo.RADEMACHER), ("gaussian", xo.GAUSSIAN)])
+def test_host_probe_matrix_matches_oracle_generator(probe, code):
+    for seed, C_in, r in ((3001, 16, 8), (3005, 256, 64), (2 ** 63 + 5, 7, 3)):
+        d = xb.make_desc(1, C_in, 1, 8, 8, 3, 1, 1, r, "f32", probe, seed)
+        Z = xb.xconv_probe_matrix(d)
+        Zo = xo.probe_matrix(code, seed, C_in, r)
+        if probe == "rademacher":
+            assert np.array_equal(Z, Zo)
+        else:
+            # same stream words, same double-precision Box-Muller: at most an ulp apart
+            assert np.max(np.abs(Z - Zo)) <= 2.4e-7 * np.max(np.abs(Zo))
+            assert np.mean(Z == Zo) > 0.99
+    d = xb.make_desc(1, 4, 1, 8, 8, 3, 1, 1, 2, "f32", "user", 1)
+    with pytest.raises(xb.XConvError) as e:
+        xb.xconv_probe_matrix(d)
+    assert e.value.status == xb.XCONV_EINVAL
+
+
+def test_entry_points_reject_bad_arguments_before_any_launch():
+    L = xb.lib()
+    d = _good()
+    p = ctypes.byref(d)
+    one = ctypes.c_void_p(4096)          # never dereferenced: validation fails first
+    assert L.xconv_probe_fwd(p, None, one, one, None, 0, None) == xb.XCONV_EINVAL
+    assert L.xconv_probe_fwd(p, one, None, one, None, 0, None) == xb.XCONV_EINVAL
+    assert L.xconv_probe_fwd(p, one, ctypes.c_void_p(4100), one, None, 0, None) == xb.XCONV_EINVAL   # Xt misaligned
+    assert L.xconv_probe_fwd(p, one, one, None, None, 0, None) == xb.XCONV_EINVAL                    # no Z, no scratch
+    assert L.xconv_probe_fwd(p, one, one, None, one, 16, None) == xb.XCONV_EWORKSPACE
+    assert L.xconv_dw_estimate(p, None, one, one, one, one, 1 << 30, None) == xb.XCONV_EINVAL
+    assert L.xconv_dw_estimate(p, one, one, one, None, one, 1 << 30, None) == xb.XCONV_EINVAL
+    assert L.xconv_dw_estimate(p, one, one, one, one, None, 1 << 30, None) == xb.XCONV_EINVAL
+    assert L.xconv_dw_estimate(p, one, one, one, one, one, 64, None) == xb.XCONV_EWORKSPACE
+    assert L.xconv_dw_exact(p, one, None, one, one, 1 << 30, None) == xb.XCONV_EINVAL
+    assert L.xconv_dw_exact(p, one, one, one, one, 64, None) == xb.XCONV_EWORKSPACE
+    assert L.xconv_xt_unpack(p, None, one, None) == xb.XCONV_EINVAL
+    du = _good()
+    du.probe = xb.XCONV_USER_Z
+    assert L.xconv_dw_estimate(ctypes.byref(du), one, one, None, one, one, 1 << 30, None) == xb.XCONV_EINVAL
+    dn = _good()
+    dn.layout = xb.XCONV_NHWC
+    assert L.xconv_probe_fwd(ctypes.byref(dn), one, one, one, None, 0, None) == xb.XCONV_EUNSUPPORTED
+
+
+def test_synthetic_inputs_are_storage_representable_and_seeded():
+    cfg = synth.small_variant(synth.CONFIGS["C3"], B=2, H=12, W=12, C_in=8, C_out=8)
+    X, dY = synth.make_layer(cfg)
+    X2, dY2 = synth.make_layer(cfg)
+    assert np.array_equal(X, X2) and np.array_equal(dY, dY2)
+    assert np.array_equal(synth.round_to_storage(X, "bf16"), X)
+    assert X.min() == 0.0 and 0.3 < np.mean(X == 0.0) < 0.7           # post-ReLU: about half zeros
+    assert abs(dY.std() - 0.1) < 0.02
+    assert dY.shape == (2, 8, 6, 6)
+    bits = synth.storage_bits(X, "bf16")
+    assert bits.dtype == np.uint16
+    assert np.array_equal((bits.astype(np.uint32) << 16).view(np.float32), X)
+    h = synth.draw((64,), 5, "normal", 1.0, "f16")
+    assert np.array_equal(h.astype(np.float16).astype(np.float32), h)
