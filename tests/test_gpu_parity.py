@@ -73,16 +73,20 @@ def run_exact(cfg, d, dY, X):
     return dW.cpu().numpy().astype(np.float64)
 
 
-def check_probe_output(cfg, got, want):
+def check_probe_output(cfg, got, want, z_exact=True):
     assert got.shape == want.shape
     scale = np.max(np.abs(want))
     if cfg.dtype == "f32":
         assert np.max(np.abs(got - want)) <= 2e-6 * scale, rel_max(got, want)
     else:
-        # one rounding each of sums that differ by fp32 accumulation error: allow a unit in the last place
-        tol = 2.0 * ULP[cfg.dtype] * np.maximum(np.abs(want), 2.0 ** -14) + 1e-6 * scale
+        # One rounding each of sums that differ by the fp32 accumulation error: allow a unit in the
+        # last place.  A Z that is not representable in the storage type enters the 16-bit MFMA as
+        # hi + lo, which for bf16 leaves 2^-16 of each product; sums that cancel to almost nothing
+        # can then be off by more than their own last place, hence the larger absolute floor.
+        floor = 1e-6 if (z_exact or cfg.dtype == "f16") else 1e-4
+        tol = 2.0 * ULP[cfg.dtype] * np.maximum(np.abs(want), 2.0 ** -14) + floor * scale
         bad = np.abs(got - want) > tol
-        assert not bad.any(), (int(bad.sum()), rel_max(got, want))
+        assert not bad.any(), (int(bad.sum()), float(np.max((np.abs(got - want) - tol)[bad])), rel_max(got, want))
         assert np.mean(got == want) > 0.97
 
 
@@ -94,7 +98,7 @@ def full_parity(cfg, seed_path=False, check_exact=True):
     st, pd = (cfg.stride, cfg.stride), (cfg.pad, cfg.pad)
     Xt_o = xo.probe_fwd(X, Z, ODT[cfg.dtype])
     d, Xt, Xt_g = run_probe(cfg, X, Z, seed_path)
-    check_probe_output(cfg, Xt_g, Xt_o)
+    check_probe_output(cfg, Xt_g, Xt_o, z_exact=(cfg.probe == "rademacher"))
     want = xo.dw_from_xt(dY, Xt_o, Z, cfg.k, cfg.k, st, pd)
     got = run_estimate(cfg, d, dY, Xt, None if seed_path else Z)
     assert np.all(np.isfinite(got))
@@ -209,7 +213,7 @@ def test_edge_shapes(e):
         pass
     C.dtype = dtype
     Xt_o = xo.probe_fwd(X, Z, ODT[dtype])
-    check_probe_output(C, unp.cpu().numpy(), Xt_o)
+    check_probe_output(C, unp.cpu().numpy(), Xt_o, z_exact=(probe == "rademacher"))
     want = xo.dw_from_xt(dY, Xt_o, Z, kH, kW, (sh, sw), (ph, pw))
     assert rel_max(dW.cpu().numpy().astype(np.float64), want) <= GRAD_TOL[dtype]
     want_x = xo.dw_exact(dY, X, kH, kW, (sh, sw), (ph, pw))
