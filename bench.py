@@ -1,0 +1,247 @@
+#!/usr/bin/env python3
+"""Benchmark of the XConv weight-gradient hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic layer: xconv_probe_fwd
+(Z regenerated from the step's seed, Xt written) followed by xconv_dw_estimate
+(Z regenerated again, correlation, reduction + Z/r expansion), i.e. Algorithm 1
+forward step 2-3 and backward steps 1-4.  Inputs are resident in HBM before the
+timed region; several buffer sets are rotated so that the working set does not
+sit in the 256 MB Infinity Cache.
+
+Prints one JSON line (see README/DESIGN for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+PEAK_MFMA_TFLOPS = {"f32": 157.3, "bf16": 2500.0, "f16": 2500.0}
+
+# HBM traffic per launch of the dominant kernel from rocprofv3 --pmc runs
+# (FETCH_SIZE, WRITE_SIZE scaled by a copy kernel of known size; see
+# profiles/).  bytes, or None where not measured yet.
+MEASURED_TRAFFIC = {}
+
+
+def elem_bytes(dtype):
+    return 4 if dtype == "f32" else 2
+
+
+def algorithmic(cfg):
+    """Algorithmic bytes and flops per launch of each kernel of the path."""
+    s = elem_bytes(cfg.dtype)
+    P = cfg.B * cfg.Ho * cfg.Wo
+    k2 = cfg.k * cfg.k
+    probe_bytes = (cfg.C_in + cfg.r) * cfg.B * cfg.H * cfg.W * s
+    probe_flops = 2.0 * cfg.B * cfg.H * cfg.W * cfg.C_in * cfg.r
+    corr_bytes = P * cfg.C_out * s + cfg.B * cfg.H * cfg.W * cfg.r * s + cfg.C_out * cfg.r * k2 * 4
+    corr_flops = 2.0 * P * cfg.C_out * cfg.r * k2
+    exact_bytes = P * cfg.C_out * s + cfg.B * cfg.H * cfg.W * cfg.C_in * s + cfg.C_out * cfg.C_in * k2 * 4
+    exact_flops = 2.0 * P * cfg.C_out * cfg.C_in * k2
+    return dict(probe_bytes=probe_bytes, probe_flops=probe_flops, corr_bytes=corr_bytes, corr_flops=corr_flops,
+                exact_bytes=exact_bytes, exact_flops=exact_flops,
+                act_bytes_saved=(cfg.C_in - cfg.r) * cfg.B * cfg.H * cfg.W * s)
+
+
+class Layer:
+    """Device buffers of one layer, `nsets` rotating copies."""
+
+    def __init__(self, cfg, nsets, dev):
+        import torch
+        from paper_2106_06998_amd import binding as xb
+        from paper_2106_06998_amd import synth
+        self.cfg, self.xb = cfg, xb
+        self.desc = xb.desc_from_config(cfg)
+        X, dY = synth.make_layer(cfg)
+        self.host = (X, dY)
+        self.sets = []
+        for i in range(nsets):
+            Xd = xb.to_device(X, cfg.dtype, dev)
+            dYd = xb.to_device(dY, cfg.dtype, dev)
+            self.sets.append(dict(
+                X=Xd, dY=dYd, Xt=xb.alloc_xt(self.desc, dev),
+                dW=torch.empty((cfg.C_out, cfg.C_in, cfg.k, cfg.k), dtype=torch.float32, device=dev),
+                ws=xb.alloc_ws(self.desc, xb.XCONV_OP_ESTIMATE, dev),
+                wsx=None))
+        self.dev = dev
+
+    def step(self, i):
+        s = self.sets[i % len(self.sets)]
+        self.desc.seed = self.cfg.seeds[2] + i          # a fresh seed per iteration (Algorithm 1)
+        self.xb.xconv_probe_fwd(self.desc, s["X"], s["Xt"], None, s["ws"])
+        self.xb.xconv_dw_estimate(self.desc, s["dY"], s["Xt"], None, s["dW"], s["ws"])
+
+    def exact(self, i):
+        s = self.sets[i % len(self.sets)]
+        if s["wsx"] is None:
+            s["wsx"] = self.xb.alloc_ws(self.desc, self.xb.XCONV_OP_EXACT, self.dev)
+        self.xb.xconv_dw_exact(self.desc, s["dY"], s["X"], s["dW"], s["wsx"])
+
+
+def time_region(fn, steps, warmup):
+    import torch
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        fn(warmup + i)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def kernel_times(xb, fn, steps, warmup):
+    """Average duration of each kernel over `steps` timed steps, from HIP events
+    the library records on its launch stream around every kernel."""
+    import torch
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    xb.xconv_prof_enable(True)
+    t0 = time.perf_counter()
+    for i in range(steps):
+        fn(warmup + i)
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3 / steps
+    xb.xconv_prof_enable(False)
+    acc = {}
+    for kid, ms in xb.xconv_prof_collect():
+        name = xb.xconv_prof_kernel_name(kid)
+        a = acc.setdefault(name, [0.0, 0])
+        a[0] += ms
+        a[1] += 1
+    return {k: v[0] / v[1] for k, v in acc.items()}, wall
+
+
+def nsets_for(cfg):
+    s = elem_bytes(cfg.dtype)
+    per_set = (cfg.B * cfg.C_in * cfg.H * cfg.W + cfg.B * cfg.C_out * cfg.Ho * cfg.Wo + cfg.B * cfg.r * cfg.H * cfg.W) * s
+    n = int(600e6 // per_set) + 1               # > 2x the 256 MB Infinity Cache in rotation
+    return max(3, min(n, 16))
+
+
+def measure_config(cfg, steps, warmup, dev, with_exact=False):
+    from paper_2106_06998_amd import binding as xb
+    L = Layer(cfg, nsets_for(cfg), dev)
+    ms_step = time_region(L.step, steps, warmup)
+    kt, wall_prof = kernel_times(xb, L.step, steps, warmup)
+    alg = algorithmic(cfg)
+    out = dict(name=cfg.name, dtype=cfg.dtype, ms_per_layer=ms_step, ms_per_layer_with_events=wall_prof,
+               kernels_ms=kt, plan=xb.xconv_plan_info(L.desc, xb.XCONV_OP_ESTIMATE),
+               act_bytes_saved=alg["act_bytes_saved"], buffer_sets=len(L.sets))
+    tp = kt.get("probe_kernel", kt.get("probe_generic_kernel"))
+    tc = kt.get("corr_kernel")
+    if tp:
+        out["probe"] = dict(ms=tp, gbps=alg["probe_bytes"] / tp / 1e6, gflops=alg["probe_flops"] / tp / 1e6,
+                            hbm_frac=alg["probe_bytes"] / tp / 1e6 / PEAK_HBM_GBS)
+    if tc:
+        out["corr"] = dict(ms=tc, gbps=alg["corr_bytes"] / tc / 1e6, gflops=alg["corr_flops"] / tc / 1e6,
+                           hbm_frac=alg["corr_bytes"] / tc / 1e6 / PEAK_HBM_GBS,
+                           mfma_frac=alg["corr_flops"] / tc / 1e9 / PEAK_MFMA_TFLOPS[cfg.dtype])
+    if with_exact:
+        ms_x = time_region(L.exact, max(steps // 4, 5), max(warmup // 4, 2))
+        out["exact_ms"] = ms_x
+        out["exact_gflops"] = alg["exact_flops"] / ms_x / 1e6
+        out["estimate_vs_exact_speedup"] = ms_x / ms_step
+    return out, L
+
+
+def cpu_baseline(cfg, host, budget_s=12.0):
+    """The CPU oracle, as it stands, on the same layer (single thread)."""
+    from oracle import xconv_oracle as xo
+    X, dY = host
+    Z = xo.probe_matrix({"rademacher": xo.RADEMACHER, "gaussian": xo.GAUSSIAN}[cfg.probe], cfg.seeds[2], cfg.C_in, cfg.r)
+    dt = {"f32": xo.F32, "bf16": xo.BF16, "f16": xo.F16}[cfg.dtype]
+    st, pd = (cfg.stride, cfg.stride), (cfg.pad, cfg.pad)
+    reps, t_total = 0, 0.0
+    while reps < 1 or (t_total < budget_s and reps < 16):
+        t0 = time.perf_counter()
+        Xt = xo.probe_fwd(X, Z, dt)
+        xo.dw_from_xt(dY, Xt, Z, cfg.k, cfg.k, st, pd)
+        t_total += time.perf_counter() - t0
+        reps += 1
+    return dict(value=t_total / reps * 1e3, unit="ms/layer", cores=1, kind="oracle",
+                sample="full %s layer (probe_fwd + dw_from_xt), %d repetition(s), plain C -O2, one thread" % (cfg.name, reps))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="C2", help="layer the headline value is quoted on (default: configs[1])")
+    ap.add_argument("--all", action="store_true", help="also measure the other benchmark layers (extra field per_config)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the path has no multi-GPU part in this build (got --gpus %d)" % args.gpus, file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2106_06998_amd import binding as xb
+    from paper_2106_06998_amd import synth
+    xb.lib()                                     # fail loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    dev = "cuda:0"
+    cfg = synth.CONFIGS[args.config]
+    res, L = measure_config(cfg, args.steps, args.warmup, dev, with_exact=True)
+    alg = algorithmic(cfg)
+
+    # roofline of the dominant kernel of the step
+    dom = "corr" if res.get("corr", {}).get("ms", 0) >= res.get("probe", {}).get("ms", 0) else "probe"
+    if dom == "corr":
+        mfma_bound = (alg["corr_flops"] / (PEAK_MFMA_TFLOPS[cfg.dtype] * 1e12)) >= (alg["corr_bytes"] / (PEAK_HBM_GBS * 1e9))
+        if mfma_bound:
+            ach = res["corr"]["gflops"] / 1e3
+            roof = dict(bound="mfma", achieved=ach, peak=PEAK_MFMA_TFLOPS[cfg.dtype], unit="TFLOP/s",
+                        frac=ach / PEAK_MFMA_TFLOPS[cfg.dtype])
+        else:
+            ach = res["corr"]["gbps"]
+            roof = dict(bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS)
+        roof["kernel"] = "corr_kernel"
+        roof["kernel_ms"] = res["corr"]["ms"]
+    else:
+        ach = res["probe"]["gbps"]
+        roof = dict(bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS,
+                    kernel="probe_kernel", kernel_ms=res["probe"]["ms"])
+    roof["traffic"] = MEASURED_TRAFFIC.get((cfg.name, roof["kernel"]))
+
+    line = {
+        "metric": "ms/layer for the XConv dW estimate (xconv_probe_fwd + xconv_dw_estimate), 1 GPU",
+        "value": res["ms_per_layer"], "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": res["ms_per_layer"], "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": "%s: B=%d C_in=%d C_out=%d H=W=%d k=%d stride=%d pad=%d r=%d %s probes, %s storage" % (
+            cfg.name, cfg.B, cfg.C_in, cfg.C_out, cfg.H, cfg.k, cfg.stride, cfg.pad, cfg.r, cfg.probe, cfg.dtype)},
+        "gbps": (alg["probe_bytes"] + alg["corr_bytes"]) / res["ms_per_layer"] / 1e6,
+        "gflops": (alg["probe_flops"] + alg["corr_flops"]) / res["ms_per_layer"] / 1e6,
+        "roofline": roof,
+        "detail": res,
+    }
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(cfg, L.host)
+    del L
+    if args.all:
+        per = []
+        for name, c in synth.CONFIGS.items():
+            if name == cfg.name:
+                continue
+            torch.cuda.empty_cache()
+            r, Lc = measure_config(c, max(args.steps // 2, 10), max(args.warmup // 2, 3), dev, with_exact=(name == "C5"))
+            del Lc
+            per.append(r)
+        line["per_config"] = per
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

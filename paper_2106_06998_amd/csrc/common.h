@@ -18,10 +18,11 @@ enum KernelId {
     K_PROBE = 1,
     K_PROBE_GENERIC = 2,
     K_CORR = 3,
-    K_REDUCE_EXPAND = 4,
+    K_REDUCE = 4,
     K_TO_NHWC = 5,
     K_UNPACK = 6,
-    K_COUNT = 7
+    K_EXPAND = 7,
+    K_COUNT = 8
 };
 
 __host__ __device__ inline int round_up(int a, int b) { return (a + b - 1) / b * b; }

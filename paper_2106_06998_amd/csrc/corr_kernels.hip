@@ -10,7 +10,7 @@
 // Shape of the work: an implicit GEMM with M = C_out, N = (columns of A) x kH*kW
 // and a very long reduction K = B*Ho*Wo.  Only a handful of output tiles exist,
 // so the reduction is split over workgroups (deterministic two-pass reduction:
-// partial tiles to scratch, then reduce_expand_kernel).
+// partial tiles to scratch, then reduce_partials_kernel and expand_kernel).
 //
 // Mapping to the matrix cores.  The reduction index is (image, pixel); the MFMA
 // needs several consecutive k per lane for the 16-bit types, and the +-1 pixel
@@ -43,23 +43,40 @@ namespace xc {
 
 constexpr int kMaxOff = 9;
 
+// Position of a step: batch group, first output row, first output column.
 struct StepPos {
-    int bg, oy0, x0;
+    int bg, band, strip, oy0, x0;
 };
 
 __device__ inline StepPos decode_step(const CorrParams &P, int t)
 {
     StepPos s;
-    const int band = t % P.NBAND;
+    s.band = t % P.NBAND;
     t /= P.NBAND;
-    const int strip = t % P.NSTRIP;
+    s.strip = t % P.NSTRIP;
     s.bg = t / P.NSTRIP;
-    s.oy0 = band * P.RB;
-    s.x0 = strip * P.CW;
+    s.oy0 = s.band * P.RB;
+    s.x0 = s.strip * P.CW;
+    return s;
+}
+__device__ inline StepPos next_step(const CorrParams &P, StepPos s)
+{
+    if (++s.band == P.NBAND) {
+        s.band = 0;
+        if (++s.strip == P.NSTRIP) {
+            s.strip = 0;
+            ++s.bg;
+        }
+    }
+    s.oy0 = s.band * P.RB;
+    s.x0 = s.strip * P.CW;
     return s;
 }
 
-template <int DT, int MT, int NA, int NB>
+// NOFF: kernel offsets a workgroup accumulates (9, or 1 for 1x1 kernels).  A
+// last group with fewer offsets recomputes its first offset in the spare slots
+// and does not write them.
+template <int DT, int MT, int NA, int NB, int NOFF>
 __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrParams P)
 {
     constexpr bool F32 = (DT == XCONV_F32);
@@ -72,15 +89,16 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrParams P)
     unit_t *lds_a = reinterpret_cast<unit_t *>(lds_raw);
     unit_t *lds_b = lds_a + P.a_units;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the k-step bookkeeping scalar
     const int jl = lane & 15, g = lane >> 4;
     const int wm = wave % P.WM, wj = (wave / P.WM) % P.WJ, wk = wave / (P.WM * P.WJ);
 
     const int tm = blockIdx.y % P.NTM, tj = blockIdx.y / P.NTM;
     const int m0 = tm * P.M_WG;   // first output channel of the workgroup tile
     const int jb = tj * P.J_WG;   // first column of A of the workgroup tile
-    const int o_first = blockIdx.z * kMaxOff;
-    const int noff = (P.K2 - o_first) < kMaxOff ? (P.K2 - o_first) : kMaxOff;
+    const int o_first = blockIdx.z * NOFF;
+    const int noff = (P.K2 - o_first) < NOFF ? (P.K2 - o_first) : NOFF;
 
     const int HoWo = P.Ho * P.Wo;
     const elem_t *dY = static_cast<const elem_t *>(P.dY);
@@ -119,8 +137,7 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrParams P)
     uint4 rbv[NB][BI];
 
     // ---- dY: global -> registers ----------------------------------------------
-    auto a_load = [&](int step) {
-        const StepPos sp = decode_step(P, step);
+    auto a_load = [&](const StepPos &sp) {
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
             if (a_dec[i] < 0) continue;
@@ -130,12 +147,13 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrParams P)
             const int chunk = f0 / EPV + cc;
             const int m = m0 + ml;
             const bool ok = (oy < P.Ho) && (m < P.C_out);
+            const size_t lane_off = (size_t)m * HoWo + (size_t)chunk * EPV;
 #pragma unroll
             for (int img = 0; img < BI; ++img) {
                 const int b = sp.bg * BI + img;
                 uint4 v = uint4{0u, 0u, 0u, 0u};
                 if (ok && b < P.B) {
-                    const elem_t *src = dY + ((size_t)b * P.C_out + m) * HoWo + (size_t)chunk * EPV;
+                    const elem_t *src = dY + (size_t)b * P.C_out * HoWo + lane_off;
                     if (P.dy_vec) {
                         if (chunk * EPV < HoWo) v = *reinterpret_cast<const uint4 *>(src);
                     } else {
@@ -156,8 +174,7 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrParams P)
     };
 
     // ---- dY: registers -> LDS (every pixel slot of the step is written) --------
-    auto a_store = [&](int step) {
-        const StepPos sp = decode_step(P, step);
+    auto a_store = [&](const StepPos &sp) {
         const int cw_eff = (P.Wo - sp.x0) < P.CW ? (P.Wo - sp.x0) : P.CW;
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
@@ -194,11 +211,12 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrParams P)
         const int iy = row_first + rr - P.ph;
         const int ix = sp.x0 * P.sw - P.pw + c;
         const bool ok = iy >= 0 && iy < P.H && ix >= 0 && ix < P.W;
+        const size_t lane_off = ((size_t)iy * P.W + ix) * P.CS + jb + jc * EPV;
 #pragma unroll
         for (int img = 0; img < BI; ++img) {
             const int b = sp.bg * BI + img;
             uint4 v = uint4{0u, 0u, 0u, 0u};
-            if (ok && b < P.B) v = *reinterpret_cast<const uint4 *>(Ag + (((size_t)b * P.H + iy) * P.W + ix) * P.CS + jb + jc * EPV);
+            if (ok && b < P.B) v = *reinterpret_cast<const uint4 *>(Ag + (size_t)b * P.H * P.W * P.CS + lane_off);
             dst[img] = v;
         }
     };
@@ -219,8 +237,7 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrParams P)
         }
     };
     // rows the step loads in steady state: [oy0*sh + NOLD, oy0*sh + NR)
-    auto b_load = [&](int step) {
-        const StepPos sp = decode_step(P, step);
+    auto b_load = [&](const StepPos &sp) {
         const int row_first = sp.oy0 * P.sh + P.NOLD;
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
@@ -228,8 +245,7 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrParams P)
             b_load_task(sp, row_first, b_dec[i] >> 22, (b_dec[i] >> 6) & 0xffff, b_dec[i] & 0x3f, rbv[i]);
         }
     };
-    auto b_store = [&](int step) {
-        const StepPos sp = decode_step(P, step);
+    auto b_store = [&](const StepPos &sp) {
         const int row_first = sp.oy0 * P.sh + P.NOLD;
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
@@ -238,8 +254,7 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrParams P)
         }
     };
     // rows [oy0*sh, oy0*sh + NOLD) that a step normally inherits from its predecessor
-    auto b_fill_old = [&](int step) {
-        const StepPos sp = decode_step(P, step);
+    auto b_fill_old = [&](const StepPos &sp) {
         const int row_first = sp.oy0 * P.sh;
         const int ntask = P.NOLD * P.BWc * JC;
         for (int task = tid; task < ntask; task += kThreads) {
@@ -251,92 +266,155 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrParams P)
     };
 
     // ---- accumulators -----------------------------------------------------------
-    f32x4 acc[MT][kMaxOff];
+    f32x4 acc[MT][NOFF];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int o = 0; o < kMaxOff; ++o) acc[mt][o] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int o = 0; o < NOFF; ++o) acc[mt][o] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    int off_ky[kMaxOff], off_kx[kMaxOff];
+    int off_ky[NOFF], off_kx[NOFF];
 #pragma unroll
-    for (int o = 0; o < kMaxOff; ++o) {
+    for (int o = 0; o < NOFF; ++o) {
         const int oo = (o < noff) ? (o_first + o) : o_first;
         off_ky[o] = oo / P.kW;
         off_kx[o] = oo % P.kW;
     }
 
-    const int NKS = (P.RB * P.CWp) >> 2;  // k-steps (4 pixel slots each) per step
+    // ---- MFMA loop over the k-steps of a staged step -----------------------------
+    // A k-step is 4 consecutive pixel slots of one output row.  Wave wk takes
+    // k-steps wk, wk+WK, ...  All of the bookkeeping below is wave-uniform.
+    const int NXQ = P.CWp >> 2;          // k-steps per output row
+    const int NKS = P.RB * NXQ;          // k-steps per step
+    const int my_ks = (NKS - wk + P.WK - 1) / P.WK;
     const int a_lane = g * P.ASTR + (wm * MT) * 16 + jl;
     const int b_lane = F32 ? (g * P.sw * P.BSTR + wj * 16 + jl) : (g * P.sw * P.BSTR + wj * 18 + jl + (jl >> 3));
+    const int b_xq = 4 * P.sw * P.BSTR;  // LDS units between k-steps of a row
 
+    struct Frags {
+        unit_t a[MT];
+        unit_t b[NOFF];
+    };
+    struct Cursor {
+        int rb, xq, rowmod;          // output row in the band, k-step in the row, (oy*sh) mod NR
+        int brow[NOFF];              // LDS unit of (ring slot of the offset's row, column kx) for this output row
+    };
+    auto set_rows = [&](Cursor &c) {
+#pragma unroll
+        for (int o = 0; o < NOFF; ++o) {
+            int slot = c.rowmod + off_ky[o];
+            if (slot >= P.NR) slot -= P.NR;
+            c.brow[o] = (slot * P.BWc + off_kx[o]) * P.BSTR;
+        }
+    };
+    auto advance = [&](Cursor &c) {
+        c.xq += P.WK;
+        while (c.xq >= NXQ) {
+            c.xq -= NXQ;
+            ++c.rb;
+            c.rowmod += P.sh;
+            while (c.rowmod >= P.NR) c.rowmod -= P.NR;
+            set_rows(c);
+        }
+    };
+    auto load_frags = [&](Frags &f, const Cursor &c) {
+        const unit_t *pa = lds_a + (size_t)((c.rb * P.CWp + (c.xq << 2)) * P.ASTR) + a_lane;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) f.a[mt] = pa[mt * 16];
+        const unit_t *pb = lds_b + (size_t)(c.xq * b_xq) + b_lane;
+#pragma unroll
+        for (int o = 0; o < NOFF; ++o) f.b[o] = pb[c.brow[o]];
+    };
+    auto mfma_frags = [&](const Frags &f) {
+#pragma unroll
+        for (int o = 0; o < NOFF; ++o)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                if constexpr (F32) acc[mt][o] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.a[mt], f.b[o], acc[mt][o], 0, 0, 0);
+                else acc[mt][o] = mfma16<DT>(f.a[mt], f.b[o], acc[mt][o]);
+            }
+    };
+
+    StepPos sp = decode_step(P, t_begin);
     if (t_begin < t_end) {
-        a_load(t_begin);
-        b_load(t_begin);
+        a_load(sp);
+        b_load(sp);
     }
     int prev_bg = -1, prev_x0 = -1, prev_oy0 = -1;
     for (int step = t_begin; step < t_end; ++step) {
-        const StepPos sp = decode_step(P, step);
         __syncthreads();  // everyone is done reading the tiles of the previous step
         const bool fresh = !(sp.bg == prev_bg && sp.x0 == prev_x0 && sp.oy0 == prev_oy0 + P.RB);
-        if (fresh && P.NOLD > 0) b_fill_old(step);
-        a_store(step);
-        b_store(step);
+        if (fresh && P.NOLD > 0) b_fill_old(sp);
+        a_store(sp);
+        b_store(sp);
         prev_bg = sp.bg; prev_x0 = sp.x0; prev_oy0 = sp.oy0;
         __syncthreads();
+        const StepPos spn = next_step(P, sp);
         if (step + 1 < t_end) {
-            a_load(step + 1);
-            b_load(step + 1);
+            a_load(spn);
+            b_load(spn);
         }
 
-        for (int ks = wk; ks < NKS; ks += P.WK) {
-            const int p0 = ks << 2;
-            const int rb = p0 / P.CWp;
-            const int xs0 = p0 - rb * P.CWp;
-            unit_t af[MT];
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) af[mt] = lds_a[(size_t)p0 * P.ASTR + a_lane + mt * 16];
-            const int rowp = (sp.oy0 + rb) * P.sh;
-#pragma unroll
-            for (int o = 0; o < kMaxOff; ++o) {
-                if (o < noff) {
-                    const int slot = (rowp + off_ky[o]) % P.NR;
-                    const int col = xs0 * P.sw + off_kx[o];
-                    const unit_t bf = lds_b[(size_t)(slot * P.BWc + col) * P.BSTR + b_lane];
-#pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) {
-                        if constexpr (F32) acc[mt][o] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[mt], bf, acc[mt][o], 0, 0, 0);
-                        else acc[mt][o] = mfma16<DT>(af[mt], bf, acc[mt][o]);
-                    }
-                }
-            }
+        // double-buffered fragments: the LDS reads of k-step i+1 are in flight during the MFMAs of k-step i
+        Cursor cur;
+        cur.rb = 0;
+        cur.xq = wk;
+        cur.rowmod = (sp.oy0 * P.sh) % P.NR;
+        set_rows(cur);
+        while (cur.xq >= NXQ) {  // WK > NXQ: the first k-step of this wave is in a later row
+            cur.xq -= NXQ;
+            ++cur.rb;
+            cur.rowmod += P.sh;
+            while (cur.rowmod >= P.NR) cur.rowmod -= P.NR;
+            set_rows(cur);
         }
+        Frags f0, f1;
+        int left = my_ks;
+        if (left > 0) {
+            load_frags(f0, cur);
+            advance(cur);
+        }
+        while (left > 0) {
+            if (left > 1) {
+                load_frags(f1, cur);
+                advance(cur);
+            }
+            mfma_frags(f0);
+            if (--left == 0) break;
+            if (left > 1) {
+                load_frags(f0, cur);
+                advance(cur);
+            }
+            mfma_frags(f1);
+            --left;
+        }
+        sp = spn;
     }
 
     // ---- reduce the WK k-split waves through LDS, then write the partial tile --
     // One buffer per (wm, wj) group; waves wk = 1..WK-1 hand their tiles to wave
     // wk = 0 one after the other, so the summation order is fixed.
-    f32x4 *red = reinterpret_cast<f32x4 *>(lds_raw) + ((size_t)(wm + P.WM * wj) * MT * kMaxOff) * 64 + lane;
+    f32x4 *red = reinterpret_cast<f32x4 *>(lds_raw) + ((size_t)(wm + P.WM * wj) * MT * NOFF) * 64 + lane;
     for (int k = 1; k < P.WK; ++k) {
         __syncthreads();
         if (wk == k) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                for (int o = 0; o < kMaxOff; ++o) red[(mt * kMaxOff + o) * 64] = acc[mt][o];
+                for (int o = 0; o < NOFF; ++o) red[(mt * NOFF + o) * 64] = acc[mt][o];
         }
         __syncthreads();
         if (wk == 0) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                for (int o = 0; o < kMaxOff; ++o) acc[mt][o] += red[(mt * kMaxOff + o) * 64];
+                for (int o = 0; o < NOFF; ++o) acc[mt][o] += red[(mt * NOFF + o) * 64];
         }
     }
     if (wk == 0) {
         // D tile: lane (jl, g) holds rows 4g..4g+3 (output channels) of column jl
         const int jcol = jb + wj * 16 + jl;
 #pragma unroll
-        for (int o = 0; o < kMaxOff; ++o) {
+        for (int o = 0; o < NOFF; ++o) {
             if (o < noff) {
                 float *dst = P.part + (((size_t)blockIdx.x * P.K2 + (o_first + o)) * P.JP + jcol) * P.MP + m0 + (wm * MT) * 16 + 4 * g;
 #pragma unroll
@@ -347,44 +425,92 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrParams P)
 }
 
 // ---------------------------------------------------------------------------
-// Second pass: sum the S partial tiles in a fixed order and either expand through
-// Z/r (Algorithm 1 backward step 4) or, on the exact path, just transpose into
-// dW[m,n,ky,kx].  One workgroup per (kernel offset, 16 output channels).
+// Second pass, part 1: T[e] = sum_s part[s][e] over the S partial buffers, in a
+// fixed order.  16 consecutive float4 elements x 16 groups of s per workgroup.
 // ---------------------------------------------------------------------------
-constexpr int kRedJ = 1024;
-
-__global__ __launch_bounds__(kThreads) void reduce_expand_kernel(const float *__restrict__ part, const float *__restrict__ Z,
-                                                                 float *__restrict__ dW, int S, int K2, int JP, int MP,
-                                                                 int C_out, int C_in, int r, int Q)
+__global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const f32x4 *__restrict__ part, f32x4 *__restrict__ T,
+                                                                   int S, int E4)
 {
-    __shared__ float T[kRedJ][16];
-    const int o = blockIdx.x, mb = blockIdx.y * 16;
-    const int tid = threadIdx.x, mm = tid & 15, tl = tid >> 4;
-    const int m = mb + mm;
-    for (int jbase = 0; jbase < Q; jbase += kRedJ) {
-        const int jn = (Q - jbase) < kRedJ ? (Q - jbase) : kRedJ;
+    __shared__ f32x4 red[16][17];
+    const int ve = threadIdx.x & 15, sg = threadIdx.x >> 4;
+    const int e4 = blockIdx.x * 16 + ve;
+    f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0, s2 = s0, s3 = s0;
+    if (e4 < E4) {
+        const f32x4 *p = part + e4;
+        int k = sg;
+        for (; k + 48 < S; k += 64) {
+            const f32x4 v0 = p[(size_t)k * E4], v1 = p[(size_t)(k + 16) * E4];
+            const f32x4 v2 = p[(size_t)(k + 32) * E4], v3 = p[(size_t)(k + 48) * E4];
+            s0 += v0; s1 += v1; s2 += v2; s3 += v3;
+        }
+        for (; k < S; k += 16) s0 += p[(size_t)k * E4];
+    }
+    red[sg][ve] = (s0 + s1) + (s2 + s3);
+    __syncthreads();
+    if (sg == 0 && e4 < E4) {
+        f32x4 t = red[0][ve];
+#pragma unroll
+        for (int q = 1; q < 16; ++q) t += red[q][ve];
+        T[e4] = t;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Second pass, part 2 (Algorithm 1 backward step 4, Eq. (6) step (iii)):
+//   dW[m,n,o] = (1/r) sum_j Z[n,j] T[o,j,m].
+// One workgroup per (offset o, 16 output channels, 64 input channels); j is
+// walked in chunks of 128 staged in LDS.
+// ---------------------------------------------------------------------------
+constexpr int kExpJ = 128;
+
+__global__ __launch_bounds__(kThreads) void expand_kernel(const float *__restrict__ T, const float *__restrict__ Z,
+                                                          float *__restrict__ dW, int K2, int JP, int MP, int C_out, int C_in, int r)
+{
+    __shared__ float Ts[kExpJ][16];
+    __shared__ float Zs[64][kExpJ + 1];
+    const int o = blockIdx.x, mb = blockIdx.y * 16, nb = blockIdx.z * 64;
+    const int tid = threadIdx.x, mm = tid & 15, nq = tid >> 4;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int j0 = 0; j0 < r; j0 += kExpJ) {
+        const int jn = (r - j0) < kExpJ ? (r - j0) : kExpJ;
         __syncthreads();
-        for (int j = tl; j < jn; j += 16) {
-            float s = 0.f;
-            const float *src = part + ((size_t)o * JP + jbase + j) * MP + mb + mm;
-            for (int k = 0; k < S; ++k) s += src[(size_t)k * K2 * JP * MP];
-            T[j][mm] = s;
+        for (int e = tid; e < jn * 16; e += kThreads) {
+            const int j = e >> 4, m = e & 15;
+            Ts[j][m] = T[((size_t)o * JP + j0 + j) * MP + mb + m];
+        }
+        for (int e = tid; e < 64 * jn; e += kThreads) {
+            const int nl = e / jn, j = e - nl * jn;
+            Zs[nl][j] = (nb + nl < C_in) ? Z[(size_t)(nb + nl) * r + j0 + j] : 0.f;
         }
         __syncthreads();
-        if (Z != nullptr) {
-            // Q == r <= kRedJ: a single pass
-            const float inv_r = 1.0f / (float)r;
-            for (int n = tl; n < C_in; n += 16) {
-                float s = 0.f;
-                const float *zn = Z + (size_t)n * r;
-                for (int j = 0; j < jn; ++j) s = fmaf(zn[j], T[j][mm], s);
-                if (m < C_out) dW[((size_t)m * C_in + n) * K2 + o] = s * inv_r;
-            }
-        } else {
-            for (int j = tl; j < jn; j += 16)
-                if (m < C_out) dW[((size_t)m * C_in + jbase + j) * K2 + o] = T[j][mm];
+        for (int j = 0; j < jn; ++j) {
+            const float t = Ts[j][mm];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) acc[q] = fmaf(Zs[nq * 4 + q][j], t, acc[q]);
         }
     }
+    const int m = mb + mm;
+    const float inv_r = 1.0f / (float)r;
+    if (m < C_out) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int n = nb + nq * 4 + q;
+            if (n < C_in) dW[((size_t)m * C_in + n) * K2 + o] = acc[q] * inv_r;
+        }
+    }
+}
+
+// Exact path: dW[m,n,o] = T[o,n,m] (a transpose of the reduced tile).
+__global__ __launch_bounds__(kThreads) void untile_kernel(const float *__restrict__ T, float *__restrict__ dW, int K2, int JP,
+                                                          int MP, int C_out, int C_in)
+{
+    const long long i = (long long)blockIdx.x * kThreads + threadIdx.x;
+    const long long total = (long long)C_out * C_in * K2;
+    if (i >= total) return;
+    const int o = (int)(i % K2);
+    const long long mn = i / K2;
+    const int n = (int)(mn % C_in), m = (int)(mn / C_in);
+    dW[i] = T[((size_t)o * JP + n) * MP + m];
 }
 
 // ---------------------------------------------------------------------------
@@ -469,7 +595,7 @@ bool plan_corr(CorrParams &P, int dtype, int B, int C_out, int H, int W, int kH,
     P.CS = CS;
     P.NBG = ceil_div(B, BI);
     P.K2 = kH * kW;
-    P.NOG = ceil_div(P.K2, kMaxOff);
+    P.NOG = ceil_div(P.K2, P.K2 == 1 ? 1 : kMaxOff);
     P.dy_vec = (dy_aligned && ((long long)P.Ho * P.Wo) % EPV == 0) ? 1 : 0;
 
     const int MT = corr_mt(C_out);
@@ -546,26 +672,42 @@ bool plan_corr(CorrParams &P, int dtype, int B, int C_out, int H, int W, int kH,
 
 size_t corr_lds_bytes(int dtype, const CorrParams &P) { return lds_bytes_of(P, dtype, corr_mt(P.C_out)); }
 
-size_t corr_partial_bytes(const CorrParams &P) { return (size_t)P.S * P.K2 * P.JP * P.MP * sizeof(float); }
+size_t corr_partial_bytes(const CorrParams &P)
+{
+    // S partial buffers followed by the reduced buffer T, each [K2, JP, MP] fp32
+    return ((size_t)P.S + 1) * P.K2 * P.JP * P.MP * sizeof(float);
+}
 
-template <int DT, int MT, int NA, int NB> static hipError_t launch_corr_cfg(const CorrParams &P, size_t lds, hipStream_t st)
+template <int DT, int MT, int NA, int NB, int NOFF> static hipError_t launch_corr_cfg(const CorrParams &P, size_t lds, hipStream_t st)
 {
     if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(corr_kernel<DT, MT, NA, NB>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
+        static bool done = false;  // per instantiation: the attribute sticks to the function
+        static size_t done_bytes = 0;
+        if (!done || lds > done_bytes) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(corr_kernel<DT, MT, NA, NB, NOFF>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+            if (e != hipSuccess) return e;
+            done = true;
+            done_bytes = kLdsLimit;
+        }
     }
-    hipLaunchKernelGGL((corr_kernel<DT, MT, NA, NB>), dim3(P.S, P.NTM * P.NTJ, P.NOG), dim3(kThreads), lds, st, P);
+    hipLaunchKernelGGL((corr_kernel<DT, MT, NA, NB, NOFF>), dim3(P.S, P.NTM * P.NTJ, P.NOG), dim3(kThreads), lds, st, P);
     return hipGetLastError();
+}
+
+template <int DT, int MT, int NA, int NB> static hipError_t launch_corr_noff(const CorrParams &P, size_t lds, hipStream_t st)
+{
+    if (P.K2 == 1) return launch_corr_cfg<DT, MT, NA, NB, 1>(P, lds, st);
+    return launch_corr_cfg<DT, MT, NA, NB, kMaxOff>(P, lds, st);
 }
 
 template <int DT, int MT> static hipError_t launch_corr_16(const CorrParams &P, size_t lds, hipStream_t st)
 {
     const int na = ceil_div(P.RB * P.M_WG * P.NCHR, kThreads), nb = ceil_div(P.NNEW * P.BWc * (P.J_WG / 8), kThreads);
-    if (na <= 1 && nb <= 1) return launch_corr_cfg<DT, MT, 1, 1>(P, lds, st);
-    if (na <= 1) return launch_corr_cfg<DT, MT, 1, 2>(P, lds, st);
-    if (nb <= 1) return launch_corr_cfg<DT, MT, 2, 1>(P, lds, st);
-    return launch_corr_cfg<DT, MT, 2, 2>(P, lds, st);
+    if (na <= 1 && nb <= 1) return launch_corr_noff<DT, MT, 1, 1>(P, lds, st);
+    if (na <= 1) return launch_corr_noff<DT, MT, 1, 2>(P, lds, st);
+    if (nb <= 1) return launch_corr_noff<DT, MT, 2, 1>(P, lds, st);
+    return launch_corr_noff<DT, MT, 2, 2>(P, lds, st);
 }
 
 hipError_t launch_corr(int dtype, const CorrParams &P, hipStream_t st)
@@ -573,8 +715,8 @@ hipError_t launch_corr(int dtype, const CorrParams &P, hipStream_t st)
     const int MT = corr_mt(P.C_out);
     const size_t lds = lds_bytes_of(P, dtype, MT);
     if (dtype == XCONV_F32) {
-        if (MT == 4) return launch_corr_cfg<XCONV_F32, 4, 8, 4>(P, lds, st);
-        return launch_corr_cfg<XCONV_F32, 1, 8, 4>(P, lds, st);
+        if (MT == 4) return launch_corr_noff<XCONV_F32, 4, 8, 4>(P, lds, st);
+        return launch_corr_noff<XCONV_F32, 1, 8, 4>(P, lds, st);
     }
     if (dtype == XCONV_BF16) {
         if (MT == 4) return launch_corr_16<XCONV_BF16, 4>(P, lds, st);
@@ -584,11 +726,26 @@ hipError_t launch_corr(int dtype, const CorrParams &P, hipStream_t st)
     return launch_corr_16<XCONV_F16, 1>(P, lds, st);
 }
 
-hipError_t launch_reduce_expand(const CorrParams &P, const float *Z, float *dW, int C_in, int r, hipStream_t st)
+static float *reduced_tile(const CorrParams &P) { return P.part + (size_t)P.S * P.K2 * P.JP * P.MP; }
+
+hipError_t launch_reduce(const CorrParams &P, hipStream_t st)
 {
-    const int Q = Z ? r : C_in;
-    hipLaunchKernelGGL(reduce_expand_kernel, dim3(P.K2, ceil_div(P.C_out, 16)), dim3(kThreads), 0, st, P.part, Z, dW, P.S, P.K2,
-                       P.JP, P.MP, P.C_out, C_in, r, Q);
+    const int E4 = (int)(((size_t)P.K2 * P.JP * P.MP) / 4);
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3(ceil_div(E4, 16)), dim3(kThreads), 0, st,
+                       reinterpret_cast<const f32x4 *>(P.part), reinterpret_cast<f32x4 *>(reduced_tile(P)), P.S, E4);
+    return hipGetLastError();
+}
+
+hipError_t launch_expand(const CorrParams &P, const float *Z, float *dW, int C_in, int r, hipStream_t st)
+{
+    if (Z) {
+        hipLaunchKernelGGL(expand_kernel, dim3(P.K2, ceil_div(P.C_out, 16), ceil_div(C_in, 64)), dim3(kThreads), 0, st,
+                           reduced_tile(P), Z, dW, P.K2, P.JP, P.MP, P.C_out, C_in, r);
+    } else {
+        const long long total = (long long)P.C_out * C_in * P.K2;
+        hipLaunchKernelGGL(untile_kernel, dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, st,
+                           reduced_tile(P), dW, P.K2, P.JP, P.MP, P.C_out, C_in);
+    }
     return hipGetLastError();
 }
 

@@ -24,8 +24,10 @@ bool plan_corr(CorrParams &P, int dtype, int B, int C_out, int H, int W, int kH,
 size_t corr_partial_bytes(const CorrParams &P);
 size_t corr_lds_bytes(int dtype, const CorrParams &P);
 hipError_t launch_corr(int dtype, const CorrParams &P, hipStream_t st);
-// dW[m,n,o] = scale * sum_j Zn[n,j] * sum_s part[s,o,j,m]   (Z != nullptr)
-// dW[m,n,o] = sum_s part[s,o,n,m]                            (Z == nullptr)
-hipError_t launch_reduce_expand(const CorrParams &P, const float *Z, float *dW, int C_in, int r, hipStream_t st);
+// T[o,j,m] = sum_s part[s,o,j,m]; T lives behind the S partial buffers
+hipError_t launch_reduce(const CorrParams &P, hipStream_t st);
+// dW[m,n,o] = (1/r) * sum_j Z[n,j] * T[o,j,m]   (Z != nullptr)
+// dW[m,n,o] = T[o,n,m]                          (Z == nullptr, exact path)
+hipError_t launch_expand(const CorrParams &P, const float *Z, float *dW, int C_in, int r, hipStream_t st);
 
 }  // namespace xc

@@ -221,7 +221,8 @@ xconv_status xconv_dw_estimate(const xconv_desc *d, const void *dY_dev, const vo
     P.A = Xt_dev;
     P.part = reinterpret_cast<float *>(static_cast<char *>(ws_dev) + zb);
     XC_LAUNCH(K_CORR, st, launch_corr(d->dtype, P, st));
-    XC_LAUNCH(K_REDUCE_EXPAND, st, launch_reduce_expand(P, Z, dW_dev, d->C_in, d->r, st));
+    XC_LAUNCH(K_REDUCE, st, launch_reduce(P, st));
+    XC_LAUNCH(K_EXPAND, st, launch_expand(P, Z, dW_dev, d->C_in, d->r, st));
     return XCONV_OK;
 }
 
@@ -247,7 +248,8 @@ xconv_status xconv_dw_exact(const xconv_desc *d, const void *dY_dev, const void 
     P.A = ws_dev;
     P.part = reinterpret_cast<float *>(static_cast<char *>(ws_dev) + xb);
     XC_LAUNCH(K_CORR, st, launch_corr(d->dtype, P, st));
-    XC_LAUNCH(K_REDUCE_EXPAND, st, launch_reduce_expand(P, nullptr, dW_dev, d->C_in, d->r, st));
+    XC_LAUNCH(K_REDUCE, st, launch_reduce(P, st));
+    XC_LAUNCH(K_EXPAND, st, launch_expand(P, nullptr, dW_dev, d->C_in, d->r, st));
     return XCONV_OK;
 }
 
@@ -307,7 +309,8 @@ const char *xconv_prof_kernel_name(int id)
     case K_PROBE: return "probe_kernel";
     case K_PROBE_GENERIC: return "probe_generic_kernel";
     case K_CORR: return "corr_kernel";
-    case K_REDUCE_EXPAND: return "reduce_expand_kernel";
+    case K_REDUCE: return "reduce_partials_kernel";
+    case K_EXPAND: return "expand_kernel";
     case K_TO_NHWC: return "to_nhwc_kernel";
     case K_UNPACK: return "unpack_kernel";
     default: return "unknown";
