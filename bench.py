@@ -178,6 +178,7 @@ def main():
     ap.add_argument("--config", default="C2", help="layer the headline value is quoted on (default: configs[1])")
     ap.add_argument("--all", action="store_true", help="also measure the other benchmark layers (extra field per_config)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--no-exact", action="store_true", help="skip timing xconv_dw_exact (for clean per-kernel profiles)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the path has no multi-GPU part in this build (got --gpus %d)" % args.gpus, file=sys.stderr)
@@ -192,7 +193,7 @@ def main():
         return 2
     dev = "cuda:0"
     cfg = synth.CONFIGS[args.config]
-    res, L = measure_config(cfg, args.steps, args.warmup, dev, with_exact=True)
+    res, L = measure_config(cfg, args.steps, args.warmup, dev, with_exact=not args.no_exact)
     alg = algorithmic(cfg)
 
     # roofline of the dominant kernel of the step
@@ -235,7 +236,7 @@ def main():
             if name == cfg.name:
                 continue
             torch.cuda.empty_cache()
-            r, Lc = measure_config(c, max(args.steps // 2, 10), max(args.warmup // 2, 3), dev, with_exact=(name == "C5"))
+            r, Lc = measure_config(c, max(args.steps // 2, 10), max(args.warmup // 2, 3), dev, with_exact=(name == "C5" and not args.no_exact))
             del Lc
             per.append(r)
         line["per_config"] = per

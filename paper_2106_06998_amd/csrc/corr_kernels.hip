@@ -109,55 +109,93 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrParams P)
     const int t_end = (int)(((long long)P.NS * (blockIdx.x + 1)) / P.S);
 
     // ---- per-thread staging tasks, decoded once -------------------------------
+    // Global reads go through raw buffer loads: one resource per batch group whose
+    // size is the bytes of the images that exist, so that images past the end of
+    // the batch (and every offset marked invalid below) read as zero in hardware.
+    constexpr uint32_t ES = sizeof(elem_t);
+    constexpr uint32_t kOOR = 0x80000000u;  // beyond any resource: the plan keeps a batch group within 2^30 bytes, and no offset added to kOOR wraps
+    constexpr int LOG_EPV = F32 ? 2 : 3;
+    const uint32_t dy_img_bytes = (uint32_t)P.C_out * (uint32_t)HoWo * ES;
+    const uint32_t a_img_bytes = (uint32_t)P.H * (uint32_t)P.W * (uint32_t)P.CS * ES;
+
     // dY task: (rb, ml, cc) = output row in the band, channel in the tile, vector chunk in the row
     const int ntask_a = P.RB * P.M_WG * P.NCHR;
-    int a_dec[NA];
+    uint32_t a_goff[NA];   // byte offset inside an image without the row part, or kOOR
+    int a_rbcc[NA];        // rb << 8 | cc, or -1 for no task
+    int a_lds[NA];         // LDS unit of (rb, ml) at slot 0
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
         const int task = tid + i * kThreads;
         const int cc = task % P.NCHR;
         const int ml = (task / P.NCHR) % P.M_WG;
         const int rb = task / (P.NCHR * P.M_WG);
-        a_dec[i] = (task < ntask_a) ? ((rb << 22) | (ml << 8) | cc) : -1;
+        const bool has = task < ntask_a;
+        a_rbcc[i] = has ? ((rb << 8) | cc) : -1;
+        a_goff[i] = (has && m0 + ml < P.C_out) ? ((uint32_t)(m0 + ml) * (uint32_t)HoWo + (uint32_t)cc * EPV) * ES : kOOR;
+        a_lds[i] = F32 ? (ml * P.ASTR + rb * P.CWp) : (rb * P.CWp * P.ASTR + ml);
     }
     // A task: (rr, c, jc) = row among the rows to load, staged column, vector of EPV channels
     const int JC = P.J_WG / EPV;
     const int ntask_b = P.NNEW * P.BWc * JC;
-    int b_dec[NB];
+    const int rotmul = 8 / (P.J_WG >> 4);  // 16-bit layout: rotation of each 16-column group (see b_unit)
+    int b_rrc[NB];         // rr << 16 | c, or -1
+    int b_jc[NB];
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
         const int task = tid + i * kThreads;
         const int jc = task % JC;
         const int c = (task / JC) % P.BWc;
         const int rr = task / (JC * P.BWc);
-        b_dec[i] = (task < ntask_b) ? ((rr << 22) | (c << 6) | jc) : -1;
+        b_rrc[i] = (task < ntask_b) ? ((rr << 16) | c) : -1;
+        b_jc[i] = jc;
     }
 
     uint4 ra[NA][BI];
     uint4 rbv[NB][BI];
 
+    auto rsrc_of = [&](const elem_t *base, int bg, uint32_t img_bytes) {
+        int left = P.B - bg * BI;
+        left = left < BI ? left : BI;
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<elem_t *>(base + (size_t)bg * BI * (img_bytes / ES)), 0,
+                                                 (uint32_t)left * img_bytes, 0x00020000);
+    };
+    auto buf16 = [](__amdgpu_buffer_rsrc_t r, uint32_t voff) {
+        typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, 0, 0);
+        return uint4{v.x, v.y, v.z, v.w};
+    };
+
     // ---- dY: global -> registers ----------------------------------------------
     auto a_load = [&](const StepPos &sp) {
+        const int fs = sp.oy0 * P.Wo + sp.x0;  // flat index of the step's first pixel
+        if (P.dy_vec) {
+            const __amdgpu_buffer_rsrc_t rs = rsrc_of(dY, sp.bg, dy_img_bytes);
+            const int rows_left = P.Ho - sp.oy0;
 #pragma unroll
-        for (int i = 0; i < NA; ++i) {
-            if (a_dec[i] < 0) continue;
-            const int rb = a_dec[i] >> 22, ml = (a_dec[i] >> 8) & 0x3fff, cc = a_dec[i] & 0xff;
-            const int oy = sp.oy0 + rb;
-            const int f0 = oy * P.Wo + sp.x0;
-            const int chunk = f0 / EPV + cc;
-            const int m = m0 + ml;
-            const bool ok = (oy < P.Ho) && (m < P.C_out);
-            const size_t lane_off = (size_t)m * HoWo + (size_t)chunk * EPV;
+            for (int i = 0; i < NA; ++i) {
+                if (a_rbcc[i] < 0) continue;
+                const int rb = a_rbcc[i] >> 8;
+                const uint32_t f0 = (uint32_t)(fs + rb * P.Wo);
+                uint32_t voff = a_goff[i] + ((f0 >> LOG_EPV) << 4);
+                voff = (rb < rows_left) ? voff : kOOR;
 #pragma unroll
-            for (int img = 0; img < BI; ++img) {
-                const int b = sp.bg * BI + img;
-                uint4 v = uint4{0u, 0u, 0u, 0u};
-                if (ok && b < P.B) {
-                    const elem_t *src = dY + (size_t)b * P.C_out * HoWo + lane_off;
-                    if (P.dy_vec) {
-                        if (chunk * EPV < HoWo) v = *reinterpret_cast<const uint4 *>(src);
-                    } else {
-                        uint32_t w[4] = {0u, 0u, 0u, 0u};
+                for (int img = 0; img < BI; ++img) ra[i][img] = buf16(rs, voff + (uint32_t)img * dy_img_bytes);
+            }
+        } else {
+            // planes are not 16-byte aligned: element loads with explicit bounds
+#pragma unroll
+            for (int i = 0; i < NA; ++i) {
+                if (a_rbcc[i] < 0) continue;
+                const int rb = a_rbcc[i] >> 8, cc = a_rbcc[i] & 0xff;
+                const int oy = sp.oy0 + rb;
+                const int chunk = ((fs + rb * P.Wo) >> LOG_EPV) + cc;
+                const bool ok = (oy < P.Ho) && (a_goff[i] != kOOR);
+#pragma unroll
+                for (int img = 0; img < BI; ++img) {
+                    const int b = sp.bg * BI + img;
+                    uint32_t w[4] = {0u, 0u, 0u, 0u};
+                    if (ok && b < P.B) {
+                        const elem_t *src = dY + (size_t)b * P.C_out * HoWo + (a_goff[i] / ES - (uint32_t)cc * EPV) + (size_t)chunk * EPV;
 #pragma unroll
                         for (int e = 0; e < EPV; ++e) {
                             if (chunk * EPV + e < HoWo) {
@@ -165,31 +203,31 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrParams P)
                                 else w[e >> 1] |= (uint32_t)src[e] << (16 * (e & 1));
                             }
                         }
-                        v = uint4{w[0], w[1], w[2], w[3]};
                     }
+                    ra[i][img] = uint4{w[0], w[1], w[2], w[3]};
                 }
-                ra[i][img] = v;
             }
         }
     };
 
-    // ---- dY: registers -> LDS (every pixel slot of the step is written) --------
+    // ---- dY: registers -> LDS.  16-bit: units [slot][m]; fp32: floats [m][slot].
     auto a_store = [&](const StepPos &sp) {
         const int cw_eff = (P.Wo - sp.x0) < P.CW ? (P.Wo - sp.x0) : P.CW;
+        const int fs = sp.oy0 * P.Wo + sp.x0;
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
-            if (a_dec[i] < 0) continue;
-            const int rb = a_dec[i] >> 22, ml = (a_dec[i] >> 8) & 0x3fff, cc = a_dec[i] & 0xff;
-            const int f0 = (sp.oy0 + rb) * P.Wo + sp.x0;
-            const int chunk = f0 / EPV + cc;
-            const int xs0 = chunk * EPV - f0;  // slot of the chunk's first pixel (may be negative)
-            unit_t *dst = lds_a + (size_t)(rb * P.CWp) * P.ASTR + ml;
+            if (a_rbcc[i] < 0) continue;
+            const int rb = a_rbcc[i] >> 8, cc = a_rbcc[i] & 0xff;
+            const int xs0 = cc * EPV - ((fs + rb * P.Wo) & (EPV - 1));  // slot of the chunk's first pixel (may be negative)
             if constexpr (F32) {
-                const uint32_t w[4] = {ra[i][0].x, ra[i][0].y, ra[i][0].z, ra[i][0].w};
+                float *dst = lds_a + a_lds[i];
+                if (xs0 >= 0 && xs0 + 4 <= cw_eff && (xs0 & 3) == 0) {
+                    *reinterpret_cast<uint4 *>(dst + xs0) = ra[i][0];
+                } else {
+                    const uint32_t w[4] = {ra[i][0].x, ra[i][0].y, ra[i][0].z, ra[i][0].w};
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int xs = xs0 + e;
-                    if (xs >= 0 && xs < P.CWp) dst[xs * P.ASTR] = (xs < cw_eff) ? __uint_as_float(w[e]) : 0.0f;
+                    for (int e = 0; e < 4; ++e)
+                        if ((unsigned)(xs0 + e) < (unsigned)cw_eff) dst[xs0 + e] = __uint_as_float(w[e]);
                 }
             } else {
                 uint32_t rows[8][4];
@@ -197,31 +235,38 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrParams P)
                 for (int q = 0; q < 8; ++q) { rows[q][0] = ra[i][q].x; rows[q][1] = ra[i][q].y; rows[q][2] = ra[i][q].z; rows[q][3] = ra[i][q].w; }
                 uint4 cols[8];
                 transpose_rows8<4>(rows, cols);
+                uint4 *dst = lds_a + a_lds[i];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int xs = xs0 + e;
-                    if (xs >= 0 && xs < P.CWp) dst[xs * P.ASTR] = (xs < cw_eff) ? cols[e] : uint4{0u, 0u, 0u, 0u};
-                }
+                for (int e = 0; e < 8; ++e)
+                    if ((unsigned)(xs0 + e) < (unsigned)cw_eff) dst[(xs0 + e) * P.ASTR] = cols[e];
+            }
+        }
+        // pixel slots past the strip's last column (up to CWp) take part in the MFMAs: keep them zero
+        const int ntail = P.CWp - cw_eff;
+        if (ntail > 0) {
+            for (int t = tid; t < P.RB * ntail * P.M_WG; t += kThreads) {
+                const int ml = t % P.M_WG, q = t / P.M_WG;
+                const int xs = cw_eff + q % ntail, rb = q / ntail;
+                if constexpr (F32) lds_a[ml * P.ASTR + rb * P.CWp + xs] = 0.0f;
+                else lds_a[(size_t)(rb * P.CWp + xs) * P.ASTR + ml] = uint4{0u, 0u, 0u, 0u};
             }
         }
     };
 
     // ---- A rows: global -> registers.  Rows are in padded coordinates (iy + ph).
-    auto b_load_task = [&](const StepPos &sp, int row_first, int rr, int c, int jc, uint4 (&dst)[BI]) {
+    auto b_load_task = [&](__amdgpu_buffer_rsrc_t rs, int xbase, int row_first, int rr, int c, int jc, uint4 (&dst)[BI]) {
         const int iy = row_first + rr - P.ph;
-        const int ix = sp.x0 * P.sw - P.pw + c;
-        const bool ok = iy >= 0 && iy < P.H && ix >= 0 && ix < P.W;
-        const size_t lane_off = ((size_t)iy * P.W + ix) * P.CS + jb + jc * EPV;
+        const int ix = xbase + c;
+        const bool ok = (unsigned)iy < (unsigned)P.H && (unsigned)ix < (unsigned)P.W;
+        const uint32_t voff = ok ? ((uint32_t)(iy * P.W + ix) * (uint32_t)P.CS + (uint32_t)(jb + jc * EPV)) * ES : kOOR;
 #pragma unroll
-        for (int img = 0; img < BI; ++img) {
-            const int b = sp.bg * BI + img;
-            uint4 v = uint4{0u, 0u, 0u, 0u};
-            if (ok && b < P.B) v = *reinterpret_cast<const uint4 *>(Ag + (size_t)b * P.H * P.W * P.CS + lane_off);
-            dst[img] = v;
-        }
+        for (int img = 0; img < BI; ++img) dst[img] = buf16(rs, voff + (uint32_t)img * a_img_bytes);
     };
-    auto b_store_task = [&](int row_first, int rr, int c, int jc, const uint4 (&src)[BI]) {
-        const int slot = (row_first + rr) % P.NR;
+    // 16-bit LDS unit of (staged pixel, column j): pixel stride J_WG+1 units; inside a pixel
+    // the 16-column group G sits at 16G and is rotated by G*rotmul.  Fragment reads
+    // (16 consecutive columns of one pixel) and staging writes (8 columns per lane,
+    // lanes running over column chunks then pixels) are then both free of bank conflicts.
+    auto b_store_task = [&](int slot, int c, int jc, const uint4 (&src)[BI]) {
         if constexpr (F32) {
             float *dst = lds_b + (size_t)(slot * P.BWc + c) * P.BSTR + jc * 4;
             *reinterpret_cast<uint4 *>(dst) = src[0];
@@ -231,37 +276,45 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrParams P)
             for (int q = 0; q < 8; ++q) { rows[q][0] = src[q].x; rows[q][1] = src[q].y; rows[q][2] = src[q].z; rows[q][3] = src[q].w; }
             uint4 cols[8];
             transpose_rows8<4>(rows, cols);
-            uint4 *dst = lds_b + (size_t)(slot * P.BWc + c) * P.BSTR + jc * 9;  // 9 units per 8 columns: bank spreading
+            const int G = jc >> 1;
+            uint4 *dst = lds_b + (size_t)(slot * P.BWc + c) * P.BSTR + 16 * G;
+            const int start = ((jc & 1) * 8 + G * rotmul) & 15;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) dst[e] = cols[e];
+            for (int e = 0; e < 8; ++e) dst[(start + e) & 15] = cols[e];
         }
     };
     // rows the step loads in steady state: [oy0*sh + NOLD, oy0*sh + NR)
     auto b_load = [&](const StepPos &sp) {
+        const __amdgpu_buffer_rsrc_t rs = rsrc_of(Ag, sp.bg, a_img_bytes);
         const int row_first = sp.oy0 * P.sh + P.NOLD;
+        const int xbase = sp.x0 * P.sw - P.pw;
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
-            if (b_dec[i] < 0) continue;
-            b_load_task(sp, row_first, b_dec[i] >> 22, (b_dec[i] >> 6) & 0xffff, b_dec[i] & 0x3f, rbv[i]);
+            if (b_rrc[i] < 0) continue;
+            b_load_task(rs, xbase, row_first, b_rrc[i] >> 16, b_rrc[i] & 0xffff, b_jc[i], rbv[i]);
         }
     };
     auto b_store = [&](const StepPos &sp) {
-        const int row_first = sp.oy0 * P.sh + P.NOLD;
+        const int rowmod = (sp.oy0 * P.sh + P.NOLD) % P.NR;
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
-            if (b_dec[i] < 0) continue;
-            b_store_task(row_first, b_dec[i] >> 22, (b_dec[i] >> 6) & 0xffff, b_dec[i] & 0x3f, rbv[i]);
+            if (b_rrc[i] < 0) continue;
+            int slot = rowmod + (b_rrc[i] >> 16);
+            slot = slot >= P.NR ? slot - P.NR : slot;
+            b_store_task(slot, b_rrc[i] & 0xffff, b_jc[i], rbv[i]);
         }
     };
     // rows [oy0*sh, oy0*sh + NOLD) that a step normally inherits from its predecessor
     auto b_fill_old = [&](const StepPos &sp) {
+        const __amdgpu_buffer_rsrc_t rs = rsrc_of(Ag, sp.bg, a_img_bytes);
         const int row_first = sp.oy0 * P.sh;
+        const int xbase = sp.x0 * P.sw - P.pw;
         const int ntask = P.NOLD * P.BWc * JC;
         for (int task = tid; task < ntask; task += kThreads) {
             const int jc = task % JC, c = (task / JC) % P.BWc, rr = task / (JC * P.BWc);
             uint4 tmp[BI];
-            b_load_task(sp, row_first, rr, c, jc, tmp);
-            b_store_task(row_first, rr, c, jc, tmp);
+            b_load_task(rs, xbase, row_first, rr, c, jc, tmp);
+            b_store_task((row_first + rr) % P.NR, c, jc, tmp);
         }
     };
 
@@ -286,8 +339,10 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrParams P)
     const int NXQ = P.CWp >> 2;          // k-steps per output row
     const int NKS = P.RB * NXQ;          // k-steps per step
     const int my_ks = (NKS - wk + P.WK - 1) / P.WK;
-    const int a_lane = g * P.ASTR + (wm * MT) * 16 + jl;
-    const int b_lane = F32 ? (g * P.sw * P.BSTR + wj * 16 + jl) : (g * P.sw * P.BSTR + wj * 18 + jl + (jl >> 3));
+    // fp32 dY tile is [m][slot] (row stride ASTR floats), 16-bit tile is [slot][m] (slot stride ASTR units)
+    const int a_lane = F32 ? (((wm * MT) * 16 + jl) * P.ASTR + g) : (g * P.ASTR + (wm * MT) * 16 + jl);
+    const int a_mt = F32 ? 16 * P.ASTR : 16;  // LDS units between the M tiles of a wave
+    const int b_lane = F32 ? (g * P.sw * P.BSTR + wj * 16 + jl) : (g * P.sw * P.BSTR + wj * 16 + ((jl + wj * rotmul) & 15));
     const int b_xq = 4 * P.sw * P.BSTR;  // LDS units between k-steps of a row
 
     struct Frags {
@@ -317,9 +372,10 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrParams P)
         }
     };
     auto load_frags = [&](Frags &f, const Cursor &c) {
-        const unit_t *pa = lds_a + (size_t)((c.rb * P.CWp + (c.xq << 2)) * P.ASTR) + a_lane;
+        const int p0 = c.rb * P.CWp + (c.xq << 2);  // first pixel slot of the k-step
+        const unit_t *pa = lds_a + (F32 ? p0 : p0 * P.ASTR) + a_lane;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) f.a[mt] = pa[mt * 16];
+        for (int mt = 0; mt < MT; ++mt) f.a[mt] = pa[mt * a_mt];
         const unit_t *pb = lds_b + (size_t)(c.xq * b_xq) + b_lane;
 #pragma unroll
         for (int o = 0; o < NOFF; ++o) f.b[o] = pb[c.brow[o]];
@@ -549,14 +605,17 @@ static void fill_geometry(CorrParams &P, int dtype, int RB, int CW)
         }
     P.NCHR = nch;
     if (f32) {
-        // strides chosen so that the four lane groups of a k-step hit different banks
-        P.ASTR = P.M_WG + (80 - P.M_WG % 64) % 64;
+        // dY tile [m][slot]: row stride = 4 mod 64 floats, so that the 16 rows x 4 slots of a
+        // fragment read fall into 64 different banks; A tile [col][j]: column stride = 16 mod 64
+        const int ps = RB * P.CWp;
+        P.ASTR = ps + (68 - ps % 64) % 64;
         P.BSTR = P.J_WG + (80 - P.J_WG % 64) % 64;
+        P.a_units = round_up(P.M_WG * P.ASTR, 4);
     } else {
         P.ASTR = P.M_WG + 1;
-        P.BSTR = P.J_WG / 8 * 9;
+        P.BSTR = P.J_WG + 1;
+        P.a_units = RB * P.CWp * P.ASTR;
     }
-    P.a_units = round_up(RB * P.CWp * P.ASTR, 4);
     P.b_units = P.NR * P.BWc * P.BSTR;
     P.NS = P.NBG * P.NSTRIP * P.NBAND;
 }
@@ -597,6 +656,10 @@ bool plan_corr(CorrParams &P, int dtype, int B, int C_out, int H, int W, int kH,
     P.K2 = kH * kW;
     P.NOG = ceil_div(P.K2, P.K2 == 1 ? 1 : kMaxOff);
     P.dy_vec = (dy_aligned && ((long long)P.Ho * P.Wo) % EPV == 0) ? 1 : 0;
+
+    // the kernel addresses a batch group (BI images) with 32-bit byte offsets
+    const long long es = f32 ? 4 : 2;
+    if ((long long)BI * C_out * P.Ho * P.Wo * es > (1LL << 30) || (long long)BI * H * W * CS * es > (1LL << 30)) return false;
 
     const int MT = corr_mt(C_out);
     const int nwm = ceil_div(C_out, 16 * MT), nwj = CS / 16;
