@@ -77,7 +77,7 @@ __device__ inline StepPos next_step(const CorrParams &P, StepPos s)
 // last group with fewer offsets recomputes its first offset in the spare slots
 // and does not write them.
 template <int DT, int MT, int NA, int NB, int NOFF>
-__global__ __launch_bounds__(kThreads) void corr_kernel(const CorrParams P)
+__global__ __launch_bounds__(kThreads, (DT == XCONV_F32 ? 2 : 1)) void corr_kernel(const CorrParams P)
 {
     constexpr bool F32 = (DT == XCONV_F32);
     constexpr int BI = F32 ? 1 : 8;   // images per LDS unit
@@ -628,7 +628,8 @@ static size_t lds_bytes_of(const CorrParams &P, int dtype, int MT)
     return stage > red ? stage : red;
 }
 
-static int corr_mt(int C_out) { return C_out > 16 ? 4 : 1; }
+// output-channel tiles (of 16) per wave: fp32 keeps the accumulator file small enough for two workgroups per CU
+static int corr_mt(int dtype, int C_out) { return C_out <= 16 ? 1 : (dtype == XCONV_F32 ? 2 : 4); }
 
 static bool geometry_fits(const CorrParams &P, int dtype, int MT)
 {
@@ -661,7 +662,7 @@ bool plan_corr(CorrParams &P, int dtype, int B, int C_out, int H, int W, int kH,
     const long long es = f32 ? 4 : 2;
     if ((long long)BI * C_out * P.Ho * P.Wo * es > (1LL << 30) || (long long)BI * H * W * CS * es > (1LL << 30)) return false;
 
-    const int MT = corr_mt(C_out);
+    const int MT = corr_mt(dtype, C_out);
     const int nwm = ceil_div(C_out, 16 * MT), nwj = CS / 16;
     // waves along the A columns share dY through LDS, so prefer them; WJ must divide the column tiles
     int WJ = env_int("XCONV_CORR_WJ", 0);
@@ -733,7 +734,7 @@ bool plan_corr(CorrParams &P, int dtype, int B, int C_out, int H, int W, int kH,
     return true;
 }
 
-size_t corr_lds_bytes(int dtype, const CorrParams &P) { return lds_bytes_of(P, dtype, corr_mt(P.C_out)); }
+size_t corr_lds_bytes(int dtype, const CorrParams &P) { return lds_bytes_of(P, dtype, corr_mt(dtype, P.C_out)); }
 
 size_t corr_partial_bytes(const CorrParams &P)
 {
@@ -775,10 +776,10 @@ template <int DT, int MT> static hipError_t launch_corr_16(const CorrParams &P, 
 
 hipError_t launch_corr(int dtype, const CorrParams &P, hipStream_t st)
 {
-    const int MT = corr_mt(P.C_out);
+    const int MT = corr_mt(dtype, P.C_out);
     const size_t lds = lds_bytes_of(P, dtype, MT);
     if (dtype == XCONV_F32) {
-        if (MT == 4) return launch_corr_noff<XCONV_F32, 4, 8, 4>(P, lds, st);
+        if (MT == 2) return launch_corr_noff<XCONV_F32, 2, 8, 4>(P, lds, st);
         return launch_corr_noff<XCONV_F32, 1, 8, 4>(P, lds, st);
     }
     if (dtype == XCONV_BF16) {
