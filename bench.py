@@ -26,7 +26,10 @@ PEAK_MFMA_TFLOPS = {"f32": 157.3, "bf16": 2500.0, "f16": 2500.0}
 # HBM traffic per launch of the dominant kernel from rocprofv3 --pmc runs
 # (FETCH_SIZE, WRITE_SIZE scaled by a copy kernel of known size; see
 # profiles/).  bytes, or None where not measured yet.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    ("C2", "corr_kernel"): 71.2e6, ("C2", "probe_kernel"): 42.1e6,      # profiles/xconv_kernels_C2.txt
+    ("C5", "corr_kernel"): 209.2e6, ("C5", "probe_kernel"): 154.8e6,    # profiles/xconv_kernels_C5.txt
+}
 
 
 def elem_bytes(dtype):
@@ -179,6 +182,8 @@ def main():
     ap.add_argument("--all", action="store_true", help="also measure the other benchmark layers (extra field per_config)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--no-exact", action="store_true", help="skip timing xconv_dw_exact (for clean per-kernel profiles)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain device copy of 256 MiB ten times (reference reading for the FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the path has no multi-GPU part in this build (got --gpus %d)" % args.gpus, file=sys.stderr)
@@ -192,6 +197,16 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         return 2
     dev = "cuda:0"
+    if args.copy_calibration:
+        src = torch.full((64 * 2 ** 20,), 1.0, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        flush = torch.empty((128 * 2 ** 20,), dtype=torch.float32, device=dev)
+        for _ in range(10):
+            flush.fill_(0.0)          # push src/dst out of the Infinity Cache between copies
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": dst.numel() * 4, "copies": 10}))
+        return 0
     cfg = synth.CONFIGS[args.config]
     res, L = measure_config(cfg, args.steps, args.warmup, dev, with_exact=not args.no_exact)
     alg = algorithmic(cfg)
