@@ -77,7 +77,8 @@ size_t xconv_xt_bytes(const xconv_desc *desc);
 
 /* Bytes of device scratch the given op (xconv_op) needs in `ws_dev`.  The
  * scratch holds Z when it is regenerated from the seed, the split partial sums
- * of the correlation and, for the exact gradient, a channels-last copy of X.
+ * of the correlation, a repacked copy of dY when H'*W' is not a whole number of
+ * 16-byte vectors and, for the exact gradient, a channels-last copy of X.
  * 0 for an invalid desc. */
 size_t xconv_workspace_bytes(const xconv_desc *desc, int op);
 
@@ -100,7 +101,7 @@ xconv_status xconv_probe_fwd(const xconv_desc *desc, const void *X_dev, void *Xt
                              const float *Z_dev, void *ws_dev, size_t ws_bytes, void *stream);
 
 /* Backward estimate (Alg. 1 bwd steps 1-4).  dY_dev: [B,C_out,H',W'] in
- * desc->dtype.  Xt_dev: as written by xconv_probe_fwd for the same desc.
+ * desc->dtype, 16-byte aligned.  Xt_dev: as written by xconv_probe_fwd for the same desc.
  * Z_dev: as above (must be the Z used in the forward).  dW_dev:
  * [C_out,C_in,kH,kW] fp32, overwritten.  The result is deterministic for given
  * inputs (fixed-order two-pass reduction, no atomics). */
@@ -110,7 +111,7 @@ xconv_status xconv_dw_estimate(const xconv_desc *desc, const void *dY_dev, const
 
 /* Exact weight gradient (Eq. (2)/(5)), for comparison with the estimate: same
  * correlation kernel with the C_in real channels in place of the r probed
- * ones.  X_dev: [B,C_in,H,W]; dW_dev: [C_out,C_in,kH,kW] fp32, overwritten.
+ * ones.  X_dev: [B,C_in,H,W]; dY_dev 16-byte aligned; dW_dev: [C_out,C_in,kH,kW] fp32, overwritten.
  * desc->r, probe and seed are ignored (r must still be >= 1). */
 xconv_status xconv_dw_exact(const xconv_desc *desc, const void *dY_dev, const void *X_dev,
                             float *dW_dev, void *ws_dev, size_t ws_bytes, void *stream);

@@ -12,7 +12,7 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libxconv.so")
+LIB_PATH = os.environ.get("XCONV_LIB", os.path.join(_HERE, "libxconv.so"))   # override: A/B runs of two builds
 
 XCONV_OK, XCONV_EINVAL, XCONV_EUNSUPPORTED, XCONV_EWORKSPACE, XCONV_EHIP = range(5)
 XCONV_F32, XCONV_BF16, XCONV_F16 = 0, 1, 2

@@ -22,7 +22,8 @@ enum KernelId {
     K_TO_NHWC = 5,
     K_UNPACK = 6,
     K_EXPAND = 7,
-    K_COUNT = 8
+    K_REPACK = 8,
+    K_COUNT = 9
 };
 
 __host__ __device__ inline int round_up(int a, int b) { return (a + b - 1) / b * b; }
@@ -105,7 +106,7 @@ struct CorrParams {
     int S, NS;         // K-splits and total steps
     int K2, NOG;       // kernel offsets and offset groups of <= 9
     int MP, JP;        // padded extents of the partial buffer
-    int dy_vec;        // 1: dY planes allow aligned 16-byte loads
+    int dy_plane;      // elements between consecutive (image, channel) planes of dY as the kernel reads it (whole 16-byte vectors)
     int a_units, b_units;  // LDS units of the two staging tiles
 };
 

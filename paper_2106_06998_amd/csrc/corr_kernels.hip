@@ -43,10 +43,41 @@ namespace xc {
 
 constexpr int kMaxOff = 9;
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
+// outstanding global load of the wave (its release fence drains vmcnt), which would expose
+// the latency of the prefetch issued before the barrier; the kernel exchanges data through
+// LDS only, so waiting for the LDS counter is sufficient.
+// Compiler-only fence.  The prefetch loads of the next step have no use until the following
+// loop iteration, so the optimiser would otherwise sink them below the MFMA loop (shorter
+// live ranges) and expose their whole latency; a memory clobber keeps them where they are
+// issued without making anything wait.
+__device__ inline void pin_issued_loads()
+{
+    asm volatile("" ::: "memory");
+}
+
+__device__ inline void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // Position of a step: batch group, first output row, first output column.
 struct StepPos {
     int bg, band, strip, oy0, x0;
 };
+
+// Step positions are the same for every lane; readfirstlane says so to the compiler, which
+// otherwise may treat values that went through loop-carried structs as divergent (vector ALU
+// index math, and a lane-by-lane loop around every buffer load whose resource depends on them).
+__device__ inline StepPos uniform_pos(StepPos s)
+{
+    s.bg = __builtin_amdgcn_readfirstlane(s.bg);
+    s.band = __builtin_amdgcn_readfirstlane(s.band);
+    s.strip = __builtin_amdgcn_readfirstlane(s.strip);
+    s.oy0 = __builtin_amdgcn_readfirstlane(s.oy0);
+    s.x0 = __builtin_amdgcn_readfirstlane(s.x0);
+    return s;
+}
 
 __device__ inline StepPos decode_step(const CorrParams &P, int t)
 {
@@ -57,7 +88,7 @@ __device__ inline StepPos decode_step(const CorrParams &P, int t)
     s.bg = t / P.NSTRIP;
     s.oy0 = s.band * P.RB;
     s.x0 = s.strip * P.CW;
-    return s;
+    return uniform_pos(s);
 }
 __device__ inline StepPos next_step(const CorrParams &P, StepPos s)
 {
@@ -70,14 +101,14 @@ __device__ inline StepPos next_step(const CorrParams &P, StepPos s)
     }
     s.oy0 = s.band * P.RB;
     s.x0 = s.strip * P.CW;
-    return s;
+    return uniform_pos(s);
 }
 
 // NOFF: kernel offsets a workgroup accumulates (9, or 1 for 1x1 kernels).  A
 // last group with fewer offsets recomputes its first offset in the spare slots
 // and does not write them.
 template <int DT, int MT, int NA, int NB, int NOFF>
-__global__ __launch_bounds__(kThreads, (DT == XCONV_F32 ? 2 : 1)) void corr_kernel(const CorrParams P)
+__global__ __launch_bounds__(kThreads, (MT <= 2 ? 2 : 1)) void corr_kernel(const CorrParams P)
 {
     constexpr bool F32 = (DT == XCONV_F32);
     constexpr int BI = F32 ? 1 : 8;   // images per LDS unit
@@ -86,8 +117,8 @@ __global__ __launch_bounds__(kThreads, (DT == XCONV_F32 ? 2 : 1)) void corr_kern
     using elem_t = typename std::conditional<F32, float, uint16_t>::type;
 
     extern __shared__ uint4 lds_raw[];
-    unit_t *lds_a = reinterpret_cast<unit_t *>(lds_raw);
-    unit_t *lds_b = lds_a + P.a_units;
+    unit_t *lds_a0 = reinterpret_cast<unit_t *>(lds_raw);          // dY tile
+    unit_t *lds_b = lds_a0 + P.a_units;                            // ring of A rows
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the k-step bookkeeping scalar
@@ -100,7 +131,6 @@ __global__ __launch_bounds__(kThreads, (DT == XCONV_F32 ? 2 : 1)) void corr_kern
     const int o_first = blockIdx.z * NOFF;
     const int noff = (P.K2 - o_first) < NOFF ? (P.K2 - o_first) : NOFF;
 
-    const int HoWo = P.Ho * P.Wo;
     const elem_t *dY = static_cast<const elem_t *>(P.dY);
     const elem_t *Ag = static_cast<const elem_t *>(P.A);
 
@@ -115,13 +145,17 @@ __global__ __launch_bounds__(kThreads, (DT == XCONV_F32 ? 2 : 1)) void corr_kern
     constexpr uint32_t ES = sizeof(elem_t);
     constexpr uint32_t kOOR = 0x80000000u;  // beyond any resource: the plan keeps a batch group within 2^30 bytes, and no offset added to kOOR wraps
     constexpr int LOG_EPV = F32 ? 2 : 3;
-    const uint32_t dy_img_bytes = (uint32_t)P.C_out * (uint32_t)HoWo * ES;
+    const uint32_t dy_img_bytes = (uint32_t)P.C_out * (uint32_t)P.dy_plane * ES;  // planes padded to whole 16-byte vectors
     const uint32_t a_img_bytes = (uint32_t)P.H * (uint32_t)P.W * (uint32_t)P.CS * ES;
 
     // dY task: (rb, ml, cc) = output row in the band, channel in the tile, vector chunk in the row
     const int ntask_a = P.RB * P.M_WG * P.NCHR;
+    // Threads without a task get an encoding that fails every predicate (chunk 255 / column
+    // 65535 are never real) and an out-of-range load offset, so that the staging code below is
+    // free of divergent early-outs: waits for the prefetched registers then sit in
+    // unconditional code, where the compiler can count outstanding loads exactly.
     uint32_t a_goff[NA];   // byte offset inside an image without the row part, or kOOR
-    int a_rbcc[NA];        // rb << 8 | cc, or -1 for no task
+    int a_rbcc[NA];        // rb << 8 | cc
     int a_lds[NA];         // LDS unit of (rb, ml) at slot 0
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
@@ -130,15 +164,15 @@ __global__ __launch_bounds__(kThreads, (DT == XCONV_F32 ? 2 : 1)) void corr_kern
         const int ml = (task / P.NCHR) % P.M_WG;
         const int rb = task / (P.NCHR * P.M_WG);
         const bool has = task < ntask_a;
-        a_rbcc[i] = has ? ((rb << 8) | cc) : -1;
-        a_goff[i] = (has && m0 + ml < P.C_out) ? ((uint32_t)(m0 + ml) * (uint32_t)HoWo + (uint32_t)cc * EPV) * ES : kOOR;
-        a_lds[i] = F32 ? (ml * P.ASTR + rb * P.CWp) : (rb * P.CWp * P.ASTR + ml);
+        a_rbcc[i] = has ? ((rb << 8) | cc) : 255;
+        a_goff[i] = (has && m0 + ml < P.C_out) ? ((uint32_t)(m0 + ml) * (uint32_t)P.dy_plane + (uint32_t)cc * EPV) * ES : kOOR;
+        a_lds[i] = has ? (F32 ? (ml * P.ASTR + rb * P.CWp) : (rb * P.CWp * P.ASTR + ml)) : 0;
     }
     // A task: (rr, c, jc) = row among the rows to load, staged column, vector of EPV channels
     const int JC = P.J_WG / EPV;
     const int ntask_b = P.NNEW * P.BWc * JC;
     const int rotmul = 8 / (P.J_WG >> 4);  // 16-bit layout: rotation of each 16-column group (see b_unit)
-    int b_rrc[NB];         // rr << 16 | c, or -1
+    int b_rrc[NB];         // rr << 16 | c
     int b_jc[NB];
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
@@ -146,16 +180,23 @@ __global__ __launch_bounds__(kThreads, (DT == XCONV_F32 ? 2 : 1)) void corr_kern
         const int jc = task % JC;
         const int c = (task / JC) % P.BWc;
         const int rr = task / (JC * P.BWc);
-        b_rrc[i] = (task < ntask_b) ? ((rr << 16) | c) : -1;
-        b_jc[i] = jc;
+        b_rrc[i] = (task < ntask_b) ? ((rr << 16) | c) : 0xffff;
+        b_jc[i] = (task < ntask_b) ? jc : 0;
     }
 
     uint4 ra[NA][BI];
     uint4 rbv[NB][BI];
 
-    auto rsrc_of = [&](const elem_t *base, int bg, uint32_t img_bytes) {
+    // `live` false (the step does not exist): a resource of size zero, every load reads as zero.
+    // Prefetches are issued unconditionally with such a resource instead of being skipped by a
+    // branch, which would leave a merge of "loaded" and "old" register values for the compiler
+    // to copy (and to wait for) right after the loads are issued.
+    auto rsrc_of = [&](const elem_t *base, int bg, uint32_t img_bytes, bool live) {
+        bg = __builtin_amdgcn_readfirstlane(bg);
         int left = P.B - bg * BI;
         left = left < BI ? left : BI;
+        left = (live && left > 0) ? left : 0;
+        left = __builtin_amdgcn_readfirstlane(left);
         return __builtin_amdgcn_make_buffer_rsrc(const_cast<elem_t *>(base + (size_t)bg * BI * (img_bytes / ES)), 0,
                                                  (uint32_t)left * img_bytes, 0x00020000);
     };
@@ -166,60 +207,31 @@ __global__ __launch_bounds__(kThreads, (DT == XCONV_F32 ? 2 : 1)) void corr_kern
     };
 
     // ---- dY: global -> registers ----------------------------------------------
-    auto a_load = [&](const StepPos &sp) {
+    auto a_load = [&](const StepPos &sp, bool live) {
         const int fs = sp.oy0 * P.Wo + sp.x0;  // flat index of the step's first pixel
-        if (P.dy_vec) {
-            const __amdgpu_buffer_rsrc_t rs = rsrc_of(dY, sp.bg, dy_img_bytes);
-            const int rows_left = P.Ho - sp.oy0;
+        const __amdgpu_buffer_rsrc_t rs = rsrc_of(dY, sp.bg, dy_img_bytes, live);
+        const int rows_left = P.Ho - sp.oy0;
 #pragma unroll
-            for (int i = 0; i < NA; ++i) {
-                if (a_rbcc[i] < 0) continue;
-                const int rb = a_rbcc[i] >> 8;
-                const uint32_t f0 = (uint32_t)(fs + rb * P.Wo);
-                uint32_t voff = a_goff[i] + ((f0 >> LOG_EPV) << 4);
-                voff = (rb < rows_left) ? voff : kOOR;
+        for (int i = 0; i < NA; ++i) {
+            const int rb = a_rbcc[i] >> 8;
+            const uint32_t f0 = (uint32_t)(fs + rb * P.Wo);
+            uint32_t voff = a_goff[i] + ((f0 >> LOG_EPV) << 4);
+            voff = (rb < rows_left) ? voff : kOOR;
 #pragma unroll
-                for (int img = 0; img < BI; ++img) ra[i][img] = buf16(rs, voff + (uint32_t)img * dy_img_bytes);
-            }
-        } else {
-            // planes are not 16-byte aligned: element loads with explicit bounds
-#pragma unroll
-            for (int i = 0; i < NA; ++i) {
-                if (a_rbcc[i] < 0) continue;
-                const int rb = a_rbcc[i] >> 8, cc = a_rbcc[i] & 0xff;
-                const int oy = sp.oy0 + rb;
-                const int chunk = ((fs + rb * P.Wo) >> LOG_EPV) + cc;
-                const bool ok = (oy < P.Ho) && (a_goff[i] != kOOR);
-#pragma unroll
-                for (int img = 0; img < BI; ++img) {
-                    const int b = sp.bg * BI + img;
-                    uint32_t w[4] = {0u, 0u, 0u, 0u};
-                    if (ok && b < P.B) {
-                        const elem_t *src = dY + (size_t)b * P.C_out * HoWo + (a_goff[i] / ES - (uint32_t)cc * EPV) + (size_t)chunk * EPV;
-#pragma unroll
-                        for (int e = 0; e < EPV; ++e) {
-                            if (chunk * EPV + e < HoWo) {
-                                if constexpr (F32) w[e] = __float_as_uint(src[e]);
-                                else w[e >> 1] |= (uint32_t)src[e] << (16 * (e & 1));
-                            }
-                        }
-                    }
-                    ra[i][img] = uint4{w[0], w[1], w[2], w[3]};
-                }
-            }
+            for (int img = 0; img < BI; ++img) ra[i][img] = buf16(rs, voff + (uint32_t)img * dy_img_bytes);
         }
     };
 
     // ---- dY: registers -> LDS.  16-bit: units [slot][m]; fp32: floats [m][slot].
-    auto a_store = [&](const StepPos &sp) {
+    auto a_store = [&](const StepPos &sp, unit_t *lds_a) {
         const int cw_eff = (P.Wo - sp.x0) < P.CW ? (P.Wo - sp.x0) : P.CW;
         const int fs = sp.oy0 * P.Wo + sp.x0;
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
-            if (a_rbcc[i] < 0) continue;
             const int rb = a_rbcc[i] >> 8, cc = a_rbcc[i] & 0xff;
             const int xs0 = cc * EPV - ((fs + rb * P.Wo) & (EPV - 1));  // slot of the chunk's first pixel (may be negative)
             if constexpr (F32) {
+                asm volatile("" : "+v"(ra[i][0].x), "+v"(ra[i][0].y), "+v"(ra[i][0].z), "+v"(ra[i][0].w));  // data arrives here, not inside a branch
                 float *dst = lds_a + a_lds[i];
                 if (xs0 >= 0 && xs0 + 4 <= cw_eff && (xs0 & 3) == 0) {
                     *reinterpret_cast<uint4 *>(dst + xs0) = ra[i][0];
@@ -268,8 +280,10 @@ __global__ __launch_bounds__(kThreads, (DT == XCONV_F32 ? 2 : 1)) void corr_kern
     // lanes running over column chunks then pixels) are then both free of bank conflicts.
     auto b_store_task = [&](int slot, int c, int jc, const uint4 (&src)[BI]) {
         if constexpr (F32) {
+            uint4 v = src[0];
+            asm volatile("" : "+v"(v.x), "+v"(v.y), "+v"(v.z), "+v"(v.w));  // data arrives here, not inside a branch
             float *dst = lds_b + (size_t)(slot * P.BWc + c) * P.BSTR + jc * 4;
-            *reinterpret_cast<uint4 *>(dst) = src[0];
+            if (c < P.BWc) *reinterpret_cast<uint4 *>(dst) = v;
         } else {
             uint32_t rows[8][4];
 #pragma unroll
@@ -279,26 +293,24 @@ __global__ __launch_bounds__(kThreads, (DT == XCONV_F32 ? 2 : 1)) void corr_kern
             const int G = jc >> 1;
             uint4 *dst = lds_b + (size_t)(slot * P.BWc + c) * P.BSTR + 16 * G;
             const int start = ((jc & 1) * 8 + G * rotmul) & 15;
+            if (c < P.BWc) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) dst[(start + e) & 15] = cols[e];
+                for (int e = 0; e < 8; ++e) dst[(start + e) & 15] = cols[e];
+            }
         }
     };
     // rows the step loads in steady state: [oy0*sh + NOLD, oy0*sh + NR)
-    auto b_load = [&](const StepPos &sp) {
-        const __amdgpu_buffer_rsrc_t rs = rsrc_of(Ag, sp.bg, a_img_bytes);
+    auto b_load = [&](const StepPos &sp, bool live) {
+        const __amdgpu_buffer_rsrc_t rs = rsrc_of(Ag, sp.bg, a_img_bytes, live);
         const int row_first = sp.oy0 * P.sh + P.NOLD;
         const int xbase = sp.x0 * P.sw - P.pw;
 #pragma unroll
-        for (int i = 0; i < NB; ++i) {
-            if (b_rrc[i] < 0) continue;
-            b_load_task(rs, xbase, row_first, b_rrc[i] >> 16, b_rrc[i] & 0xffff, b_jc[i], rbv[i]);
-        }
+        for (int i = 0; i < NB; ++i) b_load_task(rs, xbase, row_first, b_rrc[i] >> 16, b_rrc[i] & 0xffff, b_jc[i], rbv[i]);
     };
     auto b_store = [&](const StepPos &sp) {
         const int rowmod = (sp.oy0 * P.sh + P.NOLD) % P.NR;
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
-            if (b_rrc[i] < 0) continue;
             int slot = rowmod + (b_rrc[i] >> 16);
             slot = slot >= P.NR ? slot - P.NR : slot;
             b_store_task(slot, b_rrc[i] & 0xffff, b_jc[i], rbv[i]);
@@ -306,7 +318,7 @@ __global__ __launch_bounds__(kThreads, (DT == XCONV_F32 ? 2 : 1)) void corr_kern
     };
     // rows [oy0*sh, oy0*sh + NOLD) that a step normally inherits from its predecessor
     auto b_fill_old = [&](const StepPos &sp) {
-        const __amdgpu_buffer_rsrc_t rs = rsrc_of(Ag, sp.bg, a_img_bytes);
+        const __amdgpu_buffer_rsrc_t rs = rsrc_of(Ag, sp.bg, a_img_bytes, true);
         const int row_first = sp.oy0 * P.sh;
         const int xbase = sp.x0 * P.sw - P.pw;
         const int ntask = P.NOLD * P.BWc * JC;
@@ -371,7 +383,7 @@ __global__ __launch_bounds__(kThreads, (DT == XCONV_F32 ? 2 : 1)) void corr_kern
             set_rows(c);
         }
     };
-    auto load_frags = [&](Frags &f, const Cursor &c) {
+    auto load_frags = [&](Frags &f, const Cursor &c, const unit_t *lds_a) {
         const int p0 = c.rb * P.CWp + (c.xq << 2);  // first pixel slot of the k-step
         const unit_t *pa = lds_a + (F32 ? p0 : p0 * P.ASTR) + a_lane;
 #pragma unroll
@@ -390,31 +402,13 @@ __global__ __launch_bounds__(kThreads, (DT == XCONV_F32 ? 2 : 1)) void corr_kern
             }
     };
 
-    StepPos sp = decode_step(P, t_begin);
-    if (t_begin < t_end) {
-        a_load(sp);
-        b_load(sp);
-    }
-    int prev_bg = -1, prev_x0 = -1, prev_oy0 = -1;
-    for (int step = t_begin; step < t_end; ++step) {
-        __syncthreads();  // everyone is done reading the tiles of the previous step
-        const bool fresh = !(sp.bg == prev_bg && sp.x0 == prev_x0 && sp.oy0 == prev_oy0 + P.RB);
-        if (fresh && P.NOLD > 0) b_fill_old(sp);
-        a_store(sp);
-        b_store(sp);
-        prev_bg = sp.bg; prev_x0 = sp.x0; prev_oy0 = sp.oy0;
-        __syncthreads();
-        const StepPos spn = next_step(P, sp);
-        if (step + 1 < t_end) {
-            a_load(spn);
-            b_load(spn);
-        }
-
-        // double-buffered fragments: the LDS reads of k-step i+1 are in flight during the MFMAs of k-step i
+    // ---- main loop ---------------------------------------------------------------
+    // MFMA loop of one staged step
+    auto compute_step = [&](const StepPos &spc, const unit_t *lds_a) {
         Cursor cur;
         cur.rb = 0;
         cur.xq = wk;
-        cur.rowmod = (sp.oy0 * P.sh) % P.NR;
+        cur.rowmod = (spc.oy0 * P.sh) % P.NR;
         set_rows(cur);
         while (cur.xq >= NXQ) {  // WK > NXQ: the first k-step of this wave is in a later row
             cur.xq -= NXQ;
@@ -423,42 +417,69 @@ __global__ __launch_bounds__(kThreads, (DT == XCONV_F32 ? 2 : 1)) void corr_kern
             while (cur.rowmod >= P.NR) cur.rowmod -= P.NR;
             set_rows(cur);
         }
+        // double-buffered fragments: the LDS reads of k-step i+1 are in flight during the MFMAs of k-step i
         Frags f0, f1;
         int left = my_ks;
         if (left > 0) {
-            load_frags(f0, cur);
+            load_frags(f0, cur, lds_a);
             advance(cur);
         }
         while (left > 0) {
             if (left > 1) {
-                load_frags(f1, cur);
+                load_frags(f1, cur, lds_a);
                 advance(cur);
             }
             mfma_frags(f0);
             if (--left == 0) break;
             if (left > 1) {
-                load_frags(f0, cur);
+                load_frags(f0, cur, lds_a);
                 advance(cur);
             }
             mfma_frags(f1);
             --left;
         }
+    };
+    auto contiguous = [&](const StepPos &a, const StepPos &b) { return b.bg == a.bg && b.x0 == a.x0 && b.oy0 == a.oy0 + P.RB; };
+
+    StepPos sp = decode_step(P, t_begin);
+    // Stage step t between two barriers, prefetch t+1 into registers, then run the MFMA loop
+    // of t while those loads are in flight.  The prefetch is issued unconditionally (a step that
+    // does not exist reads zeros through an empty resource): a branch around it would leave a
+    // merge of loaded and old register values that the compiler resolves with copies, and so
+    // with a wait for the loads right after issuing them.
+    a_load(sp, t_begin < t_end);
+    b_load(sp, t_begin < t_end);
+    StepPos prev = sp;
+    prev.bg = -1;
+    for (int step = t_begin; step < t_end; ++step) {
+        lds_barrier();  // everyone is done reading the tiles of the previous step
+        if (P.NOLD > 0 && !contiguous(prev, sp)) b_fill_old(sp);
+        a_store(sp, lds_a0);
+        b_store(sp);
+        lds_barrier();
+        const StepPos spn = next_step(P, sp);
+        a_load(spn, step + 1 < t_end);
+        b_load(spn, step + 1 < t_end);
+        pin_issued_loads();
+        compute_step(sp, lds_a0);
+        prev = sp;
         sp = spn;
     }
+    lds_barrier();
 
     // ---- reduce the WK k-split waves through LDS, then write the partial tile --
     // One buffer per (wm, wj) group; waves wk = 1..WK-1 hand their tiles to wave
     // wk = 0 one after the other, so the summation order is fixed.
     f32x4 *red = reinterpret_cast<f32x4 *>(lds_raw) + ((size_t)(wm + P.WM * wj) * MT * NOFF) * 64 + lane;
     for (int k = 1; k < P.WK; ++k) {
-        __syncthreads();
+        lds_barrier();
         if (wk == k) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                 for (int o = 0; o < NOFF; ++o) red[(mt * NOFF + o) * 64] = acc[mt][o];
         }
-        __syncthreads();
+        lds_barrier();
         if (wk == 0) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
@@ -569,6 +590,33 @@ __global__ __launch_bounds__(kThreads) void untile_kernel(const float *__restric
     dW[i] = T[((size_t)o * JP + n) * MP + m];
 }
 
+// dY planes whose size is not a whole number of 16-byte vectors are copied once into planes
+// of pitch `pitch` elements (zero tail), so that the correlation kernel only ever issues
+// aligned vector loads.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void repack_planes_kernel(const T *__restrict__ src, T *__restrict__ dst, long long nplanes,
+                                                                 int n, int pitch)
+{
+    const long long i = (long long)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= nplanes * pitch) return;
+    const long long pl = i / pitch;
+    const int e = (int)(i - pl * pitch);
+    dst[i] = e < n ? src[pl * n + e] : T(0);
+}
+
+hipError_t launch_repack_planes(int dtype, const void *src, void *dst, long long nplanes, int n, int pitch, hipStream_t st)
+{
+    const long long total = nplanes * pitch;
+    dim3 grid((unsigned)((total + kThreads - 1) / kThreads));
+    if (dtype == XCONV_F32)
+        hipLaunchKernelGGL(repack_planes_kernel<float>, grid, dim3(kThreads), 0, st, static_cast<const float *>(src),
+                           static_cast<float *>(dst), nplanes, n, pitch);
+    else
+        hipLaunchKernelGGL(repack_planes_kernel<uint16_t>, grid, dim3(kThreads), 0, st, static_cast<const uint16_t *>(src),
+                           static_cast<uint16_t *>(dst), nplanes, n, pitch);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------
 // host: launch plan
 // ---------------------------------------------------------------------------
@@ -629,7 +677,10 @@ static size_t lds_bytes_of(const CorrParams &P, int dtype, int MT)
 }
 
 // output-channel tiles (of 16) per wave: fp32 keeps the accumulator file small enough for two workgroups per CU
-static int corr_mt(int dtype, int C_out) { return C_out <= 16 ? 1 : (dtype == XCONV_F32 ? 2 : 4); }
+static int corr_mt(int dtype, int C_out)
+{
+    return C_out <= 16 ? 1 : (dtype == XCONV_F32 ? 2 : 4);
+}
 
 static bool geometry_fits(const CorrParams &P, int dtype, int MT)
 {
@@ -656,11 +707,12 @@ bool plan_corr(CorrParams &P, int dtype, int B, int C_out, int H, int W, int kH,
     P.NBG = ceil_div(B, BI);
     P.K2 = kH * kW;
     P.NOG = ceil_div(P.K2, P.K2 == 1 ? 1 : kMaxOff);
-    P.dy_vec = (dy_aligned && ((long long)P.Ho * P.Wo) % EPV == 0) ? 1 : 0;
+    P.dy_plane = round_up(P.Ho * P.Wo, EPV);  // the kernel reads dY planes of this pitch (repacked by the caller if needed)
+    (void)dy_aligned;
 
     // the kernel addresses a batch group (BI images) with 32-bit byte offsets
     const long long es = f32 ? 4 : 2;
-    if ((long long)BI * C_out * P.Ho * P.Wo * es > (1LL << 30) || (long long)BI * H * W * CS * es > (1LL << 30)) return false;
+    if ((long long)BI * C_out * round_up(P.Ho * P.Wo, EPV) * es > (1LL << 30) || (long long)BI * H * W * CS * es > (1LL << 30)) return false;
 
     const int MT = corr_mt(dtype, C_out);
     const int nwm = ceil_div(C_out, 16 * MT), nwj = CS / 16;

@@ -24,6 +24,7 @@ bool plan_corr(CorrParams &P, int dtype, int B, int C_out, int H, int W, int kH,
 size_t corr_partial_bytes(const CorrParams &P);
 size_t corr_lds_bytes(int dtype, const CorrParams &P);
 hipError_t launch_corr(int dtype, const CorrParams &P, hipStream_t st);
+hipError_t launch_repack_planes(int dtype, const void *src, void *dst, long long nplanes, int n, int pitch, hipStream_t st);
 // T[o,j,m] = sum_s part[s,o,j,m]; T lives behind the S partial buffers
 hipError_t launch_reduce(const CorrParams &P, hipStream_t st);
 // dW[m,n,o] = (1/r) * sum_j Z[n,j] * T[o,j,m]   (Z != nullptr)

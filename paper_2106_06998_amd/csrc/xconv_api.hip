@@ -100,6 +100,19 @@ bool get_plan(CorrParams &P, int dtype, int B, int C_out, int H, int W, int kH, 
 
 size_t z_bytes(const xconv_desc *d) { return align_up((size_t)d->C_in * d->r * sizeof(float), 256); }
 
+// dY planes that are not a whole number of 16-byte vectors are repacked into scratch
+int dy_pitch(const xconv_desc *d)
+{
+    const int n = out_extent(d->H, d->kH, d->stride_h, d->pad_h) * out_extent(d->W, d->kW, d->stride_w, d->pad_w);
+    return round_up(n, d->dtype == XCONV_F32 ? 4 : 8);
+}
+size_t dy_repack_bytes(const xconv_desc *d)
+{
+    const int n = out_extent(d->H, d->kH, d->stride_h, d->pad_h) * out_extent(d->W, d->kW, d->stride_w, d->pad_w);
+    if (dy_pitch(d) == n) return 0;
+    return align_up((size_t)d->B * d->C_out * dy_pitch(d) * elem_bytes(d->dtype), 256);
+}
+
 }  // namespace
 
 extern "C" {
@@ -137,13 +150,13 @@ size_t xconv_workspace_bytes(const xconv_desc *d, int op)
         if (!get_plan(P, d->dtype, d->B, d->C_out, d->H, d->W, d->kH, d->kW, d->stride_h, d->stride_w, d->pad_h, d->pad_w,
                       round_up(d->r, 16), true))
             return 0;
-        return z_bytes(d) + align_up(corr_partial_bytes(P), 256);
+        return z_bytes(d) + align_up(corr_partial_bytes(P), 256) + dy_repack_bytes(d);
     }
     if (op == XCONV_OP_EXACT) {
         const int CSx = round_up(d->C_in, 16);
         if (!get_plan(P, d->dtype, d->B, d->C_out, d->H, d->W, d->kH, d->kW, d->stride_h, d->stride_w, d->pad_h, d->pad_w, CSx, true))
             return 0;
-        return align_up((size_t)d->B * d->H * d->W * CSx * elem_bytes(d->dtype), 256) + align_up(corr_partial_bytes(P), 256);
+        return align_up((size_t)d->B * d->H * d->W * CSx * elem_bytes(d->dtype), 256) + align_up(corr_partial_bytes(P), 256) + dy_repack_bytes(d);
     }
     return 0;
 }
@@ -201,7 +214,7 @@ xconv_status xconv_dw_estimate(const xconv_desc *d, const void *dY_dev, const vo
     if (s != XCONV_OK) return s;
     if (!dY_dev || !Xt_dev || !dW_dev || !ws_dev) return XCONV_EINVAL;
     if (!aligned16(Xt_dev) || !aligned16(ws_dev) || (reinterpret_cast<uintptr_t>(dW_dev) & 3u) != 0) return XCONV_EINVAL;
-    if ((reinterpret_cast<uintptr_t>(dY_dev) & (elem_bytes(d->dtype) - 1)) != 0) return XCONV_EINVAL;
+    if (!aligned16(dY_dev)) return XCONV_EINVAL;
     if (!Z_dev && d->probe == XCONV_USER_Z) return XCONV_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int CS = round_up(d->r, 16);
@@ -209,8 +222,8 @@ xconv_status xconv_dw_estimate(const xconv_desc *d, const void *dY_dev, const vo
     if (!get_plan(P, d->dtype, d->B, d->C_out, d->H, d->W, d->kH, d->kW, d->stride_h, d->stride_w, d->pad_h, d->pad_w, CS,
                   aligned16(dY_dev)))
         return XCONV_EUNSUPPORTED;
-    const size_t zb = z_bytes(d);
-    if (ws_bytes < zb + align_up(corr_partial_bytes(P), 256)) return XCONV_EWORKSPACE;
+    const size_t zb = z_bytes(d), pb = align_up(corr_partial_bytes(P), 256), rb = dy_repack_bytes(d);
+    if (ws_bytes < zb + pb + rb) return XCONV_EWORKSPACE;
     const float *Z = Z_dev;
     if (!Z) {
         float *zw = static_cast<float *>(ws_dev);
@@ -218,6 +231,11 @@ xconv_status xconv_dw_estimate(const xconv_desc *d, const void *dY_dev, const vo
         Z = zw;
     }
     P.dY = dY_dev;
+    if (rb) {
+        void *packed = static_cast<char *>(ws_dev) + zb + pb;
+        XC_LAUNCH(K_REPACK, st, launch_repack_planes(d->dtype, dY_dev, packed, (long long)d->B * d->C_out, P.Ho * P.Wo, dy_pitch(d), st));
+        P.dY = packed;
+    }
     P.A = Xt_dev;
     P.part = reinterpret_cast<float *>(static_cast<char *>(ws_dev) + zb);
     XC_LAUNCH(K_CORR, st, launch_corr(d->dtype, P, st));
@@ -234,17 +252,22 @@ xconv_status xconv_dw_exact(const xconv_desc *d, const void *dY_dev, const void 
     if (!dY_dev || !X_dev || !dW_dev || !ws_dev) return XCONV_EINVAL;
     if (!aligned16(ws_dev) || (reinterpret_cast<uintptr_t>(dW_dev) & 3u) != 0) return XCONV_EINVAL;
     const size_t eb = elem_bytes(d->dtype);
-    if ((reinterpret_cast<uintptr_t>(dY_dev) & (eb - 1)) != 0 || (reinterpret_cast<uintptr_t>(X_dev) & (eb - 1)) != 0) return XCONV_EINVAL;
+    if (!aligned16(dY_dev) || (reinterpret_cast<uintptr_t>(X_dev) & (eb - 1)) != 0) return XCONV_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int CSx = round_up(d->C_in, 16), HW = d->H * d->W;
     CorrParams P;
     if (!get_plan(P, d->dtype, d->B, d->C_out, d->H, d->W, d->kH, d->kW, d->stride_h, d->stride_w, d->pad_h, d->pad_w, CSx,
                   aligned16(dY_dev)))
         return XCONV_EUNSUPPORTED;
-    const size_t xb = align_up((size_t)d->B * HW * CSx * eb, 256);
-    if (ws_bytes < xb + align_up(corr_partial_bytes(P), 256)) return XCONV_EWORKSPACE;
+    const size_t xb = align_up((size_t)d->B * HW * CSx * eb, 256), pb = align_up(corr_partial_bytes(P), 256), rb = dy_repack_bytes(d);
+    if (ws_bytes < xb + pb + rb) return XCONV_EWORKSPACE;
     XC_LAUNCH(K_TO_NHWC, st, launch_to_nhwc(d->dtype, X_dev, ws_dev, d->B, d->C_in, HW, CSx, st));
     P.dY = dY_dev;
+    if (rb) {
+        void *packed = static_cast<char *>(ws_dev) + xb + pb;
+        XC_LAUNCH(K_REPACK, st, launch_repack_planes(d->dtype, dY_dev, packed, (long long)d->B * d->C_out, P.Ho * P.Wo, dy_pitch(d), st));
+        P.dY = packed;
+    }
     P.A = ws_dev;
     P.part = reinterpret_cast<float *>(static_cast<char *>(ws_dev) + xb);
     XC_LAUNCH(K_CORR, st, launch_corr(d->dtype, P, st));
@@ -313,6 +336,7 @@ const char *xconv_prof_kernel_name(int id)
     case K_EXPAND: return "expand_kernel";
     case K_TO_NHWC: return "to_nhwc_kernel";
     case K_UNPACK: return "unpack_kernel";
+    case K_REPACK: return "repack_planes_kernel";
     default: return "unknown";
     }
 }
