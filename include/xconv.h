@@ -76,7 +76,8 @@ xconv_status xconv_check_desc(const xconv_desc *desc);
 size_t xconv_xt_bytes(const xconv_desc *desc);
 
 /* Bytes of device scratch the given op (xconv_op) needs in `ws_dev`.  The
- * scratch holds Z when it is regenerated from the seed, the split partial sums
+ * scratch holds Z (fp32, and for the probe in matrix-core operand order) when
+ * it is regenerated from the seed, the split partial sums
  * of the correlation, a repacked copy of dY when H'*W' is not a whole number of
  * 16-byte vectors and, for the exact gradient, a channels-last copy of X.
  * 0 for an invalid desc. */
@@ -94,9 +95,13 @@ xconv_status xconv_probe_matrix_dev(const xconv_desc *desc, float *Z_dev, void *
 
 /* Forward probe (Alg. 1 fwd step 3).  X_dev: [B,C_in,H,W] in desc->dtype.
  * Xt_dev: xconv_xt_bytes() bytes, written once.  Z_dev: [C_in,r] fp32 or NULL;
- * NULL regenerates Z from (probe, seed) into the workspace (XCONV_USER_Z then
- * is XCONV_EINVAL).  Sums are fp32; Xt is rounded once (nearest even) to
- * desc->dtype.  ws_dev may be NULL when Z_dev is given. */
+ * NULL draws Z from (probe, seed) into the workspace (XCONV_USER_Z then is
+ * XCONV_EINVAL).  Sums are fp32; Xt is rounded once (nearest even) to
+ * desc->dtype.  ws_dev may be NULL when Z_dev is given; with a workspace Z is
+ * first laid out once in the matrix-core operand order, without one every
+ * workgroup gathers its operands from Z_dev (same result, slower).  A non-NULL
+ * ws_dev smaller than xconv_workspace_bytes(XCONV_OP_PROBE) is
+ * XCONV_EWORKSPACE. */
 xconv_status xconv_probe_fwd(const xconv_desc *desc, const void *X_dev, void *Xt_dev,
                              const float *Z_dev, void *ws_dev, size_t ws_bytes, void *stream);
 

@@ -23,7 +23,8 @@ enum KernelId {
     K_UNPACK = 6,
     K_EXPAND = 7,
     K_REPACK = 8,
-    K_COUNT = 9
+    K_PACK_Z = 9,
+    K_COUNT = 10
 };
 
 __host__ __device__ inline int round_up(int a, int b) { return (a + b - 1) / b * b; }

@@ -534,45 +534,61 @@ __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const f32x4 *
 
 // ---------------------------------------------------------------------------
 // Second pass, part 2 (Algorithm 1 backward step 4, Eq. (6) step (iii)):
-//   dW[m,n,o] = (1/r) sum_j Z[n,j] T[o,j,m].
-// One workgroup per (offset o, 16 output channels, 64 input channels); j is
-// walked in chunks of 128 staged in LDS.
+//   dW[m,n,o] = (1/r) sum_j Z[n,j] T[o,j,m],
+// one small fp32 GEMM per offset (rows m, columns n, contraction over the r probes) on the
+// 16x16x4 matrix instruction.  One wave owns a 16 x 16 tile of (m, n) and OG consecutive
+// offsets: the A operand (T, channel-contiguous) and the B operand (Z rows) are read straight
+// from global memory, and a lane ends up with all OG offsets of its (m, n) pairs, which are
+// adjacent in dW.
 // ---------------------------------------------------------------------------
-constexpr int kExpJ = 128;
-
-__global__ __launch_bounds__(kThreads) void expand_kernel(const float *__restrict__ T, const float *__restrict__ Z,
-                                                          float *__restrict__ dW, int K2, int JP, int MP, int C_out, int C_in, int r)
+template <int OG>
+__global__ __launch_bounds__(64) void expand_kernel(const float *__restrict__ T, const float *__restrict__ Z,
+                                                    float *__restrict__ dW, int K2, int JP, int MP, int C_out, int C_in, int r,
+                                                    int NTN)
 {
-    __shared__ float Ts[kExpJ][16];
-    __shared__ float Zs[64][kExpJ + 1];
-    const int o = blockIdx.x, mb = blockIdx.y * 16, nb = blockIdx.z * 64;
-    const int tid = threadIdx.x, mm = tid & 15, nq = tid >> 4;
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int j0 = 0; j0 < r; j0 += kExpJ) {
-        const int jn = (r - j0) < kExpJ ? (r - j0) : kExpJ;
-        __syncthreads();
-        for (int e = tid; e < jn * 16; e += kThreads) {
-            const int j = e >> 4, m = e & 15;
-            Ts[j][m] = T[((size_t)o * JP + j0 + j) * MP + mb + m];
-        }
-        for (int e = tid; e < 64 * jn; e += kThreads) {
-            const int nl = e / jn, j = e - nl * jn;
-            Zs[nl][j] = (nb + nl < C_in) ? Z[(size_t)(nb + nl) * r + j0 + j] : 0.f;
-        }
-        __syncthreads();
-        for (int j = 0; j < jn; ++j) {
-            const float t = Ts[j][mm];
+    const int lane = threadIdx.x, l16 = lane & 15, g = lane >> 4;
+    const int nt = blockIdx.x % NTN, mt = blockIdx.x / NTN;
+    const int o0 = blockIdx.y * OG;
+    const int ncol = nt * 16 + l16;
+    const float *zrow = Z + (size_t)(ncol < C_in ? ncol : C_in - 1) * r;
+    const float *tcol[OG];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) acc[q] = fmaf(Zs[nq * 4 + q][j], t, acc[q]);
-        }
+    for (int o = 0; o < OG; ++o) {
+        const int oo = (o0 + o < K2) ? o0 + o : K2 - 1;  // offsets past the end repeat the last one and are not stored
+        tcol[o] = T + (size_t)oo * JP * MP + mt * 16 + l16;
     }
-    const int m = mb + mm;
-    const float inv_r = 1.0f / (float)r;
-    if (m < C_out) {
+    f32x4 acc[OG];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int n = nb + nq * 4 + q;
-            if (n < C_in) dW[((size_t)m * C_in + n) * K2 + o] = acc[q] * inv_r;
+    for (int o = 0; o < OG; ++o) acc[o] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // four k-steps per trip, all loads issued before the first use; probes past r are clamped
+    // to the last one and enter with a zero B operand
+    for (int j0 = 0; j0 < r; j0 += 16) {
+        float bv[4], av[4][OG];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int j = j0 + 4 * u + g;
+            const int jc = j < r ? j : r - 1;
+            const float zv = zrow[jc];
+            bv[u] = j < r ? zv : 0.f;
+#pragma unroll
+            for (int o = 0; o < OG; ++o) av[u][o] = tcol[o][(size_t)jc * MP];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int o = 0; o < OG; ++o) acc[o] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][o], bv[u], acc[o], 0, 0, 0);
+    }
+    const float inv_r = 1.0f / (float)r;
+    if (ncol < C_in) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int m = mt * 16 + 4 * g + v;
+            if (m < C_out) {
+                float *dst = dW + ((size_t)m * C_in + ncol) * K2 + o0;
+#pragma unroll
+                for (int o = 0; o < OG; ++o)
+                    if (o0 + o < K2) dst[o] = acc[o][v] * inv_r;
+            }
         }
     }
 }
@@ -855,8 +871,20 @@ hipError_t launch_reduce(const CorrParams &P, hipStream_t st)
 hipError_t launch_expand(const CorrParams &P, const float *Z, float *dW, int C_in, int r, hipStream_t st)
 {
     if (Z) {
-        hipLaunchKernelGGL(expand_kernel, dim3(P.K2, ceil_div(P.C_out, 16), ceil_div(C_in, 64)), dim3(kThreads), 0, st,
-                           reduced_tile(P), Z, dW, P.K2, P.JP, P.MP, P.C_out, C_in, r);
+        // few tiles: split the offsets over more waves; many tiles: a lane writes whole runs of offsets
+        const int NTM16 = ceil_div(P.C_out, 16), NTN = ceil_div(C_in, 16);
+        const long long tiles = (long long)NTM16 * NTN;
+        int og = P.K2 == 1 ? 1 : (tiles * ceil_div(P.K2, 9) >= 2048 ? 9 : (tiles * ceil_div(P.K2, 3) >= 2048 ? 3 : 1));
+        og = env_int("XCONV_EXPAND_OG", og);
+        const dim3 grid((unsigned)tiles, (unsigned)ceil_div(P.K2, og));
+        const float *T = reduced_tile(P);
+        if (og == 9)
+            hipLaunchKernelGGL(expand_kernel<9>, grid, dim3(64), 0, st, T, Z, dW, P.K2, P.JP, P.MP, P.C_out, C_in, r, NTN);
+        else if (og == 3)
+            hipLaunchKernelGGL(expand_kernel<3>, grid, dim3(64), 0, st, T, Z, dW, P.K2, P.JP, P.MP, P.C_out, C_in, r, NTN);
+        else
+            hipLaunchKernelGGL(expand_kernel<1>, dim3((unsigned)tiles, (unsigned)P.K2), dim3(64), 0, st, T, Z, dW, P.K2, P.JP, P.MP,
+                               P.C_out, C_in, r, NTN);
     } else {
         const long long total = (long long)P.C_out * C_in * P.K2;
         hipLaunchKernelGGL(untile_kernel, dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, st,

@@ -8,8 +8,11 @@ namespace xc {
 void host_probe_matrix(int dist, uint64_t seed, int n, float *Z);
 hipError_t launch_gen_z(float *Z, int n, int dist, uint64_t seed, hipStream_t st);
 bool probe_fast_path_ok(int dtype, int C_in, int HW);
-hipError_t launch_probe(int dtype, const void *X, const float *Z, void *Xt, int B, int C_in, int HW, int r, int CS,
-                        bool z_exact16, hipStream_t st);
+size_t zpack_bytes(int dtype, int C_in, int r, bool z_exact16);
+hipError_t launch_pack_z(int dtype, const float *Z, void *out, int C_in, int r, bool z_exact16, int dist, uint64_t seed,
+                         hipStream_t st);
+hipError_t launch_probe(int dtype, const void *X, const float *Z, const void *zpack, void *Xt, int B, int C_in, int HW, int r,
+                        int CS, bool z_exact16, hipStream_t st);
 hipError_t launch_probe_generic(int dtype, const void *X, const float *Z, void *Xt, int B, int C_in, int HW, int r, int CS,
                                 hipStream_t st);
 hipError_t launch_unpack(int dtype, const void *Xt, float *out, int B, int HW, int r, int CS, hipStream_t st);

@@ -59,6 +59,67 @@ __global__ __launch_bounds__(kThreads) void gen_z_kernel(float *__restrict__ Z, 
 __device__ inline int jmap(int jt, int i, int JT) { return (i >> 2) * (4 * JT) + jt * 4 + (i & 3); }
 
 // ---------------------------------------------------------------------------
+// Z in MFMA A-operand order, written once per call so that every workgroup of the probe
+// kernels fills its LDS copy with a straight vector copy.  Probe columns are handled in
+// blocks of 64 (four 16-row tiles, fewer in the last block).  Z == nullptr draws the entries
+// from the seed (Alg. 1 forward step 2).
+//   fp32:   block bi at float offset bi*KQ4*4*64, entry (kq, jt, lane) = Z[4kq + lane/16][j],
+//           KQ4 = channel quads rounded up to a multiple of 4, zero beyond C_in and r.
+//   16-bit: block bi at uint4 offset bi*KK*4*64*(split ? 2 : 1), entry (kk, jt, lane) = the 8
+//           channels 32kk + 8(lane/16) .. +7 of column j; with `split` the rounding residue
+//           z - hi follows nfrag entries later.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void pack_z_f32_kernel(const float *__restrict__ Z, float *__restrict__ out, int C_in, int r,
+                                                              int NTJ, int KQ4, int dist, uint64_t seed)
+{
+    const int e = blockIdx.x * kThreads + threadIdx.x;
+    if (e >= KQ4 * NTJ * 64) return;
+    const int l = e & 63, tj = (e >> 6) % NTJ, kq = (e >> 6) / NTJ;
+    const int bi = tj >> 2, jt = tj & 3, JTb = (NTJ - 4 * bi) < 4 ? (NTJ - 4 * bi) : 4;
+    const int c = kq * 4 + (l >> 4), j = 64 * bi + jmap(jt, l & 15, JTb);
+    float z = 0.0f;
+    if (c < C_in && j < r) {
+        const size_t idx = (size_t)c * r + j;
+        z = Z ? Z[idx] : probe_entry(dist, mix_fin(seed + 0x9E3779B97F4A7C15ull), (uint64_t)idx);
+    }
+    out[(size_t)bi * KQ4 * 4 * 64 + (kq * JTb + jt) * 64 + l] = z;
+}
+
+template <int DT>
+__global__ __launch_bounds__(kThreads) void pack_z_16_kernel(const float *__restrict__ Z, uint4 *__restrict__ out, int C_in, int r,
+                                                             int NTJ, int KK, int split, int dist, uint64_t seed)
+{
+    const int e = blockIdx.x * kThreads + threadIdx.x;
+    if (e >= KK * NTJ * 64) return;
+    const int l = e & 63, tj = (e >> 6) % NTJ, kk = (e >> 6) / NTJ;
+    const int bi = tj >> 2, jt = tj & 3, JTb = (NTJ - 4 * bi) < 4 ? (NTJ - 4 * bi) : 4;
+    const int j = 64 * bi + jmap(jt, l & 15, JTb);
+    const uint64_t key = mix_fin(seed + 0x9E3779B97F4A7C15ull);
+    uint32_t hi[4], lo[4];
+#pragma unroll
+    for (int q = 0; q < 8; q += 2) {
+        float z[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int c = kk * 32 + 8 * (l >> 4) + q + u;
+            z[u] = 0.0f;
+            if (c < C_in && j < r) {
+                const size_t idx = (size_t)c * r + j;
+                z[u] = Z ? Z[idx] : probe_entry(dist, key, (uint64_t)idx);
+            }
+        }
+        const uint16_t h0 = f32_to_st16<DT>(z[0]), h1 = f32_to_st16<DT>(z[1]);
+        hi[q >> 1] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+        const uint16_t w0 = f32_to_st16<DT>(z[0] - st16_to_f32<DT>(h0)), w1 = f32_to_st16<DT>(z[1] - st16_to_f32<DT>(h1));
+        lo[q >> 1] = (uint32_t)w0 | ((uint32_t)w1 << 16);
+    }
+    const size_t nfrag = (size_t)KK * JTb * 64;
+    const size_t at = (size_t)bi * KK * 4 * 64 * (split ? 2 : 1) + (kk * JTb + jt) * 64 + l;
+    out[at] = uint4{hi[0], hi[1], hi[2], hi[3]};
+    if (split) out[at + nfrag] = uint4{lo[0], lo[1], lo[2], lo[3]};
+}
+
+// ---------------------------------------------------------------------------
 // fp32 probe.  v_mfma_f32_16x16x4_f32: A = Z^T tile (16 probe rows x 4
 // channels), B = X tile (4 channels x 16 pixel columns).  Each lane loads four
 // consecutive pixels (16 bytes) of one channel; MFMA t uses element t, so MFMA
@@ -66,27 +127,35 @@ __device__ inline int jmap(int jt, int i, int JT) { return (i >> 2) * (4 * JT) +
 // ---------------------------------------------------------------------------
 template <int JT>
 __global__ __launch_bounds__(kThreads) void probe_f32_kernel(const float *__restrict__ X, const float *__restrict__ Z,
-                                                             float *__restrict__ Xt, int C_in, int HW, int r, int CS,
-                                                             int j0, long long ngroups, int ntiles)
+                                                             const float *__restrict__ zpack, float *__restrict__ Xt, int C_in,
+                                                             int HW, int r, int CS, int j0, long long ngroups, int ntiles)
 {
-    extern __shared__ float zs[];  // [KQ][JT][64] A-operand fragments
+    extern __shared__ float zs[];  // [KQ4][JT][64] A-operand fragments, zero beyond C_in
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int KQ = (C_in + 3) >> 2;
-    for (int e = tid; e < KQ * JT * 64; e += kThreads) {
-        const int l = e & 63, jt = (e >> 6) % JT, kq = (e >> 6) / JT;
-        const int c = kq * 4 + (l >> 4);
-        const int j = j0 + jmap(jt, l & 15, JT);
-        zs[e] = (c < C_in && j < r) ? Z[(size_t)c * r + j] : 0.0f;
+    const int KQ4 = ((C_in + 15) >> 4) << 2;
+    const int nfrag = KQ4 * JT * 64;
+    if (zpack) {
+        for (int e = tid; e < nfrag / 4; e += kThreads)
+            reinterpret_cast<float4 *>(zs)[e] = reinterpret_cast<const float4 *>(zpack)[e];
+    } else {
+        for (int e = tid; e < nfrag; e += kThreads) {
+            const int l = e & 63, jt = (e >> 6) % JT, kq = (e >> 6) / JT;
+            const int c = kq * 4 + (l >> 4);
+            const int j = j0 + jmap(jt, l & 15, JT);
+            zs[e] = (c < C_in && j < r) ? Z[(size_t)c * r + j] : 0.0f;
+        }
     }
     __syncthreads();
 
     const int n = lane & 15, g = lane >> 4;
+    const long long last_group = ngroups - 1;
     for (int tile = blockIdx.x * 4 + wave; tile < ntiles; tile += gridDim.x * 4) {
-        const long long pg = (long long)tile * 16 + n;
-        const bool valid = pg < ngroups;
+        const long long pg_raw = (long long)tile * 16 + n;
+        const bool valid = pg_raw < ngroups;
+        const long long pg = valid ? pg_raw : last_group;  // lanes past the end redo the last group and store nothing
         const long long flat = pg * 4;
-        const int b = valid ? (int)(flat / HW) : 0;
-        const int p = valid ? (int)(flat % HW) : 0;
+        const int b = (int)(flat / HW);
+        const int p = (int)(flat % HW);
         const float *xb = X + (size_t)b * C_in * HW + p;
         f32x4 acc[JT][4];
 #pragma unroll
@@ -94,27 +163,45 @@ __global__ __launch_bounds__(kThreads) void probe_f32_kernel(const float *__rest
 #pragma unroll
             for (int t = 0; t < 4; ++t) acc[jt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-        for (int c0 = 0; c0 < C_in; c0 += 16) {
-            float4 v[4];
+        // Loads are unconditional (channels past the end re-read the last channel against zero
+        // fragment entries), so the next 16 channels are fetched while these are multiplied.
+        auto load16 = [&](float4 (&v)[4], int c0) {
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int c = c0 + 4 * u + g;
-                v[u] = (valid && c < C_in) ? *reinterpret_cast<const float4 *>(xb + (size_t)c * HW) : float4{0.f, 0.f, 0.f, 0.f};
+                int c = c0 + 4 * u + g;
+                c = c < C_in ? c : C_in - 1;
+                v[u] = *reinterpret_cast<const float4 *>(xb + (size_t)c * HW);
             }
+        };
+        auto process = [&](const float4 (&v)[4], int c0) {
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int kq = (c0 >> 2) + u;
-                if (kq < KQ) {
 #pragma unroll
-                    for (int jt = 0; jt < JT; ++jt) {
-                        const float a = zs[(kq * JT + jt) * 64 + lane];
-                        acc[jt][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, v[u].x, acc[jt][0], 0, 0, 0);
-                        acc[jt][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, v[u].y, acc[jt][1], 0, 0, 0);
-                        acc[jt][2] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, v[u].z, acc[jt][2], 0, 0, 0);
-                        acc[jt][3] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, v[u].w, acc[jt][3], 0, 0, 0);
-                    }
+                for (int jt = 0; jt < JT; ++jt) {
+                    const float a = zs[(kq * JT + jt) * 64 + lane];
+                    acc[jt][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, v[u].x, acc[jt][0], 0, 0, 0);
+                    acc[jt][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, v[u].y, acc[jt][1], 0, 0, 0);
+                    acc[jt][2] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, v[u].z, acc[jt][2], 0, 0, 0);
+                    acc[jt][3] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, v[u].w, acc[jt][3], 0, 0, 0);
                 }
             }
+        };
+        float4 v0[4], v1[4];
+        load16(v0, 0);
+        int c0 = 0;
+        for (; c0 + 32 < C_in; c0 += 32) {  // both fetches of a trip are needed ones
+            load16(v1, c0 + 16);
+            process(v0, c0);
+            load16(v0, c0 + 32);
+            process(v1, c0 + 16);
+        }
+        if (c0 + 16 < C_in) {
+            load16(v1, c0 + 16);
+            process(v0, c0);
+            process(v1, c0 + 16);
+        } else {
+            process(v0, c0);
         }
         if (valid) {
             // lane (n, g) holds rows 4g..4g+3 of every tile = probe columns j0 + g*4*JT + jt*4 + v
@@ -138,39 +225,63 @@ __global__ __launch_bounds__(kThreads) void probe_f32_kernel(const float *__rest
 // ---------------------------------------------------------------------------
 template <int DT, int JT, int PT, bool SPLIT>
 __global__ __launch_bounds__(kThreads) void probe_16_kernel(const uint16_t *__restrict__ X, const float *__restrict__ Z,
-                                                            uint16_t *__restrict__ Xt, int C_in, int HW, int r, int CS,
-                                                            int j0, long long ngroups, int ntiles)
+                                                            const uint4 *__restrict__ zpack, uint16_t *__restrict__ Xt, int C_in,
+                                                            int HW, int r, int CS, int j0, long long ngroups, int ntiles)
 {
     extern __shared__ uint4 zf[];  // [SPLIT?2:1][KK][JT][64] A-operand fragments
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int KK = (C_in + 31) >> 5;
     const int nfrag = KK * JT * 64;
-    for (int e = tid; e < nfrag; e += kThreads) {
-        const int l = e & 63, jt = (e >> 6) % JT, kk = (e >> 6) / JT;
-        const int j = j0 + jmap(jt, l & 15, JT);
-        uint32_t hi[4], lo[4];
+    if (zpack) {
+        for (int e = tid; e < nfrag * (SPLIT ? 2 : 1); e += kThreads) zf[e] = zpack[e];
+    } else {
+        // Z fragments: four entries (32 scalar loads) per thread in flight at a time
+        for (int base = 0; base < nfrag; base += 4 * kThreads) {
+            float z[4][8];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            const int c = kk * 32 + 8 * (l >> 4) + q;
-            const float z = (c < C_in && j < r) ? Z[(size_t)c * r + j] : 0.0f;
-            const uint16_t h = f32_to_st16<DT>(z);
-            const uint16_t w = f32_to_st16<DT>(z - st16_to_f32<DT>(h));
-            if (q & 1) { hi[q >> 1] |= (uint32_t)h << 16; lo[q >> 1] |= (uint32_t)w << 16; }
-            else       { hi[q >> 1] = h; lo[q >> 1] = w; }
+            for (int k = 0; k < 4; ++k) {
+                const int e = base + k * kThreads + tid;
+                const int l = e & 63, jt = (e >> 6) % JT, kk = (e >> 6) / JT;
+                const int j = j0 + jmap(jt, l & 15, JT);
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const int c = kk * 32 + 8 * (l >> 4) + q;
+                    z[k][q] = (e < nfrag && c < C_in && j < r) ? Z[(size_t)c * r + j] : 0.0f;
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int e = base + k * kThreads + tid;
+                uint32_t hi[4], lo[4];
+#pragma unroll
+                for (int q = 0; q < 8; q += 2) {
+                    const uint16_t h0 = f32_to_st16<DT>(z[k][q]), h1 = f32_to_st16<DT>(z[k][q + 1]);
+                    hi[q >> 1] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+                    if constexpr (SPLIT) {
+                        const uint16_t w0 = f32_to_st16<DT>(z[k][q] - st16_to_f32<DT>(h0));
+                        const uint16_t w1 = f32_to_st16<DT>(z[k][q + 1] - st16_to_f32<DT>(h1));
+                        lo[q >> 1] = (uint32_t)w0 | ((uint32_t)w1 << 16);
+                    }
+                }
+                if (e < nfrag) {
+                    zf[e] = uint4{hi[0], hi[1], hi[2], hi[3]};
+                    if constexpr (SPLIT) zf[nfrag + e] = uint4{lo[0], lo[1], lo[2], lo[3]};
+                }
+            }
         }
-        zf[e] = uint4{hi[0], hi[1], hi[2], hi[3]};
-        if (SPLIT) zf[nfrag + e] = uint4{lo[0], lo[1], lo[2], lo[3]};
     }
     __syncthreads();
 
     constexpr int NW = PT / 2;
     const int n = lane & 15, g = lane >> 4;
+    const long long last_group = ngroups - 1;
     for (int tile = blockIdx.x * 4 + wave; tile < ntiles; tile += gridDim.x * 4) {
-        const long long pg = (long long)tile * 16 + n;
-        const bool valid = pg < ngroups;
+        const long long pg_raw = (long long)tile * 16 + n;
+        const bool valid = pg_raw < ngroups;
+        const long long pg = valid ? pg_raw : last_group;  // lanes past the end redo the last group and store nothing
         const long long flat = pg * PT;
-        const int b = valid ? (int)(flat / HW) : 0;
-        const int p = valid ? (int)(flat % HW) : 0;
+        const int b = (int)(flat / HW);
+        const int p = (int)(flat % HW);
         const uint16_t *xb = X + (size_t)b * C_in * HW + p;
         f32x4 acc[JT][PT];
 #pragma unroll
@@ -178,20 +289,23 @@ __global__ __launch_bounds__(kThreads) void probe_16_kernel(const uint16_t *__re
 #pragma unroll
             for (int t = 0; t < PT; ++t) acc[jt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-        for (int kk = 0; kk < KK; ++kk) {
-            uint32_t rows[8][NW];
+        // Loads are unconditional (channels past the end re-read the last channel, whose Z
+        // fragment entries are zero), so the next K-step can be prefetched without branches.
+        auto load_rows = [&](uint32_t (&rows)[8][NW], int kk) {
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
-                const int c = kk * 32 + 8 * g + q;
-                const bool ok = valid && c < C_in;
+                int c = kk * 32 + 8 * g + q;
+                c = c < C_in ? c : C_in - 1;
                 if constexpr (PT == 8) {
-                    const uint4 v = ok ? *reinterpret_cast<const uint4 *>(xb + (size_t)c * HW) : uint4{0, 0, 0, 0};
+                    const uint4 v = *reinterpret_cast<const uint4 *>(xb + (size_t)c * HW);
                     rows[q][0] = v.x; rows[q][1] = v.y; rows[q][2] = v.z; rows[q][3] = v.w;
                 } else {
-                    const uint2 v = ok ? *reinterpret_cast<const uint2 *>(xb + (size_t)c * HW) : uint2{0, 0};
+                    const uint2 v = *reinterpret_cast<const uint2 *>(xb + (size_t)c * HW);
                     rows[q][0] = v.x; rows[q][1] = v.y;
                 }
             }
+        };
+        auto process = [&](const uint32_t (&rows)[8][NW], int kk) {
             uint4 cols[PT];
             transpose_rows8<NW>(rows, cols);
 #pragma unroll
@@ -205,18 +319,44 @@ __global__ __launch_bounds__(kThreads) void probe_16_kernel(const uint16_t *__re
                     for (int t = 0; t < PT; ++t) acc[jt][t] = mfma16<DT>(al, cols[t], acc[jt][t]);
                 }
             }
+        };
+        uint32_t r0[8][NW], r1[8][NW];
+        load_rows(r0, 0);
+        int kk = 0;
+        for (; kk + 2 < KK; kk += 2) {  // both fetches of a trip are needed ones
+            load_rows(r1, kk + 1);
+            process(r0, kk);
+            load_rows(r0, kk + 2);
+            process(r1, kk + 1);
+        }
+        if (kk + 1 < KK) {
+            load_rows(r1, kk + 1);
+            process(r0, kk);
+            process(r1, kk + 1);
+        } else {
+            process(r0, kk);
         }
         if (valid) {
+            // lane (n, g) holds probe columns j0 + g*4*JT .. +4*JT-1 of pixel t: one run of 8*JT bytes
             uint16_t *out = Xt + (size_t)flat * CS + j0 + g * (4 * JT);
 #pragma unroll
-            for (int t = 0; t < PT; ++t)
+            for (int t = 0; t < PT; ++t) {
+                uint32_t w[2 * JT];
 #pragma unroll
                 for (int jt = 0; jt < JT; ++jt) {
-                    uint2 w;
-                    w.x = (uint32_t)f32_to_st16<DT>(acc[jt][t][0]) | ((uint32_t)f32_to_st16<DT>(acc[jt][t][1]) << 16);
-                    w.y = (uint32_t)f32_to_st16<DT>(acc[jt][t][2]) | ((uint32_t)f32_to_st16<DT>(acc[jt][t][3]) << 16);
-                    *reinterpret_cast<uint2 *>(out + (size_t)t * CS + jt * 4) = w;
+                    w[2 * jt] = (uint32_t)f32_to_st16<DT>(acc[jt][t][0]) | ((uint32_t)f32_to_st16<DT>(acc[jt][t][1]) << 16);
+                    w[2 * jt + 1] = (uint32_t)f32_to_st16<DT>(acc[jt][t][2]) | ((uint32_t)f32_to_st16<DT>(acc[jt][t][3]) << 16);
                 }
+                uint16_t *o = out + (size_t)t * CS;
+                if constexpr (JT % 2 == 0) {
+#pragma unroll
+                    for (int k = 0; k < JT / 2; ++k)
+                        *reinterpret_cast<uint4 *>(o + 8 * k) = uint4{w[4 * k], w[4 * k + 1], w[4 * k + 2], w[4 * k + 3]};
+                } else {
+#pragma unroll
+                    for (int k = 0; k < JT; ++k) *reinterpret_cast<uint2 *>(o + 4 * k) = uint2{w[2 * k], w[2 * k + 1]};
+                }
+            }
         }
     }
 }
@@ -319,45 +459,45 @@ static int probe_grid(int ntiles)
 }
 
 template <int JT>
-static hipError_t launch_probe_f32_jt(const float *X, const float *Z, float *Xt, int C_in, int HW, int r, int CS, int j0,
-                                      long long npix, hipStream_t st)
+static hipError_t launch_probe_f32_jt(const float *X, const float *Z, const float *zpack, float *Xt, int C_in, int HW, int r, int CS,
+                                      int j0, long long npix, hipStream_t st)
 {
     const long long ngroups = npix / 4;
     const int ntiles = (int)((ngroups + 15) / 16);
-    const size_t lds = (size_t)ceil_div(C_in, 4) * JT * 64 * sizeof(float);
+    const size_t lds = (size_t)ceil_div(C_in, 16) * 4 * JT * 64 * sizeof(float);
     hipError_t e = set_lds(probe_f32_kernel<JT>, lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(probe_f32_kernel<JT>, dim3(probe_grid(ntiles)), dim3(kThreads), lds, st, X, Z, Xt, C_in, HW, r, CS, j0,
-                       ngroups, ntiles);
+    hipLaunchKernelGGL(probe_f32_kernel<JT>, dim3(probe_grid(ntiles)), dim3(kThreads), lds, st, X, Z, zpack, Xt, C_in, HW, r, CS,
+                       j0, ngroups, ntiles);
     return hipGetLastError();
 }
 
 template <int DT, int JT, int PT, bool SPLIT>
-static hipError_t launch_probe_16_cfg(const uint16_t *X, const float *Z, uint16_t *Xt, int C_in, int HW, int r, int CS, int j0,
-                                      long long npix, hipStream_t st)
+static hipError_t launch_probe_16_cfg(const uint16_t *X, const float *Z, const uint4 *zpack, uint16_t *Xt, int C_in, int HW, int r,
+                                      int CS, int j0, long long npix, hipStream_t st)
 {
     const long long ngroups = npix / PT;
     const int ntiles = (int)((ngroups + 15) / 16);
     const size_t lds = (size_t)(SPLIT ? 2 : 1) * ceil_div(C_in, 32) * JT * 64 * sizeof(uint4);
     hipError_t e = set_lds(probe_16_kernel<DT, JT, PT, SPLIT>, lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((probe_16_kernel<DT, JT, PT, SPLIT>), dim3(probe_grid(ntiles)), dim3(kThreads), lds, st, X, Z, Xt, C_in,
-                       HW, r, CS, j0, ngroups, ntiles);
+    hipLaunchKernelGGL((probe_16_kernel<DT, JT, PT, SPLIT>), dim3(probe_grid(ntiles)), dim3(kThreads), lds, st, X, Z, zpack, Xt,
+                       C_in, HW, r, CS, j0, ngroups, ntiles);
     return hipGetLastError();
 }
 
 template <int DT, int JT>
-static hipError_t launch_probe_16_jt(const uint16_t *X, const float *Z, uint16_t *Xt, int C_in, int HW, int r, int CS, int j0,
-                                     long long npix, bool split, hipStream_t st)
+static hipError_t launch_probe_16_jt(const uint16_t *X, const float *Z, const uint4 *zpack, uint16_t *Xt, int C_in, int HW, int r,
+                                     int CS, int j0, long long npix, bool split, hipStream_t st)
 {
     // 8 pixels per lane when the accumulators stay small, 4 for wide probe blocks
     const bool pt8 = (JT <= 2) && (HW % 8 == 0);
     if (pt8) {
-        if (split) return launch_probe_16_cfg<DT, JT, 8, true>(X, Z, Xt, C_in, HW, r, CS, j0, npix, st);
-        return launch_probe_16_cfg<DT, JT, 8, false>(X, Z, Xt, C_in, HW, r, CS, j0, npix, st);
+        if (split) return launch_probe_16_cfg<DT, JT, 8, true>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, st);
+        return launch_probe_16_cfg<DT, JT, 8, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, st);
     }
-    if (split) return launch_probe_16_cfg<DT, JT, 4, true>(X, Z, Xt, C_in, HW, r, CS, j0, npix, st);
-    return launch_probe_16_cfg<DT, JT, 4, false>(X, Z, Xt, C_in, HW, r, CS, j0, npix, st);
+    if (split) return launch_probe_16_cfg<DT, JT, 4, true>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, st);
+    return launch_probe_16_cfg<DT, JT, 4, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, st);
 }
 
 bool probe_fast_path_ok(int dtype, int C_in, int HW)
@@ -365,12 +505,43 @@ bool probe_fast_path_ok(int dtype, int C_in, int HW)
     // aligned vector loads of 4 pixels (16 bytes fp32, 8 bytes 16-bit) per channel row;
     // LDS for the Z fragments (worst case JT = 4, split) must fit
     if (HW % 4 != 0) return false;
-    const size_t lds = dtype == XCONV_F32 ? (size_t)ceil_div(C_in, 4) * 4 * 64 * 4 : (size_t)2 * ceil_div(C_in, 32) * 4 * 64 * 16;
+    const size_t lds = dtype == XCONV_F32 ? (size_t)ceil_div(C_in, 16) * 4 * 4 * 64 * 4 : (size_t)2 * ceil_div(C_in, 32) * 4 * 64 * 16;
     return lds <= 128 * 1024;
 }
 
-hipError_t launch_probe(int dtype, const void *X, const float *Z, void *Xt, int B, int C_in, int HW, int r, int CS,
-                        bool z_exact16, hipStream_t st)
+// Bytes of Z in fragment order (pack_z_*_kernel) for all column blocks.
+size_t zpack_bytes(int dtype, int C_in, int r, bool z_exact16)
+{
+    const size_t ntj = (size_t)ceil_div(r, 16);
+    if (dtype == XCONV_F32) return (size_t)ceil_div(C_in, 16) * 4 * ntj * 64 * sizeof(float);
+    return (size_t)(z_exact16 ? 1 : 2) * ceil_div(C_in, 32) * ntj * 64 * sizeof(uint4);
+}
+
+hipError_t launch_pack_z(int dtype, const float *Z, void *out, int C_in, int r, bool z_exact16, int dist, uint64_t seed,
+                         hipStream_t st)
+{
+    const int ntj = ceil_div(r, 16);
+    if (dtype == XCONV_F32) {
+        const int KQ4 = ceil_div(C_in, 16) * 4;
+        hipLaunchKernelGGL(pack_z_f32_kernel, dim3(ceil_div(KQ4 * ntj * 64, kThreads)), dim3(kThreads), 0, st, Z,
+                           static_cast<float *>(out), C_in, r, ntj, KQ4, dist, seed);
+    } else {
+        const int KK = ceil_div(C_in, 32);
+        const dim3 grid(ceil_div(KK * ntj * 64, kThreads));
+        if (dtype == XCONV_BF16)
+            hipLaunchKernelGGL(pack_z_16_kernel<XCONV_BF16>, grid, dim3(kThreads), 0, st, Z, static_cast<uint4 *>(out), C_in, r, ntj,
+                               KK, z_exact16 ? 0 : 1, dist, seed);
+        else
+            hipLaunchKernelGGL(pack_z_16_kernel<XCONV_F16>, grid, dim3(kThreads), 0, st, Z, static_cast<uint4 *>(out), C_in, r, ntj,
+                               KK, z_exact16 ? 0 : 1, dist, seed);
+    }
+    return hipGetLastError();
+}
+
+// zpack: Z in fragment order (launch_pack_z) or nullptr, in which case every workgroup gathers
+// its fragments from Z itself.
+hipError_t launch_probe(int dtype, const void *X, const float *Z, const void *zpack, void *Xt, int B, int C_in, int HW, int r,
+                        int CS, bool z_exact16, hipStream_t st)
 {
     const long long npix = (long long)B * HW;
     const int ntj = CS / 16;
@@ -378,25 +549,28 @@ hipError_t launch_probe(int dtype, const void *X, const float *Z, void *Xt, int 
     for (int t0 = 0; t0 < ntj && e == hipSuccess; t0 += 4) {
         const int jt = (ntj - t0) < 4 ? (ntj - t0) : 4;
         const int j0 = t0 * 16;
+        const size_t bi = (size_t)(t0 / 4);
         if (dtype == XCONV_F32) {
             const float *x = static_cast<const float *>(X);
             float *o = static_cast<float *>(Xt);
+            const float *zp = zpack ? static_cast<const float *>(zpack) + bi * ceil_div(C_in, 16) * 4 * 4 * 64 : nullptr;
             switch (jt) {
-            case 1: e = launch_probe_f32_jt<1>(x, Z, o, C_in, HW, r, CS, j0, npix, st); break;
-            case 2: e = launch_probe_f32_jt<2>(x, Z, o, C_in, HW, r, CS, j0, npix, st); break;
-            case 3: e = launch_probe_f32_jt<3>(x, Z, o, C_in, HW, r, CS, j0, npix, st); break;
-            default: e = launch_probe_f32_jt<4>(x, Z, o, C_in, HW, r, CS, j0, npix, st); break;
+            case 1: e = launch_probe_f32_jt<1>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, st); break;
+            case 2: e = launch_probe_f32_jt<2>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, st); break;
+            case 3: e = launch_probe_f32_jt<3>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, st); break;
+            default: e = launch_probe_f32_jt<4>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, st); break;
             }
         } else {
             const uint16_t *x = static_cast<const uint16_t *>(X);
             uint16_t *o = static_cast<uint16_t *>(Xt);
             const bool split = !z_exact16;
-#define XC_P16(DT)                                                                                        \
-    switch (jt) {                                                                                         \
-    case 1: e = launch_probe_16_jt<DT, 1>(x, Z, o, C_in, HW, r, CS, j0, npix, split, st); break;          \
-    case 2: e = launch_probe_16_jt<DT, 2>(x, Z, o, C_in, HW, r, CS, j0, npix, split, st); break;          \
-    case 3: e = launch_probe_16_jt<DT, 3>(x, Z, o, C_in, HW, r, CS, j0, npix, split, st); break;          \
-    default: e = launch_probe_16_jt<DT, 4>(x, Z, o, C_in, HW, r, CS, j0, npix, split, st); break;         \
+            const uint4 *zp = zpack ? static_cast<const uint4 *>(zpack) + bi * ceil_div(C_in, 32) * 4 * 64 * (split ? 2 : 1) : nullptr;
+#define XC_P16(DT)                                                                                            \
+    switch (jt) {                                                                                             \
+    case 1: e = launch_probe_16_jt<DT, 1>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, st); break;          \
+    case 2: e = launch_probe_16_jt<DT, 2>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, st); break;          \
+    case 3: e = launch_probe_16_jt<DT, 3>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, st); break;          \
+    default: e = launch_probe_16_jt<DT, 4>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, st); break;         \
     }
             if (dtype == XCONV_BF16) { XC_P16(XCONV_BF16) } else { XC_P16(XCONV_F16) }
 #undef XC_P16

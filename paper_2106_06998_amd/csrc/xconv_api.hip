@@ -99,6 +99,11 @@ bool get_plan(CorrParams &P, int dtype, int B, int C_out, int H, int W, int kH, 
 }
 
 size_t z_bytes(const xconv_desc *d) { return align_up((size_t)d->C_in * d->r * sizeof(float), 256); }
+// Z in the fragment order of the probe kernels, behind the fp32 Z in the probe workspace
+size_t zfrag_bytes(const xconv_desc *d)
+{
+    return align_up(zpack_bytes(d->dtype, d->C_in, d->r, d->probe == XCONV_RADEMACHER), 256);
+}
 
 // dY planes that are not a whole number of 16-byte vectors are repacked into scratch
 int dy_pitch(const xconv_desc *d)
@@ -144,7 +149,7 @@ size_t xconv_xt_bytes(const xconv_desc *d)
 size_t xconv_workspace_bytes(const xconv_desc *d, int op)
 {
     if (xconv_check_desc(d) != XCONV_OK) return 0;
-    if (op == XCONV_OP_PROBE) return z_bytes(d);
+    if (op == XCONV_OP_PROBE) return z_bytes(d) + zfrag_bytes(d);
     CorrParams P;
     if (op == XCONV_OP_ESTIMATE) {
         if (!get_plan(P, d->dtype, d->B, d->C_out, d->H, d->W, d->kH, d->kW, d->stride_h, d->stride_w, d->pad_h, d->pad_w,
@@ -189,19 +194,29 @@ xconv_status xconv_probe_fwd(const xconv_desc *d, const void *X_dev, void *Xt_de
     if (!aligned16(Xt_dev) || (reinterpret_cast<uintptr_t>(X_dev) & (elem_bytes(d->dtype) - 1)) != 0) return XCONV_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int CS = round_up(d->r, 16), HW = d->H * d->W;
-    const float *Z = Z_dev;
-    if (!Z) {
-        if (d->probe == XCONV_USER_Z) return XCONV_EINVAL;
-        if (!ws_dev || !aligned16(ws_dev)) return XCONV_EINVAL;
-        if (ws_bytes < z_bytes(d)) return XCONV_EWORKSPACE;
-        float *zw = static_cast<float *>(ws_dev);
-        XC_LAUNCH(K_GEN_Z, st, launch_gen_z(zw, d->C_in * d->r, d->probe, d->seed, st));
-        Z = zw;
-    }
     const bool z_exact16 = d->probe == XCONV_RADEMACHER;
-    if (probe_fast_path_ok(d->dtype, d->C_in, HW) && aligned16(X_dev)) {
-        XC_LAUNCH(K_PROBE, st, launch_probe(d->dtype, X_dev, Z, Xt_dev, d->B, d->C_in, HW, d->r, CS, z_exact16, st));
+    const bool fast = probe_fast_path_ok(d->dtype, d->C_in, HW) && aligned16(X_dev);
+    const size_t zb = z_bytes(d), fb = zfrag_bytes(d);
+    if (!Z_dev && d->probe == XCONV_USER_Z) return XCONV_EINVAL;
+    if (ws_dev) {
+        if (!aligned16(ws_dev)) return XCONV_EINVAL;
+        if (ws_bytes < zb + fb) return XCONV_EWORKSPACE;
+    } else if (!Z_dev) {
+        return XCONV_EINVAL;
+    }
+    if (fast) {
+        // With scratch, Z goes to the kernels in fragment order (drawn from the seed when no Z
+        // is given); without it, every workgroup gathers its fragments from Z_dev.
+        void *zpack = ws_dev ? static_cast<char *>(ws_dev) + zb : nullptr;
+        if (zpack) XC_LAUNCH(K_PACK_Z, st, launch_pack_z(d->dtype, Z_dev, zpack, d->C_in, d->r, z_exact16, d->probe, d->seed, st));
+        XC_LAUNCH(K_PROBE, st, launch_probe(d->dtype, X_dev, Z_dev, zpack, Xt_dev, d->B, d->C_in, HW, d->r, CS, z_exact16, st));
     } else {
+        const float *Z = Z_dev;
+        if (!Z) {
+            float *zw = static_cast<float *>(ws_dev);
+            XC_LAUNCH(K_GEN_Z, st, launch_gen_z(zw, d->C_in * d->r, d->probe, d->seed, st));
+            Z = zw;
+        }
         XC_LAUNCH(K_PROBE_GENERIC, st, launch_probe_generic(d->dtype, X_dev, Z, Xt_dev, d->B, d->C_in, HW, d->r, CS, st));
     }
     return XCONV_OK;
@@ -337,6 +352,7 @@ const char *xconv_prof_kernel_name(int id)
     case K_TO_NHWC: return "to_nhwc_kernel";
     case K_UNPACK: return "unpack_kernel";
     case K_REPACK: return "repack_planes_kernel";
+    case K_PACK_Z: return "pack_z_kernel";
     default: return "unknown";
     }
 }

@@ -47,6 +47,11 @@ def run_probe(cfg, X, Z=None, seed_path=False):
     else:
         Zd = torch.from_numpy(np.ascontiguousarray(Z, dtype=np.float32)).to(DEV)
         xb.xconv_probe_fwd(d, Xd, Xt, Zd, None)
+        # the same Z through the scratch-backed route (fragments packed once per call)
+        Xt2 = xb.alloc_xt(d, DEV)
+        Xt2.fill_(0x7f)
+        xb.xconv_probe_fwd(d, Xd, Xt2, Zd, xb.alloc_ws(d, xb.XCONV_OP_PROBE, DEV))
+        assert torch.equal(Xt, Xt2)
     out = torch.empty((cfg.B, cfg.r, cfg.H, cfg.W), dtype=torch.float32, device=DEV)
     xb.xconv_xt_unpack(d, Xt, out)
     torch.cuda.synchronize()
@@ -201,6 +206,10 @@ def test_edge_shapes(e):
     Xt = xb.alloc_xt(d, DEV)
     Xt.fill_(0x7f)
     xb.xconv_probe_fwd(d, Xd, Xt, Zd, None)
+    Xt2 = xb.alloc_xt(d, DEV)
+    Xt2.fill_(0x7f)
+    xb.xconv_probe_fwd(d, Xd, Xt2, Zd, xb.alloc_ws(d, xb.XCONV_OP_PROBE, DEV))   # Z packed into scratch first
+    assert torch.equal(Xt, Xt2)
     unp = torch.empty((B, r, H, W), dtype=torch.float32, device=DEV)
     xb.xconv_xt_unpack(d, Xt, unp)
     dW = torch.full((C_out, C_in, kH, kW), float("nan"), dtype=torch.float32, device=DEV)
