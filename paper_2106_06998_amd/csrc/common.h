@@ -109,6 +109,7 @@ struct CorrParams {
     int MP, JP;        // padded extents of the partial buffer
     int dy_plane;      // elements between consecutive (image, channel) planes of dY as the kernel reads it (whole 16-byte vectors)
     int a_units, b_units;  // LDS units of the two staging tiles
+    int AL;            // every staged row segment of dY starts on a 16-byte vector
 };
 
 }  // namespace xc

@@ -107,8 +107,11 @@ __device__ inline StepPos next_step(const CorrParams &P, StepPos s)
 // NOFF: kernel offsets a workgroup accumulates (9, or 1 for 1x1 kernels).  A
 // last group with fewer offsets recomputes its first offset in the spare slots
 // and does not write them.
-template <int DT, int MT, int NA, int NB, int NOFF>
-__global__ __launch_bounds__(kThreads, (MT <= 2 ? 2 : 1)) void corr_kernel(const CorrParams P)
+// AL: every row segment of dY that a step stages starts on a 16-byte vector (W' and the
+// strip width are multiples of the vector length); the staging of dY then has fixed LDS
+// addresses per thread and needs no per-element predicates.
+template <int DT, int MT, int NA, int NB, int NOFF, bool AL>
+__global__ __launch_bounds__(kThreads, ((DT == XCONV_F32 && MT <= 2) ? 2 : 1)) void corr_kernel(const CorrParams P)
 {
     constexpr bool F32 = (DT == XCONV_F32);
     constexpr int BI = F32 ? 1 : 8;   // images per LDS unit
@@ -116,6 +119,8 @@ __global__ __launch_bounds__(kThreads, (MT <= 2 ? 2 : 1)) void corr_kernel(const
     using unit_t = typename std::conditional<F32, float, uint4>::type;
     using elem_t = typename std::conditional<F32, float, uint16_t>::type;
 
+#define XC_TRACE()
+    __builtin_amdgcn_s_setprio(2);
     extern __shared__ uint4 lds_raw[];
     unit_t *lds_a0 = reinterpret_cast<unit_t *>(lds_raw);          // dY tile
     unit_t *lds_b = lds_a0 + P.a_units;                            // ring of A rows
@@ -154,9 +159,10 @@ __global__ __launch_bounds__(kThreads, (MT <= 2 ? 2 : 1)) void corr_kernel(const
     // 65535 are never real) and an out-of-range load offset, so that the staging code below is
     // free of divergent early-outs: waits for the prefetched registers then sit in
     // unconditional code, where the compiler can count outstanding loads exactly.
-    uint32_t a_goff[NA];   // byte offset inside an image without the row part, or kOOR
+    uint32_t a_goff[NA];   // byte offset inside an image without the step's part, or kOOR
     int a_rbcc[NA];        // rb << 8 | cc
-    int a_lds[NA];         // LDS unit of (rb, ml) at slot 0
+    int a_lds[NA];         // LDS unit of (rb, ml) at slot 0; AL: of the task's first slot
+    bool a_st[NA];         // AL: the task has a place in the tile
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
         const int task = tid + i * kThreads;
@@ -167,21 +173,32 @@ __global__ __launch_bounds__(kThreads, (MT <= 2 ? 2 : 1)) void corr_kernel(const
         a_rbcc[i] = has ? ((rb << 8) | cc) : 255;
         a_goff[i] = (has && m0 + ml < P.C_out) ? ((uint32_t)(m0 + ml) * (uint32_t)P.dy_plane + (uint32_t)cc * EPV) * ES : kOOR;
         a_lds[i] = has ? (F32 ? (ml * P.ASTR + rb * P.CWp) : (rb * P.CWp * P.ASTR + ml)) : 0;
+        a_st[i] = has;
+        if constexpr (AL) {
+            if (has) a_goff[i] += (uint32_t)(rb * P.Wo) * ES;  // kOOR stays out of range
+            a_lds[i] += F32 ? cc * EPV : cc * EPV * P.ASTR;
+        }
     }
     // A task: (rr, c, jc) = row among the rows to load, staged column, vector of EPV channels
     const int JC = P.J_WG / EPV;
     const int ntask_b = P.NNEW * P.BWc * JC;
-    const int rotmul = 8 / (P.J_WG >> 4);  // 16-bit layout: rotation of each 16-column group (see b_unit)
-    int b_rrc[NB];         // rr << 16 | c
-    int b_jc[NB];
+    const int rotmul = 8 / (P.J_WG >> 4);  // 16-bit layout: rotation of each 16-column group (see b_store_task)
+    int b_rr[NB], b_c[NB];   // c = 65535 for a thread without a task: fails every column test
+    uint32_t b_goff[NB];     // byte offset of (row rr, column c, vector jc) from the step's first row and column
+    int b_lds[NB];           // LDS unit of (slot 0, column c, vector jc)
+    int b_rot[NB];           // 16-bit: first unit, inside the 16-column group, of the task's 8 columns
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
         const int task = tid + i * kThreads;
         const int jc = task % JC;
         const int c = (task / JC) % P.BWc;
         const int rr = task / (JC * P.BWc);
-        b_rrc[i] = (task < ntask_b) ? ((rr << 16) | c) : 0xffff;
-        b_jc[i] = (task < ntask_b) ? jc : 0;
+        const bool has = task < ntask_b;
+        b_rr[i] = has ? rr : 0;
+        b_c[i] = has ? c : 0xffff;
+        b_goff[i] = ((uint32_t)(rr * P.W + c) * (uint32_t)P.CS + (uint32_t)(jb + jc * EPV)) * ES;
+        b_lds[i] = F32 ? (c * P.BSTR + jc * 4) : (c * P.BSTR + 16 * (jc >> 1));
+        b_rot[i] = F32 ? 0 : (((jc & 1) * 8 + (jc >> 1) * rotmul) & 15);
     }
 
     uint4 ra[NA][BI];
@@ -211,12 +228,20 @@ __global__ __launch_bounds__(kThreads, (MT <= 2 ? 2 : 1)) void corr_kernel(const
         const int fs = sp.oy0 * P.Wo + sp.x0;  // flat index of the step's first pixel
         const __amdgpu_buffer_rsrc_t rs = rsrc_of(dY, sp.bg, dy_img_bytes, live);
         const int rows_left = P.Ho - sp.oy0;
+        const int cw_eff = (P.Wo - sp.x0) < P.CW ? (P.Wo - sp.x0) : P.CW;
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
             const int rb = a_rbcc[i] >> 8;
-            const uint32_t f0 = (uint32_t)(fs + rb * P.Wo);
-            uint32_t voff = a_goff[i] + ((f0 >> LOG_EPV) << 4);
-            voff = (rb < rows_left) ? voff : kOOR;
+            uint32_t voff;
+            if constexpr (AL) {
+                // chunks past the strip's last column read as zero: they are the tile's zero tail
+                voff = a_goff[i] + (uint32_t)fs * ES;
+                voff = (rb < rows_left && (a_rbcc[i] & 0xff) * EPV < cw_eff) ? voff : kOOR;
+            } else {
+                const uint32_t f0 = (uint32_t)(fs + rb * P.Wo);
+                voff = a_goff[i] + ((f0 >> LOG_EPV) << 4);
+                voff = (rb < rows_left) ? voff : kOOR;
+            }
 #pragma unroll
             for (int img = 0; img < BI; ++img) ra[i][img] = buf16(rs, voff + (uint32_t)img * dy_img_bytes);
         }
@@ -228,6 +253,24 @@ __global__ __launch_bounds__(kThreads, (MT <= 2 ? 2 : 1)) void corr_kernel(const
         const int fs = sp.oy0 * P.Wo + sp.x0;
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
+            if constexpr (AL) {
+                if constexpr (F32) {
+                    asm volatile("" : "+v"(ra[i][0].x), "+v"(ra[i][0].y), "+v"(ra[i][0].z), "+v"(ra[i][0].w));
+                    if (a_st[i]) *reinterpret_cast<uint4 *>(lds_a + a_lds[i]) = ra[i][0];
+                } else {
+                    uint32_t rows[8][4];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) { rows[q][0] = ra[i][q].x; rows[q][1] = ra[i][q].y; rows[q][2] = ra[i][q].z; rows[q][3] = ra[i][q].w; }
+                    uint4 cols[8];
+                    transpose_rows8<4>(rows, cols);
+                    uint4 *dst = lds_a + a_lds[i];
+                    if (a_st[i]) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) dst[e * P.ASTR] = cols[e];
+                    }
+                }
+                continue;
+            }
             const int rb = a_rbcc[i] >> 8, cc = a_rbcc[i] & 0xff;
             const int xs0 = cc * EPV - ((fs + rb * P.Wo) & (EPV - 1));  // slot of the chunk's first pixel (may be negative)
             if constexpr (F32) {
@@ -254,7 +297,7 @@ __global__ __launch_bounds__(kThreads, (MT <= 2 ? 2 : 1)) void corr_kernel(const
             }
         }
         // pixel slots past the strip's last column (up to CWp) take part in the MFMAs: keep them zero
-        const int ntail = P.CWp - cw_eff;
+        const int ntail = AL ? 0 : P.CWp - cw_eff;
         if (ntail > 0) {
             for (int t = tid; t < P.RB * ntail * P.M_WG; t += kThreads) {
                 const int ml = t % P.M_WG, q = t / P.M_WG;
@@ -266,11 +309,11 @@ __global__ __launch_bounds__(kThreads, (MT <= 2 ? 2 : 1)) void corr_kernel(const
     };
 
     // ---- A rows: global -> registers.  Rows are in padded coordinates (iy + ph).
-    auto b_load_task = [&](__amdgpu_buffer_rsrc_t rs, int xbase, int row_first, int rr, int c, int jc, uint4 (&dst)[BI]) {
-        const int iy = row_first + rr - P.ph;
-        const int ix = xbase + c;
-        const bool ok = (unsigned)iy < (unsigned)P.H && (unsigned)ix < (unsigned)P.W;
-        const uint32_t voff = ok ? ((uint32_t)(iy * P.W + ix) * (uint32_t)P.CS + (uint32_t)(jb + jc * EPV)) * ES : kOOR;
+    // iy0, ix0: input row and column of the task grid's origin (may be negative: padding)
+    auto b_load_task = [&](__amdgpu_buffer_rsrc_t rs, int iy0, int ix0, int rr, int c, uint32_t goff, uint4 (&dst)[BI]) {
+        const bool ok = (unsigned)(iy0 + rr) < (unsigned)P.H && (unsigned)(ix0 + c) < (unsigned)P.W;
+        const uint32_t base = (uint32_t)(iy0 * P.W + ix0) * ((uint32_t)P.CS * ES);  // wraps when negative; exact for every in-range pixel
+        const uint32_t voff = ok ? base + goff : kOOR;
 #pragma unroll
         for (int img = 0; img < BI; ++img) dst[img] = buf16(rs, voff + (uint32_t)img * a_img_bytes);
     };
@@ -278,11 +321,11 @@ __global__ __launch_bounds__(kThreads, (MT <= 2 ? 2 : 1)) void corr_kernel(const
     // the 16-column group G sits at 16G and is rotated by G*rotmul.  Fragment reads
     // (16 consecutive columns of one pixel) and staging writes (8 columns per lane,
     // lanes running over column chunks then pixels) are then both free of bank conflicts.
-    auto b_store_task = [&](int slot, int c, int jc, const uint4 (&src)[BI]) {
+    auto b_store_task = [&](int slot, int c, int lds0, int rot, const uint4 (&src)[BI]) {
         if constexpr (F32) {
             uint4 v = src[0];
             asm volatile("" : "+v"(v.x), "+v"(v.y), "+v"(v.z), "+v"(v.w));  // data arrives here, not inside a branch
-            float *dst = lds_b + (size_t)(slot * P.BWc + c) * P.BSTR + jc * 4;
+            float *dst = lds_b + slot * (P.BWc * P.BSTR) + lds0;
             if (c < P.BWc) *reinterpret_cast<uint4 *>(dst) = v;
         } else {
             uint32_t rows[8][4];
@@ -290,43 +333,44 @@ __global__ __launch_bounds__(kThreads, (MT <= 2 ? 2 : 1)) void corr_kernel(const
             for (int q = 0; q < 8; ++q) { rows[q][0] = src[q].x; rows[q][1] = src[q].y; rows[q][2] = src[q].z; rows[q][3] = src[q].w; }
             uint4 cols[8];
             transpose_rows8<4>(rows, cols);
-            const int G = jc >> 1;
-            uint4 *dst = lds_b + (size_t)(slot * P.BWc + c) * P.BSTR + 16 * G;
-            const int start = ((jc & 1) * 8 + G * rotmul) & 15;
+            uint4 *dst = lds_b + slot * (P.BWc * P.BSTR) + lds0;
             if (c < P.BWc) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) dst[(start + e) & 15] = cols[e];
+                for (int e = 0; e < 8; ++e) dst[(rot + e) & 15] = cols[e];
             }
         }
     };
     // rows the step loads in steady state: [oy0*sh + NOLD, oy0*sh + NR)
     auto b_load = [&](const StepPos &sp, bool live) {
         const __amdgpu_buffer_rsrc_t rs = rsrc_of(Ag, sp.bg, a_img_bytes, live);
-        const int row_first = sp.oy0 * P.sh + P.NOLD;
-        const int xbase = sp.x0 * P.sw - P.pw;
+        const int iy0 = sp.oy0 * P.sh + P.NOLD - P.ph;
+        const int ix0 = sp.x0 * P.sw - P.pw;
 #pragma unroll
-        for (int i = 0; i < NB; ++i) b_load_task(rs, xbase, row_first, b_rrc[i] >> 16, b_rrc[i] & 0xffff, b_jc[i], rbv[i]);
+        for (int i = 0; i < NB; ++i) b_load_task(rs, iy0, ix0, b_rr[i], b_c[i], b_goff[i], rbv[i]);
     };
     auto b_store = [&](const StepPos &sp) {
         const int rowmod = (sp.oy0 * P.sh + P.NOLD) % P.NR;
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
-            int slot = rowmod + (b_rrc[i] >> 16);
+            int slot = rowmod + b_rr[i];
             slot = slot >= P.NR ? slot - P.NR : slot;
-            b_store_task(slot, b_rrc[i] & 0xffff, b_jc[i], rbv[i]);
+            b_store_task(slot, b_c[i], b_lds[i], b_rot[i], rbv[i]);
         }
     };
     // rows [oy0*sh, oy0*sh + NOLD) that a step normally inherits from its predecessor
     auto b_fill_old = [&](const StepPos &sp) {
         const __amdgpu_buffer_rsrc_t rs = rsrc_of(Ag, sp.bg, a_img_bytes, true);
         const int row_first = sp.oy0 * P.sh;
-        const int xbase = sp.x0 * P.sw - P.pw;
+        const int ix0 = sp.x0 * P.sw - P.pw;
         const int ntask = P.NOLD * P.BWc * JC;
         for (int task = tid; task < ntask; task += kThreads) {
             const int jc = task % JC, c = (task / JC) % P.BWc, rr = task / (JC * P.BWc);
+            const uint32_t goff = ((uint32_t)(rr * P.W + c) * (uint32_t)P.CS + (uint32_t)(jb + jc * EPV)) * ES;
+            const int lds0 = F32 ? (c * P.BSTR + jc * 4) : (c * P.BSTR + 16 * (jc >> 1));
+            const int rot = F32 ? 0 : (((jc & 1) * 8 + (jc >> 1) * rotmul) & 15);
             uint4 tmp[BI];
-            b_load_task(rs, xbase, row_first, rr, c, jc, tmp);
-            b_store_task((row_first + rr) % P.NR, c, jc, tmp);
+            b_load_task(rs, row_first - P.ph, ix0, rr, c, goff, tmp);
+            b_store_task((row_first + rr) % P.NR, c, lds0, rot, tmp);
         }
     };
 
@@ -461,7 +505,13 @@ __global__ __launch_bounds__(kThreads, (MT <= 2 ? 2 : 1)) void corr_kernel(const
         a_load(spn, step + 1 < t_end);
         b_load(spn, step + 1 < t_end);
         pin_issued_loads();
+        // A wave that issues MFMAs back to back is always ready, and the issue arbiter then
+        // starves the vector, LDS and load instructions of the other waves on its SIMD (those of
+        // the second workgroup on the CU, which is staging while this one multiplies).  Everything
+        // but the MFMA loop runs at a raised priority so that staging slips in between MFMAs.
+        __builtin_amdgcn_s_setprio(0);
         compute_step(sp, lds_a0);
+        __builtin_amdgcn_s_setprio(2);
         prev = sp;
         sp = spn;
     }
@@ -668,6 +718,7 @@ static void fill_geometry(CorrParams &P, int dtype, int RB, int CW)
             if (need > nch) nch = need;
         }
     P.NCHR = nch;
+    P.AL = (P.Wo % EPV == 0 && CW % EPV == 0) ? 1 : 0;
     if (f32) {
         // dY tile [m][slot]: row stride = 4 mod 64 floats, so that the 16 rows x 4 slots of a
         // fragment read fall into 64 different banks; A tile [col][j]: column stride = 16 mod 64
@@ -810,27 +861,32 @@ size_t corr_partial_bytes(const CorrParams &P)
     return ((size_t)P.S + 1) * P.K2 * P.JP * P.MP * sizeof(float);
 }
 
-template <int DT, int MT, int NA, int NB, int NOFF> static hipError_t launch_corr_cfg(const CorrParams &P, size_t lds, hipStream_t st)
+template <int DT, int MT, int NA, int NB, int NOFF, bool AL>
+static hipError_t launch_corr_cfg(const CorrParams &P, size_t lds, hipStream_t st)
 {
     if (lds > 64 * 1024) {
         static bool done = false;  // per instantiation: the attribute sticks to the function
         static size_t done_bytes = 0;
         if (!done || lds > done_bytes) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(corr_kernel<DT, MT, NA, NB, NOFF>),
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(corr_kernel<DT, MT, NA, NB, NOFF, AL>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
             if (e != hipSuccess) return e;
             done = true;
             done_bytes = kLdsLimit;
         }
     }
-    hipLaunchKernelGGL((corr_kernel<DT, MT, NA, NB, NOFF>), dim3(P.S, P.NTM * P.NTJ, P.NOG), dim3(kThreads), lds, st, P);
+    hipLaunchKernelGGL((corr_kernel<DT, MT, NA, NB, NOFF, AL>), dim3(P.S, P.NTM * P.NTJ, P.NOG), dim3(kThreads), lds, st, P);
     return hipGetLastError();
 }
 
 template <int DT, int MT, int NA, int NB> static hipError_t launch_corr_noff(const CorrParams &P, size_t lds, hipStream_t st)
 {
-    if (P.K2 == 1) return launch_corr_cfg<DT, MT, NA, NB, 1>(P, lds, st);
-    return launch_corr_cfg<DT, MT, NA, NB, kMaxOff>(P, lds, st);
+    if (P.AL) {
+        if (P.K2 == 1) return launch_corr_cfg<DT, MT, NA, NB, 1, true>(P, lds, st);
+        return launch_corr_cfg<DT, MT, NA, NB, kMaxOff, true>(P, lds, st);
+    }
+    if (P.K2 == 1) return launch_corr_cfg<DT, MT, NA, NB, 1, false>(P, lds, st);
+    return launch_corr_cfg<DT, MT, NA, NB, kMaxOff, false>(P, lds, st);
 }
 
 template <int DT, int MT> static hipError_t launch_corr_16(const CorrParams &P, size_t lds, hipStream_t st)
