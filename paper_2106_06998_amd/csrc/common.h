@@ -112,4 +112,27 @@ struct CorrParams {
     int AL;            // every staged row segment of dY starts on a 16-byte vector
 };
 
+
+// ---- launch plan of the producer/consumer correlation kernel (16-bit storage) ----
+struct WsParams {
+    const void *dY;    // [B, C_out, Ho, Wo] storage dtype
+    const void *A;     // channels-last [B, H, W, CS] storage dtype
+    float *part;       // [S, K2, JP, MP] fp32 partial sums
+    int B, C_out, H, W, Ho, Wo;
+    int kH, kW, sh, sw, ph, pw;
+    int CS, NBG;            // channel stride of A; groups of 8 images
+    int CW, NSTRIP;         // output columns per strip, strips per output row
+    int CWs, NSUB;          // output columns per sub-step (multiple of 4), sub-steps per row-step
+    int BWc, NRING;         // staged columns per ring row; ring rows (kH + sh)
+    int WM, WJ, M_WG, J_WG, NTM, NTJ;
+    int S, NS;              // K-splits, row-steps in total (NBG * NSTRIP * Ho)
+    int K2, NOG, MP, JP;
+    int a_units;            // LDS units of one dY buffer (CWs * M_WG)
+    int b_row_units, BSTR;  // LDS units per ring row, per staged column (J_WG + 1)
+    int NA, NA_pad;         // dY tasks per sub-step and the same rounded up to whole waves
+    int TS, TB;             // A tasks per sub-step slice, per row-step (sh * BWc * J_WG/8)
+    int MT, NTASK;          // 16-row tiles per consumer wave; tasks per producer thread
+    int dbg_noload;         // timing experiments only: producers read through empty resources (zeros, no memory traffic)
+};
+
 }  // namespace xc

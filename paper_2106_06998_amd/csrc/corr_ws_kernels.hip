@@ -1,0 +1,695 @@
+// Offset-wise correlation (Algorithm 1, backward step 3 with the shift of step 4) for 16-bit
+// storage, as a producer/consumer kernel:
+//
+//   G[m,j,ky,kx] = sum_{b,oy,ox} dY[b,m,oy,ox] * A[b, oy*sh+ky-ph, ox*sw+kx-pw, j]
+//
+// Same mapping to the matrix cores as corr_kernel (corr_kernels.hip): the reduction index of
+// v_mfma_f32_16x16x32 is (8 consecutive images) x (4 pixel slots), one LDS unit (16 bytes)
+// holds the 8 images of one (pixel, channel), so kernel offsets and strides only select
+// which unit a lane reads.  What differs is who does what:
+//
+//   waves 0-3 (consumers)  only read fragments from LDS and issue MFMAs.  Each owns
+//                          MT*16 output channels x 16 columns x NOFF offsets.
+//   waves 4-7 (producers)  bring dY (NCHW) and A (channels-last) from global memory into the
+//                          unit form: eight 16-byte loads (one per image), an 8x8 transpose in
+//                          registers, eight LDS writes.  Loads run D sub-steps ahead of the
+//                          consumers and wait in registers, so HBM latency is covered by
+//                          several sub-steps of MFMA work instead of one.
+//
+// A row-step is one output row of one strip of 8 images; it is cut into NSUB sub-steps of CWs
+// output columns.  dY tiles are double-buffered per sub-step; the rows of A live in a ring of
+// kH + sh row slots, so the rows a row-step adds are written while the previous rows are
+// still being read.  One workgroup barrier per sub-step hands a dY buffer (and the ring rows
+// written meanwhile) from the producers to the consumers and the previous buffer back.  The
+// consumers run that barrier one k-step early: the fragments of the last k-step of a sub-step
+// are already in registers, so its MFMAs overlap the barrier and the first fragment reads of
+// the next sub-step.
+#include <type_traits>
+
+#include "common.h"
+#include "launch.h"
+
+namespace xc {
+
+namespace {
+
+constexpr int kWsThreads = 512;
+constexpr int kProducers = 256;
+constexpr uint32_t kOOR = 0x80000000u;  // beyond any buffer resource (a group of 8 images stays below 2^30 bytes)
+
+__device__ inline void ws_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Position of a sub-step; every field is wave-uniform.
+struct WsPos {
+    int u;       // sub-step inside the row-step
+    int y;       // output row
+    int strip;   // column strip
+    int bg;      // group of 8 images
+    int rowmod;  // (y * sh) mod NRING: ring slot of the first input row of the window
+    int t;       // row-step index
+};
+
+__device__ inline WsPos ws_uniform(WsPos p)
+{
+    p.u = __builtin_amdgcn_readfirstlane(p.u);
+    p.y = __builtin_amdgcn_readfirstlane(p.y);
+    p.strip = __builtin_amdgcn_readfirstlane(p.strip);
+    p.bg = __builtin_amdgcn_readfirstlane(p.bg);
+    p.rowmod = __builtin_amdgcn_readfirstlane(p.rowmod);
+    p.t = __builtin_amdgcn_readfirstlane(p.t);
+    return p;
+}
+
+__device__ inline WsPos ws_pos_of(const WsParams &P, int t)
+{
+    WsPos p;
+    p.t = t;
+    p.u = 0;
+    p.y = t % P.Ho;
+    const int q = t / P.Ho;
+    p.strip = q % P.NSTRIP;
+    p.bg = q / P.NSTRIP;
+    p.rowmod = (p.y * P.sh) % P.NRING;
+    return ws_uniform(p);
+}
+
+__device__ inline WsPos ws_next_row(const WsParams &P, WsPos p)
+{
+    ++p.t;
+    p.rowmod += P.sh;
+    while (p.rowmod >= P.NRING) p.rowmod -= P.NRING;
+    if (++p.y == P.Ho) {
+        p.y = 0;
+        p.rowmod = 0;
+        if (++p.strip == P.NSTRIP) {
+            p.strip = 0;
+            ++p.bg;
+        }
+    }
+    return p;
+}
+
+__device__ inline WsPos ws_advance(const WsParams &P, WsPos p)
+{
+    if (++p.u == P.NSUB) {
+        p.u = 0;
+        p = ws_next_row(P, p);
+    }
+    return ws_uniform(p);
+}
+
+// output columns of the sub-step that exist (the rest of its CWs slots is zero padding)
+__device__ inline int ws_cw_sub(const WsParams &P, const WsPos &p)
+{
+    const int x0 = p.strip * P.CW;
+    int cw = P.Wo - x0;
+    cw = cw < P.CW ? cw : P.CW;
+    cw -= p.u * P.CWs;
+    return cw < P.CWs ? cw : P.CWs;
+}
+
+}  // namespace
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// 32x32x16 MFMA on eight 16-bit values per lane.  This shape runs at the full matrix-core rate
+// from a single wave per SIMD; the 16x16x32 shape needs twice the issue slots per flop.
+template <int DT> __device__ inline f32x16 mfma32(const uint4 &a, const uint4 &b, f32x16 c)
+{
+    if constexpr (DT == XCONV_BF16)
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+
+// REUSE (3x3 offsets, column stride 1): a k-step covers two neighbouring pixel slots, so the
+// fragment of column offset kx = 2 of one k-step is the fragment of kx = 0 of the next one and
+// stays in registers.
+template <int DT, int NOFF, int NTASK, int D, bool REUSE>
+__global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
+{
+    extern __shared__ uint4 ws_lds[];
+    uint4 *lds_a = ws_lds;                    // two dY tiles [slot][M_WG]
+    uint4 *lds_b = ws_lds + 2 * P.a_units;    // ring of A rows [slot][column][BSTR]
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tm = blockIdx.y % P.NTM, tj = blockIdx.y / P.NTM;
+    const int m0 = tm * P.M_WG;
+    const int jb = tj * P.J_WG;
+    const int o_first = blockIdx.z * NOFF;
+    const int noff = (P.K2 - o_first) < NOFF ? (P.K2 - o_first) : NOFF;
+
+    const int t_begin = (int)(((long long)P.NS * blockIdx.x) / P.S);
+    const int t_end = (int)(((long long)P.NS * (blockIdx.x + 1)) / P.S);
+    const int NI = (t_end - t_begin) * P.NSUB;  // sub-steps of this workgroup
+    const int rotmul = 8 / (P.J_WG >> 4);
+
+    if (wave < 4) {
+        // =========================== consumers ===========================
+        // MFMA operands: A = dY units, lane (m = lane % 32, g = lane / 32) takes pixel slot 2q+g;
+        // B = A-tensor units, lane (j = lane % 32, g) takes the shifted pixel; D is 32 x 32.
+        const int l32 = lane & 31, g = lane >> 5;
+        const int wm = wave % P.WM, wj = wave / P.WM;
+        const int a_lane = g * P.M_WG + wm * 32 + l32;
+        const int G = 2 * wj + (l32 >> 4);  // 16-column group of this lane's column
+        const int b_lane = g * P.sw * P.BSTR + G * 16 + (((l32 & 15) + G * rotmul) & 15);
+
+        f32x16 acc[NOFF];
+#pragma unroll
+        for (int o = 0; o < NOFF; ++o)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[o][e] = 0.f;
+
+        int off_ky[NOFF], off_kx[NOFF];
+#pragma unroll
+        for (int o = 0; o < NOFF; ++o) {
+            const int oo = (o < noff) ? (o_first + o) : o_first;  // spare slots redo the first offset and are not written
+            off_ky[o] = oo / P.kW;
+            off_kx[o] = oo % P.kW;
+        }
+        auto set_brow = [&](const WsPos &p, int (&brow)[NOFF]) {
+#pragma unroll
+            for (int o = 0; o < NOFF; ++o) {
+                int slot = p.rowmod + off_ky[o];
+                slot = slot >= P.NRING ? slot - P.NRING : slot;
+                brow[o] = __builtin_amdgcn_readfirstlane(slot * P.b_row_units + off_kx[o] * P.BSTR);
+            }
+        };
+
+        if (NI > 0) {
+            WsPos pc = ws_pos_of(P, t_begin);
+            int brow[NOFF];
+            set_brow(pc, brow);
+            const int step_a = 2 * P.M_WG;            // LDS units between k-steps
+            const int step_b = 2 * P.sw * P.BSTR;
+
+            ws_barrier();  // the first dY tile and the rows of the first row-step are in LDS
+
+            // fragments of the k-step being multiplied, and where the fragments of the one after it are
+            uint4 a, b[NOFF];
+            const uint4 *pa = lds_a + a_lane;
+            const uint4 *pbo[NOFF];
+            {
+                const uint4 *pb = lds_b + (pc.u * P.CWs * P.sw) * P.BSTR + b_lane;
+                a = *pa;
+#pragma unroll
+                for (int o = 0; o < NOFF; ++o) {
+                    pbo[o] = pb + brow[o];
+                    b[o] = *pbo[o];
+                }
+            }
+            // One scheduling region per k-step: its MFMAs, the requests for the next k-step's
+            // fragments (A first, then the B fragment of an offset right after the MFMA that used
+            // the old one) and the address updates, so LDS latency and address arithmetic hide
+            // behind the MFMAs.  `fresh`: new row-step, REUSE has nothing to carry over.
+            auto kstep = [&](bool fresh) {
+                __builtin_amdgcn_sched_barrier(0);
+                const uint4 an = *pa;
+                if constexpr (REUSE) {
+#pragma unroll
+                    for (int o = 0; o < NOFF; o += 3) {
+                        acc[o] = mfma32<DT>(a, b[o], acc[o]);
+                        acc[o + 1] = mfma32<DT>(a, b[o + 1], acc[o + 1]);
+                        acc[o + 2] = mfma32<DT>(a, b[o + 2], acc[o + 2]);
+                        b[o] = b[o + 2];  // a plain register move: nothing waits on LDS here
+                        b[o + 1] = *pbo[o + 1];
+                        b[o + 2] = *pbo[o + 2];
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+#pragma unroll
+                    for (int o = 0; o < NOFF; o += 3) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 3, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                    }
+                } else {
+#pragma unroll
+                    for (int o = 0; o < NOFF; ++o) {
+                        acc[o] = mfma32<DT>(a, b[o], acc[o]);
+                        b[o] = *pbo[o];
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+#pragma unroll
+                    for (int o = 0; o < NOFF; ++o) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (REUSE) {
+                    if (fresh) {
+#pragma unroll
+                        for (int o = 0; o < NOFF; o += 3) b[o] = *pbo[o];
+                    }
+                }
+                a = an;
+            };
+
+            for (int i = 0; i < NI; ++i) {
+                const int nkq = (ws_cw_sub(P, pc) + 1) >> 1;
+                // k-steps whose successor lies in the same sub-step: constant address steps
+                auto kstep_same = [&]() {
+                    pa += step_a;
+#pragma unroll
+                    for (int o = 0; o < NOFF; ++o) pbo[o] += step_b;
+                    kstep(false);
+                };
+                // (unrolled by hand: inside straight-line code the compiler counts the outstanding
+                // LDS requests exactly, across a loop back-edge it waits for all of them)
+                int left = nkq - 1;
+                for (; left >= 4; left -= 4) {
+                    kstep_same();
+                    kstep_same();
+                    kstep_same();
+                    kstep_same();
+                }
+                if (left >= 2) {
+                    kstep_same();
+                    kstep_same();
+                    left -= 2;
+                }
+                if (left >= 1) kstep_same();
+                // The last k-step of the sub-step.  Its fragments were requested a whole k-step
+                // ago; once they are here the consumers no longer read sub-step i, so its buffer and
+                // the ring rows it alone used go back to the producers now, and the fragments
+                // requested during this k-step are those of the next sub-step.
+                bool fresh = true;
+                if (i + 1 < NI) {
+                    const WsPos pn = ws_advance(P, pc);
+                    if (pn.u == 0 && pn.y == 0) ws_barrier();  // run boundary: the producers refill the whole ring first
+                    ws_barrier();
+                    if (pn.t != pc.t) set_brow(pn, brow);
+                    fresh = pn.t != pc.t;
+                    pa = lds_a + ((i + 1) & 1) * P.a_units + a_lane;
+                    const uint4 *pb = lds_b + (pn.u * P.CWs * P.sw) * P.BSTR + b_lane;
+#pragma unroll
+                    for (int o = 0; o < NOFF; ++o) pbo[o] = pb + brow[o];
+                    pc = pn;
+                }
+                // (after the very last sub-step the requests repeat the current addresses)
+                kstep(fresh);
+            }
+        }
+
+
+        // D tile: lane (l32, g) holds column l32 and rows 8v + 4g .. 8v + 4g + 3 (v = 0..3)
+        const int jcol = jb + wj * 32 + l32;
+#pragma unroll
+        for (int o = 0; o < NOFF; ++o) {
+            if (o < noff) {
+                float *dst = P.part + (((size_t)blockIdx.x * P.K2 + (o_first + o)) * P.JP + jcol) * P.MP + m0 + wm * 32 + 4 * g;
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    *reinterpret_cast<f32x4 *>(dst + 8 * v) = f32x4{acc[o][4 * v], acc[o][4 * v + 1], acc[o][4 * v + 2], acc[o][4 * v + 3]};
+            }
+        }
+    } else {
+        // =========================== producers ===========================
+        __builtin_amdgcn_s_setprio(3);
+        const int p = tid - kProducers;
+        const uint16_t *dY = static_cast<const uint16_t *>(P.dY);
+        const uint16_t *Ag = static_cast<const uint16_t *>(P.A);
+        const int HoWo = P.Ho * P.Wo;
+        const uint32_t dy_img_bytes = (uint32_t)P.C_out * (uint32_t)HoWo * 2u;
+        const uint32_t a_img_bytes = (uint32_t)P.H * (uint32_t)P.W * (uint32_t)P.CS * 2u;
+        const int JC = P.J_WG >> 3;
+        const int jc_shift = JC == 8 ? 3 : (JC == 4 ? 2 : 1);
+
+        // Task slots of this thread.  Slots below NA_pad (whole waves) stage dY: output channel
+        // m = slot % M_WG, chunk of 8 columns slot / M_WG, so that the 64 lanes of a wave write
+        // 64 consecutive units of one pixel slot.  The remaining slots stage A.
+        bool is_a[NTASK];
+        uint32_t a_goff[NTASK];
+        int a_lds[NTASK], a_c8[NTASK], b_w[NTASK];
+#pragma unroll
+        for (int k = 0; k < NTASK; ++k) {
+            const int s = p + kProducers * k;
+            is_a[k] = __builtin_amdgcn_readfirstlane((int)(s < P.NA_pad)) != 0;
+            // chunk index fastest: neighbouring lanes read neighbouring 16-byte pieces of one
+            // (image, channel) row, which the memory pipeline merges into one request
+            const int nch = (P.CWs + 7) >> 3;
+            const int ch = s % nch, m = s / nch;
+            a_goff[k] = (s < P.NA && m0 + m < P.C_out) ? ((uint32_t)(m0 + m) * (uint32_t)HoWo + 8u * ch) * 2u : kOOR;
+            a_lds[k] = 8 * ch * P.M_WG + m;
+            a_c8[k] = 8 * ch;
+            b_w[k] = s - P.NA_pad;
+        }
+
+        auto rsrc_of = [&](const uint16_t *base, int bg, uint32_t img_bytes, bool live) {
+            bg = __builtin_amdgcn_readfirstlane(bg);
+            int left = P.B - bg * 8;
+            left = left < 8 ? left : 8;
+            left = (live && left > 0 && (P.dbg_noload & 1) == 0) ? left : 0;
+            left = __builtin_amdgcn_readfirstlane(left);
+            return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(base + (size_t)bg * 8 * (img_bytes / 2)), 0,
+                                                     (uint32_t)left * img_bytes, 0x00020000);
+        };
+        auto buf16 = [](__amdgpu_buffer_rsrc_t r, uint32_t voff) {
+            typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, 0, 0);
+            return uint4{v.x, v.y, v.z, v.w};
+        };
+
+        // A task `idx` of a row window: staged column c, row rr of the rows being added, 8-column
+        // vector jc.  pr0/slot0: padded input row and ring slot of rr = 0.
+        struct XtTask {
+            uint32_t voff;  // byte offset inside an image, or kOOR
+            int lds;        // LDS unit of the task's first column, before the rotation
+            int rot;
+        };
+        auto xt_task = [&](int idx, bool ok, int pr0, int slot0, int ix0) {
+            const int jc = idx & (JC - 1);
+            const int rem = idx >> jc_shift;
+            const int rr = rem / P.BWc;
+            const int c = rem - rr * P.BWc;
+            const int iy = pr0 + rr - P.ph, ix = ix0 + c;
+            const bool in = ok && (unsigned)iy < (unsigned)P.H && (unsigned)ix < (unsigned)P.W;
+            int slot = slot0 + rr;
+            while (slot >= P.NRING) slot -= P.NRING;
+            XtTask t;
+            t.voff = in ? ((uint32_t)(iy * P.W + ix) * (uint32_t)P.CS + (uint32_t)(jb + 8 * jc)) * 2u : kOOR;
+            t.lds = slot * P.b_row_units + c * P.BSTR + 16 * (jc >> 1);
+            t.rot = ((jc & 1) * 8 + (jc >> 1) * rotmul) & 15;
+            return t;
+        };
+        auto xt_store = [&](const XtTask &t, const uint4 (&src)[8]) {
+            uint32_t rows[8][4];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) { rows[q][0] = src[q].x; rows[q][1] = src[q].y; rows[q][2] = src[q].z; rows[q][3] = src[q].w; }
+            uint4 cols[8];
+            transpose_rows8<4>(rows, cols);
+            uint4 *dst = lds_b + t.lds;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) dst[(t.rot + e) & 15] = cols[e];
+        };
+
+        // The rows of A that sub-step `ps` brings in, as (row-step they belong to, slice).
+        // One slice per sub-step: with a single sub-step per row-step the row-step's own new
+        // rows; otherwise sub-step 0 brings the last slice of its own row-step and sub-step
+        // u >= 1 slice u-1 of the next row-step (which reads them one row-step later).
+        struct XtPlan {
+            bool on;
+            int slice, pr0, slot0, ix0;
+        };
+        auto xt_plan = [&](const WsPos &ps) {
+            XtPlan x;
+            int y = ps.y, rowmod = ps.rowmod;
+            x.on = true;
+            x.slice = 0;
+            if (P.NSUB > 1) {
+                if (ps.u == 0) {
+                    x.slice = P.NSUB - 1;
+                } else {
+                    x.slice = ps.u - 1;
+                    x.on = (ps.y + 1 < P.Ho) && (ps.t + 1 < t_end);
+                    y = ps.y + 1;
+                    rowmod += P.sh;
+                    while (rowmod >= P.NRING) rowmod -= P.NRING;
+                }
+            }
+            x.pr0 = y * P.sh + P.kH - P.sh;  // first of the sh rows that this row-step adds (kH <= sh: all of them start at 0)
+            int slot0 = rowmod + P.kH - P.sh;
+            if (P.kH < P.sh) { x.pr0 = y * P.sh; slot0 = rowmod; }
+            while (slot0 >= P.NRING) slot0 -= P.NRING;
+            x.slot0 = slot0;
+            x.ix0 = ps.strip * P.CW * P.sw - P.pw;
+            x.on = __builtin_amdgcn_readfirstlane((int)x.on) != 0;
+            x.slice = __builtin_amdgcn_readfirstlane(x.slice);
+            x.pr0 = __builtin_amdgcn_readfirstlane(x.pr0);
+            x.slot0 = __builtin_amdgcn_readfirstlane(x.slot0);
+            x.ix0 = __builtin_amdgcn_readfirstlane(x.ix0);
+            return x;
+        };
+
+        // ---- global -> registers for sub-step ps --------------------------------------
+        auto issue = [&](const WsPos &ps, bool live, uint4 (&r)[NTASK][8]) {
+            const int cw_sub = ws_cw_sub(P, ps);
+            const uint32_t fs = (uint32_t)(ps.y * P.Wo + ps.strip * P.CW + ps.u * P.CWs) * 2u;
+            const __amdgpu_buffer_rsrc_t rsA = rsrc_of(dY, ps.bg, dy_img_bytes, live);
+            const XtPlan x = xt_plan(ps);
+            const __amdgpu_buffer_rsrc_t rsB = rsrc_of(Ag, ps.bg, a_img_bytes, live && x.on);
+#pragma unroll
+            for (int k = 0; k < NTASK; ++k) {
+                uint32_t voff;
+                uint32_t stride;
+                __amdgpu_buffer_rsrc_t rs;
+                if (is_a[k]) {
+                    voff = (a_goff[k] != kOOR && a_c8[k] < cw_sub) ? a_goff[k] + fs : kOOR;
+                    stride = dy_img_bytes;
+                    rs = rsA;
+                } else {
+                    const int idx = x.slice * P.TS + b_w[k];
+                    const XtTask t = xt_task(idx, b_w[k] < P.TS && idx < P.TB, x.pr0, x.slot0, x.ix0);
+                    voff = t.voff;
+                    stride = a_img_bytes;
+                    rs = rsB;
+                }
+#pragma unroll
+                for (int img = 0; img < 8; ++img) r[k][img] = buf16(rs, voff + (uint32_t)img * stride);
+            }
+        };
+        // ---- registers -> LDS for sub-step ps (buffer `buf` of the dY tiles) ------------
+        auto write = [&](const WsPos &ps, int buf, const uint4 (&r)[NTASK][8]) {
+            const int cw_sub = ws_cw_sub(P, ps);
+            const XtPlan x = xt_plan(ps);
+#pragma unroll
+            for (int k = 0; k < NTASK; ++k) {
+                if (is_a[k]) {
+                    uint32_t rows[8][4];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) { rows[q][0] = r[k][q].x; rows[q][1] = r[k][q].y; rows[q][2] = r[k][q].z; rows[q][3] = r[k][q].w; }
+                    uint4 cols[8];
+                    transpose_rows8<4>(rows, cols);
+                    uint4 *dst = lds_a + buf * P.a_units + a_lds[k];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int slot = a_c8[k] + e;
+                        // columns past the end of the row take part in the MFMAs: they must be zero
+                        const uint4 v = slot < cw_sub ? cols[e] : uint4{0u, 0u, 0u, 0u};
+                        if (slot < P.CWs) dst[e * P.M_WG] = v;
+                    }
+                } else if (x.on) {
+                    const int idx = x.slice * P.TS + b_w[k];
+                    if (b_w[k] < P.TS && idx < P.TB) {
+                        const XtTask t = xt_task(idx, true, x.pr0, x.slot0, x.ix0);
+                        xt_store(t, r[k]);
+                    }
+                }
+            }
+        };
+        // ---- every row of the window of row-step ps, loaded and written at once (start of a run)
+        auto prime = [&](const WsPos &ps) {
+            const __amdgpu_buffer_rsrc_t rsB = rsrc_of(Ag, ps.bg, a_img_bytes, true);
+            const int total = P.kH * P.BWc * JC;
+            const int pr0 = ps.y * P.sh, slot0 = ps.rowmod, ix0 = ps.strip * P.CW * P.sw - P.pw;
+            for (int base = 0; base < total; base += 2 * kProducers) {
+                uint4 r0[8], r1[8];
+                const int i0 = base + p, i1 = base + kProducers + p;
+                const XtTask t0 = xt_task(i0, i0 < total, pr0, slot0, ix0);
+                const XtTask t1 = xt_task(i1, i1 < total, pr0, slot0, ix0);
+#pragma unroll
+                for (int img = 0; img < 8; ++img) r0[img] = buf16(rsB, t0.voff + (uint32_t)img * a_img_bytes);
+#pragma unroll
+                for (int img = 0; img < 8; ++img) r1[img] = buf16(rsB, t1.voff + (uint32_t)img * a_img_bytes);
+                if (i0 < total) xt_store(t0, r0);
+                if (i1 < total) xt_store(t1, r1);
+            }
+        };
+
+        if (NI > 0) {
+            WsPos pw = ws_pos_of(P, t_begin);  // sub-step whose data is written next
+            WsPos pi = pw;                     // sub-step whose loads are issued next
+            uint4 st[D][NTASK][8];
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                issue(pi, d < NI, st[d]);
+                pi = ws_advance(P, pi);
+            }
+            if (!(P.dbg_noload & 2)) prime(pw);
+            for (int i0 = 0; i0 < NI; i0 += D) {
+#pragma unroll
+                for (int d = 0; d < D; ++d) {
+                    const int i = i0 + d;
+                    if (i < NI) {
+                        if (i > 0 && pw.u == 0 && pw.y == 0) {
+                            ws_barrier();  // the consumers have left the previous run: its ring rows are free
+                            prime(pw);
+                        }
+                        if (!(P.dbg_noload & 2)) write(pw, i & 1, st[d]);
+                        if (!(P.dbg_noload & 4)) issue(pi, i + D < NI, st[d]);
+                        pw = ws_advance(P, pw);
+                        pi = ws_advance(P, pi);
+                        ws_barrier();
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host: launch plan
+// ---------------------------------------------------------------------------
+static int ws_env_int(const char *name, int dflt)
+{
+    const char *v = getenv(name);
+    return (v && *v) ? atoi(v) : dflt;
+}
+
+static const size_t kWsLdsLimit = 160 * 1024;
+
+size_t corr_ws_lds_bytes(const WsParams &P)
+{
+    return ((size_t)2 * P.a_units + (size_t)P.NRING * P.b_row_units) * 16;
+}
+
+// Fills the step geometry for a strip width CW cut into NSUB sub-steps; false if it does not fit.
+static bool ws_geometry(WsParams &P, int CW, int NSUB)
+{
+    P.CW = CW;
+    P.NSTRIP = ceil_div(P.Wo, CW);
+    P.NSUB = NSUB;
+    P.CWs = round_up(ceil_div(CW, NSUB), 4);
+    if ((NSUB - 1) * P.CWs >= CW) return false;  // an empty last sub-step
+    if (NSUB > 1 && P.NSTRIP > 1) return false;  // sub-steps only for whole rows
+    P.BWc = (round_up(CW, 4) - 1) * P.sw + P.kW;
+    P.NRING = P.kH + P.sh;
+    P.a_units = P.CWs * P.M_WG;
+    P.BSTR = P.J_WG;  // pixel stride = whole 256-byte bank rows: the four pixel slots of a fragment read then fall on the same banks, which is what ds_read_b128 wants
+    P.b_row_units = P.BWc * P.BSTR;
+    P.NA = P.M_WG * ceil_div(P.CWs, 8);
+    P.NA_pad = round_up(P.NA, 64);
+    const int rows_new = P.sh < P.kH ? P.sh : P.kH;
+    P.TB = rows_new * P.BWc * (P.J_WG / 8);
+    P.TS = ceil_div(P.TB, NSUB);
+    P.NTASK = ceil_div(P.NA_pad + P.TS, kProducers);
+    P.NS = P.NBG * P.NSTRIP * P.Ho;
+    if (corr_ws_lds_bytes(P) > kWsLdsLimit) return false;
+    if (P.NTASK > 3) return false;
+    return true;
+}
+
+bool plan_corr_ws(WsParams &P, int dtype, int B, int C_out, int H, int W, int kH, int kW, int sh, int sw, int ph, int pw, int CS)
+{
+    if (dtype == XCONV_F32) return false;
+    if (ws_env_int("XCONV_CORR_WS", 1) == 0) return false;
+    P = WsParams{};
+    P.B = B; P.C_out = C_out; P.H = H; P.W = W;
+    P.kH = kH; P.kW = kW; P.sh = sh; P.sw = sw; P.ph = ph; P.pw = pw;
+    P.Ho = (H + 2 * ph - kH) / sh + 1;
+    P.Wo = (W + 2 * pw - kW) / sw + 1;
+    P.CS = CS;
+    P.NBG = ceil_div(B, 8);
+    P.dbg_noload = ws_env_int("XCONV_WS_NOLOAD", 0);
+    P.K2 = kH * kW;
+    if (P.K2 == 1) return false;          // 1x1 kernels have no halo to share: corr_kernel handles them
+    if (kH > sh + 8 || sh > 8) return false;
+    if (P.Wo % 2 != 0) return false;      // row starts of dY must be 4-byte aligned
+    P.NOG = ceil_div(P.K2, 9);
+    // a group of 8 images is addressed with 32-bit byte offsets
+    if ((long long)8 * C_out * P.Ho * P.Wo * 2 > (1LL << 30) || (long long)8 * H * W * CS * 2 > (1LL << 30)) return false;
+
+    // consumer waves: each owns 32 output channels x 32 columns; along the columns of A first
+    // (those waves share the dY tile), WM * WJ = 4
+    if (CS % 32 != 0) return false;
+    const int nwj = CS / 32;
+    int WJ = (nwj % 2 == 0) ? 2 : 1;
+    if (C_out <= 32 && nwj % 4 == 0) WJ = 4;
+    WJ = ws_env_int("XCONV_WS_WJ", WJ);
+    if (WJ != 1 && WJ != 2 && WJ != 4) return false;
+    if (nwj % WJ != 0) return false;
+    const int WM = 4 / WJ;
+    P.WM = WM; P.WJ = WJ; P.MT = 1;
+    P.M_WG = WM * 32;
+    P.J_WG = WJ * 32;
+    P.NTM = ceil_div(C_out, P.M_WG);
+    P.NTJ = CS / P.J_WG;
+    P.MP = P.NTM * P.M_WG;
+    P.JP = CS;
+
+    // whole rows cut into sub-steps if the ring fits, else column strips
+    bool found = false;
+    const int fCW = ws_env_int("XCONV_WS_CW", 0), fNSUB = ws_env_int("XCONV_WS_NSUB", 0);
+    if (fCW > 0 && fNSUB > 0) {
+        found = ws_geometry(P, fCW, fNSUB);
+    } else {
+        WsParams best = P;
+        int best_ntask = 99, best_cws = 0;
+        for (int nsub = 1; nsub <= 8; ++nsub) {
+            WsParams Q = P;
+            if (!ws_geometry(Q, P.Wo, nsub)) continue;
+            if (Q.CWs > 32) continue;
+            if (Q.NTASK < best_ntask || (Q.NTASK == best_ntask && Q.CWs > best_cws)) { best = Q; best_ntask = Q.NTASK; best_cws = Q.CWs; found = true; }
+        }
+        if (!found) {
+            for (int cw = 32; cw >= 8; cw -= 4) {
+                if (cw >= P.Wo) continue;
+                WsParams Q = P;
+                if (!ws_geometry(Q, cw, 1)) continue;
+                // prefer few tasks per thread, then little padding in the last strip, then wide strips
+                const int waste = Q.NSTRIP * round_up(cw, 4) - P.Wo;
+                const int score = Q.NTASK * 1000 + waste * 10 - cw / 4;
+                if (!found || score < best_ntask) { best = Q; best_ntask = score; found = true; }
+            }
+        }
+        if (found) P = best;
+    }
+    if (!found) return false;
+
+    // K-split: one workgroup per compute unit
+    const int ny = P.NTM * P.NTJ * P.NOG;
+    int target = ws_env_int("XCONV_WS_SPLITS", 0);
+    if (target <= 0) {
+        target = 256 / ny;
+        if (target < 1) target = 1;
+        if (target > P.NS) target = P.NS;
+        int bestS = target;
+        double best_eff = 0.0;
+        for (int S = target; S >= 1 && S >= target * 3 / 4; --S) {
+            const double eff = (double)P.NS / ((double)S * ceil_div(P.NS, S)) * ((double)S / target);
+            if (eff > best_eff + 1e-9) { best_eff = eff; bestS = S; }
+        }
+        target = bestS;
+    }
+    if (target > P.NS) target = P.NS;
+    if (target < 1) target = 1;
+    P.S = target;
+    return true;
+}
+
+template <int DT, int NTASK, int D, bool REUSE>
+static hipError_t launch_ws_cfg(const WsParams &P, hipStream_t st)
+{
+    const size_t lds = corr_ws_lds_bytes(P);
+    static bool done = false;  // per instantiation: the attribute sticks to the function
+    if (!done && lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(corr_ws_kernel<DT, 9, NTASK, D, REUSE>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kWsLdsLimit);
+        if (e != hipSuccess) return e;
+        done = true;
+    }
+    hipLaunchKernelGGL((corr_ws_kernel<DT, 9, NTASK, D, REUSE>), dim3(P.S, P.NTM * P.NTJ, P.NOG), dim3(kWsThreads), lds, st, P);
+    return hipGetLastError();
+}
+
+template <int DT, bool REUSE> static hipError_t launch_ws_dt(const WsParams &P, hipStream_t st)
+{
+    switch (P.NTASK) {
+    case 1: return launch_ws_cfg<DT, 1, 3, REUSE>(P, st);
+    case 2: return launch_ws_cfg<DT, 2, 2, REUSE>(P, st);
+    default: return launch_ws_cfg<DT, 3, 2, REUSE>(P, st);
+    }
+}
+
+hipError_t launch_corr_ws(int dtype, const WsParams &P, hipStream_t st)
+{
+    const bool reuse = P.sw == 1 && P.kW == 3 && P.K2 == 9 && ws_env_int("XCONV_WS_REUSE", 1) != 0;
+    if (dtype == XCONV_BF16) return reuse ? launch_ws_dt<XCONV_BF16, true>(P, st) : launch_ws_dt<XCONV_BF16, false>(P, st);
+    return reuse ? launch_ws_dt<XCONV_F16, true>(P, st) : launch_ws_dt<XCONV_F16, false>(P, st);
+}
+
+}  // namespace xc

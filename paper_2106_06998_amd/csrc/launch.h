@@ -34,4 +34,11 @@ hipError_t launch_reduce(const CorrParams &P, hipStream_t st);
 // dW[m,n,o] = T[o,n,m]                          (Z == nullptr, exact path)
 hipError_t launch_expand(const CorrParams &P, const float *Z, float *dW, int C_in, int r, hipStream_t st);
 
+
+// corr_ws_kernels.hip: producer/consumer variant for 16-bit storage.  plan_corr_ws returns
+// false when the layer does not fit it (the caller then uses plan_corr / launch_corr).
+bool plan_corr_ws(WsParams &P, int dtype, int B, int C_out, int H, int W, int kH, int kW, int sh, int sw, int ph, int pw, int CS);
+size_t corr_ws_lds_bytes(const WsParams &P);
+hipError_t launch_corr_ws(int dtype, const WsParams &P, hipStream_t st);
+
 }  // namespace xc

@@ -69,13 +69,15 @@ struct PlanKey {
 };
 struct PlanEntry {
     PlanKey key;
-    CorrParams P;
+    CorrParams P;   // launch plan of corr_kernel; with `ws` only the fields the reduction and expansion read
+    WsParams Wp;    // launch plan of corr_ws_kernel when `ws`
+    bool ws;
     bool ok;
 };
 std::mutex g_plan_mu;
 std::vector<PlanEntry> g_plans;
 
-bool get_plan(CorrParams &P, int dtype, int B, int C_out, int H, int W, int kH, int kW, int sh, int sw, int ph, int pw, int CS,
+bool get_plan(PlanEntry &out, int dtype, int B, int C_out, int H, int W, int kH, int kW, int sh, int sw, int ph, int pw, int CS,
               bool dy_aligned)
 {
     PlanKey k{{dtype, B, C_out, H, W, kH, kW, sh, sw, ph, pw, CS, dy_aligned ? 1 : 0, 0}};
@@ -83,15 +85,26 @@ bool get_plan(CorrParams &P, int dtype, int B, int C_out, int H, int W, int kH, 
         std::lock_guard<std::mutex> lk(g_plan_mu);
         for (const PlanEntry &e : g_plans)
             if (e.key == k) {
-                P = e.P;
+                out = e;
                 return e.ok;
             }
     }
     PlanEntry e;
     e.key = k;
     e.P = CorrParams{};
-    e.ok = plan_corr(e.P, dtype, B, C_out, H, W, kH, kW, sh, sw, ph, pw, CS, dy_aligned);
-    P = e.P;
+    e.Wp = WsParams{};
+    // the producer/consumer kernel reads dY in place, so the caller's planes must be usable as they are
+    e.ws = dy_aligned && plan_corr_ws(e.Wp, dtype, B, C_out, H, W, kH, kW, sh, sw, ph, pw, CS);
+    if (e.ws) {
+        e.ok = true;
+        e.P.C_out = C_out;
+        e.P.S = e.Wp.S; e.P.NS = e.Wp.NS;
+        e.P.K2 = e.Wp.K2; e.P.JP = e.Wp.JP; e.P.MP = e.Wp.MP;
+        e.P.Ho = e.Wp.Ho; e.P.Wo = e.Wp.Wo;
+    } else {
+        e.ok = plan_corr(e.P, dtype, B, C_out, H, W, kH, kW, sh, sw, ph, pw, CS, dy_aligned);
+    }
+    out = e;
     std::lock_guard<std::mutex> lk(g_plan_mu);
     if (g_plans.size() >= 64) g_plans.erase(g_plans.begin());
     g_plans.push_back(e);
@@ -150,18 +163,18 @@ size_t xconv_workspace_bytes(const xconv_desc *d, int op)
 {
     if (xconv_check_desc(d) != XCONV_OK) return 0;
     if (op == XCONV_OP_PROBE) return z_bytes(d) + zfrag_bytes(d);
-    CorrParams P;
+    PlanEntry E;
     if (op == XCONV_OP_ESTIMATE) {
-        if (!get_plan(P, d->dtype, d->B, d->C_out, d->H, d->W, d->kH, d->kW, d->stride_h, d->stride_w, d->pad_h, d->pad_w,
+        if (!get_plan(E, d->dtype, d->B, d->C_out, d->H, d->W, d->kH, d->kW, d->stride_h, d->stride_w, d->pad_h, d->pad_w,
                       round_up(d->r, 16), true))
             return 0;
-        return z_bytes(d) + align_up(corr_partial_bytes(P), 256) + dy_repack_bytes(d);
+        return z_bytes(d) + align_up(corr_partial_bytes(E.P), 256) + dy_repack_bytes(d);
     }
     if (op == XCONV_OP_EXACT) {
         const int CSx = round_up(d->C_in, 16);
-        if (!get_plan(P, d->dtype, d->B, d->C_out, d->H, d->W, d->kH, d->kW, d->stride_h, d->stride_w, d->pad_h, d->pad_w, CSx, true))
+        if (!get_plan(E, d->dtype, d->B, d->C_out, d->H, d->W, d->kH, d->kW, d->stride_h, d->stride_w, d->pad_h, d->pad_w, CSx, true))
             return 0;
-        return align_up((size_t)d->B * d->H * d->W * CSx * elem_bytes(d->dtype), 256) + align_up(corr_partial_bytes(P), 256) + dy_repack_bytes(d);
+        return align_up((size_t)d->B * d->H * d->W * CSx * elem_bytes(d->dtype), 256) + align_up(corr_partial_bytes(E.P), 256) + dy_repack_bytes(d);
     }
     return 0;
 }
@@ -233,10 +246,11 @@ xconv_status xconv_dw_estimate(const xconv_desc *d, const void *dY_dev, const vo
     if (!Z_dev && d->probe == XCONV_USER_Z) return XCONV_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int CS = round_up(d->r, 16);
-    CorrParams P;
-    if (!get_plan(P, d->dtype, d->B, d->C_out, d->H, d->W, d->kH, d->kW, d->stride_h, d->stride_w, d->pad_h, d->pad_w, CS,
+    PlanEntry E;
+    if (!get_plan(E, d->dtype, d->B, d->C_out, d->H, d->W, d->kH, d->kW, d->stride_h, d->stride_w, d->pad_h, d->pad_w, CS,
                   aligned16(dY_dev)))
         return XCONV_EUNSUPPORTED;
+    CorrParams &P = E.P;
     const size_t zb = z_bytes(d), pb = align_up(corr_partial_bytes(P), 256), rb = dy_repack_bytes(d);
     if (ws_bytes < zb + pb + rb) return XCONV_EWORKSPACE;
     const float *Z = Z_dev;
@@ -246,14 +260,21 @@ xconv_status xconv_dw_estimate(const xconv_desc *d, const void *dY_dev, const vo
         Z = zw;
     }
     P.dY = dY_dev;
-    if (rb) {
+    if (rb && !E.ws) {
         void *packed = static_cast<char *>(ws_dev) + zb + pb;
         XC_LAUNCH(K_REPACK, st, launch_repack_planes(d->dtype, dY_dev, packed, (long long)d->B * d->C_out, P.Ho * P.Wo, dy_pitch(d), st));
         P.dY = packed;
     }
     P.A = Xt_dev;
     P.part = reinterpret_cast<float *>(static_cast<char *>(ws_dev) + zb);
-    XC_LAUNCH(K_CORR, st, launch_corr(d->dtype, P, st));
+    if (E.ws) {
+        E.Wp.dY = dY_dev;
+        E.Wp.A = Xt_dev;
+        E.Wp.part = P.part;
+        XC_LAUNCH(K_CORR, st, launch_corr_ws(d->dtype, E.Wp, st));
+    } else {
+        XC_LAUNCH(K_CORR, st, launch_corr(d->dtype, P, st));
+    }
     XC_LAUNCH(K_REDUCE, st, launch_reduce(P, st));
     XC_LAUNCH(K_EXPAND, st, launch_expand(P, Z, dW_dev, d->C_in, d->r, st));
     return XCONV_OK;
@@ -270,22 +291,30 @@ xconv_status xconv_dw_exact(const xconv_desc *d, const void *dY_dev, const void 
     if (!aligned16(dY_dev) || (reinterpret_cast<uintptr_t>(X_dev) & (eb - 1)) != 0) return XCONV_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int CSx = round_up(d->C_in, 16), HW = d->H * d->W;
-    CorrParams P;
-    if (!get_plan(P, d->dtype, d->B, d->C_out, d->H, d->W, d->kH, d->kW, d->stride_h, d->stride_w, d->pad_h, d->pad_w, CSx,
+    PlanEntry E;
+    if (!get_plan(E, d->dtype, d->B, d->C_out, d->H, d->W, d->kH, d->kW, d->stride_h, d->stride_w, d->pad_h, d->pad_w, CSx,
                   aligned16(dY_dev)))
         return XCONV_EUNSUPPORTED;
+    CorrParams &P = E.P;
     const size_t xb = align_up((size_t)d->B * HW * CSx * eb, 256), pb = align_up(corr_partial_bytes(P), 256), rb = dy_repack_bytes(d);
     if (ws_bytes < xb + pb + rb) return XCONV_EWORKSPACE;
     XC_LAUNCH(K_TO_NHWC, st, launch_to_nhwc(d->dtype, X_dev, ws_dev, d->B, d->C_in, HW, CSx, st));
     P.dY = dY_dev;
-    if (rb) {
+    if (rb && !E.ws) {
         void *packed = static_cast<char *>(ws_dev) + xb + pb;
         XC_LAUNCH(K_REPACK, st, launch_repack_planes(d->dtype, dY_dev, packed, (long long)d->B * d->C_out, P.Ho * P.Wo, dy_pitch(d), st));
         P.dY = packed;
     }
     P.A = ws_dev;
     P.part = reinterpret_cast<float *>(static_cast<char *>(ws_dev) + xb);
-    XC_LAUNCH(K_CORR, st, launch_corr(d->dtype, P, st));
+    if (E.ws) {
+        E.Wp.dY = dY_dev;
+        E.Wp.A = ws_dev;
+        E.Wp.part = P.part;
+        XC_LAUNCH(K_CORR, st, launch_corr_ws(d->dtype, E.Wp, st));
+    } else {
+        XC_LAUNCH(K_CORR, st, launch_corr(d->dtype, P, st));
+    }
     XC_LAUNCH(K_REDUCE, st, launch_reduce(P, st));
     XC_LAUNCH(K_EXPAND, st, launch_expand(P, nullptr, dW_dev, d->C_in, d->r, st));
     return XCONV_OK;
@@ -297,9 +326,17 @@ xconv_status xconv_plan_info(const xconv_desc *d, int op, int32_t *out)
     if (s != XCONV_OK) return s;
     if (!out || (op != XCONV_OP_ESTIMATE && op != XCONV_OP_EXACT)) return XCONV_EINVAL;
     const int CS = round_up(op == XCONV_OP_ESTIMATE ? d->r : d->C_in, 16);
-    CorrParams P;
-    if (!get_plan(P, d->dtype, d->B, d->C_out, d->H, d->W, d->kH, d->kW, d->stride_h, d->stride_w, d->pad_h, d->pad_w, CS, true))
+    PlanEntry E;
+    if (!get_plan(E, d->dtype, d->B, d->C_out, d->H, d->W, d->kH, d->kW, d->stride_h, d->stride_w, d->pad_h, d->pad_w, CS, true))
         return XCONV_EUNSUPPORTED;
+    if (E.ws) {
+        const WsParams &Q = E.Wp;
+        const int32_t v[16] = {Q.S, Q.NS, 1, Q.CW, Q.WM, Q.WJ, 1, Q.M_WG, Q.J_WG, (int32_t)corr_ws_lds_bytes(Q),
+                               Q.NTM, Q.NTJ, Q.NOG, Q.CS, Q.NSUB, 1};
+        for (int i = 0; i < 16; ++i) out[i] = v[i];
+        return XCONV_OK;
+    }
+    const CorrParams &P = E.P;
     const int32_t v[16] = {P.S, P.NS, P.RB, P.CW, P.WM, P.WJ, P.WK, P.M_WG, P.J_WG, (int32_t)corr_lds_bytes(d->dtype, P),
                            P.NTM, P.NTJ, P.NOG, P.CS, P.NCHR, 0};
     for (int i = 0; i < 16; ++i) out[i] = v[i];
