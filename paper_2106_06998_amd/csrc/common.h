@@ -132,7 +132,6 @@ struct WsParams {
     int NA, NA_pad;         // dY tasks per sub-step and the same rounded up to whole waves
     int TS, TB;             // A tasks per sub-step slice, per row-step (sh * BWc * J_WG/8)
     int MT, NTASK;          // 16-row tiles per consumer wave; tasks per producer thread
-    int dbg_noload;         // timing experiments only: producers read through empty resources (zeros, no memory traffic)
 };
 
 }  // namespace xc

@@ -3,13 +3,15 @@
 //
 //   G[m,j,ky,kx] = sum_{b,oy,ox} dY[b,m,oy,ox] * A[b, oy*sh+ky-ph, ox*sw+kx-pw, j]
 //
-// Same mapping to the matrix cores as corr_kernel (corr_kernels.hip): the reduction index of
-// v_mfma_f32_16x16x32 is (8 consecutive images) x (4 pixel slots), one LDS unit (16 bytes)
-// holds the 8 images of one (pixel, channel), so kernel offsets and strides only select
-// which unit a lane reads.  What differs is who does what:
+// As in corr_kernel (corr_kernels.hip) the reduction index is packed along the batch: one LDS
+// unit (16 bytes) holds the 8 images of one (pixel, channel), so kernel offsets and strides
+// only select which unit a lane reads.  Here the matrix instruction is v_mfma_f32_32x32x16
+// (reduction = 8 images x 2 neighbouring pixel slots): measured on MI355X it reaches the full
+// matrix-core rate from one wave per SIMD, the 16x16x32 shape only half of it.  Work is split
+// by role:
 //
 //   waves 0-3 (consumers)  only read fragments from LDS and issue MFMAs.  Each owns
-//                          MT*16 output channels x 16 columns x NOFF offsets.
+//                          32 output channels x 32 columns x NOFF offsets (NOFF 32x32 tiles).
 //   waves 4-7 (producers)  bring dY (NCHW) and A (channels-last) from global memory into the
 //                          unit form: eight 16-byte loads (one per image), an 8x8 transpose in
 //                          registers, eight LDS writes.  Loads run D sub-steps ahead of the
@@ -125,10 +127,7 @@ template <int DT> __device__ inline f32x16 mfma32(const uint4 &a, const uint4 &b
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
 }
 
-// REUSE (3x3 offsets, column stride 1): a k-step covers two neighbouring pixel slots, so the
-// fragment of column offset kx = 2 of one k-step is the fragment of kx = 0 of the next one and
-// stays in registers.
-template <int DT, int NOFF, int NTASK, int D, bool REUSE>
+template <int DT, int NOFF, int NTASK, int D>
 __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
 {
     extern __shared__ uint4 ws_lds[];
@@ -146,17 +145,23 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
     const int t_begin = (int)(((long long)P.NS * blockIdx.x) / P.S);
     const int t_end = (int)(((long long)P.NS * (blockIdx.x + 1)) / P.S);
     const int NI = (t_end - t_begin) * P.NSUB;  // sub-steps of this workgroup
-    const int rotmul = 8 / (P.J_WG >> 4);
+    // Units of one staged pixel: the 16-column group G sits at 16G, rotated by (G/2)*rotmul.  Both
+    // groups that a consumer wave reads together (G = 2wj, 2wj+1) have the same rotation, which
+    // ds_read_b128 needs to stay free of bank conflicts; the rotation between waves' groups spreads
+    // the producers' writes (8 columns per lane, lanes running over the column vectors) over banks.
+    const int rotmul = 8 / P.WJ;
 
     if (wave < 4) {
         // =========================== consumers ===========================
         // MFMA operands: A = dY units, lane (m = lane % 32, g = lane / 32) takes pixel slot 2q+g;
         // B = A-tensor units, lane (j = lane % 32, g) takes the shifted pixel; D is 32 x 32.
+        // the MFMA stream goes first; the producers' vector and LDS instructions fill the gaps
+        __builtin_amdgcn_s_setprio(3);
         const int l32 = lane & 31, g = lane >> 5;
         const int wm = wave % P.WM, wj = wave / P.WM;
         const int a_lane = g * P.M_WG + wm * 32 + l32;
         const int G = 2 * wj + (l32 >> 4);  // 16-column group of this lane's column
-        const int b_lane = g * P.sw * P.BSTR + G * 16 + (((l32 & 15) + G * rotmul) & 15);
+        const int b_lane = g * P.sw * P.BSTR + G * 16 + (((l32 & 15) + wj * rotmul) & 15);
 
         f32x16 acc[NOFF];
 #pragma unroll
@@ -181,118 +186,89 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
         };
 
         if (NI > 0) {
+            typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
             WsPos pc = ws_pos_of(P, t_begin);
             int brow[NOFF];
             set_brow(pc, brow);
-            const int step_a = 2 * P.M_WG;            // LDS units between k-steps
-            const int step_b = 2 * P.sw * P.BSTR;
+            // LDS byte addresses (the dynamic allocation starts behind the static one)
+            const uint32_t lds0 = __builtin_amdgcn_groupstaticsize();
+            const uint32_t a_base = lds0 + (uint32_t)a_lane * 16u;
+            const uint32_t b_base = lds0 + (uint32_t)(2 * P.a_units + b_lane) * 16u;
+            const uint32_t step_a = (uint32_t)(2 * P.M_WG) * 16u;            // bytes between k-steps
+            const uint32_t step_b = (uint32_t)(2 * P.sw * P.BSTR) * 16u;
+
+            // Fragment reads are issued as opaque instructions and waited for by hand.  Left to the
+            // compiler, every loop back-edge and branch between two k-steps gets a wait for all
+            // outstanding LDS reads, i.e. for the ones issued a few cycles earlier, and the matrix
+            // cores idle for an LDS round trip per k-step.  The requests of a k-step are issued in
+            // a fixed order (A of the next k-step, then after the MFMA of offset o the B fragment of
+            // offset o for the next k-step), LDS returns in order, so just before the MFMA of any
+            // offset at most NOFF younger requests may still be in flight (NOFF - 1 with the reads
+            // issued one MFMA late, see kstep).
+            auto lds_read = [](u32x4 &dst, uint32_t addr) {
+                asm volatile("ds_read_b128 %0, %1" : "=v"(dst) : "v"(addr) : "memory");
+            };
+            u32x4 a, an, b[NOFF];
+            uint32_t pa = a_base, pbo[NOFF];
+            {
+                const uint32_t pb = b_base + (uint32_t)((pc.u * P.CWs * P.sw) * P.BSTR) * 16u;
+#pragma unroll
+                for (int o = 0; o < NOFF; ++o) pbo[o] = pb + (uint32_t)brow[o] * 16u;
+            }
 
             ws_barrier();  // the first dY tile and the rows of the first row-step are in LDS
 
-            // fragments of the k-step being multiplied, and where the fragments of the one after it are
-            uint4 a, b[NOFF];
-            const uint4 *pa = lds_a + a_lane;
-            const uint4 *pbo[NOFF];
-            {
-                const uint4 *pb = lds_b + (pc.u * P.CWs * P.sw) * P.BSTR + b_lane;
-                a = *pa;
+            lds_read(a, pa);
+#pragma unroll
+            for (int o = 0; o < NOFF; ++o) lds_read(b[o], pbo[o]);
+
+            // One k-step: its MFMAs and the requests for the fragments at (pa, pbo).
+            auto kstep = [&]() {
+                __builtin_amdgcn_sched_barrier(0);
+                lds_read(an, pa);
 #pragma unroll
                 for (int o = 0; o < NOFF; ++o) {
-                    pbo[o] = pb + brow[o];
-                    b[o] = *pbo[o];
+                    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b[o]) : "n"(NOFF > 1 ? NOFF - 1 : 1) : "memory");
+                    acc[o] = mfma32<DT>(__builtin_bit_cast(uint4, a), __builtin_bit_cast(uint4, b[o]), acc[o]);
+                    // The fragment of offset o-1 is replaced one MFMA late: a load into the registers
+                    // that the MFMA just issued still reads would be held back until that MFMA is done.
+                    if (o >= 1) lds_read(b[o - 1], pbo[o - 1]);
                 }
-            }
-            // One scheduling region per k-step: its MFMAs, the requests for the next k-step's
-            // fragments (A first, then the B fragment of an offset right after the MFMA that used
-            // the old one) and the address updates, so LDS latency and address arithmetic hide
-            // behind the MFMAs.  `fresh`: new row-step, REUSE has nothing to carry over.
-            auto kstep = [&](bool fresh) {
-                __builtin_amdgcn_sched_barrier(0);
-                const uint4 an = *pa;
-                if constexpr (REUSE) {
-#pragma unroll
-                    for (int o = 0; o < NOFF; o += 3) {
-                        acc[o] = mfma32<DT>(a, b[o], acc[o]);
-                        acc[o + 1] = mfma32<DT>(a, b[o + 1], acc[o + 1]);
-                        acc[o + 2] = mfma32<DT>(a, b[o + 2], acc[o + 2]);
-                        b[o] = b[o + 2];  // a plain register move: nothing waits on LDS here
-                        b[o + 1] = *pbo[o + 1];
-                        b[o + 2] = *pbo[o + 2];
-                    }
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-#pragma unroll
-                    for (int o = 0; o < NOFF; o += 3) {
-                        __builtin_amdgcn_sched_group_barrier(0x008, 3, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-                    }
-                } else {
-#pragma unroll
-                    for (int o = 0; o < NOFF; ++o) {
-                        acc[o] = mfma32<DT>(a, b[o], acc[o]);
-                        b[o] = *pbo[o];
-                    }
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-#pragma unroll
-                    for (int o = 0; o < NOFF; ++o) {
-                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                    }
-                }
-                __builtin_amdgcn_sched_barrier(0);
-                if constexpr (REUSE) {
-                    if (fresh) {
-#pragma unroll
-                        for (int o = 0; o < NOFF; o += 3) b[o] = *pbo[o];
-                    }
-                }
+                lds_read(b[NOFF - 1], pbo[NOFF - 1]);
+                // the A fragment of the next k-step is the oldest of the NOFF + 1 requests just issued
+                asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(an) : "n"(NOFF) : "memory");
                 a = an;
+                __builtin_amdgcn_sched_barrier(0);
             };
 
             for (int i = 0; i < NI; ++i) {
                 const int nkq = (ws_cw_sub(P, pc) + 1) >> 1;
                 // k-steps whose successor lies in the same sub-step: constant address steps
-                auto kstep_same = [&]() {
+                for (int q = 0; q + 1 < nkq; ++q) {
                     pa += step_a;
 #pragma unroll
                     for (int o = 0; o < NOFF; ++o) pbo[o] += step_b;
-                    kstep(false);
-                };
-                // (unrolled by hand: inside straight-line code the compiler counts the outstanding
-                // LDS requests exactly, across a loop back-edge it waits for all of them)
-                int left = nkq - 1;
-                for (; left >= 4; left -= 4) {
-                    kstep_same();
-                    kstep_same();
-                    kstep_same();
-                    kstep_same();
+                    kstep();
                 }
-                if (left >= 2) {
-                    kstep_same();
-                    kstep_same();
-                    left -= 2;
-                }
-                if (left >= 1) kstep_same();
                 // The last k-step of the sub-step.  Its fragments were requested a whole k-step
                 // ago; once they are here the consumers no longer read sub-step i, so its buffer and
                 // the ring rows it alone used go back to the producers now, and the fragments
                 // requested during this k-step are those of the next sub-step.
-                bool fresh = true;
                 if (i + 1 < NI) {
                     const WsPos pn = ws_advance(P, pc);
+                    if (pn.t != pc.t) set_brow(pn, brow);
+                    pa = a_base + (uint32_t)(((i + 1) & 1) * P.a_units) * 16u;
+                    const uint32_t pb = b_base + (uint32_t)((pn.u * P.CWs * P.sw) * P.BSTR) * 16u;
+#pragma unroll
+                    for (int o = 0; o < NOFF; ++o) pbo[o] = pb + (uint32_t)brow[o] * 16u;
                     if (pn.u == 0 && pn.y == 0) ws_barrier();  // run boundary: the producers refill the whole ring first
                     ws_barrier();
-                    if (pn.t != pc.t) set_brow(pn, brow);
-                    fresh = pn.t != pc.t;
-                    pa = lds_a + ((i + 1) & 1) * P.a_units + a_lane;
-                    const uint4 *pb = lds_b + (pn.u * P.CWs * P.sw) * P.BSTR + b_lane;
-#pragma unroll
-                    for (int o = 0; o < NOFF; ++o) pbo[o] = pb + brow[o];
                     pc = pn;
                 }
                 // (after the very last sub-step the requests repeat the current addresses)
-                kstep(fresh);
+                kstep();
             }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         }
 
 
@@ -309,7 +285,7 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
         }
     } else {
         // =========================== producers ===========================
-        __builtin_amdgcn_s_setprio(3);
+        __builtin_amdgcn_s_setprio(0);
         const int p = tid - kProducers;
         const uint16_t *dY = static_cast<const uint16_t *>(P.dY);
         const uint16_t *Ag = static_cast<const uint16_t *>(P.A);
@@ -339,19 +315,31 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
             b_w[k] = s - P.NA_pad;
         }
 
+        // Buffer resources are built by hand (base, size, flags) so that they can be handed to the
+        // load instruction below.  A group with fewer than 8 images, or a sub-step that does not
+        // exist, gets a smaller (or empty) resource: reads past it return zero in hardware.
+        typedef int i32x4 __attribute__((ext_vector_type(4)));
+        typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
         auto rsrc_of = [&](const uint16_t *base, int bg, uint32_t img_bytes, bool live) {
             bg = __builtin_amdgcn_readfirstlane(bg);
             int left = P.B - bg * 8;
             left = left < 8 ? left : 8;
-            left = (live && left > 0 && (P.dbg_noload & 1) == 0) ? left : 0;
-            left = __builtin_amdgcn_readfirstlane(left);
-            return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(base + (size_t)bg * 8 * (img_bytes / 2)), 0,
-                                                     (uint32_t)left * img_bytes, 0x00020000);
+            left = (live && left > 0) ? left : 0;
+            const uint64_t addr = reinterpret_cast<uint64_t>(base + (size_t)bg * 8 * (img_bytes / 2));
+            i32x4 r;
+            r.x = __builtin_amdgcn_readfirstlane((int)(uint32_t)addr);
+            r.y = __builtin_amdgcn_readfirstlane((int)(uint32_t)((addr >> 32) & 0xffffu));
+            r.z = __builtin_amdgcn_readfirstlane((int)((uint32_t)left * img_bytes));
+            r.w = 0x00020000;
+            return r;
         };
-        auto buf16 = [](__amdgpu_buffer_rsrc_t r, uint32_t voff) {
-            typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, 0, 0);
-            return uint4{v.x, v.y, v.z, v.w};
+        // Loads of the software pipeline.  They are issued as opaque instructions: the compiler
+        // places its own waits for loads it knows about right before the first use and, across
+        // this kernel's loops and branches, falls back to waiting for (nearly) all outstanding
+        // loads, which would undo the prefetch distance.  The pipeline waits by hand instead
+        // (stage_wait below); nothing reads a stage between its loads and its wait.
+        auto buf16_async = [](u32x4 &dst, i32x4 r, uint32_t voff) {
+            asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(dst) : "v"(voff), "s"(r) : "memory");
         };
 
         // A task `idx` of a row window: staged column c, row rr of the rows being added, 8-column
@@ -363,17 +351,22 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
         };
         auto xt_task = [&](int idx, bool ok, int pr0, int slot0, int ix0) {
             const int jc = idx & (JC - 1);
-            const int rem = idx >> jc_shift;
-            const int rr = rem / P.BWc;
-            const int c = rem - rr * P.BWc;
+            int c = idx >> jc_shift, rr = 0;
+#pragma unroll
+            for (int q = 1; q < 8; ++q) {  // at most 8 rows are added per row-step (plan_corr_ws)
+                const bool wrap = c >= P.BWc;
+                c = wrap ? c - P.BWc : c;
+                rr = wrap ? rr + 1 : rr;
+            }
             const int iy = pr0 + rr - P.ph, ix = ix0 + c;
             const bool in = ok && (unsigned)iy < (unsigned)P.H && (unsigned)ix < (unsigned)P.W;
             int slot = slot0 + rr;
-            while (slot >= P.NRING) slot -= P.NRING;
+            slot = slot >= P.NRING ? slot - P.NRING : slot;
+            slot = slot >= P.NRING ? slot - P.NRING : slot;
             XtTask t;
             t.voff = in ? ((uint32_t)(iy * P.W + ix) * (uint32_t)P.CS + (uint32_t)(jb + 8 * jc)) * 2u : kOOR;
             t.lds = slot * P.b_row_units + c * P.BSTR + 16 * (jc >> 1);
-            t.rot = ((jc & 1) * 8 + (jc >> 1) * rotmul) & 15;
+            t.rot = ((jc & 1) * 8 + (jc >> 2) * rotmul) & 15;
             return t;
         };
         auto xt_store = [&](const XtTask &t, const uint4 (&src)[8]) {
@@ -426,90 +419,114 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
         };
 
         // ---- global -> registers for sub-step ps --------------------------------------
-        auto issue = [&](const WsPos &ps, bool live, uint4 (&r)[NTASK][8]) {
+        auto issue = [&](const WsPos &ps, bool live, u32x4 (&r)[NTASK][8]) {
             const int cw_sub = ws_cw_sub(P, ps);
             const uint32_t fs = (uint32_t)(ps.y * P.Wo + ps.strip * P.CW + ps.u * P.CWs) * 2u;
-            const __amdgpu_buffer_rsrc_t rsA = rsrc_of(dY, ps.bg, dy_img_bytes, live);
+            const i32x4 rsA = rsrc_of(dY, ps.bg, dy_img_bytes, live);
             const XtPlan x = xt_plan(ps);
-            const __amdgpu_buffer_rsrc_t rsB = rsrc_of(Ag, ps.bg, a_img_bytes, live && x.on);
+            const i32x4 rsB = rsrc_of(Ag, ps.bg, a_img_bytes, live && x.on);
 #pragma unroll
             for (int k = 0; k < NTASK; ++k) {
-                uint32_t voff;
-                uint32_t stride;
-                __amdgpu_buffer_rsrc_t rs;
                 if (is_a[k]) {
-                    voff = (a_goff[k] != kOOR && a_c8[k] < cw_sub) ? a_goff[k] + fs : kOOR;
-                    stride = dy_img_bytes;
-                    rs = rsA;
+                    const uint32_t voff = (a_goff[k] != kOOR && a_c8[k] < cw_sub) ? a_goff[k] + fs : kOOR;
+#pragma unroll
+                    for (int img = 0; img < 8; ++img) buf16_async(r[k][img], rsA, voff + (uint32_t)img * dy_img_bytes);
                 } else {
                     const int idx = x.slice * P.TS + b_w[k];
                     const XtTask t = xt_task(idx, b_w[k] < P.TS && idx < P.TB, x.pr0, x.slot0, x.ix0);
-                    voff = t.voff;
-                    stride = a_img_bytes;
-                    rs = rsB;
-                }
 #pragma unroll
-                for (int img = 0; img < 8; ++img) r[k][img] = buf16(rs, voff + (uint32_t)img * stride);
+                    for (int img = 0; img < 8; ++img) buf16_async(r[k][img], rsB, t.voff + (uint32_t)img * a_img_bytes);
+                }
             }
         };
+        // Waits until the loads of a stage have arrived: they are the oldest outstanding ones and
+        // loads return in order, so it is enough that at most the (D-1) younger stages are still
+        // in flight.  (Loads that the compiler issues in between only make this wait longer.)  The
+        // stage's registers are operands so that every use of them stays behind the wait.
+        auto stage_wait = [&](u32x4 (&r)[NTASK][8]) {
+            constexpr int kYounger = (D - 1) * NTASK * 8;
+            static_assert(kYounger <= 63, "vmcnt field");
+#pragma unroll
+            for (int k = 0; k < NTASK; ++k)
+                asm volatile("s_waitcnt vmcnt(%8)"
+                             : "+v"(r[k][0]), "+v"(r[k][1]), "+v"(r[k][2]), "+v"(r[k][3]), "+v"(r[k][4]), "+v"(r[k][5]),
+                               "+v"(r[k][6]), "+v"(r[k][7])
+                             : "n"(kYounger)
+                             : "memory");
+        };
         // ---- registers -> LDS for sub-step ps (buffer `buf` of the dY tiles) ------------
-        auto write = [&](const WsPos &ps, int buf, const uint4 (&r)[NTASK][8]) {
+        auto write = [&](const WsPos &ps, int buf, const u32x4 (&r)[NTASK][8]) {
             const int cw_sub = ws_cw_sub(P, ps);
             const XtPlan x = xt_plan(ps);
 #pragma unroll
             for (int k = 0; k < NTASK; ++k) {
+                uint4 src[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) src[q] = uint4{r[k][q].x, r[k][q].y, r[k][q].z, r[k][q].w};
                 if (is_a[k]) {
                     uint32_t rows[8][4];
 #pragma unroll
-                    for (int q = 0; q < 8; ++q) { rows[q][0] = r[k][q].x; rows[q][1] = r[k][q].y; rows[q][2] = r[k][q].z; rows[q][3] = r[k][q].w; }
+                    for (int q = 0; q < 8; ++q) { rows[q][0] = src[q].x; rows[q][1] = src[q].y; rows[q][2] = src[q].z; rows[q][3] = src[q].w; }
                     uint4 cols[8];
                     transpose_rows8<4>(rows, cols);
                     uint4 *dst = lds_a + buf * P.a_units + a_lds[k];
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
-                        const int slot = a_c8[k] + e;
                         // columns past the end of the row take part in the MFMAs: they must be zero
-                        const uint4 v = slot < cw_sub ? cols[e] : uint4{0u, 0u, 0u, 0u};
-                        if (slot < P.CWs) dst[e * P.M_WG] = v;
+                        // (the tile has whole chunks of 8 slots, so every store has a place)
+                        const bool in = a_c8[k] + e < cw_sub;
+                        dst[e * P.M_WG] = uint4{in ? cols[e].x : 0u, in ? cols[e].y : 0u, in ? cols[e].z : 0u, in ? cols[e].w : 0u};
                     }
                 } else if (x.on) {
                     const int idx = x.slice * P.TS + b_w[k];
                     if (b_w[k] < P.TS && idx < P.TB) {
                         const XtTask t = xt_task(idx, true, x.pr0, x.slot0, x.ix0);
-                        xt_store(t, r[k]);
+                        xt_store(t, src);
                     }
                 }
             }
         };
         // ---- every row of the window of row-step ps, loaded and written at once (start of a run)
         auto prime = [&](const WsPos &ps) {
-            const __amdgpu_buffer_rsrc_t rsB = rsrc_of(Ag, ps.bg, a_img_bytes, true);
+            const i32x4 rsB = rsrc_of(Ag, ps.bg, a_img_bytes, true);
             const int total = P.kH * P.BWc * JC;
             const int pr0 = ps.y * P.sh, slot0 = ps.rowmod, ix0 = ps.strip * P.CW * P.sw - P.pw;
             for (int base = 0; base < total; base += 2 * kProducers) {
-                uint4 r0[8], r1[8];
+                u32x4 r0[8], r1[8];
                 const int i0 = base + p, i1 = base + kProducers + p;
                 const XtTask t0 = xt_task(i0, i0 < total, pr0, slot0, ix0);
                 const XtTask t1 = xt_task(i1, i1 < total, pr0, slot0, ix0);
 #pragma unroll
-                for (int img = 0; img < 8; ++img) r0[img] = buf16(rsB, t0.voff + (uint32_t)img * a_img_bytes);
+                for (int img = 0; img < 8; ++img) buf16_async(r0[img], rsB, t0.voff + (uint32_t)img * a_img_bytes);
 #pragma unroll
-                for (int img = 0; img < 8; ++img) r1[img] = buf16(rsB, t1.voff + (uint32_t)img * a_img_bytes);
-                if (i0 < total) xt_store(t0, r0);
-                if (i1 < total) xt_store(t1, r1);
+                for (int img = 0; img < 8; ++img) buf16_async(r1[img], rsB, t1.voff + (uint32_t)img * a_img_bytes);
+                // needed right away: wait for everything in flight
+                asm volatile("s_waitcnt vmcnt(0)"
+                             : "+v"(r0[0]), "+v"(r0[1]), "+v"(r0[2]), "+v"(r0[3]), "+v"(r0[4]), "+v"(r0[5]), "+v"(r0[6]), "+v"(r0[7]),
+                               "+v"(r1[0]), "+v"(r1[1]), "+v"(r1[2]), "+v"(r1[3]), "+v"(r1[4]), "+v"(r1[5]), "+v"(r1[6]), "+v"(r1[7])
+                             :
+                             : "memory");
+                uint4 s0[8], s1[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    s0[q] = uint4{r0[q].x, r0[q].y, r0[q].z, r0[q].w};
+                    s1[q] = uint4{r1[q].x, r1[q].y, r1[q].z, r1[q].w};
+                }
+                if (i0 < total) xt_store(t0, s0);
+                if (i1 < total) xt_store(t1, s1);
             }
         };
 
         if (NI > 0) {
             WsPos pw = ws_pos_of(P, t_begin);  // sub-step whose data is written next
             WsPos pi = pw;                     // sub-step whose loads are issued next
-            uint4 st[D][NTASK][8];
+            u32x4 st[D][NTASK][8];
 #pragma unroll
             for (int d = 0; d < D; ++d) {
                 issue(pi, d < NI, st[d]);
                 pi = ws_advance(P, pi);
             }
-            if (!(P.dbg_noload & 2)) prime(pw);
+            prime(pw);
             for (int i0 = 0; i0 < NI; i0 += D) {
 #pragma unroll
                 for (int d = 0; d < D; ++d) {
@@ -519,14 +536,16 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
                             ws_barrier();  // the consumers have left the previous run: its ring rows are free
                             prime(pw);
                         }
-                        if (!(P.dbg_noload & 2)) write(pw, i & 1, st[d]);
-                        if (!(P.dbg_noload & 4)) issue(pi, i + D < NI, st[d]);
+                        stage_wait(st[d]);
+                        write(pw, i & 1, st[d]);
+                        issue(pi, i + D < NI, st[d]);
                         pw = ws_advance(P, pw);
                         pi = ws_advance(P, pi);
                         ws_barrier();
                     }
                 }
             }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the last (empty) prefetches
         }
     }
 }
@@ -558,7 +577,7 @@ static bool ws_geometry(WsParams &P, int CW, int NSUB)
     if (NSUB > 1 && P.NSTRIP > 1) return false;  // sub-steps only for whole rows
     P.BWc = (round_up(CW, 4) - 1) * P.sw + P.kW;
     P.NRING = P.kH + P.sh;
-    P.a_units = P.CWs * P.M_WG;
+    P.a_units = round_up(P.CWs, 8) * P.M_WG;  // whole chunks of 8 slots: the producers store every slot of a chunk
     P.BSTR = P.J_WG;  // pixel stride = whole 256-byte bank rows: the four pixel slots of a fragment read then fall on the same banks, which is what ds_read_b128 wants
     P.b_row_units = P.BWc * P.BSTR;
     P.NA = P.M_WG * ceil_div(P.CWs, 8);
@@ -569,7 +588,9 @@ static bool ws_geometry(WsParams &P, int CW, int NSUB)
     P.NTASK = ceil_div(P.NA_pad + P.TS, kProducers);
     P.NS = P.NBG * P.NSTRIP * P.Ho;
     if (corr_ws_lds_bytes(P) > kWsLdsLimit) return false;
-    if (P.NTASK > 3) return false;
+    // More than one task per producer thread does not fit the register file next to the
+    // consumers' accumulators (the staged loads of D sub-steps live in registers).
+    if (P.NTASK > 1) return false;
     return true;
 }
 
@@ -584,10 +605,9 @@ bool plan_corr_ws(WsParams &P, int dtype, int B, int C_out, int H, int W, int kH
     P.Wo = (W + 2 * pw - kW) / sw + 1;
     P.CS = CS;
     P.NBG = ceil_div(B, 8);
-    P.dbg_noload = ws_env_int("XCONV_WS_NOLOAD", 0);
     P.K2 = kH * kW;
     if (P.K2 == 1) return false;          // 1x1 kernels have no halo to share: corr_kernel handles them
-    if (kH > sh + 8 || sh > 8) return false;
+    if (kH > 8 || sh > 8) return false;    // rows added per row-step and rows of a window (xt_task)
     if (P.Wo % 2 != 0) return false;      // row starts of dY must be 4-byte aligned
     P.NOG = ceil_div(P.K2, 9);
     // a group of 8 images is addressed with 32-bit byte offsets
@@ -661,35 +681,26 @@ bool plan_corr_ws(WsParams &P, int dtype, int B, int C_out, int H, int W, int kH
     return true;
 }
 
-template <int DT, int NTASK, int D, bool REUSE>
+template <int DT, int NTASK, int D>
 static hipError_t launch_ws_cfg(const WsParams &P, hipStream_t st)
 {
     const size_t lds = corr_ws_lds_bytes(P);
     static bool done = false;  // per instantiation: the attribute sticks to the function
     if (!done && lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(corr_ws_kernel<DT, 9, NTASK, D, REUSE>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(corr_ws_kernel<DT, 9, NTASK, D>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kWsLdsLimit);
         if (e != hipSuccess) return e;
         done = true;
     }
-    hipLaunchKernelGGL((corr_ws_kernel<DT, 9, NTASK, D, REUSE>), dim3(P.S, P.NTM * P.NTJ, P.NOG), dim3(kWsThreads), lds, st, P);
+    hipLaunchKernelGGL((corr_ws_kernel<DT, 9, NTASK, D>), dim3(P.S, P.NTM * P.NTJ, P.NOG), dim3(kWsThreads), lds, st, P);
     return hipGetLastError();
-}
-
-template <int DT, bool REUSE> static hipError_t launch_ws_dt(const WsParams &P, hipStream_t st)
-{
-    switch (P.NTASK) {
-    case 1: return launch_ws_cfg<DT, 1, 3, REUSE>(P, st);
-    case 2: return launch_ws_cfg<DT, 2, 2, REUSE>(P, st);
-    default: return launch_ws_cfg<DT, 3, 2, REUSE>(P, st);
-    }
 }
 
 hipError_t launch_corr_ws(int dtype, const WsParams &P, hipStream_t st)
 {
-    const bool reuse = P.sw == 1 && P.kW == 3 && P.K2 == 9 && ws_env_int("XCONV_WS_REUSE", 1) != 0;
-    if (dtype == XCONV_BF16) return reuse ? launch_ws_dt<XCONV_BF16, true>(P, st) : launch_ws_dt<XCONV_BF16, false>(P, st);
-    return reuse ? launch_ws_dt<XCONV_F16, true>(P, st) : launch_ws_dt<XCONV_F16, false>(P, st);
+    // (plan_corr_ws only accepts plans with one task per producer thread)
+    if (dtype == XCONV_BF16) return launch_ws_cfg<XCONV_BF16, 1, 3>(P, st);
+    return launch_ws_cfg<XCONV_F16, 1, 3>(P, st);
 }
 
 }  // namespace xc
