@@ -164,7 +164,7 @@ def xconv_dw_exact(desc, dY_dev, X_dev, dW_dev, ws_dev, stream=None):
                                 _nbytes(ws_dev), _stream(stream)), "xconv_dw_exact")
 
 
-PLAN_FIELDS = ("S", "NS", "RB", "CW", "WM", "WJ", "WK", "M_WG", "J_WG", "lds_bytes", "NTM", "NTJ", "NOG", "CS", "NCHR")
+PLAN_FIELDS = ("S", "NS", "RB", "CW", "WM", "WJ", "WK", "M_WG", "J_WG", "lds_bytes", "NTM", "NTJ", "NOG", "CS", "NCHR", "ws")
 
 
 def xconv_plan_info(desc, op):

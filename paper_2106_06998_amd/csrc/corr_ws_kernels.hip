@@ -293,7 +293,7 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
         const uint32_t dy_img_bytes = (uint32_t)P.C_out * (uint32_t)HoWo * 2u;
         const uint32_t a_img_bytes = (uint32_t)P.H * (uint32_t)P.W * (uint32_t)P.CS * 2u;
         const int JC = P.J_WG >> 3;
-        const int jc_shift = JC == 8 ? 3 : (JC == 4 ? 2 : 1);
+        const int jc_shift = __builtin_ctz((unsigned)JC);  // J_WG is 32, 64 or 128
 
         // Task slots of this thread.  Slots below NA_pad (whole waves) stage dY: output channel
         // m = slot % M_WG, chunk of 8 columns slot / M_WG, so that the 64 lanes of a wave write

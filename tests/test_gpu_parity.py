@@ -191,6 +191,68 @@ def _edge_cfg(e):
 
 @pytest.mark.parametrize("e", EDGE, ids=[e[0] for e in EDGE])
 def test_edge_shapes(e):
+    run_edge(e)
+
+
+# Shapes that the producer/consumer correlation kernel takes (16-bit storage, probe columns a
+# multiple of 32, even output width): partial groups of 8 images, output channels that do not
+# fill a 32-row tile, strides, paddings, 4 / 3 / 25 kernel offsets, column strips with a ragged
+# last strip, several workgroup tiles along the probe columns, and a split of the reduction
+# whose ranges cross from one group of images into the next.
+WS_EDGE = [
+    ("ws-partial-group-f16", 11, 16, 40, 12, 12, 3, 1, 1, 32, "rademacher", "f16"),
+    ("ws-r64-bf16", 9, 24, 70, 10, 14, 3, 1, 1, 64, "rademacher", "bf16"),
+    ("ws-stride2-bf16", 8, 16, 48, 14, 20, 3, 2, 1, 32, "rademacher", "bf16"),
+    ("ws-k2x2-f16", 8, 16, 32, 9, 13, (2, 2), 1, 0, 32, "gaussian", "f16"),
+    ("ws-k5-f16", 8, 16, 32, 12, 12, 5, 1, 2, 32, "rademacher", "f16"),
+    ("ws-k1x3-f16", 16, 16, 64, 6, 16, (1, 3), 1, (0, 1), 64, "rademacher", "f16"),
+    ("ws-strips-f16", 8, 16, 32, 4, 260, 3, 1, 1, 32, "rademacher", "f16"),
+    ("ws-r128-f16", 8, 16, 32, 8, 8, 3, 1, 1, 128, "rademacher", "f16"),
+    ("ws-pad2-s2-bf16", 8, 16, 32, 13, 17, 3, 2, 2, 32, "rademacher", "bf16"),
+    ("ws-exact-cin64-f16", 8, 64, 32, 8, 8, 3, 1, 1, 16, "rademacher", "f16"),   # the exact gradient takes it (64 channels)
+    ("ws-runs-f16", 40, 16, 32, 6, 6, 3, 1, 1, 32, "rademacher", "f16"),         # 4 ranges over 5 groups x 6 rows
+]
+
+
+@pytest.mark.parametrize("e", WS_EDGE, ids=[e[0] for e in WS_EDGE])
+def test_producer_consumer_kernel_shapes(e):
+    import os
+    name, B, C_in, C_out, H, W, k, stride, pad, r, probe, dtype = e
+    d = xb.make_desc(B, C_in, C_out, H, W, k, stride, pad, r, dtype, probe, 13)
+    if name.startswith("ws-runs"):
+        os.environ["XCONV_WS_SPLITS"] = "4"      # read when the launch plan of this shape is made
+    try:
+        op = xb.XCONV_OP_EXACT if name.startswith("ws-exact") else xb.XCONV_OP_ESTIMATE
+        plan = xb.xconv_plan_info(d, op)
+    finally:
+        os.environ.pop("XCONV_WS_SPLITS", None)
+    assert plan["ws"] == 1, plan
+    if name.startswith("ws-runs"):
+        assert plan["S"] == 4 and plan["NS"] == 30, plan
+    run_edge(e)
+
+
+def test_producer_consumer_kernel_is_deterministic():
+    say("determinism, producer/consumer kernel")
+    e = WS_EDGE[1]
+    name, B, C_in, C_out, H, W, k, stride, pad, r, probe, dtype = e
+    X = synth.draw((B, C_in, H, W), 31, "relu_normal", 1.0, dtype)
+    dY = synth.draw((B, C_out, H, W), 32, "normal", 1e-2, dtype)
+    d = xb.make_desc(B, C_in, C_out, H, W, k, stride, pad, r, dtype, probe, 33)
+    assert xb.xconv_plan_info(d, xb.XCONV_OP_ESTIMATE)["ws"] == 1
+    Xd, dYd = xb.to_device(X, dtype, DEV), xb.to_device(dY, dtype, DEV)
+    Xt = xb.alloc_xt(d, DEV)
+    xb.xconv_probe_fwd(d, Xd, Xt, None, xb.alloc_ws(d, xb.XCONV_OP_PROBE, DEV))
+    outs = []
+    for _ in range(3):
+        dW = torch.full((C_out, C_in, 3, 3), float("nan"), dtype=torch.float32, device=DEV)
+        xb.xconv_dw_estimate(d, dYd, Xt, None, dW, xb.alloc_ws(d, xb.XCONV_OP_ESTIMATE, DEV))
+        torch.cuda.synchronize()
+        outs.append(dW.cpu().numpy())
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+
+
+def run_edge(e):
     name, B, C_in, C_out, H, W, k, stride, pad, r, probe, dtype = e
     kH, kW = (k, k) if isinstance(k, int) else k
     sh, sw = (stride, stride) if isinstance(stride, int) else stride
