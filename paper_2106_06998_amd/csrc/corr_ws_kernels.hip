@@ -113,6 +113,14 @@ __device__ inline int ws_cw_sub(const WsParams &P, const WsPos &p)
     return cw < P.CWs ? cw : P.CWs;
 }
 
+template <int Q, int N, class F> __device__ inline void ws_static_for(F &&f)
+{
+    if constexpr (Q < N) {
+        f(std::integral_constant<int, Q>{});
+        ws_static_for<Q + 1, N>(f);
+    }
+}
+
 }  // namespace
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -127,7 +135,9 @@ template <int DT> __device__ inline f32x16 mfma32(const uint4 &a, const uint4 &b
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
 }
 
-template <int DT, int NOFF, int NTASK, int D>
+// CB > 0: 3x3 offsets and the bytes of one staged column of A (BSTR * 16) known at compile time:
+// the three column offsets of a kernel row are then immediates of one address register.
+template <int DT, int NOFF, int NTASK, int D, int CB>
 __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
 {
     extern __shared__ uint4 ws_lds[];
@@ -205,36 +215,52 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
             // offset o for the next k-step), LDS returns in order, so just before the MFMA of any
             // offset at most NOFF younger requests may still be in flight (NOFF - 1 with the reads
             // issued one MFMA late, see kstep).
-            auto lds_read = [](u32x4 &dst, uint32_t addr) {
-                asm volatile("ds_read_b128 %0, %1" : "=v"(dst) : "v"(addr) : "memory");
+            auto lds_read = [](u32x4 &dst, uint32_t addr, auto off) {
+                asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(decltype(off)::value) : "memory");
             };
+            // address registers of the B fragments: one per offset, or (CB > 0) one per kernel row
+            constexpr int NPB = CB > 0 ? 3 : NOFF;
             u32x4 a, an, b[NOFF];
-            uint32_t pa = a_base, pbo[NOFF];
-            {
-                const uint32_t pb = b_base + (uint32_t)((pc.u * P.CWs * P.sw) * P.BSTR) * 16u;
+            uint32_t pa = a_base, pbo[NPB];
+            auto set_pbo = [&](const WsPos &p) {
+                const uint32_t pb = b_base + (uint32_t)((p.u * P.CWs * P.sw) * P.BSTR) * 16u;
 #pragma unroll
-                for (int o = 0; o < NOFF; ++o) pbo[o] = pb + (uint32_t)brow[o] * 16u;
-            }
+                for (int q = 0; q < NPB; ++q) pbo[q] = pb + (uint32_t)brow[CB > 0 ? 3 * q : q] * 16u;
+            };
+            auto read_b = [&](auto oc) {
+                constexpr int o = decltype(oc)::value;
+                if constexpr (CB > 0) lds_read(b[o], pbo[o / 3], std::integral_constant<int, (o % 3) * CB>{});
+                else lds_read(b[o], pbo[o], std::integral_constant<int, 0>{});
+            };
+            set_pbo(pc);
 
             ws_barrier();  // the first dY tile and the rows of the first row-step are in LDS
 
-            lds_read(a, pa);
-#pragma unroll
-            for (int o = 0; o < NOFF; ++o) lds_read(b[o], pbo[o]);
+            lds_read(a, pa, std::integral_constant<int, 0>{});
+            ws_static_for<0, NOFF>([&](auto oc) { read_b(oc); });
 
-            // One k-step: its MFMAs and the requests for the fragments at (pa, pbo).
+            // One k-step: its MFMAs and the requests for the fragments at (pa, pbo).  The fragment
+            // of offset o-1 is replaced one MFMA late (a load into registers that the MFMA just
+            // issued still reads would be held back until that MFMA is done), and the waits come
+            // once per three MFMAs: before the MFMA of offset o = 0, 3, 6 the fragment of offset
+            // o+2 must be there, after which at most 6 younger requests are in flight.
+            constexpr int WG3 = (NOFF % 3 == 0) ? 3 : 1;   // MFMAs per wait
+            constexpr int WN = WG3 == 3 ? 6 : (NOFF > 1 ? NOFF - 1 : 1);
             auto kstep = [&]() {
                 __builtin_amdgcn_sched_barrier(0);
-                lds_read(an, pa);
-#pragma unroll
-                for (int o = 0; o < NOFF; ++o) {
-                    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b[o]) : "n"(NOFF > 1 ? NOFF - 1 : 1) : "memory");
+                lds_read(an, pa, std::integral_constant<int, 0>{});
+                ws_static_for<0, NOFF>([&](auto oc) {
+                    constexpr int o = decltype(oc)::value;
+                    if constexpr (o % WG3 == 0) {
+                        if constexpr (WG3 == 3)
+                            asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b[o]), "+v"(b[o + 1]), "+v"(b[o + 2]) : "n"(WN) : "memory");
+                        else
+                            asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b[o]) : "n"(WN) : "memory");
+                    }
                     acc[o] = mfma32<DT>(__builtin_bit_cast(uint4, a), __builtin_bit_cast(uint4, b[o]), acc[o]);
-                    // The fragment of offset o-1 is replaced one MFMA late: a load into the registers
-                    // that the MFMA just issued still reads would be held back until that MFMA is done.
-                    if (o >= 1) lds_read(b[o - 1], pbo[o - 1]);
-                }
-                lds_read(b[NOFF - 1], pbo[NOFF - 1]);
+                    if constexpr (o >= 1) read_b(std::integral_constant<int, o - 1>{});
+                });
+                read_b(std::integral_constant<int, NOFF - 1>{});
                 // the A fragment of the next k-step is the oldest of the NOFF + 1 requests just issued
                 asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(an) : "n"(NOFF) : "memory");
                 a = an;
@@ -247,7 +273,7 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
                 for (int q = 0; q + 1 < nkq; ++q) {
                     pa += step_a;
 #pragma unroll
-                    for (int o = 0; o < NOFF; ++o) pbo[o] += step_b;
+                    for (int o = 0; o < NPB; ++o) pbo[o] += step_b;
                     kstep();
                 }
                 // The last k-step of the sub-step.  Its fragments were requested a whole k-step
@@ -258,9 +284,7 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
                     const WsPos pn = ws_advance(P, pc);
                     if (pn.t != pc.t) set_brow(pn, brow);
                     pa = a_base + (uint32_t)(((i + 1) & 1) * P.a_units) * 16u;
-                    const uint32_t pb = b_base + (uint32_t)((pn.u * P.CWs * P.sw) * P.BSTR) * 16u;
-#pragma unroll
-                    for (int o = 0; o < NOFF; ++o) pbo[o] = pb + (uint32_t)brow[o] * 16u;
+                    set_pbo(pn);
                     if (pn.u == 0 && pn.y == 0) ws_barrier();  // run boundary: the producers refill the whole ring first
                     ws_barrier();
                     pc = pn;
@@ -380,6 +404,31 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
             for (int e = 0; e < 8; ++e) dst[(t.rot + e) & 15] = cols[e];
         };
 
+        // The A tasks of this thread, decoded once for each of the (at most two) slices: byte
+        // offset of (row rr, column c, column vector jc) from the first added row and first
+        // staged column, or kOOR for a thread without a task in that slice; LDS unit inside a ring
+        // row; c, rr and the rotation packed into one word.
+        uint32_t x_goff[NTASK][2];
+        int x_lds[NTASK][2], x_crr[NTASK][2];
+#pragma unroll
+        for (int k = 0; k < NTASK; ++k)
+#pragma unroll
+            for (int v = 0; v < 2; ++v) {
+                const int idx = v * P.TS + b_w[k];
+                const bool ok = !is_a[k] && v < P.NSUB && b_w[k] >= 0 && b_w[k] < P.TS && idx < P.TB;
+                const int jc = idx & (JC - 1);
+                int c = idx >> jc_shift, rr = 0;
+#pragma unroll
+                for (int q = 1; q < 8; ++q) {
+                    const bool wrap = c >= P.BWc;
+                    c = wrap ? c - P.BWc : c;
+                    rr = wrap ? rr + 1 : rr;
+                }
+                x_goff[k][v] = ok ? ((uint32_t)(rr * P.W + c) * (uint32_t)P.CS + (uint32_t)(jb + 8 * jc)) * 2u : kOOR;
+                x_lds[k][v] = c * P.BSTR + 16 * (jc >> 1);
+                x_crr[k][v] = c | (rr << 16) | ((((jc & 1) * 8 + (jc >> 2) * rotmul) & 15) << 24);
+            }
+
         // The rows of A that sub-step `ps` brings in, as (row-step they belong to, slice).
         // One slice per sub-step: with a single sub-step per row-step the row-step's own new
         // rows; otherwise sub-step 0 brings the last slice of its own row-step and sub-step
@@ -432,10 +481,15 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
 #pragma unroll
                     for (int img = 0; img < 8; ++img) buf16_async(r[k][img], rsA, voff + (uint32_t)img * dy_img_bytes);
                 } else {
-                    const int idx = x.slice * P.TS + b_w[k];
-                    const XtTask t = xt_task(idx, b_w[k] < P.TS && idx < P.TB, x.pr0, x.slot0, x.ix0);
+                    const uint32_t goff = x.slice ? x_goff[k][1] : x_goff[k][0];
+                    const int crr = x.slice ? x_crr[k][1] : x_crr[k][0];
+                    const int iy = x.pr0 - P.ph + ((crr >> 16) & 0xff), ix = x.ix0 + (crr & 0xffff);
+                    const bool in = goff != kOOR && (unsigned)iy < (unsigned)P.H && (unsigned)ix < (unsigned)P.W;
+                    // (the origin may lie in the padding: the sum wraps and is exact for every pixel inside the image)
+                    const uint32_t origin = (uint32_t)((x.pr0 - P.ph) * P.W + x.ix0) * ((uint32_t)P.CS * 2u);
+                    const uint32_t voff = in ? origin + goff : kOOR;
 #pragma unroll
-                    for (int img = 0; img < 8; ++img) buf16_async(r[k][img], rsB, t.voff + (uint32_t)img * a_img_bytes);
+                    for (int img = 0; img < 8; ++img) buf16_async(r[k][img], rsB, voff + (uint32_t)img * a_img_bytes);
                 }
             }
         };
@@ -463,25 +517,36 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
                 uint4 src[8];
 #pragma unroll
                 for (int q = 0; q < 8; ++q) src[q] = uint4{r[k][q].x, r[k][q].y, r[k][q].z, r[k][q].w};
+                uint32_t rows[8][4];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) { rows[q][0] = src[q].x; rows[q][1] = src[q].y; rows[q][2] = src[q].z; rows[q][3] = src[q].w; }
+                uint4 cols[8];
+                transpose_rows8<4>(rows, cols);
                 if (is_a[k]) {
-                    uint32_t rows[8][4];
-#pragma unroll
-                    for (int q = 0; q < 8; ++q) { rows[q][0] = src[q].x; rows[q][1] = src[q].y; rows[q][2] = src[q].z; rows[q][3] = src[q].w; }
-                    uint4 cols[8];
-                    transpose_rows8<4>(rows, cols);
                     uint4 *dst = lds_a + buf * P.a_units + a_lds[k];
+                    if (cw_sub >= ((P.CWs + 7) & ~7)) {  // every slot of every chunk is a real column
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        // columns past the end of the row take part in the MFMAs: they must be zero
-                        // (the tile has whole chunks of 8 slots, so every store has a place)
-                        const bool in = a_c8[k] + e < cw_sub;
-                        dst[e * P.M_WG] = uint4{in ? cols[e].x : 0u, in ? cols[e].y : 0u, in ? cols[e].z : 0u, in ? cols[e].w : 0u};
+                        for (int e = 0; e < 8; ++e) dst[e * P.M_WG] = cols[e];
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            // columns past the end of the row take part in the MFMAs: they must be zero
+                            // (the tile has whole chunks of 8 slots, so every store has a place)
+                            const bool in = a_c8[k] + e < cw_sub;
+                            dst[e * P.M_WG] = uint4{in ? cols[e].x : 0u, in ? cols[e].y : 0u, in ? cols[e].z : 0u, in ? cols[e].w : 0u};
+                        }
                     }
                 } else if (x.on) {
-                    const int idx = x.slice * P.TS + b_w[k];
-                    if (b_w[k] < P.TS && idx < P.TB) {
-                        const XtTask t = xt_task(idx, true, x.pr0, x.slot0, x.ix0);
-                        xt_store(t, src);
+                    const uint32_t goff = x.slice ? x_goff[k][1] : x_goff[k][0];
+                    if (goff != kOOR) {
+                        const int crr = x.slice ? x_crr[k][1] : x_crr[k][0];
+                        int slot = x.slot0 + ((crr >> 16) & 0xff);
+                        slot = slot >= P.NRING ? slot - P.NRING : slot;
+                        slot = slot >= P.NRING ? slot - P.NRING : slot;
+                        uint4 *dst = lds_b + slot * P.b_row_units + (x.slice ? x_lds[k][1] : x_lds[k][0]);
+                        const int rot = (crr >> 24) & 15;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) dst[(rot + e) & 15] = cols[e];
                     }
                 }
             }
@@ -634,12 +699,12 @@ bool plan_corr_ws(WsParams &P, int dtype, int B, int C_out, int H, int W, int kH
     // whole rows cut into sub-steps if the ring fits, else column strips
     bool found = false;
     const int fCW = ws_env_int("XCONV_WS_CW", 0), fNSUB = ws_env_int("XCONV_WS_NSUB", 0);
-    if (fCW > 0 && fNSUB > 0) {
+    if (fCW > 0 && fNSUB > 0 && fNSUB <= 2) {
         found = ws_geometry(P, fCW, fNSUB);
     } else {
         WsParams best = P;
         int best_ntask = 99, best_cws = 0;
-        for (int nsub = 1; nsub <= 8; ++nsub) {
+        for (int nsub = 1; nsub <= 2; ++nsub) {  // the producers keep per-slice constants for two slices
             WsParams Q = P;
             if (!ws_geometry(Q, P.Wo, nsub)) continue;
             if (Q.CWs > 32) continue;
@@ -681,26 +746,40 @@ bool plan_corr_ws(WsParams &P, int dtype, int B, int C_out, int H, int W, int kH
     return true;
 }
 
-template <int DT, int NTASK, int D>
+template <int DT, int NTASK, int D, int CB>
 static hipError_t launch_ws_cfg(const WsParams &P, hipStream_t st)
 {
     const size_t lds = corr_ws_lds_bytes(P);
     static bool done = false;  // per instantiation: the attribute sticks to the function
     if (!done && lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(corr_ws_kernel<DT, 9, NTASK, D>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(corr_ws_kernel<DT, 9, NTASK, D, CB>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kWsLdsLimit);
         if (e != hipSuccess) return e;
         done = true;
     }
-    hipLaunchKernelGGL((corr_ws_kernel<DT, 9, NTASK, D>), dim3(P.S, P.NTM * P.NTJ, P.NOG), dim3(kWsThreads), lds, st, P);
+    hipLaunchKernelGGL((corr_ws_kernel<DT, 9, NTASK, D, CB>), dim3(P.S, P.NTM * P.NTJ, P.NOG), dim3(kWsThreads), lds, st, P);
     return hipGetLastError();
+}
+
+template <int DT> static hipError_t launch_ws_dt(const WsParams &P, hipStream_t st)
+{
+    // (plan_corr_ws only accepts plans with one task per producer thread)
+    static const bool generic = ws_env_int("XCONV_WS_GENERIC", 0) != 0;
+    if (!generic && P.K2 == 9 && P.kW == 3) {
+        switch (P.BSTR) {
+        case 32: return launch_ws_cfg<DT, 1, 3, 32 * 16>(P, st);
+        case 64: return launch_ws_cfg<DT, 1, 3, 64 * 16>(P, st);
+        case 128: return launch_ws_cfg<DT, 1, 3, 128 * 16>(P, st);
+        default: break;
+        }
+    }
+    return launch_ws_cfg<DT, 1, 3, 0>(P, st);
 }
 
 hipError_t launch_corr_ws(int dtype, const WsParams &P, hipStream_t st)
 {
-    // (plan_corr_ws only accepts plans with one task per producer thread)
-    if (dtype == XCONV_BF16) return launch_ws_cfg<XCONV_BF16, 1, 3>(P, st);
-    return launch_ws_cfg<XCONV_F16, 1, 3>(P, st);
+    if (dtype == XCONV_BF16) return launch_ws_dt<XCONV_BF16>(P, st);
+    return launch_ws_dt<XCONV_F16>(P, st);
 }
 
 }  // namespace xc
