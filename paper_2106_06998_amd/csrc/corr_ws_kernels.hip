@@ -552,33 +552,36 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
             }
         };
         // ---- every row of the window of row-step ps, loaded and written at once (start of a run)
-        auto prime = [&](const WsPos &ps) {
+        auto prime = [&](const WsPos &ps, auto npc) {
             const i32x4 rsB = rsrc_of(Ag, ps.bg, a_img_bytes, true);
             const int total = P.kH * P.BWc * JC;
             const int pr0 = ps.y * P.sh, slot0 = ps.rowmod, ix0 = ps.strip * P.CW * P.sw - P.pw;
-            for (int base = 0; base < total; base += 2 * kProducers) {
-                u32x4 r0[8], r1[8];
-                const int i0 = base + p, i1 = base + kProducers + p;
-                const XtTask t0 = xt_task(i0, i0 < total, pr0, slot0, ix0);
-                const XtTask t1 = xt_task(i1, i1 < total, pr0, slot0, ix0);
+            // tasks in flight per thread: with 3, one round trip to memory covers 768 tasks (start of
+            // the kernel, when the registers of the stages are still free); 1 inside the pipeline
+            constexpr int NP = decltype(npc)::value;
+            for (int base = 0; base < total; base += NP * kProducers) {
+                u32x4 r[NP][8];
+                XtTask t[NP];
 #pragma unroll
-                for (int img = 0; img < 8; ++img) buf16_async(r0[img], rsB, t0.voff + (uint32_t)img * a_img_bytes);
+                for (int u = 0; u < NP; ++u) {
+                    const int idx = base + u * kProducers + p;
+                    t[u] = xt_task(idx, idx < total, pr0, slot0, ix0);
 #pragma unroll
-                for (int img = 0; img < 8; ++img) buf16_async(r1[img], rsB, t1.voff + (uint32_t)img * a_img_bytes);
-                // needed right away: wait for everything in flight
-                asm volatile("s_waitcnt vmcnt(0)"
-                             : "+v"(r0[0]), "+v"(r0[1]), "+v"(r0[2]), "+v"(r0[3]), "+v"(r0[4]), "+v"(r0[5]), "+v"(r0[6]), "+v"(r0[7]),
-                               "+v"(r1[0]), "+v"(r1[1]), "+v"(r1[2]), "+v"(r1[3]), "+v"(r1[4]), "+v"(r1[5]), "+v"(r1[6]), "+v"(r1[7])
-                             :
-                             : "memory");
-                uint4 s0[8], s1[8];
-#pragma unroll
-                for (int q = 0; q < 8; ++q) {
-                    s0[q] = uint4{r0[q].x, r0[q].y, r0[q].z, r0[q].w};
-                    s1[q] = uint4{r1[q].x, r1[q].y, r1[q].z, r1[q].w};
+                    for (int img = 0; img < 8; ++img) buf16_async(r[u][img], rsB, t[u].voff + (uint32_t)img * a_img_bytes);
                 }
-                if (i0 < total) xt_store(t0, s0);
-                if (i1 < total) xt_store(t1, s1);
+#pragma unroll
+                for (int u = 0; u < NP; ++u) {
+                    // needed right away; the loads of task u are older than those of the tasks after it
+                    asm volatile("s_waitcnt vmcnt(%8)"
+                                 : "+v"(r[u][0]), "+v"(r[u][1]), "+v"(r[u][2]), "+v"(r[u][3]), "+v"(r[u][4]), "+v"(r[u][5]),
+                                   "+v"(r[u][6]), "+v"(r[u][7])
+                                 : "n"((NP - 1 - u) * 8)
+                                 : "memory");
+                    uint4 src[8];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) src[q] = uint4{r[u][q].x, r[u][q].y, r[u][q].z, r[u][q].w};
+                    if (base + u * kProducers + p < total) xt_store(t[u], src);
+                }
             }
         };
 
@@ -586,12 +589,12 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
             WsPos pw = ws_pos_of(P, t_begin);  // sub-step whose data is written next
             WsPos pi = pw;                     // sub-step whose loads are issued next
             u32x4 st[D][NTASK][8];
+            prime(pw, std::integral_constant<int, 3>{});  // (before the pipeline fills: its loads need the registers of the stages)
 #pragma unroll
             for (int d = 0; d < D; ++d) {
                 issue(pi, d < NI, st[d]);
                 pi = ws_advance(P, pi);
             }
-            prime(pw);
             for (int i0 = 0; i0 < NI; i0 += D) {
 #pragma unroll
                 for (int d = 0; d < D; ++d) {
@@ -599,7 +602,7 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
                     if (i < NI) {
                         if (i > 0 && pw.u == 0 && pw.y == 0) {
                             ws_barrier();  // the consumers have left the previous run: its ring rows are free
-                            prime(pw);
+                            prime(pw, std::integral_constant<int, 1>{});
                         }
                         stage_wait(st[d]);
                         write(pw, i & 1, st[d]);
