@@ -1,6 +1,7 @@
 // Internal definitions shared by the HIP translation units of libxconv.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <math.h>
 #include <stdint.h>
 
 #include "../../include/xconv.h"
@@ -84,6 +85,29 @@ template <int NW> __device__ inline void transpose_rows8(const uint32_t (&rows)[
         cols[2 * w + 1].z = (rows[4][w] >> 16) | (rows[5][w] & 0xffff0000u);
         cols[2 * w + 1].w = (rows[6][w] >> 16) | (rows[7][w] & 0xffff0000u);
     }
+}
+
+// ---------------------------------------------------------------------------
+// Z[s]: SplitMix64 in counter form.  Word ctr of the stream of `seed` is
+// fin(key + gamma*(ctr+1)) with key = fin(seed + gamma).
+// ---------------------------------------------------------------------------
+__host__ __device__ inline uint64_t mix_fin(uint64_t z)
+{
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+__host__ __device__ inline uint64_t stream_word(uint64_t key, uint64_t ctr)
+{
+    return mix_fin(key + 0x9E3779B97F4A7C15ull * (ctr + 1ull));
+}
+__host__ __device__ inline float probe_entry(int dist, uint64_t key, uint64_t idx)
+{
+    if (dist == XCONV_RADEMACHER) return (stream_word(key, idx) >> 63) ? -1.0f : 1.0f;
+    // Box-Muller in double on two 53-bit uniforms, u1 in (0,1], u2 in [0,1)
+    const double u1 = ((double)(stream_word(key, 2ull * idx) >> 11) + 1.0) * 0x1.0p-53;
+    const double u2 = (double)(stream_word(key, 2ull * idx + 1ull) >> 11) * 0x1.0p-53;
+    return (float)(sqrt(-2.0 * log(u1)) * cos(6.283185307179586476925 * u2));
 }
 
 // ---- launch plan of the correlation kernel (host fills, kernel reads) ------

@@ -556,11 +556,19 @@ __global__ __launch_bounds__(kThreads, ((DT == XCONV_F32 && MT <= 2) ? 2 : 1)) v
 // fixed order.  16 consecutive float4 elements x 16 groups of s per workgroup.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const f32x4 *__restrict__ part, f32x4 *__restrict__ T,
-                                                                   int S, int E4)
+                                                                   int S, int E4, float *__restrict__ Zout, int nz, int zblocks,
+                                                                   int dist, uint64_t seed)
 {
+    // The first `zblocks` workgroups redraw Z[s] for the expansion that follows (Alg. 1 backward
+    // step 2) instead of a kernel launch of its own; the rest reduce.
+    if ((int)blockIdx.x < zblocks) {
+        const int i = blockIdx.x * kThreads + threadIdx.x;
+        if (i < nz) Zout[i] = probe_entry(dist, mix_fin(seed + 0x9E3779B97F4A7C15ull), (uint64_t)i);
+        return;
+    }
     __shared__ f32x4 red[16][17];
     const int ve = threadIdx.x & 15, sg = threadIdx.x >> 4;
-    const int e4 = blockIdx.x * 16 + ve;
+    const int e4 = ((int)blockIdx.x - zblocks) * 16 + ve;
     f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0, s2 = s0, s3 = s0;
     if (e4 < E4) {
         const f32x4 *p = part + e4;
@@ -916,11 +924,13 @@ hipError_t launch_corr(int dtype, const CorrParams &P, hipStream_t st)
 
 static float *reduced_tile(const CorrParams &P) { return P.part + (size_t)P.S * P.K2 * P.JP * P.MP; }
 
-hipError_t launch_reduce(const CorrParams &P, hipStream_t st)
+hipError_t launch_reduce(const CorrParams &P, hipStream_t st, float *Zout, int nz, int dist, uint64_t seed)
 {
     const int E4 = (int)(((size_t)P.K2 * P.JP * P.MP) / 4);
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3(ceil_div(E4, 16)), dim3(kThreads), 0, st,
-                       reinterpret_cast<const f32x4 *>(P.part), reinterpret_cast<f32x4 *>(reduced_tile(P)), P.S, E4);
+    const int zblocks = Zout ? ceil_div(nz, kThreads) : 0;
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3(zblocks + ceil_div(E4, 16)), dim3(kThreads), 0, st,
+                       reinterpret_cast<const f32x4 *>(P.part), reinterpret_cast<f32x4 *>(reduced_tile(P)), P.S, E4, Zout, nz,
+                       zblocks, dist, seed);
     return hipGetLastError();
 }
 

@@ -28,8 +28,9 @@ size_t corr_partial_bytes(const CorrParams &P);
 size_t corr_lds_bytes(int dtype, const CorrParams &P);
 hipError_t launch_corr(int dtype, const CorrParams &P, hipStream_t st);
 hipError_t launch_repack_planes(int dtype, const void *src, void *dst, long long nplanes, int n, int pitch, hipStream_t st);
-// T[o,j,m] = sum_s part[s,o,j,m]; T lives behind the S partial buffers
-hipError_t launch_reduce(const CorrParams &P, hipStream_t st);
+// T[o,j,m] = sum_s part[s,o,j,m]; T lives behind the S partial buffers.  Zout != nullptr: the same
+// launch also draws Z[s] (nz = C_in * r entries) from (dist, seed) into Zout.
+hipError_t launch_reduce(const CorrParams &P, hipStream_t st, float *Zout = nullptr, int nz = 0, int dist = 0, uint64_t seed = 0);
 // dW[m,n,o] = (1/r) * sum_j Z[n,j] * T[o,j,m]   (Z != nullptr)
 // dW[m,n,o] = T[o,n,m]                          (Z == nullptr, exact path)
 hipError_t launch_expand(const CorrParams &P, const float *Z, float *dW, int C_in, int r, hipStream_t st);

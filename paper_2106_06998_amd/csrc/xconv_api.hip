@@ -253,10 +253,11 @@ xconv_status xconv_dw_estimate(const xconv_desc *d, const void *dY_dev, const vo
     CorrParams &P = E.P;
     const size_t zb = z_bytes(d), pb = align_up(corr_partial_bytes(P), 256), rb = dy_repack_bytes(d);
     if (ws_bytes < zb + pb + rb) return XCONV_EWORKSPACE;
+    // Z[s] is only needed by the expansion: it is redrawn by spare workgroups of the reduction launch
     const float *Z = Z_dev;
+    float *zw = nullptr;
     if (!Z) {
-        float *zw = static_cast<float *>(ws_dev);
-        XC_LAUNCH(K_GEN_Z, st, launch_gen_z(zw, d->C_in * d->r, d->probe, d->seed, st));
+        zw = static_cast<float *>(ws_dev);
         Z = zw;
     }
     P.dY = dY_dev;
@@ -275,7 +276,7 @@ xconv_status xconv_dw_estimate(const xconv_desc *d, const void *dY_dev, const vo
     } else {
         XC_LAUNCH(K_CORR, st, launch_corr(d->dtype, P, st));
     }
-    XC_LAUNCH(K_REDUCE, st, launch_reduce(P, st));
+    XC_LAUNCH(K_REDUCE, st, launch_reduce(P, st, zw, d->C_in * d->r, d->probe, d->seed));
     XC_LAUNCH(K_EXPAND, st, launch_expand(P, Z, dW_dev, d->C_in, d->r, st));
     return XCONV_OK;
 }
