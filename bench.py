@@ -27,8 +27,8 @@ PEAK_MFMA_TFLOPS = {"f32": 157.3, "bf16": 2500.0, "f16": 2500.0}
 # (FETCH_SIZE, WRITE_SIZE scaled by a copy kernel of known size; see
 # profiles/).  bytes, or None where not measured yet.
 MEASURED_TRAFFIC = {
-    ("C2", "corr_kernel"): 71.2e6, ("C2", "probe_kernel"): 42.1e6,      # profiles/xconv_kernels_C2.txt
-    ("C5", "corr_kernel"): 209.2e6, ("C5", "probe_kernel"): 154.8e6,    # profiles/xconv_kernels_C5.txt
+    ("C2", "corr_kernel"): 62.7e6, ("C2", "probe_kernel"): 42.0e6,       # profiles/xconv_kernels_C2.txt
+    ("C5", "corr_ws_kernel"): 201.3e6, ("C5", "probe_kernel"): 154.3e6,  # profiles/xconv_kernels_C5.txt
 }
 
 
@@ -222,7 +222,7 @@ def main():
         else:
             ach = res["corr"]["gbps"]
             roof = dict(bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS)
-        roof["kernel"] = "corr_kernel"
+        roof["kernel"] = "corr_ws_kernel" if res["plan"].get("ws") else "corr_kernel"
         roof["kernel_ms"] = res["corr"]["ms"]
     else:
         ach = res["probe"]["gbps"]
