@@ -87,6 +87,23 @@ template <int NW> __device__ inline void transpose_rows8(const uint32_t (&rows)[
     }
 }
 
+// Quotient and remainder of small non-negative integers (n, d < 2^22) through one float
+// multiplication and a correction step: a handful of instructions where the integer division
+// of the instruction set takes some thirty.  rd = frcp(d).
+__device__ inline float frcp(int d) { return __builtin_amdgcn_rcpf((float)d); }
+__device__ inline void fast_divmod(int n, int d, float rd, int &q, int &r)
+{
+    q = (int)((float)n * rd);
+    r = n - q * d;
+    if (r < 0) {
+        r += d;
+        --q;
+    } else if (r >= d) {
+        r -= d;
+        ++q;
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Z[s]: SplitMix64 in counter form.  Word ctr of the stream of `seed` is
 // fin(key + gamma*(ctr+1)) with key = fin(seed + gamma).
@@ -129,6 +146,7 @@ struct CorrParams {
     int NCHR;          // vector chunks of dY staged per row and output channel
     int NTM, NTJ;      // tiles along C_out and along the probe columns
     int S, NS;         // K-splits and total steps
+    int SQ, SR;        // NS / S and NS % S (set at launch): workgroup x takes SQ steps, one more if x < SR
     int K2, NOG;       // kernel offsets and offset groups of <= 9
     int MP, JP;        // padded extents of the partial buffer
     int dy_plane;      // elements between consecutive (image, channel) planes of dY as the kernel reads it (whole 16-byte vectors)
@@ -150,6 +168,7 @@ struct WsParams {
     int BWc, NRING;         // staged columns per ring row; ring rows (kH + sh)
     int WM, WJ, M_WG, J_WG, NTM, NTJ;
     int S, NS;              // K-splits, row-steps in total (NBG * NSTRIP * Ho)
+    int SQ, SR;             // NS / S and NS % S (set at launch): workgroup x takes SQ row-steps, one more if x < SR
     int K2, NOG, MP, JP;
     int a_units;            // LDS units of one dY buffer (CWs * M_WG)
     int b_row_units, BSTR;  // LDS units per ring row, per staged column (J_WG + 1)

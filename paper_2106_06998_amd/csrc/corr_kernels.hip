@@ -43,6 +43,14 @@ namespace xc {
 
 constexpr int kMaxOff = 9;
 
+template <int Q, int N, class F> __device__ inline void ws_for(F &&f)
+{
+    if constexpr (Q < N) {
+        f(std::integral_constant<int, Q>{});
+        ws_for<Q + 1, N>(f);
+    }
+}
+
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
 // outstanding global load of the wave (its release fence drains vmcnt), which would expose
 // the latency of the prefetch issued before the barrier; the kernel exchanges data through
@@ -82,10 +90,16 @@ __device__ inline StepPos uniform_pos(StepPos s)
 __device__ inline StepPos decode_step(const CorrParams &P, int t)
 {
     StepPos s;
-    s.band = t % P.NBAND;
-    t /= P.NBAND;
-    s.strip = t % P.NSTRIP;
-    s.bg = t / P.NSTRIP;
+    if (t < (1 << 22)) {
+        int q;
+        fast_divmod(t, P.NBAND, frcp(P.NBAND), q, s.band);
+        fast_divmod(q, P.NSTRIP, frcp(P.NSTRIP), s.bg, s.strip);
+    } else {
+        s.band = t % P.NBAND;
+        t /= P.NBAND;
+        s.strip = t % P.NSTRIP;
+        s.bg = t / P.NSTRIP;
+    }
     s.oy0 = s.band * P.RB;
     s.x0 = s.strip * P.CW;
     return uniform_pos(s);
@@ -128,9 +142,12 @@ __global__ __launch_bounds__(kThreads, ((DT == XCONV_F32 && MT <= 2) ? 2 : 1)) v
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the k-step bookkeeping scalar
     const int jl = lane & 15, g = lane >> 4;
-    const int wm = wave % P.WM, wj = (wave / P.WM) % P.WJ, wk = wave / (P.WM * P.WJ);
+    // WM, WJ, WK are powers of two
+    const int wm_shift = __builtin_ctz((unsigned)P.WM), wj_shift = __builtin_ctz((unsigned)P.WJ);
+    const int wm = wave & (P.WM - 1), wj = (wave >> wm_shift) & (P.WJ - 1), wk = wave >> (wm_shift + wj_shift);
 
-    const int tm = blockIdx.y % P.NTM, tj = blockIdx.y / P.NTM;
+    int tm, tj;
+    fast_divmod((int)blockIdx.y, P.NTM, frcp(P.NTM), tj, tm);
     const int m0 = tm * P.M_WG;   // first output channel of the workgroup tile
     const int jb = tj * P.J_WG;   // first column of A of the workgroup tile
     const int o_first = blockIdx.z * NOFF;
@@ -140,8 +157,9 @@ __global__ __launch_bounds__(kThreads, ((DT == XCONV_F32 && MT <= 2) ? 2 : 1)) v
     const elem_t *Ag = static_cast<const elem_t *>(P.A);
 
     // my share of the steps
-    const int t_begin = (int)(((long long)P.NS * blockIdx.x) / P.S);
-    const int t_end = (int)(((long long)P.NS * (blockIdx.x + 1)) / P.S);
+    const int bx = blockIdx.x;
+    const int t_begin = bx * P.SQ + (bx < P.SR ? bx : P.SR);
+    const int t_end = t_begin + P.SQ + (bx < P.SR ? 1 : 0);
 
     // ---- per-thread staging tasks, decoded once -------------------------------
     // Global reads go through raw buffer loads: one resource per batch group whose
@@ -155,6 +173,7 @@ __global__ __launch_bounds__(kThreads, ((DT == XCONV_F32 && MT <= 2) ? 2 : 1)) v
 
     // dY task: (rb, ml, cc) = output row in the band, channel in the tile, vector chunk in the row
     const int ntask_a = P.RB * P.M_WG * P.NCHR;
+    const float rcp_nchr = frcp(P.NCHR), rcp_mwg = frcp(P.M_WG);
     // Threads without a task get an encoding that fails every predicate (chunk 255 / column
     // 65535 are never real) and an out-of-range load offset, so that the staging code below is
     // free of divergent early-outs: waits for the prefetched registers then sit in
@@ -166,9 +185,9 @@ __global__ __launch_bounds__(kThreads, ((DT == XCONV_F32 && MT <= 2) ? 2 : 1)) v
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
         const int task = tid + i * kThreads;
-        const int cc = task % P.NCHR;
-        const int ml = (task / P.NCHR) % P.M_WG;
-        const int rb = task / (P.NCHR * P.M_WG);
+        int cc, ml, rb, q;
+        fast_divmod(task, P.NCHR, rcp_nchr, q, cc);
+        fast_divmod(q, P.M_WG, rcp_mwg, rb, ml);
         const bool has = task < ntask_a;
         a_rbcc[i] = has ? ((rb << 8) | cc) : 255;
         a_goff[i] = (has && m0 + ml < P.C_out) ? ((uint32_t)(m0 + ml) * (uint32_t)P.dy_plane + (uint32_t)cc * EPV) * ES : kOOR;
@@ -180,9 +199,11 @@ __global__ __launch_bounds__(kThreads, ((DT == XCONV_F32 && MT <= 2) ? 2 : 1)) v
         }
     }
     // A task: (rr, c, jc) = row among the rows to load, staged column, vector of EPV channels
-    const int JC = P.J_WG / EPV;
+    const int JC = P.J_WG >> LOG_EPV;
     const int ntask_b = P.NNEW * P.BWc * JC;
-    const int rotmul = 8 / (P.J_WG >> 4);  // 16-bit layout: rotation of each 16-column group (see b_store_task)
+    const int jc_shift = __builtin_ctz((unsigned)JC);
+    const float rcp_bwc = frcp(P.BWc), rcp_nr = frcp(P.NR);
+    const int rotmul = 8 >> __builtin_ctz((unsigned)(P.J_WG >> 4));  // 16-bit layout: rotation of each 16-column group (see b_store_task)
     int b_rr[NB], b_c[NB];   // c = 65535 for a thread without a task: fails every column test
     uint32_t b_goff[NB];     // byte offset of (row rr, column c, vector jc) from the step's first row and column
     int b_lds[NB];           // LDS unit of (slot 0, column c, vector jc)
@@ -190,9 +211,9 @@ __global__ __launch_bounds__(kThreads, ((DT == XCONV_F32 && MT <= 2) ? 2 : 1)) v
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
         const int task = tid + i * kThreads;
-        const int jc = task % JC;
-        const int c = (task / JC) % P.BWc;
-        const int rr = task / (JC * P.BWc);
+        const int jc = task & (JC - 1);  // J_WG is 16, 32 or 64 and a vector is 4 or 8 columns: JC is a power of two
+        int c, rr;
+        fast_divmod(task >> jc_shift, P.BWc, rcp_bwc, rr, c);
         const bool has = task < ntask_b;
         b_rr[i] = has ? rr : 0;
         b_c[i] = has ? c : 0xffff;
@@ -349,7 +370,8 @@ __global__ __launch_bounds__(kThreads, ((DT == XCONV_F32 && MT <= 2) ? 2 : 1)) v
         for (int i = 0; i < NB; ++i) b_load_task(rs, iy0, ix0, b_rr[i], b_c[i], b_goff[i], rbv[i]);
     };
     auto b_store = [&](const StepPos &sp) {
-        const int rowmod = (sp.oy0 * P.sh + P.NOLD) % P.NR;
+        int rowmod, qd_;
+        fast_divmod(sp.oy0 * P.sh + P.NOLD, P.NR, rcp_nr, qd_, rowmod);
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
             int slot = rowmod + b_rr[i];
@@ -364,13 +386,17 @@ __global__ __launch_bounds__(kThreads, ((DT == XCONV_F32 && MT <= 2) ? 2 : 1)) v
         const int ix0 = sp.x0 * P.sw - P.pw;
         const int ntask = P.NOLD * P.BWc * JC;
         for (int task = tid; task < ntask; task += kThreads) {
-            const int jc = task % JC, c = (task / JC) % P.BWc, rr = task / (JC * P.BWc);
+            const int jc = task & (JC - 1);
+            int c, rr;
+            fast_divmod(task >> jc_shift, P.BWc, rcp_bwc, rr, c);
             const uint32_t goff = ((uint32_t)(rr * P.W + c) * (uint32_t)P.CS + (uint32_t)(jb + jc * EPV)) * ES;
             const int lds0 = F32 ? (c * P.BSTR + jc * 4) : (c * P.BSTR + 16 * (jc >> 1));
             const int rot = F32 ? 0 : (((jc & 1) * 8 + (jc >> 1) * rotmul) & 15);
             uint4 tmp[BI];
             b_load_task(rs, row_first - P.ph, ix0, rr, c, goff, tmp);
-            b_store_task((row_first + rr) % P.NR, c, lds0, rot, tmp);
+            int slot, qd_;
+            fast_divmod(row_first + rr, P.NR, rcp_nr, qd_, slot);
+            b_store_task(slot, c, lds0, rot, tmp);
         }
     };
 
@@ -382,106 +408,133 @@ __global__ __launch_bounds__(kThreads, ((DT == XCONV_F32 && MT <= 2) ? 2 : 1)) v
         for (int o = 0; o < NOFF; ++o) acc[mt][o] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     int off_ky[NOFF], off_kx[NOFF];
+    const float rcp_kw = frcp(P.kW);
 #pragma unroll
     for (int o = 0; o < NOFF; ++o) {
         const int oo = (o < noff) ? (o_first + o) : o_first;
-        off_ky[o] = oo / P.kW;
-        off_kx[o] = oo % P.kW;
+        fast_divmod(oo, P.kW, rcp_kw, off_ky[o], off_kx[o]);
     }
 
     // ---- MFMA loop over the k-steps of a staged step -----------------------------
     // A k-step is 4 consecutive pixel slots of one output row.  Wave wk takes
     // k-steps wk, wk+WK, ...  All of the bookkeeping below is wave-uniform.
     const int NXQ = P.CWp >> 2;          // k-steps per output row
-    const int NKS = P.RB * NXQ;          // k-steps per step
-    const int my_ks = (NKS - wk + P.WK - 1) / P.WK;
     // fp32 dY tile is [m][slot] (row stride ASTR floats), 16-bit tile is [slot][m] (slot stride ASTR units)
     const int a_lane = F32 ? (((wm * MT) * 16 + jl) * P.ASTR + g) : (g * P.ASTR + (wm * MT) * 16 + jl);
     const int a_mt = F32 ? 16 * P.ASTR : 16;  // LDS units between the M tiles of a wave
     const int b_lane = F32 ? (g * P.sw * P.BSTR + wj * 16 + jl) : (g * P.sw * P.BSTR + wj * 16 + ((jl + wj * rotmul) & 15));
     const int b_xq = 4 * P.sw * P.BSTR;  // LDS units between k-steps of a row
 
-    struct Frags {
-        unit_t a[MT];
-        unit_t b[NOFF];
+    // Fragment reads are issued as opaque instructions and waited for by hand.  Left to the
+    // compiler, the reads of a k-step end up right in front of the MFMAs that use them (it
+    // folds the double buffer into one set of registers), and the matrix cores idle for an LDS
+    // round trip per k-step.  Here the fragments of k-step i+1 are requested during the MFMAs
+    // of k-step i, each B fragment into the registers that the MFMAs of the previous offset
+    // have just read; LDS returns in order, so counting the younger requests tells when a
+    // fragment has arrived.
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+    using frag_t = typename std::conditional<F32, float, u32x4>::type;
+    constexpr uint32_t US = sizeof(unit_t);
+    auto lds_read = [](frag_t &dst, uint32_t addr) {
+        if constexpr (F32) asm volatile("ds_read_b32 %0, %1" : "=v"(dst) : "v"(addr) : "memory");
+        else asm volatile("ds_read_b128 %0, %1" : "=v"(dst) : "v"(addr) : "memory");
     };
-    struct Cursor {
-        int rb, xq, rowmod;          // output row in the band, k-step in the row, (oy*sh) mod NR
-        int brow[NOFF];              // LDS unit of (ring slot of the offset's row, column kx) for this output row
-    };
-    auto set_rows = [&](Cursor &c) {
-#pragma unroll
-        for (int o = 0; o < NOFF; ++o) {
-            int slot = c.rowmod + off_ky[o];
-            if (slot >= P.NR) slot -= P.NR;
-            c.brow[o] = (slot * P.BWc + off_kx[o]) * P.BSTR;
-        }
-    };
-    auto advance = [&](Cursor &c) {
-        c.xq += P.WK;
-        while (c.xq >= NXQ) {
-            c.xq -= NXQ;
-            ++c.rb;
-            c.rowmod += P.sh;
-            while (c.rowmod >= P.NR) c.rowmod -= P.NR;
-            set_rows(c);
-        }
-    };
-    auto load_frags = [&](Frags &f, const Cursor &c, const unit_t *lds_a) {
-        const int p0 = c.rb * P.CWp + (c.xq << 2);  // first pixel slot of the k-step
-        const unit_t *pa = lds_a + (F32 ? p0 : p0 * P.ASTR) + a_lane;
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) f.a[mt] = pa[mt * a_mt];
-        const unit_t *pb = lds_b + (size_t)(c.xq * b_xq) + b_lane;
-#pragma unroll
-        for (int o = 0; o < NOFF; ++o) f.b[o] = pb[c.brow[o]];
-    };
-    auto mfma_frags = [&](const Frags &f) {
-#pragma unroll
-        for (int o = 0; o < NOFF; ++o)
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                if constexpr (F32) acc[mt][o] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.a[mt], f.b[o], acc[mt][o], 0, 0, 0);
-                else acc[mt][o] = mfma16<DT>(f.a[mt], f.b[o], acc[mt][o]);
-            }
-    };
+    const uint32_t lds0 = __builtin_amdgcn_groupstaticsize();  // the dynamic allocation starts behind the static one
+    const uint32_t a_base = lds0 + (uint32_t)a_lane * US;
+    const uint32_t b_base = lds0 + (uint32_t)(P.a_units + b_lane) * US;
+    const uint32_t a_slot_bytes = F32 ? 4u : (uint32_t)P.ASTR * 16u;
+    const uint32_t a_mt_bytes = (uint32_t)a_mt * US;
+    const uint32_t step_a = (uint32_t)(4 * P.WK) * a_slot_bytes;   // bytes between two k-steps of this wave in a row
+    const uint32_t step_b = (uint32_t)(P.WK * b_xq) * US;
+    const int n_row = (NXQ - wk + P.WK - 1) >> __builtin_ctz((unsigned)P.WK);                // k-steps of this wave in every output row: xq = wk, wk + WK, ...
+    int sh_mod, qs_;
+    fast_divmod(P.sh, P.NR, rcp_nr, qs_, sh_mod);
+    const int kRB = P.RB, kNR = P.NR, kCWp = P.CWp, kBWc = P.BWc, kBSTR = P.BSTR;  // loop constants, read once
 
     // ---- main loop ---------------------------------------------------------------
     // MFMA loop of one staged step
-    auto compute_step = [&](const StepPos &spc, const unit_t *lds_a) {
-        Cursor cur;
-        cur.rb = 0;
-        cur.xq = wk;
-        cur.rowmod = (spc.oy0 * P.sh) % P.NR;
-        set_rows(cur);
-        while (cur.xq >= NXQ) {  // WK > NXQ: the first k-step of this wave is in a later row
-            cur.xq -= NXQ;
-            ++cur.rb;
-            cur.rowmod += P.sh;
-            while (cur.rowmod >= P.NR) cur.rowmod -= P.NR;
-            set_rows(cur);
-        }
-        // double-buffered fragments: the LDS reads of k-step i+1 are in flight during the MFMAs of k-step i
-        Frags f0, f1;
-        int left = my_ks;
-        if (left > 0) {
-            load_frags(f0, cur, lds_a);
-            advance(cur);
-        }
-        while (left > 0) {
-            if (left > 1) {
-                load_frags(f1, cur, lds_a);
-                advance(cur);
+    auto compute_step = [&](const StepPos &spc) {
+        if (n_row <= 0) return;
+        const int total = kRB * n_row;
+        int rowmod, qd_;   // ring slot of the first row that output row rb needs
+        fast_divmod(spc.oy0 * P.sh, kNR, rcp_nr, qd_, rowmod);
+        uint32_t pa[MT], pb[NOFF];
+        auto set_row = [&](int rb) {
+            const uint32_t a0 = a_base + (uint32_t)(rb * kCWp + 4 * wk) * a_slot_bytes;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) pa[mt] = a0 + (uint32_t)mt * a_mt_bytes;
+#pragma unroll
+            for (int o = 0; o < NOFF; ++o) {
+                int slot = rowmod + off_ky[o];
+                slot = slot >= kNR ? slot - kNR : slot;
+                const int u = __builtin_amdgcn_readfirstlane(wk * b_xq + (slot * kBWc + off_kx[o]) * kBSTR);
+                pb[o] = b_base + (uint32_t)u * US;
             }
-            mfma_frags(f0);
-            if (--left == 0) break;
-            if (left > 1) {
-                load_frags(f0, cur, lds_a);
-                advance(cur);
+        };
+        auto tie = [](frag_t &r) { asm volatile("" : "+v"(r)); };
+        frag_t a[MT], an[MT], b[NOFF];
+        auto a_arrived = [&]() {  // the A fragments are the oldest of the MT + NOFF requests of a k-step
+            asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(NOFF) : "memory");
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) tie(an[mt]);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) a[mt] = an[mt];
+        };
+        set_row(0);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) lds_read(an[mt], pa[mt]);
+#pragma unroll
+        for (int o = 0; o < NOFF; ++o) lds_read(b[o], pb[o]);
+        a_arrived();
+
+        // One k-step: its MFMAs and the requests for the fragments at (pa, pb).  Requests in
+        // issue order: A (MT), then B of offset o-1 right after the MFMAs of offset o, B of the
+        // last offset at the end.  Before the MFMAs of offsets o..o+2 (o = 0, 3, 6) the previous
+        // k-step's requests up to offset o+2 must be done: at that point the younger ones are
+        // the rest of the previous k-step, this k-step's A and its B up to offset o-2.
+        constexpr int WG3 = (NOFF % 3 == 0) ? 3 : 1;
+        auto kstep = [&]() {
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) lds_read(an[mt], pa[mt]);
+            ws_for<0, NOFF>([&](auto oc) {
+                constexpr int o = decltype(oc)::value;
+                if constexpr (o % WG3 == 0) {
+                    constexpr int younger = (NOFF - WG3 - o) + MT + (o >= 2 ? o - 1 : 0);
+                    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(younger) : "memory");
+#pragma unroll
+                    for (int q = 0; q < WG3; ++q) tie(b[o + q]);
+                }
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    if constexpr (F32) acc[mt][o] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[mt], b[o], acc[mt][o], 0, 0, 0);
+                    else acc[mt][o] = mfma16<DT>(__builtin_bit_cast(uint4, a[mt]), __builtin_bit_cast(uint4, b[o]), acc[mt][o]);
+                }
+                if constexpr (o >= 1) lds_read(b[o - 1], pb[o - 1]);
+            });
+            lds_read(b[NOFF - 1], pb[NOFF - 1]);
+            a_arrived();
+            __builtin_amdgcn_sched_barrier(0);
+        };
+
+        int i_row = 0, rb = 0;
+        for (int i = 0; i < total; ++i) {
+            // addresses of the k-step after this one (after the last one: unchanged, the requests repeat)
+            if (++i_row == n_row) {
+                i_row = 0;
+                ++rb;
+                rowmod += sh_mod;
+                rowmod = rowmod >= kNR ? rowmod - kNR : rowmod;
+                if (rb < kRB) set_row(rb);
+            } else {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) pa[mt] += step_a;
+#pragma unroll
+                for (int o = 0; o < NOFF; ++o) pb[o] += step_b;
             }
-            mfma_frags(f1);
-            --left;
+            kstep();
         }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     };
     auto contiguous = [&](const StepPos &a, const StepPos &b) { return b.bg == a.bg && b.x0 == a.x0 && b.oy0 == a.oy0 + P.RB; };
 
@@ -510,7 +563,7 @@ __global__ __launch_bounds__(kThreads, ((DT == XCONV_F32 && MT <= 2) ? 2 : 1)) v
         // the second workgroup on the CU, which is staging while this one multiplies).  Everything
         // but the MFMA loop runs at a raised priority so that staging slips in between MFMAs.
         __builtin_amdgcn_s_setprio(0);
-        compute_step(sp, lds_a0);
+        compute_step(sp);
         __builtin_amdgcn_s_setprio(2);
         prev = sp;
         sp = spn;
@@ -883,7 +936,10 @@ static hipError_t launch_corr_cfg(const CorrParams &P, size_t lds, hipStream_t s
             done_bytes = kLdsLimit;
         }
     }
-    hipLaunchKernelGGL((corr_kernel<DT, MT, NA, NB, NOFF, AL>), dim3(P.S, P.NTM * P.NTJ, P.NOG), dim3(kThreads), lds, st, P);
+    CorrParams Q = P;
+    Q.SQ = P.NS / P.S;
+    Q.SR = P.NS % P.S;
+    hipLaunchKernelGGL((corr_kernel<DT, MT, NA, NB, NOFF, AL>), dim3(P.S, P.NTM * P.NTJ, P.NOG), dim3(kThreads), lds, st, Q);
     return hipGetLastError();
 }
 

@@ -70,11 +70,18 @@ __device__ inline WsPos ws_pos_of(const WsParams &P, int t)
     WsPos p;
     p.t = t;
     p.u = 0;
-    p.y = t % P.Ho;
-    const int q = t / P.Ho;
-    p.strip = q % P.NSTRIP;
-    p.bg = q / P.NSTRIP;
-    p.rowmod = (p.y * P.sh) % P.NRING;
+    if (t < (1 << 22)) {
+        int q;
+        fast_divmod(t, P.Ho, frcp(P.Ho), q, p.y);
+        fast_divmod(q, P.NSTRIP, frcp(P.NSTRIP), p.bg, p.strip);
+    } else {
+        p.y = t % P.Ho;
+        const int q = t / P.Ho;
+        p.strip = q % P.NSTRIP;
+        p.bg = q / P.NSTRIP;
+    }
+    int qr;
+    fast_divmod(p.y * P.sh, P.NRING, frcp(P.NRING), qr, p.rowmod);
     return ws_uniform(p);
 }
 
@@ -146,20 +153,22 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int tm = blockIdx.y % P.NTM, tj = blockIdx.y / P.NTM;
+    int tm, tj;
+    fast_divmod((int)blockIdx.y, P.NTM, frcp(P.NTM), tj, tm);
     const int m0 = tm * P.M_WG;
     const int jb = tj * P.J_WG;
     const int o_first = blockIdx.z * NOFF;
     const int noff = (P.K2 - o_first) < NOFF ? (P.K2 - o_first) : NOFF;
 
-    const int t_begin = (int)(((long long)P.NS * blockIdx.x) / P.S);
-    const int t_end = (int)(((long long)P.NS * (blockIdx.x + 1)) / P.S);
+    const int bx = blockIdx.x;
+    const int t_begin = bx * P.SQ + (bx < P.SR ? bx : P.SR);
+    const int t_end = t_begin + P.SQ + (bx < P.SR ? 1 : 0);
     const int NI = (t_end - t_begin) * P.NSUB;  // sub-steps of this workgroup
     // Units of one staged pixel: the 16-column group G sits at 16G, rotated by (G/2)*rotmul.  Both
     // groups that a consumer wave reads together (G = 2wj, 2wj+1) have the same rotation, which
     // ds_read_b128 needs to stay free of bank conflicts; the rotation between waves' groups spreads
     // the producers' writes (8 columns per lane, lanes running over the column vectors) over banks.
-    const int rotmul = 8 / P.WJ;
+    const int rotmul = 8 >> __builtin_ctz((unsigned)P.WJ);  // WJ is 1, 2 or 4
 
     if (wave < 4) {
         // =========================== consumers ===========================
@@ -168,7 +177,7 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
         // the MFMA stream goes first; the producers' vector and LDS instructions fill the gaps
         __builtin_amdgcn_s_setprio(3);
         const int l32 = lane & 31, g = lane >> 5;
-        const int wm = wave % P.WM, wj = wave / P.WM;
+        const int wm = wave & (P.WM - 1), wj = wave >> __builtin_ctz((unsigned)P.WM);  // WM is 1, 2 or 4
         const int a_lane = g * P.M_WG + wm * 32 + l32;
         const int G = 2 * wj + (l32 >> 4);  // 16-column group of this lane's column
         const int b_lane = g * P.sw * P.BSTR + G * 16 + (((l32 & 15) + wj * rotmul) & 15);
@@ -183,8 +192,7 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
 #pragma unroll
         for (int o = 0; o < NOFF; ++o) {
             const int oo = (o < noff) ? (o_first + o) : o_first;  // spare slots redo the first offset and are not written
-            off_ky[o] = oo / P.kW;
-            off_kx[o] = oo % P.kW;
+            fast_divmod(oo, P.kW, frcp(P.kW), off_ky[o], off_kx[o]);
         }
         auto set_brow = [&](const WsPos &p, int (&brow)[NOFF]) {
 #pragma unroll
@@ -332,7 +340,8 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
             // chunk index fastest: neighbouring lanes read neighbouring 16-byte pieces of one
             // (image, channel) row, which the memory pipeline merges into one request
             const int nch = (P.CWs + 7) >> 3;
-            const int ch = s % nch, m = s / nch;
+            int ch, m;
+            fast_divmod(s, nch, frcp(nch), m, ch);
             a_goff[k] = (s < P.NA && m0 + m < P.C_out) ? ((uint32_t)(m0 + m) * (uint32_t)HoWo + 8u * ch) * 2u : kOOR;
             a_lds[k] = 8 * ch * P.M_WG + m;
             a_c8[k] = 8 * ch;
@@ -760,7 +769,10 @@ static hipError_t launch_ws_cfg(const WsParams &P, hipStream_t st)
         if (e != hipSuccess) return e;
         done = true;
     }
-    hipLaunchKernelGGL((corr_ws_kernel<DT, 9, NTASK, D, CB>), dim3(P.S, P.NTM * P.NTJ, P.NOG), dim3(kWsThreads), lds, st, P);
+    WsParams Q = P;
+    Q.SQ = P.NS / P.S;
+    Q.SR = P.NS % P.S;
+    hipLaunchKernelGGL((corr_ws_kernel<DT, 9, NTASK, D, CB>), dim3(P.S, P.NTM * P.NTJ, P.NOG), dim3(kWsThreads), lds, st, Q);
     return hipGetLastError();
 }
 
