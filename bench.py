@@ -55,7 +55,8 @@ def algorithmic(cfg):
 class Layer:
     """Device buffers of one layer, `nsets` rotating copies."""
 
-    def __init__(self, cfg, nsets, dev):
+    def __init__(self, cfg, nsets, dev, nhwc=False):
+        import numpy as np
         import torch
         from paper_2106_06998_amd import binding as xb
         from paper_2106_06998_amd import synth
@@ -63,6 +64,10 @@ class Layer:
         self.desc = xb.desc_from_config(cfg)
         X, dY = synth.make_layer(cfg)
         self.host = (X, dY)
+        if nhwc:            # the same values handed over channels-last
+            self.desc.layout = xb.XCONV_NHWC
+            X = np.ascontiguousarray(X.transpose(0, 2, 3, 1))
+            dY = np.ascontiguousarray(dY.transpose(0, 2, 3, 1))
         self.sets = []
         for i in range(nsets):
             Xd = xb.to_device(X, cfg.dtype, dev)
@@ -129,9 +134,9 @@ def nsets_for(cfg):
     return max(3, min(n, 16))
 
 
-def measure_config(cfg, steps, warmup, dev, with_exact=False):
+def measure_config(cfg, steps, warmup, dev, with_exact=False, nhwc=False):
     from paper_2106_06998_amd import binding as xb
-    L = Layer(cfg, nsets_for(cfg), dev)
+    L = Layer(cfg, nsets_for(cfg), dev, nhwc)
     ms_step = time_region(L.step, steps, warmup)
     kt, wall_prof = kernel_times(xb, L.step, steps, warmup)
     alg = algorithmic(cfg)
@@ -180,6 +185,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="C2", help="layer the headline value is quoted on (default: configs[1])")
     ap.add_argument("--all", action="store_true", help="also measure the other benchmark layers (extra field per_config)")
+    ap.add_argument("--nhwc", action="store_true", help="hand X and dY over channels-last (layout XCONV_NHWC) instead of NCHW")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--no-exact", action="store_true", help="skip timing xconv_dw_exact (for clean per-kernel profiles)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -208,7 +214,7 @@ def main():
         print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": dst.numel() * 4, "copies": 10}))
         return 0
     cfg = synth.CONFIGS[args.config]
-    res, L = measure_config(cfg, args.steps, args.warmup, dev, with_exact=not args.no_exact)
+    res, L = measure_config(cfg, args.steps, args.warmup, dev, with_exact=not args.no_exact, nhwc=args.nhwc)
     alg = algorithmic(cfg)
 
     # roofline of the dominant kernel of the step
@@ -235,8 +241,9 @@ def main():
         "value": res["ms_per_layer"], "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": res["ms_per_layer"], "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": "%s: B=%d C_in=%d C_out=%d H=W=%d k=%d stride=%d pad=%d r=%d %s probes, %s storage" % (
-            cfg.name, cfg.B, cfg.C_in, cfg.C_out, cfg.H, cfg.k, cfg.stride, cfg.pad, cfg.r, cfg.probe, cfg.dtype)},
+        "config": {"workload": "%s: B=%d C_in=%d C_out=%d H=W=%d k=%d stride=%d pad=%d r=%d %s probes, %s storage, %s" % (
+            cfg.name, cfg.B, cfg.C_in, cfg.C_out, cfg.H, cfg.k, cfg.stride, cfg.pad, cfg.r, cfg.probe, cfg.dtype,
+            "NHWC" if args.nhwc else "NCHW")},
         "gbps": (alg["probe_bytes"] + alg["corr_bytes"]) / res["ms_per_layer"] / 1e6,
         "gflops": (alg["probe_flops"] + alg["corr_flops"]) / res["ms_per_layer"] / 1e6,
         "roofline": roof,

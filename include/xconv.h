@@ -46,7 +46,7 @@ typedef enum {
 } xconv_status;
 
 typedef enum { XCONV_F32 = 0, XCONV_BF16 = 1, XCONV_F16 = 2 } xconv_dtype;   /* storage of X, dY, Xt; sums and dW are fp32 */
-typedef enum { XCONV_NCHW = 0, XCONV_NHWC = 1 } xconv_layout;                /* of X and dY                                 */
+typedef enum { XCONV_NCHW = 0, XCONV_NHWC = 1 } xconv_layout;                /* of X and dY ([B,C,H,W] or [B,H,W,C]); dW is always [C_out,C_in,kH,kW] */
 typedef enum { XCONV_RADEMACHER = 0, XCONV_GAUSSIAN = 1, XCONV_USER_Z = 2 } xconv_probe;
 typedef enum { XCONV_OP_PROBE = 0, XCONV_OP_ESTIMATE = 1, XCONV_OP_EXACT = 2 } xconv_op;
 
@@ -66,7 +66,7 @@ typedef struct xconv_desc {
 
 /* Host-only validation.  XCONV_EINVAL: null desc, an extent < 1, stride < 1,
  * pad < 0, r < 1, H' or W' < 1, unknown enum, reserved != 0.
- * XCONV_EUNSUPPORTED: layout NHWC; r > 1024; C_in or C_out > 65536; kH*kW > 49;
+ * XCONV_EUNSUPPORTED: r > 1024; C_in or C_out > 65536; kH*kW > 49;
  * an extent whose tensors exceed 2^31-1 elements per image plane. */
 xconv_status xconv_check_desc(const xconv_desc *desc);
 
@@ -79,7 +79,9 @@ size_t xconv_xt_bytes(const xconv_desc *desc);
  * scratch holds Z (fp32, and for the probe in matrix-core operand order) when
  * it is regenerated from the seed, the split partial sums
  * of the correlation, a repacked copy of dY when H'*W' is not a whole number of
- * 16-byte vectors and, for the exact gradient, a channels-last copy of X.
+ * 16-byte vectors or dY is channels-last (the correlation reads dY as planes; the
+ * copy costs one extra read and write of dY) and, for the exact gradient, a
+ * channels-last copy of X (not needed for an NHWC X whose C_in is a multiple of 16).
  * 0 for an invalid desc. */
 size_t xconv_workspace_bytes(const xconv_desc *desc, int op);
 
@@ -93,7 +95,8 @@ xconv_status xconv_probe_matrix(const xconv_desc *desc, float *Z_host);
 /* The same matrix generated on the device into Z_dev[C_in*r] (fp32). */
 xconv_status xconv_probe_matrix_dev(const xconv_desc *desc, float *Z_dev, void *stream);
 
-/* Forward probe (Alg. 1 fwd step 3).  X_dev: [B,C_in,H,W] in desc->dtype.
+/* Forward probe (Alg. 1 fwd step 3).  X_dev: [B,C_in,H,W] (or [B,H,W,C_in] for
+ * XCONV_NHWC, read directly) in desc->dtype.
  * Xt_dev: xconv_xt_bytes() bytes, written once.  Z_dev: [C_in,r] fp32 or NULL;
  * NULL draws Z from (probe, seed) into the workspace (XCONV_USER_Z then is
  * XCONV_EINVAL).  Sums are fp32; Xt is rounded once (nearest even) to
@@ -105,8 +108,8 @@ xconv_status xconv_probe_matrix_dev(const xconv_desc *desc, float *Z_dev, void *
 xconv_status xconv_probe_fwd(const xconv_desc *desc, const void *X_dev, void *Xt_dev,
                              const float *Z_dev, void *ws_dev, size_t ws_bytes, void *stream);
 
-/* Backward estimate (Alg. 1 bwd steps 1-4).  dY_dev: [B,C_out,H',W'] in
- * desc->dtype, 16-byte aligned.  Xt_dev: as written by xconv_probe_fwd for the same desc.
+/* Backward estimate (Alg. 1 bwd steps 1-4).  dY_dev: [B,C_out,H',W'] (or
+ * [B,H',W',C_out] for XCONV_NHWC) in desc->dtype, 16-byte aligned.  Xt_dev: as written by xconv_probe_fwd for the same desc.
  * Z_dev: as above (must be the Z used in the forward).  dW_dev:
  * [C_out,C_in,kH,kW] fp32, overwritten.  The result is deterministic for given
  * inputs (fixed-order two-pass reduction, no atomics). */
@@ -116,7 +119,7 @@ xconv_status xconv_dw_estimate(const xconv_desc *desc, const void *dY_dev, const
 
 /* Exact weight gradient (Eq. (2)/(5)), for comparison with the estimate: same
  * correlation kernel with the C_in real channels in place of the r probed
- * ones.  X_dev: [B,C_in,H,W]; dY_dev 16-byte aligned; dW_dev: [C_out,C_in,kH,kW] fp32, overwritten.
+ * ones.  X_dev: [B,C_in,H,W] (XCONV_NHWC: X and dY channels-last); dY_dev 16-byte aligned; dW_dev: [C_out,C_in,kH,kW] fp32, overwritten.
  * desc->r, probe and seed are ignored (r must still be >= 1). */
 xconv_status xconv_dw_exact(const xconv_desc *desc, const void *dY_dev, const void *X_dev,
                             float *dW_dev, void *ws_dev, size_t ws_bytes, void *stream);

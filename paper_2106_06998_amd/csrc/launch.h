@@ -7,16 +7,21 @@ namespace xc {
 // probe_kernels.hip
 void host_probe_matrix(int dist, uint64_t seed, int n, float *Z);
 hipError_t launch_gen_z(float *Z, int n, int dist, uint64_t seed, hipStream_t st);
-bool probe_fast_path_ok(int dtype, int C_in, int HW);
+// nhwc: X is channels-last [B, H, W, C_in] instead of [B, C_in, H, W]
+bool probe_fast_path_ok(int dtype, int C_in, int HW, bool nhwc);
 size_t zpack_bytes(int dtype, int C_in, int r, bool z_exact16);
 hipError_t launch_pack_z(int dtype, const float *Z, void *out, int C_in, int r, bool z_exact16, int dist, uint64_t seed,
-                         hipStream_t st);
+                         bool nhwc, hipStream_t st);
 hipError_t launch_probe(int dtype, const void *X, const float *Z, const void *zpack, void *Xt, int B, int C_in, int HW, int r,
-                        int CS, bool z_exact16, hipStream_t st);
+                        int CS, bool z_exact16, bool nhwc, hipStream_t st);
 hipError_t launch_probe_generic(int dtype, const void *X, const float *Z, void *Xt, int B, int C_in, int HW, int r, int CS,
-                                hipStream_t st);
+                                bool nhwc, hipStream_t st);
 hipError_t launch_unpack(int dtype, const void *Xt, float *out, int B, int HW, int r, int CS, hipStream_t st);
 hipError_t launch_to_nhwc(int dtype, const void *X, void *out, int B, int C, int HW, int CS, hipStream_t st);
+// channels-last [B, HW, C] -> planes [B, C, pitch], zero tail
+hipError_t launch_to_nchw(int dtype, const void *src, void *out, int B, int C, int HW, int pitch, hipStream_t st);
+// channels-last [npix, C] -> [npix, CS], zero columns C..CS-1
+hipError_t launch_pad_channels(int dtype, const void *src, void *out, long long npix, int C, int CS, hipStream_t st);
 
 // corr_kernels.hip
 // Fills every field of P except the three pointers.  Q is the number of

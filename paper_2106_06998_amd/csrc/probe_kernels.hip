@@ -46,14 +46,19 @@ __device__ inline int jmap(int jt, int i, int JT) { return (i >> 2) * (4 * JT) +
 //           channels 32kk + 8(lane/16) .. +7 of column j; with `split` the rounding residue
 //           z - hi follows nfrag entries later.
 // ---------------------------------------------------------------------------
+// channel that lane group g of fragment kq stands for.  NCHW: 4kq + g.  Channels-last input: a
+// lane loads 4 consecutive channels and MFMA u takes element u, so within a block of 16
+// channels fragment u holds channel 4g + u.
+__device__ inline int f32_frag_channel(int kq, int g, bool nhwc) { return nhwc ? 16 * (kq >> 2) + 4 * g + (kq & 3) : 4 * kq + g; }
+
 __global__ __launch_bounds__(kThreads) void pack_z_f32_kernel(const float *__restrict__ Z, float *__restrict__ out, int C_in, int r,
-                                                              int NTJ, int KQ4, int dist, uint64_t seed)
+                                                              int NTJ, int KQ4, int dist, uint64_t seed, int nhwc)
 {
     const int e = blockIdx.x * kThreads + threadIdx.x;
     if (e >= KQ4 * NTJ * 64) return;
     const int l = e & 63, tj = (e >> 6) % NTJ, kq = (e >> 6) / NTJ;
     const int bi = tj >> 2, jt = tj & 3, JTb = (NTJ - 4 * bi) < 4 ? (NTJ - 4 * bi) : 4;
-    const int c = kq * 4 + (l >> 4), j = 64 * bi + jmap(jt, l & 15, JTb);
+    const int c = f32_frag_channel(kq, l >> 4, nhwc != 0), j = 64 * bi + jmap(jt, l & 15, JTb);
     float z = 0.0f;
     if (c < C_in && j < r) {
         const size_t idx = (size_t)c * r + j;
@@ -102,7 +107,10 @@ __global__ __launch_bounds__(kThreads) void pack_z_16_kernel(const float *__rest
 // consecutive pixels (16 bytes) of one channel; MFMA t uses element t, so MFMA
 // column n stands for pixel 4n+t of the wave's 64-pixel tile.
 // ---------------------------------------------------------------------------
-template <int JT>
+// NHWC: X is [pixels, C_in]; a lane then loads four consecutive channels (16 bytes) of one pixel,
+// MFMA u uses element u of every lane (see f32_frag_channel), and the wave's tile is four
+// sub-tiles of 16 pixels; `ngroups` is the number of pixels.
+template <int JT, bool NHWC>
 __global__ __launch_bounds__(kThreads) void probe_f32_kernel(const float *__restrict__ X, const float *__restrict__ Z,
                                                              const float *__restrict__ zpack, float *__restrict__ Xt, int C_in,
                                                              int HW, int r, int CS, int j0, long long ngroups, int ntiles)
@@ -117,7 +125,7 @@ __global__ __launch_bounds__(kThreads) void probe_f32_kernel(const float *__rest
     } else {
         for (int e = tid; e < nfrag; e += kThreads) {
             const int l = e & 63, jt = (e >> 6) % JT, kq = (e >> 6) / JT;
-            const int c = kq * 4 + (l >> 4);
+            const int c = f32_frag_channel(kq, l >> 4, NHWC);
             const int j = j0 + jmap(jt, l & 15, JT);
             zs[e] = (c < C_in && j < r) ? Z[(size_t)c * r + j] : 0.0f;
         }
@@ -127,27 +135,44 @@ __global__ __launch_bounds__(kThreads) void probe_f32_kernel(const float *__rest
     const int n = lane & 15, g = lane >> 4;
     const long long last_group = ngroups - 1;
     for (int tile = blockIdx.x * 4 + wave; tile < ntiles; tile += gridDim.x * 4) {
-        const long long pg_raw = (long long)tile * 16 + n;
-        const bool valid = pg_raw < ngroups;
-        const long long pg = valid ? pg_raw : last_group;  // lanes past the end redo the last group and store nothing
-        const long long flat = pg * 4;
-        const int b = (int)(flat / HW);
-        const int p = (int)(flat % HW);
-        const float *xb = X + (size_t)b * C_in * HW + p;
         f32x4 acc[JT][4];
 #pragma unroll
         for (int jt = 0; jt < JT; ++jt)
 #pragma unroll
             for (int t = 0; t < 4; ++t) acc[jt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        // pixel (or group of 4 pixels) of this lane; lanes past the end redo the last one and store nothing
+        const float *xb[NHWC ? 4 : 1];
+        long long first[NHWC ? 4 : 1];
+        bool valid[NHWC ? 4 : 1];
+        if constexpr (NHWC) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const long long pp = (long long)tile * 64 + 16 * t + n;
+                valid[t] = pp < ngroups;
+                first[t] = valid[t] ? pp : last_group;
+                xb[t] = X + (size_t)first[t] * C_in;
+            }
+        } else {
+            const long long pg_raw = (long long)tile * 16 + n;
+            valid[0] = pg_raw < ngroups;
+            first[0] = (valid[0] ? pg_raw : last_group) * 4;
+            xb[0] = X + (size_t)(first[0] / HW) * C_in * HW + (int)(first[0] % HW);
+        }
 
-        // Loads are unconditional (channels past the end re-read the last channel against zero
+        // Loads are unconditional (channels past the end re-read the last channels against zero
         // fragment entries), so the next 16 channels are fetched while these are multiplied.
         auto load16 = [&](float4 (&v)[4], int c0) {
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                int c = c0 + 4 * u + g;
-                c = c < C_in ? c : C_in - 1;
-                v[u] = *reinterpret_cast<const float4 *>(xb + (size_t)c * HW);
+                if constexpr (NHWC) {
+                    int c = c0 + 4 * g;
+                    c = c < C_in ? c : C_in - 4;
+                    v[u] = *reinterpret_cast<const float4 *>(xb[u] + c);
+                } else {
+                    int c = c0 + 4 * u + g;
+                    c = c < C_in ? c : C_in - 1;
+                    v[u] = *reinterpret_cast<const float4 *>(xb[0] + (size_t)c * HW);
+                }
             }
         };
         auto process = [&](const float4 (&v)[4], int c0) {
@@ -157,10 +182,22 @@ __global__ __launch_bounds__(kThreads) void probe_f32_kernel(const float *__rest
 #pragma unroll
                 for (int jt = 0; jt < JT; ++jt) {
                     const float a = zs[(kq * JT + jt) * 64 + lane];
-                    acc[jt][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, v[u].x, acc[jt][0], 0, 0, 0);
-                    acc[jt][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, v[u].y, acc[jt][1], 0, 0, 0);
-                    acc[jt][2] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, v[u].z, acc[jt][2], 0, 0, 0);
-                    acc[jt][3] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, v[u].w, acc[jt][3], 0, 0, 0);
+                    if constexpr (NHWC) {
+                        // fragment u multiplies element u of the four pixels' channel vectors
+                        const float e0 = u == 0 ? v[0].x : u == 1 ? v[0].y : u == 2 ? v[0].z : v[0].w;
+                        const float e1 = u == 0 ? v[1].x : u == 1 ? v[1].y : u == 2 ? v[1].z : v[1].w;
+                        const float e2 = u == 0 ? v[2].x : u == 1 ? v[2].y : u == 2 ? v[2].z : v[2].w;
+                        const float e3 = u == 0 ? v[3].x : u == 1 ? v[3].y : u == 2 ? v[3].z : v[3].w;
+                        acc[jt][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, e0, acc[jt][0], 0, 0, 0);
+                        acc[jt][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, e1, acc[jt][1], 0, 0, 0);
+                        acc[jt][2] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, e2, acc[jt][2], 0, 0, 0);
+                        acc[jt][3] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, e3, acc[jt][3], 0, 0, 0);
+                    } else {
+                        acc[jt][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, v[u].x, acc[jt][0], 0, 0, 0);
+                        acc[jt][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, v[u].y, acc[jt][1], 0, 0, 0);
+                        acc[jt][2] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, v[u].z, acc[jt][2], 0, 0, 0);
+                        acc[jt][3] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, v[u].w, acc[jt][3], 0, 0, 0);
+                    }
                 }
             }
         };
@@ -180,14 +217,13 @@ __global__ __launch_bounds__(kThreads) void probe_f32_kernel(const float *__rest
         } else {
             process(v0, c0);
         }
-        if (valid) {
-            // lane (n, g) holds rows 4g..4g+3 of every tile = probe columns j0 + g*4*JT + jt*4 + v
-            float *out = Xt + (size_t)flat * CS + j0 + g * (4 * JT);
+        // lane (n, g) holds rows 4g..4g+3 of every tile = probe columns j0 + g*4*JT + jt*4 + v
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
+        for (int t = 0; t < 4; ++t) {
+            if (!valid[NHWC ? t : 0]) continue;
+            float *out = Xt + (size_t)(NHWC ? first[NHWC ? t : 0] : first[0] + t) * CS + j0 + g * (4 * JT);
 #pragma unroll
-                for (int jt = 0; jt < JT; ++jt)
-                    *reinterpret_cast<f32x4 *>(out + (size_t)t * CS + jt * 4) = acc[jt][t];
+            for (int jt = 0; jt < JT; ++jt) *reinterpret_cast<f32x4 *>(out + jt * 4) = acc[jt][t];
         }
     }
 }
@@ -200,7 +236,9 @@ __global__ __launch_bounds__(kThreads) void probe_f32_kernel(const float *__rest
 // every lane.  SPLIT: Z is not exactly representable in the storage type
 // (Gaussian or user Z), so it is used as hi + lo (two MFMAs); +-1 needs one.
 // ---------------------------------------------------------------------------
-template <int DT, int JT, int PT, bool SPLIT>
+// NHWC: X is [pixels, C_in]; the 8 channels a lane supplies are then one 16-byte load, no
+// transpose; the wave's tile is PT sub-tiles of 16 pixels and `ngroups` is the number of pixels.
+template <int DT, int JT, int PT, bool SPLIT, bool NHWC>
 __global__ __launch_bounds__(kThreads) void probe_16_kernel(const uint16_t *__restrict__ X, const float *__restrict__ Z,
                                                             const uint4 *__restrict__ zpack, uint16_t *__restrict__ Xt, int C_in,
                                                             int HW, int r, int CS, int j0, long long ngroups, int ntiles)
@@ -253,38 +291,67 @@ __global__ __launch_bounds__(kThreads) void probe_16_kernel(const uint16_t *__re
     const int n = lane & 15, g = lane >> 4;
     const long long last_group = ngroups - 1;
     for (int tile = blockIdx.x * 4 + wave; tile < ntiles; tile += gridDim.x * 4) {
-        const long long pg_raw = (long long)tile * 16 + n;
-        const bool valid = pg_raw < ngroups;
-        const long long pg = valid ? pg_raw : last_group;  // lanes past the end redo the last group and store nothing
-        const long long flat = pg * PT;
-        const int b = (int)(flat / HW);
-        const int p = (int)(flat % HW);
-        const uint16_t *xb = X + (size_t)b * C_in * HW + p;
         f32x4 acc[JT][PT];
 #pragma unroll
         for (int jt = 0; jt < JT; ++jt)
 #pragma unroll
             for (int t = 0; t < PT; ++t) acc[jt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-        // Loads are unconditional (channels past the end re-read the last channel, whose Z
-        // fragment entries are zero), so the next K-step can be prefetched without branches.
-        auto load_rows = [&](uint32_t (&rows)[8][NW], int kk) {
+        // pixel (NHWC) or group of PT pixels (NCHW) of this lane; lanes past the end redo the last one and store nothing
+        constexpr int NP = NHWC ? PT : 1;
+        const uint16_t *xb[NP];
+        long long first[NP];
+        bool valid[NP];
+        if constexpr (NHWC) {
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                int c = kk * 32 + 8 * g + q;
-                c = c < C_in ? c : C_in - 1;
-                if constexpr (PT == 8) {
-                    const uint4 v = *reinterpret_cast<const uint4 *>(xb + (size_t)c * HW);
-                    rows[q][0] = v.x; rows[q][1] = v.y; rows[q][2] = v.z; rows[q][3] = v.w;
-                } else {
-                    const uint2 v = *reinterpret_cast<const uint2 *>(xb + (size_t)c * HW);
-                    rows[q][0] = v.x; rows[q][1] = v.y;
+            for (int t = 0; t < PT; ++t) {
+                const long long pp = (long long)tile * (16 * PT) + 16 * t + n;
+                valid[t] = pp < ngroups;
+                first[t] = valid[t] ? pp : last_group;
+                xb[t] = X + (size_t)first[t] * C_in;
+            }
+        } else {
+            const long long pg_raw = (long long)tile * 16 + n;
+            valid[0] = pg_raw < ngroups;
+            first[0] = (valid[0] ? pg_raw : last_group) * PT;
+            xb[0] = X + (size_t)(first[0] / HW) * C_in * HW + (int)(first[0] % HW);
+        }
+
+        // MFMA operands of one K-step: cols[t] = the 8 channels 32kk + 8g .. +7 of pixel t.
+        // Loads are unconditional (channels past the end re-read the last channels, whose Z
+        // fragment entries are zero), so the next K-step can be prefetched without branches.
+        struct Staged {
+            uint32_t rows[NHWC ? 1 : 8][NHWC ? 1 : NW];  // NCHW: 8 channel rows of PT pixels
+            uint4 cols[NHWC ? PT : 1];                   // NHWC: ready-made operands
+        };
+        auto load_step = [&](Staged &sg, int kk) {
+            if constexpr (NHWC) {
+                int c = kk * 32 + 8 * g;
+                c = c < C_in ? c : C_in - 8;
+#pragma unroll
+                for (int t = 0; t < PT; ++t) sg.cols[t] = *reinterpret_cast<const uint4 *>(xb[t] + c);
+            } else {
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    int c = kk * 32 + 8 * g + q;
+                    c = c < C_in ? c : C_in - 1;
+                    if constexpr (PT == 8) {
+                        const uint4 v = *reinterpret_cast<const uint4 *>(xb[0] + (size_t)c * HW);
+                        sg.rows[q][0] = v.x; sg.rows[q][1] = v.y; sg.rows[q][2] = v.z; sg.rows[q][3] = v.w;
+                    } else {
+                        const uint2 v = *reinterpret_cast<const uint2 *>(xb[0] + (size_t)c * HW);
+                        sg.rows[q][0] = v.x; sg.rows[q][1] = v.y;
+                    }
                 }
             }
         };
-        auto process = [&](const uint32_t (&rows)[8][NW], int kk) {
+        auto process = [&](const Staged &sg, int kk) {
             uint4 cols[PT];
-            transpose_rows8<NW>(rows, cols);
+            if constexpr (NHWC) {
+#pragma unroll
+                for (int t = 0; t < PT; ++t) cols[t] = sg.cols[t];
+            } else {
+                transpose_rows8<NW>(sg.rows, cols);
+            }
 #pragma unroll
             for (int jt = 0; jt < JT; ++jt) {
                 const uint4 ah = zf[(kk * JT + jt) * 64 + lane];
@@ -297,42 +364,40 @@ __global__ __launch_bounds__(kThreads) void probe_16_kernel(const uint16_t *__re
                 }
             }
         };
-        uint32_t r0[8][NW], r1[8][NW];
-        load_rows(r0, 0);
+        Staged r0, r1;
+        load_step(r0, 0);
         int kk = 0;
         for (; kk + 2 < KK; kk += 2) {  // both fetches of a trip are needed ones
-            load_rows(r1, kk + 1);
+            load_step(r1, kk + 1);
             process(r0, kk);
-            load_rows(r0, kk + 2);
+            load_step(r0, kk + 2);
             process(r1, kk + 1);
         }
         if (kk + 1 < KK) {
-            load_rows(r1, kk + 1);
+            load_step(r1, kk + 1);
             process(r0, kk);
             process(r1, kk + 1);
         } else {
             process(r0, kk);
         }
-        if (valid) {
-            // lane (n, g) holds probe columns j0 + g*4*JT .. +4*JT-1 of pixel t: one run of 8*JT bytes
-            uint16_t *out = Xt + (size_t)flat * CS + j0 + g * (4 * JT);
+        // lane (n, g) holds probe columns j0 + g*4*JT .. +4*JT-1 of pixel t: one run of 8*JT bytes
 #pragma unroll
-            for (int t = 0; t < PT; ++t) {
-                uint32_t w[2 * JT];
+        for (int t = 0; t < PT; ++t) {
+            if (!valid[NHWC ? t : 0]) continue;
+            uint32_t w[2 * JT];
 #pragma unroll
-                for (int jt = 0; jt < JT; ++jt) {
-                    w[2 * jt] = (uint32_t)f32_to_st16<DT>(acc[jt][t][0]) | ((uint32_t)f32_to_st16<DT>(acc[jt][t][1]) << 16);
-                    w[2 * jt + 1] = (uint32_t)f32_to_st16<DT>(acc[jt][t][2]) | ((uint32_t)f32_to_st16<DT>(acc[jt][t][3]) << 16);
-                }
-                uint16_t *o = out + (size_t)t * CS;
-                if constexpr (JT % 2 == 0) {
+            for (int jt = 0; jt < JT; ++jt) {
+                w[2 * jt] = (uint32_t)f32_to_st16<DT>(acc[jt][t][0]) | ((uint32_t)f32_to_st16<DT>(acc[jt][t][1]) << 16);
+                w[2 * jt + 1] = (uint32_t)f32_to_st16<DT>(acc[jt][t][2]) | ((uint32_t)f32_to_st16<DT>(acc[jt][t][3]) << 16);
+            }
+            uint16_t *o = Xt + (size_t)(NHWC ? first[NHWC ? t : 0] : first[0] + t) * CS + j0 + g * (4 * JT);
+            if constexpr (JT % 2 == 0) {
 #pragma unroll
-                    for (int k = 0; k < JT / 2; ++k)
-                        *reinterpret_cast<uint4 *>(o + 8 * k) = uint4{w[4 * k], w[4 * k + 1], w[4 * k + 2], w[4 * k + 3]};
-                } else {
+                for (int k = 0; k < JT / 2; ++k)
+                    *reinterpret_cast<uint4 *>(o + 8 * k) = uint4{w[4 * k], w[4 * k + 1], w[4 * k + 2], w[4 * k + 3]};
+            } else {
 #pragma unroll
-                    for (int k = 0; k < JT; ++k) *reinterpret_cast<uint2 *>(o + 4 * k) = uint2{w[2 * k], w[2 * k + 1]};
-                }
+                for (int k = 0; k < JT; ++k) *reinterpret_cast<uint2 *>(o + 4 * k) = uint2{w[2 * k], w[2 * k + 1]};
             }
         }
     }
@@ -346,7 +411,7 @@ __global__ __launch_bounds__(kThreads) void probe_16_kernel(const uint16_t *__re
 template <int DT>
 __global__ __launch_bounds__(kThreads) void probe_generic_kernel(const void *__restrict__ Xv, const float *__restrict__ Z,
                                                                  void *__restrict__ Xtv, int C_in, int HW, int r, int CS,
-                                                                 long long npix)
+                                                                 long long npix, int nhwc)
 {
     const long long flat = (long long)blockIdx.x * kThreads + threadIdx.x;
     if (flat >= npix) return;
@@ -356,7 +421,7 @@ __global__ __launch_bounds__(kThreads) void probe_generic_kernel(const void *__r
 #pragma unroll
     for (int jj = 0; jj < 16; ++jj) acc[jj] = 0.f;
     for (int c = 0; c < C_in; ++c) {
-        const size_t xi = ((size_t)b * C_in + c) * HW + p;
+        const size_t xi = nhwc ? (size_t)flat * C_in + c : ((size_t)b * C_in + c) * HW + p;
         float x;
         if constexpr (DT == XCONV_F32) x = static_cast<const float *>(Xv)[xi];
         else x = st16_to_f32<DT>(static_cast<const uint16_t *>(Xv)[xi]);
@@ -412,6 +477,84 @@ __global__ __launch_bounds__(kThreads) void to_nhwc_kernel(const T *__restrict__
     }
 }
 
+// Channels-last [B, HW, C] -> planes [B, C, pitch] with a zero tail HW..pitch-1 (a channels-last
+// dY in the plane form the correlation kernels read).  32x32 tiles through LDS.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void to_nchw_kernel(const T *__restrict__ src, T *__restrict__ out, int C, int HW, int pitch)
+{
+    __shared__ T tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+    const int p0 = blockIdx.x * 32, c0 = blockIdx.y * 32, b = blockIdx.z;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int p = p0 + ty + 8 * k, c = c0 + tx;
+        tile[ty + 8 * k][tx] = (c < C && p < HW) ? src[((size_t)b * HW + p) * C + c] : T(0);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int c = c0 + ty + 8 * k, p = p0 + tx;
+        if (c < C && p < pitch) out[((size_t)b * C + c) * pitch + p] = tile[tx][ty + 8 * k];
+    }
+}
+
+// The same for C a multiple of the 16-byte vector (VE = 8 or 4 elements), without LDS: a thread
+// loads VE pixels x VE channels (one vector per pixel), transposes the block in registers and
+// stores one vector of VE pixels per channel.  Lanes run over 8 channel vectors (128 contiguous
+// bytes of a pixel on the way in) and 8 pixel blocks (128 contiguous bytes of a plane on the way
+// out).  Planes whose pitch is not a multiple of VE are stored element by element.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void to_nchw_vec_kernel(const T *__restrict__ src, T *__restrict__ out, int C, int HW,
+                                                               int pitch)
+{
+    constexpr int VE = 16 / sizeof(T);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int cx = lane & 7, pb = lane >> 3;
+    const int c = blockIdx.y * (8 * VE) + cx * VE;
+    const int p0 = (blockIdx.x * 4 + wave) * (8 * VE) + pb * VE;
+    const int b = blockIdx.z;
+    if (c >= C || p0 >= pitch) return;
+    uint32_t rows[VE][4];
+#pragma unroll
+    for (int q = 0; q < VE; ++q) {
+        uint4 v = uint4{0u, 0u, 0u, 0u};
+        if (p0 + q < HW) v = *reinterpret_cast<const uint4 *>(src + ((size_t)b * HW + p0 + q) * C + c);
+        rows[q][0] = v.x; rows[q][1] = v.y; rows[q][2] = v.z; rows[q][3] = v.w;
+    }
+    uint4 cols[VE];
+    if constexpr (VE == 8) {
+        transpose_rows8<4>(rows, cols);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) cols[e] = uint4{rows[0][e], rows[1][e], rows[2][e], rows[3][e]};
+    }
+    const bool vec = (pitch % VE) == 0;  // then p0 + VE <= pitch and every plane starts on a vector
+#pragma unroll
+    for (int e = 0; e < VE; ++e) {
+        T *dst = out + ((size_t)b * C + c + e) * pitch + p0;
+        if (vec) {
+            *reinterpret_cast<uint4 *>(dst) = cols[e];
+        } else {
+            const T *vals = reinterpret_cast<const T *>(&cols[e]);
+#pragma unroll
+            for (int q = 0; q < VE; ++q)
+                if (p0 + q < pitch) dst[q] = vals[q];
+        }
+    }
+}
+
+// Channels-last [npix, C] -> [npix, CS] with zero columns C..CS-1.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void pad_channels_kernel(const T *__restrict__ src, T *__restrict__ out, int C, int CS,
+                                                                long long total)
+{
+    const long long i = (long long)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= total) return;
+    const long long pix = i / CS;
+    const int c = (int)(i - pix * CS);
+    out[i] = c < C ? src[pix * C + c] : T(0);
+}
+
 // ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
@@ -435,53 +578,59 @@ static int probe_grid(int ntiles)
     return want < 2048 ? want : 2048;
 }
 
-template <int JT>
+template <int JT, bool NHWC>
 static hipError_t launch_probe_f32_jt(const float *X, const float *Z, const float *zpack, float *Xt, int C_in, int HW, int r, int CS,
                                       int j0, long long npix, hipStream_t st)
 {
-    const long long ngroups = npix / 4;
-    const int ntiles = (int)((ngroups + 15) / 16);
+    // a lane owns 4 consecutive pixels of a plane (NCHW) or one pixel of each of 4 sub-tiles (NHWC)
+    const long long ngroups = NHWC ? npix : npix / 4;
+    const int ntiles = (int)(NHWC ? (npix + 63) / 64 : (ngroups + 15) / 16);
     const size_t lds = (size_t)ceil_div(C_in, 16) * 4 * JT * 64 * sizeof(float);
-    hipError_t e = set_lds(probe_f32_kernel<JT>, lds);
+    hipError_t e = set_lds(probe_f32_kernel<JT, NHWC>, lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(probe_f32_kernel<JT>, dim3(probe_grid(ntiles)), dim3(kThreads), lds, st, X, Z, zpack, Xt, C_in, HW, r, CS,
-                       j0, ngroups, ntiles);
+    hipLaunchKernelGGL((probe_f32_kernel<JT, NHWC>), dim3(probe_grid(ntiles)), dim3(kThreads), lds, st, X, Z, zpack, Xt, C_in, HW, r,
+                       CS, j0, ngroups, ntiles);
     return hipGetLastError();
 }
 
-template <int DT, int JT, int PT, bool SPLIT>
+template <int DT, int JT, int PT, bool SPLIT, bool NHWC>
 static hipError_t launch_probe_16_cfg(const uint16_t *X, const float *Z, const uint4 *zpack, uint16_t *Xt, int C_in, int HW, int r,
                                       int CS, int j0, long long npix, hipStream_t st)
 {
-    const long long ngroups = npix / PT;
-    const int ntiles = (int)((ngroups + 15) / 16);
+    const long long ngroups = NHWC ? npix : npix / PT;
+    const int ntiles = (int)(NHWC ? (npix + 16 * PT - 1) / (16 * PT) : (ngroups + 15) / 16);
     const size_t lds = (size_t)(SPLIT ? 2 : 1) * ceil_div(C_in, 32) * JT * 64 * sizeof(uint4);
-    hipError_t e = set_lds(probe_16_kernel<DT, JT, PT, SPLIT>, lds);
+    hipError_t e = set_lds(probe_16_kernel<DT, JT, PT, SPLIT, NHWC>, lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((probe_16_kernel<DT, JT, PT, SPLIT>), dim3(probe_grid(ntiles)), dim3(kThreads), lds, st, X, Z, zpack, Xt,
-                       C_in, HW, r, CS, j0, ngroups, ntiles);
+    hipLaunchKernelGGL((probe_16_kernel<DT, JT, PT, SPLIT, NHWC>), dim3(probe_grid(ntiles)), dim3(kThreads), lds, st, X, Z, zpack,
+                       Xt, C_in, HW, r, CS, j0, ngroups, ntiles);
     return hipGetLastError();
 }
 
 template <int DT, int JT>
 static hipError_t launch_probe_16_jt(const uint16_t *X, const float *Z, const uint4 *zpack, uint16_t *Xt, int C_in, int HW, int r,
-                                     int CS, int j0, long long npix, bool split, hipStream_t st)
+                                     int CS, int j0, long long npix, bool split, bool nhwc, hipStream_t st)
 {
+    if (nhwc) {
+        if (split) return launch_probe_16_cfg<DT, JT, 4, true, true>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, st);
+        return launch_probe_16_cfg<DT, JT, 4, false, true>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, st);
+    }
     // 8 pixels per lane when the accumulators stay small, 4 for wide probe blocks
     const bool pt8 = (JT <= 2) && (HW % 8 == 0);
     if (pt8) {
-        if (split) return launch_probe_16_cfg<DT, JT, 8, true>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, st);
-        return launch_probe_16_cfg<DT, JT, 8, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, st);
+        if (split) return launch_probe_16_cfg<DT, JT, 8, true, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, st);
+        return launch_probe_16_cfg<DT, JT, 8, false, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, st);
     }
-    if (split) return launch_probe_16_cfg<DT, JT, 4, true>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, st);
-    return launch_probe_16_cfg<DT, JT, 4, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, st);
+    if (split) return launch_probe_16_cfg<DT, JT, 4, true, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, st);
+    return launch_probe_16_cfg<DT, JT, 4, false, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, st);
 }
 
-bool probe_fast_path_ok(int dtype, int C_in, int HW)
+bool probe_fast_path_ok(int dtype, int C_in, int HW, bool nhwc)
 {
-    // aligned vector loads of 4 pixels (16 bytes fp32, 8 bytes 16-bit) per channel row;
-    // LDS for the Z fragments (worst case JT = 4, split) must fit
-    if (HW % 4 != 0) return false;
+    // aligned vector loads: 4 pixels (16 bytes fp32, 8 bytes 16-bit) per channel row, or (NHWC)
+    // 16 bytes of consecutive channels per pixel; LDS for the Z fragments (worst case JT = 4,
+    // split) must fit
+    if (nhwc ? (C_in % (dtype == XCONV_F32 ? 4 : 8) != 0) : (HW % 4 != 0)) return false;
     const size_t lds = dtype == XCONV_F32 ? (size_t)ceil_div(C_in, 16) * 4 * 4 * 64 * 4 : (size_t)2 * ceil_div(C_in, 32) * 4 * 64 * 16;
     return lds <= 128 * 1024;
 }
@@ -495,13 +644,13 @@ size_t zpack_bytes(int dtype, int C_in, int r, bool z_exact16)
 }
 
 hipError_t launch_pack_z(int dtype, const float *Z, void *out, int C_in, int r, bool z_exact16, int dist, uint64_t seed,
-                         hipStream_t st)
+                         bool nhwc, hipStream_t st)
 {
     const int ntj = ceil_div(r, 16);
     if (dtype == XCONV_F32) {
         const int KQ4 = ceil_div(C_in, 16) * 4;
         hipLaunchKernelGGL(pack_z_f32_kernel, dim3(ceil_div(KQ4 * ntj * 64, kThreads)), dim3(kThreads), 0, st, Z,
-                           static_cast<float *>(out), C_in, r, ntj, KQ4, dist, seed);
+                           static_cast<float *>(out), C_in, r, ntj, KQ4, dist, seed, nhwc ? 1 : 0);
     } else {
         const int KK = ceil_div(C_in, 32);
         const dim3 grid(ceil_div(KK * ntj * 64, kThreads));
@@ -518,7 +667,7 @@ hipError_t launch_pack_z(int dtype, const float *Z, void *out, int C_in, int r, 
 // zpack: Z in fragment order (launch_pack_z) or nullptr, in which case every workgroup gathers
 // its fragments from Z itself.
 hipError_t launch_probe(int dtype, const void *X, const float *Z, const void *zpack, void *Xt, int B, int C_in, int HW, int r,
-                        int CS, bool z_exact16, hipStream_t st)
+                        int CS, bool z_exact16, bool nhwc, hipStream_t st)
 {
     const long long npix = (long long)B * HW;
     const int ntj = CS / 16;
@@ -531,12 +680,15 @@ hipError_t launch_probe(int dtype, const void *X, const float *Z, const void *zp
             const float *x = static_cast<const float *>(X);
             float *o = static_cast<float *>(Xt);
             const float *zp = zpack ? static_cast<const float *>(zpack) + bi * ceil_div(C_in, 16) * 4 * 4 * 64 : nullptr;
-            switch (jt) {
-            case 1: e = launch_probe_f32_jt<1>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, st); break;
-            case 2: e = launch_probe_f32_jt<2>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, st); break;
-            case 3: e = launch_probe_f32_jt<3>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, st); break;
-            default: e = launch_probe_f32_jt<4>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, st); break;
-            }
+#define XC_P32(NH)                                                                                  \
+    switch (jt) {                                                                                   \
+    case 1: e = launch_probe_f32_jt<1, NH>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, st); break;      \
+    case 2: e = launch_probe_f32_jt<2, NH>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, st); break;      \
+    case 3: e = launch_probe_f32_jt<3, NH>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, st); break;      \
+    default: e = launch_probe_f32_jt<4, NH>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, st); break;     \
+    }
+            if (nhwc) { XC_P32(true) } else { XC_P32(false) }
+#undef XC_P32
         } else {
             const uint16_t *x = static_cast<const uint16_t *>(X);
             uint16_t *o = static_cast<uint16_t *>(Xt);
@@ -544,10 +696,10 @@ hipError_t launch_probe(int dtype, const void *X, const float *Z, const void *zp
             const uint4 *zp = zpack ? static_cast<const uint4 *>(zpack) + bi * ceil_div(C_in, 32) * 4 * 64 * (split ? 2 : 1) : nullptr;
 #define XC_P16(DT)                                                                                            \
     switch (jt) {                                                                                             \
-    case 1: e = launch_probe_16_jt<DT, 1>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, st); break;          \
-    case 2: e = launch_probe_16_jt<DT, 2>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, st); break;          \
-    case 3: e = launch_probe_16_jt<DT, 3>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, st); break;          \
-    default: e = launch_probe_16_jt<DT, 4>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, st); break;         \
+    case 1: e = launch_probe_16_jt<DT, 1>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, nhwc, st); break;          \
+    case 2: e = launch_probe_16_jt<DT, 2>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, nhwc, st); break;          \
+    case 3: e = launch_probe_16_jt<DT, 3>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, nhwc, st); break;          \
+    default: e = launch_probe_16_jt<DT, 4>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, nhwc, st); break;         \
     }
             if (dtype == XCONV_BF16) { XC_P16(XCONV_BF16) } else { XC_P16(XCONV_F16) }
 #undef XC_P16
@@ -557,16 +709,16 @@ hipError_t launch_probe(int dtype, const void *X, const float *Z, const void *zp
 }
 
 hipError_t launch_probe_generic(int dtype, const void *X, const float *Z, void *Xt, int B, int C_in, int HW, int r, int CS,
-                                hipStream_t st)
+                                bool nhwc, hipStream_t st)
 {
     const long long npix = (long long)B * HW;
     dim3 grid((unsigned)((npix + kThreads - 1) / kThreads), CS / 16);
     if (dtype == XCONV_F32)
-        hipLaunchKernelGGL(probe_generic_kernel<XCONV_F32>, grid, dim3(kThreads), 0, st, X, Z, Xt, C_in, HW, r, CS, npix);
+        hipLaunchKernelGGL(probe_generic_kernel<XCONV_F32>, grid, dim3(kThreads), 0, st, X, Z, Xt, C_in, HW, r, CS, npix, nhwc ? 1 : 0);
     else if (dtype == XCONV_BF16)
-        hipLaunchKernelGGL(probe_generic_kernel<XCONV_BF16>, grid, dim3(kThreads), 0, st, X, Z, Xt, C_in, HW, r, CS, npix);
+        hipLaunchKernelGGL(probe_generic_kernel<XCONV_BF16>, grid, dim3(kThreads), 0, st, X, Z, Xt, C_in, HW, r, CS, npix, nhwc ? 1 : 0);
     else
-        hipLaunchKernelGGL(probe_generic_kernel<XCONV_F16>, grid, dim3(kThreads), 0, st, X, Z, Xt, C_in, HW, r, CS, npix);
+        hipLaunchKernelGGL(probe_generic_kernel<XCONV_F16>, grid, dim3(kThreads), 0, st, X, Z, Xt, C_in, HW, r, CS, npix, nhwc ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -592,6 +744,42 @@ hipError_t launch_to_nhwc(int dtype, const void *X, void *out, int B, int C, int
     else
         hipLaunchKernelGGL(to_nhwc_kernel<uint16_t>, grid, dim3(kThreads), 0, st, static_cast<const uint16_t *>(X),
                            static_cast<uint16_t *>(out), C, HW, CS);
+    return hipGetLastError();
+}
+
+hipError_t launch_to_nchw(int dtype, const void *src, void *out, int B, int C, int HW, int pitch, hipStream_t st)
+{
+    const int VE = dtype == XCONV_F32 ? 4 : 8;
+    if (C % VE == 0 && (reinterpret_cast<uintptr_t>(src) & 15u) == 0 && (reinterpret_cast<uintptr_t>(out) & 15u) == 0) {
+        dim3 vgrid(ceil_div(pitch, 32 * VE), ceil_div(C, 8 * VE), B);
+        if (dtype == XCONV_F32)
+            hipLaunchKernelGGL(to_nchw_vec_kernel<float>, vgrid, dim3(kThreads), 0, st, static_cast<const float *>(src),
+                               static_cast<float *>(out), C, HW, pitch);
+        else
+            hipLaunchKernelGGL(to_nchw_vec_kernel<uint16_t>, vgrid, dim3(kThreads), 0, st, static_cast<const uint16_t *>(src),
+                               static_cast<uint16_t *>(out), C, HW, pitch);
+        return hipGetLastError();
+    }
+    dim3 grid(ceil_div(pitch, 32), ceil_div(C, 32), B);
+    if (dtype == XCONV_F32)
+        hipLaunchKernelGGL(to_nchw_kernel<float>, grid, dim3(kThreads), 0, st, static_cast<const float *>(src),
+                           static_cast<float *>(out), C, HW, pitch);
+    else
+        hipLaunchKernelGGL(to_nchw_kernel<uint16_t>, grid, dim3(kThreads), 0, st, static_cast<const uint16_t *>(src),
+                           static_cast<uint16_t *>(out), C, HW, pitch);
+    return hipGetLastError();
+}
+
+hipError_t launch_pad_channels(int dtype, const void *src, void *out, long long npix, int C, int CS, hipStream_t st)
+{
+    const long long total = npix * CS;
+    dim3 grid((unsigned)((total + kThreads - 1) / kThreads));
+    if (dtype == XCONV_F32)
+        hipLaunchKernelGGL(pad_channels_kernel<float>, grid, dim3(kThreads), 0, st, static_cast<const float *>(src),
+                           static_cast<float *>(out), C, CS, total);
+    else
+        hipLaunchKernelGGL(pad_channels_kernel<uint16_t>, grid, dim3(kThreads), 0, st, static_cast<const uint16_t *>(src),
+                           static_cast<uint16_t *>(out), C, CS, total);
     return hipGetLastError();
 }
 

@@ -127,7 +127,8 @@ int dy_pitch(const xconv_desc *d)
 size_t dy_repack_bytes(const xconv_desc *d)
 {
     const int n = out_extent(d->H, d->kH, d->stride_h, d->pad_h) * out_extent(d->W, d->kW, d->stride_w, d->pad_w);
-    if (dy_pitch(d) == n) return 0;
+    // a channels-last dY is always brought into plane form first
+    if (dy_pitch(d) == n && d->layout == XCONV_NCHW) return 0;
     return align_up((size_t)d->B * d->C_out * dy_pitch(d) * elem_bytes(d->dtype), 256);
 }
 
@@ -145,7 +146,6 @@ xconv_status xconv_check_desc(const xconv_desc *d)
     if (d->layout < XCONV_NCHW || d->layout > XCONV_NHWC) return XCONV_EINVAL;
     if (d->probe < XCONV_RADEMACHER || d->probe > XCONV_USER_Z) return XCONV_EINVAL;
     if (out_extent(d->H, d->kH, d->stride_h, d->pad_h) < 1 || out_extent(d->W, d->kW, d->stride_w, d->pad_w) < 1) return XCONV_EINVAL;
-    if (d->layout != XCONV_NCHW) return XCONV_EUNSUPPORTED;
     if (d->r > 1024 || d->C_in > 65536 || d->C_out > 65536 || (long long)d->kH * d->kW > 49) return XCONV_EUNSUPPORTED;
     if ((long long)d->H * d->W > 0x7fffffffLL / 8 || (long long)(d->H + 2 * d->pad_h) * (d->W + 2 * d->pad_w) > 0x7fffffffLL / 8)
         return XCONV_EUNSUPPORTED;
@@ -208,7 +208,8 @@ xconv_status xconv_probe_fwd(const xconv_desc *d, const void *X_dev, void *Xt_de
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int CS = round_up(d->r, 16), HW = d->H * d->W;
     const bool z_exact16 = d->probe == XCONV_RADEMACHER;
-    const bool fast = probe_fast_path_ok(d->dtype, d->C_in, HW) && aligned16(X_dev);
+    const bool nhwc = d->layout == XCONV_NHWC;
+    const bool fast = probe_fast_path_ok(d->dtype, d->C_in, HW, nhwc) && aligned16(X_dev);
     const size_t zb = z_bytes(d), fb = zfrag_bytes(d);
     if (!Z_dev && d->probe == XCONV_USER_Z) return XCONV_EINVAL;
     if (ws_dev) {
@@ -221,8 +222,8 @@ xconv_status xconv_probe_fwd(const xconv_desc *d, const void *X_dev, void *Xt_de
         // With scratch, Z goes to the kernels in fragment order (drawn from the seed when no Z
         // is given); without it, every workgroup gathers its fragments from Z_dev.
         void *zpack = ws_dev ? static_cast<char *>(ws_dev) + zb : nullptr;
-        if (zpack) XC_LAUNCH(K_PACK_Z, st, launch_pack_z(d->dtype, Z_dev, zpack, d->C_in, d->r, z_exact16, d->probe, d->seed, st));
-        XC_LAUNCH(K_PROBE, st, launch_probe(d->dtype, X_dev, Z_dev, zpack, Xt_dev, d->B, d->C_in, HW, d->r, CS, z_exact16, st));
+        if (zpack) XC_LAUNCH(K_PACK_Z, st, launch_pack_z(d->dtype, Z_dev, zpack, d->C_in, d->r, z_exact16, d->probe, d->seed, nhwc, st));
+        XC_LAUNCH(K_PROBE, st, launch_probe(d->dtype, X_dev, Z_dev, zpack, Xt_dev, d->B, d->C_in, HW, d->r, CS, z_exact16, nhwc, st));
     } else {
         const float *Z = Z_dev;
         if (!Z) {
@@ -230,7 +231,7 @@ xconv_status xconv_probe_fwd(const xconv_desc *d, const void *X_dev, void *Xt_de
             XC_LAUNCH(K_GEN_Z, st, launch_gen_z(zw, d->C_in * d->r, d->probe, d->seed, st));
             Z = zw;
         }
-        XC_LAUNCH(K_PROBE_GENERIC, st, launch_probe_generic(d->dtype, X_dev, Z, Xt_dev, d->B, d->C_in, HW, d->r, CS, st));
+        XC_LAUNCH(K_PROBE_GENERIC, st, launch_probe_generic(d->dtype, X_dev, Z, Xt_dev, d->B, d->C_in, HW, d->r, CS, nhwc, st));
     }
     return XCONV_OK;
 }
@@ -261,7 +262,12 @@ xconv_status xconv_dw_estimate(const xconv_desc *d, const void *dY_dev, const vo
         Z = zw;
     }
     P.dY = dY_dev;
-    if (rb && !E.ws) {
+    if (d->layout == XCONV_NHWC) {
+        // channels-last dY -> the plane form the kernels read (pitch of the kernel that runs)
+        void *packed = static_cast<char *>(ws_dev) + zb + pb;
+        XC_LAUNCH(K_REPACK, st, launch_to_nchw(d->dtype, dY_dev, packed, d->B, d->C_out, P.Ho * P.Wo, E.ws ? P.Ho * P.Wo : dy_pitch(d), st));
+        P.dY = packed;
+    } else if (rb && !E.ws) {
         void *packed = static_cast<char *>(ws_dev) + zb + pb;
         XC_LAUNCH(K_REPACK, st, launch_repack_planes(d->dtype, dY_dev, packed, (long long)d->B * d->C_out, P.Ho * P.Wo, dy_pitch(d), st));
         P.dY = packed;
@@ -269,7 +275,7 @@ xconv_status xconv_dw_estimate(const xconv_desc *d, const void *dY_dev, const vo
     P.A = Xt_dev;
     P.part = reinterpret_cast<float *>(static_cast<char *>(ws_dev) + zb);
     if (E.ws) {
-        E.Wp.dY = dY_dev;
+        E.Wp.dY = P.dY;
         E.Wp.A = Xt_dev;
         E.Wp.part = P.part;
         XC_LAUNCH(K_CORR, st, launch_corr_ws(d->dtype, E.Wp, st));
@@ -299,18 +305,30 @@ xconv_status xconv_dw_exact(const xconv_desc *d, const void *dY_dev, const void 
     CorrParams &P = E.P;
     const size_t xb = align_up((size_t)d->B * HW * CSx * eb, 256), pb = align_up(corr_partial_bytes(P), 256), rb = dy_repack_bytes(d);
     if (ws_bytes < xb + pb + rb) return XCONV_EWORKSPACE;
-    XC_LAUNCH(K_TO_NHWC, st, launch_to_nhwc(d->dtype, X_dev, ws_dev, d->B, d->C_in, HW, CSx, st));
+    // the correlation kernels read X channels-last with a channel stride that is a multiple of 16
+    const void *A = ws_dev;
+    if (d->layout == XCONV_NCHW) {
+        XC_LAUNCH(K_TO_NHWC, st, launch_to_nhwc(d->dtype, X_dev, ws_dev, d->B, d->C_in, HW, CSx, st));
+    } else if (d->C_in == CSx && aligned16(X_dev)) {
+        A = X_dev;  // already in that form
+    } else {
+        XC_LAUNCH(K_TO_NHWC, st, launch_pad_channels(d->dtype, X_dev, ws_dev, (long long)d->B * HW, d->C_in, CSx, st));
+    }
     P.dY = dY_dev;
-    if (rb && !E.ws) {
+    if (d->layout == XCONV_NHWC) {
+        void *packed = static_cast<char *>(ws_dev) + xb + pb;
+        XC_LAUNCH(K_REPACK, st, launch_to_nchw(d->dtype, dY_dev, packed, d->B, d->C_out, P.Ho * P.Wo, E.ws ? P.Ho * P.Wo : dy_pitch(d), st));
+        P.dY = packed;
+    } else if (rb && !E.ws) {
         void *packed = static_cast<char *>(ws_dev) + xb + pb;
         XC_LAUNCH(K_REPACK, st, launch_repack_planes(d->dtype, dY_dev, packed, (long long)d->B * d->C_out, P.Ho * P.Wo, dy_pitch(d), st));
         P.dY = packed;
     }
-    P.A = ws_dev;
+    P.A = A;
     P.part = reinterpret_cast<float *>(static_cast<char *>(ws_dev) + xb);
     if (E.ws) {
-        E.Wp.dY = dY_dev;
-        E.Wp.A = ws_dev;
+        E.Wp.dY = P.dY;
+        E.Wp.A = A;
         E.Wp.part = P.part;
         XC_LAUNCH(K_CORR, st, launch_corr_ws(d->dtype, E.Wp, st));
     } else {

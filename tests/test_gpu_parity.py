@@ -252,7 +252,30 @@ def test_producer_consumer_kernel_is_deterministic():
     assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
 
 
-def run_edge(e):
+# Channels-last X and dY (layout NHWC): the probe reads X directly (fast path when C_in is a
+# multiple of the 16-byte vector, any-shape kernel otherwise, tiles with a ragged tail of
+# pixels), dY is brought into plane form first, the exact path takes X as it is when C_in is a
+# multiple of 16 and pads the channels otherwise.  Same oracle, fed the NCHW arrays.
+NHWC_EDGE = [
+    ("nhwc-f32-c16", 3, 16, 24, 13, 11, 3, 1, 1, 8, "rademacher", "f32"),
+    ("nhwc-f32-c40-gauss", 5, 40, 64, 10, 12, 3, 1, 1, 20, "gaussian", "f32"),
+    ("nhwc-f32-c6-generic", 2, 6, 10, 9, 9, 3, 1, 1, 4, "rademacher", "f32"),
+    ("nhwc-f32-s2", 4, 32, 32, 17, 16, 3, 2, 1, 16, "gaussian", "f32"),
+    ("nhwc-bf16-c64-r64", 9, 64, 64, 14, 14, 3, 1, 1, 64, "rademacher", "bf16"),
+    ("nhwc-f16-c72-r32", 8, 72, 96, 12, 12, 3, 1, 1, 32, "rademacher", "f16"),
+    ("nhwc-f16-gauss-r24", 6, 48, 32, 11, 10, 3, 1, 1, 24, "gaussian", "f16"),
+    ("nhwc-bf16-c12-generic", 3, 12, 16, 8, 8, 3, 1, 1, 8, "rademacher", "bf16"),
+    ("nhwc-f16-k5-s2", 8, 32, 64, 15, 15, 5, 2, 2, 32, "rademacher", "f16"),
+    ("nhwc-f16-1x1", 8, 32, 48, 9, 9, 1, 1, 0, 16, "rademacher", "f16"),
+]
+
+
+@pytest.mark.parametrize("e", NHWC_EDGE, ids=[e[0] for e in NHWC_EDGE])
+def test_channels_last_inputs(e):
+    run_edge(e, nhwc=True)
+
+
+def run_edge(e, nhwc=False):
     name, B, C_in, C_out, H, W, k, stride, pad, r, probe, dtype = e
     kH, kW = (k, k) if isinstance(k, int) else k
     sh, sw = (stride, stride) if isinstance(stride, int) else stride
@@ -262,8 +285,13 @@ def run_edge(e):
     X = synth.draw((B, C_in, H, W), 11, "relu_normal", 1.0, dtype)
     dY = synth.draw((B, C_out, Ho, Wo), 12, "normal", 1e-2, dtype)
     Z = xo.probe_matrix(OPROBE[probe], 13, C_in, r)
-    d = xb.make_desc(B, C_in, C_out, H, W, (kH, kW), (sh, sw), (ph, pw), r, dtype, probe, 13)
-    Xd, dYd = xb.to_device(X, dtype, DEV), xb.to_device(dY, dtype, DEV)
+    d = xb.make_desc(B, C_in, C_out, H, W, (kH, kW), (sh, sw), (ph, pw), r, dtype, probe, 13,
+                     layout=xb.XCONV_NHWC if nhwc else xb.XCONV_NCHW)
+    if nhwc:
+        Xd = xb.to_device(np.ascontiguousarray(X.transpose(0, 2, 3, 1)), dtype, DEV)
+        dYd = xb.to_device(np.ascontiguousarray(dY.transpose(0, 2, 3, 1)), dtype, DEV)
+    else:
+        Xd, dYd = xb.to_device(X, dtype, DEV), xb.to_device(dY, dtype, DEV)
     Zd = torch.from_numpy(Z).to(DEV)
     Xt = xb.alloc_xt(d, DEV)
     Xt.fill_(0x7f)

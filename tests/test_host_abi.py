@@ -46,7 +46,10 @@ def test_check_desc_statuses():
     d = _good()
     d.kH = d.kW = 40            # kernel larger than the padded image: empty output
     assert xb.xconv_check_desc(d) == xb.XCONV_EINVAL
-    for field, val in (("layout", xb.XCONV_NHWC), ("r", 1025), ("C_in", 70000), ("C_out", 70000)):
+    d = _good()
+    d.layout = xb.XCONV_NHWC
+    assert xb.xconv_check_desc(d) == xb.XCONV_OK
+    for field, val in (("r", 1025), ("C_in", 70000), ("C_out", 70000)):
         d = _good()
         setattr(d, field, val)
         assert xb.xconv_check_desc(d) == xb.XCONV_EUNSUPPORTED, field
@@ -116,9 +119,11 @@ def test_entry_points_reject_bad_arguments_before_any_launch():
     du = _good()
     du.probe = xb.XCONV_USER_Z
     assert L.xconv_dw_estimate(ctypes.byref(du), one, one, None, one, one, 1 << 30, None) == xb.XCONV_EINVAL
+    # a channels-last dY is always copied into plane form: its workspace is larger by that copy
     dn = _good()
     dn.layout = xb.XCONV_NHWC
-    assert L.xconv_probe_fwd(ctypes.byref(dn), one, one, one, None, 0, None) == xb.XCONV_EUNSUPPORTED
+    for op in (xb.XCONV_OP_ESTIMATE, xb.XCONV_OP_EXACT):
+        assert xb.xconv_workspace_bytes(dn, op) > xb.xconv_workspace_bytes(_good(), op)
 
 
 def test_synthetic_inputs_are_storage_representable_and_seeded():
