@@ -12,6 +12,8 @@
  *   exact gradient      dw_i^{n,m} = tr( X^n (dY^m)^T T_{-k(i)} )        Sec. 3, Eq. (2), Eq. (5)
  *   trace estimator     tr(A) ~ (1/r) sum_j z_j^T A z_j, E[z z^T] = I    Sec. 3, Eq. (3)
  *   multi-channel est.  G^{m,n} = (1/r) sum_j z_{n,j}^T (A z_j)_m        Sec. 3, Eq. (6)
+ *   block-sparse probes z_{n,j} = 0 with probability 1 - p, scaled by      Sec. 3, Eq. (7), Eq. (8)
+ *                       1/nnz(Z_n) instead of 1/r
  *   Algorithm 1         fwd: Xbar = Z[s]^T X, keep (Xbar, s)
  *                       bwd: L = Xbar dY^T,  dw_i = (1/r) tr(L T_{-k(i)} Z[s])
  *
@@ -95,6 +97,29 @@ int xo_probe_matrix(int dist, uint64_t seed, int C_in, int r, float *Z)
             }
         }
     }
+    return 0;
+}
+
+/* Block-sparse probing vectors (Sec. 3, Eq. (7), restricted to the channel
+ * axis like the dense probe): entry (n, j) keeps its dense value with
+ * probability p and is zero otherwise, independently for every (n, j).  The
+ * paper allows a probability p_n per block; one p for all blocks is taken
+ * here, p = keep_q15 / 32768 with keep_q15 in 1..32767 (0 means dense).  The
+ * keep decision of entry idx = n*r+j is (u < keep_q15) with u the top 15 bits
+ * of word idx of the stream of (seed xor XO_MASK_STREAM), a stream of its own
+ * so that the kept entries equal those of the dense matrix of the same seed. */
+#define XO_MASK_STREAM 0x5851F42D4C957F2Dull
+
+int xo_probe_matrix_sparse(int dist, uint64_t seed, int keep_q15, int C_in, int r, float *Z)
+{
+    int rc = xo_probe_matrix(dist, seed, C_in, r, Z);
+    if (rc != 0 || keep_q15 == 0) return rc;
+    for (int c = 0; c < C_in; ++c)
+        for (int j = 0; j < r; ++j) {
+            uint64_t idx = (uint64_t)c * (uint64_t)r + (uint64_t)j;
+            uint64_t u = xo_stream_word(seed ^ XO_MASK_STREAM, idx) >> 49;
+            if (u >= (uint64_t)keep_q15) Z[idx] = 0.0f;
+        }
     return 0;
 }
 
@@ -224,6 +249,28 @@ void xo_expand(const double *G, const float *Z, double *dW,
                 s += (double)Z[(size_t)n * r + j] * G[((size_t)m * r + j) * K2 + o];
             dW[((size_t)m * C_in + n) * K2 + o] = s / (double)r;
         }
+}
+
+/* The same with the scaling of Eq. (8) for block-sparse probing vectors:     */
+/*   dW[m,n,ky,kx] = (1/nnz(Z_n)) sum_j Z[n,j] * G[m,j,ky,kx],               */
+/* nnz(Z_n) = number of non-zero entries of row n of Z.  A row without any   */
+/* (the estimator has nothing to go on for that input channel) gives zeros.  */
+void xo_expand_nnz(const double *G, const float *Z, double *dW,
+                   int C_out, int C_in, int r, int kH, int kW)
+{
+    int K2 = kH * kW;
+    for (int n = 0; n < C_in; ++n) {
+        int nnz = 0;
+        for (int j = 0; j < r; ++j)
+            if (Z[(size_t)n * r + j] != 0.0f) ++nnz;
+        for (int m = 0; m < C_out; ++m)
+            for (int o = 0; o < K2; ++o) {
+                double s = 0.0;
+                for (int j = 0; j < r; ++j)
+                    s += (double)Z[(size_t)n * r + j] * G[((size_t)m * r + j) * K2 + o];
+                dW[((size_t)m * C_in + n) * K2 + o] = nnz > 0 ? s / (double)nnz : 0.0;
+            }
+    }
 }
 
 /* Backward pass of Algorithm 1 from the stored Xt: steps 3 and 4. */

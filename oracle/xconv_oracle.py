@@ -48,6 +48,10 @@ def lib():
         L.xo_correlate.argtypes = [_c_f32p, _c_f32p, _c_f64p] + [ctypes.c_int] * 11
         L.xo_dw_exact.restype = None
         L.xo_dw_exact.argtypes = [_c_f32p, _c_f32p, _c_f64p] + [ctypes.c_int] * 11
+        L.xo_probe_matrix_sparse.restype = ctypes.c_int
+        L.xo_probe_matrix_sparse.argtypes = [ctypes.c_int, ctypes.c_uint64, ctypes.c_int, ctypes.c_int, ctypes.c_int, _c_f32p]
+        L.xo_expand_nnz.restype = None
+        L.xo_expand_nnz.argtypes = [_c_f64p, _c_f32p, _c_f64p] + [ctypes.c_int] * 5
         L.xo_expand.restype = None
         L.xo_expand.argtypes = [_c_f64p, _c_f32p, _c_f64p] + [ctypes.c_int] * 5
         L.xo_dw_from_xt.restype = None
@@ -88,9 +92,10 @@ def stream_word(seed, ctr):
     return int(lib().xo_stream_word(ctypes.c_uint64(seed), ctypes.c_uint64(ctr)))
 
 
-def probe_matrix(dist, seed, C_in, r):
+def probe_matrix(dist, seed, C_in, r, keep_q15=0):
+    """Z[C_in, r]; keep_q15 > 0: block-sparse probes (Eq. (7)), entries kept with probability keep_q15 / 32768."""
     Z = np.empty((C_in, r), dtype=np.float32)
-    rc = lib().xo_probe_matrix(dist, ctypes.c_uint64(seed), C_in, r, Z.ctypes.data_as(_c_f32p))
+    rc = lib().xo_probe_matrix_sparse(dist, ctypes.c_uint64(seed), keep_q15, C_in, r, Z.ctypes.data_as(_c_f32p))
     if rc != 0:
         raise ValueError("unknown probe distribution %r" % (dist,))
     return Z
@@ -135,18 +140,21 @@ def dw_exact(dY, X, kH, kW, stride=(1, 1), pad=(0, 0)):
     return dW
 
 
-def expand(G, Z):
+def expand(G, Z, nnz_norm=False):
+    """dW = Z G / r (Eq. (6) step (iii)), or with nnz_norm rows scaled by 1 / nnz(Z_n) (Eq. (8))."""
     G, Gp = _f64(G)
     Z, Zp = _f32(Z)
     C_out, r, kH, kW = G.shape
     C_in = Z.shape[0]
     assert Z.shape[1] == r
     dW = np.empty((C_out, C_in, kH, kW), dtype=np.float64)
-    lib().xo_expand(Gp, Zp, dW.ctypes.data_as(_c_f64p), C_out, C_in, r, kH, kW)
+    (lib().xo_expand_nnz if nnz_norm else lib().xo_expand)(Gp, Zp, dW.ctypes.data_as(_c_f64p), C_out, C_in, r, kH, kW)
     return dW
 
 
-def dw_from_xt(dY, Xt, Z, kH, kW, stride=(1, 1), pad=(0, 0)):
+def dw_from_xt(dY, Xt, Z, kH, kW, stride=(1, 1), pad=(0, 0), nnz_norm=False):
+    if nnz_norm:    # the two steps one after the other, the second with the scaling of Eq. (8)
+        return expand(correlate(dY, Xt, kH, kW, stride, pad), Z, nnz_norm=True)
     dY, dYp = _f32(dY)
     Xt, Xtp = _f32(Xt)
     Z, Zp = _f32(Z)

@@ -414,3 +414,79 @@ def test_paper_memory_ratio_table():
     # Sec. 4.1: N*C_in/r = 2^(14-gamma) for N = 1024, C_in = 16, r = 2^gamma
     for gamma, ratio in _read_numbers("paper_memory_ratio.txt"):
         assert 1024 * 16 // (2 ** gamma) == ratio == 2 ** (14 - gamma)
+
+
+# ---------------------------------------------------------------------------
+# Block-sparse probing vectors and the 1/nnz scaling (Sec. 3, Eq. (7), Eq. (8))
+# ---------------------------------------------------------------------------
+def test_sparse_probe_matrix_is_the_dense_one_with_entries_dropped():
+    C_in, r = 64, 48
+    for dist in (xo.RADEMACHER, xo.GAUSSIAN):
+        dense = xo.probe_matrix(dist, 77, C_in, r)
+        assert np.array_equal(xo.probe_matrix(dist, 77, C_in, r, 0), dense)
+        for keep in (4096, 16384, 24576):
+            Z = xo.probe_matrix(dist, 77, C_in, r, keep)
+            kept = Z != 0
+            assert np.array_equal(Z[kept], dense[kept])                # kept entries are the dense values
+            p = keep / 32768.0
+            n = C_in * r
+            assert abs(kept.mean() - p) < 4.0 * np.sqrt(p * (1 - p) / n)   # Bernoulli(p) per entry (Eq. (7))
+            # the keep decision does not depend on the value: +1 and -1 are dropped alike
+            if dist == xo.RADEMACHER:
+                assert abs(Z.sum()) < 4.0 * np.sqrt(n * p)
+        # the mask is its own stream: it is the same for both distributions of one seed
+    assert np.array_equal(xo.probe_matrix(xo.RADEMACHER, 77, C_in, r, 16384) != 0,
+                          xo.probe_matrix(xo.GAUSSIAN, 77, C_in, r, 16384) != 0)
+    assert not np.array_equal(xo.probe_matrix(xo.RADEMACHER, 77, C_in, r, 16384) != 0,
+                              xo.probe_matrix(xo.RADEMACHER, 78, C_in, r, 16384) != 0)
+
+
+@pytest.mark.parametrize("case", CLOSED_FORM_CASES)
+def test_sparse_estimate_closed_form(case):
+    # With the scaling of Eq. (8) the estimator is still linear in X:
+    #   dW_est[m,n] = sum_n' (D Z Z^T)[n,n'] dW_exact[m,n'],  D = diag(1 / nnz(Z_n)).
+    B, C_in, C_out, H, W, k, st, p, r, dist = case
+    rng = np.random.default_rng(17)
+    X = rng.standard_normal((B, C_in, H, W)).astype(np.float32)
+    Ho, Wo = xo.out_extent(H, k, st, p), xo.out_extent(W, k, st, p)
+    dY = rng.standard_normal((B, C_out, Ho, Wo)).astype(np.float32)
+    Z = xo.probe_matrix(dist, 12, C_in, r, 20000)
+    Z[0, :] = 0.0                                  # a block without any probe: nothing to estimate from
+    Xt = xo.probe_fwd(X, Z, xo.F32)
+    est = xo.dw_from_xt(dY, Xt, Z, k, k, (st, st), (p, p), nnz_norm=True)
+    w = torch.zeros((C_out, C_in, k, k), dtype=torch.float64, requires_grad=True)
+    F.conv2d(torch.from_numpy(X).double(), w, stride=st, padding=p).backward(torch.from_numpy(dY).double())
+    Zd = Z.astype(np.float64)
+    nnz = (Zd != 0).sum(axis=1)
+    D = np.where(nnz > 0, 1.0 / np.maximum(nnz, 1), 0.0)
+    want = np.einsum("nq,mqyx->mnyx", D[:, None] * (Zd @ Zd.T), w.grad.numpy())
+    assert np.max(np.abs(est - want)) <= 2e-6 * np.max(np.abs(want))
+    assert np.all(est[:, 0] == 0.0)
+    # dense Z: nnz = r, the two scalings coincide
+    Zf = xo.probe_matrix(dist, 12, C_in, r)
+    Xtf = xo.probe_fwd(X, Zf, xo.F32)
+    assert np.allclose(xo.dw_from_xt(dY, Xtf, Zf, k, k, (st, st), (p, p), nnz_norm=True),
+                       xo.dw_from_xt(dY, Xtf, Zf, k, k, (st, st), (p, p)), rtol=1e-12, atol=0)
+
+
+def test_sparse_estimator_is_unbiased_with_the_nnz_scaling_only():
+    # Eq. (8): dividing by nnz(Z_n) keeps the estimator unbiased; dividing by r
+    # (Eq. (6)) would shrink it by the keep probability.
+    X, dY = _layer(14)
+    C_in, r, keep = X.shape[1], 16, 16384          # p = 1/2; a block is empty with probability 2^-16
+    exact = xo.dw_exact(dY, X, 3, 3, (1, 1), (1, 1))
+    S_list = [16, 64, 256, 1024]
+    errs, acc, acc_r, done = [], np.zeros_like(exact), np.zeros_like(exact), 0
+    for S in S_list:
+        while done < S:
+            Z = xo.probe_matrix(xo.RADEMACHER, 300000 + done, C_in, r, keep)
+            Xt = xo.probe_fwd(X, Z, xo.F32)
+            G = xo.correlate(dY, Xt, 3, 3, (1, 1), (1, 1))
+            acc += xo.expand(G, Z, nnz_norm=True)
+            acc_r += xo.expand(G, Z)
+            done += 1
+        errs.append(np.linalg.norm(acc / S - exact) / np.linalg.norm(exact))
+    slope = np.polyfit(np.log(S_list), np.log(errs), 1)[0]
+    assert -0.65 < slope < -0.35, (slope, errs)
+    shrink = np.sum(acc_r / done * exact) / np.sum(exact * exact)
+    assert abs(shrink - 0.5) < 0.05, shrink
