@@ -60,12 +60,19 @@ typedef struct xconv_desc {
     int32_t dtype;                           /* xconv_dtype                                          */
     int32_t layout;                          /* xconv_layout                                         */
     int32_t probe;                           /* xconv_probe: how Z is obtained when no Z is passed   */
-    int32_t reserved;                        /* must be 0                                            */
+    int32_t keep_q15;                        /* 0: dense probes, scaled by 1/r (Eq. (3), (6)).
+                                              * 1..32767: block-sparse probes (Eq. (7)): every entry
+                                              * Z[n,j] is kept with probability keep_q15/32768 and is
+                                              * zero otherwise (one probability for all n), and the
+                                              * estimate of input channel n is scaled by 1/nnz(Z_n),
+                                              * the number of non-zero entries of row n of Z (Eq. (8));
+                                              * a row without any gives zeros.  With a caller's Z
+                                              * any non-zero value selects that scaling.              */
     uint64_t seed;                           /* Algorithm 1's s: same value in forward and backward  */
 } xconv_desc;
 
 /* Host-only validation.  XCONV_EINVAL: null desc, an extent < 1, stride < 1,
- * pad < 0, r < 1, H' or W' < 1, unknown enum, reserved != 0.
+ * pad < 0, r < 1, H' or W' < 1, unknown enum, keep_q15 outside 0..32767.
  * XCONV_EUNSUPPORTED: r > 1024; C_in or C_out > 65536; kH*kW > 49;
  * an extent whose tensors exceed 2^31-1 elements per image plane. */
 xconv_status xconv_check_desc(const xconv_desc *desc);
@@ -89,7 +96,9 @@ size_t xconv_workspace_bytes(const xconv_desc *desc, int op);
  * probing matrix that `desc->probe` and `desc->seed` define (Alg. 1 fwd step 2
  * / bwd step 2).  Rademacher: +1/-1 from the top bit of word c*r+j of the
  * SplitMix64 stream of the seed.  Gaussian: Box-Muller in double on words
- * 2(c*r+j), 2(c*r+j)+1, rounded to fp32.  XCONV_EINVAL for XCONV_USER_Z. */
+ * 2(c*r+j), 2(c*r+j)+1, rounded to fp32.  keep_q15 != 0: entry c*r+j is then
+ * zeroed unless the top 15 bits of word c*r+j of the stream of
+ * (seed xor 0x5851F42D4C957F2D) are below keep_q15.  XCONV_EINVAL for XCONV_USER_Z. */
 xconv_status xconv_probe_matrix(const xconv_desc *desc, float *Z_host);
 
 /* The same matrix generated on the device into Z_dev[C_in*r] (fp32). */

@@ -27,7 +27,7 @@ PROBES = {"rademacher": XCONV_RADEMACHER, "gaussian": XCONV_GAUSSIAN, "user": XC
 class xconv_desc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("B", "C_in", "C_out", "H", "W", "kH", "kW", "stride_h", "stride_w", "pad_h", "pad_w",
-                 "r", "dtype", "layout", "probe", "reserved")] + [("seed", ctypes.c_uint64)]
+                 "r", "dtype", "layout", "probe", "keep_q15")] + [("seed", ctypes.c_uint64)]
 
 
 class XConvError(RuntimeError):
@@ -82,13 +82,14 @@ def lib():
     return _lib
 
 
-def make_desc(B, C_in, C_out, H, W, k, stride=1, pad=0, r=1, dtype="f32", probe="rademacher", seed=0, layout=XCONV_NCHW):
+def make_desc(B, C_in, C_out, H, W, k, stride=1, pad=0, r=1, dtype="f32", probe="rademacher", seed=0, layout=XCONV_NCHW,
+              keep_q15=0):
     kH, kW = (k, k) if isinstance(k, int) else k
     sh, sw = (stride, stride) if isinstance(stride, int) else stride
     ph, pw = (pad, pad) if isinstance(pad, int) else pad
     return xconv_desc(B, C_in, C_out, H, W, kH, kW, sh, sw, ph, pw, r,
                       DTYPES[dtype] if isinstance(dtype, str) else dtype, layout,
-                      PROBES[probe] if isinstance(probe, str) else probe, 0, seed)
+                      PROBES[probe] if isinstance(probe, str) else probe, keep_q15, seed)
 
 
 def desc_from_config(cfg, seed=None):

@@ -118,12 +118,31 @@ __host__ __device__ inline uint64_t stream_word(uint64_t key, uint64_t ctr)
 {
     return mix_fin(key + 0x9E3779B97F4A7C15ull * (ctr + 1ull));
 }
-__host__ __device__ inline float probe_entry(int dist, uint64_t key, uint64_t idx)
+// `dist` carries the distribution in its low byte and, above it, keep_q15: 0 for dense probes,
+// else entry idx is kept with probability keep_q15 / 32768 and zero otherwise (block-sparse
+// probing vectors, Eq. (7)); the keep decision compares the top 15 bits of word idx of a
+// second stream (seed xor kMaskStream), so kept entries equal those of the dense matrix.
+constexpr uint64_t kMaskStream = 0x5851F42D4C957F2Dull;
+struct ProbeGen {
+    int dist, keep_q15;
+    uint64_t key, mkey;
+};
+__host__ __device__ inline ProbeGen probe_gen(int dist, uint64_t seed)
 {
-    if (dist == XCONV_RADEMACHER) return (stream_word(key, idx) >> 63) ? -1.0f : 1.0f;
+    ProbeGen g;
+    g.dist = dist & 0xff;
+    g.keep_q15 = dist >> 8;
+    g.key = mix_fin(seed + 0x9E3779B97F4A7C15ull);
+    g.mkey = mix_fin((seed ^ kMaskStream) + 0x9E3779B97F4A7C15ull);
+    return g;
+}
+__host__ __device__ inline float probe_entry(const ProbeGen &g, uint64_t idx)
+{
+    if (g.keep_q15 != 0 && (int)(stream_word(g.mkey, idx) >> 49) >= g.keep_q15) return 0.0f;
+    if (g.dist == XCONV_RADEMACHER) return (stream_word(g.key, idx) >> 63) ? -1.0f : 1.0f;
     // Box-Muller in double on two 53-bit uniforms, u1 in (0,1], u2 in [0,1)
-    const double u1 = ((double)(stream_word(key, 2ull * idx) >> 11) + 1.0) * 0x1.0p-53;
-    const double u2 = (double)(stream_word(key, 2ull * idx + 1ull) >> 11) * 0x1.0p-53;
+    const double u1 = ((double)(stream_word(g.key, 2ull * idx) >> 11) + 1.0) * 0x1.0p-53;
+    const double u2 = (double)(stream_word(g.key, 2ull * idx + 1ull) >> 11) * 0x1.0p-53;
     return (float)(sqrt(-2.0 * log(u1)) * cos(6.283185307179586476925 * u2));
 }
 

@@ -616,7 +616,7 @@ __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const f32x4 *
     // step 2) instead of a kernel launch of its own; the rest reduce.
     if ((int)blockIdx.x < zblocks) {
         const int i = blockIdx.x * kThreads + threadIdx.x;
-        if (i < nz) Zout[i] = probe_entry(dist, mix_fin(seed + 0x9E3779B97F4A7C15ull), (uint64_t)i);
+        if (i < nz) Zout[i] = probe_entry(probe_gen(dist, seed), (uint64_t)i);
         return;
     }
     __shared__ f32x4 red[16][17];
@@ -652,10 +652,12 @@ __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const f32x4 *
 // from global memory, and a lane ends up with all OG offsets of its (m, n) pairs, which are
 // adjacent in dW.
 // ---------------------------------------------------------------------------
+// nnz_norm: rows are scaled by 1 / nnz(Z_n), the number of non-zero entries of row n of Z (Eq. (8),
+// block-sparse probing vectors), instead of 1 / r; a row without any gives zeros.
 template <int OG>
 __global__ __launch_bounds__(64) void expand_kernel(const float *__restrict__ T, const float *__restrict__ Z,
                                                     float *__restrict__ dW, int K2, int JP, int MP, int C_out, int C_in, int r,
-                                                    int NTN)
+                                                    int NTN, int nnz_norm)
 {
     const int lane = threadIdx.x, l16 = lane & 15, g = lane >> 4;
     const int nt = blockIdx.x % NTN, mt = blockIdx.x / NTN;
@@ -689,7 +691,12 @@ __global__ __launch_bounds__(64) void expand_kernel(const float *__restrict__ T,
 #pragma unroll
             for (int o = 0; o < OG; ++o) acc[o] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][o], bv[u], acc[o], 0, 0, 0);
     }
-    const float inv_r = 1.0f / (float)r;
+    float inv_r = 1.0f / (float)r;
+    if (nnz_norm) {
+        int cnt = 0;
+        for (int j = 0; j < r; ++j) cnt += zrow[j] != 0.0f ? 1 : 0;
+        inv_r = cnt > 0 ? 1.0f / (float)cnt : 0.0f;
+    }
     if (ncol < C_in) {
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
@@ -990,8 +997,9 @@ hipError_t launch_reduce(const CorrParams &P, hipStream_t st, float *Zout, int n
     return hipGetLastError();
 }
 
-hipError_t launch_expand(const CorrParams &P, const float *Z, float *dW, int C_in, int r, hipStream_t st)
+hipError_t launch_expand(const CorrParams &P, const float *Z, float *dW, int C_in, int r, hipStream_t st, bool nnz_norm)
 {
+    const int nn = nnz_norm ? 1 : 0;
     if (Z) {
         // few tiles: split the offsets over more waves; many tiles: a lane writes whole runs of offsets
         const int NTM16 = ceil_div(P.C_out, 16), NTN = ceil_div(C_in, 16);
@@ -1001,12 +1009,12 @@ hipError_t launch_expand(const CorrParams &P, const float *Z, float *dW, int C_i
         const dim3 grid((unsigned)tiles, (unsigned)ceil_div(P.K2, og));
         const float *T = reduced_tile(P);
         if (og == 9)
-            hipLaunchKernelGGL(expand_kernel<9>, grid, dim3(64), 0, st, T, Z, dW, P.K2, P.JP, P.MP, P.C_out, C_in, r, NTN);
+            hipLaunchKernelGGL(expand_kernel<9>, grid, dim3(64), 0, st, T, Z, dW, P.K2, P.JP, P.MP, P.C_out, C_in, r, NTN, nn);
         else if (og == 3)
-            hipLaunchKernelGGL(expand_kernel<3>, grid, dim3(64), 0, st, T, Z, dW, P.K2, P.JP, P.MP, P.C_out, C_in, r, NTN);
+            hipLaunchKernelGGL(expand_kernel<3>, grid, dim3(64), 0, st, T, Z, dW, P.K2, P.JP, P.MP, P.C_out, C_in, r, NTN, nn);
         else
             hipLaunchKernelGGL(expand_kernel<1>, dim3((unsigned)tiles, (unsigned)P.K2), dim3(64), 0, st, T, Z, dW, P.K2, P.JP, P.MP,
-                               P.C_out, C_in, r, NTN);
+                               P.C_out, C_in, r, NTN, nn);
     } else {
         const long long total = (long long)P.C_out * C_in * P.K2;
         hipLaunchKernelGGL(untile_kernel, dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, st,

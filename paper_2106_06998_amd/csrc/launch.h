@@ -38,7 +38,7 @@ hipError_t launch_repack_planes(int dtype, const void *src, void *dst, long long
 hipError_t launch_reduce(const CorrParams &P, hipStream_t st, float *Zout = nullptr, int nz = 0, int dist = 0, uint64_t seed = 0);
 // dW[m,n,o] = (1/r) * sum_j Z[n,j] * T[o,j,m]   (Z != nullptr)
 // dW[m,n,o] = T[o,n,m]                          (Z == nullptr, exact path)
-hipError_t launch_expand(const CorrParams &P, const float *Z, float *dW, int C_in, int r, hipStream_t st);
+hipError_t launch_expand(const CorrParams &P, const float *Z, float *dW, int C_in, int r, hipStream_t st, bool nnz_norm = false);
 
 
 // corr_ws_kernels.hip: producer/consumer variant for 16-bit storage.  plan_corr_ws returns

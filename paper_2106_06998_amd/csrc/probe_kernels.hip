@@ -19,16 +19,15 @@ namespace xc {
 
 void host_probe_matrix(int dist, uint64_t seed, int n, float *Z)
 {
-    const uint64_t key = mix_fin(seed + 0x9E3779B97F4A7C15ull);
-    for (int i = 0; i < n; ++i) Z[i] = probe_entry(dist, key, (uint64_t)i);
+    const ProbeGen g = probe_gen(dist, seed);
+    for (int i = 0; i < n; ++i) Z[i] = probe_entry(g, (uint64_t)i);
 }
 
 __global__ __launch_bounds__(kThreads) void gen_z_kernel(float *__restrict__ Z, int n, int dist, uint64_t seed)
 {
     const int i = blockIdx.x * kThreads + threadIdx.x;
     if (i >= n) return;
-    const uint64_t key = mix_fin(seed + 0x9E3779B97F4A7C15ull);
-    Z[i] = probe_entry(dist, key, (uint64_t)i);
+    Z[i] = probe_entry(probe_gen(dist, seed), (uint64_t)i);
 }
 
 // Row i of MFMA tile jt holds probe column j0 + jmap: lane group g = i/4 then
@@ -62,7 +61,7 @@ __global__ __launch_bounds__(kThreads) void pack_z_f32_kernel(const float *__res
     float z = 0.0f;
     if (c < C_in && j < r) {
         const size_t idx = (size_t)c * r + j;
-        z = Z ? Z[idx] : probe_entry(dist, mix_fin(seed + 0x9E3779B97F4A7C15ull), (uint64_t)idx);
+        z = Z ? Z[idx] : probe_entry(probe_gen(dist, seed), (uint64_t)idx);
     }
     out[(size_t)bi * KQ4 * 4 * 64 + (kq * JTb + jt) * 64 + l] = z;
 }
@@ -76,7 +75,7 @@ __global__ __launch_bounds__(kThreads) void pack_z_16_kernel(const float *__rest
     const int l = e & 63, tj = (e >> 6) % NTJ, kk = (e >> 6) / NTJ;
     const int bi = tj >> 2, jt = tj & 3, JTb = (NTJ - 4 * bi) < 4 ? (NTJ - 4 * bi) : 4;
     const int j = 64 * bi + jmap(jt, l & 15, JTb);
-    const uint64_t key = mix_fin(seed + 0x9E3779B97F4A7C15ull);
+    const ProbeGen gen = probe_gen(dist, seed);
     uint32_t hi[4], lo[4];
 #pragma unroll
     for (int q = 0; q < 8; q += 2) {
@@ -87,7 +86,7 @@ __global__ __launch_bounds__(kThreads) void pack_z_16_kernel(const float *__rest
             z[u] = 0.0f;
             if (c < C_in && j < r) {
                 const size_t idx = (size_t)c * r + j;
-                z[u] = Z ? Z[idx] : probe_entry(dist, key, (uint64_t)idx);
+                z[u] = Z ? Z[idx] : probe_entry(gen, (uint64_t)idx);
             }
         }
         const uint16_t h0 = f32_to_st16<DT>(z[0]), h1 = f32_to_st16<DT>(z[1]);

@@ -111,6 +111,9 @@ bool get_plan(PlanEntry &out, int dtype, int B, int C_out, int H, int W, int kH,
     return e.ok;
 }
 
+// distribution and keep probability in the form the generator takes
+int probe_code(const xconv_desc *d) { return d->probe | (d->keep_q15 << 8); }
+
 size_t z_bytes(const xconv_desc *d) { return align_up((size_t)d->C_in * d->r * sizeof(float), 256); }
 // Z in the fragment order of the probe kernels, behind the fp32 Z in the probe workspace
 size_t zfrag_bytes(const xconv_desc *d)
@@ -141,7 +144,7 @@ xconv_status xconv_check_desc(const xconv_desc *d)
     if (!d) return XCONV_EINVAL;
     if (d->B < 1 || d->C_in < 1 || d->C_out < 1 || d->H < 1 || d->W < 1) return XCONV_EINVAL;
     if (d->kH < 1 || d->kW < 1 || d->stride_h < 1 || d->stride_w < 1 || d->pad_h < 0 || d->pad_w < 0) return XCONV_EINVAL;
-    if (d->r < 1 || d->reserved != 0) return XCONV_EINVAL;
+    if (d->r < 1 || d->keep_q15 < 0 || d->keep_q15 > 32767) return XCONV_EINVAL;
     if (d->dtype < XCONV_F32 || d->dtype > XCONV_F16) return XCONV_EINVAL;
     if (d->layout < XCONV_NCHW || d->layout > XCONV_NHWC) return XCONV_EINVAL;
     if (d->probe < XCONV_RADEMACHER || d->probe > XCONV_USER_Z) return XCONV_EINVAL;
@@ -184,7 +187,7 @@ xconv_status xconv_probe_matrix(const xconv_desc *d, float *Z_host)
     xconv_status s = xconv_check_desc(d);
     if (s != XCONV_OK) return s;
     if (!Z_host || d->probe == XCONV_USER_Z) return XCONV_EINVAL;
-    host_probe_matrix(d->probe, d->seed, d->C_in * d->r, Z_host);
+    host_probe_matrix(probe_code(d), d->seed, d->C_in * d->r, Z_host);
     return XCONV_OK;
 }
 
@@ -194,7 +197,7 @@ xconv_status xconv_probe_matrix_dev(const xconv_desc *d, float *Z_dev, void *str
     if (s != XCONV_OK) return s;
     if (!Z_dev || d->probe == XCONV_USER_Z) return XCONV_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    XC_LAUNCH(K_GEN_Z, st, launch_gen_z(Z_dev, d->C_in * d->r, d->probe, d->seed, st));
+    XC_LAUNCH(K_GEN_Z, st, launch_gen_z(Z_dev, d->C_in * d->r, probe_code(d), d->seed, st));
     return XCONV_OK;
 }
 
@@ -222,13 +225,13 @@ xconv_status xconv_probe_fwd(const xconv_desc *d, const void *X_dev, void *Xt_de
         // With scratch, Z goes to the kernels in fragment order (drawn from the seed when no Z
         // is given); without it, every workgroup gathers its fragments from Z_dev.
         void *zpack = ws_dev ? static_cast<char *>(ws_dev) + zb : nullptr;
-        if (zpack) XC_LAUNCH(K_PACK_Z, st, launch_pack_z(d->dtype, Z_dev, zpack, d->C_in, d->r, z_exact16, d->probe, d->seed, nhwc, st));
+        if (zpack) XC_LAUNCH(K_PACK_Z, st, launch_pack_z(d->dtype, Z_dev, zpack, d->C_in, d->r, z_exact16, probe_code(d), d->seed, nhwc, st));
         XC_LAUNCH(K_PROBE, st, launch_probe(d->dtype, X_dev, Z_dev, zpack, Xt_dev, d->B, d->C_in, HW, d->r, CS, z_exact16, nhwc, st));
     } else {
         const float *Z = Z_dev;
         if (!Z) {
             float *zw = static_cast<float *>(ws_dev);
-            XC_LAUNCH(K_GEN_Z, st, launch_gen_z(zw, d->C_in * d->r, d->probe, d->seed, st));
+            XC_LAUNCH(K_GEN_Z, st, launch_gen_z(zw, d->C_in * d->r, probe_code(d), d->seed, st));
             Z = zw;
         }
         XC_LAUNCH(K_PROBE_GENERIC, st, launch_probe_generic(d->dtype, X_dev, Z, Xt_dev, d->B, d->C_in, HW, d->r, CS, nhwc, st));
@@ -282,8 +285,8 @@ xconv_status xconv_dw_estimate(const xconv_desc *d, const void *dY_dev, const vo
     } else {
         XC_LAUNCH(K_CORR, st, launch_corr(d->dtype, P, st));
     }
-    XC_LAUNCH(K_REDUCE, st, launch_reduce(P, st, zw, d->C_in * d->r, d->probe, d->seed));
-    XC_LAUNCH(K_EXPAND, st, launch_expand(P, Z, dW_dev, d->C_in, d->r, st));
+    XC_LAUNCH(K_REDUCE, st, launch_reduce(P, st, zw, d->C_in * d->r, probe_code(d), d->seed));
+    XC_LAUNCH(K_EXPAND, st, launch_expand(P, Z, dW_dev, d->C_in, d->r, st, d->keep_q15 != 0));
     return XCONV_OK;
 }
 

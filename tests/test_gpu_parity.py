@@ -252,6 +252,62 @@ def test_producer_consumer_kernel_is_deterministic():
     assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
 
 
+# ---------------------------------------------------------------------------
+# block-sparse probing vectors with the 1/nnz scaling (Eq. (7), Eq. (8))
+# ---------------------------------------------------------------------------
+SPARSE = [
+    # name, B, C_in, C_out, H, W, k, stride, pad, r, probe, dtype, keep_q15
+    ("sp-f32-rad", 4, 24, 20, 14, 14, 3, 1, 1, 16, "rademacher", "f32", 16384),
+    ("sp-f32-gauss", 3, 40, 64, 12, 10, 3, 1, 1, 20, "gaussian", "f32", 8192),
+    ("sp-f16-rad-ws", 9, 64, 64, 14, 14, 3, 1, 1, 64, "rademacher", "f16", 12000),
+    ("sp-bf16-gauss-s2", 8, 32, 48, 15, 15, 3, 2, 1, 32, "gaussian", "bf16", 20000),
+    ("sp-f32-empty-rows", 2, 32, 16, 10, 10, 3, 1, 1, 4, "rademacher", "f32", 6000),   # some rows of Z are all zero
+]
+
+
+@pytest.mark.parametrize("e", SPARSE, ids=[e[0] for e in SPARSE])
+@pytest.mark.parametrize("given_z", [False, True], ids=["seedZ", "givenZ"])
+def test_block_sparse_probes(e, given_z):
+    name, B, C_in, C_out, H, W, k, stride, pad, r, probe, dtype, keep = e
+    say("block-sparse probes %s, Z %s" % (name, "given" if given_z else "from the seed"))
+    Ho, Wo = xo.out_extent(H, k, stride, pad), xo.out_extent(W, k, stride, pad)
+    X = synth.draw((B, C_in, H, W), 51, "relu_normal", 1.0, dtype)
+    dY = synth.draw((B, C_out, Ho, Wo), 52, "normal", 1e-2, dtype)
+    Z = xo.probe_matrix(OPROBE[probe], 53, C_in, r, keep)
+    assert 0 < np.count_nonzero(Z) < Z.size
+    d = xb.make_desc(B, C_in, C_out, H, W, k, stride, pad, r, dtype, probe, 53, keep_q15=keep)
+    # the device generator drops the same entries
+    Zg = torch.empty((C_in, r), dtype=torch.float32, device=DEV)
+    xb.xconv_probe_matrix_dev(d, Zg)
+    torch.cuda.synchronize()
+    assert np.array_equal(Zg.cpu().numpy() == 0, Z == 0)
+    assert np.max(np.abs(Zg.cpu().numpy() - Z)) <= 2.4e-7 * np.max(np.abs(Z))
+    Xd, dYd = xb.to_device(X, dtype, DEV), xb.to_device(dY, dtype, DEV)
+    Zd = torch.from_numpy(Z).to(DEV) if given_z else None
+    if given_z:
+        d.probe = xb.XCONV_USER_Z
+    Xt = xb.alloc_xt(d, DEV)
+    xb.xconv_probe_fwd(d, Xd, Xt, Zd, xb.alloc_ws(d, xb.XCONV_OP_PROBE, DEV))
+    unp = torch.empty((B, r, H, W), dtype=torch.float32, device=DEV)
+    xb.xconv_xt_unpack(d, Xt, unp)
+    dW = torch.full((C_out, C_in, k, k), float("nan"), dtype=torch.float32, device=DEV)
+    xb.xconv_dw_estimate(d, dYd, Xt, Zd, dW, xb.alloc_ws(d, xb.XCONV_OP_ESTIMATE, DEV))
+    torch.cuda.synchronize()
+
+    class C:
+        pass
+    C.dtype = dtype
+    Xt_o = xo.probe_fwd(X, Z, ODT[dtype])
+    check_probe_output(C, unp.cpu().numpy(), Xt_o, z_exact=(probe == "rademacher"))
+    want = xo.dw_from_xt(dY, Xt_o, Z, k, k, (stride, stride), (pad, pad), nnz_norm=True)
+    got = dW.cpu().numpy().astype(np.float64)
+    assert rel_max(got, want) <= GRAD_TOL[dtype]
+    empty = np.count_nonzero(Z, axis=1) == 0
+    assert np.all(got[:, empty] == 0.0)
+    if name == "sp-f32-empty-rows":
+        assert empty.any()
+
+
 # Channels-last X and dY (layout NHWC): the probe reads X directly (fast path when C_in is a
 # multiple of the 16-byte vector, any-shape kernel otherwise, tiles with a ragged tail of
 # pixels), dY is brought into plane form first, the exact path takes X as it is when C_in is a

@@ -39,7 +39,7 @@ def test_check_desc_statuses():
     assert xb.lib().xconv_check_desc(None) == xb.XCONV_EINVAL
     for field, val in (("B", 0), ("C_in", -1), ("C_out", 0), ("H", 0), ("W", 0), ("kH", 0), ("kW", 0),
                        ("stride_h", 0), ("stride_w", 0), ("pad_h", -1), ("pad_w", -1), ("r", 0),
-                       ("dtype", 3), ("dtype", -1), ("layout", 2), ("probe", 3), ("reserved", 1)):
+                       ("dtype", 3), ("dtype", -1), ("layout", 2), ("probe", 3), ("keep_q15", -1), ("keep_q15", 32768)):
         d = _good()
         setattr(d, field, val)
         assert xb.xconv_check_desc(d) == xb.XCONV_EINVAL, field
@@ -93,6 +93,13 @@ def test_host_probe_matrix_matches_oracle_generator(probe, code):
             # same stream words, same double-precision Box-Muller: at most an ulp apart
             assert np.max(np.abs(Z - Zo)) <= 2.4e-7 * np.max(np.abs(Zo))
             assert np.mean(Z == Zo) > 0.99
+    # block-sparse probes: the same entries dropped as in the oracle's matrix
+    for keep in (1, 8192, 16384, 32767):
+        d = xb.make_desc(1, 48, 1, 8, 8, 3, 1, 1, 40, "f32", probe, 4242, keep_q15=keep)
+        Z = xb.xconv_probe_matrix(d)
+        Zo = xo.probe_matrix(code, 4242, 48, 40, keep)
+        assert np.array_equal(Z == 0, Zo == 0)
+        assert np.max(np.abs(Z - Zo)) <= 2.4e-7 * max(np.max(np.abs(Zo)), 1e-30)
     d = xb.make_desc(1, 4, 1, 8, 8, 3, 1, 1, 2, "f32", "user", 1)
     with pytest.raises(xb.XConvError) as e:
         xb.xconv_probe_matrix(d)
