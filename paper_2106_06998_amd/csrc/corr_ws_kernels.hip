@@ -144,7 +144,7 @@ template <int DT> __device__ inline f32x16 mfma32(const uint4 &a, const uint4 &b
 
 // CB > 0: 3x3 offsets and the bytes of one staged column of A (BSTR * 16) known at compile time:
 // the three column offsets of a kernel row are then immediates of one address register.
-template <int DT, int NOFF, int NTASK, int D, int CB>
+template <int DT, int NOFF, int NTASK, int D, int CB, bool RU>
 __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
 {
     extern __shared__ uint4 ws_lds[];
@@ -204,6 +204,208 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
         };
 
         if (NI > 0) {
+          if constexpr (RU) {
+            // ---- 3x3, unit stride: the fragments of one staged pixel serve three k-steps ----
+            // Lane group g takes pixel slot q + g*Q of a sub-step of 2Q slots (not 2q + g), so the
+            // B fragment of kernel column kx at k-step q is the one of column 0 at k-step q + kx:
+            // per kernel row a window of three fragments slides along the staged row, and a
+            // k-step requests 1 + 3 fragments instead of 1 + 9.  The three window registers of a
+            // kernel row are used in rotation: k-steps come in groups of three (one variant of the
+            // code per position in the group), each requesting the new column into the registers
+            // whose last use was issued an MFMA earlier.  The k-steps left over at the end of a
+            // sub-step, and its last one, refill the whole window instead (nine requests).
+            typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+            WsPos pc = ws_pos_of(P, t_begin);
+            int brow[NOFF];
+            set_brow(pc, brow);
+            const uint32_t lds0 = __builtin_amdgcn_groupstaticsize();
+            const uint32_t a_wave = lds0 + (uint32_t)(wm * 32 + l32) * 16u;
+            const uint32_t b_wave = lds0 + (uint32_t)(2 * P.a_units + G * 16 + (((l32 & 15) + wj * rotmul) & 15)) * 16u;
+            const uint32_t step_a = (uint32_t)P.M_WG * 16u;  // one pixel slot per k-step
+            auto a_addr = [&](int buf, int Q) { return a_wave + (uint32_t)(buf * P.a_units + g * Q * P.M_WG) * 16u; };
+            // column 0 of kernel row ky for the lane's half of the sub-step
+            auto b_addr = [&](const WsPos &p, int Q, int ky) {
+                return b_wave + (uint32_t)(brow[3 * ky] + (p.u * P.CWs + g * Q) * P.BSTR) * 16u;
+            };
+            auto lds_read = [](u32x4 &dst, uint32_t addr, auto off) {
+                asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(decltype(off)::value) : "memory");
+            };
+            // requests return in order: at most N younger ones may be in flight behind x, y, z
+            auto arrived3 = [](auto nc, u32x4 &x, u32x4 &y, u32x4 &z) {
+                asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(x), "+v"(y), "+v"(z) : "n"(decltype(nc)::value) : "memory");
+            };
+            auto arrived1 = [](auto nc, u32x4 &x) { asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(x) : "n"(decltype(nc)::value) : "memory"); };
+            using I0 = std::integral_constant<int, 0>;
+            using C1 = std::integral_constant<int, CB>;
+            using C2 = std::integral_constant<int, 2 * CB>;
+            using O0 = std::integral_constant<int, 0>; using O1 = std::integral_constant<int, 1>; using O2 = std::integral_constant<int, 2>;
+            using O3 = std::integral_constant<int, 3>; using O4 = std::integral_constant<int, 4>; using O5 = std::integral_constant<int, 5>;
+            using O6 = std::integral_constant<int, 6>; using O7 = std::integral_constant<int, 7>; using O8 = std::integral_constant<int, 8>;
+            u32x4 a, an, b[9];   // b[3*ky + w]: window register w of kernel row ky
+            uint32_t pa, pb3[3];
+            auto mma = [&](auto oc, const u32x4 &bf) {
+                constexpr int o = decltype(oc)::value;
+                acc[o] = mfma32<DT>(__builtin_bit_cast(uint4, a), __builtin_bit_cast(uint4, bf), acc[o]);
+            };
+
+            int Q = ws_cw_sub(P, pc) >> 1;
+            pa = a_addr(0, Q);
+#pragma unroll
+            for (int ky = 0; ky < 3; ++ky) pb3[ky] = b_addr(pc, Q, ky);
+            ws_barrier();  // the first dY tile and the rows of the first row-step are in LDS
+            lds_read(an, pa, I0{});
+            ws_static_for<0, 9>([&](auto oc) {   // window register w <- column w, kernel rows inside
+                constexpr int o = decltype(oc)::value;
+                lds_read(b[3 * (o % 3) + o / 3], pb3[o % 3], std::integral_constant<int, (o / 3) * CB>{});
+            });
+            arrived1(std::integral_constant<int, 9>{}, an);
+            a = an;
+#pragma unroll
+            for (int ky = 0; ky < 3; ++ky) pb3[ky] += 3u * CB;   // the column that k-step 0 requests
+
+            // Position `ph` of a group of three k-steps: window register (ph + kx) % 3 holds the
+            // column of kernel column kx.  In flight at the start: the three requests of the k-step
+            // before, or the nine of a window refill; counted from the youngest, what a kernel
+            // column needs is followed by at most 7 / 6 / 4 requests, and in the steady state the
+            // first two waits fall through.
+            auto inner = [&](auto phc) {
+                constexpr int w0 = decltype(phc)::value, w1 = (w0 + 1) % 3, w2 = (w0 + 2) % 3;
+                __builtin_amdgcn_sched_barrier(0);
+                lds_read(an, pa, I0{});
+                arrived3(std::integral_constant<int, 7>{}, b[w0], b[3 + w0], b[6 + w0]);
+                mma(O0{}, b[w0]);
+                mma(O3{}, b[3 + w0]);
+                __builtin_amdgcn_sched_barrier(0);
+                lds_read(b[w0], pb3[0], I0{});
+                __builtin_amdgcn_sched_barrier(0);
+                mma(O6{}, b[6 + w0]);
+                __builtin_amdgcn_sched_barrier(0);
+                lds_read(b[3 + w0], pb3[1], I0{});
+                __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_sched_barrier(0);
+                arrived3(std::integral_constant<int, 6>{}, b[w1], b[3 + w1], b[6 + w1]);
+                mma(O1{}, b[w1]);
+                __builtin_amdgcn_sched_barrier(0);
+                lds_read(b[6 + w0], pb3[2], I0{});
+                __builtin_amdgcn_sched_barrier(0);
+                mma(O4{}, b[3 + w1]);
+                mma(O7{}, b[6 + w1]);
+                __builtin_amdgcn_sched_barrier(0);
+                arrived3(std::integral_constant<int, 4>{}, b[w2], b[3 + w2], b[6 + w2]);
+                mma(O2{}, b[w2]);
+                mma(O5{}, b[3 + w2]);
+                mma(O8{}, b[6 + w2]);
+                __builtin_amdgcn_sched_barrier(0);
+                arrived1(std::integral_constant<int, 3>{}, an);
+                a = an;
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            // A k-step at position 0 that refills the whole window (and A) from (pa_n, pbn): column
+            // kx into window register kx right after the MFMAs that read it.  Used for the last
+            // k-step of a sub-step (the addresses are then those of the next sub-step) and for
+            // k-steps that do not fill a group of three.
+            auto refill = [&](uint32_t pa_n, const uint32_t (&pbn)[3]) {
+                __builtin_amdgcn_sched_barrier(0);
+                lds_read(an, pa_n, I0{});
+                arrived3(std::integral_constant<int, 7>{}, b[0], b[3], b[6]);
+                mma(O0{}, b[0]);
+                mma(O3{}, b[3]);
+                __builtin_amdgcn_sched_barrier(0);
+                lds_read(b[0], pbn[0], I0{});
+                __builtin_amdgcn_sched_barrier(0);
+                mma(O6{}, b[6]);
+                __builtin_amdgcn_sched_barrier(0);
+                lds_read(b[3], pbn[1], I0{});
+                __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_sched_barrier(0);
+                arrived3(std::integral_constant<int, 6>{}, b[1], b[4], b[7]);
+                mma(O1{}, b[1]);
+                __builtin_amdgcn_sched_barrier(0);
+                lds_read(b[6], pbn[2], I0{});
+                __builtin_amdgcn_sched_barrier(0);
+                mma(O4{}, b[4]);
+                __builtin_amdgcn_sched_barrier(0);
+                lds_read(b[1], pbn[0], C1{});
+                __builtin_amdgcn_sched_barrier(0);
+                mma(O7{}, b[7]);
+                __builtin_amdgcn_sched_barrier(0);
+                lds_read(b[4], pbn[1], C1{});
+                __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_sched_barrier(0);
+                arrived3(std::integral_constant<int, 6>{}, b[2], b[5], b[8]);
+                mma(O2{}, b[2]);
+                __builtin_amdgcn_sched_barrier(0);
+                lds_read(b[7], pbn[2], C1{});
+                __builtin_amdgcn_sched_barrier(0);
+                mma(O5{}, b[5]);
+                __builtin_amdgcn_sched_barrier(0);
+                lds_read(b[2], pbn[0], C2{});
+                __builtin_amdgcn_sched_barrier(0);
+                mma(O8{}, b[8]);
+                __builtin_amdgcn_sched_barrier(0);
+                lds_read(b[5], pbn[1], C2{});
+                __builtin_amdgcn_sched_barrier(0);
+                lds_read(b[8], pbn[2], C2{});
+                __builtin_amdgcn_sched_barrier(0);
+                arrived1(std::integral_constant<int, 9>{}, an);
+                a = an;
+                __builtin_amdgcn_sched_barrier(0);
+            };
+
+            uint32_t pbn[3];
+            for (int i = 0; i < NI; ++i) {
+                const int n_in = Q - 1;                        // k-steps before the last one
+                const int n3 = (n_in * 0xAAAB) >> 17;          // n_in / 3
+                for (int t = 0; t < n3; ++t) {
+                    pa += step_a;
+                    inner(std::integral_constant<int, 0>{});
+                    pa += step_a;
+#pragma unroll
+                    for (int ky = 0; ky < 3; ++ky) pb3[ky] += (uint32_t)CB;
+                    inner(std::integral_constant<int, 1>{});
+                    pa += step_a;
+#pragma unroll
+                    for (int ky = 0; ky < 3; ++ky) pb3[ky] += (uint32_t)CB;
+                    inner(std::integral_constant<int, 2>{});
+#pragma unroll
+                    for (int ky = 0; ky < 3; ++ky) pb3[ky] += (uint32_t)CB;
+                }
+                for (int t = 3 * n3; t < n_in; ++t) {
+                    // pb3 is the column three ahead of the current one: the next k-step starts two before it
+                    pa += step_a;
+#pragma unroll
+                    for (int ky = 0; ky < 3; ++ky) pbn[ky] = pb3[ky] - 2u * CB;
+                    refill(pa, pbn);
+#pragma unroll
+                    for (int ky = 0; ky < 3; ++ky) pb3[ky] += (uint32_t)CB;
+                }
+                // The last k-step of the sub-step.  Its fragments were requested during the k-step
+                // before; once they are here the consumers no longer read sub-step i, so its buffer
+                // and the ring rows it alone used go back to the producers now.
+                uint32_t pa_n = pa;
+                int Qn = Q;
+                if (i + 1 < NI) {
+                    const WsPos pn = ws_advance(P, pc);
+                    if (pn.t != pc.t) set_brow(pn, brow);
+                    Qn = ws_cw_sub(P, pn) >> 1;
+                    pa_n = a_addr((i + 1) & 1, Qn);
+#pragma unroll
+                    for (int ky = 0; ky < 3; ++ky) pbn[ky] = b_addr(pn, Qn, ky);
+                    if (pn.u == 0 && pn.y == 0) ws_barrier();  // run boundary: the producers refill the whole ring first
+                    ws_barrier();
+                    pc = pn;
+                } else {
+                    // after the very last sub-step the requests repeat addresses of this one
+#pragma unroll
+                    for (int ky = 0; ky < 3; ++ky) pbn[ky] = b_addr(pc, Q, ky);
+                }
+                refill(pa_n, pbn);
+                pa = pa_n;
+                Q = Qn;
+#pragma unroll
+                for (int ky = 0; ky < 3; ++ky) pb3[ky] = pbn[ky] + 3u * CB;
+            }
+          } else {
             typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
             WsPos pc = ws_pos_of(P, t_begin);
             int brow[NOFF];
@@ -300,6 +502,7 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
                 // (after the very last sub-step the requests repeat the current addresses)
                 kstep();
             }
+          }
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         }
 
@@ -758,13 +961,13 @@ bool plan_corr_ws(WsParams &P, int dtype, int B, int C_out, int H, int W, int kH
     return true;
 }
 
-template <int DT, int NTASK, int D, int CB>
+template <int DT, int NTASK, int D, int CB, bool RU>
 static hipError_t launch_ws_cfg(const WsParams &P, hipStream_t st)
 {
     const size_t lds = corr_ws_lds_bytes(P);
     static bool done = false;  // per instantiation: the attribute sticks to the function
     if (!done && lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(corr_ws_kernel<DT, 9, NTASK, D, CB>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(corr_ws_kernel<DT, 9, NTASK, D, CB, RU>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kWsLdsLimit);
         if (e != hipSuccess) return e;
         done = true;
@@ -772,7 +975,7 @@ static hipError_t launch_ws_cfg(const WsParams &P, hipStream_t st)
     WsParams Q = P;
     Q.SQ = P.NS / P.S;
     Q.SR = P.NS % P.S;
-    hipLaunchKernelGGL((corr_ws_kernel<DT, 9, NTASK, D, CB>), dim3(P.S, P.NTM * P.NTJ, P.NOG), dim3(kWsThreads), lds, st, Q);
+    hipLaunchKernelGGL((corr_ws_kernel<DT, 9, NTASK, D, CB, RU>), dim3(P.S, P.NTM * P.NTJ, P.NOG), dim3(kWsThreads), lds, st, Q);
     return hipGetLastError();
 }
 
@@ -781,14 +984,24 @@ template <int DT> static hipError_t launch_ws_dt(const WsParams &P, hipStream_t 
     // (plan_corr_ws only accepts plans with one task per producer thread)
     static const bool generic = ws_env_int("XCONV_WS_GENERIC", 0) != 0;
     if (!generic && P.K2 == 9 && P.kW == 3) {
+        // unit stride: fragments are reused along the staged row
+        static const bool reuse = ws_env_int("XCONV_WS_REUSE", 1) != 0;
+        if (reuse && P.sw == 1 && P.kH == 3) {
+            switch (P.BSTR) {
+            case 32: return launch_ws_cfg<DT, 1, 3, 32 * 16, true>(P, st);
+            case 64: return launch_ws_cfg<DT, 1, 3, 64 * 16, true>(P, st);
+            case 128: return launch_ws_cfg<DT, 1, 3, 128 * 16, true>(P, st);
+            default: break;
+            }
+        }
         switch (P.BSTR) {
-        case 32: return launch_ws_cfg<DT, 1, 3, 32 * 16>(P, st);
-        case 64: return launch_ws_cfg<DT, 1, 3, 64 * 16>(P, st);
-        case 128: return launch_ws_cfg<DT, 1, 3, 128 * 16>(P, st);
+        case 32: return launch_ws_cfg<DT, 1, 3, 32 * 16, false>(P, st);
+        case 64: return launch_ws_cfg<DT, 1, 3, 64 * 16, false>(P, st);
+        case 128: return launch_ws_cfg<DT, 1, 3, 128 * 16, false>(P, st);
         default: break;
         }
     }
-    return launch_ws_cfg<DT, 1, 3, 0>(P, st);
+    return launch_ws_cfg<DT, 1, 3, 0, false>(P, st);
 }
 
 hipError_t launch_corr_ws(int dtype, const WsParams &P, hipStream_t st)
