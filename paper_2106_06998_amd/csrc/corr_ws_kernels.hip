@@ -801,9 +801,14 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
             WsPos pw = ws_pos_of(P, t_begin);  // sub-step whose data is written next
             WsPos pi = pw;                     // sub-step whose loads are issued next
             u32x4 st[D][NTASK][8];
-            prime(pw, std::integral_constant<int, 3>{});  // (before the pipeline fills: its loads need the registers of the stages)
+            // The loads of the first sub-step go out first and stay in flight during the window's
+            // round trip (one trip to memory instead of two before the first MFMA); the other stages
+            // are issued after it, their registers being used by the window's loads meanwhile.
+            issue(pi, true, st[0]);
+            pi = ws_advance(P, pi);
+            prime(pw, std::integral_constant<int, 3>{});
 #pragma unroll
-            for (int d = 0; d < D; ++d) {
+            for (int d = 1; d < D; ++d) {
                 issue(pi, d < NI, st[d]);
                 pi = ws_advance(P, pi);
             }
