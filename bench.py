@@ -228,7 +228,7 @@ def main():
         else:
             ach = res["corr"]["gbps"]
             roof = dict(bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS)
-        roof["kernel"] = "corr_ws_kernel" if res["plan"].get("ws") else "corr_kernel"
+        roof["kernel"] = {0: "corr_kernel", 1: "corr_ws_kernel", 2: "corr_ws32_kernel"}[res["plan"].get("ws", 0)]
         roof["kernel_ms"] = res["corr"]["ms"]
     else:
         ach = res["probe"]["gbps"]

@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libxconv.so")
 OBJDIR = os.path.join(HERE, "_build")
-SOURCES = ["xconv_api.hip", "probe_kernels.hip", "corr_kernels.hip", "corr_ws_kernels.hip"]
+SOURCES = ["xconv_api.hip", "probe_kernels.hip", "corr_kernels.hip", "corr_ws_kernels.hip", "corr_ws32_kernels.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -47,4 +47,9 @@ bool plan_corr_ws(WsParams &P, int dtype, int B, int C_out, int H, int W, int kH
 size_t corr_ws_lds_bytes(const WsParams &P);
 hipError_t launch_corr_ws(int dtype, const WsParams &P, hipStream_t st);
 
+// corr_ws32_kernels.hip: the producer/consumer kernel for fp32 storage (same plan structure)
+bool plan_corr_ws32(WsParams &P, int dtype, int B, int C_out, int H, int W, int kH, int kW, int sh, int sw, int ph, int pw, int CS);
+size_t corr_ws32_lds_bytes(const WsParams &P);
+hipError_t launch_corr_ws32(const WsParams &P, hipStream_t st);
+
 }  // namespace xc

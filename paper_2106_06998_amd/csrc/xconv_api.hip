@@ -70,8 +70,8 @@ struct PlanKey {
 struct PlanEntry {
     PlanKey key;
     CorrParams P;   // launch plan of corr_kernel; with `ws` only the fields the reduction and expansion read
-    WsParams Wp;    // launch plan of corr_ws_kernel when `ws`
-    bool ws;
+    WsParams Wp;    // launch plan of corr_ws_kernel (ws == 1, 16-bit storage) or corr_ws32_kernel (ws == 2, fp32)
+    int ws;
     bool ok;
 };
 std::mutex g_plan_mu;
@@ -94,7 +94,8 @@ bool get_plan(PlanEntry &out, int dtype, int B, int C_out, int H, int W, int kH,
     e.P = CorrParams{};
     e.Wp = WsParams{};
     // the producer/consumer kernel reads dY in place, so the caller's planes must be usable as they are
-    e.ws = dy_aligned && plan_corr_ws(e.Wp, dtype, B, C_out, H, W, kH, kW, sh, sw, ph, pw, CS);
+    e.ws = (dy_aligned && plan_corr_ws(e.Wp, dtype, B, C_out, H, W, kH, kW, sh, sw, ph, pw, CS)) ? 1 : 0;
+    if (!e.ws && dy_aligned && plan_corr_ws32(e.Wp, dtype, B, C_out, H, W, kH, kW, sh, sw, ph, pw, CS)) e.ws = 2;
     if (e.ws) {
         e.ok = true;
         e.P.C_out = C_out;
@@ -281,7 +282,7 @@ xconv_status xconv_dw_estimate(const xconv_desc *d, const void *dY_dev, const vo
         E.Wp.dY = P.dY;
         E.Wp.A = Xt_dev;
         E.Wp.part = P.part;
-        XC_LAUNCH(K_CORR, st, launch_corr_ws(d->dtype, E.Wp, st));
+        XC_LAUNCH(K_CORR, st, E.ws == 2 ? launch_corr_ws32(E.Wp, st) : launch_corr_ws(d->dtype, E.Wp, st));
     } else {
         XC_LAUNCH(K_CORR, st, launch_corr(d->dtype, P, st));
     }
@@ -333,7 +334,7 @@ xconv_status xconv_dw_exact(const xconv_desc *d, const void *dY_dev, const void 
         E.Wp.dY = P.dY;
         E.Wp.A = A;
         E.Wp.part = P.part;
-        XC_LAUNCH(K_CORR, st, launch_corr_ws(d->dtype, E.Wp, st));
+        XC_LAUNCH(K_CORR, st, E.ws == 2 ? launch_corr_ws32(E.Wp, st) : launch_corr_ws(d->dtype, E.Wp, st));
     } else {
         XC_LAUNCH(K_CORR, st, launch_corr(d->dtype, P, st));
     }
@@ -353,8 +354,8 @@ xconv_status xconv_plan_info(const xconv_desc *d, int op, int32_t *out)
         return XCONV_EUNSUPPORTED;
     if (E.ws) {
         const WsParams &Q = E.Wp;
-        const int32_t v[16] = {Q.S, Q.NS, 1, Q.CW, Q.WM, Q.WJ, 1, Q.M_WG, Q.J_WG, (int32_t)corr_ws_lds_bytes(Q),
-                               Q.NTM, Q.NTJ, Q.NOG, Q.CS, Q.NSUB, 1};
+        const int32_t v[16] = {Q.S, Q.NS, 1, Q.CW, Q.WM, Q.WJ, 1, Q.M_WG, Q.J_WG, (int32_t)(E.ws == 2 ? corr_ws32_lds_bytes(Q) : corr_ws_lds_bytes(Q)),
+                               Q.NTM, Q.NTJ, Q.NOG, Q.CS, Q.NSUB, E.ws};
         for (int i = 0; i < 16; ++i) out[i] = v[i];
         return XCONV_OK;
     }

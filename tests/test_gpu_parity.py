@@ -232,6 +232,37 @@ def test_producer_consumer_kernel_shapes(e):
     run_edge(e)
 
 
+# fp32 producer/consumer kernel: plans with one and with two workgroups per compute unit, strips
+# with a narrower last strip, several image groups with a partial last one, strides, 5x5 (three
+# offset groups), output channels beyond the tile, wide A (the exact path), several steps per
+# workgroup across image-group boundaries.
+WS32_EDGE = [
+    ("ws32-b5-c24", 5, 24, 24, 16, 16, 3, 1, 1, 8, "rademacher", "f32"),
+    ("ws32-strips", 3, 16, 40, 12, 40, 3, 1, 1, 16, "gaussian", "f32"),
+    ("ws32-stride2", 6, 32, 48, 17, 15, 3, 2, 1, 16, "rademacher", "f32"),
+    ("ws32-k5", 4, 16, 16, 12, 12, 5, 1, 2, 8, "gaussian", "f32"),
+    ("ws32-r40", 9, 48, 72, 10, 12, 3, 1, 1, 40, "rademacher", "f32"),
+    ("ws32-k1x3", 4, 16, 32, 9, 12, (1, 3), 1, (0, 1), 16, "rademacher", "f32"),
+    ("ws32-k3-s3", 5, 16, 16, 24, 24, 3, 3, 0, 8, "rademacher", "f32"),
+]
+
+
+@pytest.mark.parametrize("e", WS32_EDGE, ids=[e[0] for e in WS32_EDGE])
+@pytest.mark.parametrize("occ", ["1", "2"], ids=["one-wg-per-cu", "two-wg-per-cu"])
+def test_fp32_producer_consumer_kernel_shapes(e, occ, monkeypatch):
+    monkeypatch.setenv("XCONV_WS32_OCC", occ)
+    name, B, C_in, C_out, H, W, k, stride, pad, r, probe, dtype = e
+    d = xb.make_desc(B, C_in, C_out, H, W, k, stride, pad, r, dtype, probe, 13)
+    assert xb.xconv_plan_info(d, xb.XCONV_OP_ESTIMATE)["ws"] == 2
+    run_edge(e)
+
+
+def test_fp32_producer_consumer_kernel_runs_across_image_groups(monkeypatch):
+    # few workgroups: each walks through many steps, whole runs and image-group boundaries
+    monkeypatch.setenv("XCONV_WS32_SPLITS", "3")
+    run_edge(("ws32-runs", 11, 16, 16, 8, 8, 3, 1, 1, 8, "rademacher", "f32"))
+
+
 def test_producer_consumer_kernel_is_deterministic():
     say("determinism, producer/consumer kernel")
     e = WS_EDGE[1]
