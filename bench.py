@@ -27,8 +27,8 @@ PEAK_MFMA_TFLOPS = {"f32": 157.3, "bf16": 2500.0, "f16": 2500.0}
 # (FETCH_SIZE, WRITE_SIZE scaled by a copy kernel of known size; see
 # profiles/).  bytes, or None where not measured yet.
 MEASURED_TRAFFIC = {
-    ("C2", "corr_kernel"): 62.6e6, ("C2", "probe_kernel"): 42.1e6,       # profiles/xconv_kernels_C2.txt
-    ("C5", "corr_ws_kernel"): 202.7e6, ("C5", "probe_kernel"): 154.3e6,  # profiles/xconv_kernels_C5.txt
+    ("C2", "corr_ws32_kernel"): 64.7e6, ("C2", "probe_kernel"): 42.1e6,  # profiles/xconv_kernels_C2.txt
+    ("C5", "corr_ws_kernel"): 202.5e6, ("C5", "probe_kernel"): 154.3e6,  # profiles/xconv_kernels_C5.txt
 }
 
 
