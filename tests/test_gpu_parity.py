@@ -483,3 +483,73 @@ def test_full_size_sampled(name):
         G = Z.astype(np.float64) @ Z.astype(np.float64).T / cfg.r
         mixed = np.einsum("nq,mqyx->mnyx", G, got_x)
         assert rel_max(got, mixed) <= 2 * GRAD_TOL[cfg.dtype]
+
+
+# ---------------------------------------------------------------------------
+# seeded random shapes: every kernel choice the plans can make (generic, 16-bit and fp32
+# producer/consumer kernels, strips, partial image groups, offset groups, both layouts, sparse
+# probes) against the oracle
+# ---------------------------------------------------------------------------
+def _random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        dtype = ["f32", "bf16", "f16"][rng.integers(3)]
+        k = [1, 2, 3, 3, 3, 5][rng.integers(6)]
+        kH, kW = (k, k) if rng.random() < 0.8 else (k, [1, 3][rng.integers(2)])
+        sh = [1, 1, 2, 3][rng.integers(4)]
+        sw = sh if rng.random() < 0.8 else [1, 2][rng.integers(2)]
+        ph, pw = int(rng.integers(0, kH // 2 + 2)), int(rng.integers(0, kW // 2 + 2))
+        H, W = int(rng.integers(kH + 1, 30)), int(rng.integers(kW + 1, 44))
+        if rng.random() < 0.5:
+            W = (W + 3) // 4 * 4
+        if (H + 2 * ph - kH) // sh + 1 < 1 or (W + 2 * pw - kW) // sw + 1 < 1:
+            continue
+        B = int(rng.integers(1, 20))
+        C_in = int([4, 8, 16, 24, 32, 40, 64, 72][rng.integers(8)])
+        C_out = int([8, 16, 24, 32, 48, 64, 96, 136][rng.integers(8)])
+        r = int([1, 4, 8, 16, 20, 32, 64][rng.integers(7)])
+        probe = ["rademacher", "gaussian"][rng.integers(2)]
+        nhwc = bool(rng.random() < 0.3)
+        keep = int([0, 0, 0, 12000, 24000][rng.integers(5)])
+        if B * C_out * H * W * C_in > 6e7:      # keep the oracle quick
+            continue
+        out.append((len(out), B, C_in, C_out, H, W, (kH, kW), (sh, sw), (ph, pw), r, probe, dtype, nhwc, keep))
+    return out
+
+
+RANDOM_CASES = _random_cases(48, 20240607)
+
+
+@pytest.mark.parametrize("case", RANDOM_CASES, ids=["rnd%02d-%s" % (c[0], c[11]) for c in RANDOM_CASES])
+def test_random_shapes(case):
+    idx, B, C_in, C_out, H, W, (kH, kW), (sh, sw), (ph, pw), r, probe, dtype, nhwc, keep = case
+    say("random case %d: B%d C%d->%d %dx%d k%dx%d s%d,%d p%d,%d r%d %s %s %s keep=%d" % (
+        idx, B, C_in, C_out, H, W, kH, kW, sh, sw, ph, pw, r, probe, dtype, "NHWC" if nhwc else "NCHW", keep))
+    Ho, Wo = xo.out_extent(H, kH, sh, ph), xo.out_extent(W, kW, sw, pw)
+    X = synth.draw((B, C_in, H, W), 6000 + idx, "relu_normal", 1.0, dtype)
+    dY = synth.draw((B, C_out, Ho, Wo), 7000 + idx, "normal", 1e-2, dtype)
+    Z = xo.probe_matrix(OPROBE[probe], 8000 + idx, C_in, r, keep)
+    d = xb.make_desc(B, C_in, C_out, H, W, (kH, kW), (sh, sw), (ph, pw), r, dtype, probe, 8000 + idx,
+                     layout=xb.XCONV_NHWC if nhwc else xb.XCONV_NCHW, keep_q15=keep)
+    if nhwc:
+        Xd = xb.to_device(np.ascontiguousarray(X.transpose(0, 2, 3, 1)), dtype, DEV)
+        dYd = xb.to_device(np.ascontiguousarray(dY.transpose(0, 2, 3, 1)), dtype, DEV)
+    else:
+        Xd, dYd = xb.to_device(X, dtype, DEV), xb.to_device(dY, dtype, DEV)
+    # Z from the seed on the device: Rademacher is bit-identical to the oracle's, Gaussian to an ulp
+    Xt = xb.alloc_xt(d, DEV)
+    xb.xconv_probe_fwd(d, Xd, Xt, None, xb.alloc_ws(d, xb.XCONV_OP_PROBE, DEV))
+    dW = torch.full((C_out, C_in, kH, kW), float("nan"), dtype=torch.float32, device=DEV)
+    xb.xconv_dw_estimate(d, dYd, Xt, None, dW, xb.alloc_ws(d, xb.XCONV_OP_ESTIMATE, DEV))
+    dWx = torch.full((C_out, C_in, kH, kW), float("nan"), dtype=torch.float32, device=DEV)
+    xb.xconv_dw_exact(d, dYd, Xd, dWx, xb.alloc_ws(d, xb.XCONV_OP_EXACT, DEV))
+    torch.cuda.synchronize()
+    Xt_o = xo.probe_fwd(X, Z, ODT[dtype])
+    want = xo.dw_from_xt(dY, Xt_o, Z, kH, kW, (sh, sw), (ph, pw), nnz_norm=keep != 0)
+    got = dW.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(got))
+    scale = max(np.max(np.abs(want)), 1e-30)
+    assert np.max(np.abs(got - want)) / scale <= GRAD_TOL[dtype], xb.xconv_plan_info(d, xb.XCONV_OP_ESTIMATE)
+    want_x = xo.dw_exact(dY, X, kH, kW, (sh, sw), (ph, pw))
+    assert rel_max(dWx.cpu().numpy().astype(np.float64), want_x) <= GRAD_TOL[dtype], xb.xconv_plan_info(d, xb.XCONV_OP_EXACT)
