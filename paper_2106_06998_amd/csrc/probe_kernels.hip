@@ -110,7 +110,7 @@ __global__ __launch_bounds__(kThreads) void pack_z_16_kernel(const float *__rest
 // MFMA u uses element u of every lane (see f32_frag_channel), and the wave's tile is four
 // sub-tiles of 16 pixels; `ngroups` is the number of pixels.
 template <int JT, bool NHWC>
-__global__ __launch_bounds__(kThreads) void probe_f32_kernel(const float *__restrict__ X, const float *__restrict__ Z,
+__global__ __launch_bounds__(kThreads, (JT == 1 ? 4 : 2)) void probe_f32_kernel(const float *__restrict__ X, const float *__restrict__ Z,
                                                              const float *__restrict__ zpack, float *__restrict__ Xt, int C_in,
                                                              int HW, int r, int CS, int j0, long long ngroups, int ntiles)
 {
@@ -118,66 +118,96 @@ __global__ __launch_bounds__(kThreads) void probe_f32_kernel(const float *__rest
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int KQ4 = ((C_in + 15) >> 4) << 2;
     const int nfrag = KQ4 * JT * 64;
-    if (zpack) {
-        for (int e = tid; e < nfrag / 4; e += kThreads)
-            reinterpret_cast<float4 *>(zs)[e] = reinterpret_cast<const float4 *>(zpack)[e];
-    } else {
-        for (int e = tid; e < nfrag; e += kThreads) {
-            const int l = e & 63, jt = (e >> 6) % JT, kq = (e >> 6) / JT;
-            const int c = f32_frag_channel(kq, l >> 4, NHWC);
-            const int j = j0 + jmap(jt, l & 15, JT);
-            zs[e] = (c < C_in && j < r) ? Z[(size_t)c * r + j] : 0.0f;
+    auto stage_z = [&]() {
+        if (zpack) {
+            for (int e = tid; e < nfrag / 4; e += kThreads)
+                reinterpret_cast<float4 *>(zs)[e] = reinterpret_cast<const float4 *>(zpack)[e];
+        } else {
+            for (int e = tid; e < nfrag; e += kThreads) {
+                const int l = e & 63, jt = (e >> 6) % JT, kq = (e >> 6) / JT;
+                const int c = f32_frag_channel(kq, l >> 4, NHWC);
+                const int j = j0 + jmap(jt, l & 15, JT);
+                zs[e] = (c < C_in && j < r) ? Z[(size_t)c * r + j] : 0.0f;
+            }
         }
-    }
-    __syncthreads();
+    };
 
+    constexpr int D = JT == 1 ? 3 : 4;  // groups of 16 channels a wave keeps in flight (16 registers each)
+    constexpr int NP = NHWC ? 4 : 1;
     const int n = lane & 15, g = lane >> 4;
     const long long last_group = ngroups - 1;
-    for (int tile = blockIdx.x * 4 + wave; tile < ntiles; tile += gridDim.x * 4) {
+    const int KK = (C_in + 15) >> 4;
+
+    // pixel (or group of 4 pixels) of this lane; lanes past the end redo the last one and store nothing
+    struct Tile {
+        const float *xb[NP];
+        long long first[NP];
+        bool valid[NP];
+    };
+    auto locate = [&](Tile &tl, int tile) {
+        if constexpr (NHWC) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const long long pp = (long long)tile * 64 + 16 * t + n;
+                tl.valid[t] = pp < ngroups;
+                tl.first[t] = tl.valid[t] ? pp : last_group;
+                tl.xb[t] = X + (size_t)tl.first[t] * C_in;
+            }
+        } else {
+            const long long pg_raw = (long long)tile * 16 + n;
+            tl.valid[0] = pg_raw < ngroups;
+            tl.first[0] = (tl.valid[0] ? pg_raw : last_group) * 4;
+            tl.xb[0] = X + (size_t)(tl.first[0] / HW) * C_in * HW + (int)(tl.first[0] % HW);
+        }
+    };
+    // Channels past the end re-read the last channels against zero fragment entries.
+    struct Staged {
+        float4 v[4];
+    };
+    auto load16 = [&](Staged &sg, const Tile &tl, int kk) {
+        const int c0 = kk * 16;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if constexpr (NHWC) {
+                int c = c0 + 4 * g;
+                c = c < C_in ? c : C_in - 4;
+                sg.v[u] = *reinterpret_cast<const float4 *>(tl.xb[u] + c);
+            } else {
+                int c = c0 + 4 * u + g;
+                c = c < C_in ? c : C_in - 1;
+                sg.v[u] = *reinterpret_cast<const float4 *>(tl.xb[0] + (size_t)c * HW);
+            }
+        }
+    };
+    auto prefetch = [&](Staged (&rg)[D], const Tile &tl) {
+#pragma unroll
+        for (int d = 0; d < D; ++d)
+            if (d < KK) load16(rg[d], tl, d);
+    };
+
+    // The first tile's loads are in flight while the Z fragments are staged.
+    int tile = blockIdx.x * 4 + wave;
+    const int tile_step = gridDim.x * 4;
+    Tile cur;
+    Staged rg[D];
+    if (tile < ntiles) {
+        locate(cur, tile);
+        prefetch(rg, cur);
+    }
+    stage_z();
+    __syncthreads();
+
+    while (tile < ntiles) {
         f32x4 acc[JT][4];
 #pragma unroll
         for (int jt = 0; jt < JT; ++jt)
 #pragma unroll
             for (int t = 0; t < 4; ++t) acc[jt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-        // pixel (or group of 4 pixels) of this lane; lanes past the end redo the last one and store nothing
-        const float *xb[NHWC ? 4 : 1];
-        long long first[NHWC ? 4 : 1];
-        bool valid[NHWC ? 4 : 1];
-        if constexpr (NHWC) {
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const long long pp = (long long)tile * 64 + 16 * t + n;
-                valid[t] = pp < ngroups;
-                first[t] = valid[t] ? pp : last_group;
-                xb[t] = X + (size_t)first[t] * C_in;
-            }
-        } else {
-            const long long pg_raw = (long long)tile * 16 + n;
-            valid[0] = pg_raw < ngroups;
-            first[0] = (valid[0] ? pg_raw : last_group) * 4;
-            xb[0] = X + (size_t)(first[0] / HW) * C_in * HW + (int)(first[0] % HW);
-        }
-
-        // Loads are unconditional (channels past the end re-read the last channels against zero
-        // fragment entries), so the next 16 channels are fetched while these are multiplied.
-        auto load16 = [&](float4 (&v)[4], int c0) {
+        auto process = [&](const Staged &sg, int kk) {
+            const float4(&v)[4] = sg.v;
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                if constexpr (NHWC) {
-                    int c = c0 + 4 * g;
-                    c = c < C_in ? c : C_in - 4;
-                    v[u] = *reinterpret_cast<const float4 *>(xb[u] + c);
-                } else {
-                    int c = c0 + 4 * u + g;
-                    c = c < C_in ? c : C_in - 1;
-                    v[u] = *reinterpret_cast<const float4 *>(xb[0] + (size_t)c * HW);
-                }
-            }
-        };
-        auto process = [&](const float4 (&v)[4], int c0) {
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int kq = (c0 >> 2) + u;
+                const int kq = kk * 4 + u;
 #pragma unroll
                 for (int jt = 0; jt < JT; ++jt) {
                     const float a = zs[(kq * JT + jt) * 64 + lane];
@@ -200,27 +230,30 @@ __global__ __launch_bounds__(kThreads) void probe_f32_kernel(const float *__rest
                 }
             }
         };
-        float4 v0[4], v1[4];
-        load16(v0, 0);
-        int c0 = 0;
-        for (; c0 + 32 < C_in; c0 += 32) {  // both fetches of a trip are needed ones
-            load16(v1, c0 + 16);
-            process(v0, c0);
-            load16(v0, c0 + 32);
-            process(v1, c0 + 16);
+        int kk = 0;
+        for (; kk + D <= KK; kk += D) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                process(rg[d], kk + d);
+                if (kk + d + D < KK) load16(rg[d], cur, kk + d + D);
+            }
         }
-        if (c0 + 16 < C_in) {
-            load16(v1, c0 + 16);
-            process(v0, c0);
-            process(v1, c0 + 16);
-        } else {
-            process(v0, c0);
+#pragma unroll
+        for (int d = 0; d < D - 1; ++d)
+            if (kk + d < KK) process(rg[d], kk + d);
+
+        // the next tile's first loads go out before this tile's stores
+        const Tile done = cur;
+        tile += tile_step;
+        if (tile < ntiles) {
+            locate(cur, tile);
+            prefetch(rg, cur);
         }
         // lane (n, g) holds rows 4g..4g+3 of every tile = probe columns j0 + g*4*JT + jt*4 + v
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            if (!valid[NHWC ? t : 0]) continue;
-            float *out = Xt + (size_t)(NHWC ? first[NHWC ? t : 0] : first[0] + t) * CS + j0 + g * (4 * JT);
+            if (!done.valid[NHWC ? t : 0]) continue;
+            float *out = Xt + (size_t)(NHWC ? done.first[NHWC ? t : 0] : done.first[0] + t) * CS + j0 + g * (4 * JT);
 #pragma unroll
             for (int jt = 0; jt < JT; ++jt) *reinterpret_cast<f32x4 *>(out + jt * 4) = acc[jt][t];
         }
@@ -238,7 +271,7 @@ __global__ __launch_bounds__(kThreads) void probe_f32_kernel(const float *__rest
 // NHWC: X is [pixels, C_in]; the 8 channels a lane supplies are then one 16-byte load, no
 // transpose; the wave's tile is PT sub-tiles of 16 pixels and `ngroups` is the number of pixels.
 template <int DT, int JT, int PT, bool SPLIT, bool NHWC>
-__global__ __launch_bounds__(kThreads) void probe_16_kernel(const uint16_t *__restrict__ X, const float *__restrict__ Z,
+__global__ __launch_bounds__(kThreads, 2) void probe_16_kernel(const uint16_t *__restrict__ X, const float *__restrict__ Z,
                                                             const uint4 *__restrict__ zpack, uint16_t *__restrict__ Xt, int C_in,
                                                             int HW, int r, int CS, int j0, long long ngroups, int ntiles)
 {
@@ -246,103 +279,127 @@ __global__ __launch_bounds__(kThreads) void probe_16_kernel(const uint16_t *__re
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int KK = (C_in + 31) >> 5;
     const int nfrag = KK * JT * 64;
-    if (zpack) {
-        for (int e = tid; e < nfrag * (SPLIT ? 2 : 1); e += kThreads) zf[e] = zpack[e];
-    } else {
-        // Z fragments: four entries (32 scalar loads) per thread in flight at a time
-        for (int base = 0; base < nfrag; base += 4 * kThreads) {
-            float z[4][8];
+    auto stage_z = [&]() {
+        if (zpack) {
+            for (int e = tid; e < nfrag * (SPLIT ? 2 : 1); e += kThreads) zf[e] = zpack[e];
+        } else {
+            // Z fragments: four entries (32 scalar loads) per thread in flight at a time
+            for (int base = 0; base < nfrag; base += 4 * kThreads) {
+                float z[4][8];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int e = base + k * kThreads + tid;
-                const int l = e & 63, jt = (e >> 6) % JT, kk = (e >> 6) / JT;
-                const int j = j0 + jmap(jt, l & 15, JT);
+                for (int k = 0; k < 4; ++k) {
+                    const int e = base + k * kThreads + tid;
+                    const int l = e & 63, jt = (e >> 6) % JT, kk = (e >> 6) / JT;
+                    const int j = j0 + jmap(jt, l & 15, JT);
 #pragma unroll
-                for (int q = 0; q < 8; ++q) {
-                    const int c = kk * 32 + 8 * (l >> 4) + q;
-                    z[k][q] = (e < nfrag && c < C_in && j < r) ? Z[(size_t)c * r + j] : 0.0f;
-                }
-            }
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int e = base + k * kThreads + tid;
-                uint32_t hi[4], lo[4];
-#pragma unroll
-                for (int q = 0; q < 8; q += 2) {
-                    const uint16_t h0 = f32_to_st16<DT>(z[k][q]), h1 = f32_to_st16<DT>(z[k][q + 1]);
-                    hi[q >> 1] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-                    if constexpr (SPLIT) {
-                        const uint16_t w0 = f32_to_st16<DT>(z[k][q] - st16_to_f32<DT>(h0));
-                        const uint16_t w1 = f32_to_st16<DT>(z[k][q + 1] - st16_to_f32<DT>(h1));
-                        lo[q >> 1] = (uint32_t)w0 | ((uint32_t)w1 << 16);
+                    for (int q = 0; q < 8; ++q) {
+                        const int c = kk * 32 + 8 * (l >> 4) + q;
+                        z[k][q] = (e < nfrag && c < C_in && j < r) ? Z[(size_t)c * r + j] : 0.0f;
                     }
                 }
-                if (e < nfrag) {
-                    zf[e] = uint4{hi[0], hi[1], hi[2], hi[3]};
-                    if constexpr (SPLIT) zf[nfrag + e] = uint4{lo[0], lo[1], lo[2], lo[3]};
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int e = base + k * kThreads + tid;
+                    uint32_t hi[4], lo[4];
+#pragma unroll
+                    for (int q = 0; q < 8; q += 2) {
+                        const uint16_t h0 = f32_to_st16<DT>(z[k][q]), h1 = f32_to_st16<DT>(z[k][q + 1]);
+                        hi[q >> 1] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+                        if constexpr (SPLIT) {
+                            const uint16_t w0 = f32_to_st16<DT>(z[k][q] - st16_to_f32<DT>(h0));
+                            const uint16_t w1 = f32_to_st16<DT>(z[k][q + 1] - st16_to_f32<DT>(h1));
+                            lo[q >> 1] = (uint32_t)w0 | ((uint32_t)w1 << 16);
+                        }
+                    }
+                    if (e < nfrag) {
+                        zf[e] = uint4{hi[0], hi[1], hi[2], hi[3]};
+                        if constexpr (SPLIT) zf[nfrag + e] = uint4{lo[0], lo[1], lo[2], lo[3]};
+                    }
                 }
             }
         }
-    }
-    __syncthreads();
+    };
 
     constexpr int NW = PT / 2;
+    // K-steps of loads a wave keeps in flight (16 or 32 registers each)
+    constexpr int D = (!NHWC && PT == 8) ? 2 : 4;
+    constexpr int NP = NHWC ? PT : 1;
     const int n = lane & 15, g = lane >> 4;
     const long long last_group = ngroups - 1;
-    for (int tile = blockIdx.x * 4 + wave; tile < ntiles; tile += gridDim.x * 4) {
+
+    // pixel (NHWC) or group of PT pixels (NCHW) of this lane; lanes past the end redo the last one and store nothing
+    struct Tile {
+        const uint16_t *xb[NP];
+        long long first[NP];
+        bool valid[NP];
+    };
+    auto locate = [&](Tile &tl, int tile) {
+        if constexpr (NHWC) {
+#pragma unroll
+            for (int t = 0; t < PT; ++t) {
+                const long long pp = (long long)tile * (16 * PT) + 16 * t + n;
+                tl.valid[t] = pp < ngroups;
+                tl.first[t] = tl.valid[t] ? pp : last_group;
+                tl.xb[t] = X + (size_t)tl.first[t] * C_in;
+            }
+        } else {
+            const long long pg_raw = (long long)tile * 16 + n;
+            tl.valid[0] = pg_raw < ngroups;
+            tl.first[0] = (tl.valid[0] ? pg_raw : last_group) * PT;
+            tl.xb[0] = X + (size_t)(tl.first[0] / HW) * C_in * HW + (int)(tl.first[0] % HW);
+        }
+    };
+    // MFMA operands of one K-step: cols[t] = the 8 channels 32kk + 8g .. +7 of pixel t.
+    // Channels past the end re-read the last channels, whose Z fragment entries are zero.
+    struct Staged {
+        uint32_t rows[NHWC ? 1 : 8][NHWC ? 1 : NW];  // NCHW: 8 channel rows of PT pixels
+        uint4 cols[NHWC ? PT : 1];                   // NHWC: ready-made operands
+    };
+    auto load_step = [&](Staged &sg, const Tile &tl, int kk) {
+        if constexpr (NHWC) {
+            int c = kk * 32 + 8 * g;
+            c = c < C_in ? c : C_in - 8;
+#pragma unroll
+            for (int t = 0; t < PT; ++t) sg.cols[t] = *reinterpret_cast<const uint4 *>(tl.xb[t] + c);
+        } else {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                int c = kk * 32 + 8 * g + q;
+                c = c < C_in ? c : C_in - 1;
+                if constexpr (PT == 8) {
+                    const uint4 v = *reinterpret_cast<const uint4 *>(tl.xb[0] + (size_t)c * HW);
+                    sg.rows[q][0] = v.x; sg.rows[q][1] = v.y; sg.rows[q][2] = v.z; sg.rows[q][3] = v.w;
+                } else {
+                    const uint2 v = *reinterpret_cast<const uint2 *>(tl.xb[0] + (size_t)c * HW);
+                    sg.rows[q][0] = v.x; sg.rows[q][1] = v.y;
+                }
+            }
+        }
+    };
+    auto prefetch = [&](Staged (&rg)[D], const Tile &tl) {
+#pragma unroll
+        for (int d = 0; d < D; ++d)
+            if (d < KK) load_step(rg[d], tl, d);
+    };
+
+    // The first tile's loads are in flight while the Z fragments are staged.
+    int tile = blockIdx.x * 4 + wave;
+    const int tile_step = gridDim.x * 4;
+    Tile cur;
+    Staged rg[D];
+    if (tile < ntiles) {
+        locate(cur, tile);
+        prefetch(rg, cur);
+    }
+    stage_z();
+    __syncthreads();
+
+    while (tile < ntiles) {
         f32x4 acc[JT][PT];
 #pragma unroll
         for (int jt = 0; jt < JT; ++jt)
 #pragma unroll
             for (int t = 0; t < PT; ++t) acc[jt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-        // pixel (NHWC) or group of PT pixels (NCHW) of this lane; lanes past the end redo the last one and store nothing
-        constexpr int NP = NHWC ? PT : 1;
-        const uint16_t *xb[NP];
-        long long first[NP];
-        bool valid[NP];
-        if constexpr (NHWC) {
-#pragma unroll
-            for (int t = 0; t < PT; ++t) {
-                const long long pp = (long long)tile * (16 * PT) + 16 * t + n;
-                valid[t] = pp < ngroups;
-                first[t] = valid[t] ? pp : last_group;
-                xb[t] = X + (size_t)first[t] * C_in;
-            }
-        } else {
-            const long long pg_raw = (long long)tile * 16 + n;
-            valid[0] = pg_raw < ngroups;
-            first[0] = (valid[0] ? pg_raw : last_group) * PT;
-            xb[0] = X + (size_t)(first[0] / HW) * C_in * HW + (int)(first[0] % HW);
-        }
-
-        // MFMA operands of one K-step: cols[t] = the 8 channels 32kk + 8g .. +7 of pixel t.
-        // Loads are unconditional (channels past the end re-read the last channels, whose Z
-        // fragment entries are zero), so the next K-step can be prefetched without branches.
-        struct Staged {
-            uint32_t rows[NHWC ? 1 : 8][NHWC ? 1 : NW];  // NCHW: 8 channel rows of PT pixels
-            uint4 cols[NHWC ? PT : 1];                   // NHWC: ready-made operands
-        };
-        auto load_step = [&](Staged &sg, int kk) {
-            if constexpr (NHWC) {
-                int c = kk * 32 + 8 * g;
-                c = c < C_in ? c : C_in - 8;
-#pragma unroll
-                for (int t = 0; t < PT; ++t) sg.cols[t] = *reinterpret_cast<const uint4 *>(xb[t] + c);
-            } else {
-#pragma unroll
-                for (int q = 0; q < 8; ++q) {
-                    int c = kk * 32 + 8 * g + q;
-                    c = c < C_in ? c : C_in - 1;
-                    if constexpr (PT == 8) {
-                        const uint4 v = *reinterpret_cast<const uint4 *>(xb[0] + (size_t)c * HW);
-                        sg.rows[q][0] = v.x; sg.rows[q][1] = v.y; sg.rows[q][2] = v.z; sg.rows[q][3] = v.w;
-                    } else {
-                        const uint2 v = *reinterpret_cast<const uint2 *>(xb[0] + (size_t)c * HW);
-                        sg.rows[q][0] = v.x; sg.rows[q][1] = v.y;
-                    }
-                }
-            }
-        };
         auto process = [&](const Staged &sg, int kk) {
             uint4 cols[PT];
             if constexpr (NHWC) {
@@ -363,33 +420,36 @@ __global__ __launch_bounds__(kThreads) void probe_16_kernel(const uint16_t *__re
                 }
             }
         };
-        Staged r0, r1;
-        load_step(r0, 0);
         int kk = 0;
-        for (; kk + 2 < KK; kk += 2) {  // both fetches of a trip are needed ones
-            load_step(r1, kk + 1);
-            process(r0, kk);
-            load_step(r0, kk + 2);
-            process(r1, kk + 1);
+        for (; kk + D <= KK; kk += D) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                process(rg[d], kk + d);
+                if (kk + d + D < KK) load_step(rg[d], cur, kk + d + D);
+            }
         }
-        if (kk + 1 < KK) {
-            load_step(r1, kk + 1);
-            process(r0, kk);
-            process(r1, kk + 1);
-        } else {
-            process(r0, kk);
+#pragma unroll
+        for (int d = 0; d < D - 1; ++d)
+            if (kk + d < KK) process(rg[d], kk + d);
+
+        // the next tile's first loads go out before this tile's stores
+        const Tile done = cur;
+        tile += tile_step;
+        if (tile < ntiles) {
+            locate(cur, tile);
+            prefetch(rg, cur);
         }
         // lane (n, g) holds probe columns j0 + g*4*JT .. +4*JT-1 of pixel t: one run of 8*JT bytes
 #pragma unroll
         for (int t = 0; t < PT; ++t) {
-            if (!valid[NHWC ? t : 0]) continue;
+            if (!done.valid[NHWC ? t : 0]) continue;
             uint32_t w[2 * JT];
 #pragma unroll
             for (int jt = 0; jt < JT; ++jt) {
                 w[2 * jt] = (uint32_t)f32_to_st16<DT>(acc[jt][t][0]) | ((uint32_t)f32_to_st16<DT>(acc[jt][t][1]) << 16);
                 w[2 * jt + 1] = (uint32_t)f32_to_st16<DT>(acc[jt][t][2]) | ((uint32_t)f32_to_st16<DT>(acc[jt][t][3]) << 16);
             }
-            uint16_t *o = Xt + (size_t)(NHWC ? first[NHWC ? t : 0] : first[0] + t) * CS + j0 + g * (4 * JT);
+            uint16_t *o = Xt + (size_t)(NHWC ? done.first[NHWC ? t : 0] : done.first[0] + t) * CS + j0 + g * (4 * JT);
             if constexpr (JT % 2 == 0) {
 #pragma unroll
                 for (int k = 0; k < JT / 2; ++k)
@@ -615,10 +675,11 @@ static hipError_t launch_probe_16_jt(const uint16_t *X, const float *Z, const ui
         return launch_probe_16_cfg<DT, JT, 4, false, true>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, st);
     }
     // 8 pixels per lane when the accumulators stay small, 4 for wide probe blocks
-    const bool pt8 = (JT <= 2) && (HW % 8 == 0);
-    if (pt8) {
-        if (split) return launch_probe_16_cfg<DT, JT, 8, true, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, st);
-        return launch_probe_16_cfg<DT, JT, 8, false, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, st);
+    if constexpr (JT <= 2) {
+        if (HW % 8 == 0) {
+            if (split) return launch_probe_16_cfg<DT, JT, 8, true, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, st);
+            return launch_probe_16_cfg<DT, JT, 8, false, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, st);
+        }
     }
     if (split) return launch_probe_16_cfg<DT, JT, 4, true, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, st);
     return launch_probe_16_cfg<DT, JT, 4, false, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, st);
