@@ -144,6 +144,56 @@ xconv_status xconv_plan_info(const xconv_desc *desc, int op, int32_t *out);
 /* Test helper: writes the stored Xt as plain fp32 [B,r,H,W] into out_dev. */
 xconv_status xconv_xt_unpack(const xconv_desc *desc, const void *Xt_dev, float *out_dev, void *stream);
 
+/* ---- volumetric layers (3-D convolution) --------------------------------------
+ * The paper's implementations cover 2-D and 3-D convolutional layers (appendix
+ * "Implementation and code"; the experiment "Volumetric segmentation under
+ * finetuning" uses 3x3x3 kernels on 96^3 patches).  The estimator of Algorithm 1
+ * is the same with one more spatial axis:
+ *
+ *   Xt[b,j,z,y,x]     = sum_n Z[n,j] X[b,n,z,y,x]
+ *   G[m,j,kz,ky,kx]   = sum_{b,oz,oy,ox} dY[b,m,oz,oy,ox] Xt[b,j,oz+kz-pd, oy*sh+ky-ph, ox*sw+kx-pw]
+ *   dW[m,n,kz,ky,kx]  = (1/r) sum_j Z[n,j] G[m,j,kz,ky,kx]
+ *
+ * `l` states the layer in the plane (B, channels, H, W, kH, kW, strides, pads, r,
+ * dtype, probe, keep_q15, seed) exactly as for a 2-D layer; D, kD and pad_d add the
+ * depth axis.  Supported: depth stride 1 with 2*pad_d == kD-1 (output depth D' = D),
+ * l.layout == XCONV_NCHW, meaning X [B,C_in,D,H,W] and dY [B,C_out,D,H',W'];
+ * anything else is XCONV_EUNSUPPORTED.  dW is [C_out,C_in,kD,kH,kW] fp32.
+ * The conventions of the 2-D entry points (pointers, stream, status, alignment,
+ * determinism, Z_dev / seed handling) hold unchanged. */
+typedef struct xconv3d_desc {
+    xconv_desc l;
+    int32_t D, kD, pad_d;
+    int32_t reserved;        /* must be 0 */
+} xconv3d_desc;
+
+/* Host-only validation: `l` as xconv_check_desc; XCONV_EINVAL for D or kD < 1,
+ * pad_d < 0 or reserved != 0; XCONV_EUNSUPPORTED as stated above, for kD > 7 and for
+ * volumes of more than 2^28 voxels per channel. */
+xconv_status xconv3d_check_desc(const xconv3d_desc *desc);
+
+/* Bytes of the stored probe output (opaque layout: depth slices [H,W,r rounded up
+ * to 16] with pad_d zero slices between images) and of the scratch of
+ * XCONV_OP_PROBE / XCONV_OP_ESTIMATE; 0 for an invalid desc or another op.  The
+ * estimate's scratch includes a slice-major copy of dY (one extra read and write
+ * of dY). */
+size_t xconv3d_xt_bytes(const xconv3d_desc *desc);
+size_t xconv3d_workspace_bytes(const xconv3d_desc *desc, int op);
+
+/* Forward probe of a volumetric layer; arguments as xconv_probe_fwd. */
+xconv_status xconv3d_probe_fwd(const xconv3d_desc *desc, const void *X_dev, void *Xt_dev,
+                               const float *Z_dev, void *ws_dev, size_t ws_bytes, void *stream);
+
+/* Backward estimate of a volumetric layer; arguments as xconv_dw_estimate, ws_dev
+ * required.  Runs the 2-D correlation once per kernel-depth offset on the depth
+ * slices of all images, then one expansion over the kD*kH*kW offsets. */
+xconv_status xconv3d_dw_estimate(const xconv3d_desc *desc, const void *dY_dev, const void *Xt_dev,
+                                 const float *Z_dev, float *dW_dev,
+                                 void *ws_dev, size_t ws_bytes, void *stream);
+
+/* Test helper: writes the stored Xt as plain fp32 [B,r,D,H,W] into out_dev. */
+xconv_status xconv3d_xt_unpack(const xconv3d_desc *desc, const void *Xt_dev, float *out_dev, void *stream);
+
 /* Per-kernel timing with HIP events recorded on the launch stream.  While
  * enabled, every kernel the library enqueues is bracketed by two events.
  * xconv_prof_collect synchronises those events, writes up to `max` records

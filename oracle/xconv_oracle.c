@@ -295,6 +295,48 @@ void xo_dw_estimate(const float *dY, const float *X, const float *Z, double *dW,
     free(Xt);
 }
 
+/* ------------------------------------------------------------------------- */
+/* Volumetric layers: the same definitions with one more spatial axis (the    */
+/* paper's implementations cover 2-D and 3-D convolutions; the shift T_{k(i)} */
+/* of Eq. (1), (2) then runs over kD*kH*kW offsets).                           */
+/*   G[m,q,kz,ky,kx] = sum_{b,oz,oy,ox} dY[b,m,oz,oy,ox]                        */
+/*                        * A[b,q,oz*sd+kz-pd, oy*sh+ky-ph, ox*sw+kx-pw]        */
+/* dY: [B,C_out,D',H',W'], A: [B,Q,D,H,W], G: [C_out,Q,kD,kH,kW] (double).      */
+/* With A = X (Q = C_in) this is the exact gradient, Eq. (2)/(5).              */
+/* ------------------------------------------------------------------------- */
+void xo_correlate3d(const float *dY, const float *A, double *G,
+                    int B, int C_out, int Q, int D, int H, int W,
+                    int kD, int kH, int kW, int sd, int sh, int sw, int pd, int ph, int pw)
+{
+    int Do = xo_out_extent(D, kD, sd, pd);
+    int Ho = xo_out_extent(H, kH, sh, ph);
+    int Wo = xo_out_extent(W, kW, sw, pw);
+    for (int m = 0; m < C_out; ++m)
+      for (int q = 0; q < Q; ++q)
+        for (int kz = 0; kz < kD; ++kz)
+          for (int ky = 0; ky < kH; ++ky)
+            for (int kx = 0; kx < kW; ++kx) {
+                double s = 0.0;
+                for (int b = 0; b < B; ++b)
+                  for (int oz = 0; oz < Do; ++oz) {
+                      int iz = oz * sd + kz - pd;
+                      if (iz < 0 || iz >= D) continue;
+                      for (int oy = 0; oy < Ho; ++oy) {
+                          int iy = oy * sh + ky - ph;
+                          if (iy < 0 || iy >= H) continue;
+                          for (int ox = 0; ox < Wo; ++ox) {
+                              int ix = ox * sw + kx - pw;
+                              if (ix < 0 || ix >= W) continue;
+                              double g = dY[((((size_t)b * C_out + m) * Do + oz) * Ho + oy) * Wo + ox];
+                              double a = A[((((size_t)b * Q + q) * D + iz) * H + iy) * W + ix];
+                              s += g * a;
+                          }
+                      }
+                  }
+                G[((((size_t)m * Q + q) * kD + kz) * kH + ky) * kW + kx] = s;
+            }
+}
+
 /* ------------------------------------------------------------------------ */
 /* Selected entries of the estimate, for layers too large to do in full.     */
 /* idx[4*t..4*t+3] = (m, n, ky, kx); out[t] = dW_est[m,n,ky,kx].             */

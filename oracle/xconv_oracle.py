@@ -63,6 +63,8 @@ def lib():
         L.xo_dw_exact_at.restype = None
         L.xo_dw_exact_at.argtypes = [_c_f32p, _c_f32p, _c_i32p, ctypes.c_int, _c_f64p] + [ctypes.c_int] * 11
         L.xo_conv_fwd.restype = None
+        L.xo_correlate3d.restype = None
+        L.xo_correlate3d.argtypes = [_c_f32p, _c_f32p, _c_f64p] + [ctypes.c_int] * 15
         L.xo_conv_fwd.argtypes = [_c_f32p, _c_f64p, _c_f64p] + [ctypes.c_int] * 11
         _LIB = L
     return _LIB
@@ -223,3 +225,37 @@ def conv_fwd(X, Wt, stride=(1, 1), pad=(0, 0)):
     lib().xo_conv_fwd(Xp, Wp, Y.ctypes.data_as(_c_f64p), B, C_in, C_out, H, W,
                       kH, kW, stride[0], stride[1], pad[0], pad[1])
     return Y
+
+
+# ---- volumetric layers (one more spatial axis) ------------------------------------
+def probe_fwd3d(X, Z, dtype=F32):
+    """Xt[b,j,z,y,x] = sum_n Z[n,j] X[b,n,z,y,x]: the probe acts voxel by voxel, so the depth
+    axis is folded into the rows of the 2-D routine."""
+    X = np.asarray(X)
+    B, C_in, D, H, W = X.shape
+    return probe_fwd(X.reshape(B, C_in, D * H, W), Z, dtype).reshape(B, -1, D, H, W)
+
+
+def correlate3d(dY, A, k, stride=(1, 1, 1), pad=(0, 0, 0)):
+    dY, dYp = _f32(dY)
+    A, Ap = _f32(A)
+    B, C_out, Do, Ho, Wo = dY.shape
+    _, Q, D, H, W = A.shape
+    kD, kH, kW = k
+    assert (Do, Ho, Wo) == tuple(out_extent(n, kk, s, p) for n, kk, s, p in zip((D, H, W), k, stride, pad))
+    G = np.empty((C_out, Q, kD, kH, kW), dtype=np.float64)
+    lib().xo_correlate3d(dYp, Ap, G.ctypes.data_as(_c_f64p), B, C_out, Q, D, H, W, kD, kH, kW,
+                         stride[0], stride[1], stride[2], pad[0], pad[1], pad[2])
+    return G
+
+
+def dw_exact3d(dY, X, k, stride=(1, 1, 1), pad=(0, 0, 0)):
+    """Exact gradient of a 3-D layer (Eq. (2)/(5) with kD*kH*kW offsets), [C_out,C_in,kD,kH,kW]."""
+    return correlate3d(dY, X, k, stride, pad)
+
+
+def dw_from_xt3d(dY, Xt, Z, k, stride=(1, 1, 1), pad=(0, 0, 0), nnz_norm=False):
+    """Backward of Algorithm 1 for a 3-D layer from the stored probe output."""
+    G = correlate3d(dY, Xt, k, stride, pad)
+    C_out, r, kD, kH, kW = G.shape
+    return expand(G.reshape(C_out, r, kD * kH, kW), Z, nnz_norm).reshape(C_out, -1, kD, kH, kW)

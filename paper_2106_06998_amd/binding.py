@@ -30,6 +30,11 @@ class xconv_desc(ctypes.Structure):
                  "r", "dtype", "layout", "probe", "keep_q15")] + [("seed", ctypes.c_uint64)]
 
 
+class xconv3d_desc(ctypes.Structure):
+    _fields_ = [("l", xconv_desc), ("D", ctypes.c_int32), ("kD", ctypes.c_int32), ("pad_d", ctypes.c_int32),
+                ("reserved", ctypes.c_int32)]
+
+
 class XConvError(RuntimeError):
     def __init__(self, status, where):
         self.status = status
@@ -70,6 +75,19 @@ def lib():
         L.xconv_plan_info.argtypes = [P, i32, vp]
         L.xconv_xt_unpack.restype = i32
         L.xconv_xt_unpack.argtypes = [P, vp, vp, vp]
+        P3 = ctypes.POINTER(xconv3d_desc)
+        L.xconv3d_check_desc.restype = i32
+        L.xconv3d_check_desc.argtypes = [P3]
+        L.xconv3d_xt_bytes.restype = sz
+        L.xconv3d_xt_bytes.argtypes = [P3]
+        L.xconv3d_workspace_bytes.restype = sz
+        L.xconv3d_workspace_bytes.argtypes = [P3, i32]
+        L.xconv3d_probe_fwd.restype = i32
+        L.xconv3d_probe_fwd.argtypes = [P3, vp, vp, vp, vp, sz, vp]
+        L.xconv3d_dw_estimate.restype = i32
+        L.xconv3d_dw_estimate.argtypes = [P3, vp, vp, vp, vp, vp, sz, vp]
+        L.xconv3d_xt_unpack.restype = i32
+        L.xconv3d_xt_unpack.argtypes = [P3, vp, vp, vp]
         L.xconv_prof_enable.restype = None
         L.xconv_prof_enable.argtypes = [i32]
         L.xconv_prof_collect.restype = i32
@@ -176,6 +194,41 @@ def xconv_plan_info(desc, op):
 
 def xconv_xt_unpack(desc, Xt_dev, out_dev, stream=None):
     _check(lib().xconv_xt_unpack(ctypes.byref(desc), _ptr(Xt_dev), _ptr(out_dev), _stream(stream)), "xconv_xt_unpack")
+
+
+# ---- volumetric layers ---------------------------------------------------------
+def make_desc3d(B, C_in, C_out, D, H, W, k, stride=1, pad=0, r=1, dtype="f32", probe="rademacher", seed=0, keep_q15=0):
+    """k and pad are (depth, height, width) triples or one int for all three; stride is in-plane only."""
+    kD, kH, kW = (k, k, k) if isinstance(k, int) else k
+    pd, ph, pw = (pad, pad, pad) if isinstance(pad, int) else pad
+    return xconv3d_desc(make_desc(B, C_in, C_out, H, W, (kH, kW), stride, (ph, pw), r, dtype, probe, seed, XCONV_NCHW, keep_q15),
+                        D, kD, pd, 0)
+
+
+def xconv3d_check_desc(desc):
+    return int(lib().xconv3d_check_desc(ctypes.byref(desc)))
+
+
+def xconv3d_xt_bytes(desc):
+    return int(lib().xconv3d_xt_bytes(ctypes.byref(desc)))
+
+
+def xconv3d_workspace_bytes(desc, op):
+    return int(lib().xconv3d_workspace_bytes(ctypes.byref(desc), int(op)))
+
+
+def xconv3d_probe_fwd(desc, X_dev, Xt_dev, Z_dev=None, ws_dev=None, stream=None):
+    _check(lib().xconv3d_probe_fwd(ctypes.byref(desc), _ptr(X_dev), _ptr(Xt_dev), _ptr(Z_dev), _ptr(ws_dev),
+                                   _nbytes(ws_dev), _stream(stream)), "xconv3d_probe_fwd")
+
+
+def xconv3d_dw_estimate(desc, dY_dev, Xt_dev, Z_dev, dW_dev, ws_dev, stream=None):
+    _check(lib().xconv3d_dw_estimate(ctypes.byref(desc), _ptr(dY_dev), _ptr(Xt_dev), _ptr(Z_dev), _ptr(dW_dev),
+                                     _ptr(ws_dev), _nbytes(ws_dev), _stream(stream)), "xconv3d_dw_estimate")
+
+
+def xconv3d_xt_unpack(desc, Xt_dev, out_dev, stream=None):
+    _check(lib().xconv3d_xt_unpack(ctypes.byref(desc), _ptr(Xt_dev), _ptr(out_dev), _stream(stream)), "xconv3d_xt_unpack")
 
 
 def xconv_prof_enable(on):

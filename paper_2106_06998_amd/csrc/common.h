@@ -25,7 +25,8 @@ enum KernelId {
     K_EXPAND = 7,
     K_REPACK = 8,
     K_PACK_Z = 9,
-    K_COUNT = 10
+    K_ZERO_GAPS = 10,
+    K_COUNT = 11
 };
 
 __host__ __device__ inline int round_up(int a, int b) { return (a + b - 1) / b * b; }

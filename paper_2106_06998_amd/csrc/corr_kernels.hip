@@ -987,38 +987,40 @@ hipError_t launch_corr(int dtype, const CorrParams &P, hipStream_t st)
 
 static float *reduced_tile(const CorrParams &P) { return P.part + (size_t)P.S * P.K2 * P.JP * P.MP; }
 
-hipError_t launch_reduce(const CorrParams &P, hipStream_t st, float *Zout, int nz, int dist, uint64_t seed)
+hipError_t launch_reduce(const CorrParams &P, hipStream_t st, float *Zout, int nz, int dist, uint64_t seed, float *T)
 {
     const int E4 = (int)(((size_t)P.K2 * P.JP * P.MP) / 4);
     const int zblocks = Zout ? ceil_div(nz, kThreads) : 0;
     hipLaunchKernelGGL(reduce_partials_kernel, dim3(zblocks + ceil_div(E4, 16)), dim3(kThreads), 0, st,
-                       reinterpret_cast<const f32x4 *>(P.part), reinterpret_cast<f32x4 *>(reduced_tile(P)), P.S, E4, Zout, nz,
+                       reinterpret_cast<const f32x4 *>(P.part), reinterpret_cast<f32x4 *>(T ? T : reduced_tile(P)), P.S, E4, Zout, nz,
                        zblocks, dist, seed);
     return hipGetLastError();
 }
 
-hipError_t launch_expand(const CorrParams &P, const float *Z, float *dW, int C_in, int r, hipStream_t st, bool nnz_norm)
+hipError_t launch_expand(const CorrParams &P, const float *Z, float *dW, int C_in, int r, hipStream_t st, bool nnz_norm,
+                         const float *Tin, int K2in)
 {
     const int nn = nnz_norm ? 1 : 0;
+    const int K2 = K2in > 0 ? K2in : P.K2;
+    const float *T = Tin ? Tin : reduced_tile(P);
     if (Z) {
         // few tiles: split the offsets over more waves; many tiles: a lane writes whole runs of offsets
         const int NTM16 = ceil_div(P.C_out, 16), NTN = ceil_div(C_in, 16);
         const long long tiles = (long long)NTM16 * NTN;
-        int og = P.K2 == 1 ? 1 : (tiles * ceil_div(P.K2, 9) >= 2048 ? 9 : (tiles * ceil_div(P.K2, 3) >= 2048 ? 3 : 1));
+        int og = K2 == 1 ? 1 : (tiles * ceil_div(K2, 9) >= 2048 ? 9 : (tiles * ceil_div(K2, 3) >= 2048 ? 3 : 1));
         og = env_int("XCONV_EXPAND_OG", og);
-        const dim3 grid((unsigned)tiles, (unsigned)ceil_div(P.K2, og));
-        const float *T = reduced_tile(P);
+        const dim3 grid((unsigned)tiles, (unsigned)ceil_div(K2, og));
         if (og == 9)
-            hipLaunchKernelGGL(expand_kernel<9>, grid, dim3(64), 0, st, T, Z, dW, P.K2, P.JP, P.MP, P.C_out, C_in, r, NTN, nn);
+            hipLaunchKernelGGL(expand_kernel<9>, grid, dim3(64), 0, st, T, Z, dW, K2, P.JP, P.MP, P.C_out, C_in, r, NTN, nn);
         else if (og == 3)
-            hipLaunchKernelGGL(expand_kernel<3>, grid, dim3(64), 0, st, T, Z, dW, P.K2, P.JP, P.MP, P.C_out, C_in, r, NTN, nn);
+            hipLaunchKernelGGL(expand_kernel<3>, grid, dim3(64), 0, st, T, Z, dW, K2, P.JP, P.MP, P.C_out, C_in, r, NTN, nn);
         else
-            hipLaunchKernelGGL(expand_kernel<1>, dim3((unsigned)tiles, (unsigned)P.K2), dim3(64), 0, st, T, Z, dW, P.K2, P.JP, P.MP,
+            hipLaunchKernelGGL(expand_kernel<1>, dim3((unsigned)tiles, (unsigned)K2), dim3(64), 0, st, T, Z, dW, K2, P.JP, P.MP,
                                P.C_out, C_in, r, NTN, nn);
     } else {
-        const long long total = (long long)P.C_out * C_in * P.K2;
-        hipLaunchKernelGGL(untile_kernel, dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, st,
-                           reduced_tile(P), dW, P.K2, P.JP, P.MP, P.C_out, C_in);
+        const long long total = (long long)P.C_out * C_in * K2;
+        hipLaunchKernelGGL(untile_kernel, dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, st, T, dW, K2,
+                           P.JP, P.MP, P.C_out, C_in);
     }
     return hipGetLastError();
 }

@@ -12,10 +12,15 @@ bool probe_fast_path_ok(int dtype, int C_in, int HW, bool nhwc);
 size_t zpack_bytes(int dtype, int C_in, int r, bool z_exact16);
 hipError_t launch_pack_z(int dtype, const float *Z, void *out, int C_in, int r, bool z_exact16, int dist, uint64_t seed,
                          bool nhwc, hipStream_t st);
+// gap: pixels of Xt left free in front of every image (volumetric layers: the zero slices between images)
 hipError_t launch_probe(int dtype, const void *X, const float *Z, const void *zpack, void *Xt, int B, int C_in, int HW, int r,
-                        int CS, bool z_exact16, bool nhwc, hipStream_t st);
+                        int CS, bool z_exact16, bool nhwc, long long gap, hipStream_t st);
 hipError_t launch_probe_generic(int dtype, const void *X, const float *Z, void *Xt, int B, int C_in, int HW, int r, int CS,
-                                bool nhwc, hipStream_t st);
+                                bool nhwc, long long gap, hipStream_t st);
+// volumetric layers: zero slices of Xt (pd in front, pd behind each image's D slices, pd at the end) and
+// dY [B, C, D, n] -> slice-major planes [B*(D+pd), C, pitch] with zero slices behind every image
+hipError_t launch_zero_gap_slices(void *Xt, size_t slice_bytes, int B, int D, int pd, hipStream_t st);
+hipError_t launch_dy_slices(int dtype, const void *src, void *dst, int B, int C, int D, int pd, int n, int pitch, hipStream_t st);
 hipError_t launch_unpack(int dtype, const void *Xt, float *out, int B, int HW, int r, int CS, hipStream_t st);
 hipError_t launch_to_nhwc(int dtype, const void *X, void *out, int B, int C, int HW, int CS, hipStream_t st);
 // channels-last [B, HW, C] -> planes [B, C, pitch], zero tail
@@ -35,10 +40,14 @@ hipError_t launch_corr(int dtype, const CorrParams &P, hipStream_t st);
 hipError_t launch_repack_planes(int dtype, const void *src, void *dst, long long nplanes, int n, int pitch, hipStream_t st);
 // T[o,j,m] = sum_s part[s,o,j,m]; T lives behind the S partial buffers.  Zout != nullptr: the same
 // launch also draws Z[s] (nz = C_in * r entries) from (dist, seed) into Zout.
-hipError_t launch_reduce(const CorrParams &P, hipStream_t st, float *Zout = nullptr, int nz = 0, int dist = 0, uint64_t seed = 0);
+// T != nullptr: the reduced tile goes there instead.
+hipError_t launch_reduce(const CorrParams &P, hipStream_t st, float *Zout = nullptr, int nz = 0, int dist = 0, uint64_t seed = 0,
+                         float *T = nullptr);
 // dW[m,n,o] = (1/r) * sum_j Z[n,j] * T[o,j,m]   (Z != nullptr)
 // dW[m,n,o] = T[o,n,m]                          (Z == nullptr, exact path)
-hipError_t launch_expand(const CorrParams &P, const float *Z, float *dW, int C_in, int r, hipStream_t st, bool nnz_norm = false);
+// T != nullptr: K2 tiles [K2, JP, MP] are read from there (volumetric layers: kD * kH * kW offsets).
+hipError_t launch_expand(const CorrParams &P, const float *Z, float *dW, int C_in, int r, hipStream_t st, bool nnz_norm = false,
+                         const float *T = nullptr, int K2 = 0);
 
 
 // corr_ws_kernels.hip: producer/consumer variant for 16-bit storage.  plan_corr_ws returns

@@ -112,7 +112,8 @@ __global__ __launch_bounds__(kThreads) void pack_z_16_kernel(const float *__rest
 template <int JT, bool NHWC>
 __global__ __launch_bounds__(kThreads, (JT == 1 ? 4 : 2)) void probe_f32_kernel(const float *__restrict__ X, const float *__restrict__ Z,
                                                              const float *__restrict__ zpack, float *__restrict__ Xt, int C_in,
-                                                             int HW, int r, int CS, int j0, long long ngroups, int ntiles)
+                                                             int HW, int r, int CS, int j0, long long ngroups, int ntiles,
+                                                             long long gap)
 {
     extern __shared__ float zs[];  // [KQ4][JT][64] A-operand fragments, zero beyond C_in
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -142,6 +143,7 @@ __global__ __launch_bounds__(kThreads, (JT == 1 ? 4 : 2)) void probe_f32_kernel(
     struct Tile {
         const float *xb[NP];
         long long first[NP];
+        long long out[NP];  // pixel index in Xt: `gap` pixels are left free before every image
         bool valid[NP];
     };
     auto locate = [&](Tile &tl, int tile) {
@@ -152,12 +154,15 @@ __global__ __launch_bounds__(kThreads, (JT == 1 ? 4 : 2)) void probe_f32_kernel(
                 tl.valid[t] = pp < ngroups;
                 tl.first[t] = tl.valid[t] ? pp : last_group;
                 tl.xb[t] = X + (size_t)tl.first[t] * C_in;
+                tl.out[t] = tl.first[t] + (gap ? gap * (tl.first[t] / HW + 1) : 0);
             }
         } else {
             const long long pg_raw = (long long)tile * 16 + n;
             tl.valid[0] = pg_raw < ngroups;
             tl.first[0] = (tl.valid[0] ? pg_raw : last_group) * 4;
-            tl.xb[0] = X + (size_t)(tl.first[0] / HW) * C_in * HW + (int)(tl.first[0] % HW);
+            const long long img = tl.first[0] / HW;
+            tl.xb[0] = X + (size_t)img * C_in * HW + (int)(tl.first[0] % HW);
+            tl.out[0] = tl.first[0] + gap * (img + 1);
         }
     };
     // Channels past the end re-read the last channels against zero fragment entries.
@@ -253,7 +258,7 @@ __global__ __launch_bounds__(kThreads, (JT == 1 ? 4 : 2)) void probe_f32_kernel(
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             if (!done.valid[NHWC ? t : 0]) continue;
-            float *out = Xt + (size_t)(NHWC ? done.first[NHWC ? t : 0] : done.first[0] + t) * CS + j0 + g * (4 * JT);
+            float *out = Xt + (size_t)(NHWC ? done.out[NHWC ? t : 0] : done.out[0] + t) * CS + j0 + g * (4 * JT);
 #pragma unroll
             for (int jt = 0; jt < JT; ++jt) *reinterpret_cast<f32x4 *>(out + jt * 4) = acc[jt][t];
         }
@@ -273,7 +278,8 @@ __global__ __launch_bounds__(kThreads, (JT == 1 ? 4 : 2)) void probe_f32_kernel(
 template <int DT, int JT, int PT, bool SPLIT, bool NHWC>
 __global__ __launch_bounds__(kThreads, 2) void probe_16_kernel(const uint16_t *__restrict__ X, const float *__restrict__ Z,
                                                             const uint4 *__restrict__ zpack, uint16_t *__restrict__ Xt, int C_in,
-                                                            int HW, int r, int CS, int j0, long long ngroups, int ntiles)
+                                                            int HW, int r, int CS, int j0, long long ngroups, int ntiles,
+                                                            long long gap)
 {
     extern __shared__ uint4 zf[];  // [SPLIT?2:1][KK][JT][64] A-operand fragments
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -331,6 +337,7 @@ __global__ __launch_bounds__(kThreads, 2) void probe_16_kernel(const uint16_t *_
     struct Tile {
         const uint16_t *xb[NP];
         long long first[NP];
+        long long out[NP];  // pixel index in Xt: `gap` pixels are left free before every image
         bool valid[NP];
     };
     auto locate = [&](Tile &tl, int tile) {
@@ -341,12 +348,15 @@ __global__ __launch_bounds__(kThreads, 2) void probe_16_kernel(const uint16_t *_
                 tl.valid[t] = pp < ngroups;
                 tl.first[t] = tl.valid[t] ? pp : last_group;
                 tl.xb[t] = X + (size_t)tl.first[t] * C_in;
+                tl.out[t] = tl.first[t] + (gap ? gap * (tl.first[t] / HW + 1) : 0);
             }
         } else {
             const long long pg_raw = (long long)tile * 16 + n;
             tl.valid[0] = pg_raw < ngroups;
             tl.first[0] = (tl.valid[0] ? pg_raw : last_group) * PT;
-            tl.xb[0] = X + (size_t)(tl.first[0] / HW) * C_in * HW + (int)(tl.first[0] % HW);
+            const long long img = tl.first[0] / HW;
+            tl.xb[0] = X + (size_t)img * C_in * HW + (int)(tl.first[0] % HW);
+            tl.out[0] = tl.first[0] + gap * (img + 1);
         }
     };
     // MFMA operands of one K-step: cols[t] = the 8 channels 32kk + 8g .. +7 of pixel t.
@@ -449,7 +459,7 @@ __global__ __launch_bounds__(kThreads, 2) void probe_16_kernel(const uint16_t *_
                 w[2 * jt] = (uint32_t)f32_to_st16<DT>(acc[jt][t][0]) | ((uint32_t)f32_to_st16<DT>(acc[jt][t][1]) << 16);
                 w[2 * jt + 1] = (uint32_t)f32_to_st16<DT>(acc[jt][t][2]) | ((uint32_t)f32_to_st16<DT>(acc[jt][t][3]) << 16);
             }
-            uint16_t *o = Xt + (size_t)(NHWC ? done.first[NHWC ? t : 0] : done.first[0] + t) * CS + j0 + g * (4 * JT);
+            uint16_t *o = Xt + (size_t)(NHWC ? done.out[NHWC ? t : 0] : done.out[0] + t) * CS + j0 + g * (4 * JT);
             if constexpr (JT % 2 == 0) {
 #pragma unroll
                 for (int k = 0; k < JT / 2; ++k)
@@ -470,7 +480,7 @@ __global__ __launch_bounds__(kThreads, 2) void probe_16_kernel(const uint16_t *_
 template <int DT>
 __global__ __launch_bounds__(kThreads) void probe_generic_kernel(const void *__restrict__ Xv, const float *__restrict__ Z,
                                                                  void *__restrict__ Xtv, int C_in, int HW, int r, int CS,
-                                                                 long long npix, int nhwc)
+                                                                 long long npix, int nhwc, long long gap)
 {
     const long long flat = (long long)blockIdx.x * kThreads + threadIdx.x;
     if (flat >= npix) return;
@@ -491,7 +501,7 @@ __global__ __launch_bounds__(kThreads) void probe_generic_kernel(const void *__r
             acc[jj] = fmaf(z, x, acc[jj]);
         }
     }
-    const size_t oi = (size_t)flat * CS + jb;
+    const size_t oi = (size_t)(flat + gap * (b + 1)) * CS + jb;
 #pragma unroll
     for (int jj = 0; jj < 16; ++jj) {
         if constexpr (DT == XCONV_F32) static_cast<float *>(Xtv)[oi + jj] = acc[jj];
@@ -639,7 +649,7 @@ static int probe_grid(int ntiles)
 
 template <int JT, bool NHWC>
 static hipError_t launch_probe_f32_jt(const float *X, const float *Z, const float *zpack, float *Xt, int C_in, int HW, int r, int CS,
-                                      int j0, long long npix, hipStream_t st)
+                                      int j0, long long npix, long long gap, hipStream_t st)
 {
     // a lane owns 4 consecutive pixels of a plane (NCHW) or one pixel of each of 4 sub-tiles (NHWC)
     const long long ngroups = NHWC ? npix : npix / 4;
@@ -648,13 +658,13 @@ static hipError_t launch_probe_f32_jt(const float *X, const float *Z, const floa
     hipError_t e = set_lds(probe_f32_kernel<JT, NHWC>, lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((probe_f32_kernel<JT, NHWC>), dim3(probe_grid(ntiles)), dim3(kThreads), lds, st, X, Z, zpack, Xt, C_in, HW, r,
-                       CS, j0, ngroups, ntiles);
+                       CS, j0, ngroups, ntiles, gap);
     return hipGetLastError();
 }
 
 template <int DT, int JT, int PT, bool SPLIT, bool NHWC>
 static hipError_t launch_probe_16_cfg(const uint16_t *X, const float *Z, const uint4 *zpack, uint16_t *Xt, int C_in, int HW, int r,
-                                      int CS, int j0, long long npix, hipStream_t st)
+                                      int CS, int j0, long long npix, long long gap, hipStream_t st)
 {
     const long long ngroups = NHWC ? npix : npix / PT;
     const int ntiles = (int)(NHWC ? (npix + 16 * PT - 1) / (16 * PT) : (ngroups + 15) / 16);
@@ -662,27 +672,27 @@ static hipError_t launch_probe_16_cfg(const uint16_t *X, const float *Z, const u
     hipError_t e = set_lds(probe_16_kernel<DT, JT, PT, SPLIT, NHWC>, lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((probe_16_kernel<DT, JT, PT, SPLIT, NHWC>), dim3(probe_grid(ntiles)), dim3(kThreads), lds, st, X, Z, zpack,
-                       Xt, C_in, HW, r, CS, j0, ngroups, ntiles);
+                       Xt, C_in, HW, r, CS, j0, ngroups, ntiles, gap);
     return hipGetLastError();
 }
 
 template <int DT, int JT>
 static hipError_t launch_probe_16_jt(const uint16_t *X, const float *Z, const uint4 *zpack, uint16_t *Xt, int C_in, int HW, int r,
-                                     int CS, int j0, long long npix, bool split, bool nhwc, hipStream_t st)
+                                     int CS, int j0, long long npix, bool split, bool nhwc, long long gap, hipStream_t st)
 {
     if (nhwc) {
-        if (split) return launch_probe_16_cfg<DT, JT, 4, true, true>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, st);
-        return launch_probe_16_cfg<DT, JT, 4, false, true>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, st);
+        if (split) return launch_probe_16_cfg<DT, JT, 4, true, true>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, gap, st);
+        return launch_probe_16_cfg<DT, JT, 4, false, true>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, gap, st);
     }
     // 8 pixels per lane when the accumulators stay small, 4 for wide probe blocks
     if constexpr (JT <= 2) {
         if (HW % 8 == 0) {
-            if (split) return launch_probe_16_cfg<DT, JT, 8, true, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, st);
-            return launch_probe_16_cfg<DT, JT, 8, false, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, st);
+            if (split) return launch_probe_16_cfg<DT, JT, 8, true, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, gap, st);
+            return launch_probe_16_cfg<DT, JT, 8, false, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, gap, st);
         }
     }
-    if (split) return launch_probe_16_cfg<DT, JT, 4, true, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, st);
-    return launch_probe_16_cfg<DT, JT, 4, false, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, st);
+    if (split) return launch_probe_16_cfg<DT, JT, 4, true, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, gap, st);
+    return launch_probe_16_cfg<DT, JT, 4, false, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, gap, st);
 }
 
 bool probe_fast_path_ok(int dtype, int C_in, int HW, bool nhwc)
@@ -727,7 +737,7 @@ hipError_t launch_pack_z(int dtype, const float *Z, void *out, int C_in, int r, 
 // zpack: Z in fragment order (launch_pack_z) or nullptr, in which case every workgroup gathers
 // its fragments from Z itself.
 hipError_t launch_probe(int dtype, const void *X, const float *Z, const void *zpack, void *Xt, int B, int C_in, int HW, int r,
-                        int CS, bool z_exact16, bool nhwc, hipStream_t st)
+                        int CS, bool z_exact16, bool nhwc, long long gap, hipStream_t st)
 {
     const long long npix = (long long)B * HW;
     const int ntj = CS / 16;
@@ -742,10 +752,10 @@ hipError_t launch_probe(int dtype, const void *X, const float *Z, const void *zp
             const float *zp = zpack ? static_cast<const float *>(zpack) + bi * ceil_div(C_in, 16) * 4 * 4 * 64 : nullptr;
 #define XC_P32(NH)                                                                                  \
     switch (jt) {                                                                                   \
-    case 1: e = launch_probe_f32_jt<1, NH>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, st); break;      \
-    case 2: e = launch_probe_f32_jt<2, NH>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, st); break;      \
-    case 3: e = launch_probe_f32_jt<3, NH>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, st); break;      \
-    default: e = launch_probe_f32_jt<4, NH>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, st); break;     \
+    case 1: e = launch_probe_f32_jt<1, NH>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, gap, st); break;      \
+    case 2: e = launch_probe_f32_jt<2, NH>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, gap, st); break;      \
+    case 3: e = launch_probe_f32_jt<3, NH>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, gap, st); break;      \
+    default: e = launch_probe_f32_jt<4, NH>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, gap, st); break;     \
     }
             if (nhwc) { XC_P32(true) } else { XC_P32(false) }
 #undef XC_P32
@@ -756,10 +766,10 @@ hipError_t launch_probe(int dtype, const void *X, const float *Z, const void *zp
             const uint4 *zp = zpack ? static_cast<const uint4 *>(zpack) + bi * ceil_div(C_in, 32) * 4 * 64 * (split ? 2 : 1) : nullptr;
 #define XC_P16(DT)                                                                                            \
     switch (jt) {                                                                                             \
-    case 1: e = launch_probe_16_jt<DT, 1>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, nhwc, st); break;          \
-    case 2: e = launch_probe_16_jt<DT, 2>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, nhwc, st); break;          \
-    case 3: e = launch_probe_16_jt<DT, 3>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, nhwc, st); break;          \
-    default: e = launch_probe_16_jt<DT, 4>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, nhwc, st); break;         \
+    case 1: e = launch_probe_16_jt<DT, 1>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, nhwc, gap, st); break;          \
+    case 2: e = launch_probe_16_jt<DT, 2>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, nhwc, gap, st); break;          \
+    case 3: e = launch_probe_16_jt<DT, 3>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, nhwc, gap, st); break;          \
+    default: e = launch_probe_16_jt<DT, 4>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, nhwc, gap, st); break;         \
     }
             if (dtype == XCONV_BF16) { XC_P16(XCONV_BF16) } else { XC_P16(XCONV_F16) }
 #undef XC_P16
@@ -769,16 +779,83 @@ hipError_t launch_probe(int dtype, const void *X, const float *Z, const void *zp
 }
 
 hipError_t launch_probe_generic(int dtype, const void *X, const float *Z, void *Xt, int B, int C_in, int HW, int r, int CS,
-                                bool nhwc, hipStream_t st)
+                                bool nhwc, long long gap, hipStream_t st)
 {
     const long long npix = (long long)B * HW;
     dim3 grid((unsigned)((npix + kThreads - 1) / kThreads), CS / 16);
     if (dtype == XCONV_F32)
-        hipLaunchKernelGGL(probe_generic_kernel<XCONV_F32>, grid, dim3(kThreads), 0, st, X, Z, Xt, C_in, HW, r, CS, npix, nhwc ? 1 : 0);
+        hipLaunchKernelGGL(probe_generic_kernel<XCONV_F32>, grid, dim3(kThreads), 0, st, X, Z, Xt, C_in, HW, r, CS, npix, nhwc ? 1 : 0, gap);
     else if (dtype == XCONV_BF16)
-        hipLaunchKernelGGL(probe_generic_kernel<XCONV_BF16>, grid, dim3(kThreads), 0, st, X, Z, Xt, C_in, HW, r, CS, npix, nhwc ? 1 : 0);
+        hipLaunchKernelGGL(probe_generic_kernel<XCONV_BF16>, grid, dim3(kThreads), 0, st, X, Z, Xt, C_in, HW, r, CS, npix, nhwc ? 1 : 0, gap);
     else
-        hipLaunchKernelGGL(probe_generic_kernel<XCONV_F16>, grid, dim3(kThreads), 0, st, X, Z, Xt, C_in, HW, r, CS, npix, nhwc ? 1 : 0);
+        hipLaunchKernelGGL(probe_generic_kernel<XCONV_F16>, grid, dim3(kThreads), 0, st, X, Z, Xt, C_in, HW, r, CS, npix, nhwc ? 1 : 0, gap);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Volumetric layers (3-D convolution, depth stride 1, "same" padding pd in depth) run the 2-D
+// kernels on depth slices: Xt and a copy of dY are laid out as runs of slices in which every
+// image's D slices are followed by pd zero slices, so that the slice a kernel-depth offset
+// pairs with an output slice is always a constant number of slices away and is a zero slice
+// whenever it falls outside the image.
+// ---------------------------------------------------------------------------
+// Zeroes the slices of Xt that hold no image data: `lead` slices in front, `pd` behind every
+// image, `lead` more at the end.  `slice16` = 16-byte vectors per slice, `period` = D + pd.
+__global__ __launch_bounds__(kThreads) void zero_gap_slices_kernel(uint4 *__restrict__ Xt, long long slice16, int B, int D, int pd,
+                                                                   long long total16)
+{
+    const long long i = (long long)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= total16) return;
+    // gap g in [0, B + 2): g = 0 is the lead, g = 1..B follows image g-1, g = B+1 is the tail
+    const long long per_gap = (long long)pd * slice16;
+    const int g = (int)(i / per_gap);
+    const long long off = i - (long long)g * per_gap;
+    const long long period = D + pd;
+    long long first_slice;
+    if (g == 0) first_slice = 0;
+    else if (g <= B) first_slice = pd + (long long)(g - 1) * period + D;
+    else first_slice = pd + (long long)B * period;
+    Xt[first_slice * slice16 + off] = uint4{0u, 0u, 0u, 0u};
+}
+
+hipError_t launch_zero_gap_slices(void *Xt, size_t slice_bytes, int B, int D, int pd, hipStream_t st)
+{
+    if (pd <= 0) return hipSuccess;
+    const long long slice16 = (long long)(slice_bytes / 16);
+    const long long total16 = (long long)(B + 2) * pd * slice16;
+    hipLaunchKernelGGL(zero_gap_slices_kernel, dim3((unsigned)((total16 + kThreads - 1) / kThreads)), dim3(kThreads), 0, st,
+                       static_cast<uint4 *>(Xt), slice16, B, D, pd, total16);
+    return hipGetLastError();
+}
+
+// dY [B, C, D, n] (planes of n = H'*W' values) -> [B*(D+pd), C, pitch]: slice-major planes of
+// `pitch` >= n elements with zero tails, zero slices behind every image.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void dy_slices_kernel(const T *__restrict__ src, T *__restrict__ dst, int C, int D, int pd,
+                                                             int n, int pitch, long long total)
+{
+    const long long i = (long long)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= total) return;
+    const int e = (int)(i % pitch);
+    const long long pl = i / pitch;
+    const int c = (int)(pl % C);
+    const long long sl = pl / C;
+    const int period = D + pd;
+    const int z = (int)(sl % period);
+    const long long b = sl / period;
+    dst[i] = (z < D && e < n) ? src[(((size_t)b * C + c) * D + z) * n + e] : T(0);
+}
+
+hipError_t launch_dy_slices(int dtype, const void *src, void *dst, int B, int C, int D, int pd, int n, int pitch, hipStream_t st)
+{
+    const long long total = (long long)B * (D + pd) * C * pitch;
+    dim3 grid((unsigned)((total + kThreads - 1) / kThreads));
+    if (dtype == XCONV_F32)
+        hipLaunchKernelGGL(dy_slices_kernel<float>, grid, dim3(kThreads), 0, st, static_cast<const float *>(src),
+                           static_cast<float *>(dst), C, D, pd, n, pitch, total);
+    else
+        hipLaunchKernelGGL(dy_slices_kernel<uint16_t>, grid, dim3(kThreads), 0, st, static_cast<const uint16_t *>(src),
+                           static_cast<uint16_t *>(dst), C, D, pd, n, pitch, total);
     return hipGetLastError();
 }
 

@@ -202,15 +202,18 @@ xconv_status xconv_probe_matrix_dev(const xconv_desc *d, float *Z_dev, void *str
     return XCONV_OK;
 }
 
-xconv_status xconv_probe_fwd(const xconv_desc *d, const void *X_dev, void *Xt_dev, const float *Z_dev, void *ws_dev,
-                             size_t ws_bytes, void *stream)
+}  // extern "C"
+
+namespace {
+
+// Forward probe over B images of HW pixels each; `gap` pixels of Xt stay free in front of every
+// image (0 for 2-D layers).
+xconv_status probe_impl(const xconv_desc *d, int HW, long long gap, const void *X_dev, void *Xt_dev, const float *Z_dev,
+                        void *ws_dev, size_t ws_bytes, hipStream_t st)
 {
-    xconv_status s = xconv_check_desc(d);
-    if (s != XCONV_OK) return s;
     if (!X_dev || !Xt_dev) return XCONV_EINVAL;
     if (!aligned16(Xt_dev) || (reinterpret_cast<uintptr_t>(X_dev) & (elem_bytes(d->dtype) - 1)) != 0) return XCONV_EINVAL;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const int CS = round_up(d->r, 16), HW = d->H * d->W;
+    const int CS = round_up(d->r, 16);
     const bool z_exact16 = d->probe == XCONV_RADEMACHER;
     const bool nhwc = d->layout == XCONV_NHWC;
     const bool fast = probe_fast_path_ok(d->dtype, d->C_in, HW, nhwc) && aligned16(X_dev);
@@ -227,7 +230,7 @@ xconv_status xconv_probe_fwd(const xconv_desc *d, const void *X_dev, void *Xt_de
         // is given); without it, every workgroup gathers its fragments from Z_dev.
         void *zpack = ws_dev ? static_cast<char *>(ws_dev) + zb : nullptr;
         if (zpack) XC_LAUNCH(K_PACK_Z, st, launch_pack_z(d->dtype, Z_dev, zpack, d->C_in, d->r, z_exact16, probe_code(d), d->seed, nhwc, st));
-        XC_LAUNCH(K_PROBE, st, launch_probe(d->dtype, X_dev, Z_dev, zpack, Xt_dev, d->B, d->C_in, HW, d->r, CS, z_exact16, nhwc, st));
+        XC_LAUNCH(K_PROBE, st, launch_probe(d->dtype, X_dev, Z_dev, zpack, Xt_dev, d->B, d->C_in, HW, d->r, CS, z_exact16, nhwc, gap, st));
     } else {
         const float *Z = Z_dev;
         if (!Z) {
@@ -235,9 +238,50 @@ xconv_status xconv_probe_fwd(const xconv_desc *d, const void *X_dev, void *Xt_de
             XC_LAUNCH(K_GEN_Z, st, launch_gen_z(zw, d->C_in * d->r, probe_code(d), d->seed, st));
             Z = zw;
         }
-        XC_LAUNCH(K_PROBE_GENERIC, st, launch_probe_generic(d->dtype, X_dev, Z, Xt_dev, d->B, d->C_in, HW, d->r, CS, nhwc, st));
+        XC_LAUNCH(K_PROBE_GENERIC, st, launch_probe_generic(d->dtype, X_dev, Z, Xt_dev, d->B, d->C_in, HW, d->r, CS, nhwc, gap, st));
     }
     return XCONV_OK;
+}
+
+// ---- volumetric layers: geometry of the slice layout -------------------------------
+struct Vol {
+    int period;          // slices per image in the slice-major buffers: D real ones + pad_d zero ones
+    long long B2;        // images of the 2-D problem the kernels see: B * period depth slices
+    size_t slice_bytes;  // one depth slice of Xt
+};
+Vol vol_of(const xconv3d_desc *v)
+{
+    Vol g;
+    g.period = v->D + v->pad_d;
+    g.B2 = (long long)v->l.B * g.period;
+    g.slice_bytes = (size_t)v->l.H * v->l.W * round_up(v->l.r, 16) * elem_bytes(v->l.dtype);
+    return g;
+}
+// plane pitch of the slice-major copy of dY for the kernel the plan selects
+int vol_dy_pitch(const xconv3d_desc *v, const PlanEntry &E)
+{
+    const int n = E.P.Ho * E.P.Wo;
+    return E.ws ? n : round_up(n, v->l.dtype == XCONV_F32 ? 4 : 8);
+}
+bool vol_plan(PlanEntry &E, const xconv3d_desc *v)
+{
+    const xconv_desc *d = &v->l;
+    const Vol g = vol_of(v);
+    if (g.B2 > 0x7fffffffLL) return false;
+    return get_plan(E, d->dtype, (int)g.B2, d->C_out, d->H, d->W, d->kH, d->kW, d->stride_h, d->stride_w, d->pad_h, d->pad_w,
+                    round_up(d->r, 16), true);
+}
+
+}  // namespace
+
+extern "C" {
+
+xconv_status xconv_probe_fwd(const xconv_desc *d, const void *X_dev, void *Xt_dev, const float *Z_dev, void *ws_dev,
+                             size_t ws_bytes, void *stream)
+{
+    xconv_status s = xconv_check_desc(d);
+    if (s != XCONV_OK) return s;
+    return probe_impl(d, d->H * d->W, 0, X_dev, Xt_dev, Z_dev, ws_dev, ws_bytes, static_cast<hipStream_t>(stream));
 }
 
 xconv_status xconv_dw_estimate(const xconv_desc *d, const void *dY_dev, const void *Xt_dev, const float *Z_dev, float *dW_dev,
@@ -376,6 +420,126 @@ xconv_status xconv_xt_unpack(const xconv_desc *d, const void *Xt_dev, float *out
     return XCONV_OK;
 }
 
+// ---- volumetric layers -----------------------------------------------------------
+// Slice layout shared by Xt and the copy of dY: image b's depth slices z = 0..D-1 sit at slice
+// b*(D+pd) + z of the run, followed by pd zero slices; Xt has pd more zero slices in front of
+// the run and behind it.  Kernel-depth offset kz then pairs slice i of dY with slice i + kz of
+// Xt for every i, and the partner is a zero slice whenever oz + kz - pd leaves the image.
+
+xconv_status xconv3d_check_desc(const xconv3d_desc *v)
+{
+    if (!v) return XCONV_EINVAL;
+    xconv_status s = xconv_check_desc(&v->l);
+    if (s != XCONV_OK) return s;
+    if (v->D < 1 || v->kD < 1 || v->pad_d < 0 || v->reserved != 0) return XCONV_EINVAL;
+    if (v->l.layout != XCONV_NCHW || v->kD > 7 || 2 * v->pad_d != v->kD - 1) return XCONV_EUNSUPPORTED;
+    if ((long long)v->D * v->l.H * v->l.W > (1LL << 28)) return XCONV_EUNSUPPORTED;
+    if ((long long)v->l.B * (v->D + v->pad_d) > 0x7fffffffLL) return XCONV_EUNSUPPORTED;
+    return XCONV_OK;
+}
+
+size_t xconv3d_xt_bytes(const xconv3d_desc *v)
+{
+    if (xconv3d_check_desc(v) != XCONV_OK) return 0;
+    const Vol g = vol_of(v);
+    return ((size_t)g.B2 + 2 * (size_t)v->pad_d) * g.slice_bytes;
+}
+
+size_t xconv3d_workspace_bytes(const xconv3d_desc *v, int op)
+{
+    if (xconv3d_check_desc(v) != XCONV_OK) return 0;
+    const xconv_desc *d = &v->l;
+    if (op == XCONV_OP_PROBE) return z_bytes(d) + zfrag_bytes(d);
+    if (op != XCONV_OP_ESTIMATE) return 0;
+    PlanEntry E;
+    if (!vol_plan(E, v)) return 0;
+    const Vol g = vol_of(v);
+    const size_t tile = (size_t)E.P.K2 * E.P.JP * E.P.MP * sizeof(float);
+    return z_bytes(d) + align_up(corr_partial_bytes(E.P), 256) + align_up((size_t)v->kD * tile, 256) +
+           align_up((size_t)g.B2 * d->C_out * vol_dy_pitch(v, E) * elem_bytes(d->dtype), 256);
+}
+
+xconv_status xconv3d_probe_fwd(const xconv3d_desc *v, const void *X_dev, void *Xt_dev, const float *Z_dev, void *ws_dev,
+                               size_t ws_bytes, void *stream)
+{
+    xconv_status s = xconv3d_check_desc(v);
+    if (s != XCONV_OK) return s;
+    const xconv_desc *d = &v->l;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int HW = d->H * d->W;
+    s = probe_impl(d, v->D * HW, (long long)v->pad_d * HW, X_dev, Xt_dev, Z_dev, ws_dev, ws_bytes, st);
+    if (s != XCONV_OK) return s;
+    XC_LAUNCH(K_ZERO_GAPS, st, launch_zero_gap_slices(Xt_dev, vol_of(v).slice_bytes, d->B, v->D, v->pad_d, st));
+    return XCONV_OK;
+}
+
+xconv_status xconv3d_dw_estimate(const xconv3d_desc *v, const void *dY_dev, const void *Xt_dev, const float *Z_dev, float *dW_dev,
+                                 void *ws_dev, size_t ws_bytes, void *stream)
+{
+    xconv_status s = xconv3d_check_desc(v);
+    if (s != XCONV_OK) return s;
+    const xconv_desc *d = &v->l;
+    if (!dY_dev || !Xt_dev || !dW_dev || !ws_dev) return XCONV_EINVAL;
+    if (!aligned16(Xt_dev) || !aligned16(ws_dev) || (reinterpret_cast<uintptr_t>(dW_dev) & 3u) != 0) return XCONV_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(dY_dev) & (elem_bytes(d->dtype) - 1)) != 0) return XCONV_EINVAL;
+    if (!Z_dev && d->probe == XCONV_USER_Z) return XCONV_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    PlanEntry E;
+    if (!vol_plan(E, v)) return XCONV_EUNSUPPORTED;
+    CorrParams &P = E.P;
+    const Vol g = vol_of(v);
+    const int pitch = vol_dy_pitch(v, E);
+    const size_t tile = (size_t)P.K2 * P.JP * P.MP * sizeof(float);
+    const size_t zb = z_bytes(d), pb = align_up(corr_partial_bytes(P), 256), tb = align_up((size_t)v->kD * tile, 256);
+    const size_t yb = align_up((size_t)g.B2 * d->C_out * pitch * elem_bytes(d->dtype), 256);
+    if (ws_bytes < zb + pb + tb + yb) return XCONV_EWORKSPACE;
+    char *ws = static_cast<char *>(ws_dev);
+    const float *Z = Z_dev;
+    float *zw = nullptr;
+    if (!Z) {
+        zw = reinterpret_cast<float *>(ws);
+        Z = zw;
+    }
+    float *T3 = reinterpret_cast<float *>(ws + zb + pb);
+    void *dy_slices = ws + zb + pb + tb;
+    XC_LAUNCH(K_REPACK, st, launch_dy_slices(d->dtype, dY_dev, dy_slices, d->B, d->C_out, v->D, v->pad_d, P.Ho * P.Wo, pitch, st));
+    P.dY = dy_slices;
+    P.part = reinterpret_cast<float *>(ws + zb);
+    for (int kz = 0; kz < v->kD; ++kz) {
+        const void *A = static_cast<const char *>(Xt_dev) + (size_t)kz * g.slice_bytes;
+        P.A = A;
+        if (E.ws) {
+            E.Wp.dY = P.dY;
+            E.Wp.A = A;
+            E.Wp.part = P.part;
+            XC_LAUNCH(K_CORR, st, E.ws == 2 ? launch_corr_ws32(E.Wp, st) : launch_corr_ws(d->dtype, E.Wp, st));
+        } else {
+            XC_LAUNCH(K_CORR, st, launch_corr(d->dtype, P, st));
+        }
+        // Z[s] for the expansion is redrawn by spare workgroups of the first reduction launch
+        XC_LAUNCH(K_REDUCE, st, launch_reduce(P, st, kz == 0 ? zw : nullptr, d->C_in * d->r, probe_code(d), d->seed,
+                                              T3 + (size_t)kz * (tile / sizeof(float))));
+    }
+    XC_LAUNCH(K_EXPAND, st, launch_expand(P, Z, dW_dev, d->C_in, d->r, st, d->keep_q15 != 0, T3, v->kD * P.K2));
+    return XCONV_OK;
+}
+
+xconv_status xconv3d_xt_unpack(const xconv3d_desc *v, const void *Xt_dev, float *out_dev, void *stream)
+{
+    xconv_status s = xconv3d_check_desc(v);
+    if (s != XCONV_OK) return s;
+    if (!Xt_dev || !out_dev) return XCONV_EINVAL;
+    const xconv_desc *d = &v->l;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const Vol g = vol_of(v);
+    const int DHW = v->D * d->H * d->W;
+    for (int b = 0; b < d->B; ++b) {
+        const char *src = static_cast<const char *>(Xt_dev) + ((size_t)v->pad_d + (size_t)b * g.period) * g.slice_bytes;
+        XC_LAUNCH(K_UNPACK, st, launch_unpack(d->dtype, src, out_dev + (size_t)b * d->r * DHW, 1, DHW, d->r, round_up(d->r, 16), st));
+    }
+    return XCONV_OK;
+}
+
 void xconv_prof_enable(int on)
 {
     std::lock_guard<std::mutex> lk(g_prof_mu);
@@ -413,6 +577,7 @@ const char *xconv_prof_kernel_name(int id)
     case K_UNPACK: return "unpack_kernel";
     case K_REPACK: return "repack_planes_kernel";
     case K_PACK_Z: return "pack_z_kernel";
+    case K_ZERO_GAPS: return "zero_gap_slices_kernel";
     default: return "unknown";
     }
 }

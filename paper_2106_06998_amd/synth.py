@@ -106,3 +106,12 @@ def small_variant(cfg: LayerConfig, B=None, H=None, W=None, C_in=None, C_out=Non
             d[key] = val
     d["name"] = name or (cfg.name + "-small")
     return LayerConfig(**d)
+
+
+def make_volume(B, C_in, C_out, dims, out_dims, seeds, dtype="f32", dy_var=1e-2):
+    """(X [B,C_in,D,H,W], dY [B,C_out,D',H',W']) of a volumetric layer: post-activation inputs and
+    small residuals like the 2-D layers, standing in for the CT patches of the paper's volumetric
+    finetuning experiment."""
+    X = draw((B, C_in) + tuple(dims), seeds[0], "relu_normal", 1.0, dtype)
+    dY = draw((B, C_out) + tuple(out_dims), seeds[1], "normal", dy_var, dtype)
+    return X, dY

@@ -18,8 +18,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_symbol():
     text = open(os.path.join(ROOT, "include", "xconv.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = set(re.findall(r"\b(xconv_[a-z0-9_]+)\s*\(", text))
-    assert {"xconv_probe_fwd", "xconv_dw_estimate", "xconv_dw_exact"} <= names
+    names = set(re.findall(r"\b(xconv(?:3d)?_[a-z0-9_]+)\s*\(", text))
+    assert {"xconv_probe_fwd", "xconv_dw_estimate", "xconv_dw_exact", "xconv3d_probe_fwd", "xconv3d_dw_estimate"} <= names
     L = xb.lib()
     for n in sorted(names):
         assert hasattr(L, n), n
@@ -131,6 +131,46 @@ def test_entry_points_reject_bad_arguments_before_any_launch():
     dn.layout = xb.XCONV_NHWC
     for op in (xb.XCONV_OP_ESTIMATE, xb.XCONV_OP_EXACT):
         assert xb.xconv_workspace_bytes(dn, op) > xb.xconv_workspace_bytes(_good(), op)
+
+
+def test_volumetric_descriptor_and_sizes():
+    assert ctypes.sizeof(xb.xconv3d_desc) == ctypes.sizeof(xb.xconv_desc) + 16
+    good = lambda: xb.make_desc3d(2, 16, 32, 8, 12, 12, 3, 1, 1, r=8, dtype="bf16")
+    v = good()
+    assert xb.xconv3d_check_desc(v) == xb.XCONV_OK
+    assert xb.lib().xconv3d_check_desc(None) == xb.XCONV_EINVAL
+    for field, val in (("D", 0), ("kD", 0), ("pad_d", -1), ("reserved", 1)):
+        v = good()
+        setattr(v, field, val)
+        assert xb.xconv3d_check_desc(v) == xb.XCONV_EINVAL, field
+    v = good()
+    v.l.r = 0                                            # the in-plane part is validated as a 2-D layer
+    assert xb.xconv3d_check_desc(v) == xb.XCONV_EINVAL
+    for field, val in (("pad_d", 0), ("pad_d", 2), ("kD", 2), ("kD", 9)):     # depth output must equal D, kD <= 7
+        v = good()
+        setattr(v, field, val)
+        assert xb.xconv3d_check_desc(v) == xb.XCONV_EUNSUPPORTED, field
+    v = good()
+    v.l.layout = xb.XCONV_NHWC
+    assert xb.xconv3d_check_desc(v) == xb.XCONV_EUNSUPPORTED
+    v = xb.make_desc3d(1, 4, 4, 6, 8, 8, (1, 3, 3), 1, (0, 1, 1), r=4)        # a stack of independent 2-D layers
+    assert xb.xconv3d_check_desc(v) == xb.XCONV_OK
+    assert xb.xconv3d_xt_bytes(v) == 6 * 8 * 8 * 16 * 4
+    v = good()
+    # per image 8 slices and one zero slice behind them, one more in front of and behind the run
+    assert xb.xconv3d_xt_bytes(v) == (2 * 9 + 2) * 12 * 12 * 16 * 2
+    assert xb.xconv3d_workspace_bytes(v, xb.XCONV_OP_PROBE) >= 16 * 8 * 4
+    west = xb.xconv3d_workspace_bytes(v, xb.XCONV_OP_ESTIMATE)
+    assert west > 2 * 9 * 32 * 12 * 12 * 2               # holds the slice-major copy of dY
+    assert xb.xconv3d_workspace_bytes(v, xb.XCONV_OP_EXACT) == 0
+    L = xb.lib()
+    p = ctypes.byref(v)
+    one = ctypes.c_void_p(4096)          # never dereferenced: validation fails first
+    assert L.xconv3d_probe_fwd(p, None, one, one, None, 0, None) == xb.XCONV_EINVAL
+    assert L.xconv3d_probe_fwd(p, one, one, None, one, 16, None) == xb.XCONV_EWORKSPACE
+    assert L.xconv3d_dw_estimate(p, one, one, one, one, None, 1 << 30, None) == xb.XCONV_EINVAL
+    assert L.xconv3d_dw_estimate(p, one, one, one, one, one, 64, None) == xb.XCONV_EWORKSPACE
+    assert L.xconv3d_xt_unpack(p, None, one, None) == xb.XCONV_EINVAL
 
 
 def test_synthetic_inputs_are_storage_representable_and_seeded():

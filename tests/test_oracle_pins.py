@@ -490,3 +490,63 @@ def test_sparse_estimator_is_unbiased_with_the_nnz_scaling_only():
     assert -0.65 < slope < -0.35, (slope, errs)
     shrink = np.sum(acc_r / done * exact) / np.sum(exact * exact)
     assert abs(shrink - 0.5) < 0.05, shrink
+
+
+# ---------------------------------------------------------------------------
+# volumetric layers (one more spatial axis)
+# ---------------------------------------------------------------------------
+VOL_SHAPES = [
+    # B, C_in, C_out, (D, H, W), k, stride, pad
+    (2, 3, 4, (5, 6, 7), (3, 3, 3), (1, 1, 1), (1, 1, 1)),
+    (1, 2, 3, (6, 5, 8), (3, 1, 2), (2, 1, 2), (1, 0, 1)),
+    (2, 2, 2, (4, 7, 5), (1, 3, 3), (1, 2, 1), (0, 2, 0)),
+    (1, 3, 2, (7, 4, 4), (5, 3, 1), (1, 1, 1), (2, 1, 0)),
+]
+
+
+def _vol(seed, B, C_in, C_out, dims, k, stride, pad):
+    rng = np.random.default_rng(seed)
+    D, H, W = dims
+    out = tuple(xo.out_extent(n, kk, s, p) for n, kk, s, p in zip(dims, k, stride, pad))
+    X = rng.standard_normal((B, C_in, D, H, W)).astype(np.float32)
+    dY = rng.standard_normal((B, C_out) + out).astype(np.float32)
+    return X, dY
+
+
+@pytest.mark.parametrize("shape", VOL_SHAPES, ids=[str(i) for i in range(len(VOL_SHAPES))])
+def test_exact_3d_gradient_matches_autograd_of_conv3d(shape):
+    # Eq. (2)/(5) with kD*kH*kW offsets is the weight gradient of the library's 3-D convolution
+    B, C_in, C_out, dims, k, stride, pad = shape
+    X, dY = _vol(31, *shape)
+    got = xo.dw_exact3d(dY, X, k, stride, pad)
+    w = torch.zeros((C_out, C_in) + k, dtype=torch.float64, requires_grad=True)
+    F.conv3d(torch.from_numpy(X).double(), w, stride=stride, padding=pad).backward(torch.from_numpy(dY).double())
+    want = w.grad.numpy()
+    assert got.shape == want.shape
+    assert np.max(np.abs(got - want)) <= 1e-12 * np.max(np.abs(want))
+
+
+def test_3d_routines_reduce_to_the_2d_ones_for_a_single_slice():
+    rng = np.random.default_rng(32)
+    B, C_in, C_out, H, W, r = 2, 3, 4, 6, 5, 4
+    X = rng.standard_normal((B, C_in, H, W)).astype(np.float32)
+    dY = rng.standard_normal((B, C_out, 3, 5)).astype(np.float32)      # 3x3, stride (2,1), pad (1,1)
+    Z = xo.probe_matrix(xo.GAUSSIAN, 5, C_in, r)
+    Xt2 = xo.probe_fwd(X, Z, xo.BF16)
+    Xt3 = xo.probe_fwd3d(X[:, :, None], Z, xo.BF16)
+    assert np.array_equal(Xt3[:, :, 0], Xt2)
+    want = xo.dw_from_xt(dY, Xt2, Z, 3, 3, (2, 1), (1, 1))
+    got = xo.dw_from_xt3d(dY[:, :, None], Xt3, Z, (1, 3, 3), (1, 2, 1), (0, 1, 1))
+    assert np.allclose(got[:, :, 0], want, rtol=1e-13, atol=0)
+
+
+def test_3d_estimate_with_a_full_rank_orthogonal_probe_is_exact():
+    # Z Z^T = r I (Hadamard rows): the estimator of Eq. (6) returns the exact gradient
+    shape = VOL_SHAPES[0][:1] + (4, 3) + VOL_SHAPES[0][3:]
+    X, dY = _vol(33, *shape)
+    Zh = np.array([[1, 1, 1, 1], [1, -1, 1, -1], [1, 1, -1, -1], [1, -1, -1, 1]], dtype=np.float32)
+    k, stride, pad = shape[4:]
+    Xt = xo.probe_fwd3d(X, Zh, xo.F32)
+    est = xo.dw_from_xt3d(dY, Xt, Zh, k, stride, pad)
+    exact = xo.dw_exact3d(dY, X, k, stride, pad)
+    assert np.max(np.abs(est - exact)) <= 1e-5 * np.max(np.abs(exact))
