@@ -178,6 +178,63 @@ def cpu_baseline(cfg, host, budget_s=12.0):
                 sample="full %s layer (probe_fwd + dw_from_xt), %d repetition(s), plain C -O2, one thread" % (cfg.name, reps))
 
 
+# Volumetric layers (3x3x3 kernels on cubic patches, the regime of the paper's volumetric
+# finetuning experiment); not part of the headline metric, measured with --volumetric.
+VOLUMES = {
+    "V1": dict(B=2, C_in=64, C_out=64, dims=(64, 64, 64), k=3, pad=1, r=16, dtype="f32", probe="gaussian", seeds=(1101, 2101, 3101)),
+    "V2": dict(B=1, C_in=128, C_out=128, dims=(48, 48, 48), k=3, pad=1, r=32, dtype="f16", probe="rademacher", seeds=(1102, 2102, 3102)),
+}
+
+
+def measure_volume(name, steps, warmup, dev, with_cpu):
+    import torch
+    from paper_2106_06998_amd import binding as xb
+    from paper_2106_06998_amd import synth
+    c = VOLUMES[name]
+    B, C_in, C_out, (D, H, W), k, r, dtype = c["B"], c["C_in"], c["C_out"], c["dims"], c["k"], c["r"], c["dtype"]
+    v = xb.make_desc3d(B, C_in, C_out, D, H, W, k, 1, c["pad"], r, dtype, c["probe"], c["seeds"][2])
+    X, dY = synth.make_volume(B, C_in, C_out, (D, H, W), (D, H, W), c["seeds"], dtype)
+    sets = []
+    for _ in range(3):
+        sets.append(dict(X=xb.to_device(X, dtype, dev), dY=xb.to_device(dY, dtype, dev),
+                         Xt=xb.alloc_bytes(xb.xconv3d_xt_bytes(v), dev),
+                         dW=torch.empty((C_out, C_in, k, k, k), dtype=torch.float32, device=dev),
+                         ws=xb.alloc_bytes(xb.xconv3d_workspace_bytes(v, xb.XCONV_OP_ESTIMATE), dev)))
+
+    def step(i):
+        s = sets[i % len(sets)]
+        v.l.seed = c["seeds"][2] + i
+        xb.xconv3d_probe_fwd(v, s["X"], s["Xt"], None, s["ws"])
+        xb.xconv3d_dw_estimate(v, s["dY"], s["Xt"], None, s["dW"], s["ws"])
+
+    ms_step = time_region(step, steps, warmup)
+    kt, _ = kernel_times(xb, step, steps, warmup)
+    es = elem_bytes(dtype)
+    vox = B * D * H * W
+    probe_bytes = (C_in + r) * vox * es
+    corr_flops = 2.0 * vox * C_out * r * k * k          # one launch: the k*k in-plane offsets of one kernel-depth offset
+    corr_bytes = vox * C_out * es + vox * r * es + C_out * r * k * k * 4
+    tp, tc = kt.get("probe_kernel", kt.get("probe_generic_kernel")), kt["corr_kernel"]
+    out = dict(name=name, dtype=dtype, ms_per_layer=ms_step, kernels_ms=kt,
+               probe=dict(ms=tp, gbps=probe_bytes / tp / 1e6, hbm_frac=probe_bytes / tp / 1e6 / PEAK_HBM_GBS),
+               corr=dict(ms=tc, launches_per_layer=k, gflops=corr_flops / tc / 1e6, gbps=corr_bytes / tc / 1e6,
+                         mfma_frac=corr_flops / tc / 1e9 / PEAK_MFMA_TFLOPS[dtype]),
+               act_bytes_saved=(C_in - r) * vox * es,
+               workload="%s: B=%d C_in=%d C_out=%d D=H=W=%d k=%dx%dx%d pad=%d r=%d %s probes, %s storage, NCDHW" % (
+                   name, B, C_in, C_out, D, k, k, k, c["pad"], r, c["probe"], dtype))
+    if with_cpu:
+        # the oracle on the whole layer, once
+        from oracle import xconv_oracle as xo
+        Xs, dYs = X, dY
+        Z = xo.probe_matrix({"rademacher": xo.RADEMACHER, "gaussian": xo.GAUSSIAN}[c["probe"]], c["seeds"][2], C_in, r)
+        t0 = time.perf_counter()
+        Xt = xo.probe_fwd3d(Xs, Z, {"f32": xo.F32, "bf16": xo.BF16, "f16": xo.F16}[dtype])
+        xo.dw_from_xt3d(dYs, Xt, Z, (k, k, k), (1, 1, 1), (c["pad"],) * 3)
+        t = time.perf_counter() - t0
+        out["cpu_baseline"] = dict(value=t * 1e3, unit="ms/layer", cores=1, kind="oracle",
+                                   sample="full %s layer (probe_fwd3d + dw_from_xt3d), 1 repetition, plain C -O2, one thread" % name)
+    return out, corr_flops, corr_bytes
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -188,6 +245,8 @@ def main():
     ap.add_argument("--nhwc", action="store_true", help="hand X and dY over channels-last (layout XCONV_NHWC) instead of NCHW")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--no-exact", action="store_true", help="skip timing xconv_dw_exact (for clean per-kernel profiles)")
+    ap.add_argument("--volumetric", action="store_true",
+                    help="measure the volumetric (3-D convolution) layers V1 and V2 instead of the headline layer")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain device copy of 256 MiB ten times (reference reading for the FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -212,6 +271,26 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": dst.numel() * 4, "copies": 10}))
+        return 0
+    if args.volumetric:
+        res, flops, nbytes = measure_volume("V1", args.steps, args.warmup, dev, not args.no_cpu)
+        ach = res["corr"]["gflops"] / 1e3
+        line = {
+            "metric": "ms/layer for the XConv dW estimate of a 3-D layer (xconv3d_probe_fwd + xconv3d_dw_estimate), 1 GPU",
+            "value": res["ms_per_layer"], "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": res["ms_per_layer"], "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+            "dtype": res["dtype"], "data": "synthetic", "config": {"workload": res["workload"]},
+            "roofline": dict(bound="mfma", achieved=ach, peak=PEAK_MFMA_TFLOPS[res["dtype"]], unit="TFLOP/s",
+                             frac=ach / PEAK_MFMA_TFLOPS[res["dtype"]], kernel="corr_ws32_kernel", kernel_ms=res["corr"]["ms"],
+                             traffic=None),
+            "detail": res,
+        }
+        if "cpu_baseline" in res:
+            line["cpu_baseline"] = res.pop("cpu_baseline")
+        torch.cuda.empty_cache()
+        r2, _, _ = measure_volume("V2", max(args.steps // 2, 10), max(args.warmup // 2, 3), dev, False)
+        line["per_config"] = [r2]
+        print(json.dumps(line))
         return 0
     cfg = synth.CONFIGS[args.config]
     res, L = measure_config(cfg, args.steps, args.warmup, dev, with_exact=not args.no_exact, nhwc=args.nhwc)

@@ -843,11 +843,20 @@ __global__ __launch_bounds__(kThreads) void dy_slices_kernel(const T *__restrict
     const int period = D + pd;
     const int z = (int)(sl % period);
     const long long b = sl / period;
-    dst[i] = (z < D && e < n) ? src[(((size_t)b * C + c) * D + z) * n + e] : T(0);
+    dst[i] = (z < D && e < n) ? src[(((size_t)b * C + c) * D + z) * n + e] : T{};
 }
 
 hipError_t launch_dy_slices(int dtype, const void *src, void *dst, int B, int C, int D, int pd, int n, int pitch, hipStream_t st)
 {
+    const int es = dtype == XCONV_F32 ? 4 : 2;
+    const int vec = 16 / es;
+    if (n % vec == 0 && pitch % vec == 0 && (reinterpret_cast<uintptr_t>(src) & 15u) == 0) {
+        // whole 16-byte vectors: the same index arithmetic once per vector
+        const long long total = (long long)B * (D + pd) * C * (pitch / vec);
+        hipLaunchKernelGGL(dy_slices_kernel<uint4>, dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, st,
+                           static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), C, D, pd, n / vec, pitch / vec, total);
+        return hipGetLastError();
+    }
     const long long total = (long long)B * (D + pd) * C * pitch;
     dim3 grid((unsigned)((total + kThreads - 1) / kThreads));
     if (dtype == XCONV_F32)
