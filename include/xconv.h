@@ -173,10 +173,9 @@ typedef struct xconv3d_desc {
 xconv_status xconv3d_check_desc(const xconv3d_desc *desc);
 
 /* Bytes of the stored probe output (opaque layout: depth slices [H,W,r rounded up
- * to 16] with pad_d zero slices between images) and of the scratch of
- * XCONV_OP_PROBE / XCONV_OP_ESTIMATE; 0 for an invalid desc or another op.  The
- * estimate's scratch includes a slice-major copy of dY (one extra read and write
- * of dY). */
+ * to 16] with pad_d zero slices between images) and of the scratch of an op
+ * (xconv_op); 0 for an invalid desc.  The scratch of the two gradient ops
+ * includes a slice-major copy of dY (one extra read and write of dY). */
 size_t xconv3d_xt_bytes(const xconv3d_desc *desc);
 size_t xconv3d_workspace_bytes(const xconv3d_desc *desc, int op);
 
@@ -190,6 +189,12 @@ xconv_status xconv3d_probe_fwd(const xconv3d_desc *desc, const void *X_dev, void
 xconv_status xconv3d_dw_estimate(const xconv3d_desc *desc, const void *dY_dev, const void *Xt_dev,
                                  const float *Z_dev, float *dW_dev,
                                  void *ws_dev, size_t ws_bytes, void *stream);
+
+/* Exact weight gradient of a volumetric layer (Eq. (2)/(5) over kD*kH*kW offsets), for
+ * comparison with the estimate; arguments as xconv_dw_exact with X_dev [B,C_in,D,H,W].
+ * The scratch holds a channels-last copy of X in depth slices. */
+xconv_status xconv3d_dw_exact(const xconv3d_desc *desc, const void *dY_dev, const void *X_dev,
+                              float *dW_dev, void *ws_dev, size_t ws_bytes, void *stream);
 
 /* Test helper: writes the stored Xt as plain fp32 [B,r,D,H,W] into out_dev. */
 xconv_status xconv3d_xt_unpack(const xconv3d_desc *desc, const void *Xt_dev, float *out_dev, void *stream);

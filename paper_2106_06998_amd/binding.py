@@ -86,6 +86,8 @@ def lib():
         L.xconv3d_probe_fwd.argtypes = [P3, vp, vp, vp, vp, sz, vp]
         L.xconv3d_dw_estimate.restype = i32
         L.xconv3d_dw_estimate.argtypes = [P3, vp, vp, vp, vp, vp, sz, vp]
+        L.xconv3d_dw_exact.restype = i32
+        L.xconv3d_dw_exact.argtypes = [P3, vp, vp, vp, vp, sz, vp]
         L.xconv3d_xt_unpack.restype = i32
         L.xconv3d_xt_unpack.argtypes = [P3, vp, vp, vp]
         L.xconv_prof_enable.restype = None
@@ -225,6 +227,11 @@ def xconv3d_probe_fwd(desc, X_dev, Xt_dev, Z_dev=None, ws_dev=None, stream=None)
 def xconv3d_dw_estimate(desc, dY_dev, Xt_dev, Z_dev, dW_dev, ws_dev, stream=None):
     _check(lib().xconv3d_dw_estimate(ctypes.byref(desc), _ptr(dY_dev), _ptr(Xt_dev), _ptr(Z_dev), _ptr(dW_dev),
                                      _ptr(ws_dev), _nbytes(ws_dev), _stream(stream)), "xconv3d_dw_estimate")
+
+
+def xconv3d_dw_exact(desc, dY_dev, X_dev, dW_dev, ws_dev, stream=None):
+    _check(lib().xconv3d_dw_exact(ctypes.byref(desc), _ptr(dY_dev), _ptr(X_dev), _ptr(dW_dev), _ptr(ws_dev),
+                                  _nbytes(ws_dev), _stream(stream)), "xconv3d_dw_exact")
 
 
 def xconv3d_xt_unpack(desc, Xt_dev, out_dev, stream=None):

@@ -263,13 +263,13 @@ int vol_dy_pitch(const xconv3d_desc *v, const PlanEntry &E)
     const int n = E.P.Ho * E.P.Wo;
     return E.ws ? n : round_up(n, v->l.dtype == XCONV_F32 ? 4 : 8);
 }
-bool vol_plan(PlanEntry &E, const xconv3d_desc *v)
+// CS: channel stride of the slices the correlation reads (r or, on the exact path, C_in, rounded up to 16)
+bool vol_plan(PlanEntry &E, const xconv3d_desc *v, int CS)
 {
     const xconv_desc *d = &v->l;
     const Vol g = vol_of(v);
     if (g.B2 > 0x7fffffffLL) return false;
-    return get_plan(E, d->dtype, (int)g.B2, d->C_out, d->H, d->W, d->kH, d->kW, d->stride_h, d->stride_w, d->pad_h, d->pad_w,
-                    round_up(d->r, 16), true);
+    return get_plan(E, d->dtype, (int)g.B2, d->C_out, d->H, d->W, d->kH, d->kW, d->stride_h, d->stride_w, d->pad_h, d->pad_w, CS, true);
 }
 
 }  // namespace
@@ -450,12 +450,16 @@ size_t xconv3d_workspace_bytes(const xconv3d_desc *v, int op)
     if (xconv3d_check_desc(v) != XCONV_OK) return 0;
     const xconv_desc *d = &v->l;
     if (op == XCONV_OP_PROBE) return z_bytes(d) + zfrag_bytes(d);
-    if (op != XCONV_OP_ESTIMATE) return 0;
+    if (op != XCONV_OP_ESTIMATE && op != XCONV_OP_EXACT) return 0;
+    const bool exact = op == XCONV_OP_EXACT;
+    const int CS = round_up(exact ? d->C_in : d->r, 16);
     PlanEntry E;
-    if (!vol_plan(E, v)) return 0;
+    if (!vol_plan(E, v, CS)) return 0;
     const Vol g = vol_of(v);
     const size_t tile = (size_t)E.P.K2 * E.P.JP * E.P.MP * sizeof(float);
-    return z_bytes(d) + align_up(corr_partial_bytes(E.P), 256) + align_up((size_t)v->kD * tile, 256) +
+    // exact: channels-last slices of X in the layout of Xt take the place of Z
+    const size_t head = exact ? align_up(((size_t)g.B2 + 2 * (size_t)v->pad_d) * d->H * d->W * CS * elem_bytes(d->dtype), 256) : z_bytes(d);
+    return head + align_up(corr_partial_bytes(E.P), 256) + align_up((size_t)v->kD * tile, 256) +
            align_up((size_t)g.B2 * d->C_out * vol_dy_pitch(v, E) * elem_bytes(d->dtype), 256);
 }
 
@@ -485,7 +489,7 @@ xconv_status xconv3d_dw_estimate(const xconv3d_desc *v, const void *dY_dev, cons
     if (!Z_dev && d->probe == XCONV_USER_Z) return XCONV_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     PlanEntry E;
-    if (!vol_plan(E, v)) return XCONV_EUNSUPPORTED;
+    if (!vol_plan(E, v, round_up(d->r, 16))) return XCONV_EUNSUPPORTED;
     CorrParams &P = E.P;
     const Vol g = vol_of(v);
     const int pitch = vol_dy_pitch(v, E);
@@ -521,6 +525,58 @@ xconv_status xconv3d_dw_estimate(const xconv3d_desc *v, const void *dY_dev, cons
                                               T3 + (size_t)kz * (tile / sizeof(float))));
     }
     XC_LAUNCH(K_EXPAND, st, launch_expand(P, Z, dW_dev, d->C_in, d->r, st, d->keep_q15 != 0, T3, v->kD * P.K2));
+    return XCONV_OK;
+}
+
+xconv_status xconv3d_dw_exact(const xconv3d_desc *v, const void *dY_dev, const void *X_dev, float *dW_dev, void *ws_dev,
+                              size_t ws_bytes, void *stream)
+{
+    xconv_status s = xconv3d_check_desc(v);
+    if (s != XCONV_OK) return s;
+    const xconv_desc *d = &v->l;
+    if (!dY_dev || !X_dev || !dW_dev || !ws_dev) return XCONV_EINVAL;
+    if (!aligned16(ws_dev) || (reinterpret_cast<uintptr_t>(dW_dev) & 3u) != 0) return XCONV_EINVAL;
+    const size_t eb = elem_bytes(d->dtype);
+    if ((reinterpret_cast<uintptr_t>(dY_dev) & (eb - 1)) != 0 || (reinterpret_cast<uintptr_t>(X_dev) & (eb - 1)) != 0) return XCONV_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int CSx = round_up(d->C_in, 16), HW = d->H * d->W;
+    PlanEntry E;
+    if (!vol_plan(E, v, CSx)) return XCONV_EUNSUPPORTED;
+    CorrParams &P = E.P;
+    const Vol g = vol_of(v);
+    const int pitch = vol_dy_pitch(v, E);
+    const size_t xslice = (size_t)HW * CSx * eb;
+    const size_t tile = (size_t)P.K2 * P.JP * P.MP * sizeof(float);
+    const size_t xb = align_up(((size_t)g.B2 + 2 * (size_t)v->pad_d) * xslice, 256), pb = align_up(corr_partial_bytes(P), 256);
+    const size_t tb = align_up((size_t)v->kD * tile, 256), yb = align_up((size_t)g.B2 * d->C_out * pitch * eb, 256);
+    if (ws_bytes < xb + pb + tb + yb) return XCONV_EWORKSPACE;
+    char *ws = static_cast<char *>(ws_dev);
+    // X -> channels-last depth slices in the slice layout of Xt (one image at a time), zero slices between
+    for (int b = 0; b < d->B; ++b) {
+        const char *src = static_cast<const char *>(X_dev) + (size_t)b * d->C_in * v->D * HW * eb;
+        char *dst = ws + ((size_t)v->pad_d + (size_t)b * g.period) * xslice;
+        XC_LAUNCH(K_TO_NHWC, st, launch_to_nhwc(d->dtype, src, dst, 1, d->C_in, v->D * HW, CSx, st));
+    }
+    XC_LAUNCH(K_ZERO_GAPS, st, launch_zero_gap_slices(ws, xslice, d->B, v->D, v->pad_d, st));
+    float *T3 = reinterpret_cast<float *>(ws + xb + pb);
+    void *dy_slices = ws + xb + pb + tb;
+    XC_LAUNCH(K_REPACK, st, launch_dy_slices(d->dtype, dY_dev, dy_slices, d->B, d->C_out, v->D, v->pad_d, P.Ho * P.Wo, pitch, st));
+    P.dY = dy_slices;
+    P.part = reinterpret_cast<float *>(ws + xb);
+    for (int kz = 0; kz < v->kD; ++kz) {
+        const void *A = ws + (size_t)kz * xslice;
+        P.A = A;
+        if (E.ws) {
+            E.Wp.dY = P.dY;
+            E.Wp.A = A;
+            E.Wp.part = P.part;
+            XC_LAUNCH(K_CORR, st, E.ws == 2 ? launch_corr_ws32(E.Wp, st) : launch_corr_ws(d->dtype, E.Wp, st));
+        } else {
+            XC_LAUNCH(K_CORR, st, launch_corr(d->dtype, P, st));
+        }
+        XC_LAUNCH(K_REDUCE, st, launch_reduce(P, st, nullptr, 0, 0, 0, T3 + (size_t)kz * (tile / sizeof(float))));
+    }
+    XC_LAUNCH(K_EXPAND, st, launch_expand(P, nullptr, dW_dev, d->C_in, d->r, st, false, T3, v->kD * P.K2));
     return XCONV_OK;
 }
 

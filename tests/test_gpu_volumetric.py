@@ -67,6 +67,14 @@ def run_volume(e):
     assert np.all(np.isfinite(got))
     err = rel_max(got, want)
     assert err <= GRAD_TOL[dtype], err
+    # exact gradient of the same layer
+    dWx = torch.full_like(dW, float("nan"))
+    wsx = xb.alloc_bytes(xb.xconv3d_workspace_bytes(v, xb.XCONV_OP_EXACT), DEV)
+    wsx.fill_(0x7f)
+    xb.xconv3d_dw_exact(v, dYd, Xd, dWx, wsx)
+    torch.cuda.synchronize()
+    errx = rel_max(dWx.cpu().numpy().astype(np.float64), xo.dw_exact3d(dY, X, k, stride3, pad))
+    assert errx <= GRAD_TOL[dtype], errx
     return v, got
 
 

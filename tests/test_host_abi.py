@@ -162,7 +162,8 @@ def test_volumetric_descriptor_and_sizes():
     assert xb.xconv3d_workspace_bytes(v, xb.XCONV_OP_PROBE) >= 16 * 8 * 4
     west = xb.xconv3d_workspace_bytes(v, xb.XCONV_OP_ESTIMATE)
     assert west > 2 * 9 * 32 * 12 * 12 * 2               # holds the slice-major copy of dY
-    assert xb.xconv3d_workspace_bytes(v, xb.XCONV_OP_EXACT) == 0
+    assert xb.xconv3d_workspace_bytes(v, xb.XCONV_OP_EXACT) > (2 * 9 + 2) * 12 * 12 * 16 * 2     # channels-last X slices
+    assert xb.xconv3d_workspace_bytes(v, 7) == 0
     L = xb.lib()
     p = ctypes.byref(v)
     one = ctypes.c_void_p(4096)          # never dereferenced: validation fails first
@@ -170,6 +171,8 @@ def test_volumetric_descriptor_and_sizes():
     assert L.xconv3d_probe_fwd(p, one, one, None, one, 16, None) == xb.XCONV_EWORKSPACE
     assert L.xconv3d_dw_estimate(p, one, one, one, one, None, 1 << 30, None) == xb.XCONV_EINVAL
     assert L.xconv3d_dw_estimate(p, one, one, one, one, one, 64, None) == xb.XCONV_EWORKSPACE
+    assert L.xconv3d_dw_exact(p, one, None, one, one, 1 << 30, None) == xb.XCONV_EINVAL
+    assert L.xconv3d_dw_exact(p, one, one, one, one, 64, None) == xb.XCONV_EWORKSPACE
     assert L.xconv3d_xt_unpack(p, None, one, None) == xb.XCONV_EINVAL
 
 
