@@ -17,10 +17,10 @@ hipError_t launch_probe(int dtype, const void *X, const float *Z, const void *zp
                         int CS, bool z_exact16, bool nhwc, long long gap, hipStream_t st);
 hipError_t launch_probe_generic(int dtype, const void *X, const float *Z, void *Xt, int B, int C_in, int HW, int r, int CS,
                                 bool nhwc, long long gap, hipStream_t st);
-// volumetric layers: zero slices of Xt (pd in front, pd behind each image's D slices, pd at the end) and
-// dY [B, C, D, n] -> slice-major planes [B*(D+pd), C, pitch] with zero slices behind every image
-hipError_t launch_zero_gap_slices(void *Xt, size_t slice_bytes, int B, int D, int pd, hipStream_t st);
-hipError_t launch_dy_slices(int dtype, const void *src, void *dst, int B, int C, int D, int pd, int n, int pitch, hipStream_t st);
+// volumetric layers: zero slices of Xt (pd in front, pd behind each image's D slices, `tail` at the end) and
+// dY [B, C, Do, n] -> slice-major planes [B*period, C, pitch] with zero slices Do..period-1 behind every image
+hipError_t launch_zero_gap_slices(void *Xt, size_t slice_bytes, int B, int D, int pd, int tail, hipStream_t st);
+hipError_t launch_dy_slices(int dtype, const void *src, void *dst, int B, int C, int Do, int period, int n, int pitch, hipStream_t st);
 hipError_t launch_unpack(int dtype, const void *Xt, float *out, int B, int HW, int r, int CS, hipStream_t st);
 hipError_t launch_to_nhwc(int dtype, const void *X, void *out, int B, int C, int HW, int CS, hipStream_t st);
 // channels-last [B, HW, C] -> planes [B, C, pitch], zero tail

@@ -793,45 +793,47 @@ hipError_t launch_probe_generic(int dtype, const void *X, const float *Z, void *
 }
 
 // ---------------------------------------------------------------------------
-// Volumetric layers (3-D convolution, depth stride 1, "same" padding pd in depth) run the 2-D
-// kernels on depth slices: Xt and a copy of dY are laid out as runs of slices in which every
-// image's D slices are followed by pd zero slices, so that the slice a kernel-depth offset
-// pairs with an output slice is always a constant number of slices away and is a zero slice
-// whenever it falls outside the image.
+// Volumetric layers (3-D convolution, depth stride 1, padding pd in depth) run the 2-D kernels
+// on depth slices: Xt and a copy of dY are laid out as runs of slices with a period of D + pd
+// slices per image (the image's slices first, zero slices behind them), so that the slice a
+// kernel-depth offset pairs with an output slice is always a constant number of slices away
+// and is a zero slice whenever it falls outside the image.
 // ---------------------------------------------------------------------------
-// Zeroes the slices of Xt that hold no image data: `lead` slices in front, `pd` behind every
-// image, `lead` more at the end.  `slice16` = 16-byte vectors per slice, `period` = D + pd.
+// Zeroes the slices of Xt that hold no image data: `pd` slices in front, `pd` behind every
+// image's D slices, `tail` more at the end.  `slice16` = 16-byte vectors per slice.
 __global__ __launch_bounds__(kThreads) void zero_gap_slices_kernel(uint4 *__restrict__ Xt, long long slice16, int B, int D, int pd,
                                                                    long long total16)
 {
     const long long i = (long long)blockIdx.x * kThreads + threadIdx.x;
     if (i >= total16) return;
-    // gap g in [0, B + 2): g = 0 is the lead, g = 1..B follows image g-1, g = B+1 is the tail
     const long long per_gap = (long long)pd * slice16;
-    const int g = (int)(i / per_gap);
-    const long long off = i - (long long)g * per_gap;
     const long long period = D + pd;
-    long long first_slice;
-    if (g == 0) first_slice = 0;
-    else if (g <= B) first_slice = pd + (long long)(g - 1) * period + D;
-    else first_slice = pd + (long long)B * period;
-    Xt[first_slice * slice16 + off] = uint4{0u, 0u, 0u, 0u};
+    long long at;
+    if (i < (long long)(B + 1) * per_gap) {
+        // gap g: g = 0 in front of the run, g = 1..B behind image g-1
+        const int g = (int)(i / per_gap);
+        const long long first_slice = g == 0 ? 0 : pd + (long long)(g - 1) * period + D;
+        at = first_slice * slice16 + (i - (long long)g * per_gap);
+    } else {
+        at = (pd + (long long)B * period) * slice16 + (i - (long long)(B + 1) * per_gap);
+    }
+    Xt[at] = uint4{0u, 0u, 0u, 0u};
 }
 
-hipError_t launch_zero_gap_slices(void *Xt, size_t slice_bytes, int B, int D, int pd, hipStream_t st)
+hipError_t launch_zero_gap_slices(void *Xt, size_t slice_bytes, int B, int D, int pd, int tail, hipStream_t st)
 {
-    if (pd <= 0) return hipSuccess;
     const long long slice16 = (long long)(slice_bytes / 16);
-    const long long total16 = (long long)(B + 2) * pd * slice16;
+    const long long total16 = ((long long)(B + 1) * pd + tail) * slice16;
+    if (total16 <= 0) return hipSuccess;
     hipLaunchKernelGGL(zero_gap_slices_kernel, dim3((unsigned)((total16 + kThreads - 1) / kThreads)), dim3(kThreads), 0, st,
                        static_cast<uint4 *>(Xt), slice16, B, D, pd, total16);
     return hipGetLastError();
 }
 
-// dY [B, C, D, n] (planes of n = H'*W' values) -> [B*(D+pd), C, pitch]: slice-major planes of
-// `pitch` >= n elements with zero tails, zero slices behind every image.
+// dY [B, C, Do, n] (planes of n = H'*W' values) -> [B*period, C, pitch]: slice-major planes of
+// `pitch` >= n elements with zero tails; slices Do..period-1 of every image are zero.
 template <typename T>
-__global__ __launch_bounds__(kThreads) void dy_slices_kernel(const T *__restrict__ src, T *__restrict__ dst, int C, int D, int pd,
+__global__ __launch_bounds__(kThreads) void dy_slices_kernel(const T *__restrict__ src, T *__restrict__ dst, int C, int Do, int period,
                                                              int n, int pitch, long long total)
 {
     const long long i = (long long)blockIdx.x * kThreads + threadIdx.x;
@@ -840,31 +842,30 @@ __global__ __launch_bounds__(kThreads) void dy_slices_kernel(const T *__restrict
     const long long pl = i / pitch;
     const int c = (int)(pl % C);
     const long long sl = pl / C;
-    const int period = D + pd;
     const int z = (int)(sl % period);
     const long long b = sl / period;
-    dst[i] = (z < D && e < n) ? src[(((size_t)b * C + c) * D + z) * n + e] : T{};
+    dst[i] = (z < Do && e < n) ? src[(((size_t)b * C + c) * Do + z) * n + e] : T{};
 }
 
-hipError_t launch_dy_slices(int dtype, const void *src, void *dst, int B, int C, int D, int pd, int n, int pitch, hipStream_t st)
+hipError_t launch_dy_slices(int dtype, const void *src, void *dst, int B, int C, int Do, int period, int n, int pitch, hipStream_t st)
 {
     const int es = dtype == XCONV_F32 ? 4 : 2;
     const int vec = 16 / es;
     if (n % vec == 0 && pitch % vec == 0 && (reinterpret_cast<uintptr_t>(src) & 15u) == 0) {
         // whole 16-byte vectors: the same index arithmetic once per vector
-        const long long total = (long long)B * (D + pd) * C * (pitch / vec);
+        const long long total = (long long)B * period * C * (pitch / vec);
         hipLaunchKernelGGL(dy_slices_kernel<uint4>, dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, st,
-                           static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), C, D, pd, n / vec, pitch / vec, total);
+                           static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), C, Do, period, n / vec, pitch / vec, total);
         return hipGetLastError();
     }
-    const long long total = (long long)B * (D + pd) * C * pitch;
+    const long long total = (long long)B * period * C * pitch;
     dim3 grid((unsigned)((total + kThreads - 1) / kThreads));
     if (dtype == XCONV_F32)
         hipLaunchKernelGGL(dy_slices_kernel<float>, grid, dim3(kThreads), 0, st, static_cast<const float *>(src),
-                           static_cast<float *>(dst), C, D, pd, n, pitch, total);
+                           static_cast<float *>(dst), C, Do, period, n, pitch, total);
     else
         hipLaunchKernelGGL(dy_slices_kernel<uint16_t>, grid, dim3(kThreads), 0, st, static_cast<const uint16_t *>(src),
-                           static_cast<uint16_t *>(dst), C, D, pd, n, pitch, total);
+                           static_cast<uint16_t *>(dst), C, Do, period, n, pitch, total);
     return hipGetLastError();
 }
 

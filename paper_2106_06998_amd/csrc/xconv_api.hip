@@ -245,15 +245,21 @@ xconv_status probe_impl(const xconv_desc *d, int HW, long long gap, const void *
 
 // ---- volumetric layers: geometry of the slice layout -------------------------------
 struct Vol {
-    int period;          // slices per image in the slice-major buffers: D real ones + pad_d zero ones
+    int period;          // slices per image in the slice-major buffers: D + pad_d
+    int Do;              // output depth D + 2 pad_d - kD + 1
+    int tail;            // zero slices of Xt behind the last image's period
     long long B2;        // images of the 2-D problem the kernels see: B * period depth slices
+    long long slices;    // slices of Xt: pad_d in front, B * period, tail
     size_t slice_bytes;  // one depth slice of Xt
 };
 Vol vol_of(const xconv3d_desc *v)
 {
     Vol g;
     g.period = v->D + v->pad_d;
+    g.Do = v->D + 2 * v->pad_d - v->kD + 1;
+    g.tail = v->kD - 1 - v->pad_d > 0 ? v->kD - 1 - v->pad_d : 0;
     g.B2 = (long long)v->l.B * g.period;
+    g.slices = v->pad_d + g.B2 + g.tail;
     g.slice_bytes = (size_t)v->l.H * v->l.W * round_up(v->l.r, 16) * elem_bytes(v->l.dtype);
     return g;
 }
@@ -421,10 +427,11 @@ xconv_status xconv_xt_unpack(const xconv_desc *d, const void *Xt_dev, float *out
 }
 
 // ---- volumetric layers -----------------------------------------------------------
-// Slice layout shared by Xt and the copy of dY: image b's depth slices z = 0..D-1 sit at slice
-// b*(D+pd) + z of the run, followed by pd zero slices; Xt has pd more zero slices in front of
-// the run and behind it.  Kernel-depth offset kz then pairs slice i of dY with slice i + kz of
-// Xt for every i, and the partner is a zero slice whenever oz + kz - pd leaves the image.
+// Slice layout shared by Xt and the copy of dY: image b's depth slices sit at slices
+// b*(D+pd) + z of the run (z < D for Xt, z < D' for dY), the rest of the period is zero; Xt has
+// pd more zero slices in front of the run and kD-1-pd behind it.  Kernel-depth offset kz then
+// pairs slice i of dY with slice i + kz of Xt for every i, and the partner is a zero slice
+// whenever oz + kz - pd leaves the image (which needs pd <= kD-1).
 
 xconv_status xconv3d_check_desc(const xconv3d_desc *v)
 {
@@ -432,7 +439,8 @@ xconv_status xconv3d_check_desc(const xconv3d_desc *v)
     xconv_status s = xconv_check_desc(&v->l);
     if (s != XCONV_OK) return s;
     if (v->D < 1 || v->kD < 1 || v->pad_d < 0 || v->reserved != 0) return XCONV_EINVAL;
-    if (v->l.layout != XCONV_NCHW || v->kD > 7 || 2 * v->pad_d != v->kD - 1) return XCONV_EUNSUPPORTED;
+    if (v->D + 2 * v->pad_d - v->kD + 1 < 1) return XCONV_EINVAL;   // empty output
+    if (v->l.layout != XCONV_NCHW || v->kD > 7 || v->pad_d > v->kD - 1) return XCONV_EUNSUPPORTED;
     if ((long long)v->D * v->l.H * v->l.W > (1LL << 28)) return XCONV_EUNSUPPORTED;
     if ((long long)v->l.B * (v->D + v->pad_d) > 0x7fffffffLL) return XCONV_EUNSUPPORTED;
     return XCONV_OK;
@@ -442,7 +450,7 @@ size_t xconv3d_xt_bytes(const xconv3d_desc *v)
 {
     if (xconv3d_check_desc(v) != XCONV_OK) return 0;
     const Vol g = vol_of(v);
-    return ((size_t)g.B2 + 2 * (size_t)v->pad_d) * g.slice_bytes;
+    return (size_t)g.slices * g.slice_bytes;
 }
 
 size_t xconv3d_workspace_bytes(const xconv3d_desc *v, int op)
@@ -458,7 +466,7 @@ size_t xconv3d_workspace_bytes(const xconv3d_desc *v, int op)
     const Vol g = vol_of(v);
     const size_t tile = (size_t)E.P.K2 * E.P.JP * E.P.MP * sizeof(float);
     // exact: channels-last slices of X in the layout of Xt take the place of Z
-    const size_t head = exact ? align_up(((size_t)g.B2 + 2 * (size_t)v->pad_d) * d->H * d->W * CS * elem_bytes(d->dtype), 256) : z_bytes(d);
+    const size_t head = exact ? align_up((size_t)g.slices * d->H * d->W * CS * elem_bytes(d->dtype), 256) : z_bytes(d);
     return head + align_up(corr_partial_bytes(E.P), 256) + align_up((size_t)v->kD * tile, 256) +
            align_up((size_t)g.B2 * d->C_out * vol_dy_pitch(v, E) * elem_bytes(d->dtype), 256);
 }
@@ -473,7 +481,8 @@ xconv_status xconv3d_probe_fwd(const xconv3d_desc *v, const void *X_dev, void *X
     const int HW = d->H * d->W;
     s = probe_impl(d, v->D * HW, (long long)v->pad_d * HW, X_dev, Xt_dev, Z_dev, ws_dev, ws_bytes, st);
     if (s != XCONV_OK) return s;
-    XC_LAUNCH(K_ZERO_GAPS, st, launch_zero_gap_slices(Xt_dev, vol_of(v).slice_bytes, d->B, v->D, v->pad_d, st));
+    const Vol g = vol_of(v);
+    XC_LAUNCH(K_ZERO_GAPS, st, launch_zero_gap_slices(Xt_dev, g.slice_bytes, d->B, v->D, v->pad_d, g.tail, st));
     return XCONV_OK;
 }
 
@@ -506,7 +515,7 @@ xconv_status xconv3d_dw_estimate(const xconv3d_desc *v, const void *dY_dev, cons
     }
     float *T3 = reinterpret_cast<float *>(ws + zb + pb);
     void *dy_slices = ws + zb + pb + tb;
-    XC_LAUNCH(K_REPACK, st, launch_dy_slices(d->dtype, dY_dev, dy_slices, d->B, d->C_out, v->D, v->pad_d, P.Ho * P.Wo, pitch, st));
+    XC_LAUNCH(K_REPACK, st, launch_dy_slices(d->dtype, dY_dev, dy_slices, d->B, d->C_out, g.Do, g.period, P.Ho * P.Wo, pitch, st));
     P.dY = dy_slices;
     P.part = reinterpret_cast<float *>(ws + zb);
     for (int kz = 0; kz < v->kD; ++kz) {
@@ -547,7 +556,7 @@ xconv_status xconv3d_dw_exact(const xconv3d_desc *v, const void *dY_dev, const v
     const int pitch = vol_dy_pitch(v, E);
     const size_t xslice = (size_t)HW * CSx * eb;
     const size_t tile = (size_t)P.K2 * P.JP * P.MP * sizeof(float);
-    const size_t xb = align_up(((size_t)g.B2 + 2 * (size_t)v->pad_d) * xslice, 256), pb = align_up(corr_partial_bytes(P), 256);
+    const size_t xb = align_up((size_t)g.slices * xslice, 256), pb = align_up(corr_partial_bytes(P), 256);
     const size_t tb = align_up((size_t)v->kD * tile, 256), yb = align_up((size_t)g.B2 * d->C_out * pitch * eb, 256);
     if (ws_bytes < xb + pb + tb + yb) return XCONV_EWORKSPACE;
     char *ws = static_cast<char *>(ws_dev);
@@ -557,10 +566,10 @@ xconv_status xconv3d_dw_exact(const xconv3d_desc *v, const void *dY_dev, const v
         char *dst = ws + ((size_t)v->pad_d + (size_t)b * g.period) * xslice;
         XC_LAUNCH(K_TO_NHWC, st, launch_to_nhwc(d->dtype, src, dst, 1, d->C_in, v->D * HW, CSx, st));
     }
-    XC_LAUNCH(K_ZERO_GAPS, st, launch_zero_gap_slices(ws, xslice, d->B, v->D, v->pad_d, st));
+    XC_LAUNCH(K_ZERO_GAPS, st, launch_zero_gap_slices(ws, xslice, d->B, v->D, v->pad_d, g.tail, st));
     float *T3 = reinterpret_cast<float *>(ws + xb + pb);
     void *dy_slices = ws + xb + pb + tb;
-    XC_LAUNCH(K_REPACK, st, launch_dy_slices(d->dtype, dY_dev, dy_slices, d->B, d->C_out, v->D, v->pad_d, P.Ho * P.Wo, pitch, st));
+    XC_LAUNCH(K_REPACK, st, launch_dy_slices(d->dtype, dY_dev, dy_slices, d->B, d->C_out, g.Do, g.period, P.Ho * P.Wo, pitch, st));
     P.dY = dy_slices;
     P.part = reinterpret_cast<float *>(ws + xb);
     for (int kz = 0; kz < v->kD; ++kz) {

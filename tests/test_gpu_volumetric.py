@@ -23,6 +23,10 @@ VOL = [
     ("bf16-depth-only-kernel", "bf16", 2, 32, 32, (9, 8, 8), (3, 1, 1), 1, (1, 0, 0), 32, "rademacher", 0, True),
     ("f16-sparse", "f16", 2, 32, 64, (4, 12, 12), (3, 3, 3), 1, (1, 1, 1), 32, "gaussian", 16384, True),
     ("f32-single-slice", "f32", 1, 8, 8, (1, 8, 8), (1, 3, 3), 1, (0, 1, 1), 8, "rademacher", 0, False),
+    ("f32-no-depth-padding", "f32", 2, 16, 16, (6, 8, 8), (3, 3, 3), 1, (0, 1, 1), 16, "rademacher", 0, False),
+    ("bf16-wide-depth-padding", "bf16", 2, 32, 32, (4, 8, 8), (3, 3, 3), 1, (2, 1, 1), 32, "rademacher", 0, True),
+    ("f16-even-depth-kernel", "f16", 3, 16, 24, (5, 6, 8), (2, 3, 3), 1, (1, 1, 1), 16, "gaussian", 0, False),
+    ("f32-deep-kernel-no-padding", "f32", 1, 8, 8, (9, 8, 8), (4, 1, 3), 1, (0, 0, 1), 8, "gaussian", 0, True),
     ("f32-odd-volume", "f32", 2, 6, 10, (3, 5, 5), (3, 3, 3), 1, (1, 1, 1), 5, "gaussian", 0, False),
     ("f16-one-voxel-row", "f16", 5, 16, 16, (3, 4, 8), (3, 3, 3), 1, (1, 1, 1), 16, "rademacher", 0, False),
 ]

@@ -146,10 +146,17 @@ def test_volumetric_descriptor_and_sizes():
     v = good()
     v.l.r = 0                                            # the in-plane part is validated as a 2-D layer
     assert xb.xconv3d_check_desc(v) == xb.XCONV_EINVAL
-    for field, val in (("pad_d", 0), ("pad_d", 2), ("kD", 2), ("kD", 9)):     # depth output must equal D, kD <= 7
+    for field, val in (("pad_d", 0), ("pad_d", 2), ("kD", 2)):                # D' = D - 2, D + 2, D + 1
+        v = good()
+        setattr(v, field, val)
+        assert xb.xconv3d_check_desc(v) == xb.XCONV_OK, field
+    for field, val in (("pad_d", 3), ("kD", 9)):                              # pad_d <= kD - 1, kD <= 7
         v = good()
         setattr(v, field, val)
         assert xb.xconv3d_check_desc(v) == xb.XCONV_EUNSUPPORTED, field
+    v = good()
+    v.D, v.pad_d = 2, 0                                   # kernel deeper than the volume: empty output
+    assert xb.xconv3d_check_desc(v) == xb.XCONV_EINVAL
     v = good()
     v.l.layout = xb.XCONV_NHWC
     assert xb.xconv3d_check_desc(v) == xb.XCONV_EUNSUPPORTED
@@ -159,6 +166,9 @@ def test_volumetric_descriptor_and_sizes():
     v = good()
     # per image 8 slices and one zero slice behind them, one more in front of and behind the run
     assert xb.xconv3d_xt_bytes(v) == (2 * 9 + 2) * 12 * 12 * 16 * 2
+    v.pad_d = 0                                           # no padding in depth: two more slices for the deepest offset
+    assert xb.xconv3d_xt_bytes(v) == (2 * 8 + 2) * 12 * 12 * 16 * 2
+    v = good()
     assert xb.xconv3d_workspace_bytes(v, xb.XCONV_OP_PROBE) >= 16 * 8 * 4
     west = xb.xconv3d_workspace_bytes(v, xb.XCONV_OP_ESTIMATE)
     assert west > 2 * 9 * 32 * 12 * 12 * 2               # holds the slice-major copy of dY
