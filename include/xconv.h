@@ -151,12 +151,12 @@ xconv_status xconv_xt_unpack(const xconv_desc *desc, const void *Xt_dev, float *
  * is the same with one more spatial axis:
  *
  *   Xt[b,j,z,y,x]     = sum_n Z[n,j] X[b,n,z,y,x]
- *   G[m,j,kz,ky,kx]   = sum_{b,oz,oy,ox} dY[b,m,oz,oy,ox] Xt[b,j,oz+kz-pad_d, oy*sh+ky-ph, ox*sw+kx-pw]
+ *   G[m,j,kz,ky,kx]   = sum_{b,oz,oy,ox} dY[b,m,oz,oy,ox] Xt[b,j,oz*sd+kz-pad_d, oy*sh+ky-ph, ox*sw+kx-pw]
  *   dW[m,n,kz,ky,kx]  = (1/r) sum_j Z[n,j] G[m,j,kz,ky,kx]
  *
  * `l` states the layer in the plane (B, channels, H, W, kH, kW, strides, pads, r,
- * dtype, probe, keep_q15, seed) exactly as for a 2-D layer; D, kD and pad_d add the
- * depth axis; the depth stride is 1, so D' = D + 2*pad_d - kD + 1.  Supported:
+ * dtype, probe, keep_q15, seed) exactly as for a 2-D layer; D, kD, stride_d (sd above)
+ * and pad_d add the depth axis, D' = floor((D + 2*pad_d - kD)/stride_d) + 1.  Supported:
  * pad_d <= kD-1, kD <= 7 and l.layout == XCONV_NCHW, meaning X [B,C_in,D,H,W] and
  * dY [B,C_out,D',H',W']; anything else is XCONV_EUNSUPPORTED.  dW is
  * [C_out,C_in,kD,kH,kW] fp32.
@@ -164,17 +164,17 @@ xconv_status xconv_xt_unpack(const xconv_desc *desc, const void *Xt_dev, float *
  * determinism, Z_dev / seed handling) hold unchanged. */
 typedef struct xconv3d_desc {
     xconv_desc l;
-    int32_t D, kD, pad_d;
-    int32_t reserved;        /* must be 0 */
+    int32_t D, kD, stride_d, pad_d;
 } xconv3d_desc;
 
-/* Host-only validation: `l` as xconv_check_desc; XCONV_EINVAL for D or kD < 1,
- * pad_d < 0, D' < 1 or reserved != 0; XCONV_EUNSUPPORTED as stated above and for
- * volumes of more than 2^28 voxels per channel. */
+/* Host-only validation: `l` as xconv_check_desc; XCONV_EINVAL for D, kD or stride_d
+ * < 1, pad_d < 0 or D' < 1; XCONV_EUNSUPPORTED as stated above and for volumes of more
+ * than 2^28 voxels per channel. */
 xconv_status xconv3d_check_desc(const xconv3d_desc *desc);
 
 /* Bytes of the stored probe output (opaque layout: depth slices [H,W,r rounded up
- * to 16] with pad_d zero slices behind every image) and of the scratch of an op
+ * to 16], zero slices between images, one run of slices per residue of the depth
+ * index modulo stride_d) and of the scratch of an op
  * (xconv_op); 0 for an invalid desc.  The scratch of the two gradient ops
  * includes a slice-major copy of dY (one extra read and write of dY). */
 size_t xconv3d_xt_bytes(const xconv3d_desc *desc);

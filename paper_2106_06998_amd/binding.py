@@ -31,8 +31,8 @@ class xconv_desc(ctypes.Structure):
 
 
 class xconv3d_desc(ctypes.Structure):
-    _fields_ = [("l", xconv_desc), ("D", ctypes.c_int32), ("kD", ctypes.c_int32), ("pad_d", ctypes.c_int32),
-                ("reserved", ctypes.c_int32)]
+    _fields_ = [("l", xconv_desc), ("D", ctypes.c_int32), ("kD", ctypes.c_int32), ("stride_d", ctypes.c_int32),
+                ("pad_d", ctypes.c_int32)]
 
 
 class XConvError(RuntimeError):
@@ -200,11 +200,12 @@ def xconv_xt_unpack(desc, Xt_dev, out_dev, stream=None):
 
 # ---- volumetric layers ---------------------------------------------------------
 def make_desc3d(B, C_in, C_out, D, H, W, k, stride=1, pad=0, r=1, dtype="f32", probe="rademacher", seed=0, keep_q15=0):
-    """k and pad are (depth, height, width) triples or one int for all three; stride is in-plane only."""
+    """k, stride and pad are (depth, height, width) triples or one int for all three."""
     kD, kH, kW = (k, k, k) if isinstance(k, int) else k
+    sd, sh, sw = (stride, stride, stride) if isinstance(stride, int) else stride
     pd, ph, pw = (pad, pad, pad) if isinstance(pad, int) else pad
-    return xconv3d_desc(make_desc(B, C_in, C_out, H, W, (kH, kW), stride, (ph, pw), r, dtype, probe, seed, XCONV_NCHW, keep_q15),
-                        D, kD, pd, 0)
+    return xconv3d_desc(make_desc(B, C_in, C_out, H, W, (kH, kW), (sh, sw), (ph, pw), r, dtype, probe, seed, XCONV_NCHW, keep_q15),
+                        D, kD, sd, pd)
 
 
 def xconv3d_check_desc(desc):

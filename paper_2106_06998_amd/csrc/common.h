@@ -29,6 +29,30 @@ enum KernelId {
     K_COUNT = 11
 };
 
+// Where the probe output of a voxel goes in Xt.  sd == 0: plain order, pixel `first` of the
+// input is pixel `first` of Xt.  Volumetric layers (sd = depth stride >= 1): Xt is sd runs of
+// `run` depth slices; slice z of image `img` is slot (z + pd) / sd of the image's `period`
+// slots in run (z + pd) % sd, so that kernel-depth offset kz pairs output slice oz with slot
+// oz + kz / sd of run kz % sd.
+struct SliceMap {
+    int HWs, D, pd, sd, period;
+    long long run;
+    __host__ __device__ long long slice_of(long long img, int z) const
+    {
+        const int t = z + pd;
+        return (long long)(t % sd) * run + img * period + t / sd;
+    }
+    // HW = D * HWs pixels per image
+    __host__ __device__ long long out_pixel(long long first, int HW) const
+    {
+        if (sd == 0) return first;
+        const long long img = first / HW;
+        const int rem = (int)(first - img * HW);
+        const int z = rem / HWs;
+        return slice_of(img, z) * HWs + (rem - z * HWs);
+    }
+};
+
 __host__ __device__ inline int round_up(int a, int b) { return (a + b - 1) / b * b; }
 __host__ __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 

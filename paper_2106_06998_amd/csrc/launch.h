@@ -12,14 +12,17 @@ bool probe_fast_path_ok(int dtype, int C_in, int HW, bool nhwc);
 size_t zpack_bytes(int dtype, int C_in, int r, bool z_exact16);
 hipError_t launch_pack_z(int dtype, const float *Z, void *out, int C_in, int r, bool z_exact16, int dist, uint64_t seed,
                          bool nhwc, hipStream_t st);
-// gap: pixels of Xt left free in front of every image (volumetric layers: the zero slices between images)
+// sm: where the output goes in Xt (SliceMap{} = plain order; volumetric layers: depth slices in slot order)
 hipError_t launch_probe(int dtype, const void *X, const float *Z, const void *zpack, void *Xt, int B, int C_in, int HW, int r,
-                        int CS, bool z_exact16, bool nhwc, long long gap, hipStream_t st);
+                        int CS, bool z_exact16, bool nhwc, SliceMap sm, hipStream_t st);
 hipError_t launch_probe_generic(int dtype, const void *X, const float *Z, void *Xt, int B, int C_in, int HW, int r, int CS,
-                                bool nhwc, long long gap, hipStream_t st);
-// volumetric layers: zero slices of Xt (pd in front, pd behind each image's D slices, `tail` at the end) and
+                                bool nhwc, SliceMap sm, hipStream_t st);
+// volumetric layers: zero the slots of Xt without image data; X -> channels-last slices in slot order;
+// stored probe output -> fp32 [B, r, D, HWs];
 // dY [B, C, Do, n] -> slice-major planes [B*period, C, pitch] with zero slices Do..period-1 behind every image
-hipError_t launch_zero_gap_slices(void *Xt, size_t slice_bytes, int B, int D, int pd, int tail, hipStream_t st);
+hipError_t launch_zero_gap_slices(void *Xt, size_t slice_bytes, int B, SliceMap sm, hipStream_t st);
+hipError_t launch_to_slices(int dtype, const void *X, void *out, int B, int C, int CS, SliceMap sm, hipStream_t st);
+hipError_t launch_unpack_slices(int dtype, const void *Xt, float *out, int B, int r, int CS, SliceMap sm, hipStream_t st);
 hipError_t launch_dy_slices(int dtype, const void *src, void *dst, int B, int C, int Do, int period, int n, int pitch, hipStream_t st);
 hipError_t launch_unpack(int dtype, const void *Xt, float *out, int B, int HW, int r, int CS, hipStream_t st);
 hipError_t launch_to_nhwc(int dtype, const void *X, void *out, int B, int C, int HW, int CS, hipStream_t st);

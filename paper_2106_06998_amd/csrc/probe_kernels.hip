@@ -113,7 +113,7 @@ template <int JT, bool NHWC>
 __global__ __launch_bounds__(kThreads, (JT == 1 ? 4 : 2)) void probe_f32_kernel(const float *__restrict__ X, const float *__restrict__ Z,
                                                              const float *__restrict__ zpack, float *__restrict__ Xt, int C_in,
                                                              int HW, int r, int CS, int j0, long long ngroups, int ntiles,
-                                                             long long gap)
+                                                             SliceMap sm)
 {
     extern __shared__ float zs[];  // [KQ4][JT][64] A-operand fragments, zero beyond C_in
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -143,7 +143,7 @@ __global__ __launch_bounds__(kThreads, (JT == 1 ? 4 : 2)) void probe_f32_kernel(
     struct Tile {
         const float *xb[NP];
         long long first[NP];
-        long long out[NP];  // pixel index in Xt: `gap` pixels are left free before every image
+        long long out[NP];  // pixel index in Xt
         bool valid[NP];
     };
     auto locate = [&](Tile &tl, int tile) {
@@ -154,7 +154,7 @@ __global__ __launch_bounds__(kThreads, (JT == 1 ? 4 : 2)) void probe_f32_kernel(
                 tl.valid[t] = pp < ngroups;
                 tl.first[t] = tl.valid[t] ? pp : last_group;
                 tl.xb[t] = X + (size_t)tl.first[t] * C_in;
-                tl.out[t] = tl.first[t] + (gap ? gap * (tl.first[t] / HW + 1) : 0);
+                tl.out[t] = sm.out_pixel(tl.first[t], HW);
             }
         } else {
             const long long pg_raw = (long long)tile * 16 + n;
@@ -162,7 +162,7 @@ __global__ __launch_bounds__(kThreads, (JT == 1 ? 4 : 2)) void probe_f32_kernel(
             tl.first[0] = (tl.valid[0] ? pg_raw : last_group) * 4;
             const long long img = tl.first[0] / HW;
             tl.xb[0] = X + (size_t)img * C_in * HW + (int)(tl.first[0] % HW);
-            tl.out[0] = tl.first[0] + gap * (img + 1);
+            tl.out[0] = sm.out_pixel(tl.first[0], HW);
         }
     };
     // Channels past the end re-read the last channels against zero fragment entries.
@@ -279,7 +279,7 @@ template <int DT, int JT, int PT, bool SPLIT, bool NHWC>
 __global__ __launch_bounds__(kThreads, 2) void probe_16_kernel(const uint16_t *__restrict__ X, const float *__restrict__ Z,
                                                             const uint4 *__restrict__ zpack, uint16_t *__restrict__ Xt, int C_in,
                                                             int HW, int r, int CS, int j0, long long ngroups, int ntiles,
-                                                            long long gap)
+                                                            SliceMap sm)
 {
     extern __shared__ uint4 zf[];  // [SPLIT?2:1][KK][JT][64] A-operand fragments
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -337,7 +337,7 @@ __global__ __launch_bounds__(kThreads, 2) void probe_16_kernel(const uint16_t *_
     struct Tile {
         const uint16_t *xb[NP];
         long long first[NP];
-        long long out[NP];  // pixel index in Xt: `gap` pixels are left free before every image
+        long long out[NP];  // pixel index in Xt
         bool valid[NP];
     };
     auto locate = [&](Tile &tl, int tile) {
@@ -348,7 +348,7 @@ __global__ __launch_bounds__(kThreads, 2) void probe_16_kernel(const uint16_t *_
                 tl.valid[t] = pp < ngroups;
                 tl.first[t] = tl.valid[t] ? pp : last_group;
                 tl.xb[t] = X + (size_t)tl.first[t] * C_in;
-                tl.out[t] = tl.first[t] + (gap ? gap * (tl.first[t] / HW + 1) : 0);
+                tl.out[t] = sm.out_pixel(tl.first[t], HW);
             }
         } else {
             const long long pg_raw = (long long)tile * 16 + n;
@@ -356,7 +356,7 @@ __global__ __launch_bounds__(kThreads, 2) void probe_16_kernel(const uint16_t *_
             tl.first[0] = (tl.valid[0] ? pg_raw : last_group) * PT;
             const long long img = tl.first[0] / HW;
             tl.xb[0] = X + (size_t)img * C_in * HW + (int)(tl.first[0] % HW);
-            tl.out[0] = tl.first[0] + gap * (img + 1);
+            tl.out[0] = sm.out_pixel(tl.first[0], HW);
         }
     };
     // MFMA operands of one K-step: cols[t] = the 8 channels 32kk + 8g .. +7 of pixel t.
@@ -480,7 +480,7 @@ __global__ __launch_bounds__(kThreads, 2) void probe_16_kernel(const uint16_t *_
 template <int DT>
 __global__ __launch_bounds__(kThreads) void probe_generic_kernel(const void *__restrict__ Xv, const float *__restrict__ Z,
                                                                  void *__restrict__ Xtv, int C_in, int HW, int r, int CS,
-                                                                 long long npix, int nhwc, long long gap)
+                                                                 long long npix, int nhwc, SliceMap sm)
 {
     const long long flat = (long long)blockIdx.x * kThreads + threadIdx.x;
     if (flat >= npix) return;
@@ -501,7 +501,7 @@ __global__ __launch_bounds__(kThreads) void probe_generic_kernel(const void *__r
             acc[jj] = fmaf(z, x, acc[jj]);
         }
     }
-    const size_t oi = (size_t)(flat + gap * (b + 1)) * CS + jb;
+    const size_t oi = (size_t)sm.out_pixel(flat, HW) * CS + jb;
 #pragma unroll
     for (int jj = 0; jj < 16; ++jj) {
         if constexpr (DT == XCONV_F32) static_cast<float *>(Xtv)[oi + jj] = acc[jj];
@@ -649,7 +649,7 @@ static int probe_grid(int ntiles)
 
 template <int JT, bool NHWC>
 static hipError_t launch_probe_f32_jt(const float *X, const float *Z, const float *zpack, float *Xt, int C_in, int HW, int r, int CS,
-                                      int j0, long long npix, long long gap, hipStream_t st)
+                                      int j0, long long npix, SliceMap sm, hipStream_t st)
 {
     // a lane owns 4 consecutive pixels of a plane (NCHW) or one pixel of each of 4 sub-tiles (NHWC)
     const long long ngroups = NHWC ? npix : npix / 4;
@@ -658,13 +658,13 @@ static hipError_t launch_probe_f32_jt(const float *X, const float *Z, const floa
     hipError_t e = set_lds(probe_f32_kernel<JT, NHWC>, lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((probe_f32_kernel<JT, NHWC>), dim3(probe_grid(ntiles)), dim3(kThreads), lds, st, X, Z, zpack, Xt, C_in, HW, r,
-                       CS, j0, ngroups, ntiles, gap);
+                       CS, j0, ngroups, ntiles, sm);
     return hipGetLastError();
 }
 
 template <int DT, int JT, int PT, bool SPLIT, bool NHWC>
 static hipError_t launch_probe_16_cfg(const uint16_t *X, const float *Z, const uint4 *zpack, uint16_t *Xt, int C_in, int HW, int r,
-                                      int CS, int j0, long long npix, long long gap, hipStream_t st)
+                                      int CS, int j0, long long npix, SliceMap sm, hipStream_t st)
 {
     const long long ngroups = NHWC ? npix : npix / PT;
     const int ntiles = (int)(NHWC ? (npix + 16 * PT - 1) / (16 * PT) : (ngroups + 15) / 16);
@@ -672,27 +672,27 @@ static hipError_t launch_probe_16_cfg(const uint16_t *X, const float *Z, const u
     hipError_t e = set_lds(probe_16_kernel<DT, JT, PT, SPLIT, NHWC>, lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((probe_16_kernel<DT, JT, PT, SPLIT, NHWC>), dim3(probe_grid(ntiles)), dim3(kThreads), lds, st, X, Z, zpack,
-                       Xt, C_in, HW, r, CS, j0, ngroups, ntiles, gap);
+                       Xt, C_in, HW, r, CS, j0, ngroups, ntiles, sm);
     return hipGetLastError();
 }
 
 template <int DT, int JT>
 static hipError_t launch_probe_16_jt(const uint16_t *X, const float *Z, const uint4 *zpack, uint16_t *Xt, int C_in, int HW, int r,
-                                     int CS, int j0, long long npix, bool split, bool nhwc, long long gap, hipStream_t st)
+                                     int CS, int j0, long long npix, bool split, bool nhwc, SliceMap sm, hipStream_t st)
 {
     if (nhwc) {
-        if (split) return launch_probe_16_cfg<DT, JT, 4, true, true>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, gap, st);
-        return launch_probe_16_cfg<DT, JT, 4, false, true>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, gap, st);
+        if (split) return launch_probe_16_cfg<DT, JT, 4, true, true>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, sm, st);
+        return launch_probe_16_cfg<DT, JT, 4, false, true>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, sm, st);
     }
     // 8 pixels per lane when the accumulators stay small, 4 for wide probe blocks
     if constexpr (JT <= 2) {
-        if (HW % 8 == 0) {
-            if (split) return launch_probe_16_cfg<DT, JT, 8, true, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, gap, st);
-            return launch_probe_16_cfg<DT, JT, 8, false, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, gap, st);
+        if ((sm.sd ? sm.HWs : HW) % 8 == 0) {
+            if (split) return launch_probe_16_cfg<DT, JT, 8, true, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, sm, st);
+            return launch_probe_16_cfg<DT, JT, 8, false, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, sm, st);
         }
     }
-    if (split) return launch_probe_16_cfg<DT, JT, 4, true, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, gap, st);
-    return launch_probe_16_cfg<DT, JT, 4, false, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, gap, st);
+    if (split) return launch_probe_16_cfg<DT, JT, 4, true, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, sm, st);
+    return launch_probe_16_cfg<DT, JT, 4, false, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, sm, st);
 }
 
 bool probe_fast_path_ok(int dtype, int C_in, int HW, bool nhwc)
@@ -737,7 +737,7 @@ hipError_t launch_pack_z(int dtype, const float *Z, void *out, int C_in, int r, 
 // zpack: Z in fragment order (launch_pack_z) or nullptr, in which case every workgroup gathers
 // its fragments from Z itself.
 hipError_t launch_probe(int dtype, const void *X, const float *Z, const void *zpack, void *Xt, int B, int C_in, int HW, int r,
-                        int CS, bool z_exact16, bool nhwc, long long gap, hipStream_t st)
+                        int CS, bool z_exact16, bool nhwc, SliceMap sm, hipStream_t st)
 {
     const long long npix = (long long)B * HW;
     const int ntj = CS / 16;
@@ -752,10 +752,10 @@ hipError_t launch_probe(int dtype, const void *X, const float *Z, const void *zp
             const float *zp = zpack ? static_cast<const float *>(zpack) + bi * ceil_div(C_in, 16) * 4 * 4 * 64 : nullptr;
 #define XC_P32(NH)                                                                                  \
     switch (jt) {                                                                                   \
-    case 1: e = launch_probe_f32_jt<1, NH>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, gap, st); break;      \
-    case 2: e = launch_probe_f32_jt<2, NH>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, gap, st); break;      \
-    case 3: e = launch_probe_f32_jt<3, NH>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, gap, st); break;      \
-    default: e = launch_probe_f32_jt<4, NH>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, gap, st); break;     \
+    case 1: e = launch_probe_f32_jt<1, NH>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, sm, st); break;      \
+    case 2: e = launch_probe_f32_jt<2, NH>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, sm, st); break;      \
+    case 3: e = launch_probe_f32_jt<3, NH>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, sm, st); break;      \
+    default: e = launch_probe_f32_jt<4, NH>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, sm, st); break;     \
     }
             if (nhwc) { XC_P32(true) } else { XC_P32(false) }
 #undef XC_P32
@@ -766,10 +766,10 @@ hipError_t launch_probe(int dtype, const void *X, const float *Z, const void *zp
             const uint4 *zp = zpack ? static_cast<const uint4 *>(zpack) + bi * ceil_div(C_in, 32) * 4 * 64 * (split ? 2 : 1) : nullptr;
 #define XC_P16(DT)                                                                                            \
     switch (jt) {                                                                                             \
-    case 1: e = launch_probe_16_jt<DT, 1>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, nhwc, gap, st); break;          \
-    case 2: e = launch_probe_16_jt<DT, 2>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, nhwc, gap, st); break;          \
-    case 3: e = launch_probe_16_jt<DT, 3>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, nhwc, gap, st); break;          \
-    default: e = launch_probe_16_jt<DT, 4>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, nhwc, gap, st); break;         \
+    case 1: e = launch_probe_16_jt<DT, 1>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, nhwc, sm, st); break;          \
+    case 2: e = launch_probe_16_jt<DT, 2>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, nhwc, sm, st); break;          \
+    case 3: e = launch_probe_16_jt<DT, 3>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, nhwc, sm, st); break;          \
+    default: e = launch_probe_16_jt<DT, 4>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, nhwc, sm, st); break;         \
     }
             if (dtype == XCONV_BF16) { XC_P16(XCONV_BF16) } else { XC_P16(XCONV_F16) }
 #undef XC_P16
@@ -779,54 +779,121 @@ hipError_t launch_probe(int dtype, const void *X, const float *Z, const void *zp
 }
 
 hipError_t launch_probe_generic(int dtype, const void *X, const float *Z, void *Xt, int B, int C_in, int HW, int r, int CS,
-                                bool nhwc, long long gap, hipStream_t st)
+                                bool nhwc, SliceMap sm, hipStream_t st)
 {
     const long long npix = (long long)B * HW;
     dim3 grid((unsigned)((npix + kThreads - 1) / kThreads), CS / 16);
     if (dtype == XCONV_F32)
-        hipLaunchKernelGGL(probe_generic_kernel<XCONV_F32>, grid, dim3(kThreads), 0, st, X, Z, Xt, C_in, HW, r, CS, npix, nhwc ? 1 : 0, gap);
+        hipLaunchKernelGGL(probe_generic_kernel<XCONV_F32>, grid, dim3(kThreads), 0, st, X, Z, Xt, C_in, HW, r, CS, npix, nhwc ? 1 : 0, sm);
     else if (dtype == XCONV_BF16)
-        hipLaunchKernelGGL(probe_generic_kernel<XCONV_BF16>, grid, dim3(kThreads), 0, st, X, Z, Xt, C_in, HW, r, CS, npix, nhwc ? 1 : 0, gap);
+        hipLaunchKernelGGL(probe_generic_kernel<XCONV_BF16>, grid, dim3(kThreads), 0, st, X, Z, Xt, C_in, HW, r, CS, npix, nhwc ? 1 : 0, sm);
     else
-        hipLaunchKernelGGL(probe_generic_kernel<XCONV_F16>, grid, dim3(kThreads), 0, st, X, Z, Xt, C_in, HW, r, CS, npix, nhwc ? 1 : 0, gap);
+        hipLaunchKernelGGL(probe_generic_kernel<XCONV_F16>, grid, dim3(kThreads), 0, st, X, Z, Xt, C_in, HW, r, CS, npix, nhwc ? 1 : 0, sm);
     return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------
-// Volumetric layers (3-D convolution, depth stride 1, padding pd in depth) run the 2-D kernels
-// on depth slices: Xt and a copy of dY are laid out as runs of slices with a period of D + pd
-// slices per image (the image's slices first, zero slices behind them), so that the slice a
-// kernel-depth offset pairs with an output slice is always a constant number of slices away
-// and is a zero slice whenever it falls outside the image.
+// Volumetric layers (3-D convolution) run the 2-D kernels on depth slices: Xt (in the order of
+// the slice map, see SliceMap) and a copy of dY are laid out as runs of slices with the same
+// number of slots per image, so that the slice a kernel-depth offset pairs with an output slice
+// is always a constant number of slots away and is a zero slice whenever it falls outside the
+// image.
 // ---------------------------------------------------------------------------
-// Zeroes the slices of Xt that hold no image data: `pd` slices in front, `pd` behind every
-// image's D slices, `tail` more at the end.  `slice16` = 16-byte vectors per slice.
-__global__ __launch_bounds__(kThreads) void zero_gap_slices_kernel(uint4 *__restrict__ Xt, long long slice16, int B, int D, int pd,
+// Zeroes the slices of Xt that hold no image data (slots of the slice map without a depth
+// slice of the image behind them, and the `run - B * period` slices at the end of every run).
+// `slice16` = 16-byte vectors per slice.
+__global__ __launch_bounds__(kThreads) void zero_gap_slices_kernel(uint4 *__restrict__ Xt, long long slice16, int B, SliceMap sm,
                                                                    long long total16)
 {
     const long long i = (long long)blockIdx.x * kThreads + threadIdx.x;
     if (i >= total16) return;
-    const long long per_gap = (long long)pd * slice16;
-    const long long period = D + pd;
-    long long at;
-    if (i < (long long)(B + 1) * per_gap) {
-        // gap g: g = 0 in front of the run, g = 1..B behind image g-1
-        const int g = (int)(i / per_gap);
-        const long long first_slice = g == 0 ? 0 : pd + (long long)(g - 1) * period + D;
-        at = first_slice * slice16 + (i - (long long)g * per_gap);
-    } else {
-        at = (pd + (long long)B * period) * slice16 + (i - (long long)(B + 1) * per_gap);
+    const long long s = i / slice16;
+    const int rho = (int)(s / sm.run);
+    const long long w = s - (long long)rho * sm.run;
+    bool data = false;
+    if (w < (long long)B * sm.period) {
+        const int q = (int)(w % sm.period);
+        const int z = q * sm.sd + rho - sm.pd;
+        data = z >= 0 && z < sm.D;
     }
-    Xt[at] = uint4{0u, 0u, 0u, 0u};
+    if (!data) Xt[i] = uint4{0u, 0u, 0u, 0u};
 }
 
-hipError_t launch_zero_gap_slices(void *Xt, size_t slice_bytes, int B, int D, int pd, int tail, hipStream_t st)
+hipError_t launch_zero_gap_slices(void *Xt, size_t slice_bytes, int B, SliceMap sm, hipStream_t st)
 {
     const long long slice16 = (long long)(slice_bytes / 16);
-    const long long total16 = ((long long)(B + 1) * pd + tail) * slice16;
-    if (total16 <= 0) return hipSuccess;
+    const long long total16 = (long long)sm.sd * sm.run * slice16;
     hipLaunchKernelGGL(zero_gap_slices_kernel, dim3((unsigned)((total16 + kThreads - 1) / kThreads)), dim3(kThreads), 0, st,
-                       static_cast<uint4 *>(Xt), slice16, B, D, pd, total16);
+                       static_cast<uint4 *>(Xt), slice16, B, sm, total16);
+    return hipGetLastError();
+}
+
+// X [B, C, D, HWs] -> channels-last depth slices [slot][HWs][CS] in the slice map's order, zero
+// columns C..CS-1 (the exact gradient of a volumetric layer reads X like a stored probe
+// output).  32x32 tiles through LDS; blockIdx.z = image * D + z.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void to_slices_kernel(const T *__restrict__ X, T *__restrict__ out, int C, int CS, SliceMap sm)
+{
+    __shared__ T tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+    const int p0 = blockIdx.x * 32, c0 = blockIdx.y * 32;
+    const int b = blockIdx.z / sm.D, z = blockIdx.z % sm.D;
+    const int HWs = sm.HWs;
+    const T *src = X + ((size_t)b * C * sm.D + z) * HWs;
+    T *dst = out + (size_t)sm.slice_of(b, z) * HWs * CS;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int c = c0 + ty + 8 * k, p = p0 + tx;
+        tile[ty + 8 * k][tx] = (c < C && p < HWs) ? src[(size_t)c * sm.D * HWs + p] : T(0);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int p = p0 + ty + 8 * k, c = c0 + tx;
+        if (p < HWs && c < CS) dst[(size_t)p * CS + c] = tile[tx][ty + 8 * k];
+    }
+}
+
+hipError_t launch_to_slices(int dtype, const void *X, void *out, int B, int C, int CS, SliceMap sm, hipStream_t st)
+{
+    dim3 grid(ceil_div(sm.HWs, 32), ceil_div(CS, 32), B * sm.D);
+    if (dtype == XCONV_F32)
+        hipLaunchKernelGGL(to_slices_kernel<float>, grid, dim3(kThreads), 0, st, static_cast<const float *>(X),
+                           static_cast<float *>(out), C, CS, sm);
+    else
+        hipLaunchKernelGGL(to_slices_kernel<uint16_t>, grid, dim3(kThreads), 0, st, static_cast<const uint16_t *>(X),
+                           static_cast<uint16_t *>(out), C, CS, sm);
+    return hipGetLastError();
+}
+
+// Test helper: the stored probe output of a volumetric layer as plain fp32 [B, r, D, HWs].
+template <int DT>
+__global__ __launch_bounds__(kThreads) void unpack_slices_kernel(const void *__restrict__ Xtv, float *__restrict__ out, int r, int CS,
+                                                                 SliceMap sm, long long total)
+{
+    const long long i = (long long)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= total) return;
+    const int p = (int)(i % sm.HWs);
+    long long t = i / sm.HWs;
+    const int z = (int)(t % sm.D);
+    t /= sm.D;
+    const int j = (int)(t % r);
+    const long long b = t / r;
+    const size_t at = ((size_t)sm.slice_of(b, z) * sm.HWs + p) * CS + j;
+    if constexpr (DT == XCONV_F32) out[i] = static_cast<const float *>(Xtv)[at];
+    else out[i] = st16_to_f32<DT>(static_cast<const uint16_t *>(Xtv)[at]);
+}
+
+hipError_t launch_unpack_slices(int dtype, const void *Xt, float *out, int B, int r, int CS, SliceMap sm, hipStream_t st)
+{
+    const long long total = (long long)B * r * sm.D * sm.HWs;
+    dim3 grid((unsigned)((total + kThreads - 1) / kThreads));
+    if (dtype == XCONV_F32)
+        hipLaunchKernelGGL(unpack_slices_kernel<XCONV_F32>, grid, dim3(kThreads), 0, st, Xt, out, r, CS, sm, total);
+    else if (dtype == XCONV_BF16)
+        hipLaunchKernelGGL(unpack_slices_kernel<XCONV_BF16>, grid, dim3(kThreads), 0, st, Xt, out, r, CS, sm, total);
+    else
+        hipLaunchKernelGGL(unpack_slices_kernel<XCONV_F16>, grid, dim3(kThreads), 0, st, Xt, out, r, CS, sm, total);
     return hipGetLastError();
 }
 

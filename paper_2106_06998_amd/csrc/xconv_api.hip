@@ -206,9 +206,9 @@ xconv_status xconv_probe_matrix_dev(const xconv_desc *d, float *Z_dev, void *str
 
 namespace {
 
-// Forward probe over B images of HW pixels each; `gap` pixels of Xt stay free in front of every
-// image (0 for 2-D layers).
-xconv_status probe_impl(const xconv_desc *d, int HW, long long gap, const void *X_dev, void *Xt_dev, const float *Z_dev,
+// Forward probe over B images of HW pixels each; `sm` says where the output goes in Xt
+// (SliceMap{} for 2-D layers: plain order).  `HWv`: extent whose divisibility decides the vector loads.
+xconv_status probe_impl(const xconv_desc *d, int HW, int HWv, SliceMap sm, const void *X_dev, void *Xt_dev, const float *Z_dev,
                         void *ws_dev, size_t ws_bytes, hipStream_t st)
 {
     if (!X_dev || !Xt_dev) return XCONV_EINVAL;
@@ -216,7 +216,7 @@ xconv_status probe_impl(const xconv_desc *d, int HW, long long gap, const void *
     const int CS = round_up(d->r, 16);
     const bool z_exact16 = d->probe == XCONV_RADEMACHER;
     const bool nhwc = d->layout == XCONV_NHWC;
-    const bool fast = probe_fast_path_ok(d->dtype, d->C_in, HW, nhwc) && aligned16(X_dev);
+    const bool fast = probe_fast_path_ok(d->dtype, d->C_in, HWv, nhwc) && aligned16(X_dev);
     const size_t zb = z_bytes(d), fb = zfrag_bytes(d);
     if (!Z_dev && d->probe == XCONV_USER_Z) return XCONV_EINVAL;
     if (ws_dev) {
@@ -230,7 +230,7 @@ xconv_status probe_impl(const xconv_desc *d, int HW, long long gap, const void *
         // is given); without it, every workgroup gathers its fragments from Z_dev.
         void *zpack = ws_dev ? static_cast<char *>(ws_dev) + zb : nullptr;
         if (zpack) XC_LAUNCH(K_PACK_Z, st, launch_pack_z(d->dtype, Z_dev, zpack, d->C_in, d->r, z_exact16, probe_code(d), d->seed, nhwc, st));
-        XC_LAUNCH(K_PROBE, st, launch_probe(d->dtype, X_dev, Z_dev, zpack, Xt_dev, d->B, d->C_in, HW, d->r, CS, z_exact16, nhwc, gap, st));
+        XC_LAUNCH(K_PROBE, st, launch_probe(d->dtype, X_dev, Z_dev, zpack, Xt_dev, d->B, d->C_in, HW, d->r, CS, z_exact16, nhwc, sm, st));
     } else {
         const float *Z = Z_dev;
         if (!Z) {
@@ -238,31 +238,53 @@ xconv_status probe_impl(const xconv_desc *d, int HW, long long gap, const void *
             XC_LAUNCH(K_GEN_Z, st, launch_gen_z(zw, d->C_in * d->r, probe_code(d), d->seed, st));
             Z = zw;
         }
-        XC_LAUNCH(K_PROBE_GENERIC, st, launch_probe_generic(d->dtype, X_dev, Z, Xt_dev, d->B, d->C_in, HW, d->r, CS, nhwc, gap, st));
+        XC_LAUNCH(K_PROBE_GENERIC, st, launch_probe_generic(d->dtype, X_dev, Z, Xt_dev, d->B, d->C_in, HW, d->r, CS, nhwc, sm, st));
     }
     return XCONV_OK;
 }
 
 // ---- volumetric layers: geometry of the slice layout -------------------------------
 struct Vol {
-    int period;          // slices per image in the slice-major buffers: D + pad_d
-    int Do;              // output depth D + 2 pad_d - kD + 1
-    int tail;            // zero slices of Xt behind the last image's period
+    int sd;              // depth stride
+    int Do;              // output depth
+    int period;          // slots per image in the slice-major buffers
     long long B2;        // images of the 2-D problem the kernels see: B * period depth slices
-    long long slices;    // slices of Xt: pad_d in front, B * period, tail
+    long long run;       // slices per run of Xt: B2 and (kD-1)/sd zero slices behind the last image
+    long long slices;    // slices of Xt: sd runs
     size_t slice_bytes;  // one depth slice of Xt
 };
 Vol vol_of(const xconv3d_desc *v)
 {
     Vol g;
-    g.period = v->D + v->pad_d;
-    g.Do = v->D + 2 * v->pad_d - v->kD + 1;
-    g.tail = v->kD - 1 - v->pad_d > 0 ? v->kD - 1 - v->pad_d : 0;
+    g.sd = v->stride_d;
+    g.Do = (v->D + 2 * v->pad_d - v->kD) / g.sd + 1;
+    const int reach = g.Do + (v->kD - 1) / g.sd;   // slots a kernel-depth offset can pair an image's output slices with
+    if (g.sd == 1) {
+        // the pad_d leading slots of the next image are zero and take the overhang
+        g.period = v->D + v->pad_d;
+    } else {
+        const int used = (v->D - 1 + v->pad_d) / g.sd + 1;
+        g.period = used > reach ? used : reach;
+    }
     g.B2 = (long long)v->l.B * g.period;
-    g.slices = v->pad_d + g.B2 + g.tail;
+    g.run = g.B2 + (v->kD - 1) / g.sd;   // the deepest offset reads that far past the last slot (against zero slots of dY)
+    g.slices = (long long)g.sd * g.run;
     g.slice_bytes = (size_t)v->l.H * v->l.W * round_up(v->l.r, 16) * elem_bytes(v->l.dtype);
     return g;
 }
+SliceMap vol_map(const xconv3d_desc *v, const Vol &g)
+{
+    SliceMap sm;
+    sm.HWs = v->l.H * v->l.W;
+    sm.D = v->D;
+    sm.pd = v->pad_d;
+    sm.sd = g.sd;
+    sm.period = g.period;
+    sm.run = g.run;
+    return sm;
+}
+// first slice of Xt (or of X in slice form) that kernel-depth offset kz pairs with slice 0 of dY
+size_t vol_offset_slices(const Vol &g, int kz) { return (size_t)(kz % g.sd) * (size_t)g.run + (size_t)(kz / g.sd); }
 // plane pitch of the slice-major copy of dY for the kernel the plan selects
 int vol_dy_pitch(const xconv3d_desc *v, const PlanEntry &E)
 {
@@ -287,7 +309,7 @@ xconv_status xconv_probe_fwd(const xconv_desc *d, const void *X_dev, void *Xt_de
 {
     xconv_status s = xconv_check_desc(d);
     if (s != XCONV_OK) return s;
-    return probe_impl(d, d->H * d->W, 0, X_dev, Xt_dev, Z_dev, ws_dev, ws_bytes, static_cast<hipStream_t>(stream));
+    return probe_impl(d, d->H * d->W, d->H * d->W, SliceMap{}, X_dev, Xt_dev, Z_dev, ws_dev, ws_bytes, static_cast<hipStream_t>(stream));
 }
 
 xconv_status xconv_dw_estimate(const xconv_desc *d, const void *dY_dev, const void *Xt_dev, const float *Z_dev, float *dW_dev,
@@ -427,22 +449,22 @@ xconv_status xconv_xt_unpack(const xconv_desc *d, const void *Xt_dev, float *out
 }
 
 // ---- volumetric layers -----------------------------------------------------------
-// Slice layout shared by Xt and the copy of dY: image b's depth slices sit at slices
-// b*(D+pd) + z of the run (z < D for Xt, z < D' for dY), the rest of the period is zero; Xt has
-// pd more zero slices in front of the run and kD-1-pd behind it.  Kernel-depth offset kz then
-// pairs slice i of dY with slice i + kz of Xt for every i, and the partner is a zero slice
-// whenever oz + kz - pd leaves the image (which needs pd <= kD-1).
+// Slice layout: the copy of dY holds `period` slots per image, output slice oz in slot oz, the
+// rest zero.  Xt holds sd runs of the same slots; depth slice z of an image sits in slot
+// (z + pd) / sd of run (z + pd) % sd, every other slot is zero.  Kernel-depth offset kz then
+// pairs slot i of dY with slot i + kz / sd of run kz % sd of Xt for every i, and the partner is
+// a zero slot whenever oz * sd + kz - pd leaves the image.
 
 xconv_status xconv3d_check_desc(const xconv3d_desc *v)
 {
     if (!v) return XCONV_EINVAL;
     xconv_status s = xconv_check_desc(&v->l);
     if (s != XCONV_OK) return s;
-    if (v->D < 1 || v->kD < 1 || v->pad_d < 0 || v->reserved != 0) return XCONV_EINVAL;
-    if (v->D + 2 * v->pad_d - v->kD + 1 < 1) return XCONV_EINVAL;   // empty output
+    if (v->D < 1 || v->kD < 1 || v->pad_d < 0 || v->stride_d < 1) return XCONV_EINVAL;
+    if (v->D + 2 * v->pad_d - v->kD < 0) return XCONV_EINVAL;   // empty output
     if (v->l.layout != XCONV_NCHW || v->kD > 7 || v->pad_d > v->kD - 1) return XCONV_EUNSUPPORTED;
     if ((long long)v->D * v->l.H * v->l.W > (1LL << 28)) return XCONV_EUNSUPPORTED;
-    if ((long long)v->l.B * (v->D + v->pad_d) > 0x7fffffffLL) return XCONV_EUNSUPPORTED;
+    if (v->stride_d > 4096 || (long long)v->l.B * (v->D + 2 * v->pad_d) > 0x7fffffffLL) return XCONV_EUNSUPPORTED;
     return XCONV_OK;
 }
 
@@ -479,10 +501,11 @@ xconv_status xconv3d_probe_fwd(const xconv3d_desc *v, const void *X_dev, void *X
     const xconv_desc *d = &v->l;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int HW = d->H * d->W;
-    s = probe_impl(d, v->D * HW, (long long)v->pad_d * HW, X_dev, Xt_dev, Z_dev, ws_dev, ws_bytes, st);
-    if (s != XCONV_OK) return s;
     const Vol g = vol_of(v);
-    XC_LAUNCH(K_ZERO_GAPS, st, launch_zero_gap_slices(Xt_dev, g.slice_bytes, d->B, v->D, v->pad_d, g.tail, st));
+    const SliceMap sm = vol_map(v, g);
+    s = probe_impl(d, v->D * HW, HW, sm, X_dev, Xt_dev, Z_dev, ws_dev, ws_bytes, st);
+    if (s != XCONV_OK) return s;
+    XC_LAUNCH(K_ZERO_GAPS, st, launch_zero_gap_slices(Xt_dev, g.slice_bytes, d->B, sm, st));
     return XCONV_OK;
 }
 
@@ -519,7 +542,7 @@ xconv_status xconv3d_dw_estimate(const xconv3d_desc *v, const void *dY_dev, cons
     P.dY = dy_slices;
     P.part = reinterpret_cast<float *>(ws + zb);
     for (int kz = 0; kz < v->kD; ++kz) {
-        const void *A = static_cast<const char *>(Xt_dev) + (size_t)kz * g.slice_bytes;
+        const void *A = static_cast<const char *>(Xt_dev) + vol_offset_slices(g, kz) * g.slice_bytes;
         P.A = A;
         if (E.ws) {
             E.Wp.dY = P.dY;
@@ -560,20 +583,18 @@ xconv_status xconv3d_dw_exact(const xconv3d_desc *v, const void *dY_dev, const v
     const size_t tb = align_up((size_t)v->kD * tile, 256), yb = align_up((size_t)g.B2 * d->C_out * pitch * eb, 256);
     if (ws_bytes < xb + pb + tb + yb) return XCONV_EWORKSPACE;
     char *ws = static_cast<char *>(ws_dev);
-    // X -> channels-last depth slices in the slice layout of Xt (one image at a time), zero slices between
-    for (int b = 0; b < d->B; ++b) {
-        const char *src = static_cast<const char *>(X_dev) + (size_t)b * d->C_in * v->D * HW * eb;
-        char *dst = ws + ((size_t)v->pad_d + (size_t)b * g.period) * xslice;
-        XC_LAUNCH(K_TO_NHWC, st, launch_to_nhwc(d->dtype, src, dst, 1, d->C_in, v->D * HW, CSx, st));
-    }
-    XC_LAUNCH(K_ZERO_GAPS, st, launch_zero_gap_slices(ws, xslice, d->B, v->D, v->pad_d, g.tail, st));
+    // X -> channels-last depth slices in the slice layout of Xt, zero slots between
+    const SliceMap sm = vol_map(v, g);
+    if ((long long)d->B * v->D > 65535) return XCONV_EUNSUPPORTED;   // one grid row per depth slice
+    XC_LAUNCH(K_TO_NHWC, st, launch_to_slices(d->dtype, X_dev, ws, d->B, d->C_in, CSx, sm, st));
+    XC_LAUNCH(K_ZERO_GAPS, st, launch_zero_gap_slices(ws, xslice, d->B, sm, st));
     float *T3 = reinterpret_cast<float *>(ws + xb + pb);
     void *dy_slices = ws + xb + pb + tb;
     XC_LAUNCH(K_REPACK, st, launch_dy_slices(d->dtype, dY_dev, dy_slices, d->B, d->C_out, g.Do, g.period, P.Ho * P.Wo, pitch, st));
     P.dY = dy_slices;
     P.part = reinterpret_cast<float *>(ws + xb);
     for (int kz = 0; kz < v->kD; ++kz) {
-        const void *A = ws + (size_t)kz * xslice;
+        const void *A = ws + vol_offset_slices(g, kz) * xslice;
         P.A = A;
         if (E.ws) {
             E.Wp.dY = P.dY;
@@ -597,11 +618,7 @@ xconv_status xconv3d_xt_unpack(const xconv3d_desc *v, const void *Xt_dev, float 
     const xconv_desc *d = &v->l;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const Vol g = vol_of(v);
-    const int DHW = v->D * d->H * d->W;
-    for (int b = 0; b < d->B; ++b) {
-        const char *src = static_cast<const char *>(Xt_dev) + ((size_t)v->pad_d + (size_t)b * g.period) * g.slice_bytes;
-        XC_LAUNCH(K_UNPACK, st, launch_unpack(d->dtype, src, out_dev + (size_t)b * d->r * DHW, 1, DHW, d->r, round_up(d->r, 16), st));
-    }
+    XC_LAUNCH(K_UNPACK, st, launch_unpack_slices(d->dtype, Xt_dev, out_dev, d->B, d->r, round_up(d->r, 16), vol_map(v, g), st));
     return XCONV_OK;
 }
 

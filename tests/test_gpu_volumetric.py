@@ -12,23 +12,28 @@ from test_gpu_parity import DEV, GRAD_TOL, ODT, OPROBE, ULP, rel_max, say
 
 pytestmark = pytest.mark.gpu
 
-# name, dtype, B, C_in, C_out, (D,H,W), (kD,kH,kW), in-plane stride, (pd,ph,pw), r, probe, keep_q15, Z from the seed
+# name, dtype, B, C_in, C_out, (D,H,W), (kD,kH,kW), stride (depth, in-plane), (pd,ph,pw), r, probe, keep_q15, Z from the seed
 VOL = [
-    ("f32-3x3x3", "f32", 2, 16, 32, (6, 16, 16), (3, 3, 3), 1, (1, 1, 1), 16, "gaussian", 0, False),
-    ("f32-seed", "f32", 2, 16, 32, (6, 16, 16), (3, 3, 3), 1, (1, 1, 1), 16, "gaussian", 0, True),
-    ("bf16-ragged-groups", "bf16", 3, 32, 64, (5, 12, 12), (3, 3, 3), 1, (1, 1, 1), 32, "rademacher", 0, False),
-    ("f16-odd-planes", "f16", 2, 24, 40, (4, 7, 7), (3, 3, 3), 1, (1, 1, 1), 12, "rademacher", 0, True),
-    ("f32-stack-of-2d", "f32", 2, 8, 16, (5, 12, 12), (1, 3, 3), 1, (0, 1, 1), 8, "rademacher", 0, False),
-    ("f32-deep-kernel-stride2", "f32", 1, 16, 16, (7, 17, 16), (5, 3, 3), 2, (2, 1, 1), 16, "gaussian", 0, False),
-    ("bf16-depth-only-kernel", "bf16", 2, 32, 32, (9, 8, 8), (3, 1, 1), 1, (1, 0, 0), 32, "rademacher", 0, True),
-    ("f16-sparse", "f16", 2, 32, 64, (4, 12, 12), (3, 3, 3), 1, (1, 1, 1), 32, "gaussian", 16384, True),
-    ("f32-single-slice", "f32", 1, 8, 8, (1, 8, 8), (1, 3, 3), 1, (0, 1, 1), 8, "rademacher", 0, False),
-    ("f32-no-depth-padding", "f32", 2, 16, 16, (6, 8, 8), (3, 3, 3), 1, (0, 1, 1), 16, "rademacher", 0, False),
-    ("bf16-wide-depth-padding", "bf16", 2, 32, 32, (4, 8, 8), (3, 3, 3), 1, (2, 1, 1), 32, "rademacher", 0, True),
-    ("f16-even-depth-kernel", "f16", 3, 16, 24, (5, 6, 8), (2, 3, 3), 1, (1, 1, 1), 16, "gaussian", 0, False),
-    ("f32-deep-kernel-no-padding", "f32", 1, 8, 8, (9, 8, 8), (4, 1, 3), 1, (0, 0, 1), 8, "gaussian", 0, True),
-    ("f32-odd-volume", "f32", 2, 6, 10, (3, 5, 5), (3, 3, 3), 1, (1, 1, 1), 5, "gaussian", 0, False),
-    ("f16-one-voxel-row", "f16", 5, 16, 16, (3, 4, 8), (3, 3, 3), 1, (1, 1, 1), 16, "rademacher", 0, False),
+    ("f32-3x3x3", "f32", 2, 16, 32, (6, 16, 16), (3, 3, 3), (1, 1), (1, 1, 1), 16, "gaussian", 0, False),
+    ("f32-seed", "f32", 2, 16, 32, (6, 16, 16), (3, 3, 3), (1, 1), (1, 1, 1), 16, "gaussian", 0, True),
+    ("bf16-ragged-groups", "bf16", 3, 32, 64, (5, 12, 12), (3, 3, 3), (1, 1), (1, 1, 1), 32, "rademacher", 0, False),
+    ("f16-odd-planes", "f16", 2, 24, 40, (4, 7, 7), (3, 3, 3), (1, 1), (1, 1, 1), 12, "rademacher", 0, True),
+    ("f32-stack-of-2d", "f32", 2, 8, 16, (5, 12, 12), (1, 3, 3), (1, 1), (0, 1, 1), 8, "rademacher", 0, False),
+    ("f32-deep-kernel-stride2", "f32", 1, 16, 16, (7, 17, 16), (5, 3, 3), (1, 2), (2, 1, 1), 16, "gaussian", 0, False),
+    ("bf16-depth-only-kernel", "bf16", 2, 32, 32, (9, 8, 8), (3, 1, 1), (1, 1), (1, 0, 0), 32, "rademacher", 0, True),
+    ("f16-sparse", "f16", 2, 32, 64, (4, 12, 12), (3, 3, 3), (1, 1), (1, 1, 1), 32, "gaussian", 16384, True),
+    ("f32-single-slice", "f32", 1, 8, 8, (1, 8, 8), (1, 3, 3), (1, 1), (0, 1, 1), 8, "rademacher", 0, False),
+    ("f32-no-depth-padding", "f32", 2, 16, 16, (6, 8, 8), (3, 3, 3), (1, 1), (0, 1, 1), 16, "rademacher", 0, False),
+    ("bf16-wide-depth-padding", "bf16", 2, 32, 32, (4, 8, 8), (3, 3, 3), (1, 1), (2, 1, 1), 32, "rademacher", 0, True),
+    ("f16-even-depth-kernel", "f16", 3, 16, 24, (5, 6, 8), (2, 3, 3), (1, 1), (1, 1, 1), 16, "gaussian", 0, False),
+    ("f32-deep-kernel-no-padding", "f32", 1, 8, 8, (9, 8, 8), (4, 1, 3), (1, 1), (0, 0, 1), 8, "gaussian", 0, True),
+    ("f32-depth-stride2", "f32", 2, 16, 16, (8, 8, 8), (3, 3, 3), (2, 2), (1, 1, 1), 16, "gaussian", 0, False),
+    ("bf16-depth-stride2-odd-depth", "bf16", 3, 32, 32, (7, 8, 8), (3, 3, 3), (2, 1), (1, 1, 1), 32, "rademacher", 0, True),
+    ("f16-depth-stride3-deep-kernel", "f16", 2, 16, 32, (11, 6, 8), (5, 3, 3), (3, 1), (2, 1, 1), 16, "rademacher", 0, False),
+    ("f32-depth-stride2-no-padding", "f32", 2, 8, 8, (9, 8, 8), (2, 3, 3), (2, 1), (0, 1, 1), 8, "rademacher", 0, True),
+    ("f32-depth-stride-beyond-kernel", "f32", 1, 8, 8, (10, 8, 8), (2, 1, 1), (4, 1), (1, 0, 0), 8, "gaussian", 0, False),
+    ("f32-odd-volume", "f32", 2, 6, 10, (3, 5, 5), (3, 3, 3), (1, 1), (1, 1, 1), 5, "gaussian", 0, False),
+    ("f16-one-voxel-row", "f16", 5, 16, 16, (3, 4, 8), (3, 3, 3), (1, 1), (1, 1, 1), 16, "rademacher", 0, False),
 ]
 
 
@@ -36,12 +41,12 @@ def run_volume(e):
     name, dtype, B, C_in, C_out, dims, k, st, pad, r, probe, keep, seed_path = e
     say("volumetric %s" % (e,))
     D, H, W = dims
-    stride3 = (1, st, st)
+    stride3 = (st[0], st[1], st[1])
     out = tuple(xo.out_extent(n, kk, s, p) for n, kk, s, p in zip(dims, k, stride3, pad))
     seeds = (7101 + len(name), 7202 + len(name), 7303 + len(name))
     X, dY = synth.make_volume(B, C_in, C_out, dims, out, seeds, dtype)
     Z = xo.probe_matrix(OPROBE[probe], seeds[2], C_in, r, keep)
-    v = xb.make_desc3d(B, C_in, C_out, D, H, W, k, st, pad, r, dtype, probe, seeds[2], keep)
+    v = xb.make_desc3d(B, C_in, C_out, D, H, W, k, stride3, pad, r, dtype, probe, seeds[2], keep)
     assert xb.xconv3d_check_desc(v) == xb.XCONV_OK
     Xd = xb.to_device(X, dtype, DEV)
     Xt = xb.alloc_bytes(xb.xconv3d_xt_bytes(v), DEV)

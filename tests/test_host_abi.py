@@ -139,7 +139,7 @@ def test_volumetric_descriptor_and_sizes():
     v = good()
     assert xb.xconv3d_check_desc(v) == xb.XCONV_OK
     assert xb.lib().xconv3d_check_desc(None) == xb.XCONV_EINVAL
-    for field, val in (("D", 0), ("kD", 0), ("pad_d", -1), ("reserved", 1)):
+    for field, val in (("D", 0), ("kD", 0), ("pad_d", -1), ("stride_d", 0)):
         v = good()
         setattr(v, field, val)
         assert xb.xconv3d_check_desc(v) == xb.XCONV_EINVAL, field
@@ -164,10 +164,14 @@ def test_volumetric_descriptor_and_sizes():
     assert xb.xconv3d_check_desc(v) == xb.XCONV_OK
     assert xb.xconv3d_xt_bytes(v) == 6 * 8 * 8 * 16 * 4
     v = good()
-    # per image 8 slices and one zero slice behind them, one more in front of and behind the run
+    # per image one zero slot and 8 slices, two more zero slices for the deepest offset behind the run
     assert xb.xconv3d_xt_bytes(v) == (2 * 9 + 2) * 12 * 12 * 16 * 2
-    v.pad_d = 0                                           # no padding in depth: two more slices for the deepest offset
+    v.pad_d = 0
     assert xb.xconv3d_xt_bytes(v) == (2 * 8 + 2) * 12 * 12 * 16 * 2
+    v = good()
+    v.stride_d = 2                                        # two runs (even and odd slots) of 2 * 5 + 1 slices
+    assert xb.xconv3d_check_desc(v) == xb.XCONV_OK
+    assert xb.xconv3d_xt_bytes(v) == 2 * (2 * 5 + 1) * 12 * 12 * 16 * 2
     v = good()
     assert xb.xconv3d_workspace_bytes(v, xb.XCONV_OP_PROBE) >= 16 * 8 * 4
     west = xb.xconv3d_workspace_bytes(v, xb.XCONV_OP_ESTIMATE)
