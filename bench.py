@@ -186,7 +186,7 @@ VOLUMES = {
 }
 
 
-def measure_volume(name, steps, warmup, dev, with_cpu):
+def measure_volume(name, steps, warmup, dev, with_cpu, with_exact=True):
     import torch
     from paper_2106_06998_amd import binding as xb
     from paper_2106_06998_amd import synth
@@ -209,6 +209,15 @@ def measure_volume(name, steps, warmup, dev, with_cpu):
 
     ms_step = time_region(step, steps, warmup)
     kt, _ = kernel_times(xb, step, steps, warmup)
+    ms_exact = None
+    if with_exact:
+        wsx = xb.alloc_bytes(xb.xconv3d_workspace_bytes(v, xb.XCONV_OP_EXACT), dev)
+
+        def exact(i):
+            s = sets[i % len(sets)]
+            xb.xconv3d_dw_exact(v, s["dY"], s["X"], s["dW"], wsx)
+
+        ms_exact = time_region(exact, max(steps // 4, 5), max(warmup // 4, 2))
     es = elem_bytes(dtype)
     vox = B * D * H * W
     probe_bytes = (C_in + r) * vox * es
@@ -219,7 +228,7 @@ def measure_volume(name, steps, warmup, dev, with_cpu):
                probe=dict(ms=tp, gbps=probe_bytes / tp / 1e6, hbm_frac=probe_bytes / tp / 1e6 / PEAK_HBM_GBS),
                corr=dict(ms=tc, launches_per_layer=k, gflops=corr_flops / tc / 1e6, gbps=corr_bytes / tc / 1e6,
                          mfma_frac=corr_flops / tc / 1e9 / PEAK_MFMA_TFLOPS[dtype]),
-               act_bytes_saved=(C_in - r) * vox * es,
+               act_bytes_saved=(C_in - r) * vox * es, exact_ms=ms_exact, estimate_vs_exact_speedup=(ms_exact / ms_step if ms_exact else None),
                workload="%s: B=%d C_in=%d C_out=%d D=H=W=%d k=%dx%dx%d pad=%d r=%d %s probes, %s storage, NCDHW" % (
                    name, B, C_in, C_out, D, k, k, k, c["pad"], r, c["probe"], dtype))
     if with_cpu:
@@ -273,7 +282,7 @@ def main():
         print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": dst.numel() * 4, "copies": 10}))
         return 0
     if args.volumetric:
-        res, flops, nbytes = measure_volume("V1", args.steps, args.warmup, dev, not args.no_cpu)
+        res, flops, nbytes = measure_volume("V1", args.steps, args.warmup, dev, not args.no_cpu, not args.no_exact)
         ach = res["corr"]["gflops"] / 1e3
         line = {
             "metric": "ms/layer for the XConv dW estimate of a 3-D layer (xconv3d_probe_fwd + xconv3d_dw_estimate), 1 GPU",
@@ -288,7 +297,7 @@ def main():
         if "cpu_baseline" in res:
             line["cpu_baseline"] = res.pop("cpu_baseline")
         torch.cuda.empty_cache()
-        r2, _, _ = measure_volume("V2", max(args.steps // 2, 10), max(args.warmup // 2, 3), dev, False)
+        r2, _, _ = measure_volume("V2", max(args.steps // 2, 10), max(args.warmup // 2, 3), dev, False, not args.no_exact)
         line["per_config"] = [r2]
         print(json.dumps(line))
         return 0
