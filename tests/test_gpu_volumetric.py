@@ -113,3 +113,45 @@ def test_volumetric_full_rank_probe_gives_the_exact_gradient():
     torch.cuda.synchronize()
     want = xo.dw_exact3d(dY, X, k, (1, 1, 1), pad)
     assert rel_max(dW.cpu().numpy().astype(np.float64), want) <= 1e-4
+
+
+# ---------------------------------------------------------------------------
+# seeded random volumes: every kernel depth, depth stride and depth padding the entry points
+# accept, with the in-plane shapes that select each of the correlation kernels
+# ---------------------------------------------------------------------------
+def _random_volumes(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        dtype = ["f32", "bf16", "f16"][rng.integers(3)]
+        kD = int([1, 2, 3, 3, 4, 5, 7][rng.integers(7)])
+        k = int([1, 3, 3, 5][rng.integers(4)])
+        sd = int([1, 1, 2, 3][rng.integers(4)])
+        s = int([1, 1, 2][rng.integers(3)])
+        pd = int(rng.integers(0, kD))
+        p = int(rng.integers(0, k // 2 + 2))
+        D = int(rng.integers(max(kD - 2 * pd, 1), 12))
+        H, W = int(rng.integers(k + 1, 14)), int(rng.integers(k + 1, 22))
+        if rng.random() < 0.6:
+            W = (W + 3) // 4 * 4
+        if (H + 2 * p - k) // s + 1 < 1 or (W + 2 * p - k) // s + 1 < 1:
+            continue
+        B = int(rng.integers(1, 6))
+        C_in = int([4, 8, 16, 32, 40][rng.integers(5)])
+        C_out = int([8, 16, 32, 48, 72][rng.integers(5)])
+        r = int([1, 4, 8, 16, 32][rng.integers(5)])
+        probe = ["rademacher", "gaussian"][rng.integers(2)]
+        keep = int([0, 0, 0, 16000][rng.integers(4)])
+        if B * D * C_out * H * W * C_in * kD > 4e7:      # keep the oracle quick
+            continue
+        out.append(("rnd%02d" % len(out), dtype, B, C_in, C_out, (D, H, W), (kD, k, k), (sd, s), (pd, p, p), r, probe, keep,
+                    bool(rng.random() < 0.5)))
+    return out
+
+
+RANDOM_VOLUMES = _random_volumes(32, 20240611)
+
+
+@pytest.mark.parametrize("e", RANDOM_VOLUMES, ids=["%s-%s" % (e[0], e[1]) for e in RANDOM_VOLUMES])
+def test_random_volumes(e):
+    run_volume(e)
