@@ -616,9 +616,13 @@ __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const f32x4 *
     // step 2) instead of a kernel launch of its own; the rest reduce.
     if ((int)blockIdx.x < zblocks) {
         const int i = blockIdx.x * kThreads + threadIdx.x;
-        if (i < nz) Zout[i] = probe_entry(probe_gen(dist, seed), (uint64_t)i);
+        if (blockIdx.y == 0 && i < nz) Zout[i] = probe_entry(probe_gen(dist, seed), (uint64_t)i);
         return;
     }
+    // blockIdx.y: one set of S partial buffers and one reduced tile per correlation launch
+    // (volumetric layers: one per kernel-depth offset), stored back to back
+    part += (size_t)blockIdx.y * S * E4;
+    T += (size_t)blockIdx.y * E4;
     __shared__ f32x4 red[16][17];
     const int ve = threadIdx.x & 15, sg = threadIdx.x >> 4;
     const int e4 = ((int)blockIdx.x - zblocks) * 16 + ve;
@@ -987,11 +991,11 @@ hipError_t launch_corr(int dtype, const CorrParams &P, hipStream_t st)
 
 static float *reduced_tile(const CorrParams &P) { return P.part + (size_t)P.S * P.K2 * P.JP * P.MP; }
 
-hipError_t launch_reduce(const CorrParams &P, hipStream_t st, float *Zout, int nz, int dist, uint64_t seed, float *T)
+hipError_t launch_reduce(const CorrParams &P, hipStream_t st, float *Zout, int nz, int dist, uint64_t seed, float *T, int nsets)
 {
     const int E4 = (int)(((size_t)P.K2 * P.JP * P.MP) / 4);
     const int zblocks = Zout ? ceil_div(nz, kThreads) : 0;
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3(zblocks + ceil_div(E4, 16)), dim3(kThreads), 0, st,
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3(zblocks + ceil_div(E4, 16), nsets), dim3(kThreads), 0, st,
                        reinterpret_cast<const f32x4 *>(P.part), reinterpret_cast<f32x4 *>(T ? T : reduced_tile(P)), P.S, E4, Zout, nz,
                        zblocks, dist, seed);
     return hipGetLastError();

@@ -43,9 +43,10 @@ hipError_t launch_corr(int dtype, const CorrParams &P, hipStream_t st);
 hipError_t launch_repack_planes(int dtype, const void *src, void *dst, long long nplanes, int n, int pitch, hipStream_t st);
 // T[o,j,m] = sum_s part[s,o,j,m]; T lives behind the S partial buffers.  Zout != nullptr: the same
 // launch also draws Z[s] (nz = C_in * r entries) from (dist, seed) into Zout.
-// T != nullptr: the reduced tile goes there instead.
+// T != nullptr: the reduced tile goes there instead.  nsets > 1: that many sets of S partial buffers, back to back
+// from P.part on, are reduced into as many tiles from T on (volumetric layers: one set per kernel-depth offset).
 hipError_t launch_reduce(const CorrParams &P, hipStream_t st, float *Zout = nullptr, int nz = 0, int dist = 0, uint64_t seed = 0,
-                         float *T = nullptr);
+                         float *T = nullptr, int nsets = 1);
 // dW[m,n,o] = (1/r) * sum_j Z[n,j] * T[o,j,m]   (Z != nullptr)
 // dW[m,n,o] = T[o,n,m]                          (Z == nullptr, exact path)
 // T != nullptr: K2 tiles [K2, JP, MP] are read from there (volumetric layers: kD * kH * kW offsets).

@@ -283,6 +283,9 @@ SliceMap vol_map(const xconv3d_desc *v, const Vol &g)
     sm.run = g.run;
     return sm;
 }
+// scratch of the correlations of a volumetric layer: kD sets of S partial tiles, then the kD reduced tiles
+size_t vol_tile_bytes(const CorrParams &P) { return (size_t)P.K2 * P.JP * P.MP * sizeof(float); }
+size_t vol_partial_bytes(const CorrParams &P, int kD) { return align_up((size_t)kD * P.S * vol_tile_bytes(P), 256); }
 // first slice of Xt (or of X in slice form) that kernel-depth offset kz pairs with slice 0 of dY
 size_t vol_offset_slices(const Vol &g, int kz) { return (size_t)(kz % g.sd) * (size_t)g.run + (size_t)(kz / g.sd); }
 // plane pitch of the slice-major copy of dY for the kernel the plan selects
@@ -489,7 +492,7 @@ size_t xconv3d_workspace_bytes(const xconv3d_desc *v, int op)
     const size_t tile = (size_t)E.P.K2 * E.P.JP * E.P.MP * sizeof(float);
     // exact: channels-last slices of X in the layout of Xt take the place of Z
     const size_t head = exact ? align_up((size_t)g.slices * d->H * d->W * CS * elem_bytes(d->dtype), 256) : z_bytes(d);
-    return head + align_up(corr_partial_bytes(E.P), 256) + align_up((size_t)v->kD * tile, 256) +
+    return head + vol_partial_bytes(E.P, v->kD) + align_up((size_t)v->kD * tile, 256) +
            align_up((size_t)g.B2 * d->C_out * vol_dy_pitch(v, E) * elem_bytes(d->dtype), 256);
 }
 
@@ -526,7 +529,7 @@ xconv_status xconv3d_dw_estimate(const xconv3d_desc *v, const void *dY_dev, cons
     const Vol g = vol_of(v);
     const int pitch = vol_dy_pitch(v, E);
     const size_t tile = (size_t)P.K2 * P.JP * P.MP * sizeof(float);
-    const size_t zb = z_bytes(d), pb = align_up(corr_partial_bytes(P), 256), tb = align_up((size_t)v->kD * tile, 256);
+    const size_t zb = z_bytes(d), pb = vol_partial_bytes(P, v->kD), tb = align_up((size_t)v->kD * tile, 256);
     const size_t yb = align_up((size_t)g.B2 * d->C_out * pitch * elem_bytes(d->dtype), 256);
     if (ws_bytes < zb + pb + tb + yb) return XCONV_EWORKSPACE;
     char *ws = static_cast<char *>(ws_dev);
@@ -540,10 +543,11 @@ xconv_status xconv3d_dw_estimate(const xconv3d_desc *v, const void *dY_dev, cons
     void *dy_slices = ws + zb + pb + tb;
     XC_LAUNCH(K_REPACK, st, launch_dy_slices(d->dtype, dY_dev, dy_slices, d->B, d->C_out, g.Do, g.period, P.Ho * P.Wo, pitch, st));
     P.dY = dy_slices;
-    P.part = reinterpret_cast<float *>(ws + zb);
+    float *part0 = reinterpret_cast<float *>(ws + zb);
     for (int kz = 0; kz < v->kD; ++kz) {
         const void *A = static_cast<const char *>(Xt_dev) + vol_offset_slices(g, kz) * g.slice_bytes;
         P.A = A;
+        P.part = part0 + (size_t)kz * P.S * (tile / sizeof(float));
         if (E.ws) {
             E.Wp.dY = P.dY;
             E.Wp.A = A;
@@ -552,10 +556,10 @@ xconv_status xconv3d_dw_estimate(const xconv3d_desc *v, const void *dY_dev, cons
         } else {
             XC_LAUNCH(K_CORR, st, launch_corr(d->dtype, P, st));
         }
-        // Z[s] for the expansion is redrawn by spare workgroups of the first reduction launch
-        XC_LAUNCH(K_REDUCE, st, launch_reduce(P, st, kz == 0 ? zw : nullptr, d->C_in * d->r, probe_code(d), d->seed,
-                                              T3 + (size_t)kz * (tile / sizeof(float))));
     }
+    // one reduction for all kernel-depth offsets; its spare workgroups redraw Z[s] for the expansion
+    P.part = part0;
+    XC_LAUNCH(K_REDUCE, st, launch_reduce(P, st, zw, d->C_in * d->r, probe_code(d), d->seed, T3, v->kD));
     XC_LAUNCH(K_EXPAND, st, launch_expand(P, Z, dW_dev, d->C_in, d->r, st, d->keep_q15 != 0, T3, v->kD * P.K2));
     return XCONV_OK;
 }
@@ -579,7 +583,7 @@ xconv_status xconv3d_dw_exact(const xconv3d_desc *v, const void *dY_dev, const v
     const int pitch = vol_dy_pitch(v, E);
     const size_t xslice = (size_t)HW * CSx * eb;
     const size_t tile = (size_t)P.K2 * P.JP * P.MP * sizeof(float);
-    const size_t xb = align_up((size_t)g.slices * xslice, 256), pb = align_up(corr_partial_bytes(P), 256);
+    const size_t xb = align_up((size_t)g.slices * xslice, 256), pb = vol_partial_bytes(P, v->kD);
     const size_t tb = align_up((size_t)v->kD * tile, 256), yb = align_up((size_t)g.B2 * d->C_out * pitch * eb, 256);
     if (ws_bytes < xb + pb + tb + yb) return XCONV_EWORKSPACE;
     char *ws = static_cast<char *>(ws_dev);
@@ -592,10 +596,11 @@ xconv_status xconv3d_dw_exact(const xconv3d_desc *v, const void *dY_dev, const v
     void *dy_slices = ws + xb + pb + tb;
     XC_LAUNCH(K_REPACK, st, launch_dy_slices(d->dtype, dY_dev, dy_slices, d->B, d->C_out, g.Do, g.period, P.Ho * P.Wo, pitch, st));
     P.dY = dy_slices;
-    P.part = reinterpret_cast<float *>(ws + xb);
+    float *part0 = reinterpret_cast<float *>(ws + xb);
     for (int kz = 0; kz < v->kD; ++kz) {
         const void *A = ws + vol_offset_slices(g, kz) * xslice;
         P.A = A;
+        P.part = part0 + (size_t)kz * P.S * (tile / sizeof(float));
         if (E.ws) {
             E.Wp.dY = P.dY;
             E.Wp.A = A;
@@ -604,8 +609,9 @@ xconv_status xconv3d_dw_exact(const xconv3d_desc *v, const void *dY_dev, const v
         } else {
             XC_LAUNCH(K_CORR, st, launch_corr(d->dtype, P, st));
         }
-        XC_LAUNCH(K_REDUCE, st, launch_reduce(P, st, nullptr, 0, 0, 0, T3 + (size_t)kz * (tile / sizeof(float))));
     }
+    P.part = part0;
+    XC_LAUNCH(K_REDUCE, st, launch_reduce(P, st, nullptr, 0, 0, 0, T3, v->kD));
     XC_LAUNCH(K_EXPAND, st, launch_expand(P, nullptr, dW_dev, d->C_in, d->r, st, false, T3, v->kD * P.K2));
     return XCONV_OK;
 }
