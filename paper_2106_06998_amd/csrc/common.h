@@ -219,6 +219,10 @@ struct WsParams {
     int NA, NA_pad;         // dY tasks per sub-step and the same rounded up to whole waves
     int TS, TB;             // A tasks per sub-step slice, per row-step (sh * BWc * J_WG/8)
     int MT, NTASK;          // 16-row tiles per consumer wave; tasks per producer thread
+    // Volumetric layers read dY [Bv, C_out, Do, Ho*Wo] in place: image i of the kernel's batch is depth
+    // slot i % vol_period of volume i / vol_period, a zero image when the slot is >= vol_Do.  0: plain dY.
+    int vol_period, vol_Do;
+    uint32_t vol_bytes;     // bytes of the whole dY tensor (below 2^30)
 };
 
 }  // namespace xc

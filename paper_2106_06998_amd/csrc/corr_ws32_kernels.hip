@@ -27,7 +27,8 @@ namespace xc {
 // and step.  D: steps whose loads are in flight.
 // OCC: workgroups per compute unit the register budget allows for (2: two consumer waves per SIMD,
 // which the fp32 MFMA needs to issue at its full rate).
-template <int NOFF, int NTASK, int D, int OCC>
+// VOL: dY is read in place as the depth slots of volumes (WsParams::vol_*)
+template <int NOFF, int NTASK, int D, int OCC, bool VOL>
 __global__ __launch_bounds__(kWsThreads, 2 * OCC) void corr_ws32_kernel(const WsParams P)
 {
     extern __shared__ uint4 ws32_lds[];
@@ -187,7 +188,11 @@ __global__ __launch_bounds__(kWsThreads, 2 * OCC) void corr_ws32_kernel(const Ws
         const float *dY = static_cast<const float *>(P.dY);
         const float *Ag = static_cast<const float *>(P.A);
         const int HoWo = P.Ho * P.Wo;
-        const uint32_t dy_img_bytes = (uint32_t)P.C_out * (uint32_t)HoWo * 4u;
+        constexpr bool vol = VOL;
+        // bytes between the planes of consecutive channels and between consecutive images of the batch
+        const uint32_t dy_plane_bytes = (uint32_t)HoWo * 4u * (vol ? (uint32_t)P.vol_Do : 1u);
+        const uint32_t dy_img_bytes = vol ? (uint32_t)HoWo * 4u : (uint32_t)P.C_out * (uint32_t)HoWo * 4u;
+        const float rcp_period = frcp(vol ? P.vol_period : 1);
         const uint32_t a_img_bytes = (uint32_t)P.H * (uint32_t)P.W * (uint32_t)P.CS * 4u;
         const int JC = P.J_WG >> 2;                                      // 4-column vectors per staged pixel
         const int jc_shift = __builtin_ctz((unsigned)JC);                // J_WG is 16, 32 or 64
@@ -210,7 +215,7 @@ __global__ __launch_bounds__(kWsThreads, 2 * OCC) void corr_ws32_kernel(const Ws
             if (is_a[k]) {
                 int ch, m;
                 fast_divmod(s, nch, rcp_nch, m, ch);
-                t_goff[k] = (s < P.NA && m0 + m < P.C_out) ? ((uint32_t)(m0 + m) * (uint32_t)HoWo + 4u * ch) * 4u : kOOR;
+                t_goff[k] = (s < P.NA && m0 + m < P.C_out) ? (uint32_t)(m0 + m) * dy_plane_bytes + 16u * ch : kOOR;
                 t_lds[k] = 4 * ch * P.M_WG + m;
                 t_aux[k] = 4 * ch;          // first column of the chunk
             } else {
@@ -256,29 +261,48 @@ __global__ __launch_bounds__(kWsThreads, 2 * OCC) void corr_ws32_kernel(const Ws
         auto issue = [&](const WsPos &ps, bool live, u32x4 (&r)[NTASK][4]) {
             const int cw = ws_cw_sub(P, ps);
             const uint32_t fs = (uint32_t)(ps.y * P.Wo + ps.strip * P.CW) * 4u;
-            const i32x4 rsA = rsrc_of(dY, ps.bg, dy_img_bytes, live);
+            // dY: byte offset of each of the group's 4 images, or kOOR for one that does not exist
+            i32x4 rsA;
+            uint32_t doff[4] = {0u, 0u, 0u, 0u};
+            if constexpr (!vol) {
+                rsA = rsrc_of(dY, ps.bg, dy_img_bytes, live);
+            } else {
+                // the whole tensor behind one resource; image -> (volume, depth slot), empty slots read as zero
+                const uint64_t addr = reinterpret_cast<uint64_t>(dY);
+                rsA.x = __builtin_amdgcn_readfirstlane((int)(uint32_t)addr);
+                rsA.y = __builtin_amdgcn_readfirstlane((int)(uint32_t)((addr >> 32) & 0xffffu));
+                rsA.z = __builtin_amdgcn_readfirstlane((int)(live ? P.vol_bytes : 0u));
+                rsA.w = 0x00020000;
+                const uint32_t vol_stride = (uint32_t)P.C_out * dy_plane_bytes;
+#pragma unroll
+                for (int img = 0; img < 4; ++img) {
+                    const int i = __builtin_amdgcn_readfirstlane(ps.bg) * 4 + img;
+                    int bv, z;
+                    fast_divmod(i, P.vol_period, rcp_period, bv, z);
+                    doff[img] = (uint32_t)__builtin_amdgcn_readfirstlane(
+                        (int)((i < P.B && z < P.vol_Do) ? (uint32_t)bv * vol_stride + (uint32_t)z * dy_img_bytes : kOOR));
+                }
+            }
             const i32x4 rsB = rsrc_of(Ag, ps.bg, a_img_bytes, live);
             const int iy0 = ps.y * P.sh + rows_old - P.ph;   // input row of the first added row
             const int ix0 = ps.strip * P.CW * P.sw - P.pw;
             const uint32_t origin = (uint32_t)(iy0 * P.W + ix0) * ((uint32_t)P.CS * 4u);  // wraps when negative; exact for every in-range pixel
 #pragma unroll
             for (int k = 0; k < NTASK; ++k) {
-                uint32_t voff;
-                uint32_t img_bytes;
-                i32x4 rs;
                 if (is_a[k]) {
-                    voff = (t_goff[k] != kOOR && t_aux[k] < cw) ? t_goff[k] + fs : kOOR;
-                    img_bytes = dy_img_bytes;
-                    rs = rsA;
+                    const uint32_t voff = (t_goff[k] != kOOR && t_aux[k] < cw) ? t_goff[k] + fs : kOOR;
+#pragma unroll
+                    for (int img = 0; img < 4; ++img) {
+                        if constexpr (!vol) buf16_async(r[k][img], rsA, voff + (uint32_t)img * dy_img_bytes);
+                        else buf16_async(r[k][img], rsA, (voff != kOOR && doff[img] != kOOR) ? voff + doff[img] : kOOR);
+                    }
                 } else {
                     const int c = t_aux[k] & 0xffff, rr = t_aux[k] >> 16;
                     const bool in = t_goff[k] != kOOR && (unsigned)(iy0 + rr) < (unsigned)P.H && (unsigned)(ix0 + c) < (unsigned)P.W;
-                    voff = in ? origin + t_goff[k] : kOOR;
-                    img_bytes = a_img_bytes;
-                    rs = rsB;
-                }
+                    const uint32_t voff = in ? origin + t_goff[k] : kOOR;
 #pragma unroll
-                for (int img = 0; img < 4; ++img) buf16_async(r[k][img], rs, voff + (uint32_t)img * img_bytes);
+                    for (int img = 0; img < 4; ++img) buf16_async(r[k][img], rsB, voff + (uint32_t)img * a_img_bytes);
+                }
             }
         };
         // the loads of a stage are followed by those of D - 1 younger stages
@@ -490,12 +514,12 @@ bool plan_corr_ws32(WsParams &P, int dtype, int B, int C_out, int H, int W, int 
     return true;
 }
 
-template <int NTASK, int D, int OCC> static hipError_t launch_ws32_cfg(const WsParams &P, hipStream_t st)
+template <int NTASK, int D, int OCC, bool VOL> static hipError_t launch_ws32_vol(const WsParams &P, hipStream_t st)
 {
     const size_t lds = corr_ws32_lds_bytes(P);
     static bool done = false;  // per instantiation: the attribute sticks to the function
     if (!done && lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(corr_ws32_kernel<9, NTASK, D, OCC>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(corr_ws32_kernel<9, NTASK, D, OCC, VOL>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kWs32LdsLimit);
         if (e != hipSuccess) return e;
         done = true;
@@ -503,8 +527,14 @@ template <int NTASK, int D, int OCC> static hipError_t launch_ws32_cfg(const WsP
     WsParams Q = P;
     Q.SQ = P.NS / P.S;
     Q.SR = P.NS % P.S;
-    hipLaunchKernelGGL((corr_ws32_kernel<9, NTASK, D, OCC>), dim3(P.S, P.NTM * P.NTJ, P.NOG), dim3(kWsThreads), lds, st, Q);
+    hipLaunchKernelGGL((corr_ws32_kernel<9, NTASK, D, OCC, VOL>), dim3(P.S, P.NTM * P.NTJ, P.NOG), dim3(kWsThreads), lds, st, Q);
     return hipGetLastError();
+}
+
+template <int NTASK, int D, int OCC> static hipError_t launch_ws32_cfg(const WsParams &P, hipStream_t st)
+{
+    if (P.vol_period != 0) return launch_ws32_vol<NTASK, D, OCC, true>(P, st);
+    return launch_ws32_vol<NTASK, D, OCC, false>(P, st);
 }
 
 hipError_t launch_corr_ws32(const WsParams &P, hipStream_t st)

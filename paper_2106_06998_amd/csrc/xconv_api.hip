@@ -1,6 +1,7 @@
 // C ABI of libxconv: argument validation, scratch layout, kernel sequencing and
 // the optional per-kernel event timing.  Declarations and their contracts are
 // in include/xconv.h.
+#include <cstdlib>
 #include <mutex>
 #include <vector>
 
@@ -283,6 +284,21 @@ SliceMap vol_map(const xconv3d_desc *v, const Vol &g)
     sm.run = g.run;
     return sm;
 }
+// The fp32 producer/consumer kernel reads the caller's dY [B, C_out, Do, H'*W'] in place (depth slots of volumes,
+// WsParams::vol_*) when its byte offsets fit; otherwise dY is first copied into slice-major planes.
+bool vol_dy_in_place(const xconv3d_desc *v, const Vol &g, PlanEntry &E, const void *dY_dev)
+{
+    const xconv_desc *d = &v->l;
+    const char *force_copy = getenv("XCONV_VOL_COPY");   // tests: take the copy route also where in-place reads fit
+    if (E.ws != 2 || !aligned16(dY_dev) || (force_copy && *force_copy == '1')) return false;
+    const long long bytes = (long long)d->B * d->C_out * g.Do * E.P.Ho * E.P.Wo * (long long)elem_bytes(d->dtype);
+    if (bytes > (1LL << 30) || g.B2 >= (1LL << 22)) return false;
+    E.Wp.vol_period = g.period;
+    E.Wp.vol_Do = g.Do;
+    E.Wp.vol_bytes = (uint32_t)bytes;
+    return true;
+}
+
 // scratch of the correlations of a volumetric layer: kD sets of S partial tiles, then the kD reduced tiles
 size_t vol_tile_bytes(const CorrParams &P) { return (size_t)P.K2 * P.JP * P.MP * sizeof(float); }
 size_t vol_partial_bytes(const CorrParams &P, int kD) { return align_up((size_t)kD * P.S * vol_tile_bytes(P), 256); }
@@ -541,8 +557,12 @@ xconv_status xconv3d_dw_estimate(const xconv3d_desc *v, const void *dY_dev, cons
     }
     float *T3 = reinterpret_cast<float *>(ws + zb + pb);
     void *dy_slices = ws + zb + pb + tb;
-    XC_LAUNCH(K_REPACK, st, launch_dy_slices(d->dtype, dY_dev, dy_slices, d->B, d->C_out, g.Do, g.period, P.Ho * P.Wo, pitch, st));
-    P.dY = dy_slices;
+    if (vol_dy_in_place(v, g, E, dY_dev)) {
+        P.dY = dY_dev;
+    } else {
+        XC_LAUNCH(K_REPACK, st, launch_dy_slices(d->dtype, dY_dev, dy_slices, d->B, d->C_out, g.Do, g.period, P.Ho * P.Wo, pitch, st));
+        P.dY = dy_slices;
+    }
     float *part0 = reinterpret_cast<float *>(ws + zb);
     for (int kz = 0; kz < v->kD; ++kz) {
         const void *A = static_cast<const char *>(Xt_dev) + vol_offset_slices(g, kz) * g.slice_bytes;
@@ -594,8 +614,12 @@ xconv_status xconv3d_dw_exact(const xconv3d_desc *v, const void *dY_dev, const v
     XC_LAUNCH(K_ZERO_GAPS, st, launch_zero_gap_slices(ws, xslice, d->B, sm, st));
     float *T3 = reinterpret_cast<float *>(ws + xb + pb);
     void *dy_slices = ws + xb + pb + tb;
-    XC_LAUNCH(K_REPACK, st, launch_dy_slices(d->dtype, dY_dev, dy_slices, d->B, d->C_out, g.Do, g.period, P.Ho * P.Wo, pitch, st));
-    P.dY = dy_slices;
+    if (vol_dy_in_place(v, g, E, dY_dev)) {
+        P.dY = dY_dev;
+    } else {
+        XC_LAUNCH(K_REPACK, st, launch_dy_slices(d->dtype, dY_dev, dy_slices, d->B, d->C_out, g.Do, g.period, P.Ho * P.Wo, pitch, st));
+        P.dY = dy_slices;
+    }
     float *part0 = reinterpret_cast<float *>(ws + xb);
     for (int kz = 0; kz < v->kD; ++kz) {
         const void *A = ws + vol_offset_slices(g, kz) * xslice;
