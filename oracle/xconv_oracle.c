@@ -337,6 +337,38 @@ void xo_correlate3d(const float *dY, const float *A, double *G,
             }
 }
 
+/* Entries idx[i] = (m, q, kz, ky, kx) of xo_correlate3d's result, one at a time (for layers too */
+/* large to correlate in full on one thread).                                                  */
+void xo_correlate3d_at(const float *dY, const float *A, const int *idx, int n, double *out,
+                       int B, int C_out, int Q, int D, int H, int W,
+                       int kD, int kH, int kW, int sd, int sh, int sw, int pd, int ph, int pw)
+{
+    int Do = xo_out_extent(D, kD, sd, pd);
+    int Ho = xo_out_extent(H, kH, sh, ph);
+    int Wo = xo_out_extent(W, kW, sw, pw);
+    (void)kD; (void)kH; (void)kW;
+    for (int i = 0; i < n; ++i) {
+        int m = idx[5 * i], q = idx[5 * i + 1], kz = idx[5 * i + 2], ky = idx[5 * i + 3], kx = idx[5 * i + 4];
+        double s = 0.0;
+        for (int b = 0; b < B; ++b)
+          for (int oz = 0; oz < Do; ++oz) {
+              int iz = oz * sd + kz - pd;
+              if (iz < 0 || iz >= D) continue;
+              for (int oy = 0; oy < Ho; ++oy) {
+                  int iy = oy * sh + ky - ph;
+                  if (iy < 0 || iy >= H) continue;
+                  for (int ox = 0; ox < Wo; ++ox) {
+                      int ix = ox * sw + kx - pw;
+                      if (ix < 0 || ix >= W) continue;
+                      s += (double)dY[((((size_t)b * C_out + m) * Do + oz) * Ho + oy) * Wo + ox] *
+                           (double)A[((((size_t)b * Q + q) * D + iz) * H + iy) * W + ix];
+                  }
+              }
+          }
+        out[i] = s;
+    }
+}
+
 /* ------------------------------------------------------------------------ */
 /* Selected entries of the estimate, for layers too large to do in full.     */
 /* idx[4*t..4*t+3] = (m, n, ky, kx); out[t] = dW_est[m,n,ky,kx].             */

@@ -65,6 +65,8 @@ def lib():
         L.xo_conv_fwd.restype = None
         L.xo_correlate3d.restype = None
         L.xo_correlate3d.argtypes = [_c_f32p, _c_f32p, _c_f64p] + [ctypes.c_int] * 15
+        L.xo_correlate3d_at.restype = None
+        L.xo_correlate3d_at.argtypes = [_c_f32p, _c_f32p, _c_i32p, ctypes.c_int, _c_f64p] + [ctypes.c_int] * 15
         L.xo_conv_fwd.argtypes = [_c_f32p, _c_f64p, _c_f64p] + [ctypes.c_int] * 11
         _LIB = L
     return _LIB
@@ -259,3 +261,33 @@ def dw_from_xt3d(dY, Xt, Z, k, stride=(1, 1, 1), pad=(0, 0, 0), nnz_norm=False):
     G = correlate3d(dY, Xt, k, stride, pad)
     C_out, r, kD, kH, kW = G.shape
     return expand(G.reshape(C_out, r, kD * kH, kW), Z, nnz_norm).reshape(C_out, -1, kD, kH, kW)
+
+
+def correlate3d_at(dY, A, idx, k, stride=(1, 1, 1), pad=(0, 0, 0)):
+    """Entries idx[i] = (m, q, kz, ky, kx) of correlate3d's result."""
+    dY, dYp = _f32(dY)
+    A, Ap = _f32(A)
+    idx = np.ascontiguousarray(idx, dtype=np.int32).reshape(-1, 5)
+    B, C_out = dY.shape[:2]
+    _, Q, D, H, W = A.shape
+    out = np.empty(idx.shape[0], dtype=np.float64)
+    lib().xo_correlate3d_at(dYp, Ap, idx.ctypes.data_as(_c_i32p), idx.shape[0], out.ctypes.data_as(_c_f64p),
+                            B, C_out, Q, D, H, W, k[0], k[1], k[2], stride[0], stride[1], stride[2], pad[0], pad[1], pad[2])
+    return out
+
+
+def dw_exact3d_at(dY, X, idx, k, stride=(1, 1, 1), pad=(0, 0, 0)):
+    """Entries idx[i] = (m, n, kz, ky, kx) of the exact 3-D gradient."""
+    return correlate3d_at(dY, X, idx, k, stride, pad)
+
+
+def dw_from_xt3d_at(dY, Xt, Z, idx, k, stride=(1, 1, 1), pad=(0, 0, 0)):
+    """Entries idx[i] = (m, n, kz, ky, kx) of dw_from_xt3d: (1/r) sum_j Z[n,j] G[m,j,kz,ky,kx]
+    (Eq. (6) step (iii)) with the r entries of G each sample needs."""
+    idx = np.ascontiguousarray(idx, dtype=np.int32).reshape(-1, 5)
+    Z = np.asarray(Z, dtype=np.float64)
+    r = Z.shape[1]
+    gi = np.repeat(idx, r, axis=0)
+    gi[:, 1] = np.tile(np.arange(r, dtype=np.int32), idx.shape[0])
+    G = correlate3d_at(dY, Xt, gi, k, stride, pad).reshape(idx.shape[0], r)
+    return np.einsum("ij,ij->i", Z[idx[:, 1]], G) / r

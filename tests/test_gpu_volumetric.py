@@ -165,3 +165,58 @@ RANDOM_VOLUMES = _random_volumes(32, 20240611)
 @pytest.mark.parametrize("e", RANDOM_VOLUMES, ids=["%s-%s" % (e[0], e[1]) for e in RANDOM_VOLUMES])
 def test_random_volumes(e):
     run_volume(e)
+
+
+# ---------------------------------------------------------------------------
+# the volumetric benchmark layers at full size, in the launch configuration bench.py times
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("name", ["V1", "V2"])
+def test_volumetric_full_size_sampled(name):
+    import bench
+    c = bench.VOLUMES[name]
+    B, C_in, C_out, dims, k, r, dtype = c["B"], c["C_in"], c["C_out"], c["dims"], c["k"], c["r"], c["dtype"]
+    D, H, W = dims
+    k3, one, pad = (k, k, k), (1, 1, 1), (c["pad"],) * 3
+    say("%s full size, sampled entries" % name)
+    X, dY = synth.make_volume(B, C_in, C_out, dims, dims, c["seeds"], dtype)
+    Z = xo.probe_matrix(OPROBE[c["probe"]], c["seeds"][2], C_in, r)
+    v = xb.make_desc3d(B, C_in, C_out, D, H, W, k, 1, c["pad"], r, dtype, c["probe"], c["seeds"][2])
+    Xd, dYd = xb.to_device(X, dtype, DEV), xb.to_device(dY, dtype, DEV)
+    Xt = xb.alloc_bytes(xb.xconv3d_xt_bytes(v), DEV)
+    ws = xb.alloc_bytes(xb.xconv3d_workspace_bytes(v, xb.XCONV_OP_ESTIMATE), DEV)
+    xb.xconv3d_probe_fwd(v, Xd, Xt, None, ws)                       # Z from the seed, as the bench does
+    dW = torch.full((C_out, C_in) + k3, float("nan"), dtype=torch.float32, device=DEV)
+    xb.xconv3d_dw_estimate(v, dYd, Xt, None, dW, ws)
+    dWx = torch.full_like(dW, float("nan"))
+    xb.xconv3d_dw_exact(v, dYd, Xd, dWx, xb.alloc_bytes(xb.xconv3d_workspace_bytes(v, xb.XCONV_OP_EXACT), DEV))
+    xt_g = torch.empty((B, r, D, H, W), dtype=torch.float32, device=DEV)
+    xb.xconv3d_xt_unpack(v, Xt, xt_g)
+    torch.cuda.synchronize()
+    got, got_x, xt_g = dW.cpu().numpy().astype(np.float64), dWx.cpu().numpy().astype(np.float64), xt_g.cpu().numpy()
+    assert np.all(np.isfinite(got)) and np.all(np.isfinite(got_x))
+    say("%s oracle probe" % name)
+    xt_o = xo.probe_fwd3d(X, Z, ODT[dtype])
+    scale = np.max(np.abs(xt_o))
+    if dtype == "f32":
+        assert np.max(np.abs(xt_g - xt_o)) <= 2e-6 * scale
+    else:
+        tol = 2.0 * ULP[dtype] * np.maximum(np.abs(xt_o), 2.0 ** -14) + 1e-6 * scale
+        assert not (np.abs(xt_g - xt_o) > tol).any()
+    rng = np.random.default_rng(6)
+    n = 32
+    idx = np.stack([rng.integers(0, C_out, n), rng.integers(0, C_in, n), rng.integers(0, k, n), rng.integers(0, k, n),
+                    rng.integers(0, k, n)], axis=1).astype(np.int32)
+    idx[0] = (0, 0, 0, 0, 0)
+    idx[1] = (C_out - 1, C_in - 1, k - 1, k - 1, k - 1)
+    say("%s oracle samples" % name)
+    want = xo.dw_from_xt3d_at(dY, xt_o, Z, idx, k3, one, pad)
+    g = np.array([got[tuple(i)] for i in idx])
+    assert np.max(np.abs(want)) <= 1.05 * np.max(np.abs(got))
+    assert np.max(np.abs(g - want)) <= GRAD_TOL[dtype] * np.max(np.abs(want)), (np.max(np.abs(g - want)), np.max(np.abs(want)))
+    wx = xo.dw_exact3d_at(dY, X, idx, k3, one, pad)
+    gx = np.array([got_x[tuple(i)] for i in idx])
+    assert np.max(np.abs(gx - wx)) <= GRAD_TOL[dtype] * np.max(np.abs(wx))
+    # property that holds at any size: the estimate is the exact gradient mixed by Z Z^T / r
+    G = Z.astype(np.float64) @ Z.astype(np.float64).T / r
+    mixed = np.einsum("nq,mqzyx->mnzyx", G, got_x)
+    assert rel_max(got, mixed) <= 2 * GRAD_TOL[dtype]

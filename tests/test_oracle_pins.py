@@ -550,3 +550,18 @@ def test_3d_estimate_with_a_full_rank_orthogonal_probe_is_exact():
     est = xo.dw_from_xt3d(dY, Xt, Zh, k, stride, pad)
     exact = xo.dw_exact3d(dY, X, k, stride, pad)
     assert np.max(np.abs(est - exact)) <= 1e-5 * np.max(np.abs(exact))
+
+
+def test_sampled_3d_entries_match_the_full_routines():
+    shape = VOL_SHAPES[1]
+    B, C_in, C_out, dims, k, stride, pad = shape
+    X, dY = _vol(34, *shape)
+    r = 3
+    Z = xo.probe_matrix(xo.GAUSSIAN, 9, C_in, r)
+    Xt = xo.probe_fwd3d(X, Z, xo.F32)
+    full_x = xo.dw_exact3d(dY, X, k, stride, pad)
+    full_e = xo.dw_from_xt3d(dY, Xt, Z, k, stride, pad)
+    idx = np.array([(m, n, kz, ky, kx) for m in range(C_out) for n in range(C_in)
+                    for kz in range(k[0]) for ky in range(k[1]) for kx in range(k[2])], dtype=np.int32)
+    assert np.allclose(xo.dw_exact3d_at(dY, X, idx, k, stride, pad), full_x.reshape(-1), rtol=1e-13, atol=0)
+    assert np.allclose(xo.dw_from_xt3d_at(dY, Xt, Z, idx, k, stride, pad), full_e.reshape(-1), rtol=1e-12, atol=1e-300)
