@@ -177,8 +177,10 @@ xconv_status xconv3d_check_desc(const xconv3d_desc *desc);
  * index modulo stride_d) and of the scratch of an op
  * (xconv_op); 0 for an invalid desc.  The scratch of the two gradient ops
  * includes room for a slice-major copy of dY, which is made (one extra read and
- * write of dY) unless the correlation kernel can read dY in place: fp32 storage,
- * W' a multiple of 4, dY 16-byte aligned and smaller than 1 GiB. */
+ * write of dY) unless the correlation kernel can read dY in place: a layer the
+ * producer/consumer kernels take (fp32 with W' a multiple of 4; 16-bit storage with
+ * W' even and r a multiple of 32; kernels larger than 1x1), dY 16-byte aligned and
+ * smaller than 1 GiB. */
 size_t xconv3d_xt_bytes(const xconv3d_desc *desc);
 size_t xconv3d_workspace_bytes(const xconv3d_desc *desc, int op);
 

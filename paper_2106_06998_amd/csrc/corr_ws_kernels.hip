@@ -49,7 +49,8 @@ template <int DT> __device__ inline f32x16 mfma32(const uint4 &a, const uint4 &b
 
 // CB > 0: 3x3 offsets and the bytes of one staged column of A (BSTR * 16) known at compile time:
 // the three column offsets of a kernel row are then immediates of one address register.
-template <int DT, int NOFF, int NTASK, int D, int CB, bool RU>
+// VOL: dY is read in place as the depth slots of volumes (WsParams::vol_*)
+template <int DT, int NOFF, int NTASK, int D, int CB, bool RU, bool VOL>
 __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
 {
     extern __shared__ uint4 ws_lds[];
@@ -430,7 +431,11 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
         const uint16_t *dY = static_cast<const uint16_t *>(P.dY);
         const uint16_t *Ag = static_cast<const uint16_t *>(P.A);
         const int HoWo = P.Ho * P.Wo;
-        const uint32_t dy_img_bytes = (uint32_t)P.C_out * (uint32_t)HoWo * 2u;
+        constexpr bool vol = VOL;
+        // bytes between the planes of consecutive channels and between consecutive images of the batch
+        const uint32_t dy_plane_bytes = (uint32_t)HoWo * 2u * (vol ? (uint32_t)P.vol_Do : 1u);
+        const uint32_t dy_img_bytes = vol ? (uint32_t)HoWo * 2u : (uint32_t)P.C_out * (uint32_t)HoWo * 2u;
+        const float rcp_period = frcp(vol ? P.vol_period : 1);
         const uint32_t a_img_bytes = (uint32_t)P.H * (uint32_t)P.W * (uint32_t)P.CS * 2u;
         const int JC = P.J_WG >> 3;
         const int jc_shift = __builtin_ctz((unsigned)JC);  // J_WG is 32, 64 or 128
@@ -450,7 +455,7 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
             const int nch = (P.CWs + 7) >> 3;
             int ch, m;
             fast_divmod(s, nch, frcp(nch), m, ch);
-            a_goff[k] = (s < P.NA && m0 + m < P.C_out) ? ((uint32_t)(m0 + m) * (uint32_t)HoWo + 8u * ch) * 2u : kOOR;
+            a_goff[k] = (s < P.NA && m0 + m < P.C_out) ? (uint32_t)(m0 + m) * dy_plane_bytes + 16u * ch : kOOR;
             a_lds[k] = 8 * ch * P.M_WG + m;
             a_c8[k] = 8 * ch;
             b_w[k] = s - P.NA_pad;
@@ -588,7 +593,28 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
         auto issue = [&](const WsPos &ps, bool live, u32x4 (&r)[NTASK][8]) {
             const int cw_sub = ws_cw_sub(P, ps);
             const uint32_t fs = (uint32_t)(ps.y * P.Wo + ps.strip * P.CW + ps.u * P.CWs) * 2u;
-            const i32x4 rsA = rsrc_of(dY, ps.bg, dy_img_bytes, live);
+            // dY: byte offset of each of the group's 8 images, or kOOR for one that does not exist
+            i32x4 rsA;
+            uint32_t doff[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+            if constexpr (!vol) {
+                rsA = rsrc_of(dY, ps.bg, dy_img_bytes, live);
+            } else {
+                // the whole tensor behind one resource; image -> (volume, depth slot), empty slots read as zero
+                const uint64_t addr = reinterpret_cast<uint64_t>(dY);
+                rsA.x = __builtin_amdgcn_readfirstlane((int)(uint32_t)addr);
+                rsA.y = __builtin_amdgcn_readfirstlane((int)(uint32_t)((addr >> 32) & 0xffffu));
+                rsA.z = __builtin_amdgcn_readfirstlane((int)(live ? P.vol_bytes : 0u));
+                rsA.w = 0x00020000;
+                const uint32_t vol_stride = (uint32_t)P.C_out * dy_plane_bytes;
+#pragma unroll
+                for (int img = 0; img < 8; ++img) {
+                    const int i = __builtin_amdgcn_readfirstlane(ps.bg) * 8 + img;
+                    int bv, z;
+                    fast_divmod(i, P.vol_period, rcp_period, bv, z);
+                    doff[img] = (uint32_t)__builtin_amdgcn_readfirstlane(
+                        (int)((i < P.B && z < P.vol_Do) ? (uint32_t)bv * vol_stride + (uint32_t)z * dy_img_bytes : kOOR));
+                }
+            }
             const XtPlan x = xt_plan(ps);
             const i32x4 rsB = rsrc_of(Ag, ps.bg, a_img_bytes, live && x.on);
 #pragma unroll
@@ -596,7 +622,10 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
                 if (is_a[k]) {
                     const uint32_t voff = (a_goff[k] != kOOR && a_c8[k] < cw_sub) ? a_goff[k] + fs : kOOR;
 #pragma unroll
-                    for (int img = 0; img < 8; ++img) buf16_async(r[k][img], rsA, voff + (uint32_t)img * dy_img_bytes);
+                    for (int img = 0; img < 8; ++img) {
+                        if constexpr (!vol) buf16_async(r[k][img], rsA, voff + (uint32_t)img * dy_img_bytes);
+                        else buf16_async(r[k][img], rsA, (voff != kOOR && doff[img] != kOOR) ? voff + doff[img] : kOOR);
+                    }
                 } else {
                     const uint32_t goff = x.slice ? x_goff[k][1] : x_goff[k][0];
                     const int crr = x.slice ? x_crr[k][1] : x_crr[k][0];
@@ -871,13 +900,13 @@ bool plan_corr_ws(WsParams &P, int dtype, int B, int C_out, int H, int W, int kH
     return true;
 }
 
-template <int DT, int NTASK, int D, int CB, bool RU>
-static hipError_t launch_ws_cfg(const WsParams &P, hipStream_t st)
+template <int DT, int NTASK, int D, int CB, bool RU, bool VOL>
+static hipError_t launch_ws_vol(const WsParams &P, hipStream_t st)
 {
     const size_t lds = corr_ws_lds_bytes(P);
     static bool done = false;  // per instantiation: the attribute sticks to the function
     if (!done && lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(corr_ws_kernel<DT, 9, NTASK, D, CB, RU>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(corr_ws_kernel<DT, 9, NTASK, D, CB, RU, VOL>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kWsLdsLimit);
         if (e != hipSuccess) return e;
         done = true;
@@ -885,8 +914,15 @@ static hipError_t launch_ws_cfg(const WsParams &P, hipStream_t st)
     WsParams Q = P;
     Q.SQ = P.NS / P.S;
     Q.SR = P.NS % P.S;
-    hipLaunchKernelGGL((corr_ws_kernel<DT, 9, NTASK, D, CB, RU>), dim3(P.S, P.NTM * P.NTJ, P.NOG), dim3(kWsThreads), lds, st, Q);
+    hipLaunchKernelGGL((corr_ws_kernel<DT, 9, NTASK, D, CB, RU, VOL>), dim3(P.S, P.NTM * P.NTJ, P.NOG), dim3(kWsThreads), lds, st, Q);
     return hipGetLastError();
+}
+
+template <int DT, int NTASK, int D, int CB, bool RU>
+static hipError_t launch_ws_cfg(const WsParams &P, hipStream_t st)
+{
+    if (P.vol_period != 0) return launch_ws_vol<DT, NTASK, D, CB, RU, true>(P, st);
+    return launch_ws_vol<DT, NTASK, D, CB, RU, false>(P, st);
 }
 
 template <int DT> static hipError_t launch_ws_dt(const WsParams &P, hipStream_t st)

@@ -284,13 +284,13 @@ SliceMap vol_map(const xconv3d_desc *v, const Vol &g)
     sm.run = g.run;
     return sm;
 }
-// The fp32 producer/consumer kernel reads the caller's dY [B, C_out, Do, H'*W'] in place (depth slots of volumes,
+// The producer/consumer kernels read the caller's dY [B, C_out, Do, H'*W'] in place (depth slots of volumes,
 // WsParams::vol_*) when its byte offsets fit; otherwise dY is first copied into slice-major planes.
 bool vol_dy_in_place(const xconv3d_desc *v, const Vol &g, PlanEntry &E, const void *dY_dev)
 {
     const xconv_desc *d = &v->l;
     const char *force_copy = getenv("XCONV_VOL_COPY");   // tests: take the copy route also where in-place reads fit
-    if (E.ws != 2 || !aligned16(dY_dev) || (force_copy && *force_copy == '1')) return false;
+    if (E.ws == 0 || !aligned16(dY_dev) || (force_copy && *force_copy == '1')) return false;
     const long long bytes = (long long)d->B * d->C_out * g.Do * E.P.Ho * E.P.Wo * (long long)elem_bytes(d->dtype);
     if (bytes > (1LL << 30) || g.B2 >= (1LL << 22)) return false;
     E.Wp.vol_period = g.period;

@@ -92,9 +92,9 @@ def test_volumetric_layers(e):
     run_volume(e)
 
 
-@pytest.mark.parametrize("e", [VOL[0], VOL[5]], ids=[VOL[0][0], VOL[5][0]])
+@pytest.mark.parametrize("e", [VOL[0], VOL[2], VOL[5]], ids=[VOL[0][0], VOL[2][0], VOL[5][0]])
 def test_volumetric_layers_through_the_dy_copy(e, monkeypatch):
-    # fp32 layers whose dY the correlation kernel reads in place by default: the slice-major copy gives the same
+    # layers whose dY the correlation kernel reads in place by default: the slice-major copy gives the same
     monkeypatch.setenv("XCONV_VOL_COPY", "1")
     _, a = run_volume(e)
     monkeypatch.delenv("XCONV_VOL_COPY")
