@@ -369,6 +369,71 @@ void xo_correlate3d_at(const float *dY, const float *A, const int *idx, int n, d
     }
 }
 
+/* ------------------------------------------------------------------------- */
+/* The estimator as the paper states it: probing vectors over the stacked     */
+/* pixel x channel space (Sec. 3 multi-channel case, Eq. (6); Algorithm 1).    */
+/* Z is [C_in*N, r] with row (n, q) = n*N + q (N = H*W pixels), entries in the */
+/* storage type (the products run in it).                                       */
+/*   forward   Xbar[b,j] = sum_{n,q} Z[(n,q),j] X[b,n,q]          (fp32 kept)   */
+/*   backward  L[j,m,p]  = (1/r) sum_b Xbar[b,j] dY[b,m,p], rounded once to     */
+/*                         the storage type (it is the operand of the shifted   */
+/*                         product that follows)                                 */
+/*             dw[m,n,ky,kx] = sum_j sum_{oy,ox} L[j,m,oy,ox]                    */
+/*                                 * Z[(n, (oy*sh+ky-ph, ox*sw+kx-pw)), j]       */
+/* which is dw_i = (1/r) tr(L T_{-k(i)} Z) with zero padding in place of the    */
+/* circular shift.                                                               */
+/* ------------------------------------------------------------------------- */
+void xo_pixel_probe_fwd(const float *X, const float *Z, float *Xbar, int B, int C_in, int H, int W, int r)
+{
+    size_t K = (size_t)C_in * H * W;
+    for (int b = 0; b < B; ++b)
+        for (int j = 0; j < r; ++j) {
+            double s = 0.0;
+            for (size_t k = 0; k < K; ++k) s += (double)Z[k * r + j] * (double)X[(size_t)b * K + k];
+            Xbar[(size_t)b * r + j] = (float)s;
+        }
+}
+
+void xo_pixel_dw_estimate(const float *dY, const float *Xbar, const float *Z, double *dW,
+                          int B, int C_in, int C_out, int H, int W, int r,
+                          int kH, int kW, int sh, int sw, int ph, int pw, int dtype)
+{
+    int Ho = xo_out_extent(H, kH, sh, ph);
+    int Wo = xo_out_extent(W, kW, sw, pw);
+    size_t P = (size_t)C_out * Ho * Wo, N = (size_t)H * W;
+    float *L = (float *)malloc((size_t)r * P * sizeof(float));
+    for (int j = 0; j < r; ++j)
+        for (size_t p = 0; p < P; ++p) {
+            double s = 0.0;
+            for (int b = 0; b < B; ++b) {
+                /* the scaled coefficient Xbar / r is formed in single precision, as the stored state is */
+                float c = Xbar[(size_t)b * r + j] * (1.0f / (float)r);
+                s += (double)c * (double)dY[(size_t)b * P + p];
+            }
+            L[(size_t)j * P + p] = (float)xo_round_storage(s, dtype);
+        }
+    for (int m = 0; m < C_out; ++m)
+      for (int n = 0; n < C_in; ++n)
+        for (int ky = 0; ky < kH; ++ky)
+          for (int kx = 0; kx < kW; ++kx) {
+              double s = 0.0;
+              for (int j = 0; j < r; ++j)
+                for (int oy = 0; oy < Ho; ++oy) {
+                    int iy = oy * sh + ky - ph;
+                    if (iy < 0 || iy >= H) continue;
+                    for (int ox = 0; ox < Wo; ++ox) {
+                        int ix = ox * sw + kx - pw;
+                        if (ix < 0 || ix >= W) continue;
+                        double l = L[(size_t)j * P + ((size_t)m * Ho + oy) * Wo + ox];
+                        double z = Z[((size_t)n * N + (size_t)iy * W + ix) * r + j];
+                        s += l * z;
+                    }
+                }
+              dW[(((size_t)m * C_in + n) * kH + ky) * kW + kx] = s;
+          }
+    free(L);
+}
+
 /* ------------------------------------------------------------------------ */
 /* Selected entries of the estimate, for layers too large to do in full.     */
 /* idx[4*t..4*t+3] = (m, n, ky, kx); out[t] = dW_est[m,n,ky,kx].             */

@@ -67,6 +67,10 @@ def lib():
         L.xo_correlate3d.argtypes = [_c_f32p, _c_f32p, _c_f64p] + [ctypes.c_int] * 15
         L.xo_correlate3d_at.restype = None
         L.xo_correlate3d_at.argtypes = [_c_f32p, _c_f32p, _c_i32p, ctypes.c_int, _c_f64p] + [ctypes.c_int] * 15
+        L.xo_pixel_probe_fwd.restype = None
+        L.xo_pixel_probe_fwd.argtypes = [_c_f32p, _c_f32p, _c_f32p] + [ctypes.c_int] * 5
+        L.xo_pixel_dw_estimate.restype = None
+        L.xo_pixel_dw_estimate.argtypes = [_c_f32p, _c_f32p, _c_f32p, _c_f64p] + [ctypes.c_int] * 13
         L.xo_conv_fwd.argtypes = [_c_f32p, _c_f64p, _c_f64p] + [ctypes.c_int] * 11
         _LIB = L
     return _LIB
@@ -291,3 +295,40 @@ def dw_from_xt3d_at(dY, Xt, Z, idx, k, stride=(1, 1, 1), pad=(0, 0, 0)):
     gi[:, 1] = np.tile(np.arange(r, dtype=np.int32), idx.shape[0])
     G = correlate3d_at(dY, Xt, gi, k, stride, pad).reshape(idx.shape[0], r)
     return np.einsum("ij,ij->i", Z[idx[:, 1]], G) / r
+
+
+# ---- the estimator with probing vectors over pixels and channels (Eq. (6), Algorithm 1 as stated) ----
+def pixel_probe_matrix(dist, seed, C_in, H, W, r, dtype=F32):
+    """Z [C_in*H*W, r], row (n, q) = n*H*W + q, from the same generator as the channel probes
+    (entry index = row * r + j), rounded to the storage type the products run in."""
+    Z = probe_matrix(dist, seed, C_in * H * W, r)
+    if dtype != F32:
+        Z = np.array([round_storage(v, dtype) for v in Z.reshape(-1)], dtype=np.float32).reshape(Z.shape)
+    return Z
+
+
+def pixel_probe_fwd(X, Z):
+    """Xbar [B, r] = Z^T X over the stacked pixel x channel axis (Alg. 1 forward step 3), fp32."""
+    X, Xp = _f32(X)
+    Z, Zp = _f32(Z)
+    B, C_in, H, W = X.shape
+    r = Z.shape[1]
+    assert Z.shape[0] == C_in * H * W
+    Xbar = np.empty((B, r), dtype=np.float32)
+    lib().xo_pixel_probe_fwd(Xp, Zp, Xbar.ctypes.data_as(_c_f32p), B, C_in, H, W, r)
+    return Xbar
+
+
+def pixel_dw_estimate(dY, Xbar, Z, C_in, H, W, kH, kW, stride=(1, 1), pad=(0, 0), dtype=F32):
+    """dw_i = (1/r) tr(L T_{-k(i)} Z), L = Xbar^T dY rounded to the storage type (Alg. 1 backward)."""
+    dY, dYp = _f32(dY)
+    Xbar, Xbp = _f32(Xbar)
+    Z, Zp = _f32(Z)
+    B, C_out, Ho, Wo = dY.shape
+    r = Z.shape[1]
+    assert Xbar.shape == (B, r) and Z.shape[0] == C_in * H * W
+    assert Ho == out_extent(H, kH, stride[0], pad[0]) and Wo == out_extent(W, kW, stride[1], pad[1])
+    dW = np.empty((C_out, C_in, kH, kW), dtype=np.float64)
+    lib().xo_pixel_dw_estimate(dYp, Xbp, Zp, dW.ctypes.data_as(_c_f64p), B, C_in, C_out, H, W, r,
+                               kH, kW, stride[0], stride[1], pad[0], pad[1], dtype)
+    return dW

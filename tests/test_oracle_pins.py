@@ -565,3 +565,83 @@ def test_sampled_3d_entries_match_the_full_routines():
                     for kz in range(k[0]) for ky in range(k[1]) for kx in range(k[2])], dtype=np.int32)
     assert np.allclose(xo.dw_exact3d_at(dY, X, idx, k, stride, pad), full_x.reshape(-1), rtol=1e-13, atol=0)
     assert np.allclose(xo.dw_from_xt3d_at(dY, Xt, Z, idx, k, stride, pad), full_e.reshape(-1), rtol=1e-12, atol=1e-300)
+
+
+# ---------------------------------------------------------------------------
+# the estimator with probing vectors over pixels and channels (Eq. (6) as stated)
+# ---------------------------------------------------------------------------
+def _pixel_case(seed, B=3, C_in=2, C_out=3, H=5, W=4, k=(3, 2), stride=(1, 2), pad=(1, 1)):
+    rng = np.random.default_rng(seed)
+    Ho, Wo = xo.out_extent(H, k[0], stride[0], pad[0]), xo.out_extent(W, k[1], stride[1], pad[1])
+    X = rng.standard_normal((B, C_in, H, W)).astype(np.float32)
+    dY = rng.standard_normal((B, C_out, Ho, Wo)).astype(np.float32)
+    return X, dY, k, stride, pad
+
+
+def test_pixel_probe_estimator_matches_its_matrix_form():
+    # Eq. (6) written with explicit shift matrices: dw_i^{m,n} = (1/r) tr(L^m T_{-k(i)} Z_n),
+    # L^m = Xbar^T dY^m, the shift as a 0/1 matrix with zero padding
+    X, dY, k, stride, pad = _pixel_case(41)
+    B, C_in, H, W = X.shape
+    C_out, Ho, Wo = dY.shape[1:]
+    r, N, Np = 5, H * W, Ho * Wo
+    Z = xo.pixel_probe_matrix(xo.GAUSSIAN, 17, C_in, H, W, r)
+    Xbar = xo.pixel_probe_fwd(X, Z)
+    assert np.allclose(Xbar, X.reshape(B, -1).astype(np.float64) @ Z.astype(np.float64), rtol=1e-6, atol=1e-6)
+    got = xo.pixel_dw_estimate(dY, Xbar, Z, C_in, H, W, k[0], k[1], stride, pad)
+    Zb = Z.astype(np.float64).reshape(C_in, N, r)
+    coef = (Xbar * np.float32(1.0 / r)).astype(np.float64)
+    for m in range(C_out):
+        L = coef.T @ dY[:, m].reshape(B, Np).astype(np.float64)             # r x N'
+        for n in range(C_in):
+            for ky in range(k[0]):
+                for kx in range(k[1]):
+                    T = np.zeros((Np, N))                                      # T[p', q] = 1 if output pixel p' reads input pixel q
+                    for oy in range(Ho):
+                        for ox in range(Wo):
+                            iy, ix = oy * stride[0] + ky - pad[0], ox * stride[1] + kx - pad[1]
+                            if 0 <= iy < H and 0 <= ix < W:
+                                T[oy * Wo + ox, iy * W + ix] = 1.0
+                    want = np.trace(L @ T @ Zb[n])
+                    assert abs(got[m, n, ky, kx] - want) <= 1e-6 * max(1.0, abs(want))     # L is rounded to fp32 storage
+
+
+def test_pixel_probe_with_an_orthogonal_full_rank_probe_is_exact():
+    # r = C_in*N probing vectors with Z Z^T = r I: every trace is probed exactly
+    X, dY, k, stride, pad = _pixel_case(42, B=2, C_in=2, C_out=2, H=4, W=4)
+    B, C_in, H, W = X.shape
+    K = C_in * H * W                                                         # 32: a Sylvester Hadamard matrix exists
+    Hd = np.array([[1.0]])
+    while Hd.shape[0] < K:
+        Hd = np.block([[Hd, Hd], [Hd, -Hd]])
+    Z = Hd.astype(np.float32)
+    est = xo.pixel_dw_estimate(dY, xo.pixel_probe_fwd(X, Z), Z, C_in, H, W, k[0], k[1], stride, pad)
+    exact = xo.dw_exact(dY, X, k[0], k[1], stride, pad)
+    assert np.max(np.abs(est - exact)) <= 1e-5 * np.max(np.abs(exact))
+
+
+def test_pixel_probe_estimator_is_unbiased():
+    X, dY, k, stride, pad = _pixel_case(43, B=4, C_in=2, C_out=2, H=6, W=6, k=(3, 3), stride=(1, 1), pad=(1, 1))
+    C_in, H, W = X.shape[1:]
+    exact = xo.dw_exact(dY, X, 3, 3, stride, pad)
+    S_list, errs, acc, done = [8, 32, 128, 512], [], np.zeros_like(exact), 0
+    for S in S_list:
+        while done < S:
+            Z = xo.pixel_probe_matrix(xo.RADEMACHER, 500000 + done, C_in, H, W, 8)
+            acc += xo.pixel_dw_estimate(dY, xo.pixel_probe_fwd(X, Z), Z, C_in, H, W, 3, 3, stride, pad)
+            done += 1
+        errs.append(np.linalg.norm(acc / S - exact) / np.linalg.norm(exact))
+    slope = np.polyfit(np.log(S_list), np.log(errs), 1)[0]
+    assert -0.65 < slope < -0.35, (slope, errs)
+
+
+def test_pixel_probe_rounds_the_outer_product_to_the_storage_type():
+    X, dY, k, stride, pad = _pixel_case(44)
+    C_in, H, W = X.shape[1:]
+    Z = xo.pixel_probe_matrix(xo.GAUSSIAN, 3, C_in, H, W, 4, xo.BF16)
+    assert np.array_equal(Z, np.array([xo.round_storage(v, xo.BF16) for v in Z.reshape(-1)], dtype=np.float32).reshape(Z.shape))
+    Xbar = xo.pixel_probe_fwd(X, Z)
+    a = xo.pixel_dw_estimate(dY, Xbar, Z, C_in, H, W, k[0], k[1], stride, pad, xo.F32)
+    b = xo.pixel_dw_estimate(dY, Xbar, Z, C_in, H, W, k[0], k[1], stride, pad, xo.BF16)
+    rel = np.max(np.abs(a - b)) / np.max(np.abs(a))
+    assert 0 < rel < 2.0 ** -6            # bf16 keeps 8 bits: the rounding shows, and stays at its size
