@@ -204,6 +204,30 @@ xconv_status xconv3d_dw_exact(const xconv3d_desc *desc, const void *dY_dev, cons
 /* Test helper: writes the stored Xt as plain fp32 [B,r,D,H,W] into out_dev. */
 xconv_status xconv3d_xt_unpack(const xconv3d_desc *desc, const void *Xt_dev, float *out_dev, void *stream);
 
+/* ---- probing vectors over pixels and channels ----------------------------------
+ * The estimator as the paper states it (Sec. 3 multi-channel case, Eq. (6); Algorithm
+ * 1): r probing vectors of length K = C_in*H*W, Z [K, r] with row (n, y, x) =
+ * (n*H + y)*W + x, drawn from (probe, seed) and never handed over; entry (k, j) is
+ * word k*r + j of the generator xconv_probe_matrix documents, rounded to desc->dtype.
+ *
+ *   forward   Xbar[b,j] = sum_{n,y,x} Z[(n,y,x),j] X[b,n,y,x]                 (Alg. 1 fwd step 3)
+ *   backward  L[j,m,oy,ox] = (1/r) sum_b Xbar[b,j] dY[b,m,oy,ox], rounded once to desc->dtype
+ *                                                                              (Alg. 1 bwd step 3)
+ *             dW[m,n,ky,kx] = sum_j sum_{oy,ox} L[j,m,oy,ox] Z[(n, oy*sh+ky-ph, ox*sw+kx-pw), j]
+ *                                                                              (Alg. 1 bwd step 4)
+ *
+ * The stored state is Xbar, B*r floats: C_in*H*W/r times smaller than X in fp32.  Z is
+ * regenerated in scratch in each pass (r*K values of desc->dtype).  Supported: NCHW,
+ * dense Rademacher or Gaussian probes from the seed (XCONV_USER_Z and keep_q15 != 0
+ * are XCONV_EUNSUPPORTED), C_in*H*W and C_out*H'*W' up to 2^28, B up to 65536.  All
+ * other conventions as above; X_dev and dY_dev 16-byte aligned, ws_dev required. */
+size_t xconv_pixel_xbar_bytes(const xconv_desc *desc);
+size_t xconv_pixel_workspace_bytes(const xconv_desc *desc, int op);    /* XCONV_OP_PROBE or XCONV_OP_ESTIMATE */
+xconv_status xconv_pixel_probe_fwd(const xconv_desc *desc, const void *X_dev, float *Xbar_dev,
+                                   void *ws_dev, size_t ws_bytes, void *stream);
+xconv_status xconv_pixel_dw_estimate(const xconv_desc *desc, const void *dY_dev, const float *Xbar_dev,
+                                     float *dW_dev, void *ws_dev, size_t ws_bytes, void *stream);
+
 /* Per-kernel timing with HIP events recorded on the launch stream.  While
  * enabled, every kernel the library enqueues is bracketed by two events.
  * xconv_prof_collect synchronises those events, writes up to `max` records

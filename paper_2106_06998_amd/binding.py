@@ -90,6 +90,14 @@ def lib():
         L.xconv3d_dw_exact.argtypes = [P3, vp, vp, vp, vp, sz, vp]
         L.xconv3d_xt_unpack.restype = i32
         L.xconv3d_xt_unpack.argtypes = [P3, vp, vp, vp]
+        L.xconv_pixel_xbar_bytes.restype = sz
+        L.xconv_pixel_xbar_bytes.argtypes = [P]
+        L.xconv_pixel_workspace_bytes.restype = sz
+        L.xconv_pixel_workspace_bytes.argtypes = [P, i32]
+        L.xconv_pixel_probe_fwd.restype = i32
+        L.xconv_pixel_probe_fwd.argtypes = [P, vp, vp, vp, sz, vp]
+        L.xconv_pixel_dw_estimate.restype = i32
+        L.xconv_pixel_dw_estimate.argtypes = [P, vp, vp, vp, vp, sz, vp]
         L.xconv_prof_enable.restype = None
         L.xconv_prof_enable.argtypes = [i32]
         L.xconv_prof_collect.restype = i32
@@ -237,6 +245,25 @@ def xconv3d_dw_exact(desc, dY_dev, X_dev, dW_dev, ws_dev, stream=None):
 
 def xconv3d_xt_unpack(desc, Xt_dev, out_dev, stream=None):
     _check(lib().xconv3d_xt_unpack(ctypes.byref(desc), _ptr(Xt_dev), _ptr(out_dev), _stream(stream)), "xconv3d_xt_unpack")
+
+
+# ---- probing vectors over pixels and channels ---------------------------------------
+def xconv_pixel_xbar_bytes(desc):
+    return int(lib().xconv_pixel_xbar_bytes(ctypes.byref(desc)))
+
+
+def xconv_pixel_workspace_bytes(desc, op):
+    return int(lib().xconv_pixel_workspace_bytes(ctypes.byref(desc), int(op)))
+
+
+def xconv_pixel_probe_fwd(desc, X_dev, Xbar_dev, ws_dev, stream=None):
+    _check(lib().xconv_pixel_probe_fwd(ctypes.byref(desc), _ptr(X_dev), _ptr(Xbar_dev), _ptr(ws_dev), _nbytes(ws_dev),
+                                       _stream(stream)), "xconv_pixel_probe_fwd")
+
+
+def xconv_pixel_dw_estimate(desc, dY_dev, Xbar_dev, dW_dev, ws_dev, stream=None):
+    _check(lib().xconv_pixel_dw_estimate(ctypes.byref(desc), _ptr(dY_dev), _ptr(Xbar_dev), _ptr(dW_dev), _ptr(ws_dev),
+                                         _nbytes(ws_dev), _stream(stream)), "xconv_pixel_dw_estimate")
 
 
 def xconv_prof_enable(on):

@@ -936,6 +936,50 @@ hipError_t launch_dy_slices(int dtype, const void *src, void *dst, int B, int C,
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// Probing vectors over the stacked pixel x channel axis (Eq. (6) as stated): Z is [K, r] with
+// K = C_in * H * W rows, entry (k, j) = generator word k * r + j.  It is laid out as `nimg`
+// images of K values in the storage type, image j = probing vector j (images r..nimg-1 are
+// zero), which is the form the probe and correlation kernels read an activation in.
+// ---------------------------------------------------------------------------
+template <int DT>
+__global__ __launch_bounds__(kThreads) void gen_zimg_kernel(void *__restrict__ out, long long K, int r, int nimg, int dist,
+                                                            uint64_t seed)
+{
+    const long long i = (long long)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= K * nimg) return;
+    const int j = (int)(i / K);
+    const long long k = i - (long long)j * K;
+    const float z = j < r ? probe_entry(probe_gen(dist, seed), (uint64_t)k * (uint64_t)r + (uint64_t)j) : 0.0f;
+    if constexpr (DT == XCONV_F32) static_cast<float *>(out)[i] = z;
+    else static_cast<uint16_t *>(out)[i] = f32_to_st16<DT>(z);
+}
+
+hipError_t launch_gen_zimg(int dtype, void *out, long long K, int r, int nimg, int dist, uint64_t seed, hipStream_t st)
+{
+    const long long total = K * nimg;
+    dim3 grid((unsigned)((total + kThreads - 1) / kThreads));
+    if (dtype == XCONV_F32)
+        hipLaunchKernelGGL(gen_zimg_kernel<XCONV_F32>, grid, dim3(kThreads), 0, st, out, K, r, nimg, dist, seed);
+    else if (dtype == XCONV_BF16)
+        hipLaunchKernelGGL(gen_zimg_kernel<XCONV_BF16>, grid, dim3(kThreads), 0, st, out, K, r, nimg, dist, seed);
+    else
+        hipLaunchKernelGGL(gen_zimg_kernel<XCONV_F16>, grid, dim3(kThreads), 0, st, out, K, r, nimg, dist, seed);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(kThreads) void scale_kernel(const float *__restrict__ in, float *__restrict__ out, int n, float f)
+{
+    const int i = blockIdx.x * kThreads + threadIdx.x;
+    if (i < n) out[i] = in[i] * f;
+}
+
+hipError_t launch_scale(const float *in, float *out, int n, float f, hipStream_t st)
+{
+    hipLaunchKernelGGL(scale_kernel, dim3(ceil_div(n, kThreads)), dim3(kThreads), 0, st, in, out, n, f);
+    return hipGetLastError();
+}
+
 hipError_t launch_unpack(int dtype, const void *Xt, float *out, int B, int HW, int r, int CS, hipStream_t st)
 {
     const long long total = (long long)B * r * HW;

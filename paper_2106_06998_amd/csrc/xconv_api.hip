@@ -652,6 +652,129 @@ xconv_status xconv3d_xt_unpack(const xconv3d_desc *v, const void *Xt_dev, float 
     return XCONV_OK;
 }
 
+// ---- probing vectors over pixels and channels (the estimator as the paper states it) ---------------
+// Composed from the kernels above.  Z [K = C_in*H*W, r] is drawn into images of K storage values
+// (image j = probing vector j).
+//   forward:  Xbar[b,j] = sum_k X[b,k] Z[k,j] is the exact-gradient path of a 1x1 layer with one
+//             image, B output channels (the rows of X), r input channels (the probing vectors)
+//             and K pixels;
+//   backward: Lt[p,j] = sum_b dY[b,p] Xbar[b,j]/r is the channel probe of a single image with B
+//             channels and P = C_out*H'*W' pixels, with Xbar/r as its probing matrix; brought into
+//             planes L[j,m,oy,ox] it is the residual of a batch of r images whose activations are
+//             the probing vectors, and dW is the exact-gradient path of that batch.
+namespace {
+
+struct PixelGeom {
+    long long K, P;      // values per image of X and of dY
+    int CS;              // r rounded up to 16: images of L and of Z in the backward pass
+    xconv_desc fwd;      // 1x1 layer of the forward product
+    xconv_desc probe;    // single-image channel probe of the backward pass (B channels)
+    xconv_desc bwd;      // batch of CS images of the shifted product
+    size_t zimg_f, zimg_b, xs, lt, l, probe_ws;
+};
+
+xconv_status pixel_geom(const xconv_desc *d, PixelGeom &g)
+{
+    xconv_status s = xconv_check_desc(d);
+    if (s != XCONV_OK) return s;
+    if (d->layout != XCONV_NCHW || d->probe == XCONV_USER_Z || d->keep_q15 != 0) return XCONV_EUNSUPPORTED;
+    const int Ho = out_extent(d->H, d->kH, d->stride_h, d->pad_h), Wo = out_extent(d->W, d->kW, d->stride_w, d->pad_w);
+    g.K = (long long)d->C_in * d->H * d->W;
+    g.P = (long long)d->C_out * Ho * Wo;
+    if (g.K > (1LL << 28) || g.P > (1LL << 28)) return XCONV_EUNSUPPORTED;
+    g.CS = round_up(d->r, 16);
+    const size_t eb = elem_bytes(d->dtype);
+    g.fwd = *d;
+    g.fwd.B = 1; g.fwd.C_out = d->B; g.fwd.C_in = d->r; g.fwd.H = d->C_in * d->H; g.fwd.W = d->W;
+    g.fwd.kH = g.fwd.kW = 1; g.fwd.stride_h = g.fwd.stride_w = 1; g.fwd.pad_h = g.fwd.pad_w = 0;
+    g.probe = *d;
+    g.probe.B = 1; g.probe.C_in = d->B; g.probe.probe = XCONV_USER_Z;
+    g.bwd = *d;
+    g.bwd.B = g.CS;
+    if (xconv_check_desc(&g.fwd) != XCONV_OK || xconv_check_desc(&g.bwd) != XCONV_OK) return XCONV_EUNSUPPORTED;
+    g.zimg_f = align_up((size_t)d->r * g.K * eb, 256);
+    g.zimg_b = align_up((size_t)g.CS * g.K * eb, 256);
+    g.xs = align_up((size_t)d->B * d->r * sizeof(float), 256);
+    g.lt = align_up((size_t)g.P * g.CS * eb, 256);
+    g.l = g.lt;
+    g.probe_ws = z_bytes(&g.probe) + zfrag_bytes(&g.probe);
+    return XCONV_OK;
+}
+
+}  // namespace
+
+size_t xconv_pixel_xbar_bytes(const xconv_desc *d)
+{
+    PixelGeom g;
+    if (pixel_geom(d, g) != XCONV_OK) return 0;
+    return (size_t)d->B * d->r * sizeof(float);
+}
+
+size_t xconv_pixel_workspace_bytes(const xconv_desc *d, int op)
+{
+    PixelGeom g;
+    if (pixel_geom(d, g) != XCONV_OK) return 0;
+    if (op == XCONV_OP_PROBE) {
+        const size_t w = xconv_workspace_bytes(&g.fwd, XCONV_OP_EXACT);
+        return w ? g.zimg_f + w : 0;
+    }
+    if (op == XCONV_OP_ESTIMATE) {
+        const size_t w = xconv_workspace_bytes(&g.bwd, XCONV_OP_EXACT);
+        return w ? g.zimg_b + g.xs + g.lt + g.l + align_up(g.probe_ws, 256) + w : 0;
+    }
+    return 0;
+}
+
+xconv_status xconv_pixel_probe_fwd(const xconv_desc *d, const void *X_dev, float *Xbar_dev, void *ws_dev, size_t ws_bytes,
+                                   void *stream)
+{
+    PixelGeom g;
+    xconv_status s = pixel_geom(d, g);
+    if (s != XCONV_OK) return s;
+    if (!X_dev || !Xbar_dev || !ws_dev) return XCONV_EINVAL;
+    if (!aligned16(X_dev) || !aligned16(ws_dev) || (reinterpret_cast<uintptr_t>(Xbar_dev) & 3u) != 0) return XCONV_EINVAL;
+    const size_t need = xconv_pixel_workspace_bytes(d, XCONV_OP_PROBE);
+    if (need == 0) return XCONV_EUNSUPPORTED;
+    if (ws_bytes < need) return XCONV_EWORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(ws_dev);
+    XC_LAUNCH(K_GEN_Z, st, launch_gen_zimg(d->dtype, ws, g.K, d->r, d->r, probe_code(d), d->seed, st));
+    // rows of X in the role of dY (B channels of one image), the probing vectors in the role of the activation
+    return xconv_dw_exact(&g.fwd, X_dev, ws, Xbar_dev, ws + g.zimg_f, ws_bytes - g.zimg_f, stream);
+}
+
+xconv_status xconv_pixel_dw_estimate(const xconv_desc *d, const void *dY_dev, const float *Xbar_dev, float *dW_dev, void *ws_dev,
+                                     size_t ws_bytes, void *stream)
+{
+    PixelGeom g;
+    xconv_status s = pixel_geom(d, g);
+    if (s != XCONV_OK) return s;
+    if (!dY_dev || !Xbar_dev || !dW_dev || !ws_dev) return XCONV_EINVAL;
+    if (!aligned16(dY_dev) || !aligned16(ws_dev) || (reinterpret_cast<uintptr_t>(dW_dev) & 3u) != 0 ||
+        (reinterpret_cast<uintptr_t>(Xbar_dev) & 3u) != 0)
+        return XCONV_EINVAL;
+    const size_t need = xconv_pixel_workspace_bytes(d, XCONV_OP_ESTIMATE);
+    if (need == 0) return XCONV_EUNSUPPORTED;
+    if (ws_bytes < need) return XCONV_EWORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(ws_dev);
+    char *zimg = ws;
+    float *xs = reinterpret_cast<float *>(ws + g.zimg_b);
+    char *lt = ws + g.zimg_b + g.xs;
+    char *l = lt + g.lt;
+    char *pws = l + g.l;
+    char *xws = pws + align_up(g.probe_ws, 256);
+    // Z[s] again (Alg. 1 backward step 2), CS images: the ones past r are zero like the matching images of L
+    XC_LAUNCH(K_GEN_Z, st, launch_gen_zimg(d->dtype, zimg, g.K, d->r, g.CS, probe_code(d), d->seed, st));
+    XC_LAUNCH(K_GEN_Z, st, launch_scale(Xbar_dev, xs, d->B * d->r, 1.0f / (float)d->r, st));
+    // Lt[p, j] = sum_b dY[b, p] Xbar[b, j] / r, rounded to the storage type (Alg. 1 backward step 3)
+    s = probe_impl(&g.probe, (int)g.P, (int)g.P, SliceMap{}, dY_dev, lt, xs, pws, g.probe_ws, st);
+    if (s != XCONV_OK) return s;
+    XC_LAUNCH(K_REPACK, st, launch_to_nchw(d->dtype, lt, l, 1, g.CS, (int)g.P, (int)g.P, st));
+    // dw_i = tr(L T_{-k(i)} Z) (Alg. 1 backward step 4; the factor 1/r is already in L)
+    return xconv_dw_exact(&g.bwd, l, zimg, dW_dev, xws, ws_bytes - (size_t)(xws - ws), stream);
+}
+
 void xconv_prof_enable(int on)
 {
     std::lock_guard<std::mutex> lk(g_prof_mu);

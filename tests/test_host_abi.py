@@ -190,6 +190,33 @@ def test_volumetric_descriptor_and_sizes():
     assert L.xconv3d_xt_unpack(p, None, one, None) == xb.XCONV_EINVAL
 
 
+def test_pixel_probe_sizes_and_argument_checks():
+    d = _good()                                            # B=4, C_in=16, 32x32, r=8, fp32
+    assert xb.xconv_pixel_xbar_bytes(d) == 4 * 8 * 4
+    wf = xb.xconv_pixel_workspace_bytes(d, xb.XCONV_OP_PROBE)
+    wb = xb.xconv_pixel_workspace_bytes(d, xb.XCONV_OP_ESTIMATE)
+    assert wf > 8 * 16 * 32 * 32 * 4 and wb > 16 * 16 * 32 * 32 * 4       # the probing vectors are redrawn in scratch
+    assert xb.xconv_pixel_workspace_bytes(d, xb.XCONV_OP_EXACT) == 0
+    for field, val in (("layout", xb.XCONV_NHWC), ("probe", xb.XCONV_USER_Z), ("keep_q15", 100)):
+        bad = _good()
+        setattr(bad, field, val)
+        assert xb.xconv_pixel_xbar_bytes(bad) == 0 and xb.xconv_pixel_workspace_bytes(bad, 0) == 0
+        assert xb.lib().xconv_pixel_probe_fwd(ctypes.byref(bad), ctypes.c_void_p(4096), ctypes.c_void_p(4096),
+                                               ctypes.c_void_p(4096), 1 << 30, None) == xb.XCONV_EUNSUPPORTED
+    L = xb.lib()
+    p = ctypes.byref(d)
+    one = ctypes.c_void_p(4096)          # never dereferenced: validation fails first
+    assert L.xconv_pixel_probe_fwd(p, None, one, one, 1 << 30, None) == xb.XCONV_EINVAL
+    assert L.xconv_pixel_probe_fwd(p, one, one, None, 1 << 30, None) == xb.XCONV_EINVAL
+    assert L.xconv_pixel_probe_fwd(p, ctypes.c_void_p(4100), one, one, 1 << 30, None) == xb.XCONV_EINVAL    # X misaligned
+    assert L.xconv_pixel_probe_fwd(p, one, one, one, 64, None) == xb.XCONV_EWORKSPACE
+    assert L.xconv_pixel_dw_estimate(p, one, None, one, one, 1 << 30, None) == xb.XCONV_EINVAL
+    assert L.xconv_pixel_dw_estimate(p, one, one, one, one, 64, None) == xb.XCONV_EWORKSPACE
+    bad = _good()
+    bad.r = 0
+    assert L.xconv_pixel_dw_estimate(ctypes.byref(bad), one, one, one, one, 1 << 30, None) == xb.XCONV_EINVAL
+
+
 def test_synthetic_inputs_are_storage_representable_and_seeded():
     cfg = synth.small_variant(synth.CONFIGS["C3"], B=2, H=12, W=12, C_in=8, C_out=8)
     X, dY = synth.make_layer(cfg)
