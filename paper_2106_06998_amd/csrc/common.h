@@ -26,7 +26,10 @@ enum KernelId {
     K_REPACK = 8,
     K_PACK_Z = 9,
     K_ZERO_GAPS = 10,
-    K_COUNT = 11
+    K_GEN_ZIMG = 11,
+    K_SCALE = 12,
+    K_PIXEL_FWD = 13,
+    K_COUNT = 14
 };
 
 // Where the probe output of a voxel goes in Xt.  sd == 0: plain order, pixel `first` of the

@@ -24,8 +24,10 @@ hipError_t launch_zero_gap_slices(void *Xt, size_t slice_bytes, int B, SliceMap 
 hipError_t launch_to_slices(int dtype, const void *X, void *out, int B, int C, int CS, SliceMap sm, hipStream_t st);
 hipError_t launch_unpack_slices(int dtype, const void *Xt, float *out, int B, int r, int CS, SliceMap sm, hipStream_t st);
 hipError_t launch_dy_slices(int dtype, const void *src, void *dst, int B, int C, int Do, int period, int n, int pitch, hipStream_t st);
-// probing vectors over pixels and channels as `nimg` images of K storage values (entry (k, j) = word k*r + j; images >= r zero)
-hipError_t launch_gen_zimg(int dtype, void *out, long long K, int r, int nimg, int dist, uint64_t seed, hipStream_t st);
+// probing vectors over pixels and channels as `nimg` images of K storage values (entry (k, j) = word k*r + j; images >= r zero);
+// cl_cs > 0: each image channels-last [pixel][cl_cs] (k = channel * pixels + pixel), zero columns C_in..cl_cs-1
+hipError_t launch_gen_zimg(int dtype, void *out, long long K, int r, int nimg, int dist, uint64_t seed, int C_in, int cl_cs,
+                           hipStream_t st);
 hipError_t launch_scale(const float *in, float *out, int n, float f, hipStream_t st);
 hipError_t launch_unpack(int dtype, const void *Xt, float *out, int B, int HW, int r, int CS, hipStream_t st);
 hipError_t launch_to_nhwc(int dtype, const void *X, void *out, int B, int C, int HW, int CS, hipStream_t st);

@@ -942,29 +942,44 @@ hipError_t launch_dy_slices(int dtype, const void *src, void *dst, int B, int C,
 // images of K values in the storage type, image j = probing vector j (images r..nimg-1 are
 // zero), which is the form the probe and correlation kernels read an activation in.
 // ---------------------------------------------------------------------------
+// cl_cs == 0: image j holds its K values in row order (k fastest).  cl_cs > 0: channels-last,
+// value (n, q) of image j at (j * N + q) * cl_cs + n with zero columns C_in..cl_cs-1 (N = K / C_in
+// pixels), the form the correlation kernels read an activation in.
 template <int DT>
 __global__ __launch_bounds__(kThreads) void gen_zimg_kernel(void *__restrict__ out, long long K, int r, int nimg, int dist,
-                                                            uint64_t seed)
+                                                            uint64_t seed, int C_in, int cl_cs)
 {
     const long long i = (long long)blockIdx.x * kThreads + threadIdx.x;
-    if (i >= K * nimg) return;
-    const int j = (int)(i / K);
-    const long long k = i - (long long)j * K;
-    const float z = j < r ? probe_entry(probe_gen(dist, seed), (uint64_t)k * (uint64_t)r + (uint64_t)j) : 0.0f;
+    float z = 0.0f;
+    if (cl_cs == 0) {
+        if (i >= K * nimg) return;
+        const int j = (int)(i / K);
+        const long long k = i - (long long)j * K;
+        if (j < r) z = probe_entry(probe_gen(dist, seed), (uint64_t)k * (uint64_t)r + (uint64_t)j);
+    } else {
+        const long long N = K / C_in;
+        if (i >= N * nimg * cl_cs) return;
+        const int n = (int)(i % cl_cs);
+        const long long jq = i / cl_cs;
+        const int j = (int)(jq / N);
+        const long long q = jq - (long long)j * N;
+        if (j < r && n < C_in) z = probe_entry(probe_gen(dist, seed), (uint64_t)((long long)n * N + q) * (uint64_t)r + (uint64_t)j);
+    }
     if constexpr (DT == XCONV_F32) static_cast<float *>(out)[i] = z;
     else static_cast<uint16_t *>(out)[i] = f32_to_st16<DT>(z);
 }
 
-hipError_t launch_gen_zimg(int dtype, void *out, long long K, int r, int nimg, int dist, uint64_t seed, hipStream_t st)
+hipError_t launch_gen_zimg(int dtype, void *out, long long K, int r, int nimg, int dist, uint64_t seed, int C_in, int cl_cs,
+                           hipStream_t st)
 {
-    const long long total = K * nimg;
+    const long long total = cl_cs ? (K / C_in) * nimg * cl_cs : K * nimg;
     dim3 grid((unsigned)((total + kThreads - 1) / kThreads));
     if (dtype == XCONV_F32)
-        hipLaunchKernelGGL(gen_zimg_kernel<XCONV_F32>, grid, dim3(kThreads), 0, st, out, K, r, nimg, dist, seed);
+        hipLaunchKernelGGL(gen_zimg_kernel<XCONV_F32>, grid, dim3(kThreads), 0, st, out, K, r, nimg, dist, seed, C_in, cl_cs);
     else if (dtype == XCONV_BF16)
-        hipLaunchKernelGGL(gen_zimg_kernel<XCONV_BF16>, grid, dim3(kThreads), 0, st, out, K, r, nimg, dist, seed);
+        hipLaunchKernelGGL(gen_zimg_kernel<XCONV_BF16>, grid, dim3(kThreads), 0, st, out, K, r, nimg, dist, seed, C_in, cl_cs);
     else
-        hipLaunchKernelGGL(gen_zimg_kernel<XCONV_F16>, grid, dim3(kThreads), 0, st, out, K, r, nimg, dist, seed);
+        hipLaunchKernelGGL(gen_zimg_kernel<XCONV_F16>, grid, dim3(kThreads), 0, st, out, K, r, nimg, dist, seed, C_in, cl_cs);
     return hipGetLastError();
 }
 

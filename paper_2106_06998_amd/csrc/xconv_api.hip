@@ -382,11 +382,18 @@ xconv_status xconv_dw_estimate(const xconv_desc *d, const void *dY_dev, const vo
     return XCONV_OK;
 }
 
-xconv_status xconv_dw_exact(const xconv_desc *d, const void *dY_dev, const void *X_dev, float *dW_dev, void *ws_dev,
-                            size_t ws_bytes, void *stream)
+}  // extern "C"
+
+namespace {
+
+// Exact-gradient path.  A_ready != nullptr: the activation is already channels-last [B, H, W, C_in rounded up
+// to 16] with zero pad columns (X_dev is then ignored and may be null).
+xconv_status exact_impl(const xconv_desc *d, const void *dY_dev, const void *X_dev, const void *A_ready, float *dW_dev, void *ws_dev,
+                        size_t ws_bytes, void *stream)
 {
     xconv_status s = xconv_check_desc(d);
     if (s != XCONV_OK) return s;
+    if (A_ready) X_dev = A_ready;
     if (!dY_dev || !X_dev || !dW_dev || !ws_dev) return XCONV_EINVAL;
     if (!aligned16(ws_dev) || (reinterpret_cast<uintptr_t>(dW_dev) & 3u) != 0) return XCONV_EINVAL;
     const size_t eb = elem_bytes(d->dtype);
@@ -402,7 +409,9 @@ xconv_status xconv_dw_exact(const xconv_desc *d, const void *dY_dev, const void 
     if (ws_bytes < xb + pb + rb) return XCONV_EWORKSPACE;
     // the correlation kernels read X channels-last with a channel stride that is a multiple of 16
     const void *A = ws_dev;
-    if (d->layout == XCONV_NCHW) {
+    if (A_ready) {
+        A = A_ready;
+    } else if (d->layout == XCONV_NCHW) {
         XC_LAUNCH(K_TO_NHWC, st, launch_to_nhwc(d->dtype, X_dev, ws_dev, d->B, d->C_in, HW, CSx, st));
     } else if (d->C_in == CSx && aligned16(X_dev)) {
         A = X_dev;  // already in that form
@@ -432,6 +441,16 @@ xconv_status xconv_dw_exact(const xconv_desc *d, const void *dY_dev, const void 
     XC_LAUNCH(K_REDUCE, st, launch_reduce(P, st));
     XC_LAUNCH(K_EXPAND, st, launch_expand(P, nullptr, dW_dev, d->C_in, d->r, st));
     return XCONV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+xconv_status xconv_dw_exact(const xconv_desc *d, const void *dY_dev, const void *X_dev, float *dW_dev, void *ws_dev,
+                            size_t ws_bytes, void *stream)
+{
+    return exact_impl(d, dY_dev, X_dev, nullptr, dW_dev, ws_dev, ws_bytes, stream);
 }
 
 xconv_status xconv_plan_info(const xconv_desc *d, int op, int32_t *out)
@@ -693,7 +712,7 @@ xconv_status pixel_geom(const xconv_desc *d, PixelGeom &g)
     g.bwd.B = g.CS;
     if (xconv_check_desc(&g.fwd) != XCONV_OK || xconv_check_desc(&g.bwd) != XCONV_OK) return XCONV_EUNSUPPORTED;
     g.zimg_f = align_up((size_t)d->r * g.K * eb, 256);
-    g.zimg_b = align_up((size_t)g.CS * g.K * eb, 256);
+    g.zimg_b = align_up((size_t)g.CS * d->H * d->W * round_up(d->C_in, 16) * eb, 256);   // channels-last, padded channels
     g.xs = align_up((size_t)d->B * d->r * sizeof(float), 256);
     g.lt = align_up((size_t)g.P * g.CS * eb, 256);
     g.l = g.lt;
@@ -738,7 +757,7 @@ xconv_status xconv_pixel_probe_fwd(const xconv_desc *d, const void *X_dev, float
     if (ws_bytes < need) return XCONV_EWORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(ws_dev);
-    XC_LAUNCH(K_GEN_Z, st, launch_gen_zimg(d->dtype, ws, g.K, d->r, d->r, probe_code(d), d->seed, st));
+    XC_LAUNCH(K_GEN_ZIMG, st, launch_gen_zimg(d->dtype, ws, g.K, d->r, d->r, probe_code(d), d->seed, d->C_in, 0, st));
     // rows of X in the role of dY (B channels of one image), the probing vectors in the role of the activation
     return xconv_dw_exact(&g.fwd, X_dev, ws, Xbar_dev, ws + g.zimg_f, ws_bytes - g.zimg_f, stream);
 }
@@ -764,15 +783,16 @@ xconv_status xconv_pixel_dw_estimate(const xconv_desc *d, const void *dY_dev, co
     char *l = lt + g.lt;
     char *pws = l + g.l;
     char *xws = pws + align_up(g.probe_ws, 256);
-    // Z[s] again (Alg. 1 backward step 2), CS images: the ones past r are zero like the matching images of L
-    XC_LAUNCH(K_GEN_Z, st, launch_gen_zimg(d->dtype, zimg, g.K, d->r, g.CS, probe_code(d), d->seed, st));
-    XC_LAUNCH(K_GEN_Z, st, launch_scale(Xbar_dev, xs, d->B * d->r, 1.0f / (float)d->r, st));
+    // Z[s] again (Alg. 1 backward step 2), CS images, channels-last as the correlation reads an activation:
+    // the images past r are zero like the matching images of L
+    XC_LAUNCH(K_GEN_ZIMG, st, launch_gen_zimg(d->dtype, zimg, g.K, d->r, g.CS, probe_code(d), d->seed, d->C_in, round_up(d->C_in, 16), st));
+    XC_LAUNCH(K_SCALE, st, launch_scale(Xbar_dev, xs, d->B * d->r, 1.0f / (float)d->r, st));
     // Lt[p, j] = sum_b dY[b, p] Xbar[b, j] / r, rounded to the storage type (Alg. 1 backward step 3)
     s = probe_impl(&g.probe, (int)g.P, (int)g.P, SliceMap{}, dY_dev, lt, xs, pws, g.probe_ws, st);
     if (s != XCONV_OK) return s;
     XC_LAUNCH(K_REPACK, st, launch_to_nchw(d->dtype, lt, l, 1, g.CS, (int)g.P, (int)g.P, st));
     // dw_i = tr(L T_{-k(i)} Z) (Alg. 1 backward step 4; the factor 1/r is already in L)
-    return xconv_dw_exact(&g.bwd, l, zimg, dW_dev, xws, ws_bytes - (size_t)(xws - ws), stream);
+    return exact_impl(&g.bwd, l, nullptr, zimg, dW_dev, xws, ws_bytes - (size_t)(xws - ws), stream);
 }
 
 void xconv_prof_enable(int on)
@@ -813,6 +833,9 @@ const char *xconv_prof_kernel_name(int id)
     case K_REPACK: return "repack_planes_kernel";
     case K_PACK_Z: return "pack_z_kernel";
     case K_ZERO_GAPS: return "zero_gap_slices_kernel";
+    case K_GEN_ZIMG: return "gen_zimg_kernel";
+    case K_SCALE: return "scale_kernel";
+    case K_PIXEL_FWD: return "pixel_fwd_kernel";
     default: return "unknown";
     }
 }
