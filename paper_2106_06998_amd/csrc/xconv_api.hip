@@ -734,6 +734,9 @@ size_t xconv_pixel_workspace_bytes(const xconv_desc *d, int op)
     PixelGeom g;
     if (pixel_geom(d, g) != XCONV_OK) return 0;
     if (op == XCONV_OP_PROBE) {
+        // the product kernel's partial sums, or (rows of X that are not whole 16-byte vectors) the scratch of the
+        // exact-gradient path of the equivalent 1x1 layer
+        if (pixel_fwd_ok(d->dtype, g.K, nullptr)) return g.zimg_f + align_up(pixel_fwd_partial_bytes(d->dtype, g.K, d->B, d->r), 256);
         const size_t w = xconv_workspace_bytes(&g.fwd, XCONV_OP_EXACT);
         return w ? g.zimg_f + w : 0;
     }
@@ -758,6 +761,11 @@ xconv_status xconv_pixel_probe_fwd(const xconv_desc *d, const void *X_dev, float
     hipStream_t st = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(ws_dev);
     XC_LAUNCH(K_GEN_ZIMG, st, launch_gen_zimg(d->dtype, ws, g.K, d->r, d->r, probe_code(d), d->seed, d->C_in, 0, st));
+    if (pixel_fwd_ok(d->dtype, g.K, X_dev)) {
+        XC_LAUNCH(K_PIXEL_FWD, st, launch_pixel_fwd(d->dtype, X_dev, ws, reinterpret_cast<float *>(ws + g.zimg_f), Xbar_dev, g.K, d->B,
+                                                    d->r, st));
+        return XCONV_OK;
+    }
     // rows of X in the role of dY (B channels of one image), the probing vectors in the role of the activation
     return xconv_dw_exact(&g.fwd, X_dev, ws, Xbar_dev, ws + g.zimg_f, ws_bytes - g.zimg_f, stream);
 }

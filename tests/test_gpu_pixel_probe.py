@@ -23,6 +23,8 @@ PIX = [
     ("bf16-odd-planes", "bf16", 9, 5, 7, 7, 9, 3, 1, 0, 12, "rademacher"),
     ("f16-1x1", "f16", 4, 16, 16, 8, 8, 1, 1, 0, 16, "rademacher"),
     ("f32-one-image", "f32", 1, 4, 4, 8, 8, 3, 1, 1, 4, "rademacher"),
+    ("f16-image-and-vector-blocks", "f16", 300, 4, 8, 8, 8, 3, 1, 1, 80, "rademacher"),
+    ("f32-ragged-blocks", "f32", 70, 4, 4, 8, 12, 3, 1, 1, 20, "gaussian"),
     ("f32-batch-40", "f32", 40, 8, 8, 8, 8, 3, 1, 1, 64, "rademacher"),
 ]
 
