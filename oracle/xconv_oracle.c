@@ -369,6 +369,12 @@ void xo_correlate3d_at(const float *dY, const float *A, const int *idx, int n, d
     }
 }
 
+/* v[i] <- v[i] rounded to the storage type (round to nearest even), in place. */
+void xo_round_array(float *v, size_t n, int dtype)
+{
+    for (size_t i = 0; i < n; ++i) v[i] = (float)xo_round_storage((double)v[i], dtype);
+}
+
 /* ------------------------------------------------------------------------- */
 /* The estimator as the paper states it: probing vectors over the stacked     */
 /* pixel x channel space (Sec. 3 multi-channel case, Eq. (6); Algorithm 1).    */

@@ -67,6 +67,8 @@ def lib():
         L.xo_correlate3d.argtypes = [_c_f32p, _c_f32p, _c_f64p] + [ctypes.c_int] * 15
         L.xo_correlate3d_at.restype = None
         L.xo_correlate3d_at.argtypes = [_c_f32p, _c_f32p, _c_i32p, ctypes.c_int, _c_f64p] + [ctypes.c_int] * 15
+        L.xo_round_array.restype = None
+        L.xo_round_array.argtypes = [_c_f32p, ctypes.c_size_t, ctypes.c_int]
         L.xo_pixel_probe_fwd.restype = None
         L.xo_pixel_probe_fwd.argtypes = [_c_f32p, _c_f32p, _c_f32p] + [ctypes.c_int] * 5
         L.xo_pixel_dw_estimate.restype = None
@@ -301,9 +303,9 @@ def dw_from_xt3d_at(dY, Xt, Z, idx, k, stride=(1, 1, 1), pad=(0, 0, 0)):
 def pixel_probe_matrix(dist, seed, C_in, H, W, r, dtype=F32):
     """Z [C_in*H*W, r], row (n, q) = n*H*W + q, from the same generator as the channel probes
     (entry index = row * r + j), rounded to the storage type the products run in."""
-    Z = probe_matrix(dist, seed, C_in * H * W, r)
+    Z = np.ascontiguousarray(probe_matrix(dist, seed, C_in * H * W, r), dtype=np.float32)
     if dtype != F32:
-        Z = np.array([round_storage(v, dtype) for v in Z.reshape(-1)], dtype=np.float32).reshape(Z.shape)
+        lib().xo_round_array(Z.ctypes.data_as(_c_f32p), Z.size, dtype)
     return Z
 
 

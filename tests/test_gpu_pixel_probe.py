@@ -72,3 +72,9 @@ def test_pixel_probe_layers(e):
 
 def test_pixel_probe_is_deterministic():
     assert np.array_equal(run_pixel(PIX[2]), run_pixel(PIX[2]))
+
+
+def test_pixel_probe_full_size_C2():
+    # the benchmark layer bench.py --pixel-probe times by default, every entry against the oracle
+    cfg = synth.CONFIGS["C2"]
+    run_pixel(("C2", cfg.dtype, cfg.B, cfg.C_in, cfg.C_out, cfg.H, cfg.W, cfg.k, cfg.stride, cfg.pad, cfg.r, cfg.probe))
