@@ -25,6 +25,7 @@ PIX = [
     ("f32-one-image", "f32", 1, 4, 4, 8, 8, 3, 1, 1, 4, "rademacher"),
     ("f16-image-and-vector-blocks", "f16", 300, 4, 8, 8, 8, 3, 1, 1, 80, "rademacher"),
     ("f32-ragged-blocks", "f32", 70, 4, 4, 8, 12, 3, 1, 1, 20, "gaussian"),
+    ("bf16-batch-520", "bf16", 520, 2, 4, 8, 8, 3, 1, 1, 8, "rademacher"),
     ("f32-batch-40", "f32", 40, 8, 8, 8, 8, 3, 1, 1, 64, "rademacher"),
 ]
 
