@@ -7,6 +7,8 @@
 // the MFMA operands: rows = probing vectors, columns = images, a lane supplies 8 (16-bit) or 4 (fp32)
 // consecutive k.  K is split over the workgroups; partial products go to scratch and are summed in a
 // fixed order by reduce_partials_kernel.
+#include <cstdlib>
+
 #include "common.h"
 #include "launch.h"
 
@@ -176,11 +178,18 @@ static PixelFwdPlan pixel_fwd_plan(int dtype, long long K, int B, int r)
     p.nbb = ceil_div(B, 16 * p.TM);
     p.njb = ceil_div(CSt, 16 * p.TN);
     // four waves per compute unit over all (image block, probing vector block) pairs (a wave keeps 16 to 32 KB of
-    // loads in flight), at least 4 stages per slice, partial sums below an eighth of the bytes of X
-    long long S = 1024 / ((long long)p.nbb * p.njb);
+    // loads in flight), at least 4 stages per slice, partial sums below a sixth of the bytes of X; then a whole
+    // number of waves per compute unit (an uneven spread costs a whole extra wave's time)
+    const long long nb = (long long)p.nbb * p.njb;
+    long long S = 1024 / nb;
     if (S > p.NM / 4) S = p.NM / 4;
-    const long long cap = K * (dtype == XCONV_F32 ? 4 : 2) / ((long long)CSt * 4 * 8);
+    const long long cap = K * (dtype == XCONV_F32 ? 4 : 2) / ((long long)CSt * 4 * 6);
     if (S > cap) S = cap;
+    if (S * nb > 256) S = (S * nb / 256) * 256 / nb;
+    if (const char *v = getenv("XCONV_PIXEL_SPLITS")) {   // sweeps
+        if (*v) S = atoi(v);
+        if (S > p.NM) S = p.NM;
+    }
     if (S < 1) S = 1;
     p.S = (int)S;
     return p;
