@@ -369,6 +369,14 @@ void xo_correlate3d_at(const float *dY, const float *A, const int *idx, int n, d
     }
 }
 
+/* Keep decisions of block-sparse probing vectors (Eq. (7)): keep[i] = 1 when the top 15 bits of word i of */
+/* the mask stream of the seed are below keep_q15 (probability keep_q15 / 32768), else 0; all 1 for 0.     */
+void xo_keep_mask(uint64_t seed, int keep_q15, size_t n, float *keep)
+{
+    for (size_t i = 0; i < n; ++i)
+        keep[i] = (keep_q15 == 0 || (xo_stream_word(seed ^ XO_MASK_STREAM, (uint64_t)i) >> 49) < (uint64_t)keep_q15) ? 1.0f : 0.0f;
+}
+
 /* v[i] <- v[i] rounded to the storage type (round to nearest even), in place. */
 void xo_round_array(float *v, size_t n, int dtype)
 {

@@ -67,6 +67,8 @@ def lib():
         L.xo_correlate3d.argtypes = [_c_f32p, _c_f32p, _c_f64p] + [ctypes.c_int] * 15
         L.xo_correlate3d_at.restype = None
         L.xo_correlate3d_at.argtypes = [_c_f32p, _c_f32p, _c_i32p, ctypes.c_int, _c_f64p] + [ctypes.c_int] * 15
+        L.xo_keep_mask.restype = None
+        L.xo_keep_mask.argtypes = [ctypes.c_uint64, ctypes.c_int, ctypes.c_size_t, _c_f32p]
         L.xo_round_array.restype = None
         L.xo_round_array.argtypes = [_c_f32p, ctypes.c_size_t, ctypes.c_int]
         L.xo_pixel_probe_fwd.restype = None
@@ -300,13 +302,31 @@ def dw_from_xt3d_at(dY, Xt, Z, idx, k, stride=(1, 1, 1), pad=(0, 0, 0)):
 
 
 # ---- the estimator with probing vectors over pixels and channels (Eq. (6), Algorithm 1 as stated) ----
-def pixel_probe_matrix(dist, seed, C_in, H, W, r, dtype=F32):
+def keep_mask(seed, keep_q15, n):
+    """Keep decisions 0/1 of n blocks (Eq. (7)); block i is kept with probability keep_q15 / 32768."""
+    m = np.empty(n, dtype=np.float32)
+    lib().xo_keep_mask(int(seed), int(keep_q15), n, m.ctypes.data_as(_c_f32p))
+    return m
+
+
+def pixel_probe_matrix(dist, seed, C_in, H, W, r, dtype=F32, keep_q15=0):
     """Z [C_in*H*W, r], row (n, q) = n*H*W + q, from the same generator as the channel probes
-    (entry index = row * r + j), rounded to the storage type the products run in."""
+    (entry index = row * r + j), rounded to the storage type the products run in.  keep_q15 != 0:
+    block-sparse probing vectors (Eq. (7)): block (n, j), the N entries of vector j on channel n, is
+    zero unless keep decision n*r + j says keep."""
     Z = np.ascontiguousarray(probe_matrix(dist, seed, C_in * H * W, r), dtype=np.float32)
     if dtype != F32:
         lib().xo_round_array(Z.ctypes.data_as(_c_f32p), Z.size, dtype)
+    if keep_q15:
+        keep = keep_mask(seed, keep_q15, C_in * r).reshape(C_in, 1, r)
+        Z = np.ascontiguousarray((Z.reshape(C_in, H * W, r) * keep).reshape(C_in * H * W, r))
     return Z
+
+
+def pixel_block_counts(Z, C_in):
+    """nnz(Z_n) of Eq. (8): the number of probing vectors with a non-zero block on channel n."""
+    Zb = np.asarray(Z).reshape(C_in, -1, Z.shape[1])
+    return np.count_nonzero(np.any(Zb != 0, axis=1), axis=1)
 
 
 def pixel_probe_fwd(X, Z):
@@ -321,8 +341,10 @@ def pixel_probe_fwd(X, Z):
     return Xbar
 
 
-def pixel_dw_estimate(dY, Xbar, Z, C_in, H, W, kH, kW, stride=(1, 1), pad=(0, 0), dtype=F32):
-    """dw_i = (1/r) tr(L T_{-k(i)} Z), L = Xbar^T dY rounded to the storage type (Alg. 1 backward)."""
+def pixel_dw_estimate(dY, Xbar, Z, C_in, H, W, kH, kW, stride=(1, 1), pad=(0, 0), dtype=F32, nnz_norm=False):
+    """dw_i = (1/r) tr(L T_{-k(i)} Z), L = Xbar^T dY rounded to the storage type (Alg. 1 backward).
+    nnz_norm: the estimate of input channel n is scaled by 1 / nnz(Z_n) instead of 1 / r (Eq. (8)); a channel
+    without any block gives zeros."""
     dY, dYp = _f32(dY)
     Xbar, Xbp = _f32(Xbar)
     Z, Zp = _f32(Z)
@@ -333,4 +355,7 @@ def pixel_dw_estimate(dY, Xbar, Z, C_in, H, W, kH, kW, stride=(1, 1), pad=(0, 0)
     dW = np.empty((C_out, C_in, kH, kW), dtype=np.float64)
     lib().xo_pixel_dw_estimate(dYp, Xbp, Zp, dW.ctypes.data_as(_c_f64p), B, C_in, C_out, H, W, r,
                                kH, kW, stride[0], stride[1], pad[0], pad[1], dtype)
+    if nnz_norm:
+        nnz = pixel_block_counts(Z, C_in)
+        dW *= np.where(nnz > 0, r / np.maximum(nnz, 1), 0.0).reshape(1, C_in, 1, 1)
     return dW

@@ -645,3 +645,58 @@ def test_pixel_probe_rounds_the_outer_product_to_the_storage_type():
     b = xo.pixel_dw_estimate(dY, Xbar, Z, C_in, H, W, k[0], k[1], stride, pad, xo.BF16)
     rel = np.max(np.abs(a - b)) / np.max(np.abs(a))
     assert 0 < rel < 2.0 ** -6            # bf16 keeps 8 bits: the rounding shows, and stays at its size
+
+
+def test_block_sparse_pixel_probes_keep_whole_blocks_and_match_the_matrix_form():
+    # Eq. (7): a block z_{n,j} (all pixels of channel n in vector j) is kept or zeroed as a whole, the kept ones equal
+    # the dense matrix; Eq. (8): dw^{m,n} = (1/nnz(Z_n)) sum_j tr(L_j T Z_{n,j})
+    X, dY, k, stride, pad = _pixel_case(45, B=3, C_in=4, C_out=2, H=4, W=5)
+    B, C_in, H, W = X.shape
+    C_out, Ho, Wo = dY.shape[1:]
+    r, N, Np, keep = 12, H * W, Ho * Wo, 16384
+    Zd = xo.pixel_probe_matrix(xo.GAUSSIAN, 23, C_in, H, W, r)
+    Z = xo.pixel_probe_matrix(xo.GAUSSIAN, 23, C_in, H, W, r, keep_q15=keep)
+    Zb, Zdb = Z.reshape(C_in, N, r), Zd.reshape(C_in, N, r)
+    kept = np.any(Zb != 0, axis=1)                                            # [C_in, r]
+    assert 0.25 < kept.mean() < 0.75
+    assert np.array_equal(Zb, Zdb * kept[:, None, :])
+    assert np.array_equal(kept.reshape(-1), xo.keep_mask(23, keep, C_in * r) != 0)
+    assert np.array_equal(xo.pixel_block_counts(Z, C_in), kept.sum(axis=1))
+    frac = (xo.keep_mask(7, 8192, 200000) != 0).mean()
+    assert abs(frac - 0.25) < 0.005
+    Xbar = xo.pixel_probe_fwd(X, Z)
+    got = xo.pixel_dw_estimate(dY, Xbar, Z, C_in, H, W, k[0], k[1], stride, pad, nnz_norm=True)
+    coef = (Xbar * np.float32(1.0 / r)).astype(np.float64) * r                # the oracle forms Xbar / r in fp32
+    for m in range(C_out):
+        L = coef.T @ dY[:, m].reshape(B, Np).astype(np.float64)
+        for n in range(C_in):
+            nnz = int(kept[n].sum())
+            for ky in range(k[0]):
+                for kx in range(k[1]):
+                    T = np.zeros((Np, N))
+                    for oy in range(Ho):
+                        for ox in range(Wo):
+                            iy, ix = oy * stride[0] + ky - pad[0], ox * stride[1] + kx - pad[1]
+                            if 0 <= iy < H and 0 <= ix < W:
+                                T[oy * Wo + ox, iy * W + ix] = 1.0
+                    want = np.trace(L @ T @ Zb[n].astype(np.float64)) / nnz if nnz else 0.0
+                    assert abs(got[m, n, ky, kx] - want) <= 1e-6 * max(1.0, abs(want))
+
+
+def test_block_sparse_pixel_probe_estimator_is_unbiased_with_the_nnz_scaling_only():
+    X, dY, k, stride, pad = _pixel_case(46, B=4, C_in=3, C_out=2, H=6, W=6, k=(3, 3), stride=(1, 1), pad=(1, 1))
+    C_in, H, W = X.shape[1:]
+    exact = xo.dw_exact(dY, X, 3, 3, stride, pad)
+    S_list, errs, acc, acc_r, done = [16, 64, 256, 1024], [], np.zeros_like(exact), np.zeros_like(exact), 0
+    for S in S_list:
+        while done < S:
+            Z = xo.pixel_probe_matrix(xo.RADEMACHER, 700000 + done, C_in, H, W, 16, keep_q15=16384)
+            Xbar = xo.pixel_probe_fwd(X, Z)
+            acc += xo.pixel_dw_estimate(dY, Xbar, Z, C_in, H, W, 3, 3, stride, pad, nnz_norm=True)
+            acc_r += xo.pixel_dw_estimate(dY, Xbar, Z, C_in, H, W, 3, 3, stride, pad)
+            done += 1
+        errs.append(np.linalg.norm(acc / S - exact) / np.linalg.norm(exact))
+    slope = np.polyfit(np.log(S_list), np.log(errs), 1)[0]
+    assert -0.65 < slope < -0.35, (slope, errs)
+    shrink = np.sum(acc_r / done * exact) / np.sum(exact * exact)
+    assert abs(shrink - 0.5) < 0.05, shrink
