@@ -217,9 +217,14 @@ xconv_status xconv3d_xt_unpack(const xconv3d_desc *desc, const void *Xt_dev, flo
  *                                                                              (Alg. 1 bwd step 4)
  *
  * The stored state is Xbar, B*r floats: C_in*H*W/r times smaller than X in fp32.  Z is
- * regenerated in scratch in each pass (r*K values of desc->dtype).  Supported: NCHW,
- * dense Rademacher or Gaussian probes from the seed (XCONV_USER_Z and keep_q15 != 0
- * are XCONV_EUNSUPPORTED), C_in*H*W and C_out*H'*W' up to 2^28, B up to 65536.  All
+ * regenerated in scratch in each pass (r*K values of desc->dtype).  keep_q15 != 0
+ * selects block-sparse probing vectors (Eq. (7)): block (n, j), the H*W entries of
+ * vector j on channel n, is zero unless the top 15 bits of word n*r + j of the mask
+ * stream (see xconv_probe_matrix) are below keep_q15, and the estimate of input channel
+ * n is scaled by 1/nnz(Z_n), the number of kept blocks of channel n, instead of 1/r
+ * (Eq. (8)); a channel without any gives zeros.  Supported: NCHW, Rademacher or
+ * Gaussian probes from the seed (XCONV_USER_Z is XCONV_EUNSUPPORTED), C_in*H*W and
+ * C_out*H'*W' up to 2^28, B up to 65536.  All
  * other conventions as above; X_dev and dY_dev 16-byte aligned, ws_dev required. */
 size_t xconv_pixel_xbar_bytes(const xconv_desc *desc);
 size_t xconv_pixel_workspace_bytes(const xconv_desc *desc, int op);    /* XCONV_OP_PROBE or XCONV_OP_ESTIMATE */

@@ -164,9 +164,19 @@ __host__ __device__ inline ProbeGen probe_gen(int dist, uint64_t seed)
     g.mkey = mix_fin((seed ^ kMaskStream) + 0x9E3779B97F4A7C15ull);
     return g;
 }
+// keep decision `block` of block-sparse probing vectors (Eq. (7)); always true for dense probes
+__host__ __device__ inline bool probe_keep(const ProbeGen &g, uint64_t block)
+{
+    return g.keep_q15 == 0 || (int)(stream_word(g.mkey, block) >> 49) < g.keep_q15;
+}
+__host__ __device__ inline float probe_value(const ProbeGen &g, uint64_t idx);
+// entry idx of Z; with block-sparse probes it is zero unless its own keep decision says keep
 __host__ __device__ inline float probe_entry(const ProbeGen &g, uint64_t idx)
 {
-    if (g.keep_q15 != 0 && (int)(stream_word(g.mkey, idx) >> 49) >= g.keep_q15) return 0.0f;
+    return probe_keep(g, idx) ? probe_value(g, idx) : 0.0f;
+}
+__host__ __device__ inline float probe_value(const ProbeGen &g, uint64_t idx)
+{
     if (g.dist == XCONV_RADEMACHER) return (stream_word(g.key, idx) >> 63) ? -1.0f : 1.0f;
     // Box-Muller in double on two 53-bit uniforms, u1 in (0,1], u2 in [0,1)
     const double u1 = ((double)(stream_word(g.key, 2ull * idx) >> 11) + 1.0) * 0x1.0p-53;

@@ -29,6 +29,8 @@ hipError_t launch_dy_slices(int dtype, const void *src, void *dst, int B, int C,
 hipError_t launch_gen_zimg(int dtype, void *out, long long K, int r, int nimg, int dist, uint64_t seed, int C_in, int cl_cs,
                            hipStream_t st);
 hipError_t launch_scale(const float *in, float *out, int n, float f, hipStream_t st);
+// dW[:, n] *= r / (kept blocks of channel n), or 0 without any (block-sparse probes over pixels and channels, Eq. (8))
+hipError_t launch_nnz_rescale(float *dW, int C_out, int C_in, int K2, int r, int dist, uint64_t seed, hipStream_t st);
 hipError_t launch_unpack(int dtype, const void *Xt, float *out, int B, int HW, int r, int CS, hipStream_t st);
 hipError_t launch_to_nhwc(int dtype, const void *X, void *out, int B, int C, int HW, int CS, hipStream_t st);
 // channels-last [B, HW, C] -> planes [B, C, pitch], zero tail

@@ -942,6 +942,8 @@ hipError_t launch_dy_slices(int dtype, const void *src, void *dst, int B, int C,
 // images of K values in the storage type, image j = probing vector j (images r..nimg-1 are
 // zero), which is the form the probe and correlation kernels read an activation in.
 // ---------------------------------------------------------------------------
+// Block-sparse probes (Eq. (7)): block (n, j), the pixels of channel n in vector j, is zero unless keep decision
+// n * r + j of the generator says keep.
 // cl_cs == 0: image j holds its K values in row order (k fastest).  cl_cs > 0: channels-last,
 // value (n, q) of image j at (j * N + q) * cl_cs + n with zero columns C_in..cl_cs-1 (N = K / C_in
 // pixels), the form the correlation kernels read an activation in.
@@ -955,7 +957,10 @@ __global__ __launch_bounds__(kThreads) void gen_zimg_kernel(void *__restrict__ o
         if (i >= K * nimg) return;
         const int j = (int)(i / K);
         const long long k = i - (long long)j * K;
-        if (j < r) z = probe_entry(probe_gen(dist, seed), (uint64_t)k * (uint64_t)r + (uint64_t)j);
+        const ProbeGen gen = probe_gen(dist, seed);
+        const long long n = k / (K / C_in);
+        if (j < r && probe_keep(gen, (uint64_t)n * (uint64_t)r + (uint64_t)j))
+            z = probe_value(gen, (uint64_t)k * (uint64_t)r + (uint64_t)j);
     } else {
         const long long N = K / C_in;
         if (i >= N * nimg * cl_cs) return;
@@ -963,7 +968,9 @@ __global__ __launch_bounds__(kThreads) void gen_zimg_kernel(void *__restrict__ o
         const long long jq = i / cl_cs;
         const int j = (int)(jq / N);
         const long long q = jq - (long long)j * N;
-        if (j < r && n < C_in) z = probe_entry(probe_gen(dist, seed), (uint64_t)((long long)n * N + q) * (uint64_t)r + (uint64_t)j);
+        const ProbeGen gen = probe_gen(dist, seed);
+        if (j < r && n < C_in && probe_keep(gen, (uint64_t)n * (uint64_t)r + (uint64_t)j))
+            z = probe_value(gen, (uint64_t)((long long)n * N + q) * (uint64_t)r + (uint64_t)j);
     }
     if constexpr (DT == XCONV_F32) static_cast<float *>(out)[i] = z;
     else static_cast<uint16_t *>(out)[i] = f32_to_st16<DT>(z);
@@ -980,6 +987,34 @@ hipError_t launch_gen_zimg(int dtype, void *out, long long K, int r, int nimg, i
         hipLaunchKernelGGL(gen_zimg_kernel<XCONV_BF16>, grid, dim3(kThreads), 0, st, out, K, r, nimg, dist, seed, C_in, cl_cs);
     else
         hipLaunchKernelGGL(gen_zimg_kernel<XCONV_F16>, grid, dim3(kThreads), 0, st, out, K, r, nimg, dist, seed, C_in, cl_cs);
+    return hipGetLastError();
+}
+
+// Eq. (8) for probes over pixels and channels: the estimate of input channel n, which carries the factor 1/r,
+// is rescaled to 1/nnz(Z_n), nnz(Z_n) = kept blocks of channel n; a channel without any gives zeros.
+// One workgroup per input channel.
+__global__ __launch_bounds__(kThreads) void nnz_rescale_kernel(float *__restrict__ dW, int C_out, int C_in, int K2, int r, int dist,
+                                                               uint64_t seed)
+{
+    const int n = blockIdx.x;
+    const ProbeGen gen = probe_gen(dist, seed);
+    int mine = 0;
+    for (int j = threadIdx.x; j < r; j += kThreads) mine += probe_keep(gen, (uint64_t)n * (uint64_t)r + (uint64_t)j) ? 1 : 0;
+    __shared__ int total;
+    if (threadIdx.x == 0) total = 0;
+    __syncthreads();
+    if (mine) atomicAdd(&total, mine);
+    __syncthreads();
+    const float f = total > 0 ? (float)r / (float)total : 0.0f;
+    for (int i = threadIdx.x; i < C_out * K2; i += kThreads) {
+        const int m = i / K2, o = i - m * K2;
+        dW[((size_t)m * C_in + n) * K2 + o] *= f;
+    }
+}
+
+hipError_t launch_nnz_rescale(float *dW, int C_out, int C_in, int K2, int r, int dist, uint64_t seed, hipStream_t st)
+{
+    hipLaunchKernelGGL(nnz_rescale_kernel, dim3(C_in), dim3(kThreads), 0, st, dW, C_out, C_in, K2, r, dist, seed);
     return hipGetLastError();
 }
 

@@ -696,7 +696,7 @@ xconv_status pixel_geom(const xconv_desc *d, PixelGeom &g)
 {
     xconv_status s = xconv_check_desc(d);
     if (s != XCONV_OK) return s;
-    if (d->layout != XCONV_NCHW || d->probe == XCONV_USER_Z || d->keep_q15 != 0) return XCONV_EUNSUPPORTED;
+    if (d->layout != XCONV_NCHW || d->probe == XCONV_USER_Z) return XCONV_EUNSUPPORTED;
     const int Ho = out_extent(d->H, d->kH, d->stride_h, d->pad_h), Wo = out_extent(d->W, d->kW, d->stride_w, d->pad_w);
     g.K = (long long)d->C_in * d->H * d->W;
     g.P = (long long)d->C_out * Ho * Wo;
@@ -800,7 +800,11 @@ xconv_status xconv_pixel_dw_estimate(const xconv_desc *d, const void *dY_dev, co
     if (s != XCONV_OK) return s;
     XC_LAUNCH(K_REPACK, st, launch_to_nchw(d->dtype, lt, l, 1, g.CS, (int)g.P, (int)g.P, st));
     // dw_i = tr(L T_{-k(i)} Z) (Alg. 1 backward step 4; the factor 1/r is already in L)
-    return exact_impl(&g.bwd, l, nullptr, zimg, dW_dev, xws, ws_bytes - (size_t)(xws - ws), stream);
+    s = exact_impl(&g.bwd, l, nullptr, zimg, dW_dev, xws, ws_bytes - (size_t)(xws - ws), stream);
+    if (s != XCONV_OK || d->keep_q15 == 0) return s;
+    // block-sparse probes: 1/nnz(Z_n) per input channel in place of the 1/r that L carries (Eq. (8))
+    XC_LAUNCH(K_SCALE, st, launch_nnz_rescale(dW_dev, d->C_out, d->C_in, d->kH * d->kW, d->r, probe_code(d), d->seed, st));
+    return XCONV_OK;
 }
 
 void xconv_prof_enable(int on)

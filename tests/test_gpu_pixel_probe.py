@@ -13,7 +13,7 @@ from test_gpu_parity import DEV, GRAD_TOL, ODT, OPROBE, rel_max, say
 
 pytestmark = pytest.mark.gpu
 
-# name, dtype, B, C_in, C_out, H, W, k, stride, pad, r, probe
+# name, dtype, B, C_in, C_out, H, W, k, stride, pad, r, probe[, keep_q15]
 PIX = [
     ("f32-3x3", "f32", 8, 8, 16, 16, 16, 3, 1, 1, 16, "gaussian"),
     ("f32-rademacher-r5", "f32", 6, 4, 8, 12, 12, 3, 1, 1, 5, "rademacher"),
@@ -26,18 +26,25 @@ PIX = [
     ("f16-image-and-vector-blocks", "f16", 300, 4, 8, 8, 8, 3, 1, 1, 80, "rademacher"),
     ("f32-ragged-blocks", "f32", 70, 4, 4, 8, 12, 3, 1, 1, 20, "gaussian"),
     ("bf16-batch-520", "bf16", 520, 2, 4, 8, 8, 3, 1, 1, 8, "rademacher"),
+    ("f32-block-sparse", "f32", 8, 8, 16, 16, 16, 3, 1, 1, 16, "gaussian", 16384),
+    ("bf16-block-sparse", "bf16", 16, 16, 32, 12, 12, 3, 1, 1, 32, "rademacher", 12000),
+    ("f16-block-sparse-empty-channels", "f16", 6, 12, 8, 8, 8, 3, 1, 1, 2, "rademacher", 9000),
     ("f32-batch-40", "f32", 40, 8, 8, 8, 8, 3, 1, 1, 64, "rademacher"),
 ]
 
 
 def run_pixel(e):
-    name, dtype, B, C_in, C_out, H, W, k, st, pad, r, probe = e
+    name, dtype, B, C_in, C_out, H, W, k, st, pad, r, probe = e[:12]
+    keep = e[12] if len(e) > 12 else 0
     say("pixel probe %s" % (e,))
     cfg = synth.LayerConfig(name=name, B=B, C_in=C_in, C_out=C_out, H=H, W=W, k=k, stride=st, pad=pad, r=r, dtype=dtype,
                             probe=probe, x_dist="relu_normal", dy_var=1e-2, seeds=(8101 + len(name), 8202 + len(name), 8303 + len(name)))
     X, dY = synth.make_layer(cfg)
     d = xb.desc_from_config(cfg)
-    Z = xo.pixel_probe_matrix(OPROBE[probe], cfg.seeds[2], C_in, H, W, r, ODT[dtype])
+    d.keep_q15 = keep
+    Z = xo.pixel_probe_matrix(OPROBE[probe], cfg.seeds[2], C_in, H, W, r, ODT[dtype], keep)
+    if name.endswith("empty-channels"):
+        assert (xo.pixel_block_counts(Z, C_in) == 0).any()      # some channel has no block: its estimate is zero
     want_xbar = xo.pixel_probe_fwd(X, Z)
     Xd, dYd = xb.to_device(X, dtype, DEV), xb.to_device(dY, dtype, DEV)
     assert xb.xconv_pixel_xbar_bytes(d) == B * r * 4
@@ -49,7 +56,7 @@ def run_pixel(e):
     got_xbar = xbar.cpu().numpy()
     assert np.max(np.abs(got_xbar - want_xbar)) <= 1e-5 * np.max(np.abs(want_xbar)), rel_max(got_xbar, want_xbar)
     # backward from the oracle's projections, so that both sides start from the same stored state
-    want = xo.pixel_dw_estimate(dY, want_xbar, Z, C_in, H, W, k, k, (st, st), (pad, pad), ODT[dtype])
+    want = xo.pixel_dw_estimate(dY, want_xbar, Z, C_in, H, W, k, k, (st, st), (pad, pad), ODT[dtype], nnz_norm=keep != 0)
     dW = torch.full((C_out, C_in, k, k), float("nan"), dtype=torch.float32, device=DEV)
     ws2 = xb.alloc_bytes(xb.xconv_pixel_workspace_bytes(d, xb.XCONV_OP_ESTIMATE), DEV)
     ws2.fill_(0x7f)

@@ -197,7 +197,10 @@ def test_pixel_probe_sizes_and_argument_checks():
     wb = xb.xconv_pixel_workspace_bytes(d, xb.XCONV_OP_ESTIMATE)
     assert wf > 8 * 16 * 32 * 32 * 4 and wb > 16 * 16 * 32 * 32 * 4       # the probing vectors are redrawn in scratch
     assert xb.xconv_pixel_workspace_bytes(d, xb.XCONV_OP_EXACT) == 0
-    for field, val in (("layout", xb.XCONV_NHWC), ("probe", xb.XCONV_USER_Z), ("keep_q15", 100)):
+    sparse = _good()
+    sparse.keep_q15 = 100
+    assert xb.xconv_pixel_xbar_bytes(sparse) == 4 * 8 * 4
+    for field, val in (("layout", xb.XCONV_NHWC), ("probe", xb.XCONV_USER_Z)):
         bad = _good()
         setattr(bad, field, val)
         assert xb.xconv_pixel_xbar_bytes(bad) == 0 and xb.xconv_pixel_workspace_bytes(bad, 0) == 0
