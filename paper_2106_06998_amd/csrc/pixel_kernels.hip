@@ -171,6 +171,9 @@ static PixelFwdPlan pixel_fwd_plan(int dtype, long long K, int B, int r)
     const int CSt = round_up(r, 16);
     p.TM = B > 32 ? 4 : (B > 16 ? 2 : 1);
     p.TN = CSt > 32 ? 4 : (CSt > 16 ? 2 : 1);
+    if (const char *v = getenv("XCONV_PIXEL_TM")) {   // sweeps
+        if (*v == '1' || *v == '2' || *v == '4') p.TM = *v - '0';
+    }
     const int ve = dtype == XCONV_F32 ? 4 : 8;
     const int vpl = (p.TM + p.TN >= 5) ? 2 : 4;
     p.KM = 4 * vpl * ve;
