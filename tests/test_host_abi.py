@@ -234,3 +234,31 @@ def test_synthetic_inputs_are_storage_representable_and_seeded():
     assert np.array_equal((bits.astype(np.uint32) << 16).view(np.float32), X)
     h = synth.draw((64,), 5, "normal", 1.0, "f16")
     assert np.array_equal(h.astype(np.float16).astype(np.float32), h)
+
+
+def test_launch_plans_stay_within_the_device_limits_on_random_layers():
+    # host plans only: every supported layer gets a plan whose LDS, split count and tile sizes are consistent
+    rng = np.random.default_rng(77)
+    seen = set()
+    for _ in range(400):
+        dtype = ["f32", "bf16", "f16"][rng.integers(3)]
+        k = int(rng.integers(1, 6))
+        s = int(rng.integers(1, 4))
+        p = int(rng.integers(0, k + 1))
+        H, W = int(rng.integers(k, 80)), int(rng.integers(k, 80))
+        d = xb.make_desc(int(rng.integers(1, 300)), int(rng.integers(1, 300)), int(rng.integers(1, 300)), H, W, k, s, p,
+                         int(rng.integers(1, 130)), dtype)
+        if xb.xconv_check_desc(d) != xb.XCONV_OK:
+            continue
+        for op in (xb.XCONV_OP_ESTIMATE, xb.XCONV_OP_EXACT):
+            ws = xb.xconv_workspace_bytes(d, op)
+            assert ws > 0, (op, [getattr(d, f[0]) for f in d._fields_])
+            plan = xb.xconv_plan_info(d, op)
+            seen.add(plan["ws"])
+            assert 1 <= plan["S"] <= plan["NS"]
+            assert 0 < plan["lds_bytes"] <= 160 * 1024
+            assert plan["WM"] * plan["WJ"] * plan["WK"] == 4
+            assert plan["CS"] % 16 == 0 and plan["CS"] >= (d.r if op == xb.XCONV_OP_ESTIMATE else d.C_in)
+            assert plan["NTM"] * plan["M_WG"] >= d.C_out and plan["NTJ"] * plan["J_WG"] == plan["CS"]
+            assert ws < 2 ** 34
+    assert seen == {0, 1, 2}          # all three correlation kernels get layers
