@@ -157,9 +157,11 @@ xconv_status xconv_xt_unpack(const xconv_desc *desc, const void *Xt_dev, float *
  * `l` states the layer in the plane (B, channels, H, W, kH, kW, strides, pads, r,
  * dtype, probe, keep_q15, seed) exactly as for a 2-D layer; D, kD, stride_d (sd above)
  * and pad_d add the depth axis, D' = floor((D + 2*pad_d - kD)/stride_d) + 1.  Supported:
- * pad_d <= kD-1, kD <= 7 and l.layout == XCONV_NCHW, meaning X [B,C_in,D,H,W] and
- * dY [B,C_out,D',H',W']; anything else is XCONV_EUNSUPPORTED.  dW is
- * [C_out,C_in,kD,kH,kW] fp32.
+ * pad_d <= kD-1 and kD <= 7; anything else is XCONV_EUNSUPPORTED.  l.layout ==
+ * XCONV_NCHW means X [B,C_in,D,H,W] and dY [B,C_out,D',H',W'], XCONV_NHWC the
+ * channels-last forms [B,D,H,W,C_in] and [B,D',H',W',C_out] (X is then read in place
+ * by the probe, dY always through the slice-major copy; B*(D+2*pad_d) up to 65535).
+ * dW is [C_out,C_in,kD,kH,kW] fp32.
  * The conventions of the 2-D entry points (pointers, stream, status, alignment,
  * determinism, Z_dev / seed handling) hold unchanged. */
 typedef struct xconv3d_desc {

@@ -207,12 +207,14 @@ def xconv_xt_unpack(desc, Xt_dev, out_dev, stream=None):
 
 
 # ---- volumetric layers ---------------------------------------------------------
-def make_desc3d(B, C_in, C_out, D, H, W, k, stride=1, pad=0, r=1, dtype="f32", probe="rademacher", seed=0, keep_q15=0):
-    """k, stride and pad are (depth, height, width) triples or one int for all three."""
+def make_desc3d(B, C_in, C_out, D, H, W, k, stride=1, pad=0, r=1, dtype="f32", probe="rademacher", seed=0, keep_q15=0,
+                layout=XCONV_NCHW):
+    """k, stride and pad are (depth, height, width) triples or one int for all three; layout XCONV_NHWC means
+    channels-last volumes [B, D, H, W, C]."""
     kD, kH, kW = (k, k, k) if isinstance(k, int) else k
     sd, sh, sw = (stride, stride, stride) if isinstance(stride, int) else stride
     pd, ph, pw = (pad, pad, pad) if isinstance(pad, int) else pad
-    return xconv3d_desc(make_desc(B, C_in, C_out, H, W, (kH, kW), (sh, sw), (ph, pw), r, dtype, probe, seed, XCONV_NCHW, keep_q15),
+    return xconv3d_desc(make_desc(B, C_in, C_out, H, W, (kH, kW), (sh, sw), (ph, pw), r, dtype, probe, seed, layout, keep_q15),
                         D, kD, sd, pd)
 
 

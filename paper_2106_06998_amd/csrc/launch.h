@@ -22,6 +22,10 @@ hipError_t launch_probe_generic(int dtype, const void *X, const float *Z, void *
 // dY [B, C, Do, n] -> slice-major planes [B*period, C, pitch] with zero slices Do..period-1 behind every image
 hipError_t launch_zero_gap_slices(void *Xt, size_t slice_bytes, int B, SliceMap sm, hipStream_t st);
 hipError_t launch_to_slices(int dtype, const void *X, void *out, int B, int C, int CS, SliceMap sm, hipStream_t st);
+// channels-last volumes: X [B, D, HWs, C] -> slices in slot order; dY [B, Do, n, C] -> slice-major planes
+hipError_t launch_x_slices_nhwc(int dtype, const void *X, void *out, int B, int C, int CS, SliceMap sm, hipStream_t st);
+hipError_t launch_dy_slices_nhwc(int dtype, const void *src, void *dst, int B, int C, int Do, int period, int n, int pitch,
+                                 hipStream_t st);
 hipError_t launch_unpack_slices(int dtype, const void *Xt, float *out, int B, int r, int CS, SliceMap sm, hipStream_t st);
 hipError_t launch_dy_slices(int dtype, const void *src, void *dst, int B, int C, int Do, int period, int n, int pitch, hipStream_t st);
 // probing vectors over pixels and channels as `nimg` images of K storage values (entry (k, j) = word k*r + j; images >= r zero);

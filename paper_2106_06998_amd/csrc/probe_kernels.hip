@@ -866,6 +866,76 @@ hipError_t launch_to_slices(int dtype, const void *X, void *out, int B, int C, i
     return hipGetLastError();
 }
 
+// Channels-last volumes.  X [B, D, HWs, C] -> the same voxels as depth slices [slot][HWs][CS] in the slice map's
+// order with zero columns C..CS-1 (one thread per element of the output).
+template <typename T>
+__global__ __launch_bounds__(kThreads) void x_slices_nhwc_kernel(const T *__restrict__ X, T *__restrict__ out, int C, int CS, SliceMap sm,
+                                                                 long long total)
+{
+    const long long i = (long long)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= total) return;
+    const int c = (int)(i % CS);
+    long long t = i / CS;
+    const int p = (int)(t % sm.HWs);
+    t /= sm.HWs;
+    const int z = (int)(t % sm.D);
+    const long long b = t / sm.D;
+    const T v = c < C ? X[(((size_t)b * sm.D + z) * sm.HWs + p) * C + c] : T(0);
+    out[((size_t)sm.slice_of(b, z) * sm.HWs + p) * CS + c] = v;
+}
+
+hipError_t launch_x_slices_nhwc(int dtype, const void *X, void *out, int B, int C, int CS, SliceMap sm, hipStream_t st)
+{
+    const long long total = (long long)B * sm.D * sm.HWs * CS;
+    dim3 grid((unsigned)((total + kThreads - 1) / kThreads));
+    if (dtype == XCONV_F32)
+        hipLaunchKernelGGL(x_slices_nhwc_kernel<float>, grid, dim3(kThreads), 0, st, static_cast<const float *>(X),
+                           static_cast<float *>(out), C, CS, sm, total);
+    else
+        hipLaunchKernelGGL(x_slices_nhwc_kernel<uint16_t>, grid, dim3(kThreads), 0, st, static_cast<const uint16_t *>(X),
+                           static_cast<uint16_t *>(out), C, CS, sm, total);
+    return hipGetLastError();
+}
+
+// dY [B, Do, n, C] (channels-last) -> slice-major planes [B*period, C, pitch], zero tails and zero slots
+// Do..period-1 behind every image.  32x32 tiles through LDS; blockIdx.z = image * period + slot.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void dy_slices_nhwc_kernel(const T *__restrict__ src, T *__restrict__ dst, int C, int Do,
+                                                                  int period, int n, int pitch)
+{
+    __shared__ T tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+    const int p0 = blockIdx.x * 32, c0 = blockIdx.y * 32;
+    const int b = blockIdx.z / period, z = blockIdx.z % period;
+    const bool real = z < Do;
+    const T *s = src + ((size_t)b * Do + (real ? z : 0)) * n * C;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int p = p0 + ty + 8 * k, c = c0 + tx;
+        tile[ty + 8 * k][tx] = (real && p < n && c < C) ? s[(size_t)p * C + c] : T(0);
+    }
+    __syncthreads();
+    T *d = dst + (size_t)blockIdx.z * C * pitch;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int c = c0 + ty + 8 * k, p = p0 + tx;
+        if (c < C && p < pitch) d[(size_t)c * pitch + p] = tile[tx][ty + 8 * k];
+    }
+}
+
+hipError_t launch_dy_slices_nhwc(int dtype, const void *src, void *dst, int B, int C, int Do, int period, int n, int pitch,
+                                 hipStream_t st)
+{
+    dim3 grid(ceil_div(pitch, 32), ceil_div(C, 32), B * period);
+    if (dtype == XCONV_F32)
+        hipLaunchKernelGGL(dy_slices_nhwc_kernel<float>, grid, dim3(kThreads), 0, st, static_cast<const float *>(src),
+                           static_cast<float *>(dst), C, Do, period, n, pitch);
+    else
+        hipLaunchKernelGGL(dy_slices_nhwc_kernel<uint16_t>, grid, dim3(kThreads), 0, st, static_cast<const uint16_t *>(src),
+                           static_cast<uint16_t *>(dst), C, Do, period, n, pitch);
+    return hipGetLastError();
+}
+
 // Test helper: the stored probe output of a volumetric layer as plain fp32 [B, r, D, HWs].
 template <int DT>
 __global__ __launch_bounds__(kThreads) void unpack_slices_kernel(const void *__restrict__ Xtv, float *__restrict__ out, int r, int CS,

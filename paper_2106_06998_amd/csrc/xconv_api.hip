@@ -290,7 +290,7 @@ bool vol_dy_in_place(const xconv3d_desc *v, const Vol &g, PlanEntry &E, const vo
 {
     const xconv_desc *d = &v->l;
     const char *force_copy = getenv("XCONV_VOL_COPY");   // tests: take the copy route also where in-place reads fit
-    if (E.ws == 0 || !aligned16(dY_dev) || (force_copy && *force_copy == '1')) return false;
+    if (E.ws == 0 || d->layout != XCONV_NCHW || !aligned16(dY_dev) || (force_copy && *force_copy == '1')) return false;
     const long long bytes = (long long)d->B * d->C_out * g.Do * E.P.Ho * E.P.Wo * (long long)elem_bytes(d->dtype);
     if (bytes > (1LL << 30) || g.B2 >= (1LL << 22)) return false;
     E.Wp.vol_period = g.period;
@@ -500,9 +500,10 @@ xconv_status xconv3d_check_desc(const xconv3d_desc *v)
     if (s != XCONV_OK) return s;
     if (v->D < 1 || v->kD < 1 || v->pad_d < 0 || v->stride_d < 1) return XCONV_EINVAL;
     if (v->D + 2 * v->pad_d - v->kD < 0) return XCONV_EINVAL;   // empty output
-    if (v->l.layout != XCONV_NCHW || v->kD > 7 || v->pad_d > v->kD - 1) return XCONV_EUNSUPPORTED;
+    if (v->kD > 7 || v->pad_d > v->kD - 1) return XCONV_EUNSUPPORTED;
     if ((long long)v->D * v->l.H * v->l.W > (1LL << 28)) return XCONV_EUNSUPPORTED;
     if (v->stride_d > 4096 || (long long)v->l.B * (v->D + 2 * v->pad_d) > 0x7fffffffLL) return XCONV_EUNSUPPORTED;
+    if ((long long)v->l.B * (v->D + 2 * v->pad_d) > 65535 && v->l.layout == XCONV_NHWC) return XCONV_EUNSUPPORTED;   // one grid row per slot
     return XCONV_OK;
 }
 
@@ -579,7 +580,10 @@ xconv_status xconv3d_dw_estimate(const xconv3d_desc *v, const void *dY_dev, cons
     if (vol_dy_in_place(v, g, E, dY_dev)) {
         P.dY = dY_dev;
     } else {
-        XC_LAUNCH(K_REPACK, st, launch_dy_slices(d->dtype, dY_dev, dy_slices, d->B, d->C_out, g.Do, g.period, P.Ho * P.Wo, pitch, st));
+        if (d->layout == XCONV_NHWC)
+            XC_LAUNCH(K_REPACK, st, launch_dy_slices_nhwc(d->dtype, dY_dev, dy_slices, d->B, d->C_out, g.Do, g.period, P.Ho * P.Wo, pitch, st));
+        else
+            XC_LAUNCH(K_REPACK, st, launch_dy_slices(d->dtype, dY_dev, dy_slices, d->B, d->C_out, g.Do, g.period, P.Ho * P.Wo, pitch, st));
         P.dY = dy_slices;
     }
     float *part0 = reinterpret_cast<float *>(ws + zb);
@@ -629,14 +633,20 @@ xconv_status xconv3d_dw_exact(const xconv3d_desc *v, const void *dY_dev, const v
     // X -> channels-last depth slices in the slice layout of Xt, zero slots between
     const SliceMap sm = vol_map(v, g);
     if ((long long)d->B * v->D > 65535) return XCONV_EUNSUPPORTED;   // one grid row per depth slice
-    XC_LAUNCH(K_TO_NHWC, st, launch_to_slices(d->dtype, X_dev, ws, d->B, d->C_in, CSx, sm, st));
+    if (d->layout == XCONV_NHWC)
+        XC_LAUNCH(K_TO_NHWC, st, launch_x_slices_nhwc(d->dtype, X_dev, ws, d->B, d->C_in, CSx, sm, st));
+    else
+        XC_LAUNCH(K_TO_NHWC, st, launch_to_slices(d->dtype, X_dev, ws, d->B, d->C_in, CSx, sm, st));
     XC_LAUNCH(K_ZERO_GAPS, st, launch_zero_gap_slices(ws, xslice, d->B, sm, st));
     float *T3 = reinterpret_cast<float *>(ws + xb + pb);
     void *dy_slices = ws + xb + pb + tb;
     if (vol_dy_in_place(v, g, E, dY_dev)) {
         P.dY = dY_dev;
     } else {
-        XC_LAUNCH(K_REPACK, st, launch_dy_slices(d->dtype, dY_dev, dy_slices, d->B, d->C_out, g.Do, g.period, P.Ho * P.Wo, pitch, st));
+        if (d->layout == XCONV_NHWC)
+            XC_LAUNCH(K_REPACK, st, launch_dy_slices_nhwc(d->dtype, dY_dev, dy_slices, d->B, d->C_out, g.Do, g.period, P.Ho * P.Wo, pitch, st));
+        else
+            XC_LAUNCH(K_REPACK, st, launch_dy_slices(d->dtype, dY_dev, dy_slices, d->B, d->C_out, g.Do, g.period, P.Ho * P.Wo, pitch, st));
         P.dY = dy_slices;
     }
     float *part0 = reinterpret_cast<float *>(ws + xb);

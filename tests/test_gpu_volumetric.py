@@ -37,7 +37,7 @@ VOL = [
 ]
 
 
-def run_volume(e):
+def run_volume(e, nhwc=False):
     name, dtype, B, C_in, C_out, dims, k, st, pad, r, probe, keep, seed_path = e
     say("volumetric %s" % (e,))
     D, H, W = dims
@@ -46,9 +46,11 @@ def run_volume(e):
     seeds = (7101 + len(name), 7202 + len(name), 7303 + len(name))
     X, dY = synth.make_volume(B, C_in, C_out, dims, out, seeds, dtype)
     Z = xo.probe_matrix(OPROBE[probe], seeds[2], C_in, r, keep)
-    v = xb.make_desc3d(B, C_in, C_out, D, H, W, k, stride3, pad, r, dtype, probe, seeds[2], keep)
+    v = xb.make_desc3d(B, C_in, C_out, D, H, W, k, stride3, pad, r, dtype, probe, seeds[2], keep,
+                       xb.XCONV_NHWC if nhwc else xb.XCONV_NCHW)
     assert xb.xconv3d_check_desc(v) == xb.XCONV_OK
-    Xd = xb.to_device(X, dtype, DEV)
+    # channels-last: the same values handed over as [B, D, H, W, C]
+    Xd = xb.to_device(np.ascontiguousarray(X.transpose(0, 2, 3, 4, 1)) if nhwc else X, dtype, DEV)
     Xt = xb.alloc_bytes(xb.xconv3d_xt_bytes(v), DEV)
     Xt.fill_(0x7f)                                   # poison: data and the zero slices must all be written
     Zd = None if seed_path else torch.from_numpy(Z).to(DEV)
@@ -65,7 +67,7 @@ def run_volume(e):
         floor = 1e-6 if (probe == "rademacher" or dtype == "f16") else 1e-4
         tol = 2.0 * ULP[dtype] * np.maximum(np.abs(want_xt), 2.0 ** -14) + floor * scale
         assert not (np.abs(got_xt - want_xt) > tol).any(), rel_max(got_xt, want_xt)
-    dYd = xb.to_device(dY, dtype, DEV)
+    dYd = xb.to_device(np.ascontiguousarray(dY.transpose(0, 2, 3, 4, 1)) if nhwc else dY, dtype, DEV)
     dW = torch.full((C_out, C_in) + tuple(k), float("nan"), dtype=torch.float32, device=DEV)
     ws = xb.alloc_bytes(xb.xconv3d_workspace_bytes(v, xb.XCONV_OP_ESTIMATE), DEV)
     ws.fill_(0x7f)
@@ -90,6 +92,16 @@ def run_volume(e):
 @pytest.mark.parametrize("e", VOL, ids=[e[0] for e in VOL])
 def test_volumetric_layers(e):
     run_volume(e)
+
+
+NDHWC = [VOL[0], VOL[1], VOL[2], VOL[3], VOL[5], VOL[7], VOL[13], VOL[15],
+         ("f32-ndhwc-odd-channels", "f32", 2, 6, 10, (3, 5, 5), (3, 3, 3), (1, 1), (1, 1, 1), 5, "gaussian", 0, False),
+         ("bf16-ndhwc-channel-tail", "bf16", 2, 24, 40, (4, 6, 8), (3, 3, 3), (2, 1), (1, 1, 1), 16, "rademacher", 0, True)]
+
+
+@pytest.mark.parametrize("e", NDHWC, ids=[e[0] for e in NDHWC])
+def test_channels_last_volumes(e):
+    run_volume(e, nhwc=True)
 
 
 @pytest.mark.parametrize("e", [VOL[0], VOL[2], VOL[5]], ids=[VOL[0][0], VOL[2][0], VOL[5][0]])

@@ -158,7 +158,9 @@ def test_volumetric_descriptor_and_sizes():
     v.D, v.pad_d = 2, 0                                   # kernel deeper than the volume: empty output
     assert xb.xconv3d_check_desc(v) == xb.XCONV_EINVAL
     v = good()
-    v.l.layout = xb.XCONV_NHWC
+    v.l.layout = xb.XCONV_NHWC                             # channels-last volumes
+    assert xb.xconv3d_check_desc(v) == xb.XCONV_OK
+    v.l.B = 8000                                          # more slots than the channels-last copies have grid rows
     assert xb.xconv3d_check_desc(v) == xb.XCONV_EUNSUPPORTED
     v = xb.make_desc3d(1, 4, 4, 6, 8, 8, (1, 3, 3), 1, (0, 1, 1), r=4)        # a stack of independent 2-D layers
     assert xb.xconv3d_check_desc(v) == xb.XCONV_OK
