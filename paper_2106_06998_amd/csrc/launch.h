@@ -13,8 +13,9 @@ size_t zpack_bytes(int dtype, int C_in, int r, bool z_exact16);
 hipError_t launch_pack_z(int dtype, const float *Z, void *out, int C_in, int r, bool z_exact16, int dist, uint64_t seed,
                          bool nhwc, hipStream_t st);
 // sm: where the output goes in Xt (SliceMap{} = plain order; volumetric layers: depth slices in slot order)
+// Z == nullptr and zpack == nullptr: every workgroup draws its fragments of Z from (dist, seed) itself
 hipError_t launch_probe(int dtype, const void *X, const float *Z, const void *zpack, void *Xt, int B, int C_in, int HW, int r,
-                        int CS, bool z_exact16, bool nhwc, SliceMap sm, hipStream_t st);
+                        int CS, bool z_exact16, bool nhwc, SliceMap sm, int dist, uint64_t seed, hipStream_t st);
 hipError_t launch_probe_generic(int dtype, const void *X, const float *Z, void *Xt, int B, int C_in, int HW, int r, int CS,
                                 bool nhwc, SliceMap sm, hipStream_t st);
 // volumetric layers: zero the slots of Xt without image data; X -> channels-last slices in slot order;

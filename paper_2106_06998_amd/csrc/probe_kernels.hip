@@ -113,7 +113,7 @@ template <int JT, bool NHWC>
 __global__ __launch_bounds__(kThreads, (JT == 1 ? 4 : 2)) void probe_f32_kernel(const float *__restrict__ X, const float *__restrict__ Z,
                                                              const float *__restrict__ zpack, float *__restrict__ Xt, int C_in,
                                                              int HW, int r, int CS, int j0, long long ngroups, int ntiles,
-                                                             SliceMap sm)
+                                                             SliceMap sm, int dist, uint64_t seed)
 {
     extern __shared__ float zs[];  // [KQ4][JT][64] A-operand fragments, zero beyond C_in
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -128,7 +128,8 @@ __global__ __launch_bounds__(kThreads, (JT == 1 ? 4 : 2)) void probe_f32_kernel(
                 const int l = e & 63, jt = (e >> 6) % JT, kq = (e >> 6) / JT;
                 const int c = f32_frag_channel(kq, l >> 4, NHWC);
                 const int j = j0 + jmap(jt, l & 15, JT);
-                zs[e] = (c < C_in && j < r) ? Z[(size_t)c * r + j] : 0.0f;
+                // without a Z in memory the entries are drawn here (small seed-defined Z: no launch of their own)
+                zs[e] = (c < C_in && j < r) ? (Z ? Z[(size_t)c * r + j] : probe_entry(probe_gen(dist, seed), (uint64_t)c * r + j)) : 0.0f;
             }
         }
     };
@@ -279,7 +280,7 @@ template <int DT, int JT, int PT, bool SPLIT, bool NHWC>
 __global__ __launch_bounds__(kThreads, 2) void probe_16_kernel(const uint16_t *__restrict__ X, const float *__restrict__ Z,
                                                             const uint4 *__restrict__ zpack, uint16_t *__restrict__ Xt, int C_in,
                                                             int HW, int r, int CS, int j0, long long ngroups, int ntiles,
-                                                            SliceMap sm)
+                                                            SliceMap sm, int dist, uint64_t seed)
 {
     extern __shared__ uint4 zf[];  // [SPLIT?2:1][KK][JT][64] A-operand fragments
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -300,7 +301,9 @@ __global__ __launch_bounds__(kThreads, 2) void probe_16_kernel(const uint16_t *_
 #pragma unroll
                     for (int q = 0; q < 8; ++q) {
                         const int c = kk * 32 + 8 * (l >> 4) + q;
-                        z[k][q] = (e < nfrag && c < C_in && j < r) ? Z[(size_t)c * r + j] : 0.0f;
+                        z[k][q] = (e < nfrag && c < C_in && j < r)
+                                      ? (Z ? Z[(size_t)c * r + j] : probe_entry(probe_gen(dist, seed), (uint64_t)c * r + j))
+                                      : 0.0f;
                     }
                 }
 #pragma unroll
@@ -649,7 +652,7 @@ static int probe_grid(int ntiles)
 
 template <int JT, bool NHWC>
 static hipError_t launch_probe_f32_jt(const float *X, const float *Z, const float *zpack, float *Xt, int C_in, int HW, int r, int CS,
-                                      int j0, long long npix, SliceMap sm, hipStream_t st)
+                                      int j0, long long npix, SliceMap sm, int dist, uint64_t seed, hipStream_t st)
 {
     // a lane owns 4 consecutive pixels of a plane (NCHW) or one pixel of each of 4 sub-tiles (NHWC)
     const long long ngroups = NHWC ? npix : npix / 4;
@@ -658,13 +661,13 @@ static hipError_t launch_probe_f32_jt(const float *X, const float *Z, const floa
     hipError_t e = set_lds(probe_f32_kernel<JT, NHWC>, lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((probe_f32_kernel<JT, NHWC>), dim3(probe_grid(ntiles)), dim3(kThreads), lds, st, X, Z, zpack, Xt, C_in, HW, r,
-                       CS, j0, ngroups, ntiles, sm);
+                       CS, j0, ngroups, ntiles, sm, dist, seed);
     return hipGetLastError();
 }
 
 template <int DT, int JT, int PT, bool SPLIT, bool NHWC>
 static hipError_t launch_probe_16_cfg(const uint16_t *X, const float *Z, const uint4 *zpack, uint16_t *Xt, int C_in, int HW, int r,
-                                      int CS, int j0, long long npix, SliceMap sm, hipStream_t st)
+                                      int CS, int j0, long long npix, SliceMap sm, int dist, uint64_t seed, hipStream_t st)
 {
     const long long ngroups = NHWC ? npix : npix / PT;
     const int ntiles = (int)(NHWC ? (npix + 16 * PT - 1) / (16 * PT) : (ngroups + 15) / 16);
@@ -672,27 +675,27 @@ static hipError_t launch_probe_16_cfg(const uint16_t *X, const float *Z, const u
     hipError_t e = set_lds(probe_16_kernel<DT, JT, PT, SPLIT, NHWC>, lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((probe_16_kernel<DT, JT, PT, SPLIT, NHWC>), dim3(probe_grid(ntiles)), dim3(kThreads), lds, st, X, Z, zpack,
-                       Xt, C_in, HW, r, CS, j0, ngroups, ntiles, sm);
+                       Xt, C_in, HW, r, CS, j0, ngroups, ntiles, sm, dist, seed);
     return hipGetLastError();
 }
 
 template <int DT, int JT>
 static hipError_t launch_probe_16_jt(const uint16_t *X, const float *Z, const uint4 *zpack, uint16_t *Xt, int C_in, int HW, int r,
-                                     int CS, int j0, long long npix, bool split, bool nhwc, SliceMap sm, hipStream_t st)
+                                     int CS, int j0, long long npix, bool split, bool nhwc, SliceMap sm, int dist, uint64_t seed, hipStream_t st)
 {
     if (nhwc) {
-        if (split) return launch_probe_16_cfg<DT, JT, 4, true, true>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, sm, st);
-        return launch_probe_16_cfg<DT, JT, 4, false, true>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, sm, st);
+        if (split) return launch_probe_16_cfg<DT, JT, 4, true, true>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, sm, dist, seed, st);
+        return launch_probe_16_cfg<DT, JT, 4, false, true>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, sm, dist, seed, st);
     }
     // 8 pixels per lane when the accumulators stay small, 4 for wide probe blocks
     if constexpr (JT <= 2) {
         if ((sm.sd ? sm.HWs : HW) % 8 == 0) {
-            if (split) return launch_probe_16_cfg<DT, JT, 8, true, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, sm, st);
-            return launch_probe_16_cfg<DT, JT, 8, false, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, sm, st);
+            if (split) return launch_probe_16_cfg<DT, JT, 8, true, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, sm, dist, seed, st);
+            return launch_probe_16_cfg<DT, JT, 8, false, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, sm, dist, seed, st);
         }
     }
-    if (split) return launch_probe_16_cfg<DT, JT, 4, true, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, sm, st);
-    return launch_probe_16_cfg<DT, JT, 4, false, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, sm, st);
+    if (split) return launch_probe_16_cfg<DT, JT, 4, true, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, sm, dist, seed, st);
+    return launch_probe_16_cfg<DT, JT, 4, false, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, sm, dist, seed, st);
 }
 
 bool probe_fast_path_ok(int dtype, int C_in, int HW, bool nhwc)
@@ -737,7 +740,7 @@ hipError_t launch_pack_z(int dtype, const float *Z, void *out, int C_in, int r, 
 // zpack: Z in fragment order (launch_pack_z) or nullptr, in which case every workgroup gathers
 // its fragments from Z itself.
 hipError_t launch_probe(int dtype, const void *X, const float *Z, const void *zpack, void *Xt, int B, int C_in, int HW, int r,
-                        int CS, bool z_exact16, bool nhwc, SliceMap sm, hipStream_t st)
+                        int CS, bool z_exact16, bool nhwc, SliceMap sm, int dist, uint64_t seed, hipStream_t st)
 {
     const long long npix = (long long)B * HW;
     const int ntj = CS / 16;
@@ -752,10 +755,10 @@ hipError_t launch_probe(int dtype, const void *X, const float *Z, const void *zp
             const float *zp = zpack ? static_cast<const float *>(zpack) + bi * ceil_div(C_in, 16) * 4 * 4 * 64 : nullptr;
 #define XC_P32(NH)                                                                                  \
     switch (jt) {                                                                                   \
-    case 1: e = launch_probe_f32_jt<1, NH>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, sm, st); break;      \
-    case 2: e = launch_probe_f32_jt<2, NH>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, sm, st); break;      \
-    case 3: e = launch_probe_f32_jt<3, NH>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, sm, st); break;      \
-    default: e = launch_probe_f32_jt<4, NH>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, sm, st); break;     \
+    case 1: e = launch_probe_f32_jt<1, NH>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, sm, dist, seed, st); break;      \
+    case 2: e = launch_probe_f32_jt<2, NH>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, sm, dist, seed, st); break;      \
+    case 3: e = launch_probe_f32_jt<3, NH>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, sm, dist, seed, st); break;      \
+    default: e = launch_probe_f32_jt<4, NH>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, sm, dist, seed, st); break;     \
     }
             if (nhwc) { XC_P32(true) } else { XC_P32(false) }
 #undef XC_P32
@@ -766,10 +769,10 @@ hipError_t launch_probe(int dtype, const void *X, const float *Z, const void *zp
             const uint4 *zp = zpack ? static_cast<const uint4 *>(zpack) + bi * ceil_div(C_in, 32) * 4 * 64 * (split ? 2 : 1) : nullptr;
 #define XC_P16(DT)                                                                                            \
     switch (jt) {                                                                                             \
-    case 1: e = launch_probe_16_jt<DT, 1>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, nhwc, sm, st); break;          \
-    case 2: e = launch_probe_16_jt<DT, 2>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, nhwc, sm, st); break;          \
-    case 3: e = launch_probe_16_jt<DT, 3>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, nhwc, sm, st); break;          \
-    default: e = launch_probe_16_jt<DT, 4>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, nhwc, sm, st); break;         \
+    case 1: e = launch_probe_16_jt<DT, 1>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, nhwc, sm, dist, seed, st); break;          \
+    case 2: e = launch_probe_16_jt<DT, 2>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, nhwc, sm, dist, seed, st); break;          \
+    case 3: e = launch_probe_16_jt<DT, 3>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, nhwc, sm, dist, seed, st); break;          \
+    default: e = launch_probe_16_jt<DT, 4>(x, Z, zp, o, C_in, HW, r, CS, j0, npix, split, nhwc, sm, dist, seed, st); break;         \
     }
             if (dtype == XCONV_BF16) { XC_P16(XCONV_BF16) } else { XC_P16(XCONV_F16) }
 #undef XC_P16
