@@ -222,6 +222,20 @@ def test_pixel_probe_sizes_and_argument_checks():
     assert L.xconv_pixel_dw_estimate(ctypes.byref(bad), one, one, one, one, 1 << 30, None) == xb.XCONV_EINVAL
 
 
+def test_pixel_probe_state_reproduces_the_paper_memory_ratio():
+    # Sec. 4.1 worked example: a 32x32 image with 16 input channels, r = 2^gamma probing vectors: the stored state of the
+    # probe over pixels and channels is N*C_in/r = 2^(14-gamma) times smaller than the activation (same element size)
+    path = os.path.join(ROOT, "tests", "golden", "paper_memory_ratio.txt")
+    rows = [tuple(int(t) for t in line.split()) for line in open(path) if line.strip() and not line.startswith("#")]
+    assert len(rows) == 8
+    for gamma, ratio in rows:
+        d = xb.make_desc(4, 16, 8, 32, 32, 3, 1, 1, 2 ** gamma, "f32")
+        act = d.B * d.C_in * d.H * d.W * 4
+        assert act // xb.xconv_pixel_xbar_bytes(d) == ratio
+        # the channel probe keeps H*W values per probing vector instead: C_in / r (r is stored padded to 16 columns)
+        assert act * 16 // xb.xconv_xt_bytes(d) == 16 * 16 // max(2 ** gamma, 16)
+
+
 def test_synthetic_inputs_are_storage_representable_and_seeded():
     cfg = synth.small_variant(synth.CONFIGS["C3"], B=2, H=12, W=12, C_in=8, C_out=8)
     X, dY = synth.make_layer(cfg)
