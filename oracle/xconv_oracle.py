@@ -1,10 +1,11 @@
 """ctypes front end of the CPU oracle (oracle/xconv_oracle.c).
 
 TEST INFRASTRUCTURE ONLY.  Only tests/, __graft_entry__.smoke() and the
-cpu_baseline leg of bench.py may import this module.  It holds no arithmetic of
-its own: every function marshals numpy arrays into the C routine of the same
-name, where the paper's formulas are written out (Sec. 3 Eq. (2), (3), (5),
-(6); Algorithm 1).
+cpu_baseline leg of bench.py may import this module.  The functions marshal
+numpy arrays into the C routine of the same name, where the paper's formulas
+are written out (Sec. 3 Eq. (2), (3), (5), (6); Algorithm 1); what is stated
+here in numpy is the block mask and 1/nnz scaling of Eq. (7)/(8) and the
+independent probing mode, a loop of single-channel calls.
 
 Array conventions: float32 inputs whose values are already representable in
 the storage type; gradients come back as float64.
@@ -358,4 +359,34 @@ def pixel_dw_estimate(dY, Xbar, Z, C_in, H, W, kH, kW, stride=(1, 1), pad=(0, 0)
     if nnz_norm:
         nnz = pixel_block_counts(Z, C_in)
         dW *= np.where(nnz > 0, r / np.maximum(nnz, 1), 0.0).reshape(1, C_in, 1, 1)
+    return dW
+
+
+def pixel_indep_probe_fwd(X, Z):
+    """Independent probing (Sec. 3, the per-channel alternative to Eq. (6)): every input channel n is
+    probed on its own with Z_n [H*W, r], the rows of channel n of Z [C_in*H*W, r].  Xbar [B, C_in, r]:
+    channel n is the single-channel forward product of X[:, n] with Z_n."""
+    X = np.asarray(X, dtype=np.float32)
+    Z = np.asarray(Z, dtype=np.float32)
+    B, C_in, H, W = X.shape
+    N = H * W
+    assert Z.shape[0] == C_in * N
+    Xbar = np.empty((B, C_in, Z.shape[1]), dtype=np.float32)
+    for n in range(C_in):
+        Xbar[:, n, :] = pixel_probe_fwd(X[:, n:n + 1], Z[n * N:(n + 1) * N])
+    return Xbar
+
+
+def pixel_indep_dw_estimate(dY, Xbar, Z, C_in, H, W, kH, kW, stride=(1, 1), pad=(0, 0), dtype=F32):
+    """Independent probing, backward: the trace estimate of every (input, output) channel pair uses the
+    probes of its own input channel only, so column n of dW is the single-channel estimate (Alg. 1
+    backward with C_in = 1) from Xbar[:, n] and Z_n; no term mixes two input channels."""
+    Xbar = np.asarray(Xbar, dtype=np.float32)
+    Z = np.asarray(Z, dtype=np.float32)
+    N = H * W
+    C_out = np.asarray(dY).shape[1]
+    assert Xbar.shape[1] == C_in and Z.shape[0] == C_in * N
+    dW = np.empty((C_out, C_in, kH, kW), dtype=np.float64)
+    for n in range(C_in):
+        dW[:, n:n + 1] = pixel_dw_estimate(dY, Xbar[:, n, :], Z[n * N:(n + 1) * N], 1, H, W, kH, kW, stride, pad, dtype)
     return dW

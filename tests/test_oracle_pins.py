@@ -700,3 +700,85 @@ def test_block_sparse_pixel_probe_estimator_is_unbiased_with_the_nnz_scaling_onl
     assert -0.65 < slope < -0.35, (slope, errs)
     shrink = np.sum(acc_r / done * exact) / np.sum(exact * exact)
     assert abs(shrink - 0.5) < 0.05, shrink
+
+
+# ---------------------------------------------------------------------------
+# independent probing: every input channel with probes of its own (Sec. 3, the alternative to Eq. (6))
+# ---------------------------------------------------------------------------
+def _hadamard(n):
+    Hd = np.array([[1.0]])
+    while Hd.shape[0] < n:
+        Hd = np.block([[Hd, Hd], [Hd, -Hd]])
+    return Hd
+
+
+def test_independent_probing_with_orthogonal_probes_per_channel_is_exact():
+    # r = N probes per channel with Z_n Z_n^T = r I probe every channel pair exactly, although r < C_in*N; the
+    # channels get different orthogonal matrices, so a probe taken from the wrong channel fails
+    X, dY, k, stride, pad = _pixel_case(47, B=3, C_in=3, C_out=2, H=4, W=4)
+    B, C_in, H, W = X.shape
+    N = H * W
+    rng = np.random.default_rng(5)
+    Z = np.concatenate([(_hadamard(N) * rng.choice([-1.0, 1.0], size=(1, N)))[rng.permutation(N)] for _ in range(C_in)])
+    Z = Z.astype(np.float32)
+    Xbar = xo.pixel_indep_probe_fwd(X, Z)
+    assert Xbar.shape == (B, C_in, N)
+    est = xo.pixel_indep_dw_estimate(dY, Xbar, Z, C_in, H, W, k[0], k[1], stride, pad)
+    exact = xo.dw_exact(dY, X, k[0], k[1], stride, pad)
+    assert np.max(np.abs(est - exact)) <= 1e-5 * np.max(np.abs(exact))
+    # the same probes used for all channels at once (Eq. (6)) are not exact: the test separates the two modes
+    sim = xo.pixel_dw_estimate(dY, xo.pixel_probe_fwd(X, Z), Z, C_in, H, W, k[0], k[1], stride, pad)
+    assert np.max(np.abs(sim - exact)) > 0.05 * np.max(np.abs(exact))
+
+
+def test_independent_probing_state_sums_to_the_multi_channel_state_and_has_no_crosstalk():
+    X, dY, k, stride, pad = _pixel_case(48, B=4, C_in=3, C_out=2, H=5, W=4)
+    B, C_in, H, W = X.shape
+    r = 6
+    Z = xo.pixel_probe_matrix(xo.GAUSSIAN, 29, C_in, H, W, r)
+    Xbar = xo.pixel_indep_probe_fwd(X, Z)
+    # Eq. (6) probes the stacked matrix: its state is the sum of the per-channel states
+    np.testing.assert_allclose(Xbar.astype(np.float64).sum(axis=1), xo.pixel_probe_fwd(X, Z), rtol=0, atol=2e-5)
+    # an input that lives on one channel gives no gradient on the others, whatever the probes (the multi-channel
+    # estimate does: that is its crosstalk)
+    X1 = X.copy()
+    X1[:, 1:] = 0
+    est = xo.pixel_indep_dw_estimate(dY, xo.pixel_indep_probe_fwd(X1, Z), Z, C_in, H, W, k[0], k[1], stride, pad)
+    assert np.all(est[:, 1:] == 0) and np.any(est[:, 0] != 0)
+    sim = xo.pixel_dw_estimate(dY, xo.pixel_probe_fwd(X1, Z), Z, C_in, H, W, k[0], k[1], stride, pad)
+    assert np.any(sim[:, 1:] != 0)
+
+
+def test_independent_probing_equals_multi_channel_probing_with_block_diagonal_vectors():
+    # C_in*r vectors, vector (n, j) non-zero on channel n only where it equals Z_n[:, j]: Eq. (6) with these vectors
+    # and the factor 1/r is the independent estimate
+    X, dY, k, stride, pad = _pixel_case(49, B=3, C_in=3, C_out=2, H=4, W=5)
+    B, C_in, H, W = X.shape
+    N, r = H * W, 4
+    Z = xo.pixel_probe_matrix(xo.RADEMACHER, 31, C_in, H, W, r)
+    Zd = np.zeros((C_in * N, C_in * r), dtype=np.float32)
+    for n in range(C_in):
+        Zd[n * N:(n + 1) * N, n * r:(n + 1) * r] = Z[n * N:(n + 1) * N]
+    Xbar = xo.pixel_indep_probe_fwd(X, Z)
+    np.testing.assert_allclose(xo.pixel_probe_fwd(X, Zd), Xbar.reshape(B, C_in * r), rtol=0, atol=1e-6)
+    want = xo.pixel_dw_estimate(dY, Xbar.reshape(B, C_in * r), Zd, C_in, H, W, k[0], k[1], stride, pad) * C_in
+    got = xo.pixel_indep_dw_estimate(dY, Xbar, Z, C_in, H, W, k[0], k[1], stride, pad)
+    assert np.max(np.abs(got - want)) <= 2e-6 * np.max(np.abs(want))
+
+
+def test_independent_probing_is_unbiased_and_closer_than_multi_channel_probing():
+    X, dY, k, stride, pad = _pixel_case(50, B=4, C_in=4, C_out=2, H=6, W=6, k=(3, 3), stride=(1, 1), pad=(1, 1))
+    C_in, H, W = X.shape[1:]
+    exact = xo.dw_exact(dY, X, 3, 3, stride, pad)
+    acc, e_ind, e_sim, S = np.zeros_like(exact), 0.0, 0.0, 256
+    for t in range(S):
+        Z = xo.pixel_probe_matrix(xo.RADEMACHER, 900000 + t, C_in, H, W, 8)
+        ind = xo.pixel_indep_dw_estimate(dY, xo.pixel_indep_probe_fwd(X, Z), Z, C_in, H, W, 3, 3, stride, pad)
+        sim = xo.pixel_dw_estimate(dY, xo.pixel_probe_fwd(X, Z), Z, C_in, H, W, 3, 3, stride, pad)
+        acc += ind
+        e_ind += np.sum((ind - exact) ** 2)
+        e_sim += np.sum((sim - exact) ** 2)
+    one = np.sqrt(e_ind / S) / np.linalg.norm(exact)
+    mean = np.linalg.norm(acc / S - exact) / np.linalg.norm(exact)
+    assert mean < 3.0 * one / np.sqrt(S), (mean, one)                       # the mean of S draws shrinks like 1/sqrt(S)
+    assert e_ind < 0.6 * e_sim, (e_ind, e_sim)                               # C_in = 4 channels of crosstalk removed
