@@ -235,6 +235,26 @@ xconv_status xconv_pixel_probe_fwd(const xconv_desc *desc, const void *X_dev, fl
 xconv_status xconv_pixel_dw_estimate(const xconv_desc *desc, const void *dY_dev, const float *Xbar_dev,
                                      float *dW_dev, void *ws_dev, size_t ws_bytes, void *stream);
 
+/* Independent probing (Sec. 3: trace estimation applied to every input/output channel
+ * pair on its own, the alternative that the multi-channel case of Eq. (6) is set
+ * against; the experiments' "Indep." curves): input channel n has r probing vectors of
+ * its own, Z_n [H*W, r] = the rows of channel n of the Z above (same generator words),
+ *
+ *   forward   Xbar[b,n,j] = sum_{y,x} Z_n[(y,x),j] X[b,n,y,x]
+ *   backward  L_n[j,m,oy,ox] = (1/r) sum_b Xbar[b,n,j] dY[b,m,oy,ox], rounded once to desc->dtype
+ *             dW[m,n,ky,kx] = sum_j sum_{oy,ox} L_n[j,m,oy,ox] Z_n[(oy*sh+ky-ph, ox*sw+kx-pw), j]
+ *
+ * so no term mixes two input channels (no crosstalk), at C_in times the stored state:
+ * Xbar is [B, C_in, r] floats, H*W/r times smaller than X in fp32.  Computed as the
+ * multi-channel estimator with C_in*r block-diagonal probing vectors; limits as above
+ * and C_in*r <= 1024, keep_q15 == 0 (else XCONV_EUNSUPPORTED). */
+size_t xconv_pixel_indep_xbar_bytes(const xconv_desc *desc);
+size_t xconv_pixel_indep_workspace_bytes(const xconv_desc *desc, int op);
+xconv_status xconv_pixel_indep_probe_fwd(const xconv_desc *desc, const void *X_dev, float *Xbar_dev,
+                                         void *ws_dev, size_t ws_bytes, void *stream);
+xconv_status xconv_pixel_indep_dw_estimate(const xconv_desc *desc, const void *dY_dev, const float *Xbar_dev,
+                                           float *dW_dev, void *ws_dev, size_t ws_bytes, void *stream);
+
 /* Per-kernel timing with HIP events recorded on the launch stream.  While
  * enabled, every kernel the library enqueues is bracketed by two events.
  * xconv_prof_collect synchronises those events, writes up to `max` records

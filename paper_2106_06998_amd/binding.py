@@ -98,6 +98,14 @@ def lib():
         L.xconv_pixel_probe_fwd.argtypes = [P, vp, vp, vp, sz, vp]
         L.xconv_pixel_dw_estimate.restype = i32
         L.xconv_pixel_dw_estimate.argtypes = [P, vp, vp, vp, vp, sz, vp]
+        L.xconv_pixel_indep_xbar_bytes.restype = sz
+        L.xconv_pixel_indep_xbar_bytes.argtypes = [P]
+        L.xconv_pixel_indep_workspace_bytes.restype = sz
+        L.xconv_pixel_indep_workspace_bytes.argtypes = [P, i32]
+        L.xconv_pixel_indep_probe_fwd.restype = i32
+        L.xconv_pixel_indep_probe_fwd.argtypes = [P, vp, vp, vp, sz, vp]
+        L.xconv_pixel_indep_dw_estimate.restype = i32
+        L.xconv_pixel_indep_dw_estimate.argtypes = [P, vp, vp, vp, vp, sz, vp]
         L.xconv_prof_enable.restype = None
         L.xconv_prof_enable.argtypes = [i32]
         L.xconv_prof_collect.restype = i32
@@ -303,3 +311,22 @@ def to_device(values_f32, dtype, device="cuda:0"):
     t = torch.from_numpy(np.ascontiguousarray(values_f32, dtype=np.float32))
     td = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[dtype]
     return t.to(td).to(device)
+
+
+# ---- independent probing: every input channel with probing vectors of its own --------
+def xconv_pixel_indep_xbar_bytes(desc):
+    return int(lib().xconv_pixel_indep_xbar_bytes(ctypes.byref(desc)))
+
+
+def xconv_pixel_indep_workspace_bytes(desc, op):
+    return int(lib().xconv_pixel_indep_workspace_bytes(ctypes.byref(desc), int(op)))
+
+
+def xconv_pixel_indep_probe_fwd(desc, X_dev, Xbar_dev, ws_dev, stream=None):
+    _check(lib().xconv_pixel_indep_probe_fwd(ctypes.byref(desc), _ptr(X_dev), _ptr(Xbar_dev), _ptr(ws_dev), _nbytes(ws_dev),
+                                             _stream(stream)), "xconv_pixel_indep_probe_fwd")
+
+
+def xconv_pixel_indep_dw_estimate(desc, dY_dev, Xbar_dev, dW_dev, ws_dev, stream=None):
+    _check(lib().xconv_pixel_indep_dw_estimate(ctypes.byref(desc), _ptr(dY_dev), _ptr(Xbar_dev), _ptr(dW_dev), _ptr(ws_dev),
+                                               _nbytes(ws_dev), _stream(stream)), "xconv_pixel_indep_dw_estimate")

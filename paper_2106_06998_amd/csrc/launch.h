@@ -30,9 +30,10 @@ hipError_t launch_dy_slices_nhwc(int dtype, const void *src, void *dst, int B, i
 hipError_t launch_unpack_slices(int dtype, const void *Xt, float *out, int B, int r, int CS, SliceMap sm, hipStream_t st);
 hipError_t launch_dy_slices(int dtype, const void *src, void *dst, int B, int C, int Do, int period, int n, int pitch, hipStream_t st);
 // probing vectors over pixels and channels as `nimg` images of K storage values (entry (k, j) = word k*r + j; images >= r zero);
-// cl_cs > 0: each image channels-last [pixel][cl_cs] (k = channel * pixels + pixel), zero columns C_in..cl_cs-1
+// cl_cs > 0: each image channels-last [pixel][cl_cs] (k = channel * pixels + pixel), zero columns C_in..cl_cs-1;
+// indep != 0: C_in*r vectors, vector n*r + j = column j of Z on the rows of channel n, zero elsewhere
 hipError_t launch_gen_zimg(int dtype, void *out, long long K, int r, int nimg, int dist, uint64_t seed, int C_in, int cl_cs,
-                           hipStream_t st);
+                           int indep, hipStream_t st);
 hipError_t launch_scale(const float *in, float *out, int n, float f, hipStream_t st);
 // dW[:, n] *= r / (kept blocks of channel n), or 0 without any (block-sparse probes over pixels and channels, Eq. (8))
 hipError_t launch_nnz_rescale(float *dW, int C_out, int C_in, int K2, int r, int dist, uint64_t seed, hipStream_t st);

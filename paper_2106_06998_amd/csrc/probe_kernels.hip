@@ -1020,46 +1020,53 @@ hipError_t launch_dy_slices(int dtype, const void *src, void *dst, int B, int C,
 // cl_cs == 0: image j holds its K values in row order (k fastest).  cl_cs > 0: channels-last,
 // value (n, q) of image j at (j * N + q) * cl_cs + n with zero columns C_in..cl_cs-1 (N = K / C_in
 // pixels), the form the correlation kernels read an activation in.
+// indep != 0: independent probing, C_in * r images; image n * r + j is probing vector j of channel n, the values
+// of column j of Z on the rows of channel n and zero on every other channel.
 template <int DT>
 __global__ __launch_bounds__(kThreads) void gen_zimg_kernel(void *__restrict__ out, long long K, int r, int nimg, int dist,
-                                                            uint64_t seed, int C_in, int cl_cs)
+                                                            uint64_t seed, int C_in, int cl_cs, int indep)
 {
     const long long i = (long long)blockIdx.x * kThreads + threadIdx.x;
+    const int ncol = indep ? C_in * r : r;
     float z = 0.0f;
+    int j;
+    long long k, n;
     if (cl_cs == 0) {
         if (i >= K * nimg) return;
-        const int j = (int)(i / K);
-        const long long k = i - (long long)j * K;
-        const ProbeGen gen = probe_gen(dist, seed);
-        const long long n = k / (K / C_in);
-        if (j < r && probe_keep(gen, (uint64_t)n * (uint64_t)r + (uint64_t)j))
-            z = probe_value(gen, (uint64_t)k * (uint64_t)r + (uint64_t)j);
+        j = (int)(i / K);
+        k = i - (long long)j * K;
+        n = k / (K / C_in);
     } else {
         const long long N = K / C_in;
         if (i >= N * nimg * cl_cs) return;
-        const int n = (int)(i % cl_cs);
+        n = i % cl_cs;
         const long long jq = i / cl_cs;
-        const int j = (int)(jq / N);
-        const long long q = jq - (long long)j * N;
+        j = (int)(jq / N);
+        k = n * N + (jq - (long long)j * N);
+    }
+    if (j < ncol && n < C_in) {
         const ProbeGen gen = probe_gen(dist, seed);
-        if (j < r && n < C_in && probe_keep(gen, (uint64_t)n * (uint64_t)r + (uint64_t)j))
-            z = probe_value(gen, (uint64_t)((long long)n * N + q) * (uint64_t)r + (uint64_t)j);
+        if (indep) {
+            if (j / r == n) z = probe_value(gen, (uint64_t)k * (uint64_t)r + (uint64_t)(j % r));
+        } else if (probe_keep(gen, (uint64_t)n * (uint64_t)r + (uint64_t)j)) {
+            z = probe_value(gen, (uint64_t)k * (uint64_t)r + (uint64_t)j);
+        }
     }
     if constexpr (DT == XCONV_F32) static_cast<float *>(out)[i] = z;
     else static_cast<uint16_t *>(out)[i] = f32_to_st16<DT>(z);
 }
 
 hipError_t launch_gen_zimg(int dtype, void *out, long long K, int r, int nimg, int dist, uint64_t seed, int C_in, int cl_cs,
-                           hipStream_t st)
+                           int indep, hipStream_t st)
 {
     const long long total = cl_cs ? (K / C_in) * nimg * cl_cs : K * nimg;
     dim3 grid((unsigned)((total + kThreads - 1) / kThreads));
     if (dtype == XCONV_F32)
-        hipLaunchKernelGGL(gen_zimg_kernel<XCONV_F32>, grid, dim3(kThreads), 0, st, out, K, r, nimg, dist, seed, C_in, cl_cs);
+        hipLaunchKernelGGL(gen_zimg_kernel<XCONV_F32>, grid, dim3(kThreads), 0, st, out, K, r, nimg, dist, seed, C_in, cl_cs, indep);
     else if (dtype == XCONV_BF16)
-        hipLaunchKernelGGL(gen_zimg_kernel<XCONV_BF16>, grid, dim3(kThreads), 0, st, out, K, r, nimg, dist, seed, C_in, cl_cs);
+        hipLaunchKernelGGL(gen_zimg_kernel<XCONV_BF16>, grid, dim3(kThreads), 0, st, out, K, r, nimg, dist, seed, C_in, cl_cs, indep);
     else
-        hipLaunchKernelGGL(gen_zimg_kernel<XCONV_F16>, grid, dim3(kThreads), 0, st, out, K, r, nimg, dist, seed, C_in, cl_cs);
+        hipLaunchKernelGGL(gen_zimg_kernel<XCONV_F16>, grid, dim3(kThreads), 0, st, out, K, r, nimg, dist, seed, C_in, cl_cs, indep);
     return hipGetLastError();
 }
 

@@ -698,62 +698,67 @@ xconv_status xconv3d_xt_unpack(const xconv3d_desc *v, const void *Xt_dev, float 
 //             channels and P = C_out*H'*W' pixels, with Xbar/r as its probing matrix; brought into
 //             planes L[j,m,oy,ox] it is the residual of a batch of r images whose activations are
 //             the probing vectors, and dW is the exact-gradient path of that batch.
+// Independent probing (every input channel with r probing vectors of its own, Sec. 3) runs the same
+// steps with R = C_in*r vectors that are block diagonal over the channels: vector n*r + j is column j
+// of Z on the rows of channel n and zero elsewhere, and the factor stays 1/r.
 namespace {
 
 struct PixelGeom {
     long long K, P;      // values per image of X and of dY
-    int CS;              // r rounded up to 16: images of L and of Z in the backward pass
+    int R;               // probing vectors of the products: r, or C_in*r with independent probing
+    int CS;              // R rounded up to 16: images of L and of Z in the backward pass
     xconv_desc fwd;      // 1x1 layer of the forward product
     xconv_desc probe;    // single-image channel probe of the backward pass (B channels)
     xconv_desc bwd;      // batch of CS images of the shifted product
     size_t zimg_f, zimg_b, xs, lt, l, probe_ws;
 };
 
-xconv_status pixel_geom(const xconv_desc *d, PixelGeom &g)
+xconv_status pixel_geom(const xconv_desc *d, bool indep, PixelGeom &g)
 {
     xconv_status s = xconv_check_desc(d);
     if (s != XCONV_OK) return s;
     if (d->layout != XCONV_NCHW || d->probe == XCONV_USER_Z) return XCONV_EUNSUPPORTED;
+    if (indep && (d->keep_q15 != 0 || (long long)d->C_in * d->r > 1024)) return XCONV_EUNSUPPORTED;
     const int Ho = out_extent(d->H, d->kH, d->stride_h, d->pad_h), Wo = out_extent(d->W, d->kW, d->stride_w, d->pad_w);
     g.K = (long long)d->C_in * d->H * d->W;
     g.P = (long long)d->C_out * Ho * Wo;
     if (g.K > (1LL << 28) || g.P > (1LL << 28)) return XCONV_EUNSUPPORTED;
-    g.CS = round_up(d->r, 16);
+    g.R = indep ? d->C_in * d->r : d->r;
+    g.CS = round_up(g.R, 16);
     const size_t eb = elem_bytes(d->dtype);
     g.fwd = *d;
-    g.fwd.B = 1; g.fwd.C_out = d->B; g.fwd.C_in = d->r; g.fwd.H = d->C_in * d->H; g.fwd.W = d->W;
+    g.fwd.B = 1; g.fwd.C_out = d->B; g.fwd.C_in = g.R; g.fwd.H = d->C_in * d->H; g.fwd.W = d->W;
     g.fwd.kH = g.fwd.kW = 1; g.fwd.stride_h = g.fwd.stride_w = 1; g.fwd.pad_h = g.fwd.pad_w = 0;
     g.probe = *d;
-    g.probe.B = 1; g.probe.C_in = d->B; g.probe.probe = XCONV_USER_Z;
+    g.probe.B = 1; g.probe.C_in = d->B; g.probe.r = g.R; g.probe.probe = XCONV_USER_Z;
     g.bwd = *d;
     g.bwd.B = g.CS;
-    if (xconv_check_desc(&g.fwd) != XCONV_OK || xconv_check_desc(&g.bwd) != XCONV_OK) return XCONV_EUNSUPPORTED;
-    g.zimg_f = align_up((size_t)d->r * g.K * eb, 256);
+    if (xconv_check_desc(&g.fwd) != XCONV_OK || xconv_check_desc(&g.probe) != XCONV_OK || xconv_check_desc(&g.bwd) != XCONV_OK)
+        return XCONV_EUNSUPPORTED;
+    g.zimg_f = align_up((size_t)g.R * g.K * eb, 256);
     g.zimg_b = align_up((size_t)g.CS * d->H * d->W * round_up(d->C_in, 16) * eb, 256);   // channels-last, padded channels
-    g.xs = align_up((size_t)d->B * d->r * sizeof(float), 256);
+    g.xs = align_up((size_t)d->B * g.R * sizeof(float), 256);
     g.lt = align_up((size_t)g.P * g.CS * eb, 256);
     g.l = g.lt;
     g.probe_ws = z_bytes(&g.probe) + zfrag_bytes(&g.probe);
     return XCONV_OK;
 }
 
-}  // namespace
-
-size_t xconv_pixel_xbar_bytes(const xconv_desc *d)
+size_t pixel_xbar_bytes(const xconv_desc *d, bool indep)
 {
     PixelGeom g;
-    if (pixel_geom(d, g) != XCONV_OK) return 0;
-    return (size_t)d->B * d->r * sizeof(float);
+    if (pixel_geom(d, indep, g) != XCONV_OK) return 0;
+    return (size_t)d->B * g.R * sizeof(float);
 }
 
-size_t xconv_pixel_workspace_bytes(const xconv_desc *d, int op)
+size_t pixel_workspace_bytes(const xconv_desc *d, bool indep, int op)
 {
     PixelGeom g;
-    if (pixel_geom(d, g) != XCONV_OK) return 0;
+    if (pixel_geom(d, indep, g) != XCONV_OK) return 0;
     if (op == XCONV_OP_PROBE) {
         // the product kernel's partial sums, or (rows of X that are not whole 16-byte vectors) the scratch of the
         // exact-gradient path of the equivalent 1x1 layer
-        if (pixel_fwd_ok(d->dtype, g.K, nullptr)) return g.zimg_f + align_up(pixel_fwd_partial_bytes(d->dtype, g.K, d->B, d->r), 256);
+        if (pixel_fwd_ok(d->dtype, g.K, nullptr)) return g.zimg_f + align_up(pixel_fwd_partial_bytes(d->dtype, g.K, d->B, g.R), 256);
         const size_t w = xconv_workspace_bytes(&g.fwd, XCONV_OP_EXACT);
         return w ? g.zimg_f + w : 0;
     }
@@ -764,40 +769,40 @@ size_t xconv_pixel_workspace_bytes(const xconv_desc *d, int op)
     return 0;
 }
 
-xconv_status xconv_pixel_probe_fwd(const xconv_desc *d, const void *X_dev, float *Xbar_dev, void *ws_dev, size_t ws_bytes,
-                                   void *stream)
+xconv_status pixel_probe_fwd(const xconv_desc *d, bool indep, const void *X_dev, float *Xbar_dev, void *ws_dev, size_t ws_bytes,
+                             void *stream)
 {
     PixelGeom g;
-    xconv_status s = pixel_geom(d, g);
+    xconv_status s = pixel_geom(d, indep, g);
     if (s != XCONV_OK) return s;
     if (!X_dev || !Xbar_dev || !ws_dev) return XCONV_EINVAL;
     if (!aligned16(X_dev) || !aligned16(ws_dev) || (reinterpret_cast<uintptr_t>(Xbar_dev) & 3u) != 0) return XCONV_EINVAL;
-    const size_t need = xconv_pixel_workspace_bytes(d, XCONV_OP_PROBE);
+    const size_t need = pixel_workspace_bytes(d, indep, XCONV_OP_PROBE);
     if (need == 0) return XCONV_EUNSUPPORTED;
     if (ws_bytes < need) return XCONV_EWORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(ws_dev);
-    XC_LAUNCH(K_GEN_ZIMG, st, launch_gen_zimg(d->dtype, ws, g.K, d->r, d->r, probe_code(d), d->seed, d->C_in, 0, st));
+    XC_LAUNCH(K_GEN_ZIMG, st, launch_gen_zimg(d->dtype, ws, g.K, d->r, g.R, probe_code(d), d->seed, d->C_in, 0, indep, st));
     if (pixel_fwd_ok(d->dtype, g.K, X_dev)) {
         XC_LAUNCH(K_PIXEL_FWD, st, launch_pixel_fwd(d->dtype, X_dev, ws, reinterpret_cast<float *>(ws + g.zimg_f), Xbar_dev, g.K, d->B,
-                                                    d->r, st));
+                                                    g.R, st));
         return XCONV_OK;
     }
     // rows of X in the role of dY (B channels of one image), the probing vectors in the role of the activation
     return xconv_dw_exact(&g.fwd, X_dev, ws, Xbar_dev, ws + g.zimg_f, ws_bytes - g.zimg_f, stream);
 }
 
-xconv_status xconv_pixel_dw_estimate(const xconv_desc *d, const void *dY_dev, const float *Xbar_dev, float *dW_dev, void *ws_dev,
-                                     size_t ws_bytes, void *stream)
+xconv_status pixel_dw_estimate(const xconv_desc *d, bool indep, const void *dY_dev, const float *Xbar_dev, float *dW_dev,
+                               void *ws_dev, size_t ws_bytes, void *stream)
 {
     PixelGeom g;
-    xconv_status s = pixel_geom(d, g);
+    xconv_status s = pixel_geom(d, indep, g);
     if (s != XCONV_OK) return s;
     if (!dY_dev || !Xbar_dev || !dW_dev || !ws_dev) return XCONV_EINVAL;
     if (!aligned16(dY_dev) || !aligned16(ws_dev) || (reinterpret_cast<uintptr_t>(dW_dev) & 3u) != 0 ||
         (reinterpret_cast<uintptr_t>(Xbar_dev) & 3u) != 0)
         return XCONV_EINVAL;
-    const size_t need = xconv_pixel_workspace_bytes(d, XCONV_OP_ESTIMATE);
+    const size_t need = pixel_workspace_bytes(d, indep, XCONV_OP_ESTIMATE);
     if (need == 0) return XCONV_EUNSUPPORTED;
     if (ws_bytes < need) return XCONV_EWORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -809,9 +814,10 @@ xconv_status xconv_pixel_dw_estimate(const xconv_desc *d, const void *dY_dev, co
     char *pws = l + g.l;
     char *xws = pws + align_up(g.probe_ws, 256);
     // Z[s] again (Alg. 1 backward step 2), CS images, channels-last as the correlation reads an activation:
-    // the images past r are zero like the matching images of L
-    XC_LAUNCH(K_GEN_ZIMG, st, launch_gen_zimg(d->dtype, zimg, g.K, d->r, g.CS, probe_code(d), d->seed, d->C_in, round_up(d->C_in, 16), st));
-    XC_LAUNCH(K_SCALE, st, launch_scale(Xbar_dev, xs, d->B * d->r, 1.0f / (float)d->r, st));
+    // the images past R are zero like the matching images of L
+    XC_LAUNCH(K_GEN_ZIMG, st, launch_gen_zimg(d->dtype, zimg, g.K, d->r, g.CS, probe_code(d), d->seed, d->C_in, round_up(d->C_in, 16),
+                                              indep, st));
+    XC_LAUNCH(K_SCALE, st, launch_scale(Xbar_dev, xs, d->B * g.R, 1.0f / (float)d->r, st));
     // Lt[p, j] = sum_b dY[b, p] Xbar[b, j] / r, rounded to the storage type (Alg. 1 backward step 3)
     s = probe_impl(&g.probe, (int)g.P, (int)g.P, SliceMap{}, dY_dev, lt, xs, pws, g.probe_ws, st);
     if (s != XCONV_OK) return s;
@@ -822,6 +828,34 @@ xconv_status xconv_pixel_dw_estimate(const xconv_desc *d, const void *dY_dev, co
     // block-sparse probes: 1/nnz(Z_n) per input channel in place of the 1/r that L carries (Eq. (8))
     XC_LAUNCH(K_SCALE, st, launch_nnz_rescale(dW_dev, d->C_out, d->C_in, d->kH * d->kW, d->r, probe_code(d), d->seed, st));
     return XCONV_OK;
+}
+
+}  // namespace
+
+size_t xconv_pixel_xbar_bytes(const xconv_desc *d) { return pixel_xbar_bytes(d, false); }
+size_t xconv_pixel_workspace_bytes(const xconv_desc *d, int op) { return pixel_workspace_bytes(d, false, op); }
+xconv_status xconv_pixel_probe_fwd(const xconv_desc *d, const void *X_dev, float *Xbar_dev, void *ws_dev, size_t ws_bytes,
+                                   void *stream)
+{
+    return pixel_probe_fwd(d, false, X_dev, Xbar_dev, ws_dev, ws_bytes, stream);
+}
+xconv_status xconv_pixel_dw_estimate(const xconv_desc *d, const void *dY_dev, const float *Xbar_dev, float *dW_dev, void *ws_dev,
+                                     size_t ws_bytes, void *stream)
+{
+    return pixel_dw_estimate(d, false, dY_dev, Xbar_dev, dW_dev, ws_dev, ws_bytes, stream);
+}
+
+size_t xconv_pixel_indep_xbar_bytes(const xconv_desc *d) { return pixel_xbar_bytes(d, true); }
+size_t xconv_pixel_indep_workspace_bytes(const xconv_desc *d, int op) { return pixel_workspace_bytes(d, true, op); }
+xconv_status xconv_pixel_indep_probe_fwd(const xconv_desc *d, const void *X_dev, float *Xbar_dev, void *ws_dev, size_t ws_bytes,
+                                         void *stream)
+{
+    return pixel_probe_fwd(d, true, X_dev, Xbar_dev, ws_dev, ws_bytes, stream);
+}
+xconv_status xconv_pixel_indep_dw_estimate(const xconv_desc *d, const void *dY_dev, const float *Xbar_dev, float *dW_dev, void *ws_dev,
+                                           size_t ws_bytes, void *stream)
+{
+    return pixel_dw_estimate(d, true, dY_dev, Xbar_dev, dW_dev, ws_dev, ws_bytes, stream);
 }
 
 void xconv_prof_enable(int on)

@@ -222,6 +222,31 @@ def test_pixel_probe_sizes_and_argument_checks():
     assert L.xconv_pixel_dw_estimate(ctypes.byref(bad), one, one, one, one, 1 << 30, None) == xb.XCONV_EINVAL
 
 
+def test_independent_probing_sizes_and_limits():
+    d = _good()                                            # B=4, C_in=16, 32x32, r=8, fp32
+    assert xb.xconv_pixel_indep_xbar_bytes(d) == 4 * 16 * 8 * 4            # [B, C_in, r] floats
+    wf = xb.xconv_pixel_indep_workspace_bytes(d, xb.XCONV_OP_PROBE)
+    wb = xb.xconv_pixel_indep_workspace_bytes(d, xb.XCONV_OP_ESTIMATE)
+    assert wf > 16 * 8 * 16 * 32 * 32 * 4 and wb > wf                       # C_in*r block-diagonal vectors in scratch
+    assert wf > xb.xconv_pixel_workspace_bytes(d, xb.XCONV_OP_PROBE)
+    L = xb.lib()
+    one = ctypes.c_void_p(4096)          # never dereferenced: validation fails first
+    assert L.xconv_pixel_indep_probe_fwd(ctypes.byref(d), one, one, one, 64, None) == xb.XCONV_EWORKSPACE
+    assert L.xconv_pixel_indep_probe_fwd(ctypes.byref(d), None, one, one, 1 << 40, None) == xb.XCONV_EINVAL
+    assert L.xconv_pixel_indep_dw_estimate(ctypes.byref(d), one, one, one, one, 64, None) == xb.XCONV_EWORKSPACE
+    wide = _good()
+    wide.r = 1024 // wide.C_in + 1                          # C_in * r beyond 1024 vectors
+    sparse = _good()
+    sparse.keep_q15 = 16384                                 # block-sparse vectors belong to the multi-channel mode
+    for bad in (wide, sparse):
+        assert xb.xconv_pixel_indep_xbar_bytes(bad) == 0 and xb.xconv_pixel_indep_workspace_bytes(bad, xb.XCONV_OP_ESTIMATE) == 0
+        assert L.xconv_pixel_indep_probe_fwd(ctypes.byref(bad), one, one, one, 1 << 40, None) == xb.XCONV_EUNSUPPORTED
+        assert L.xconv_pixel_indep_dw_estimate(ctypes.byref(bad), one, one, one, one, 1 << 40, None) == xb.XCONV_EUNSUPPORTED
+    edge = _good()
+    edge.r = 1024 // edge.C_in
+    assert xb.xconv_pixel_indep_xbar_bytes(edge) == 4 * 1024 * 4
+
+
 def test_pixel_probe_state_reproduces_the_paper_memory_ratio():
     # Sec. 4.1 worked example: a 32x32 image with 16 input channels, r = 2^gamma probing vectors: the stored state of the
     # probe over pixels and channels is N*C_in/r = 2^(14-gamma) times smaller than the activation (same element size)
