@@ -244,31 +244,38 @@ def measure_volume(name, steps, warmup, dev, with_cpu, with_exact=True):
                                    sample="full %s layer (probe_fwd3d + dw_from_xt3d), 1 repetition, plain C -O2, one thread" % name)
     return out, corr_flops, corr_bytes
 
-def measure_pixel(cfg, steps, warmup, dev, with_cpu):
+def measure_pixel(cfg, steps, warmup, dev, with_cpu, indep=False):
     """The estimator with probing vectors over pixels and channels on a benchmark layer: forward and
-    backward timed separately (they run in different passes of training), kernels by HIP events."""
+    backward timed separately (they run in different passes of training), kernels by HIP events.
+    indep: independent probing (xconv_pixel_indep_*), r vectors per input channel."""
     import torch
     from paper_2106_06998_amd import binding as xb
     from paper_2106_06998_amd import synth
     d = xb.desc_from_config(cfg)
     X, dY = synth.make_layer(cfg)
+    ws_bytes = xb.xconv_pixel_indep_workspace_bytes if indep else xb.xconv_pixel_workspace_bytes
+    probe_fwd = xb.xconv_pixel_indep_probe_fwd if indep else xb.xconv_pixel_probe_fwd
+    dw_estimate = xb.xconv_pixel_indep_dw_estimate if indep else xb.xconv_pixel_dw_estimate
+    nvec = cfg.C_in * cfg.r if indep else cfg.r            # stored values per image
+    if ws_bytes(d, xb.XCONV_OP_ESTIMATE) == 0:
+        raise SystemExit("bench.py: %s with r=%d is outside what this mode supports (independent probing: C_in*r <= 1024)" % (cfg.name, cfg.r))
     sets = []
     for _ in range(3):
         sets.append(dict(X=xb.to_device(X, cfg.dtype, dev), dY=xb.to_device(dY, cfg.dtype, dev),
-                         xbar=torch.empty((cfg.B, cfg.r), dtype=torch.float32, device=dev),
+                         xbar=torch.empty((cfg.B, nvec), dtype=torch.float32, device=dev),
                          dW=torch.empty((cfg.C_out, cfg.C_in, cfg.k, cfg.k), dtype=torch.float32, device=dev),
-                         wsf=xb.alloc_bytes(xb.xconv_pixel_workspace_bytes(d, xb.XCONV_OP_PROBE), dev),
-                         wsb=xb.alloc_bytes(xb.xconv_pixel_workspace_bytes(d, xb.XCONV_OP_ESTIMATE), dev)))
+                         wsf=xb.alloc_bytes(ws_bytes(d, xb.XCONV_OP_PROBE), dev),
+                         wsb=xb.alloc_bytes(ws_bytes(d, xb.XCONV_OP_ESTIMATE), dev)))
 
     def fwd(i):
         s = sets[i % len(sets)]
         d.seed = cfg.seeds[2] + i
-        xb.xconv_pixel_probe_fwd(d, s["X"], s["xbar"], s["wsf"])
+        probe_fwd(d, s["X"], s["xbar"], s["wsf"])
 
     def bwd(i):
         s = sets[i % len(sets)]
         d.seed = cfg.seeds[2] + i
-        xb.xconv_pixel_dw_estimate(d, s["dY"], s["xbar"], s["dW"], s["wsb"])
+        dw_estimate(d, s["dY"], s["xbar"], s["dW"], s["wsb"])
 
     def both(i):
         fwd(i)
@@ -279,17 +286,30 @@ def measure_pixel(cfg, steps, warmup, dev, with_cpu):
     kb, ms_b = kernel_times(xb, bwd, steps, warmup)
     es = elem_bytes(cfg.dtype)
     K = cfg.C_in * cfg.H * cfg.W
-    fwd_bytes = cfg.B * K * es + cfg.B * cfg.r * 4
+    fwd_bytes = cfg.B * K * es + cfg.B * nvec * 4
     bwd_flops = 2.0 * cfg.r * cfg.Ho * cfg.Wo * cfg.C_out * cfg.C_in * cfg.k * cfg.k
     out = dict(name=cfg.name, dtype=cfg.dtype, ms_per_layer=ms_step, fwd_ms_with_events=ms_f, bwd_ms_with_events=ms_b,
                fwd_kernels_ms=kf, bwd_kernels_ms=kb,
                fwd=dict(gbps=fwd_bytes / (sum(kf.values())) / 1e6),
                bwd=dict(shifted_product_gflops=bwd_flops / kb["corr_kernel"] / 1e6,
                         mfma_frac=bwd_flops / kb["corr_kernel"] / 1e9 / PEAK_MFMA_TFLOPS[cfg.dtype]),
-               stored_bytes=cfg.B * cfg.r * 4, act_bytes=cfg.B * K * es,
-               workload="%s: B=%d C_in=%d C_out=%d H=W=%d k=%d stride=%d pad=%d r=%d %s probes over pixels and channels, %s storage" % (
-                   cfg.name, cfg.B, cfg.C_in, cfg.C_out, cfg.H, cfg.k, cfg.stride, cfg.pad, cfg.r, cfg.probe, cfg.dtype))
-    if with_cpu:
+               stored_bytes=cfg.B * nvec * 4, act_bytes=cfg.B * K * es,
+               workload="%s: B=%d C_in=%d C_out=%d H=W=%d k=%d stride=%d pad=%d r=%d %s probes over %s, %s storage" % (
+                   cfg.name, cfg.B, cfg.C_in, cfg.C_out, cfg.H, cfg.k, cfg.stride, cfg.pad, cfg.r, cfg.probe,
+                   "the pixels of every input channel on its own (independent probing)" if indep else "pixels and channels", cfg.dtype))
+    if with_cpu and indep:
+        from oracle import xconv_oracle as xo
+        dt = {"f32": xo.F32, "bf16": xo.BF16, "f16": xo.F16}[cfg.dtype]
+        t0 = time.perf_counter()
+        Z = xo.pixel_probe_matrix({"rademacher": xo.RADEMACHER, "gaussian": xo.GAUSSIAN}[cfg.probe], cfg.seeds[2], cfg.C_in, cfg.H,
+                                  cfg.W, cfg.r)
+        xbar = xo.pixel_indep_probe_fwd(X, Z)
+        xo.pixel_indep_dw_estimate(dY, xbar, Z, cfg.C_in, cfg.H, cfg.W, cfg.k, cfg.k, (cfg.stride, cfg.stride), (cfg.pad, cfg.pad), dt)
+        t = time.perf_counter() - t0
+        out["cpu_baseline"] = dict(value=t * 1e3, unit="ms/layer", cores=1, kind="oracle",
+                                   sample="full %s layer (pixel_probe_matrix + pixel_indep_probe_fwd + pixel_indep_dw_estimate), "
+                                          "1 repetition, plain C -O2, one thread" % cfg.name)
+    elif with_cpu:
         from oracle import xconv_oracle as xo
         dt = {"f32": xo.F32, "bf16": xo.BF16, "f16": xo.F16}[cfg.dtype]
         t0 = time.perf_counter()
@@ -317,6 +337,9 @@ def main():
                     help="measure the volumetric (3-D convolution) layers V1 and V2 instead of the headline layer")
     ap.add_argument("--pixel-probe", action="store_true",
                     help="measure the estimator with probing vectors over pixels and channels (xconv_pixel_*) on --config instead")
+    ap.add_argument("--independent", action="store_true",
+                    help="with --pixel-probe: independent probing (xconv_pixel_indep_*), r probing vectors per input channel")
+    ap.add_argument("--r", type=int, default=0, help="with --pixel-probe: number of probing vectors instead of the layer's own")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain device copy of 256 MiB ten times (reference reading for the FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -364,11 +387,16 @@ def main():
         return 0
     if args.pixel_probe:
         cfg = synth.CONFIGS[args.config]
-        res, flops = measure_pixel(cfg, args.steps, args.warmup, dev, not args.no_cpu)
+        if args.r > 0:
+            import dataclasses
+            cfg = dataclasses.replace(cfg, r=args.r)
+        res, flops = measure_pixel(cfg, args.steps, args.warmup, dev, not args.no_cpu, indep=args.independent)
         tc = res["bwd_kernels_ms"]["corr_kernel"]
         ach = flops / tc / 1e9
         line = {
-            "metric": "ms/layer for the XConv dW estimate with probes over pixels and channels (xconv_pixel_probe_fwd + xconv_pixel_dw_estimate), 1 GPU",
+            "metric": ("ms/layer for the XConv dW estimate with independent probing (xconv_pixel_indep_probe_fwd + "
+                       "xconv_pixel_indep_dw_estimate), 1 GPU") if args.independent else
+                      "ms/layer for the XConv dW estimate with probes over pixels and channels (xconv_pixel_probe_fwd + xconv_pixel_dw_estimate), 1 GPU",
             "value": res["ms_per_layer"], "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
             "ms_per_step": res["ms_per_layer"], "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
             "dtype": cfg.dtype, "data": "synthetic", "config": {"workload": res["workload"]},
