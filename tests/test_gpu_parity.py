@@ -181,6 +181,11 @@ EDGE = [
     ("wide-f32", 1, 8, 8, 6, 700, 3, 1, 1, 4, "rademacher", "f32"),            # several column strips
     ("wide-f16", 8, 16, 16, 4, 260, 3, 1, 1, 16, "rademacher", "f16"),
     ("big-cout-f32", 1, 8, 300, 8, 8, 3, 1, 1, 8, "rademacher", "f32"),
+    ("cin-512-f32", 2, 512, 16, 8, 8, 3, 1, 1, 64, "gaussian", "f32"),           # the probe's Z fragments fill its LDS budget (128 KB)
+    ("cin-512-f16-split", 8, 512, 16, 8, 8, 3, 1, 1, 64, "gaussian", "f16"),
+    ("cin-528-f16", 8, 528, 16, 8, 8, 3, 1, 1, 32, "rademacher", "f16"),         # one channel block more: the generic probe takes it
+    ("r-1024-f16", 2, 1040, 16, 6, 6, 3, 1, 1, 1024, "rademacher", "f16"),       # the largest r the library takes
+    ("r-1000-f32", 1, 1030, 8, 5, 5, 3, 1, 1, 1000, "gaussian", "f32"),
 ]
 
 
