@@ -160,7 +160,7 @@ xconv_status xconv_xt_unpack(const xconv_desc *desc, const void *Xt_dev, float *
  * pad_d <= kD-1 and kD <= 7; anything else is XCONV_EUNSUPPORTED.  l.layout ==
  * XCONV_NCHW means X [B,C_in,D,H,W] and dY [B,C_out,D',H',W'], XCONV_NHWC the
  * channels-last forms [B,D,H,W,C_in] and [B,D',H',W',C_out] (X is then read in place
- * by the probe, dY always through the slice-major copy; B*(D+2*pad_d) up to 65535).
+ * by the probe, dY always through the slice-major copy).
  * dW is [C_out,C_in,kD,kH,kW] fp32.
  * The conventions of the 2-D entry points (pointers, stream, status, alignment,
  * determinism, Z_dev / seed handling) hold unchanged. */

@@ -9,6 +9,7 @@
 namespace xc {
 
 constexpr int kThreads = 256;  // every kernel runs 4 wavefronts of 64 lanes per workgroup
+constexpr int kMaxGridZ = 65535;  // largest third extent of a grid: launches over more images go in pieces
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));

@@ -531,11 +531,11 @@ __global__ __launch_bounds__(kThreads) void unpack_kernel(const void *__restrict
 // X [B, C, HW] -> channels-last [B, HW, CS] with zero columns C..CS-1 (input of
 // the correlation kernel on the exact-gradient path).  32x32 tiles through LDS.
 template <typename T>
-__global__ __launch_bounds__(kThreads) void to_nhwc_kernel(const T *__restrict__ X, T *__restrict__ out, int C, int HW, int CS)
+__global__ __launch_bounds__(kThreads) void to_nhwc_kernel(const T *__restrict__ X, T *__restrict__ out, int C, int HW, int CS, int z0)
 {
     __shared__ T tile[32][33];
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
-    const int p0 = blockIdx.x * 32, c0 = blockIdx.y * 32, b = blockIdx.z;
+    const int p0 = blockIdx.x * 32, c0 = blockIdx.y * 32, b = z0 + blockIdx.z;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const int c = c0 + ty + 8 * k, p = p0 + tx;
@@ -552,11 +552,11 @@ __global__ __launch_bounds__(kThreads) void to_nhwc_kernel(const T *__restrict__
 // Channels-last [B, HW, C] -> planes [B, C, pitch] with a zero tail HW..pitch-1 (a channels-last
 // dY in the plane form the correlation kernels read).  32x32 tiles through LDS.
 template <typename T>
-__global__ __launch_bounds__(kThreads) void to_nchw_kernel(const T *__restrict__ src, T *__restrict__ out, int C, int HW, int pitch)
+__global__ __launch_bounds__(kThreads) void to_nchw_kernel(const T *__restrict__ src, T *__restrict__ out, int C, int HW, int pitch, int z0)
 {
     __shared__ T tile[32][33];
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
-    const int p0 = blockIdx.x * 32, c0 = blockIdx.y * 32, b = blockIdx.z;
+    const int p0 = blockIdx.x * 32, c0 = blockIdx.y * 32, b = z0 + blockIdx.z;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const int p = p0 + ty + 8 * k, c = c0 + tx;
@@ -577,14 +577,14 @@ __global__ __launch_bounds__(kThreads) void to_nchw_kernel(const T *__restrict__
 // out).  Planes whose pitch is not a multiple of VE are stored element by element.
 template <typename T>
 __global__ __launch_bounds__(kThreads) void to_nchw_vec_kernel(const T *__restrict__ src, T *__restrict__ out, int C, int HW,
-                                                               int pitch)
+                                                               int pitch, int z0)
 {
     constexpr int VE = 16 / sizeof(T);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int cx = lane & 7, pb = lane >> 3;
     const int c = blockIdx.y * (8 * VE) + cx * VE;
     const int p0 = (blockIdx.x * 4 + wave) * (8 * VE) + pb * VE;
-    const int b = blockIdx.z;
+    const int b = z0 + blockIdx.z;
     if (c >= C || p0 >= pitch) return;
     uint32_t rows[VE][4];
 #pragma unroll
@@ -833,14 +833,15 @@ hipError_t launch_zero_gap_slices(void *Xt, size_t slice_bytes, int B, SliceMap 
 
 // X [B, C, D, HWs] -> channels-last depth slices [slot][HWs][CS] in the slice map's order, zero
 // columns C..CS-1 (the exact gradient of a volumetric layer reads X like a stored probe
-// output).  32x32 tiles through LDS; blockIdx.z = image * D + z.
+// output).  32x32 tiles through LDS; z0 + blockIdx.z = image * D + z.
 template <typename T>
-__global__ __launch_bounds__(kThreads) void to_slices_kernel(const T *__restrict__ X, T *__restrict__ out, int C, int CS, SliceMap sm)
+__global__ __launch_bounds__(kThreads) void to_slices_kernel(const T *__restrict__ X, T *__restrict__ out, int C, int CS, SliceMap sm,
+                                                             int z0)
 {
     __shared__ T tile[32][33];
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
     const int p0 = blockIdx.x * 32, c0 = blockIdx.y * 32;
-    const int b = blockIdx.z / sm.D, z = blockIdx.z % sm.D;
+    const int b = (z0 + blockIdx.z) / sm.D, z = (z0 + blockIdx.z) % sm.D;
     const int HWs = sm.HWs;
     const T *src = X + ((size_t)b * C * sm.D + z) * HWs;
     T *dst = out + (size_t)sm.slice_of(b, z) * HWs * CS;
@@ -859,13 +860,16 @@ __global__ __launch_bounds__(kThreads) void to_slices_kernel(const T *__restrict
 
 hipError_t launch_to_slices(int dtype, const void *X, void *out, int B, int C, int CS, SliceMap sm, hipStream_t st)
 {
-    dim3 grid(ceil_div(sm.HWs, 32), ceil_div(CS, 32), B * sm.D);
-    if (dtype == XCONV_F32)
-        hipLaunchKernelGGL(to_slices_kernel<float>, grid, dim3(kThreads), 0, st, static_cast<const float *>(X),
-                           static_cast<float *>(out), C, CS, sm);
-    else
-        hipLaunchKernelGGL(to_slices_kernel<uint16_t>, grid, dim3(kThreads), 0, st, static_cast<const uint16_t *>(X),
-                           static_cast<uint16_t *>(out), C, CS, sm);
+    const long long nz = (long long)B * sm.D;
+    for (long long z0 = 0; z0 < nz; z0 += kMaxGridZ) {   // a grid's third extent is 16 bits
+        dim3 grid(ceil_div(sm.HWs, 32), ceil_div(CS, 32), (unsigned)(nz - z0 < kMaxGridZ ? nz - z0 : kMaxGridZ));
+        if (dtype == XCONV_F32)
+            hipLaunchKernelGGL(to_slices_kernel<float>, grid, dim3(kThreads), 0, st, static_cast<const float *>(X),
+                               static_cast<float *>(out), C, CS, sm, (int)z0);
+        else
+            hipLaunchKernelGGL(to_slices_kernel<uint16_t>, grid, dim3(kThreads), 0, st, static_cast<const uint16_t *>(X),
+                               static_cast<uint16_t *>(out), C, CS, sm, (int)z0);
+    }
     return hipGetLastError();
 }
 
@@ -901,15 +905,16 @@ hipError_t launch_x_slices_nhwc(int dtype, const void *X, void *out, int B, int 
 }
 
 // dY [B, Do, n, C] (channels-last) -> slice-major planes [B*period, C, pitch], zero tails and zero slots
-// Do..period-1 behind every image.  32x32 tiles through LDS; blockIdx.z = image * period + slot.
+// Do..period-1 behind every image.  32x32 tiles through LDS; z0 + blockIdx.z = image * period + slot.
 template <typename T>
 __global__ __launch_bounds__(kThreads) void dy_slices_nhwc_kernel(const T *__restrict__ src, T *__restrict__ dst, int C, int Do,
-                                                                  int period, int n, int pitch)
+                                                                  int period, int n, int pitch, int z0)
 {
     __shared__ T tile[32][33];
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
     const int p0 = blockIdx.x * 32, c0 = blockIdx.y * 32;
-    const int b = blockIdx.z / period, z = blockIdx.z % period;
+    const int slot = z0 + blockIdx.z;
+    const int b = slot / period, z = slot % period;
     const bool real = z < Do;
     const T *s = src + ((size_t)b * Do + (real ? z : 0)) * n * C;
 #pragma unroll
@@ -918,7 +923,7 @@ __global__ __launch_bounds__(kThreads) void dy_slices_nhwc_kernel(const T *__res
         tile[ty + 8 * k][tx] = (real && p < n && c < C) ? s[(size_t)p * C + c] : T(0);
     }
     __syncthreads();
-    T *d = dst + (size_t)blockIdx.z * C * pitch;
+    T *d = dst + (size_t)slot * C * pitch;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const int c = c0 + ty + 8 * k, p = p0 + tx;
@@ -929,13 +934,16 @@ __global__ __launch_bounds__(kThreads) void dy_slices_nhwc_kernel(const T *__res
 hipError_t launch_dy_slices_nhwc(int dtype, const void *src, void *dst, int B, int C, int Do, int period, int n, int pitch,
                                  hipStream_t st)
 {
-    dim3 grid(ceil_div(pitch, 32), ceil_div(C, 32), B * period);
-    if (dtype == XCONV_F32)
-        hipLaunchKernelGGL(dy_slices_nhwc_kernel<float>, grid, dim3(kThreads), 0, st, static_cast<const float *>(src),
-                           static_cast<float *>(dst), C, Do, period, n, pitch);
-    else
-        hipLaunchKernelGGL(dy_slices_nhwc_kernel<uint16_t>, grid, dim3(kThreads), 0, st, static_cast<const uint16_t *>(src),
-                           static_cast<uint16_t *>(dst), C, Do, period, n, pitch);
+    const long long nz = (long long)B * period;
+    for (long long z0 = 0; z0 < nz; z0 += kMaxGridZ) {
+        dim3 grid(ceil_div(pitch, 32), ceil_div(C, 32), (unsigned)(nz - z0 < kMaxGridZ ? nz - z0 : kMaxGridZ));
+        if (dtype == XCONV_F32)
+            hipLaunchKernelGGL(dy_slices_nhwc_kernel<float>, grid, dim3(kThreads), 0, st, static_cast<const float *>(src),
+                               static_cast<float *>(dst), C, Do, period, n, pitch, (int)z0);
+        else
+            hipLaunchKernelGGL(dy_slices_nhwc_kernel<uint16_t>, grid, dim3(kThreads), 0, st, static_cast<const uint16_t *>(src),
+                               static_cast<uint16_t *>(dst), C, Do, period, n, pitch, (int)z0);
+    }
     return hipGetLastError();
 }
 
@@ -1125,13 +1133,15 @@ hipError_t launch_unpack(int dtype, const void *Xt, float *out, int B, int HW, i
 
 hipError_t launch_to_nhwc(int dtype, const void *X, void *out, int B, int C, int HW, int CS, hipStream_t st)
 {
-    dim3 grid(ceil_div(HW, 32), ceil_div(CS, 32), B);
-    if (dtype == XCONV_F32)
-        hipLaunchKernelGGL(to_nhwc_kernel<float>, grid, dim3(kThreads), 0, st, static_cast<const float *>(X),
-                           static_cast<float *>(out), C, HW, CS);
-    else
-        hipLaunchKernelGGL(to_nhwc_kernel<uint16_t>, grid, dim3(kThreads), 0, st, static_cast<const uint16_t *>(X),
-                           static_cast<uint16_t *>(out), C, HW, CS);
+    for (int z0 = 0; z0 < B; z0 += kMaxGridZ) {   // a grid's third extent is 16 bits
+        dim3 grid(ceil_div(HW, 32), ceil_div(CS, 32), B - z0 < kMaxGridZ ? B - z0 : kMaxGridZ);
+        if (dtype == XCONV_F32)
+            hipLaunchKernelGGL(to_nhwc_kernel<float>, grid, dim3(kThreads), 0, st, static_cast<const float *>(X),
+                               static_cast<float *>(out), C, HW, CS, z0);
+        else
+            hipLaunchKernelGGL(to_nhwc_kernel<uint16_t>, grid, dim3(kThreads), 0, st, static_cast<const uint16_t *>(X),
+                               static_cast<uint16_t *>(out), C, HW, CS, z0);
+    }
     return hipGetLastError();
 }
 
@@ -1139,22 +1149,26 @@ hipError_t launch_to_nchw(int dtype, const void *src, void *out, int B, int C, i
 {
     const int VE = dtype == XCONV_F32 ? 4 : 8;
     if (C % VE == 0 && (reinterpret_cast<uintptr_t>(src) & 15u) == 0 && (reinterpret_cast<uintptr_t>(out) & 15u) == 0) {
-        dim3 vgrid(ceil_div(pitch, 32 * VE), ceil_div(C, 8 * VE), B);
-        if (dtype == XCONV_F32)
-            hipLaunchKernelGGL(to_nchw_vec_kernel<float>, vgrid, dim3(kThreads), 0, st, static_cast<const float *>(src),
-                               static_cast<float *>(out), C, HW, pitch);
-        else
-            hipLaunchKernelGGL(to_nchw_vec_kernel<uint16_t>, vgrid, dim3(kThreads), 0, st, static_cast<const uint16_t *>(src),
-                               static_cast<uint16_t *>(out), C, HW, pitch);
+        for (int z0 = 0; z0 < B; z0 += kMaxGridZ) {
+            dim3 vgrid(ceil_div(pitch, 32 * VE), ceil_div(C, 8 * VE), B - z0 < kMaxGridZ ? B - z0 : kMaxGridZ);
+            if (dtype == XCONV_F32)
+                hipLaunchKernelGGL(to_nchw_vec_kernel<float>, vgrid, dim3(kThreads), 0, st, static_cast<const float *>(src),
+                                   static_cast<float *>(out), C, HW, pitch, z0);
+            else
+                hipLaunchKernelGGL(to_nchw_vec_kernel<uint16_t>, vgrid, dim3(kThreads), 0, st, static_cast<const uint16_t *>(src),
+                                   static_cast<uint16_t *>(out), C, HW, pitch, z0);
+        }
         return hipGetLastError();
     }
-    dim3 grid(ceil_div(pitch, 32), ceil_div(C, 32), B);
-    if (dtype == XCONV_F32)
-        hipLaunchKernelGGL(to_nchw_kernel<float>, grid, dim3(kThreads), 0, st, static_cast<const float *>(src),
-                           static_cast<float *>(out), C, HW, pitch);
-    else
-        hipLaunchKernelGGL(to_nchw_kernel<uint16_t>, grid, dim3(kThreads), 0, st, static_cast<const uint16_t *>(src),
-                           static_cast<uint16_t *>(out), C, HW, pitch);
+    for (int z0 = 0; z0 < B; z0 += kMaxGridZ) {
+        dim3 grid(ceil_div(pitch, 32), ceil_div(C, 32), B - z0 < kMaxGridZ ? B - z0 : kMaxGridZ);
+        if (dtype == XCONV_F32)
+            hipLaunchKernelGGL(to_nchw_kernel<float>, grid, dim3(kThreads), 0, st, static_cast<const float *>(src),
+                               static_cast<float *>(out), C, HW, pitch, z0);
+        else
+            hipLaunchKernelGGL(to_nchw_kernel<uint16_t>, grid, dim3(kThreads), 0, st, static_cast<const uint16_t *>(src),
+                               static_cast<uint16_t *>(out), C, HW, pitch, z0);
+    }
     return hipGetLastError();
 }
 

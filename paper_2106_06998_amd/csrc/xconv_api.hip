@@ -510,7 +510,6 @@ xconv_status xconv3d_check_desc(const xconv3d_desc *v)
     if (v->kD > 7 || v->pad_d > v->kD - 1) return XCONV_EUNSUPPORTED;
     if ((long long)v->D * v->l.H * v->l.W > (1LL << 28)) return XCONV_EUNSUPPORTED;
     if (v->stride_d > 4096 || (long long)v->l.B * (v->D + 2 * v->pad_d) > 0x7fffffffLL) return XCONV_EUNSUPPORTED;
-    if ((long long)v->l.B * (v->D + 2 * v->pad_d) > 65535 && v->l.layout == XCONV_NHWC) return XCONV_EUNSUPPORTED;   // one grid row per slot
     return XCONV_OK;
 }
 
@@ -639,7 +638,6 @@ xconv_status xconv3d_dw_exact(const xconv3d_desc *v, const void *dY_dev, const v
     char *ws = static_cast<char *>(ws_dev);
     // X -> channels-last depth slices in the slice layout of Xt, zero slots between
     const SliceMap sm = vol_map(v, g);
-    if ((long long)d->B * v->D > 65535) return XCONV_EUNSUPPORTED;   // one grid row per depth slice
     if (d->layout == XCONV_NHWC)
         XC_LAUNCH(K_TO_NHWC, st, launch_x_slices_nhwc(d->dtype, X_dev, ws, d->B, d->C_in, CSx, sm, st));
     else

@@ -186,6 +186,7 @@ EDGE = [
     ("cin-528-f16", 8, 528, 16, 8, 8, 3, 1, 1, 32, "rademacher", "f16"),         # one channel block more: the generic probe takes it
     ("r-1024-f16", 2, 1040, 16, 6, 6, 3, 1, 1, 1024, "rademacher", "f16"),       # the largest r the library takes
     ("r-1000-f32", 1, 1030, 8, 5, 5, 3, 1, 1, 1000, "gaussian", "f32"),
+    ("batch-65541-f32", 65541, 8, 8, 4, 4, 3, 1, 1, 4, "rademacher", "f32"),     # more images than one grid extent holds
 ]
 
 
@@ -359,6 +360,8 @@ NHWC_EDGE = [
     ("nhwc-bf16-c12-generic", 3, 12, 16, 8, 8, 3, 1, 1, 8, "rademacher", "bf16"),
     ("nhwc-f16-k5-s2", 8, 32, 64, 15, 15, 5, 2, 2, 32, "rademacher", "f16"),
     ("nhwc-f16-1x1", 8, 32, 48, 9, 9, 1, 1, 0, 16, "rademacher", "f16"),
+    ("nhwc-batch-65541-f16", 65541, 8, 8, 4, 4, 3, 1, 1, 4, "rademacher", "f16"),   # more images than one grid extent holds
+    ("nhwc-batch-65541-f32-c6", 65541, 8, 6, 4, 4, 3, 1, 1, 4, "rademacher", "f32"),
 ]
 
 

@@ -34,6 +34,7 @@ VOL = [
     ("f32-depth-stride-beyond-kernel", "f32", 1, 8, 8, (10, 8, 8), (2, 1, 1), (4, 1), (1, 0, 0), 8, "gaussian", 0, False),
     ("f32-odd-volume", "f32", 2, 6, 10, (3, 5, 5), (3, 3, 3), (1, 1), (1, 1, 1), 5, "gaussian", 0, False),
     ("f16-one-voxel-row", "f16", 5, 16, 16, (3, 4, 8), (3, 3, 3), (1, 1), (1, 1, 1), 16, "rademacher", 0, False),
+    ("f16-67200-slices", "f16", 4200, 8, 8, (16, 4, 4), (3, 3, 3), (1, 1), (1, 1, 1), 4, "rademacher", 0, False),  # beyond one grid extent
 ]
 
 
@@ -94,7 +95,7 @@ def test_volumetric_layers(e):
     run_volume(e)
 
 
-NDHWC = [VOL[0], VOL[1], VOL[2], VOL[3], VOL[5], VOL[7], VOL[13], VOL[15],
+NDHWC = [VOL[0], VOL[1], VOL[2], VOL[3], VOL[5], VOL[7], VOL[13], VOL[15], VOL[20],
          ("f32-ndhwc-odd-channels", "f32", 2, 6, 10, (3, 5, 5), (3, 3, 3), (1, 1), (1, 1, 1), 5, "gaussian", 0, False),
          ("bf16-ndhwc-channel-tail", "bf16", 2, 24, 40, (4, 6, 8), (3, 3, 3), (2, 1), (1, 1, 1), 16, "rademacher", 0, True)]
 

@@ -160,8 +160,8 @@ def test_volumetric_descriptor_and_sizes():
     v = good()
     v.l.layout = xb.XCONV_NHWC                             # channels-last volumes
     assert xb.xconv3d_check_desc(v) == xb.XCONV_OK
-    v.l.B = 8000                                          # more slots than the channels-last copies have grid rows
-    assert xb.xconv3d_check_desc(v) == xb.XCONV_EUNSUPPORTED
+    v.l.B = 8000                                          # more depth slots than one grid extent: the copies go in pieces
+    assert xb.xconv3d_check_desc(v) == xb.XCONV_OK and xb.xconv3d_workspace_bytes(v, xb.XCONV_OP_ESTIMATE) > 0
     v = xb.make_desc3d(1, 4, 4, 6, 8, 8, (1, 3, 3), 1, (0, 1, 1), r=4)        # a stack of independent 2-D layers
     assert xb.xconv3d_check_desc(v) == xb.XCONV_OK
     assert xb.xconv3d_xt_bytes(v) == 6 * 8 * 8 * 16 * 4
