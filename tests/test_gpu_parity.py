@@ -493,6 +493,56 @@ def test_full_size_sampled(name):
         assert rel_max(got, mixed) <= 2 * GRAD_TOL[cfg.dtype]
 
 
+def test_byte_offsets_beyond_4_gib():
+    # X, dY and the stored probe output of 4.8 GB each (fp16): 144 copies of a batch of 16 images.  The small batch
+    # is checked against the oracle (probe output in full, sampled gradient entries); on the large one every copy's
+    # stored probe output must equal the small batch's bit for bit, and both gradients are 144 times the small
+    # batch's (same products, a longer fp32 sum).
+    B0, rep, C, H, r, dtype = 16, 144, 64, 128, 64, "f16"
+    say("4.8 GB tensors: %d copies of %d images, C=%d, %dx%d, r=%d" % (rep, B0, C, H, H, r))
+    X = synth.draw((B0, C, H, H), 21, "relu_normal", 1.0, dtype)
+    dY = synth.draw((B0, C, H, H), 22, "normal", 1e-2, dtype)
+    Z = xo.probe_matrix(OPROBE["rademacher"], 23, C, r)
+
+    def run(B, Xd, dYd):
+        d = xb.make_desc(B, C, C, H, H, 3, 1, 1, r, dtype, "rademacher", 23)
+        Xt = xb.alloc_xt(d, DEV)
+        xb.xconv_probe_fwd(d, Xd, Xt, None, xb.alloc_ws(d, xb.XCONV_OP_PROBE, DEV))
+        unp = torch.empty((B, r, H, H), dtype=torch.float32, device=DEV)
+        xb.xconv_xt_unpack(d, Xt, unp)
+        dW = torch.full((C, C, 3, 3), float("nan"), dtype=torch.float32, device=DEV)
+        xb.xconv_dw_estimate(d, dYd, Xt, None, dW, xb.alloc_ws(d, xb.XCONV_OP_ESTIMATE, DEV))
+        dWx = torch.full((C, C, 3, 3), float("nan"), dtype=torch.float32, device=DEV)
+        xb.xconv_dw_exact(d, dYd, Xd, dWx, xb.alloc_ws(d, xb.XCONV_OP_EXACT, DEV))
+        torch.cuda.synchronize()
+        return unp, dW.cpu().numpy().astype(np.float64), dWx.cpu().numpy().astype(np.float64)
+
+    X0, dY0 = xb.to_device(X, dtype, DEV), xb.to_device(dY, dtype, DEV)
+    unp0, dW0, dWx0 = run(B0, X0, dY0)
+    Xt_o = xo.probe_fwd(X, Z, ODT[dtype])
+
+    class Storage:  # minimal stand-in for check_probe_output
+        pass
+    Storage.dtype = dtype
+    check_probe_output(Storage, unp0.cpu().numpy(), Xt_o, z_exact=True)
+    rng = np.random.default_rng(6)
+    idx = np.stack([rng.integers(0, C, 24), rng.integers(0, C, 24), rng.integers(0, 3, 24), rng.integers(0, 3, 24)], axis=1).astype(np.int32)
+    want = xo.dw_from_xt_at(dY, Xt_o, Z, idx, 3, 3, (1, 1), (1, 1))
+    g = np.array([dW0[tuple(i)] for i in idx])
+    assert np.max(np.abs(g - want)) <= GRAD_TOL[dtype] * np.max(np.abs(want))
+    wx = xo.dw_exact_at(dY, X, idx, 3, 3, (1, 1), (1, 1))
+    gx = np.array([dWx0[tuple(i)] for i in idx])
+    assert np.max(np.abs(gx - wx)) <= GRAD_TOL[dtype] * np.max(np.abs(wx))
+
+    say("4.8 GB tensors: the large batch")
+    Xb, dYb = X0.repeat(rep, 1, 1, 1), dY0.repeat(rep, 1, 1, 1)
+    assert Xb.numel() * Xb.element_size() > 2 ** 32
+    unp, dW, dWx = run(B0 * rep, Xb, dYb)
+    assert bool((unp.view(rep, B0, r, H, H) == unp0.unsqueeze(0)).all())
+    del unp
+    assert rel_max(dW, rep * dW0) <= 1e-3 and rel_max(dWx, rep * dWx0) <= 1e-3
+
+
 # ---------------------------------------------------------------------------
 # seeded random shapes: every kernel choice the plans can make (generic, 16-bit and fp32
 # producer/consumer kernels, strips, partial image groups, offset groups, both layouts, sparse
