@@ -224,7 +224,8 @@ xconv_status xconv3d_xt_unpack(const xconv3d_desc *desc, const void *Xt_dev, flo
  * vector j on channel n, is zero unless the top 15 bits of word n*r + j of the mask
  * stream (see xconv_probe_matrix) are below keep_q15, and the estimate of input channel
  * n is scaled by 1/nnz(Z_n), the number of kept blocks of channel n, instead of 1/r
- * (Eq. (8)); a channel without any gives zeros.  Supported: NCHW, Rademacher or
+ * (Eq. (8)); a channel without any gives zeros.  Supported: both layouts (Z is indexed
+ * by (n, y, x) as above whatever the order X keeps its values in), Rademacher or
  * Gaussian probes from the seed (XCONV_USER_Z is XCONV_EUNSUPPORTED), C_in*H*W and
  * C_out*H'*W' up to 2^28, B up to 65536.  All
  * other conventions as above; X_dev and dY_dev 16-byte aligned, ws_dev required. */

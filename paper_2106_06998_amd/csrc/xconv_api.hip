@@ -715,7 +715,7 @@ xconv_status pixel_geom(const xconv_desc *d, bool indep, PixelGeom &g)
 {
     xconv_status s = xconv_check_desc(d);
     if (s != XCONV_OK) return s;
-    if (d->layout != XCONV_NCHW || d->probe == XCONV_USER_Z) return XCONV_EUNSUPPORTED;
+    if (d->probe == XCONV_USER_Z) return XCONV_EUNSUPPORTED;
     if (indep && (d->keep_q15 != 0 || (long long)d->C_in * d->r > 1024)) return XCONV_EUNSUPPORTED;
     const int Ho = out_extent(d->H, d->kH, d->stride_h, d->pad_h), Wo = out_extent(d->W, d->kW, d->stride_w, d->pad_w);
     g.K = (long long)d->C_in * d->H * d->W;
@@ -727,8 +727,11 @@ xconv_status pixel_geom(const xconv_desc *d, bool indep, PixelGeom &g)
     g.fwd = *d;
     g.fwd.B = 1; g.fwd.C_out = d->B; g.fwd.C_in = g.R; g.fwd.H = d->C_in * d->H; g.fwd.W = d->W;
     g.fwd.kH = g.fwd.kW = 1; g.fwd.stride_h = g.fwd.stride_w = 1; g.fwd.pad_h = g.fwd.pad_w = 0;
+    // the two products see rows of K (or P) contiguous values whatever their order; only the shifted product
+    // looks at the layout (of L, which inherits dY's)
+    g.fwd.layout = XCONV_NCHW;
     g.probe = *d;
-    g.probe.B = 1; g.probe.C_in = d->B; g.probe.r = g.R; g.probe.probe = XCONV_USER_Z;
+    g.probe.B = 1; g.probe.C_in = d->B; g.probe.r = g.R; g.probe.probe = XCONV_USER_Z; g.probe.layout = XCONV_NCHW;
     g.bwd = *d;
     g.bwd.B = g.CS;
     if (xconv_check_desc(&g.fwd) != XCONV_OK || xconv_check_desc(&g.probe) != XCONV_OK || xconv_check_desc(&g.bwd) != XCONV_OK)
@@ -780,7 +783,9 @@ xconv_status pixel_probe_fwd(const xconv_desc *d, bool indep, const void *X_dev,
     if (ws_bytes < need) return XCONV_EWORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(ws_dev);
-    XC_LAUNCH(K_GEN_ZIMG, st, launch_gen_zimg(d->dtype, ws, g.K, d->r, g.R, probe_code(d), d->seed, d->C_in, 0, indep, st));
+    // probing vectors as rows in the order X keeps its values in: (n, y, x), or (y, x, n) for channels-last
+    XC_LAUNCH(K_GEN_ZIMG, st, launch_gen_zimg(d->dtype, ws, g.K, d->r, g.R, probe_code(d), d->seed, d->C_in,
+                                              d->layout == XCONV_NHWC ? d->C_in : 0, indep, st));
     if (pixel_fwd_ok(d->dtype, g.K, X_dev)) {
         XC_LAUNCH(K_PIXEL_FWD, st, launch_pixel_fwd(d->dtype, X_dev, ws, reinterpret_cast<float *>(ws + g.zimg_f), Xbar_dev, g.K, d->B,
                                                     g.R, st));
@@ -816,7 +821,8 @@ xconv_status pixel_dw_estimate(const xconv_desc *d, bool indep, const void *dY_d
     XC_LAUNCH(K_GEN_ZIMG, st, launch_gen_zimg(d->dtype, zimg, g.K, d->r, g.CS, probe_code(d), d->seed, d->C_in, round_up(d->C_in, 16),
                                               indep, st));
     XC_LAUNCH(K_SCALE, st, launch_scale(Xbar_dev, xs, d->B * g.R, 1.0f / (float)d->r, st));
-    // Lt[p, j] = sum_b dY[b, p] Xbar[b, j] / r, rounded to the storage type (Alg. 1 backward step 3)
+    // Lt[p, j] = sum_b dY[b, p] Xbar[b, j] / r, rounded to the storage type (Alg. 1 backward step 3); p runs over
+    // an image of dY in its own order, so the images of L come out in dY's layout
     s = probe_impl(&g.probe, (int)g.P, (int)g.P, SliceMap{}, dY_dev, lt, xs, pws, g.probe_ws, st);
     if (s != XCONV_OK) return s;
     XC_LAUNCH(K_REPACK, st, launch_to_nchw(d->dtype, lt, l, 1, g.CS, (int)g.P, (int)g.P, st));

@@ -54,12 +54,17 @@ def gpu_bwd(d, dYd, xbar, shape):
     return dW.cpu().numpy().astype(np.float64)
 
 
-def run_indep(e):
+def run_indep(e, nhwc=False):
     name, dtype, B, C_in, C_out, H, W, k, st, pad, r, probe = e
-    say("independent probing %s" % (e,))
+    say("independent probing %s%s" % (e, " channels-last" if nhwc else ""))
     cfg, d, X, dY, Z = setup(e)
     want_xbar = xo.pixel_indep_probe_fwd(X, Z)
-    Xd, dYd = xb.to_device(X, dtype, DEV), xb.to_device(dY, dtype, DEV)
+    if nhwc:   # the same values handed over as [B, H, W, C]
+        d.layout = xb.XCONV_NHWC
+        Xd = xb.to_device(np.ascontiguousarray(X.transpose(0, 2, 3, 1)), dtype, DEV)
+        dYd = xb.to_device(np.ascontiguousarray(dY.transpose(0, 2, 3, 1)), dtype, DEV)
+    else:
+        Xd, dYd = xb.to_device(X, dtype, DEV), xb.to_device(dY, dtype, DEV)
     xbar = gpu_fwd(d, Xd, B, C_in, r)
     got_xbar = xbar.cpu().numpy()
     assert np.max(np.abs(got_xbar - want_xbar)) <= 1e-5 * np.max(np.abs(want_xbar)), rel_max(got_xbar, want_xbar)
@@ -77,6 +82,11 @@ def run_indep(e):
 @pytest.mark.parametrize("e", IND, ids=[e[0] for e in IND])
 def test_independent_probing_layers(e):
     run_indep(e)
+
+
+@pytest.mark.parametrize("e", [IND[0], IND[1], IND[2], IND[3]], ids=[e[0] for e in IND[:4]])
+def test_independent_probing_channels_last(e):
+    run_indep(e, nhwc=True)
 
 
 def test_independent_probing_is_deterministic():

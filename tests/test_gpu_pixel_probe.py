@@ -33,20 +33,26 @@ PIX = [
 ]
 
 
-def run_pixel(e):
+def run_pixel(e, nhwc=False):
     name, dtype, B, C_in, C_out, H, W, k, st, pad, r, probe = e[:12]
     keep = e[12] if len(e) > 12 else 0
-    say("pixel probe %s" % (e,))
+    say("pixel probe %s%s" % (e, " channels-last" if nhwc else ""))
     cfg = synth.LayerConfig(name=name, B=B, C_in=C_in, C_out=C_out, H=H, W=W, k=k, stride=st, pad=pad, r=r, dtype=dtype,
                             probe=probe, x_dist="relu_normal", dy_var=1e-2, seeds=(8101 + len(name), 8202 + len(name), 8303 + len(name)))
     X, dY = synth.make_layer(cfg)
     d = xb.desc_from_config(cfg)
     d.keep_q15 = keep
+    if nhwc:
+        d.layout = xb.XCONV_NHWC
     Z = xo.pixel_probe_matrix(OPROBE[probe], cfg.seeds[2], C_in, H, W, r, ODT[dtype], keep)
     if name.endswith("empty-channels"):
         assert (xo.pixel_block_counts(Z, C_in) == 0).any()      # some channel has no block: its estimate is zero
     want_xbar = xo.pixel_probe_fwd(X, Z)
-    Xd, dYd = xb.to_device(X, dtype, DEV), xb.to_device(dY, dtype, DEV)
+    if nhwc:   # the same values handed over as [B, H, W, C]
+        Xd = xb.to_device(np.ascontiguousarray(X.transpose(0, 2, 3, 1)), dtype, DEV)
+        dYd = xb.to_device(np.ascontiguousarray(dY.transpose(0, 2, 3, 1)), dtype, DEV)
+    else:
+        Xd, dYd = xb.to_device(X, dtype, DEV), xb.to_device(dY, dtype, DEV)
     assert xb.xconv_pixel_xbar_bytes(d) == B * r * 4
     xbar = torch.full((B, r), float("nan"), dtype=torch.float32, device=DEV)
     ws = xb.alloc_bytes(xb.xconv_pixel_workspace_bytes(d, xb.XCONV_OP_PROBE), DEV)
@@ -76,6 +82,15 @@ def run_pixel(e):
 @pytest.mark.parametrize("e", PIX, ids=[e[0] for e in PIX])
 def test_pixel_probe_layers(e):
     run_pixel(e)
+
+
+NHWC_PIX = [PIX[0], PIX[2], PIX[3], PIX[4], PIX[5], PIX[6], PIX[9], PIX[12]]
+
+
+@pytest.mark.parametrize("e", NHWC_PIX, ids=[e[0] for e in NHWC_PIX])
+def test_pixel_probe_channels_last(e):
+    # the oracle's NCHW result: the estimator does not depend on the order the tensors are stored in
+    run_pixel(e, nhwc=True)
 
 
 def test_pixel_probe_is_deterministic():

@@ -202,7 +202,11 @@ def test_pixel_probe_sizes_and_argument_checks():
     sparse = _good()
     sparse.keep_q15 = 100
     assert xb.xconv_pixel_xbar_bytes(sparse) == 4 * 8 * 4
-    for field, val in (("layout", xb.XCONV_NHWC), ("probe", xb.XCONV_USER_Z)):
+    cl = _good()
+    cl.layout = xb.XCONV_NHWC                               # channels-last: same state, the backward pass also repacks L
+    assert xb.xconv_pixel_xbar_bytes(cl) == 4 * 8 * 4 and xb.xconv_pixel_workspace_bytes(cl, xb.XCONV_OP_PROBE) == wf
+    assert xb.xconv_pixel_workspace_bytes(cl, xb.XCONV_OP_ESTIMATE) > wb
+    for field, val in (("probe", xb.XCONV_USER_Z),):
         bad = _good()
         setattr(bad, field, val)
         assert xb.xconv_pixel_xbar_bytes(bad) == 0 and xb.xconv_pixel_workspace_bytes(bad, 0) == 0
