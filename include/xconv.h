@@ -22,6 +22,10 @@
  *     by the caller; the library allocates no device memory.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Device work is enqueued on it and the call returns without waiting.
+ *     A call issues kernel launches only (no allocation, no memset, no copy, no
+ *     synchronisation), so it may be recorded into a HIP graph by stream capture;
+ *     the first call for a kernel sets that kernel's LDS attribute and is best
+ *     made once outside a capture.
  *   - Return value: an xconv_status.  Arguments are validated on the host before
  *     anything is enqueued; on a non-zero status nothing was launched (except
  *     XCONV_EHIP, which reports a failed launch).  Nothing aborts or throws.
