@@ -130,3 +130,11 @@ def test_independent_probing_has_no_crosstalk():
     assert np.all(got[:, 1:] == 0) and np.any(got[:, 0] != 0)
     want = xo.pixel_indep_dw_estimate(dY, xo.pixel_indep_probe_fwd(X, Z), Z, C_in, H, W, k, k, (st, st), (pad, pad))
     assert rel_max(got, want) <= GRAD_TOL[dtype]
+
+
+def test_independent_probing_full_size_C2():
+    # the layer bench.py --pixel-probe --independent times by default (64 channels x 16 vectors = the 1024-vector limit),
+    # every entry against the oracle
+    cfg = synth.CONFIGS["C2"]
+    run_indep(("C2", cfg.dtype, cfg.B, cfg.C_in, cfg.C_out, cfg.H, cfg.W, cfg.k, cfg.stride, cfg.pad, cfg.r, cfg.probe))
+

@@ -101,3 +101,11 @@ def test_pixel_probe_full_size_C2():
     # the benchmark layer bench.py --pixel-probe times by default, every entry against the oracle
     cfg = synth.CONFIGS["C2"]
     run_pixel(("C2", cfg.dtype, cfg.B, cfg.C_in, cfg.C_out, cfg.H, cfg.W, cfg.k, cfg.stride, cfg.pad, cfg.r, cfg.probe))
+
+
+def test_pixel_probe_full_size_C5():
+    # the largest 16-bit benchmark layer (K = 200704 values per image, r = 64, B = 256), every entry against the
+    # oracle, which takes about half a minute for it
+    cfg = synth.CONFIGS["C5"]
+    run_pixel(("C5", cfg.dtype, cfg.B, cfg.C_in, cfg.C_out, cfg.H, cfg.W, cfg.k, cfg.stride, cfg.pad, cfg.r, cfg.probe))
+
