@@ -1001,10 +1001,11 @@ hipError_t launch_reduce(const CorrParams &P, hipStream_t st, float *Zout, int n
     return hipGetLastError();
 }
 
-// T[e] = sum_s part[s][e] for E4 float4 elements (the same fixed-order kernel, for other callers' partial sums)
-hipError_t launch_reduce_raw(const float *part, float *T, int S, int E4, hipStream_t st)
+// T[e] = sum_s part[s][e] for E4 float4 elements (the same fixed-order kernel, for other callers' partial sums);
+// nsets such sums stored back to back
+hipError_t launch_reduce_raw(const float *part, float *T, int S, int E4, hipStream_t st, int nsets)
 {
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3(ceil_div(E4, 16), 1), dim3(kThreads), 0, st, reinterpret_cast<const f32x4 *>(part),
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3(ceil_div(E4, 16), nsets), dim3(kThreads), 0, st, reinterpret_cast<const f32x4 *>(part),
                        reinterpret_cast<f32x4 *>(T), S, E4, nullptr, 0, 0, 0, (uint64_t)0);
     return hipGetLastError();
 }

@@ -60,7 +60,7 @@ hipError_t launch_repack_planes(int dtype, const void *src, void *dst, long long
 // from P.part on, are reduced into as many tiles from T on (volumetric layers: one set per kernel-depth offset).
 hipError_t launch_reduce(const CorrParams &P, hipStream_t st, float *Zout = nullptr, int nz = 0, int dist = 0, uint64_t seed = 0,
                          float *T = nullptr, int nsets = 1);
-hipError_t launch_reduce_raw(const float *part, float *T, int S, int E4, hipStream_t st);
+hipError_t launch_reduce_raw(const float *part, float *T, int S, int E4, hipStream_t st, int nsets = 1);
 // dW[m,n,o] = (1/r) * sum_j Z[n,j] * T[o,j,m]   (Z != nullptr)
 // dW[m,n,o] = T[o,n,m]                          (Z == nullptr, exact path)
 // T != nullptr: K2 tiles [K2, JP, MP] are read from there (volumetric layers: kD * kH * kW offsets).
@@ -82,6 +82,10 @@ hipError_t launch_corr_ws32(const WsParams &P, hipStream_t st);
 // pixel_kernels.hip: Xbar[b, j] = sum_k X[b, k] Zimg[j, k] (forward product of the pixel x channel probes)
 bool pixel_fwd_ok(int dtype, long long K, const void *X);
 size_t pixel_fwd_partial_bytes(int dtype, long long K, int B, int r);
+// independent probing on NCHW rows: one product per input channel over its N = H*W values (whole 16-byte vectors)
+size_t pixel_fwd_indep_partial_bytes(int dtype, long long N, int C, int B, int r);
+hipError_t launch_pixel_fwd_indep(int dtype, const void *X, const void *Zimg, float *part, float *Xbar, long long N, int C, int B,
+                                  int r, hipStream_t st);
 hipError_t launch_pixel_fwd(int dtype, const void *X, const void *Zimg, float *part, float *Xbar, long long K, int B, int r,
                             hipStream_t st);
 

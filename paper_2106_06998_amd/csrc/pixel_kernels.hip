@@ -24,8 +24,8 @@ constexpr int kPfThreads = 256;
 // loads are in flight.  The k a lane supplies to an MFMA only has to be the same on both operands.
 template <int DT, int TM, int TN>
 __global__ __launch_bounds__(kPfThreads, 2) void pixel_fwd_kernel(const void *__restrict__ Xv, const void *__restrict__ Zv,
-                                                              float *__restrict__ part, long long K, int B, int r_img, int CSt,
-                                                              int NM, int S, int nbb, int njb)
+                                                              float *__restrict__ part, long long K, long long ld, int B,
+                                                              int r_img, int CSt, int NM, int S, int nbb, int njb)
 {
     constexpr int ES = DT == XCONV_F32 ? 4 : 2;
     constexpr int VE = 16 / ES;                          // k per vector
@@ -44,8 +44,11 @@ __global__ __launch_bounds__(kPfThreads, 2) void pixel_fwd_kernel(const void *__
     const int step0 = s * q + (s < rem ? s : rem);
     const int nstep = q + (s < rem ? 1 : 0);
 
-    const char *X = static_cast<const char *>(Xv);
-    const char *Z = static_cast<const char *>(Zv);
+    // blockIdx.y: independent probing, one product per input channel over its own K values of every row (rows are
+    // `ld` values apart); a single product has ld = K and one grid row
+    const char *X = static_cast<const char *>(Xv) + (size_t)blockIdx.y * (size_t)K * ES;
+    const char *Z = static_cast<const char *>(Zv) + (size_t)blockIdx.y * (size_t)K * ES;
+    part += (size_t)blockIdx.y * (size_t)S * B * CSt;
     // rows of this lane: image b0 + 16 tm + l16 and probing vector j0 + 16 tn + l16; past the end the
     // last one is read again and its products are not stored
     const char *xrow[TM];
@@ -54,13 +57,13 @@ __global__ __launch_bounds__(kPfThreads, 2) void pixel_fwd_kernel(const void *__
     for (int t = 0; t < TM; ++t) {
         int b = b0 + 16 * t + l16;
         b = b < B ? b : B - 1;
-        xrow[t] = X + (size_t)b * (size_t)K * ES;
+        xrow[t] = X + (size_t)b * (size_t)ld * ES;
     }
 #pragma unroll
     for (int t = 0; t < TN; ++t) {
         int j = j0 + 16 * t + l16;
         j = j < r_img ? j : r_img - 1;
-        zrow[t] = Z + (size_t)j * (size_t)K * ES;
+        zrow[t] = Z + (size_t)j * (size_t)ld * ES;
     }
 
     f32x4 acc[TN][TM];   // [row tile of probing vectors][column tile of images]
@@ -152,6 +155,18 @@ __global__ __launch_bounds__(kPfThreads) void pixel_xbar_compact_kernel(const fl
     Xbar[i] = T[(size_t)b * CSt + j];
 }
 
+// Independent probing: Xbar[b, c, j] = T[c, b, j] for j < r (T has one [B, CSt] block per input channel)
+__global__ __launch_bounds__(kPfThreads) void pixel_xbar_indep_kernel(const float *__restrict__ T, float *__restrict__ Xbar, int B,
+                                                                      int C, int CSt, int r)
+{
+    const long long i = (long long)blockIdx.x * kPfThreads + threadIdx.x;
+    if (i >= (long long)B * C * r) return;
+    const int j = (int)(i % r);
+    const long long bc = i / r;
+    const int c = (int)(bc % C), b = (int)(bc / C);
+    Xbar[i] = T[((size_t)c * B + b) * CSt + j];
+}
+
 }  // namespace
 
 // The product takes X and the probing vectors as rows of K values each in whole 16-byte vectors.
@@ -205,19 +220,20 @@ size_t pixel_fwd_partial_bytes(int dtype, long long K, int B, int r)
 }
 
 template <int DT, int TM, int TN>
-static void pixel_fwd_launch(const PixelFwdPlan &p, const void *X, const void *Zimg, float *part, long long K, int B, int r,
-                             hipStream_t st)
+static void pixel_fwd_launch(const PixelFwdPlan &p, const void *X, const void *Zimg, float *part, long long K, long long ld,
+                             int nprod, int B, int r, hipStream_t st)
 {
     const long long workers = (long long)p.S * p.nbb * p.njb;
-    hipLaunchKernelGGL((pixel_fwd_kernel<DT, TM, TN>), dim3((unsigned)((workers + 3) / 4)), dim3(kPfThreads), 0, st, X, Zimg, part, K,
-                       B, r, round_up(r, 16), p.NM, p.S, p.nbb, p.njb);
+    hipLaunchKernelGGL((pixel_fwd_kernel<DT, TM, TN>), dim3((unsigned)((workers + 3) / 4), nprod), dim3(kPfThreads), 0, st, X, Zimg,
+                       part, K, ld, B, r, round_up(r, 16), p.NM, p.S, p.nbb, p.njb);
 }
 
 template <int DT>
-static void pixel_fwd_dt(const PixelFwdPlan &p, const void *X, const void *Zimg, float *part, long long K, int B, int r, hipStream_t st)
+static void pixel_fwd_dt(const PixelFwdPlan &p, const void *X, const void *Zimg, float *part, long long K, long long ld, int nprod,
+                         int B, int r, hipStream_t st)
 {
 #define XC_PF(TM_, TN_) \
-    if (p.TM == TM_ && p.TN == TN_) return pixel_fwd_launch<DT, TM_, TN_>(p, X, Zimg, part, K, B, r, st);
+    if (p.TM == TM_ && p.TN == TN_) return pixel_fwd_launch<DT, TM_, TN_>(p, X, Zimg, part, K, ld, nprod, B, r, st);
     XC_PF(1, 1) XC_PF(1, 2) XC_PF(1, 4) XC_PF(2, 1) XC_PF(2, 2) XC_PF(2, 4) XC_PF(4, 1) XC_PF(4, 2) XC_PF(4, 4)
 #undef XC_PF
 }
@@ -227,9 +243,9 @@ hipError_t launch_pixel_fwd(int dtype, const void *X, const void *Zimg, float *p
                             hipStream_t st)
 {
     const PixelFwdPlan p = pixel_fwd_plan(dtype, K, B, r);
-    if (dtype == XCONV_F32) pixel_fwd_dt<XCONV_F32>(p, X, Zimg, part, K, B, r, st);
-    else if (dtype == XCONV_BF16) pixel_fwd_dt<XCONV_BF16>(p, X, Zimg, part, K, B, r, st);
-    else pixel_fwd_dt<XCONV_F16>(p, X, Zimg, part, K, B, r, st);
+    if (dtype == XCONV_F32) pixel_fwd_dt<XCONV_F32>(p, X, Zimg, part, K, K, 1, B, r, st);
+    else if (dtype == XCONV_BF16) pixel_fwd_dt<XCONV_BF16>(p, X, Zimg, part, K, K, 1, B, r, st);
+    else pixel_fwd_dt<XCONV_F16>(p, X, Zimg, part, K, K, 1, B, r, st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int CSt = round_up(r, 16);
@@ -239,6 +255,34 @@ hipError_t launch_pixel_fwd(int dtype, const void *X, const void *Zimg, float *p
     e = launch_reduce_raw(part, T, p.S, B * CSt / 4, st);
     if (e != hipSuccess || direct) return e;
     hipLaunchKernelGGL(pixel_xbar_compact_kernel, dim3(ceil_div(B * r, kPfThreads)), dim3(kPfThreads), 0, st, T, Xbar, B, CSt, r);
+    return hipGetLastError();
+}
+
+// Independent probing on NCHW rows: one product per input channel, Xbar[b, c, j] = sum_q X[b, c, q] Z[c*N + q, j], from the
+// same r images of K = C*N values (the rows of channel c of Z are the probing vectors of channel c).  N values per
+// channel in whole 16-byte vectors.  part: pixel_fwd_indep_partial_bytes() of scratch.
+size_t pixel_fwd_indep_partial_bytes(int dtype, long long N, int C, int B, int r)
+{
+    return (size_t)C * ((size_t)pixel_fwd_plan(dtype, N, B, r).S + 1) * B * round_up(r, 16) * sizeof(float);
+}
+
+hipError_t launch_pixel_fwd_indep(int dtype, const void *X, const void *Zimg, float *part, float *Xbar, long long N, int C, int B,
+                                  int r, hipStream_t st)
+{
+    const PixelFwdPlan p = pixel_fwd_plan(dtype, N, B, r);
+    const long long K = N * C;
+    if (dtype == XCONV_F32) pixel_fwd_dt<XCONV_F32>(p, X, Zimg, part, N, K, C, B, r, st);
+    else if (dtype == XCONV_BF16) pixel_fwd_dt<XCONV_BF16>(p, X, Zimg, part, N, K, C, B, r, st);
+    else pixel_fwd_dt<XCONV_F16>(p, X, Zimg, part, N, K, C, B, r, st);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int CSt = round_up(r, 16);
+    float *T = part + (size_t)C * p.S * B * CSt;
+    e = launch_reduce_raw(part, T, p.S, B * CSt / 4, st, C);
+    if (e != hipSuccess) return e;
+    const long long total = (long long)B * C * r;
+    hipLaunchKernelGGL(pixel_xbar_indep_kernel, dim3((unsigned)((total + kPfThreads - 1) / kPfThreads)), dim3(kPfThreads), 0, st, T,
+                       Xbar, B, C, CSt, r);
     return hipGetLastError();
 }
 

@@ -709,6 +709,8 @@ struct PixelGeom {
     xconv_desc probe;    // single-image channel probe of the backward pass (B channels)
     xconv_desc bwd;      // batch of CS images of the shifted product
     size_t zimg_f, zimg_b, xs, lt, l, probe_ws;
+    bool per_channel;    // independent probing, forward: one product per input channel from the r vectors of Z itself
+    size_t zimg_c;       // ... and the bytes of those r vectors
 };
 
 xconv_status pixel_geom(const xconv_desc *d, bool indep, PixelGeom &g)
@@ -742,6 +744,9 @@ xconv_status pixel_geom(const xconv_desc *d, bool indep, PixelGeom &g)
     g.lt = align_up((size_t)g.P * g.CS * eb, 256);
     g.l = g.lt;
     g.probe_ws = z_bytes(&g.probe) + zfrag_bytes(&g.probe);
+    // rows of one channel are contiguous in NCHW only, and the product wants them in whole 16-byte vectors
+    g.per_channel = indep && d->layout == XCONV_NCHW && pixel_fwd_ok(d->dtype, (long long)d->H * d->W, nullptr);
+    g.zimg_c = align_up((size_t)d->r * g.K * eb, 256);
     return XCONV_OK;
 }
 
@@ -759,9 +764,17 @@ size_t pixel_workspace_bytes(const xconv_desc *d, bool indep, int op)
     if (op == XCONV_OP_PROBE) {
         // the product kernel's partial sums, or (rows of X that are not whole 16-byte vectors) the scratch of the
         // exact-gradient path of the equivalent 1x1 layer
-        if (pixel_fwd_ok(d->dtype, g.K, nullptr)) return g.zimg_f + align_up(pixel_fwd_partial_bytes(d->dtype, g.K, d->B, g.R), 256);
+        // (an X that is not 16-byte aligned takes the block-diagonal route at run time: room for both)
+        size_t alt = 0;
+        if (g.per_channel)
+            alt = g.zimg_c + align_up(pixel_fwd_indep_partial_bytes(d->dtype, (long long)d->H * d->W, d->C_in, d->B, d->r), 256);
+        if (pixel_fwd_ok(d->dtype, g.K, nullptr)) {
+            const size_t w = g.zimg_f + align_up(pixel_fwd_partial_bytes(d->dtype, g.K, d->B, g.R), 256);
+            return w > alt ? w : alt;
+        }
         const size_t w = xconv_workspace_bytes(&g.fwd, XCONV_OP_EXACT);
-        return w ? g.zimg_f + w : 0;
+        if (w == 0) return 0;
+        return g.zimg_f + w > alt ? g.zimg_f + w : alt;
     }
     if (op == XCONV_OP_ESTIMATE) {
         const size_t w = xconv_workspace_bytes(&g.bwd, XCONV_OP_EXACT);
@@ -783,6 +796,13 @@ xconv_status pixel_probe_fwd(const xconv_desc *d, bool indep, const void *X_dev,
     if (ws_bytes < need) return XCONV_EWORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(ws_dev);
+    if (g.per_channel && pixel_fwd_ok(d->dtype, (long long)d->H * d->W, X_dev)) {
+        // the r vectors of Z; channel n's product reads their rows of channel n
+        XC_LAUNCH(K_GEN_ZIMG, st, launch_gen_zimg(d->dtype, ws, g.K, d->r, d->r, probe_code(d), d->seed, d->C_in, 0, 0, st));
+        XC_LAUNCH(K_PIXEL_FWD, st, launch_pixel_fwd_indep(d->dtype, X_dev, ws, reinterpret_cast<float *>(ws + g.zimg_c), Xbar_dev,
+                                                          (long long)d->H * d->W, d->C_in, d->B, d->r, st));
+        return XCONV_OK;
+    }
     // probing vectors as rows in the order X keeps its values in: (n, y, x), or (y, x, n) for channels-last
     XC_LAUNCH(K_GEN_ZIMG, st, launch_gen_zimg(d->dtype, ws, g.K, d->r, g.R, probe_code(d), d->seed, d->C_in,
                                               d->layout == XCONV_NHWC ? d->C_in : 0, indep, st));
