@@ -250,9 +250,10 @@ xconv_status xconv_pixel_dw_estimate(const xconv_desc *desc, const void *dY_dev,
  *             dW[m,n,ky,kx] = sum_j sum_{oy,ox} L_n[j,m,oy,ox] Z_n[(oy*sh+ky-ph, ox*sw+kx-pw), j]
  *
  * so no term mixes two input channels (no crosstalk), at C_in times the stored state:
- * Xbar is [B, C_in, r] floats, H*W/r times smaller than X in fp32.  Computed as the
- * multi-channel estimator with C_in*r block-diagonal probing vectors; limits as above
- * and C_in*r <= 1024, keep_q15 == 0 (else XCONV_EUNSUPPORTED). */
+ * Xbar is [B, C_in, r] floats, H*W/r times smaller than X in fp32.  The backward pass
+ * runs as the multi-channel estimator with C_in*r block-diagonal probing vectors (and
+ * costs accordingly); limits as above and C_in*r <= 1024, keep_q15 == 0 (else
+ * XCONV_EUNSUPPORTED). */
 size_t xconv_pixel_indep_xbar_bytes(const xconv_desc *desc);
 size_t xconv_pixel_indep_workspace_bytes(const xconv_desc *desc, int op);
 xconv_status xconv_pixel_indep_probe_fwd(const xconv_desc *desc, const void *X_dev, float *Xbar_dev,
