@@ -1,0 +1,165 @@
+"""Drop-in convolution layer around the weight-gradient estimator (the usage the paper's code
+example shows: a layer with a probing size next to the usual arguments, and a helper that swaps the
+convolutions of an existing network).
+
+What the layer changes is what is kept between the forward and the backward pass (Algorithm 1):
+instead of the input X it stores the probe output, r/C_in of X for probes over the channels
+(mode "channel"), B*r numbers for probes over pixels and channels (mode "multi", Eq. (6)), B*C_in*r
+for independent probing (mode "independent"); the weight gradient then comes from the matching
+estimate entry point of the library.  The forward convolution, the input gradient and the bias
+gradient are the framework's own operators and are exact; they are not part of this library.
+
+Z is drawn from a seed that changes with every forward call (Algorithm 1: seed and probing matrix
+are redrawn for each layer and iteration); nothing but the seed is kept of it.
+"""
+import itertools
+
+import torch
+import torch.nn.functional as F
+
+from . import binding as xb
+
+MODES = ("channel", "multi", "independent")
+_DTYPE = {torch.float32: "f32", torch.bfloat16: "bf16", torch.float16: "f16"}
+_calls = itertools.count(1)
+
+
+def _pair(v):
+    return (v, v) if isinstance(v, int) else tuple(v)
+
+
+def _layout_of(x):
+    """(layout code, tensor whose memory is in that layout)."""
+    if x.is_contiguous():
+        return xb.XCONV_NCHW, x
+    if x.is_contiguous(memory_format=torch.channels_last):
+        return xb.XCONV_NHWC, x
+    return xb.XCONV_NCHW, x.contiguous()
+
+
+def _as_layout(t, layout):
+    if layout == xb.XCONV_NHWC:
+        return t.contiguous(memory_format=torch.channels_last)
+    return t.contiguous()
+
+
+class _XConvFunction(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x, weight, bias, stride, padding, r, probe, mode, seed):
+        y = F.conv2d(x, weight, bias, stride, padding)
+        ctx.has_state = False
+        ctx.stride, ctx.padding, ctx.x_shape = stride, padding, x.shape
+        ctx.has_bias = bias is not None
+        if not weight.requires_grad:
+            ctx.save_for_backward(weight)
+            return y
+        if not x.is_cuda:
+            raise RuntimeError("XConv2d: the estimator runs on the GPU only (input on %s)" % x.device)
+        if x.dtype not in _DTYPE:
+            raise RuntimeError("XConv2d: storage type %s is not supported (float32, bfloat16, float16)" % x.dtype)
+        layout, xs = _layout_of(x.detach())
+        B, C_in, H, W = x.shape
+        d = xb.make_desc(B, C_in, weight.shape[0], H, W, tuple(weight.shape[2:]), stride, padding, r, _DTYPE[x.dtype], probe,
+                         seed, layout)
+        dev = x.device
+        with torch.cuda.device(dev):
+            if mode == "channel":
+                if xb.xconv_xt_bytes(d) == 0 or xb.xconv_workspace_bytes(d, xb.XCONV_OP_ESTIMATE) == 0:
+                    raise RuntimeError("XConv2d: layer not supported by the library (%s, r=%d)" % (tuple(x.shape), r))
+                state = xb.alloc_bytes(xb.xconv_xt_bytes(d), dev)
+                xb.xconv_probe_fwd(d, xs, state, None, xb.alloc_bytes(xb.xconv_workspace_bytes(d, xb.XCONV_OP_PROBE), dev))
+            else:
+                indep = mode == "independent"
+                nbytes = (xb.xconv_pixel_indep_xbar_bytes if indep else xb.xconv_pixel_xbar_bytes)(d)
+                wbytes = (xb.xconv_pixel_indep_workspace_bytes if indep else xb.xconv_pixel_workspace_bytes)(d, xb.XCONV_OP_PROBE)
+                if nbytes == 0 or wbytes == 0:
+                    raise RuntimeError("XConv2d: layer not supported in mode %r (%s, r=%d)" % (mode, tuple(x.shape), r))
+                state = torch.empty(nbytes // 4, dtype=torch.float32, device=dev)
+                (xb.xconv_pixel_indep_probe_fwd if indep else xb.xconv_pixel_probe_fwd)(d, xs, state, xb.alloc_bytes(wbytes, dev))
+        ctx.save_for_backward(weight, state)
+        ctx.has_state, ctx.desc, ctx.mode, ctx.layout, ctx.x_dtype = True, d, mode, layout, x.dtype
+        return y
+
+    @staticmethod
+    def backward(ctx, dy):
+        saved = ctx.saved_tensors
+        weight = saved[0]
+        dx = dw = db = None
+        if ctx.needs_input_grad[0]:
+            dx = torch.nn.grad.conv2d_input(ctx.x_shape, weight, dy, stride=ctx.stride, padding=ctx.padding)
+        if ctx.has_state and ctx.needs_input_grad[1]:
+            state, d, dev = saved[1], ctx.desc, dy.device
+            dys = _as_layout(dy.to(ctx.x_dtype), ctx.layout)
+            dw32 = torch.empty(weight.shape, dtype=torch.float32, device=dev)
+            with torch.cuda.device(dev):
+                if ctx.mode == "channel":
+                    ws = xb.alloc_bytes(xb.xconv_workspace_bytes(d, xb.XCONV_OP_ESTIMATE), dev)
+                    xb.xconv_dw_estimate(d, dys, state, None, dw32, ws)
+                elif ctx.mode == "multi":
+                    ws = xb.alloc_bytes(xb.xconv_pixel_workspace_bytes(d, xb.XCONV_OP_ESTIMATE), dev)
+                    xb.xconv_pixel_dw_estimate(d, dys, state, dw32, ws)
+                else:
+                    ws = xb.alloc_bytes(xb.xconv_pixel_indep_workspace_bytes(d, xb.XCONV_OP_ESTIMATE), dev)
+                    xb.xconv_pixel_indep_dw_estimate(d, dys, state, dw32, ws)
+            dw = dw32.to(weight.dtype)
+        if ctx.has_bias and ctx.needs_input_grad[2]:
+            db = dy.sum(dim=(0, 2, 3))
+        return dx, dw, db, None, None, None, None, None, None
+
+
+class XConv2d(torch.nn.Conv2d):
+    """torch.nn.Conv2d whose weight gradient is the estimate from `r` probing vectors.
+
+    r: number of probing vectors (the paper's probing size); probe: "rademacher" or "gaussian";
+    mode: "channel" (probes over the input channels, state r/C_in of X), "multi" (probes over pixels
+    and channels, Eq. (6), state B*r numbers) or "independent" (every input channel on its own).
+    Supported: dilation 1, groups 1, zero padding given as numbers.  In eval mode, or when the
+    weight needs no gradient, it is a plain convolution.  `last_seed` is the seed of the latest
+    training forward call.
+    """
+
+    def __init__(self, in_channels, out_channels, kernel_size, r=16, stride=1, padding=0, bias=True, probe="rademacher",
+                 mode="channel", base_seed=0, **kw):
+        super().__init__(in_channels, out_channels, kernel_size, stride=stride, padding=padding, bias=bias, **kw)
+        if _pair(self.dilation) != (1, 1) or self.groups != 1 or self.padding_mode != "zeros" or isinstance(self.padding, str):
+            raise ValueError("XConv2d: dilation 1, groups 1 and numeric zero padding only")
+        if mode not in MODES:
+            raise ValueError("XConv2d: mode must be one of %s" % (MODES,))
+        if probe not in ("rademacher", "gaussian"):
+            raise ValueError("XConv2d: probe must be 'rademacher' or 'gaussian'")
+        self.r, self.probe, self.mode, self.base_seed, self.last_seed = int(r), probe, mode, int(base_seed), None
+
+    def forward(self, x):
+        if not (self.training and torch.is_grad_enabled() and self.weight.requires_grad):
+            return super().forward(x)
+        self.last_seed = (self.base_seed * 0x9E3779B1 + next(_calls)) & 0x7FFFFFFFFFFFFFFF
+        return _XConvFunction.apply(x, self.weight, self.bias, _pair(self.stride), _pair(self.padding), self.r, self.probe,
+                                    self.mode, self.last_seed)
+
+    def extra_repr(self):
+        return super().extra_repr() + ", r=%d, probe=%s, mode=%s" % (self.r, self.probe, self.mode)
+
+
+def convert_net(model, r=16, probe="rademacher", mode="channel", min_in_channels=None):
+    """Replaces, in place, every torch.nn.Conv2d of `model` that the layer supports (dilation 1,
+    groups 1, zero padding, and at least `min_in_channels` input channels; default: more than r in
+    mode "channel", where fewer channels than probing vectors save nothing) by an XConv2d that
+    shares its parameters.  Returns the model and the number of layers replaced."""
+    if min_in_channels is None:
+        min_in_channels = r + 1 if mode == "channel" else 1
+    n = 0
+    for parent in list(model.modules()):
+        for name, child in list(parent.named_children()):
+            if type(child) is not torch.nn.Conv2d:
+                continue
+            if (_pair(child.dilation) != (1, 1) or child.groups != 1 or child.padding_mode != "zeros" or isinstance(child.padding, str)
+                    or child.in_channels < min_in_channels):
+                continue
+            new = XConv2d(child.in_channels, child.out_channels, child.kernel_size, r=r, stride=child.stride, padding=child.padding,
+                          bias=child.bias is not None, probe=probe, mode=mode, base_seed=n + 1,
+                          device=child.weight.device, dtype=child.weight.dtype)
+            new.weight, new.bias = child.weight, child.bias
+            new.train(child.training)
+            setattr(parent, name, new)
+            n += 1
+    return model, n
