@@ -140,8 +140,91 @@ class XConv2d(torch.nn.Conv2d):
         return super().extra_repr() + ", r=%d, probe=%s, mode=%s" % (self.r, self.probe, self.mode)
 
 
+def _triple(v):
+    return (v, v, v) if isinstance(v, int) else tuple(v)
+
+
+class _XConv3dFunction(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x, weight, bias, stride, padding, r, probe, seed):
+        y = F.conv3d(x, weight, bias, stride, padding)
+        ctx.has_state = False
+        ctx.stride, ctx.padding, ctx.x_shape = stride, padding, x.shape
+        ctx.has_bias = bias is not None
+        if not weight.requires_grad:
+            ctx.save_for_backward(weight)
+            return y
+        if not x.is_cuda:
+            raise RuntimeError("XConv3d: the estimator runs on the GPU only (input on %s)" % x.device)
+        if x.dtype not in _DTYPE:
+            raise RuntimeError("XConv3d: storage type %s is not supported (float32, bfloat16, float16)" % x.dtype)
+        xs, layout = x.detach(), xb.XCONV_NCHW
+        if not xs.is_contiguous():
+            if xs.is_contiguous(memory_format=torch.channels_last_3d):
+                layout = xb.XCONV_NHWC
+            else:
+                xs = xs.contiguous()
+        B, C_in, D, H, W = x.shape
+        v = xb.make_desc3d(B, C_in, weight.shape[0], D, H, W, tuple(weight.shape[2:]), stride, padding, r, _DTYPE[x.dtype], probe,
+                           seed, 0, layout)
+        dev = x.device
+        if xb.xconv3d_xt_bytes(v) == 0 or xb.xconv3d_workspace_bytes(v, xb.XCONV_OP_ESTIMATE) == 0:
+            raise RuntimeError("XConv3d: layer not supported by the library (%s, kernel %s, padding %s, r=%d)" % (
+                tuple(x.shape), tuple(weight.shape[2:]), padding, r))
+        with torch.cuda.device(dev):
+            state = xb.alloc_bytes(xb.xconv3d_xt_bytes(v), dev)
+            xb.xconv3d_probe_fwd(v, xs, state, None, xb.alloc_bytes(xb.xconv3d_workspace_bytes(v, xb.XCONV_OP_PROBE), dev))
+        ctx.save_for_backward(weight, state)
+        ctx.has_state, ctx.desc, ctx.layout, ctx.x_dtype = True, v, layout, x.dtype
+        return y
+
+    @staticmethod
+    def backward(ctx, dy):
+        saved = ctx.saved_tensors
+        weight = saved[0]
+        dx = dw = db = None
+        if ctx.needs_input_grad[0]:
+            dx = torch.nn.grad.conv3d_input(ctx.x_shape, weight, dy, stride=ctx.stride, padding=ctx.padding)
+        if ctx.has_state and ctx.needs_input_grad[1]:
+            state, v, dev = saved[1], ctx.desc, dy.device
+            dys = dy.to(ctx.x_dtype)
+            dys = dys.contiguous(memory_format=torch.channels_last_3d) if ctx.layout == xb.XCONV_NHWC else dys.contiguous()
+            dw32 = torch.empty(weight.shape, dtype=torch.float32, device=dev)
+            with torch.cuda.device(dev):
+                xb.xconv3d_dw_estimate(v, dys, state, None, dw32, xb.alloc_bytes(xb.xconv3d_workspace_bytes(v, xb.XCONV_OP_ESTIMATE), dev))
+            dw = dw32.to(weight.dtype)
+        if ctx.has_bias and ctx.needs_input_grad[2]:
+            db = dy.sum(dim=(0, 2, 3, 4))
+        return dx, dw, db, None, None, None, None, None
+
+
+class XConv3d(torch.nn.Conv3d):
+    """torch.nn.Conv3d whose weight gradient is the estimate from `r` probing vectors over the input
+    channels (the stored state is r/C_in of X).  Supported: dilation 1, groups 1, numeric zero padding,
+    kernel depth up to 7 and depth padding below the kernel depth; NCDHW or channels-last volumes."""
+
+    def __init__(self, in_channels, out_channels, kernel_size, r=16, stride=1, padding=0, bias=True, probe="rademacher",
+                 base_seed=0, **kw):
+        super().__init__(in_channels, out_channels, kernel_size, stride=stride, padding=padding, bias=bias, **kw)
+        if _triple(self.dilation) != (1, 1, 1) or self.groups != 1 or self.padding_mode != "zeros" or isinstance(self.padding, str):
+            raise ValueError("XConv3d: dilation 1, groups 1 and numeric zero padding only")
+        if probe not in ("rademacher", "gaussian"):
+            raise ValueError("XConv3d: probe must be 'rademacher' or 'gaussian'")
+        self.r, self.probe, self.base_seed, self.last_seed = int(r), probe, int(base_seed), None
+
+    def forward(self, x):
+        if not (self.training and torch.is_grad_enabled() and self.weight.requires_grad):
+            return super().forward(x)
+        self.last_seed = (self.base_seed * 0x9E3779B1 + next(_calls)) & 0x7FFFFFFFFFFFFFFF
+        return _XConv3dFunction.apply(x, self.weight, self.bias, _triple(self.stride), _triple(self.padding), self.r, self.probe,
+                                      self.last_seed)
+
+    def extra_repr(self):
+        return super().extra_repr() + ", r=%d, probe=%s" % (self.r, self.probe)
+
+
 def convert_net(model, r=16, probe="rademacher", mode="channel", min_in_channels=None):
-    """Replaces, in place, every torch.nn.Conv2d of `model` that the layer supports (dilation 1,
+    """Replaces, in place, every torch.nn.Conv2d (and, in mode "channel", torch.nn.Conv3d) of `model` that the layer supports (dilation 1,
     groups 1, zero padding, and at least `min_in_channels` input channels; default: more than r in
     mode "channel", where fewer channels than probing vectors save nothing) by an XConv2d that
     shares its parameters.  Returns the model and the number of layers replaced."""
@@ -150,6 +233,19 @@ def convert_net(model, r=16, probe="rademacher", mode="channel", min_in_channels
     n = 0
     for parent in list(model.modules()):
         for name, child in list(parent.named_children()):
+            if type(child) is torch.nn.Conv3d and mode == "channel":
+                kD, pd = child.kernel_size[0], child.padding[0] if not isinstance(child.padding, str) else -1
+                if (_triple(child.dilation) != (1, 1, 1) or child.groups != 1 or child.padding_mode != "zeros" or pd < 0 or pd > kD - 1
+                        or kD > 7 or child.in_channels < min_in_channels):
+                    continue
+                new = XConv3d(child.in_channels, child.out_channels, child.kernel_size, r=r, stride=child.stride,
+                              padding=child.padding, bias=child.bias is not None, probe=probe, base_seed=n + 1,
+                              device=child.weight.device, dtype=child.weight.dtype)
+                new.weight, new.bias = child.weight, child.bias
+                new.train(child.training)
+                setattr(parent, name, new)
+                n += 1
+                continue
             if type(child) is not torch.nn.Conv2d:
                 continue
             if (_pair(child.dilation) != (1, 1) or child.groups != 1 or child.padding_mode != "zeros" or isinstance(child.padding, str)

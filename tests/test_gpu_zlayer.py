@@ -8,7 +8,7 @@ import torch
 from oracle import xconv_oracle as xo
 from paper_2106_06998_amd import binding as xb
 from paper_2106_06998_amd import synth
-from paper_2106_06998_amd.layer import XConv2d, convert_net
+from paper_2106_06998_amd.layer import XConv2d, XConv3d, convert_net
 from test_gpu_parity import DEV, GRAD_TOL, ODT, OPROBE, rel_max, say
 
 pytestmark = pytest.mark.gpu
@@ -128,3 +128,44 @@ def test_convert_net_swaps_the_supported_convolutions_and_trains():
         opt.step()
         losses.append(float(loss.detach()))
     assert np.isfinite(losses).all() and np.mean(losses[-5:]) < losses[0] - 0.1, losses   # the noisy gradients still fit a fixed batch
+
+
+# dtype, B, C_in, C_out, (D,H,W), k, stride, pad, r, probe, channels-last
+VOLS = [
+    ("f32", 2, 16, 24, (6, 12, 12), (3, 3, 3), (1, 1, 1), (1, 1, 1), 8, "gaussian", False),
+    ("f16", 3, 32, 32, (7, 8, 8), (3, 3, 3), (2, 1, 1), (1, 1, 1), 16, "rademacher", False),
+    ("bf16", 2, 32, 16, (5, 8, 8), (3, 3, 3), (1, 1, 1), (1, 1, 1), 16, "rademacher", True),
+]
+
+
+@pytest.mark.parametrize("e", VOLS, ids=["%s%s" % (e[0], "-cl" if e[10] else "") for e in VOLS])
+def test_volumetric_layer_gradients(e):
+    dtype, B, C_in, C_out, dims, k, st, pad, r, probe, cl = e
+    say("volumetric layer %s" % (e,))
+    out = tuple(xo.out_extent(n, kk, s, p) for n, kk, s, p in zip(dims, k, st, pad))
+    X, G = synth.make_volume(B, C_in, C_out, dims, out, (71, 72, 0), dtype)
+    torch.manual_seed(6)
+    layer = XConv3d(C_in, C_out, k, r=r, stride=st, padding=pad, probe=probe).to(DEV).to(TD[dtype])
+    ref = torch.nn.Conv3d(C_in, C_out, k, stride=st, padding=pad).to(DEV).to(TD[dtype])
+    ref.load_state_dict(layer.state_dict())
+    fmt = torch.channels_last_3d if cl else torch.contiguous_format
+    x = xb.to_device(X, dtype, DEV).contiguous(memory_format=fmt).requires_grad_(True)
+    xr = x.detach().clone().requires_grad_(True)
+    g = xb.to_device(G, dtype, DEV).contiguous(memory_format=fmt)
+    y = layer(x)
+    saved = [t for t in y.grad_fn.saved_tensors if t is not layer.weight]
+    (y * g).sum().backward()
+    (ref(xr) * g).sum().backward()
+    torch.cuda.synchronize()
+    ex = 1e-3 if dtype == "f32" else 2e-2
+    assert torch.allclose(x.grad.float(), xr.grad.float(), rtol=ex, atol=ex * float(xr.grad.float().abs().max()))
+    assert torch.allclose(layer.bias.grad.float(), ref.bias.grad.float(), rtol=ex, atol=ex * float(ref.bias.grad.float().abs().max()))
+    Z = xo.probe_matrix(OPROBE[probe], layer.last_seed, C_in, r)
+    want = xo.dw_from_xt3d(G, xo.probe_fwd3d(X, Z, ODT[dtype]), Z, k, st, pad)
+    got = layer.weight.grad.float().cpu().numpy().astype(np.float64)
+    tol = GRAD_TOL[dtype] + (2.0 ** -8 if dtype == "bf16" else 2.0 ** -11 if dtype == "f16" else 0.0)
+    assert rel_max(got, want) <= tol, rel_max(got, want)
+    v = xb.make_desc3d(B, C_in, C_out, dims[0], dims[1], dims[2], k, st, pad, r, dtype, probe, layer.last_seed, 0,
+                       xb.XCONV_NHWC if cl else xb.XCONV_NCHW)
+    assert len(saved) == 1 and saved[0].numel() * saved[0].element_size() == xb.xconv3d_xt_bytes(v)   # the probe output, not X
+

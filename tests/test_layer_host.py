@@ -3,7 +3,7 @@ and a loud refusal to estimate without a GPU (there is no CPU fallback)."""
 import pytest
 import torch
 
-from paper_2106_06998_amd.layer import XConv2d, convert_net
+from paper_2106_06998_amd.layer import XConv2d, XConv3d, convert_net
 
 
 def test_layer_is_a_conv2d_with_the_probing_arguments():
@@ -55,3 +55,23 @@ def test_convert_net_replaces_only_what_the_layer_supports():
     assert again == 0                                           # already converted layers are left alone
     net2, n2 = convert_net(torch.nn.Sequential(torch.nn.Conv2d(3, 8, 3)), r=8, mode="multi")
     assert n2 == 1                                              # probes over pixels and channels pay off for any channel count
+
+
+def test_volumetric_layer_and_its_conversion():
+    layer = XConv3d(32, 8, 3, r=8, padding=1)
+    assert isinstance(layer, torch.nn.Conv3d) and "r=8" in repr(layer)
+    with pytest.raises(ValueError):
+        XConv3d(32, 8, 3, r=8, dilation=2)
+    with pytest.raises(RuntimeError, match="GPU only"):
+        layer(torch.randn(1, 32, 4, 4, 4))
+    layer.eval()
+    x = torch.randn(1, 32, 4, 4, 4)
+    assert torch.equal(layer(x), torch.nn.functional.conv3d(x, layer.weight, layer.bias, 1, 1))
+    net = torch.nn.Sequential(torch.nn.Conv3d(32, 8, 3, padding=1),
+                              torch.nn.Conv3d(32, 8, 3, padding=3),     # depth padding beyond the kernel depth: kept
+                              torch.nn.Conv3d(4, 8, 3, padding=1))      # fewer channels than probing vectors: kept
+    net, n = convert_net(net, r=8)
+    assert n == 1 and isinstance(net[0], XConv3d) and type(net[1]) is torch.nn.Conv3d and type(net[2]) is torch.nn.Conv3d
+    _, m = convert_net(torch.nn.Sequential(torch.nn.Conv3d(32, 8, 3, padding=1)), r=8, mode="multi")
+    assert m == 0                                                       # volumetric layers take channel probes only
+
