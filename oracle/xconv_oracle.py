@@ -390,3 +390,23 @@ def pixel_indep_dw_estimate(dY, Xbar, Z, C_in, H, W, kH, kW, stride=(1, 1), pad=
     for n in range(C_in):
         dW[:, n:n + 1] = pixel_dw_estimate(dY, Xbar[:, n, :], Z[n * N:(n + 1) * N], 1, H, W, kH, kW, stride, pad, dtype)
     return dW
+
+
+def relu_sign_fwd(X):
+    """ReLU that keeps only the signs of its input for the backward pass (Sec. 5, "Overall effective memory
+    savings": layers that relied on the convolution to store their state): Y = max(X, 0) and one bit per
+    element, bit i%64 of 64-bit word i//64 set iff element i (row-major) is positive."""
+    X = np.asarray(X)
+    pos = (X.reshape(-1) > 0)
+    n = pos.size
+    padded = np.zeros((n + 63) // 64 * 64, dtype=np.uint8)
+    padded[:n] = pos
+    words = np.packbits(padded.reshape(-1, 64), axis=1, bitorder="little").view("<u8").reshape(-1)
+    return np.maximum(X, 0), words
+
+
+def relu_sign_bwd(dY, words):
+    """dX = dY where the stored sign bit is set, else 0."""
+    dY = np.asarray(dY)
+    bits = np.unpackbits(np.ascontiguousarray(words, dtype="<u8").view(np.uint8), bitorder="little")[:dY.size]
+    return np.where(bits.reshape(dY.shape) != 0, dY, 0).astype(dY.dtype)

@@ -782,3 +782,33 @@ def test_independent_probing_is_unbiased_and_closer_than_multi_channel_probing()
     mean = np.linalg.norm(acc / S - exact) / np.linalg.norm(exact)
     assert mean < 3.0 * one / np.sqrt(S), (mean, one)                       # the mean of S draws shrinks like 1/sqrt(S)
     assert e_ind < 0.6 * e_sim, (e_ind, e_sim)                               # C_in = 4 channels of crosstalk removed
+
+
+# ---------------------------------------------------------------------------
+# ReLU that keeps signs only (Sec. 5, overall effective memory savings: layers that relied on the convolution's stored input)
+# ---------------------------------------------------------------------------
+def test_sign_relu_bit_layout_and_values():
+    x = -np.ones(130, dtype=np.float32)
+    x[[0, 63, 64, 129]] = [2.0, 0.5, 3.0, 1.0]
+    x[5] = 0.0                                            # zero is not positive: no gradient through it
+    y, words = xo.relu_sign_fwd(x)
+    assert words.dtype == np.uint64 and words.tolist() == [1 | (1 << 63), 1, 2]
+    assert np.array_equal(y, np.where(x > 0, x, 0))
+    dy = np.arange(1, 131, dtype=np.float32)
+    dx = xo.relu_sign_bwd(dy, words)
+    assert np.array_equal(np.nonzero(dx)[0], [0, 63, 64, 129]) and dx[129] == 130.0
+
+
+def test_sign_relu_matches_autograd():
+    import torch
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal((3, 5, 7, 6)).astype(np.float32)
+    x[0, 0, 0, :3] = 0.0
+    dy = rng.standard_normal(x.shape).astype(np.float32)
+    t = torch.from_numpy(x).requires_grad_(True)
+    out = torch.relu(t)
+    out.backward(torch.from_numpy(dy))
+    y, words = xo.relu_sign_fwd(x)
+    assert np.array_equal(y, out.detach().numpy())
+    assert words.size == (x.size + 63) // 64
+    assert np.array_equal(xo.relu_sign_bwd(dy, words), t.grad.numpy())
