@@ -261,6 +261,24 @@ xconv_status xconv_pixel_indep_probe_fwd(const xconv_desc *desc, const void *X_d
 xconv_status xconv_pixel_indep_dw_estimate(const xconv_desc *desc, const void *dY_dev, const float *Xbar_dev,
                                            float *dW_dev, void *ws_dev, size_t ws_bytes, void *stream);
 
+/* ---- ReLU that keeps signs only --------------------------------------------------
+ * A ReLU in front of a convolution used to find its output stored by that convolution;
+ * with the layers above the convolution keeps the probe output instead, so the ReLU
+ * keeps one bit per element (Sec. 5, "Overall effective memory savings").
+ *
+ *   forward   Y[i] = max(X[i], 0);  bit i%64 of the 64-bit word i/64 of mask = (X[i] > 0)
+ *   backward  dX[i] = that bit ? dY[i] : 0
+ *
+ * n elements of `dtype` (an xconv_dtype) in any shape, taken in memory order.  mask_dev:
+ * xconv_relu_mask_bytes(n) bytes, 8-byte aligned, owned by the caller; X_dev, Y_dev,
+ * dY_dev, dX_dev 16-byte aligned.  Y_dev may equal X_dev and dX_dev may equal dY_dev
+ * (in place).  A NaN stays a NaN in Y and counts as not positive.  n == 0 is a no-op;
+ * XCONV_EINVAL for a bad dtype, n < 0, a null or misaligned pointer; n above 2^40 is
+ * XCONV_EUNSUPPORTED. */
+size_t xconv_relu_mask_bytes(long long n);
+xconv_status xconv_relu_fwd(int dtype, const void *X_dev, void *Y_dev, void *mask_dev, long long n, void *stream);
+xconv_status xconv_relu_bwd(int dtype, const void *dY_dev, const void *mask_dev, void *dX_dev, long long n, void *stream);
+
 /* Per-kernel timing with HIP events recorded on the launch stream.  While
  * enabled, every kernel the library enqueues is bracketed by two events.
  * xconv_prof_collect synchronises those events, writes up to `max` records

@@ -98,6 +98,12 @@ def lib():
         L.xconv_pixel_probe_fwd.argtypes = [P, vp, vp, vp, sz, vp]
         L.xconv_pixel_dw_estimate.restype = i32
         L.xconv_pixel_dw_estimate.argtypes = [P, vp, vp, vp, vp, sz, vp]
+        L.xconv_relu_mask_bytes.restype = sz
+        L.xconv_relu_mask_bytes.argtypes = [ctypes.c_longlong]
+        L.xconv_relu_fwd.restype = i32
+        L.xconv_relu_fwd.argtypes = [i32, vp, vp, vp, ctypes.c_longlong, vp]
+        L.xconv_relu_bwd.restype = i32
+        L.xconv_relu_bwd.argtypes = [i32, vp, vp, vp, ctypes.c_longlong, vp]
         L.xconv_pixel_indep_xbar_bytes.restype = sz
         L.xconv_pixel_indep_xbar_bytes.argtypes = [P]
         L.xconv_pixel_indep_workspace_bytes.restype = sz
@@ -330,3 +336,19 @@ def xconv_pixel_indep_probe_fwd(desc, X_dev, Xbar_dev, ws_dev, stream=None):
 def xconv_pixel_indep_dw_estimate(desc, dY_dev, Xbar_dev, dW_dev, ws_dev, stream=None):
     _check(lib().xconv_pixel_indep_dw_estimate(ctypes.byref(desc), _ptr(dY_dev), _ptr(Xbar_dev), _ptr(dW_dev), _ptr(ws_dev),
                                                _nbytes(ws_dev), _stream(stream)), "xconv_pixel_indep_dw_estimate")
+
+
+# ---- ReLU that keeps one sign bit per element -----------------------------------------
+def xconv_relu_mask_bytes(n):
+    return int(lib().xconv_relu_mask_bytes(int(n)))
+
+
+def xconv_relu_fwd(dtype, X_dev, Y_dev, mask_dev, n, stream=None):
+    _check(lib().xconv_relu_fwd(DTYPES[dtype] if isinstance(dtype, str) else dtype, _ptr(X_dev), _ptr(Y_dev), _ptr(mask_dev), int(n),
+                                _stream(stream)), "xconv_relu_fwd")
+
+
+def xconv_relu_bwd(dtype, dY_dev, mask_dev, dX_dev, n, stream=None):
+    _check(lib().xconv_relu_bwd(DTYPES[dtype] if isinstance(dtype, str) else dtype, _ptr(dY_dev), _ptr(mask_dev), _ptr(dX_dev), int(n),
+                                _stream(stream)), "xconv_relu_bwd")
+

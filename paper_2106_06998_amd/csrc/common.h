@@ -30,7 +30,8 @@ enum KernelId {
     K_GEN_ZIMG = 11,
     K_SCALE = 12,
     K_PIXEL_FWD = 13,
-    K_COUNT = 14
+    K_RELU = 14,
+    K_COUNT = 15
 };
 
 // Where the probe output of a voxel goes in Xt.  sd == 0: plain order, pixel `first` of the

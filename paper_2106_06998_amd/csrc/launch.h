@@ -35,6 +35,9 @@ hipError_t launch_dy_slices(int dtype, const void *src, void *dst, int B, int C,
 hipError_t launch_gen_zimg(int dtype, void *out, long long K, int r, int nimg, int dist, uint64_t seed, int C_in, int cl_cs,
                            int indep, hipStream_t st);
 hipError_t launch_scale(const float *in, float *out, int n, float f, hipStream_t st);
+// ReLU that keeps one sign bit per element (64-bit words, bit i%64 of word i/64); Y may be X, dX may be dY
+hipError_t launch_relu_sign_fwd(int dtype, const void *X, void *Y, void *words, long long n, hipStream_t st);
+hipError_t launch_relu_sign_bwd(int dtype, const void *dY, const void *words, void *dX, long long n, hipStream_t st);
 // dW[:, n] *= r / (kept blocks of channel n), or 0 without any (block-sparse probes over pixels and channels, Eq. (8))
 hipError_t launch_nnz_rescale(float *dW, int C_out, int C_in, int K2, int r, int dist, uint64_t seed, hipStream_t st);
 hipError_t launch_unpack(int dtype, const void *Xt, float *out, int B, int HW, int r, int CS, hipStream_t st);

@@ -882,6 +882,33 @@ xconv_status xconv_pixel_indep_dw_estimate(const xconv_desc *d, const void *dY_d
     return pixel_dw_estimate(d, true, dY_dev, Xbar_dev, dW_dev, ws_dev, ws_bytes, stream);
 }
 
+// ---- ReLU that keeps signs only -----------------------------------------------------
+size_t xconv_relu_mask_bytes(long long n) { return n <= 0 ? 0 : (size_t)((n + 63) / 64) * 8; }
+
+xconv_status xconv_relu_fwd(int dtype, const void *X_dev, void *Y_dev, void *mask_dev, long long n, void *stream)
+{
+    if (dtype < XCONV_F32 || dtype > XCONV_F16 || n < 0) return XCONV_EINVAL;
+    if (n == 0) return XCONV_OK;
+    if (!X_dev || !Y_dev || !mask_dev) return XCONV_EINVAL;
+    if (!aligned16(X_dev) || !aligned16(Y_dev) || (reinterpret_cast<uintptr_t>(mask_dev) & 7u) != 0) return XCONV_EINVAL;
+    if (n > (1LL << 40)) return XCONV_EUNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    XC_LAUNCH(K_RELU, st, launch_relu_sign_fwd(dtype, X_dev, Y_dev, mask_dev, n, st));
+    return XCONV_OK;
+}
+
+xconv_status xconv_relu_bwd(int dtype, const void *dY_dev, const void *mask_dev, void *dX_dev, long long n, void *stream)
+{
+    if (dtype < XCONV_F32 || dtype > XCONV_F16 || n < 0) return XCONV_EINVAL;
+    if (n == 0) return XCONV_OK;
+    if (!dY_dev || !dX_dev || !mask_dev) return XCONV_EINVAL;
+    if (!aligned16(dY_dev) || !aligned16(dX_dev) || (reinterpret_cast<uintptr_t>(mask_dev) & 7u) != 0) return XCONV_EINVAL;
+    if (n > (1LL << 40)) return XCONV_EUNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    XC_LAUNCH(K_RELU, st, launch_relu_sign_bwd(dtype, dY_dev, mask_dev, dX_dev, n, st));
+    return XCONV_OK;
+}
+
 void xconv_prof_enable(int on)
 {
     std::lock_guard<std::mutex> lk(g_prof_mu);
@@ -923,6 +950,7 @@ const char *xconv_prof_kernel_name(int id)
     case K_GEN_ZIMG: return "gen_zimg_kernel";
     case K_SCALE: return "scale_kernel";
     case K_PIXEL_FWD: return "pixel_fwd_kernel";
+    case K_RELU: return "relu_sign_kernel";
     default: return "unknown";
     }
 }

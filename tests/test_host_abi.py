@@ -307,3 +307,18 @@ def test_launch_plans_stay_within_the_device_limits_on_random_layers():
             assert plan["NTM"] * plan["M_WG"] >= d.C_out and plan["NTJ"] * plan["J_WG"] == plan["CS"]
             assert ws < 2 ** 34
     assert seen == {0, 1, 2}          # all three correlation kernels get layers
+
+
+def test_sign_relu_sizes_and_argument_checks():
+    assert [xb.xconv_relu_mask_bytes(n) for n in (0, 1, 64, 65, 1 << 20)] == [0, 8, 8, 16, 1 << 17]
+    L = xb.lib()
+    one = ctypes.c_void_p(4096)          # never dereferenced: validation fails first
+    assert L.xconv_relu_fwd(0, None, None, None, 0, None) == xb.XCONV_OK            # nothing to do
+    assert L.xconv_relu_fwd(3, one, one, one, 8, None) == xb.XCONV_EINVAL           # dtype
+    assert L.xconv_relu_fwd(0, one, one, one, -1, None) == xb.XCONV_EINVAL
+    assert L.xconv_relu_fwd(0, None, one, one, 8, None) == xb.XCONV_EINVAL
+    assert L.xconv_relu_fwd(0, ctypes.c_void_p(4100), one, one, 8, None) == xb.XCONV_EINVAL   # X misaligned
+    assert L.xconv_relu_fwd(0, one, one, ctypes.c_void_p(4100), 8, None) == xb.XCONV_EINVAL   # mask misaligned
+    assert L.xconv_relu_bwd(1, one, None, one, 8, None) == xb.XCONV_EINVAL
+    assert L.xconv_relu_bwd(2, one, one, one, (1 << 40) + 1, None) == xb.XCONV_EUNSUPPORTED
+
