@@ -140,6 +140,49 @@ class XConv2d(torch.nn.Conv2d):
         return super().extra_repr() + ", r=%d, probe=%s, mode=%s" % (self.r, self.probe, self.mode)
 
 
+class _SignReLUFunction(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x):
+        if not x.is_cuda:
+            raise RuntimeError("SignReLU: runs on the GPU only (input on %s)" % x.device)
+        if x.dtype not in _DTYPE:
+            raise RuntimeError("SignReLU: storage type %s is not supported (float32, bfloat16, float16)" % x.dtype)
+        # values in memory order: the mask is per element, whatever the layout
+        xs = x.detach()
+        if not (xs.is_contiguous() or xs.is_contiguous(memory_format=torch.channels_last)
+                or (xs.dim() == 5 and xs.is_contiguous(memory_format=torch.channels_last_3d))):
+            xs = xs.contiguous()
+        y = torch.empty_like(xs)          # same strides as xs
+        n = xs.numel()
+        mask = torch.empty(max(xb.xconv_relu_mask_bytes(n) // 8, 1), dtype=torch.int64, device=x.device)
+        with torch.cuda.device(x.device):
+            xb.xconv_relu_fwd(_DTYPE[x.dtype], xs, y, mask, n)
+        ctx.save_for_backward(mask)
+        ctx.meta = (tuple(y.shape), tuple(y.stride()), y.dtype)     # not y itself: nothing but the mask is kept
+        return y
+
+    @staticmethod
+    def backward(ctx, dy):
+        (mask,) = ctx.saved_tensors
+        shape, strides, dtype = ctx.meta
+        # the gradient in the memory order of the output
+        g = torch.empty_strided(shape, strides, dtype=dtype, device=dy.device)
+        g.copy_(dy)
+        with torch.cuda.device(g.device):
+            xb.xconv_relu_bwd(_DTYPE[g.dtype], g, mask, g, g.numel())
+        return g
+
+
+class SignReLU(torch.nn.Module):
+    """ReLU that keeps one bit per element for its backward pass instead of its output (which the
+    next convolution no longer stores once it is an XConv layer)."""
+
+    def forward(self, x):
+        if not (torch.is_grad_enabled() and x.requires_grad):
+            return F.relu(x)
+        return _SignReLUFunction.apply(x)
+
+
 def _triple(v):
     return (v, v, v) if isinstance(v, int) else tuple(v)
 
@@ -223,16 +266,20 @@ class XConv3d(torch.nn.Conv3d):
         return super().extra_repr() + ", r=%d, probe=%s" % (self.r, self.probe)
 
 
-def convert_net(model, r=16, probe="rademacher", mode="channel", min_in_channels=None):
+def convert_net(model, r=16, probe="rademacher", mode="channel", min_in_channels=None, relu=False):
     """Replaces, in place, every torch.nn.Conv2d (and, in mode "channel", torch.nn.Conv3d) of `model` that the layer supports (dilation 1,
     groups 1, zero padding, and at least `min_in_channels` input channels; default: more than r in
     mode "channel", where fewer channels than probing vectors save nothing) by an XConv2d that
-    shares its parameters.  Returns the model and the number of layers replaced."""
+    shares its parameters.  relu=True also replaces every torch.nn.ReLU by a SignReLU, which keeps one bit per
+    element instead of its output.  Returns the model and the number of convolutions replaced."""
     if min_in_channels is None:
         min_in_channels = r + 1 if mode == "channel" else 1
     n = 0
     for parent in list(model.modules()):
         for name, child in list(parent.named_children()):
+            if relu and type(child) is torch.nn.ReLU:
+                setattr(parent, name, SignReLU())
+                continue
             if type(child) is torch.nn.Conv3d and mode == "channel":
                 kD, pd = child.kernel_size[0], child.padding[0] if not isinstance(child.padding, str) else -1
                 if (_triple(child.dilation) != (1, 1, 1) or child.groups != 1 or child.padding_mode != "zeros" or pd < 0 or pd > kD - 1

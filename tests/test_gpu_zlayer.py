@@ -8,7 +8,7 @@ import torch
 from oracle import xconv_oracle as xo
 from paper_2106_06998_amd import binding as xb
 from paper_2106_06998_amd import synth
-from paper_2106_06998_amd.layer import XConv2d, XConv3d, convert_net
+from paper_2106_06998_amd.layer import SignReLU, XConv2d, XConv3d, convert_net
 from test_gpu_parity import DEV, GRAD_TOL, ODT, OPROBE, rel_max, say
 
 pytestmark = pytest.mark.gpu
@@ -168,4 +168,55 @@ def test_volumetric_layer_gradients(e):
     v = xb.make_desc3d(B, C_in, C_out, dims[0], dims[1], dims[2], k, st, pad, r, dtype, probe, layer.last_seed, 0,
                        xb.XCONV_NHWC if cl else xb.XCONV_NCHW)
     assert len(saved) == 1 and saved[0].numel() * saved[0].element_size() == xb.xconv3d_xt_bytes(v)   # the probe output, not X
+
+
+@pytest.mark.parametrize("dtype,cl", [("f32", False), ("f16", True), ("bf16", False)])
+def test_sign_relu_module_gives_the_relu_gradient_and_keeps_bits_only(dtype, cl):
+    say("SignReLU module %s%s" % (dtype, " channels-last" if cl else ""))
+    fmt = torch.channels_last if cl else torch.contiguous_format
+    x = xb.to_device(synth.draw((5, 12, 9, 7), 77, "normal", 1.0, dtype), dtype, DEV).contiguous(memory_format=fmt).requires_grad_(True)
+    g = xb.to_device(synth.draw((5, 12, 9, 7), 78, "normal", 1.0, dtype), dtype, DEV)
+    y = SignReLU()(x)
+    saved = list(y.grad_fn.saved_tensors)
+    y.backward(g)
+    xr = x.detach().clone().requires_grad_(True)
+    yr = torch.relu(xr)
+    yr.backward(g)
+    torch.cuda.synchronize()
+    assert torch.equal(y, yr) and torch.equal(x.grad, xr.grad)
+    assert len(saved) == 1 and saved[0].numel() * 8 == xb.xconv_relu_mask_bytes(x.numel())   # 1 bit per element
+    assert torch.equal(SignReLU()(x.detach()), torch.relu(x.detach()))                         # no gradient needed: plain ReLU
+
+
+def saved_bytes(net, x):
+    """Bytes of the distinct tensors autograd keeps for the backward pass of net(x) (parameters excluded)."""
+    seen, params = {}, {p.data_ptr() for p in net.parameters()}
+
+    def pack(t):
+        if t.data_ptr() not in params:
+            seen[t.data_ptr()] = t.numel() * t.element_size()
+        return t
+
+    with torch.autograd.graph.saved_tensors_hooks(pack, lambda t: t):
+        y = net(x)
+    y.sum().backward()
+    return sum(seen.values())
+
+
+def test_converted_network_keeps_a_fraction_of_the_activations():
+    # C_in = 64, r = 16: a convolution keeps a quarter of its input and a ReLU 1/32 of its output (fp32) instead of the
+    # shared full tensor
+    torch.manual_seed(3)
+    layers = []
+    for _ in range(6):
+        layers += [torch.nn.Conv2d(64, 64, 3, padding=1), torch.nn.ReLU()]
+    net = torch.nn.Sequential(*layers).to(DEV)
+    x = torch.randn(16, 64, 32, 32, device=DEV).relu_()
+    plain = saved_bytes(net, x)
+    act = x.numel() * 4
+    assert plain >= 6 * act
+    net, n = convert_net(net, r=16, relu=True)
+    assert n == 6
+    small = saved_bytes(net, x)
+    assert small <= 6 * act * (16 / 64 + 1 / 32) * 1.02, (plain, small)
 

@@ -3,7 +3,7 @@ and a loud refusal to estimate without a GPU (there is no CPU fallback)."""
 import pytest
 import torch
 
-from paper_2106_06998_amd.layer import XConv2d, XConv3d, convert_net
+from paper_2106_06998_amd.layer import SignReLU, XConv2d, XConv3d, convert_net
 
 
 def test_layer_is_a_conv2d_with_the_probing_arguments():
@@ -74,4 +74,17 @@ def test_volumetric_layer_and_its_conversion():
     assert n == 1 and isinstance(net[0], XConv3d) and type(net[1]) is torch.nn.Conv3d and type(net[2]) is torch.nn.Conv3d
     _, m = convert_net(torch.nn.Sequential(torch.nn.Conv3d(32, 8, 3, padding=1)), r=8, mode="multi")
     assert m == 0                                                       # volumetric layers take channel probes only
+
+
+def test_sign_relu_module_on_the_host():
+    m = SignReLU()
+    x = torch.tensor([-1.0, 0.0, 2.0])
+    assert torch.equal(m(x), torch.tensor([0.0, 0.0, 2.0]))                # no gradient needed: a plain ReLU
+    with pytest.raises(RuntimeError, match="GPU only"):
+        m(x.clone().requires_grad_(True))
+    net = torch.nn.Sequential(torch.nn.Conv2d(32, 8, 3), torch.nn.ReLU(), torch.nn.Sequential(torch.nn.ReLU(inplace=True)))
+    net, n = convert_net(net, r=8, relu=True)
+    assert n == 1 and isinstance(net[1], SignReLU) and isinstance(net[2][0], SignReLU)
+    net, n = convert_net(torch.nn.Sequential(torch.nn.Conv2d(32, 8, 3), torch.nn.ReLU()), r=8)
+    assert type(net[1]) is torch.nn.ReLU                                    # only on request
 
