@@ -323,6 +323,61 @@ def measure_pixel(cfg, steps, warmup, dev, with_cpu, indep=False):
                                           "plain C -O2, one thread" % cfg.name)
     return out, bwd_flops
 
+def measure_network(steps, warmup, dev, layers=12, B=128, C=64, HW=32, r=16):
+    """Forward + backward of a stack of 3x3 convolutions and ReLUs (the geometry of layer C2), with torch's layers
+    and with the layers swapped by convert_net: time per step, peak memory above the resident tensors, and the bytes
+    autograd keeps for the backward pass."""
+    import torch
+    from paper_2106_06998_amd.layer import convert_net
+
+    def build():
+        torch.manual_seed(11)
+        mods = []
+        for _ in range(layers):
+            mods += [torch.nn.Conv2d(C, C, 3, padding=1), torch.nn.ReLU()]
+        return torch.nn.Sequential(*mods).to(dev)
+
+    x = torch.randn(B, C, HW, HW, device=dev).relu_()
+    out = {}
+    for name, kw in (("torch", None), ("channel", dict(r=r, mode="channel", relu=True, probe="gaussian")),
+                     ("multi", dict(r=r, mode="multi", relu=True, probe="gaussian"))):
+        net = build()
+        if kw:
+            net, n = convert_net(net, **kw)
+            assert n == layers
+
+        def step():
+            net.zero_grad(set_to_none=True)
+            net(x).mean().backward()
+
+        seen, params = {}, {p.data_ptr() for p in net.parameters()}
+
+        def pack(t):
+            if t.data_ptr() not in params:
+                seen[t.data_ptr()] = t.numel() * t.element_size()
+            return t
+
+        with torch.autograd.graph.saved_tensors_hooks(pack, lambda t: t):
+            y = net(x)
+        y.mean().backward()
+        del y
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        base = torch.cuda.memory_allocated()
+        torch.cuda.reset_peak_memory_stats()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        out[name] = dict(ms_per_step=ms, peak_bytes_above_resident=torch.cuda.max_memory_allocated() - base,
+                         saved_bytes=sum(seen.values()))
+        del net
+    out["workload"] = "%d x [Conv2d(%d, %d, 3, padding=1) + ReLU], B=%d, %dx%d, fp32, r=%d Gaussian probes" % (layers, C, C, B, HW, HW, r)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -340,6 +395,8 @@ def main():
     ap.add_argument("--independent", action="store_true",
                     help="with --pixel-probe: independent probing (xconv_pixel_indep_*), r probing vectors per input channel")
     ap.add_argument("--r", type=int, default=0, help="with --pixel-probe: number of probing vectors instead of the layer's own")
+    ap.add_argument("--network", action="store_true",
+                    help="forward + backward of a stack of convolutions and ReLUs, torch's layers against XConv2d + SignReLU")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain device copy of 256 MiB ten times (reference reading for the FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -383,6 +440,16 @@ def main():
         torch.cuda.empty_cache()
         r2, _, _ = measure_volume("V2", max(args.steps // 2, 10), max(args.warmup // 2, 3), dev, False, not args.no_exact)
         line["per_config"] = [r2]
+        print(json.dumps(line))
+        return 0
+    if args.network:
+        res = measure_network(min(args.steps, 30), min(args.warmup, 5), dev)
+        line = {
+            "metric": "ms/step (forward + backward) of a convolution + ReLU stack with XConv2d (channel probes) and SignReLU, 1 GPU",
+            "value": res["channel"]["ms_per_step"], "unit": "ms", "n_gpus": 1, "steps": min(args.steps, 30), "warmup": min(args.warmup, 5),
+            "ms_per_step": res["channel"]["ms_per_step"], "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+            "dtype": "f32", "data": "synthetic", "config": {"workload": res.pop("workload")}, "detail": res,
+        }
         print(json.dumps(line))
         return 0
     if args.pixel_probe:
