@@ -323,7 +323,7 @@ def measure_pixel(cfg, steps, warmup, dev, with_cpu, indep=False):
                                           "plain C -O2, one thread" % cfg.name)
     return out, bwd_flops
 
-def measure_network(steps, warmup, dev, layers=12, B=128, C=64, HW=32, r=16):
+def measure_network(steps, warmup, dev, layers=12, B=128, C=64, HW=32, r=16, dtype="f32"):
     """Forward + backward of a stack of 3x3 convolutions and ReLUs (the geometry of layer C2), with torch's layers
     and with the layers swapped by convert_net: time per step, peak memory above the resident tensors, and the bytes
     autograd keeps for the backward pass."""
@@ -335,9 +335,10 @@ def measure_network(steps, warmup, dev, layers=12, B=128, C=64, HW=32, r=16):
         mods = []
         for _ in range(layers):
             mods += [torch.nn.Conv2d(C, C, 3, padding=1), torch.nn.ReLU()]
-        return torch.nn.Sequential(*mods).to(dev)
+        return torch.nn.Sequential(*mods).to(dev).to(td)
 
-    x = torch.randn(B, C, HW, HW, device=dev).relu_()
+    td = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[dtype]
+    x = torch.randn(B, C, HW, HW, device=dev).relu_().to(td)
     out = {}
     for name, kw in (("torch", None), ("channel", dict(r=r, mode="channel", relu=True, probe="gaussian")),
                      ("multi", dict(r=r, mode="multi", relu=True, probe="gaussian"))):
@@ -348,7 +349,7 @@ def measure_network(steps, warmup, dev, layers=12, B=128, C=64, HW=32, r=16):
 
         def step():
             net.zero_grad(set_to_none=True)
-            net(x).mean().backward()
+            net(x).float().mean().backward()
 
         seen, params = {}, {p.data_ptr() for p in net.parameters()}
 
@@ -359,7 +360,7 @@ def measure_network(steps, warmup, dev, layers=12, B=128, C=64, HW=32, r=16):
 
         with torch.autograd.graph.saved_tensors_hooks(pack, lambda t: t):
             y = net(x)
-        y.mean().backward()
+        y.float().mean().backward()
         del y
         for _ in range(warmup):
             step()
@@ -374,7 +375,7 @@ def measure_network(steps, warmup, dev, layers=12, B=128, C=64, HW=32, r=16):
         out[name] = dict(ms_per_step=ms, peak_bytes_above_resident=torch.cuda.max_memory_allocated() - base,
                          saved_bytes=sum(seen.values()))
         del net
-    out["workload"] = "%d x [Conv2d(%d, %d, 3, padding=1) + ReLU], B=%d, %dx%d, fp32, r=%d Gaussian probes" % (layers, C, C, B, HW, HW, r)
+    out["workload"] = "%d x [Conv2d(%d, %d, 3, padding=1) + ReLU], B=%d, %dx%d, %s, r=%d Gaussian probes" % (layers, C, C, B, HW, HW, dtype, r)
     return out
 
 
@@ -397,6 +398,7 @@ def main():
     ap.add_argument("--r", type=int, default=0, help="with --pixel-probe: number of probing vectors instead of the layer's own")
     ap.add_argument("--network", action="store_true",
                     help="forward + backward of a stack of convolutions and ReLUs, torch's layers against XConv2d + SignReLU")
+    ap.add_argument("--net-dtype", default="f32", choices=["f32", "bf16", "f16"], help="with --network: storage type of the stack")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain device copy of 256 MiB ten times (reference reading for the FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -443,12 +445,12 @@ def main():
         print(json.dumps(line))
         return 0
     if args.network:
-        res = measure_network(min(args.steps, 30), min(args.warmup, 5), dev)
+        res = measure_network(min(args.steps, 30), min(args.warmup, 5), dev, dtype=args.net_dtype)
         line = {
             "metric": "ms/step (forward + backward) of a convolution + ReLU stack with XConv2d (channel probes) and SignReLU, 1 GPU",
             "value": res["channel"]["ms_per_step"], "unit": "ms", "n_gpus": 1, "steps": min(args.steps, 30), "warmup": min(args.warmup, 5),
             "ms_per_step": res["channel"]["ms_per_step"], "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-            "dtype": "f32", "data": "synthetic", "config": {"workload": res.pop("workload")}, "detail": res,
+            "dtype": args.net_dtype, "data": "synthetic", "config": {"workload": res.pop("workload")}, "detail": res,
         }
         print(json.dumps(line))
         return 0
