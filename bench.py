@@ -258,7 +258,7 @@ def measure_pixel(cfg, steps, warmup, dev, with_cpu, indep=False):
     dw_estimate = xb.xconv_pixel_indep_dw_estimate if indep else xb.xconv_pixel_dw_estimate
     nvec = cfg.C_in * cfg.r if indep else cfg.r            # stored values per image
     if ws_bytes(d, xb.XCONV_OP_ESTIMATE) == 0:
-        raise SystemExit("bench.py: %s with r=%d is outside what this mode supports (independent probing: C_in*r <= 1024)" % (cfg.name, cfg.r))
+        raise SystemExit("bench.py: %s with r=%d is outside what this mode supports (independent probing: C_in*r <= 65536)" % (cfg.name, cfg.r))
     sets = []
     for _ in range(3):
         sets.append(dict(X=xb.to_device(X, cfg.dtype, dev), dY=xb.to_device(dY, cfg.dtype, dev),

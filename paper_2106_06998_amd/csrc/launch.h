@@ -31,10 +31,13 @@ hipError_t launch_unpack_slices(int dtype, const void *Xt, float *out, int B, in
 hipError_t launch_dy_slices(int dtype, const void *src, void *dst, int B, int C, int Do, int period, int n, int pitch, hipStream_t st);
 // probing vectors over pixels and channels as `nimg` images of K storage values (entry (k, j) = word k*r + j; images >= r zero);
 // cl_cs > 0: each image channels-last [pixel][cl_cs] (k = channel * pixels + pixel), zero columns C_in..cl_cs-1;
-// indep != 0: C_in*r vectors, vector n*r + j = column j of Z on the rows of channel n, zero elsewhere
+// indep != 0: nch*r vectors over the channel window [n0, n0+nch), vector nl*r + j = column j of Z on the rows of channel
+// n0+nl, zero elsewhere (n0 = 0, nch = C_in: all channels); with cl_cs > 0 the channel slots are the window's channels
 hipError_t launch_gen_zimg(int dtype, void *out, long long K, int r, int nimg, int dist, uint64_t seed, int C_in, int cl_cs,
-                           int indep, hipStream_t st);
+                           int indep, int n0, int nch, hipStream_t st);
 hipError_t launch_scale(const float *in, float *out, int n, float f, hipStream_t st);
+hipError_t launch_scale_cols(const float *in, float *out, int rows, int ld, int c0, int ncol, float f, hipStream_t st);
+hipError_t launch_scatter_channels(const float *part, float *dW, int C_out, int C_in, int K2, int n0, int nch, hipStream_t st);
 // ReLU that keeps one sign bit per element (64-bit words, bit i%64 of word i/64); Y may be X, dX may be dY
 hipError_t launch_relu_sign_fwd(int dtype, const void *X, void *Y, void *words, long long n, hipStream_t st);
 hipError_t launch_relu_sign_bwd(int dtype, const void *dY, const void *words, void *dX, long long n, hipStream_t st);

@@ -1028,34 +1028,36 @@ hipError_t launch_dy_slices(int dtype, const void *src, void *dst, int B, int C,
 // cl_cs == 0: image j holds its K values in row order (k fastest).  cl_cs > 0: channels-last,
 // value (n, q) of image j at (j * N + q) * cl_cs + n with zero columns C_in..cl_cs-1 (N = K / C_in
 // pixels), the form the correlation kernels read an activation in.
-// indep != 0: independent probing, C_in * r images; image n * r + j is probing vector j of channel n, the values
-// of column j of Z on the rows of channel n and zero on every other channel.
+// indep != 0: independent probing over the channel window [n0, n0 + nch): nch * r images; image nl * r + j is probing
+// vector j of channel n0 + nl, the values of column j of Z on the rows of that channel and zero on every other channel.
+// With cl_cs > 0 the cl_cs channel slots of an image are the channels of the window (slot = channel - n0).
 template <int DT>
 __global__ __launch_bounds__(kThreads) void gen_zimg_kernel(void *__restrict__ out, long long K, int r, int nimg, int dist,
-                                                            uint64_t seed, int C_in, int cl_cs, int indep)
+                                                            uint64_t seed, int C_in, int cl_cs, int indep, int n0, int nch)
 {
     const long long i = (long long)blockIdx.x * kThreads + threadIdx.x;
-    const int ncol = indep ? C_in * r : r;
+    const long long N = K / C_in;
+    const int ncol = indep ? nch * r : r;
     float z = 0.0f;
     int j;
-    long long k, n;
+    long long k, nl;   // nl: channel relative to the window
     if (cl_cs == 0) {
         if (i >= K * nimg) return;
         j = (int)(i / K);
         k = i - (long long)j * K;
-        n = k / (K / C_in);
+        nl = k / N - n0;
     } else {
-        const long long N = K / C_in;
         if (i >= N * nimg * cl_cs) return;
-        n = i % cl_cs;
+        nl = i % cl_cs;
         const long long jq = i / cl_cs;
         j = (int)(jq / N);
-        k = n * N + (jq - (long long)j * N);
+        k = (n0 + nl) * N + (jq - (long long)j * N);
     }
-    if (j < ncol && n < C_in) {
+    if (j < ncol && nl >= 0 && nl < nch) {
         const ProbeGen gen = probe_gen(dist, seed);
+        const long long n = n0 + nl;
         if (indep) {
-            if (j / r == n) z = probe_value(gen, (uint64_t)k * (uint64_t)r + (uint64_t)(j % r));
+            if (j / r == nl) z = probe_value(gen, (uint64_t)k * (uint64_t)r + (uint64_t)(j % r));
         } else if (probe_keep(gen, (uint64_t)n * (uint64_t)r + (uint64_t)j)) {
             z = probe_value(gen, (uint64_t)k * (uint64_t)r + (uint64_t)j);
         }
@@ -1064,17 +1066,19 @@ __global__ __launch_bounds__(kThreads) void gen_zimg_kernel(void *__restrict__ o
     else static_cast<uint16_t *>(out)[i] = f32_to_st16<DT>(z);
 }
 
+// n0, nch: channel window of the images (0, C_in for all channels); with cl_cs > 0 an image has cl_cs channel slots
+// for the channels n0 .. n0 + nch - 1 and N = K / C_in pixels
 hipError_t launch_gen_zimg(int dtype, void *out, long long K, int r, int nimg, int dist, uint64_t seed, int C_in, int cl_cs,
-                           int indep, hipStream_t st)
+                           int indep, int n0, int nch, hipStream_t st)
 {
     const long long total = cl_cs ? (K / C_in) * nimg * cl_cs : K * nimg;
     dim3 grid((unsigned)((total + kThreads - 1) / kThreads));
     if (dtype == XCONV_F32)
-        hipLaunchKernelGGL(gen_zimg_kernel<XCONV_F32>, grid, dim3(kThreads), 0, st, out, K, r, nimg, dist, seed, C_in, cl_cs, indep);
+        hipLaunchKernelGGL(gen_zimg_kernel<XCONV_F32>, grid, dim3(kThreads), 0, st, out, K, r, nimg, dist, seed, C_in, cl_cs, indep, n0, nch);
     else if (dtype == XCONV_BF16)
-        hipLaunchKernelGGL(gen_zimg_kernel<XCONV_BF16>, grid, dim3(kThreads), 0, st, out, K, r, nimg, dist, seed, C_in, cl_cs, indep);
+        hipLaunchKernelGGL(gen_zimg_kernel<XCONV_BF16>, grid, dim3(kThreads), 0, st, out, K, r, nimg, dist, seed, C_in, cl_cs, indep, n0, nch);
     else
-        hipLaunchKernelGGL(gen_zimg_kernel<XCONV_F16>, grid, dim3(kThreads), 0, st, out, K, r, nimg, dist, seed, C_in, cl_cs, indep);
+        hipLaunchKernelGGL(gen_zimg_kernel<XCONV_F16>, grid, dim3(kThreads), 0, st, out, K, r, nimg, dist, seed, C_in, cl_cs, indep, n0, nch);
     return hipGetLastError();
 }
 
@@ -1115,6 +1119,39 @@ __global__ __launch_bounds__(kThreads) void scale_kernel(const float *__restrict
 hipError_t launch_scale(const float *in, float *out, int n, float f, hipStream_t st)
 {
     hipLaunchKernelGGL(scale_kernel, dim3(ceil_div(n, kThreads)), dim3(kThreads), 0, st, in, out, n, f);
+    return hipGetLastError();
+}
+
+// out[b, c] = in[b, c0 + c] * f for c < ncol (rows of `ld` values in, of `ncol` values out)
+__global__ __launch_bounds__(kThreads) void scale_cols_kernel(const float *__restrict__ in, float *__restrict__ out, int rows, int ld,
+                                                              int c0, int ncol, float f)
+{
+    const int i = blockIdx.x * kThreads + threadIdx.x;
+    if (i >= rows * ncol) return;
+    const int b = i / ncol, c = i - b * ncol;
+    out[i] = in[(size_t)b * ld + c0 + c] * f;
+}
+
+hipError_t launch_scale_cols(const float *in, float *out, int rows, int ld, int c0, int ncol, float f, hipStream_t st)
+{
+    hipLaunchKernelGGL(scale_cols_kernel, dim3(ceil_div(rows * ncol, kThreads)), dim3(kThreads), 0, st, in, out, rows, ld, c0, ncol, f);
+    return hipGetLastError();
+}
+
+// dW[m, n0 + nl, o] = part[m, nl, o]: the gradient of a window of nch input channels into its place in [C_out, C_in, K2]
+__global__ __launch_bounds__(kThreads) void scatter_channels_kernel(const float *__restrict__ part, float *__restrict__ dW, int C_out,
+                                                                    int C_in, int K2, int n0, int nch)
+{
+    const int i = blockIdx.x * kThreads + threadIdx.x;
+    if (i >= C_out * nch * K2) return;
+    const int o = i % K2, nl = (i / K2) % nch, m = i / (K2 * nch);
+    dW[((size_t)m * C_in + n0 + nl) * K2 + o] = part[i];
+}
+
+hipError_t launch_scatter_channels(const float *part, float *dW, int C_out, int C_in, int K2, int n0, int nch, hipStream_t st)
+{
+    hipLaunchKernelGGL(scatter_channels_kernel, dim3(ceil_div(C_out * nch * K2, kThreads)), dim3(kThreads), 0, st, part, dW, C_out, C_in,
+                       K2, n0, nch);
     return hipGetLastError();
 }
 

@@ -703,12 +703,14 @@ namespace {
 
 struct PixelGeom {
     long long K, P;      // values per image of X and of dY
-    int R;               // probing vectors of the products: r, or C_in*r with independent probing
-    int CS;              // R rounded up to 16: images of L and of Z in the backward pass
+    int R;               // values of Xbar per image: r, or C_in*r with independent probing
+    int G;               // independent probing: input channels per pass of the backward products (else 0)
+    int Rb;              // probing vectors of one pass of the backward products: r, or G*r
+    int CS;              // Rb rounded up to 16: images of L and of Z in one pass
     xconv_desc fwd;      // 1x1 layer of the forward product
     xconv_desc probe;    // single-image channel probe of the backward pass (B channels)
     xconv_desc bwd;      // batch of CS images of the shifted product
-    size_t zimg_f, zimg_b, xs, lt, l, probe_ws;
+    size_t zimg_f, zimg_b, xs, lt, l, probe_ws, dwg, exact_ws;
     bool per_channel;    // independent probing, forward: one product per input channel from the r vectors of Z itself
     size_t zimg_c;       // ... and the bytes of those r vectors
 };
@@ -718,13 +720,22 @@ xconv_status pixel_geom(const xconv_desc *d, bool indep, PixelGeom &g)
     xconv_status s = xconv_check_desc(d);
     if (s != XCONV_OK) return s;
     if (d->probe == XCONV_USER_Z) return XCONV_EUNSUPPORTED;
-    if (indep && (d->keep_q15 != 0 || (long long)d->C_in * d->r > 1024)) return XCONV_EUNSUPPORTED;
+    if (indep && d->keep_q15 != 0) return XCONV_EUNSUPPORTED;
+    if ((long long)d->C_in * d->r > (1LL << 24)) return XCONV_EUNSUPPORTED;
     const int Ho = out_extent(d->H, d->kH, d->stride_h, d->pad_h), Wo = out_extent(d->W, d->kW, d->stride_w, d->pad_w);
     g.K = (long long)d->C_in * d->H * d->W;
     g.P = (long long)d->C_out * Ho * Wo;
     if (g.K > (1LL << 28) || g.P > (1LL << 28)) return XCONV_EUNSUPPORTED;
     g.R = indep ? d->C_in * d->r : d->r;
-    g.CS = round_up(g.R, 16);
+    // independent probing, backward: groups of up to 16 input channels (one block of channel slots of the shifted
+    // product) and at most 1024 probing vectors per pass
+    g.G = 0;
+    if (indep) {
+        g.G = 1024 / d->r < 16 ? 1024 / d->r : 16;
+        if (g.G > d->C_in) g.G = d->C_in;
+    }
+    g.Rb = indep ? g.G * d->r : d->r;
+    g.CS = round_up(g.Rb, 16);
     const size_t eb = elem_bytes(d->dtype);
     g.fwd = *d;
     g.fwd.B = 1; g.fwd.C_out = d->B; g.fwd.C_in = g.R; g.fwd.H = d->C_in * d->H; g.fwd.W = d->W;
@@ -733,17 +744,29 @@ xconv_status pixel_geom(const xconv_desc *d, bool indep, PixelGeom &g)
     // looks at the layout (of L, which inherits dY's)
     g.fwd.layout = XCONV_NCHW;
     g.probe = *d;
-    g.probe.B = 1; g.probe.C_in = d->B; g.probe.r = g.R; g.probe.probe = XCONV_USER_Z; g.probe.layout = XCONV_NCHW;
+    g.probe.B = 1; g.probe.C_in = d->B; g.probe.r = g.Rb; g.probe.probe = XCONV_USER_Z; g.probe.layout = XCONV_NCHW;
     g.bwd = *d;
     g.bwd.B = g.CS;
+    if (indep) g.bwd.C_in = g.G;
     if (xconv_check_desc(&g.fwd) != XCONV_OK || xconv_check_desc(&g.probe) != XCONV_OK || xconv_check_desc(&g.bwd) != XCONV_OK)
         return XCONV_EUNSUPPORTED;
     g.zimg_f = align_up((size_t)g.R * g.K * eb, 256);
-    g.zimg_b = align_up((size_t)g.CS * d->H * d->W * round_up(d->C_in, 16) * eb, 256);   // channels-last, padded channels
-    g.xs = align_up((size_t)d->B * g.R * sizeof(float), 256);
+    g.zimg_b = align_up((size_t)g.CS * d->H * d->W * round_up(g.bwd.C_in, 16) * eb, 256);   // channels-last, padded channels
+    g.xs = align_up((size_t)d->B * g.Rb * sizeof(float), 256);
     g.lt = align_up((size_t)g.P * g.CS * eb, 256);
     g.l = g.lt;
     g.probe_ws = z_bytes(&g.probe) + zfrag_bytes(&g.probe);
+    g.dwg = indep ? align_up((size_t)d->C_out * g.G * d->kH * d->kW * sizeof(float), 256) : 0;
+    g.exact_ws = xconv_workspace_bytes(&g.bwd, XCONV_OP_EXACT);
+    if (indep && d->C_in % g.G != 0) {
+        // the last pass has fewer channels: its shifted product may plan differently
+        xconv_desc last = g.bwd;
+        last.C_in = d->C_in % g.G;
+        last.B = round_up(last.C_in * d->r, 16);
+        const size_t w = xconv_workspace_bytes(&last, XCONV_OP_EXACT);
+        if (w == 0) g.exact_ws = 0;
+        else if (w > g.exact_ws) g.exact_ws = w;
+    }
     // rows of one channel are contiguous in NCHW only, and the product wants them in whole 16-byte vectors
     g.per_channel = indep && d->layout == XCONV_NCHW && pixel_fwd_ok(d->dtype, (long long)d->H * d->W, nullptr);
     g.zimg_c = align_up((size_t)d->r * g.K * eb, 256);
@@ -777,8 +800,7 @@ size_t pixel_workspace_bytes(const xconv_desc *d, bool indep, int op)
         return g.zimg_f + w > alt ? g.zimg_f + w : alt;
     }
     if (op == XCONV_OP_ESTIMATE) {
-        const size_t w = xconv_workspace_bytes(&g.bwd, XCONV_OP_EXACT);
-        return w ? g.zimg_b + g.xs + g.lt + g.l + align_up(g.probe_ws, 256) + w : 0;
+        return g.exact_ws ? g.zimg_b + g.xs + g.lt + g.l + align_up(g.probe_ws, 256) + g.dwg + g.exact_ws : 0;
     }
     return 0;
 }
@@ -798,14 +820,14 @@ xconv_status pixel_probe_fwd(const xconv_desc *d, bool indep, const void *X_dev,
     char *ws = static_cast<char *>(ws_dev);
     if (g.per_channel && pixel_fwd_ok(d->dtype, (long long)d->H * d->W, X_dev)) {
         // the r vectors of Z; channel n's product reads their rows of channel n
-        XC_LAUNCH(K_GEN_ZIMG, st, launch_gen_zimg(d->dtype, ws, g.K, d->r, d->r, probe_code(d), d->seed, d->C_in, 0, 0, st));
+        XC_LAUNCH(K_GEN_ZIMG, st, launch_gen_zimg(d->dtype, ws, g.K, d->r, d->r, probe_code(d), d->seed, d->C_in, 0, 0, 0, d->C_in, st));
         XC_LAUNCH(K_PIXEL_FWD, st, launch_pixel_fwd_indep(d->dtype, X_dev, ws, reinterpret_cast<float *>(ws + g.zimg_c), Xbar_dev,
                                                           (long long)d->H * d->W, d->C_in, d->B, d->r, st));
         return XCONV_OK;
     }
     // probing vectors as rows in the order X keeps its values in: (n, y, x), or (y, x, n) for channels-last
     XC_LAUNCH(K_GEN_ZIMG, st, launch_gen_zimg(d->dtype, ws, g.K, d->r, g.R, probe_code(d), d->seed, d->C_in,
-                                              d->layout == XCONV_NHWC ? d->C_in : 0, indep, st));
+                                              d->layout == XCONV_NHWC ? d->C_in : 0, indep, 0, d->C_in, st));
     if (pixel_fwd_ok(d->dtype, g.K, X_dev)) {
         XC_LAUNCH(K_PIXEL_FWD, st, launch_pixel_fwd(d->dtype, X_dev, ws, reinterpret_cast<float *>(ws + g.zimg_f), Xbar_dev, g.K, d->B,
                                                     g.R, st));
@@ -835,11 +857,36 @@ xconv_status pixel_dw_estimate(const xconv_desc *d, bool indep, const void *dY_d
     char *lt = ws + g.zimg_b + g.xs;
     char *l = lt + g.lt;
     char *pws = l + g.l;
-    char *xws = pws + align_up(g.probe_ws, 256);
+    float *dwg = reinterpret_cast<float *>(pws + align_up(g.probe_ws, 256));
+    char *xws = reinterpret_cast<char *>(dwg) + g.dwg;
+    const size_t xws_bytes = ws_bytes - (size_t)(xws - ws);
+    if (indep) {
+        // one pass per group of input channels: its probing vectors are block diagonal over the group's channels, which
+        // are the channel slots of the images the shifted product reads
+        const int K2 = d->kH * d->kW;
+        for (int n0 = 0; n0 < d->C_in; n0 += g.G) {
+            const int Gc = d->C_in - n0 < g.G ? d->C_in - n0 : g.G;
+            const int Rg = Gc * d->r, CSg = round_up(Rg, 16);
+            xconv_desc probe_g = g.probe, bwd_g = g.bwd;
+            probe_g.r = Rg;
+            bwd_g.B = CSg;
+            bwd_g.C_in = Gc;
+            XC_LAUNCH(K_GEN_ZIMG, st, launch_gen_zimg(d->dtype, zimg, g.K, d->r, CSg, probe_code(d), d->seed, d->C_in, 16, 1, n0, Gc, st));
+            XC_LAUNCH(K_SCALE, st, launch_scale_cols(Xbar_dev, xs, d->B, g.R, n0 * d->r, Rg, 1.0f / (float)d->r, st));
+            s = probe_impl(&probe_g, (int)g.P, (int)g.P, SliceMap{}, dY_dev, lt, xs, pws, g.probe_ws, st);
+            if (s != XCONV_OK) return s;
+            XC_LAUNCH(K_REPACK, st, launch_to_nchw(d->dtype, lt, l, 1, CSg, (int)g.P, (int)g.P, st));
+            const bool whole = Gc == d->C_in;
+            s = exact_impl(&bwd_g, l, nullptr, zimg, whole ? dW_dev : dwg, xws, xws_bytes, stream);
+            if (s != XCONV_OK) return s;
+            if (!whole) XC_LAUNCH(K_SCALE, st, launch_scatter_channels(dwg, dW_dev, d->C_out, d->C_in, K2, n0, Gc, st));
+        }
+        return XCONV_OK;
+    }
     // Z[s] again (Alg. 1 backward step 2), CS images, channels-last as the correlation reads an activation:
-    // the images past R are zero like the matching images of L
+    // the images past r are zero like the matching images of L
     XC_LAUNCH(K_GEN_ZIMG, st, launch_gen_zimg(d->dtype, zimg, g.K, d->r, g.CS, probe_code(d), d->seed, d->C_in, round_up(d->C_in, 16),
-                                              indep, st));
+                                              0, 0, d->C_in, st));
     XC_LAUNCH(K_SCALE, st, launch_scale(Xbar_dev, xs, d->B * g.R, 1.0f / (float)d->r, st));
     // Lt[p, j] = sum_b dY[b, p] Xbar[b, j] / r, rounded to the storage type (Alg. 1 backward step 3); p runs over
     // an image of dY in its own order, so the images of L come out in dY's layout
@@ -847,7 +894,7 @@ xconv_status pixel_dw_estimate(const xconv_desc *d, bool indep, const void *dY_d
     if (s != XCONV_OK) return s;
     XC_LAUNCH(K_REPACK, st, launch_to_nchw(d->dtype, lt, l, 1, g.CS, (int)g.P, (int)g.P, st));
     // dw_i = tr(L T_{-k(i)} Z) (Alg. 1 backward step 4; the factor 1/r is already in L)
-    s = exact_impl(&g.bwd, l, nullptr, zimg, dW_dev, xws, ws_bytes - (size_t)(xws - ws), stream);
+    s = exact_impl(&g.bwd, l, nullptr, zimg, dW_dev, xws, xws_bytes, stream);
     if (s != XCONV_OK || d->keep_q15 == 0) return s;
     // block-sparse probes: 1/nnz(Z_n) per input channel in place of the 1/r that L carries (Eq. (8))
     XC_LAUNCH(K_SCALE, st, launch_nnz_rescale(dW_dev, d->C_out, d->C_in, d->kH * d->kW, d->r, probe_code(d), d->seed, st));

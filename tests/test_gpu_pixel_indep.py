@@ -22,6 +22,10 @@ IND = [
     ("f32-one-channel", "f32", 7, 1, 6, 12, 12, 3, 1, 1, 16, "gaussian"),
     ("f16-1024-vectors", "f16", 40, 32, 16, 8, 8, 3, 1, 1, 32, "rademacher"),
     ("bf16-1x1", "bf16", 12, 8, 8, 8, 8, 1, 1, 0, 16, "rademacher"),
+    ("f32-2048-vectors", "f32", 6, 64, 8, 8, 8, 3, 1, 1, 32, "rademacher"),        # four groups of 16 channels
+    ("f16-ragged-groups", "f16", 5, 40, 12, 8, 8, 3, 1, 1, 4, "gaussian"),         # groups of 16, 16 and 8 channels
+    ("f32-wide-r-groups", "f32", 4, 20, 6, 6, 8, 3, 1, 1, 128, "rademacher"),       # r = 128: groups of 8, 8 and 4 channels
+    ("bf16-one-channel-groups", "bf16", 3, 3, 4, 8, 8, 3, 1, 1, 1024, "rademacher"),  # r = 1024: one channel per pass
 ]
 
 
@@ -84,7 +88,7 @@ def test_independent_probing_layers(e):
     run_indep(e)
 
 
-@pytest.mark.parametrize("e", [IND[0], IND[1], IND[2], IND[3]], ids=[e[0] for e in IND[:4]])
+@pytest.mark.parametrize("e", [IND[0], IND[1], IND[2], IND[3], IND[8]], ids=[e[0] for e in IND[:4]] + [IND[8][0]])
 def test_independent_probing_channels_last(e):
     run_indep(e, nhwc=True)
 
@@ -133,7 +137,7 @@ def test_independent_probing_has_no_crosstalk():
 
 
 def test_independent_probing_full_size_C2():
-    # the layer bench.py --pixel-probe --independent times by default (64 channels x 16 vectors = the 1024-vector limit),
+    # the layer bench.py --pixel-probe --independent times by default (64 channels x 16 vectors, four passes over groups of 16 channels),
     # every entry against the oracle
     cfg = synth.CONFIGS["C2"]
     run_indep(("C2", cfg.dtype, cfg.B, cfg.C_in, cfg.C_out, cfg.H, cfg.W, cfg.k, cfg.stride, cfg.pad, cfg.r, cfg.probe))
