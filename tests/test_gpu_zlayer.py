@@ -220,3 +220,25 @@ def test_converted_network_keeps_a_fraction_of_the_activations():
     small = saved_bytes(net, x)
     assert small <= 6 * act * (16 / 64 + 1 / 32) * 1.02, (plain, small)
 
+
+def test_converted_volumetric_network_runs_and_matches_the_plain_input_gradient():
+    # one Conv3d + ReLU block converted in place, on channels-last volumes: output, input gradient and bias gradient
+    # are those of the plain block (only the weight gradient is an estimate)
+    torch.manual_seed(9)
+    plain = torch.nn.Sequential(torch.nn.Conv3d(32, 16, 3, padding=1), torch.nn.ReLU()).to(DEV)
+    conv = torch.nn.Sequential(torch.nn.Conv3d(32, 16, 3, padding=1), torch.nn.ReLU()).to(DEV)
+    conv.load_state_dict(plain.state_dict())
+    conv, n = convert_net(conv, r=8, relu=True)
+    assert n == 1 and isinstance(conv[0], XConv3d) and isinstance(conv[1], SignReLU)
+    x = torch.randn(2, 32, 5, 8, 8, device=DEV).contiguous(memory_format=torch.channels_last_3d)
+    xa, xb_ = x.clone().requires_grad_(True), x.clone().requires_grad_(True)
+    g = torch.randn(2, 16, 5, 8, 8, device=DEV)
+    ya, yb = plain(xa), conv(xb_)
+    ya.backward(g)
+    yb.backward(g)
+    torch.cuda.synchronize()
+    assert torch.allclose(ya.detach(), yb.detach(), rtol=1e-4, atol=1e-5)
+    assert torch.allclose(xa.grad, xb_.grad, rtol=1e-3, atol=1e-3 * float(xa.grad.abs().max()))
+    assert torch.allclose(plain[0].bias.grad, conv[0].bias.grad, rtol=1e-3, atol=1e-4)
+    assert torch.isfinite(conv[0].weight.grad).all() and float(conv[0].weight.grad.abs().max()) > 0
+
