@@ -157,6 +157,19 @@ def measure_config(cfg, steps, warmup, dev, with_exact=False, nhwc=False):
         out["exact_ms"] = ms_x
         out["exact_gflops"] = alg["exact_flops"] / ms_x / 1e6
         out["estimate_vs_exact_speedup"] = ms_x / ms_step
+        # the framework's own exact weight gradient on the same tensors (MIOpen through torch), for context only
+        if not nhwc:
+            try:
+                import torch
+
+                def lib_dw(i):
+                    s = L.sets[i % len(L.sets)]
+                    torch.nn.grad.conv2d_weight(s["X"], (cfg.C_out, cfg.C_in, cfg.k, cfg.k), s["dY"], stride=cfg.stride, padding=cfg.pad)
+
+                out["torch_exact_dw_ms"] = time_region(lib_dw, max(steps // 4, 5), max(warmup // 4, 3))
+            except Exception as e:      # a missing or failing library kernel must not break the benchmark line
+                out["torch_exact_dw_ms"] = None
+                out["torch_exact_dw_error"] = str(e)[:200]
     return out, L
 
 
