@@ -336,7 +336,7 @@ def measure_pixel(cfg, steps, warmup, dev, with_cpu, indep=False):
                                           "plain C -O2, one thread" % cfg.name)
     return out, bwd_flops
 
-def measure_network(steps, warmup, dev, layers=12, B=128, C=64, HW=32, r=16, dtype="f32"):
+def measure_network(steps, warmup, dev, layers=12, B=128, C=64, HW=32, r=16, dtype="f32", probe="gaussian"):
     """Forward + backward of a stack of 3x3 convolutions and ReLUs (the geometry of layer C2), with torch's layers
     and with the layers swapped by convert_net: time per step, peak memory above the resident tensors, and the bytes
     autograd keeps for the backward pass."""
@@ -353,8 +353,8 @@ def measure_network(steps, warmup, dev, layers=12, B=128, C=64, HW=32, r=16, dty
     td = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[dtype]
     x = torch.randn(B, C, HW, HW, device=dev).relu_().to(td)
     out = {}
-    for name, kw in (("torch", None), ("channel", dict(r=r, mode="channel", relu=True, probe="gaussian")),
-                     ("multi", dict(r=r, mode="multi", relu=True, probe="gaussian"))):
+    for name, kw in (("torch", None), ("channel", dict(r=r, mode="channel", relu=True, probe=probe)),
+                     ("multi", dict(r=r, mode="multi", relu=True, probe=probe))):
         net = build()
         if kw:
             net, n = convert_net(net, **kw)
@@ -388,7 +388,7 @@ def measure_network(steps, warmup, dev, layers=12, B=128, C=64, HW=32, r=16, dty
         out[name] = dict(ms_per_step=ms, peak_bytes_above_resident=torch.cuda.max_memory_allocated() - base,
                          saved_bytes=sum(seen.values()))
         del net
-    out["workload"] = "%d x [Conv2d(%d, %d, 3, padding=1) + ReLU], B=%d, %dx%d, %s, r=%d Gaussian probes" % (layers, C, C, B, HW, HW, dtype, r)
+    out["workload"] = "%d x [Conv2d(%d, %d, 3, padding=1) + ReLU], B=%d, %dx%d, %s, r=%d %s probes" % (layers, C, C, B, HW, HW, dtype, r, probe)
     return out
 
 
@@ -411,6 +411,7 @@ def main():
     ap.add_argument("--r", type=int, default=0, help="with --pixel-probe: number of probing vectors instead of the layer's own")
     ap.add_argument("--network", action="store_true",
                     help="forward + backward of a stack of convolutions and ReLUs, torch's layers against XConv2d + SignReLU")
+    ap.add_argument("--net-probe", default="gaussian", choices=["gaussian", "rademacher"], help="with --network: probe distribution")
     ap.add_argument("--net-dtype", default="f32", choices=["f32", "bf16", "f16"], help="with --network: storage type of the stack")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain device copy of 256 MiB ten times (reference reading for the FETCH_SIZE/WRITE_SIZE counters)")
@@ -458,7 +459,7 @@ def main():
         print(json.dumps(line))
         return 0
     if args.network:
-        res = measure_network(min(args.steps, 30), min(args.warmup, 5), dev, dtype=args.net_dtype)
+        res = measure_network(min(args.steps, 30), min(args.warmup, 5), dev, dtype=args.net_dtype, probe=args.net_probe)
         line = {
             "metric": "ms/step (forward + backward) of a convolution + ReLU stack with XConv2d (channel probes) and SignReLU, 1 GPU",
             "value": res["channel"]["ms_per_step"], "unit": "ms", "n_gpus": 1, "steps": min(args.steps, 30), "warmup": min(args.warmup, 5),
