@@ -251,7 +251,7 @@ xconv_status xconv_pixel_dw_estimate(const xconv_desc *desc, const void *dY_dev,
  *
  * so no term mixes two input channels (no crosstalk), at C_in times the stored state:
  * Xbar is [B, C_in, r] floats, H*W/r times smaller than X in fp32.  The backward pass
- * runs in groups of up to 16 input channels, each as the multi-channel estimator with
+ * runs in groups of input channels (16 or more), each as the multi-channel estimator with
  * block-diagonal probing vectors over the group; limits as above and C_in*r <= 65536,
  * keep_q15 == 0 (else XCONV_EUNSUPPORTED). */
 size_t xconv_pixel_indep_xbar_bytes(const xconv_desc *desc);

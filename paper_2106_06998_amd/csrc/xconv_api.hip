@@ -727,11 +727,13 @@ xconv_status pixel_geom(const xconv_desc *d, bool indep, PixelGeom &g)
     g.P = (long long)d->C_out * Ho * Wo;
     if (g.K > (1LL << 28) || g.P > (1LL << 28)) return XCONV_EUNSUPPORTED;
     g.R = indep ? d->C_in * d->r : d->r;
-    // independent probing, backward: groups of up to 16 input channels (one block of channel slots of the shifted
-    // product) and at most 1024 probing vectors per pass
+    // independent probing, backward: groups of input channels, 16 (one block of channel slots of the shifted product)
+    // or, for few vectors per channel, as many as give a pass about 256 vectors (a pass has fixed costs); at most 1024
+    // probing vectors per pass
     g.G = 0;
     if (indep) {
-        g.G = 1024 / d->r < 16 ? 1024 / d->r : 16;
+        g.G = 256 / d->r > 16 ? 256 / d->r / 16 * 16 : 16;
+        if (g.G > 1024 / d->r) g.G = 1024 / d->r;
         if (g.G > d->C_in) g.G = d->C_in;
     }
     g.Rb = indep ? g.G * d->r : d->r;
@@ -862,7 +864,7 @@ xconv_status pixel_dw_estimate(const xconv_desc *d, bool indep, const void *dY_d
     const size_t xws_bytes = ws_bytes - (size_t)(xws - ws);
     if (indep) {
         // one pass per group of input channels: its probing vectors are block diagonal over the group's channels, which
-        // are the channel slots of the images the shifted product reads
+        // are the channel slots (a multiple of 16) of the images the shifted product reads
         const int K2 = d->kH * d->kW;
         for (int n0 = 0; n0 < d->C_in; n0 += g.G) {
             const int Gc = d->C_in - n0 < g.G ? d->C_in - n0 : g.G;
@@ -871,7 +873,7 @@ xconv_status pixel_dw_estimate(const xconv_desc *d, bool indep, const void *dY_d
             probe_g.r = Rg;
             bwd_g.B = CSg;
             bwd_g.C_in = Gc;
-            XC_LAUNCH(K_GEN_ZIMG, st, launch_gen_zimg(d->dtype, zimg, g.K, d->r, CSg, probe_code(d), d->seed, d->C_in, 16, 1, n0, Gc, st));
+            XC_LAUNCH(K_GEN_ZIMG, st, launch_gen_zimg(d->dtype, zimg, g.K, d->r, CSg, probe_code(d), d->seed, d->C_in, round_up(Gc, 16), 1, n0, Gc, st));
             XC_LAUNCH(K_SCALE, st, launch_scale_cols(Xbar_dev, xs, d->B, g.R, n0 * d->r, Rg, 1.0f / (float)d->r, st));
             s = probe_impl(&probe_g, (int)g.P, (int)g.P, SliceMap{}, dY_dev, lt, xs, pws, g.probe_ws, st);
             if (s != XCONV_OK) return s;

@@ -26,6 +26,8 @@ IND = [
     ("f16-ragged-groups", "f16", 5, 40, 12, 8, 8, 3, 1, 1, 4, "gaussian"),         # groups of 16, 16 and 8 channels
     ("f32-wide-r-groups", "f32", 4, 20, 6, 6, 8, 3, 1, 1, 128, "rademacher"),       # r = 128: groups of 8, 8 and 4 channels
     ("bf16-one-channel-groups", "bf16", 3, 3, 4, 8, 8, 3, 1, 1, 1024, "rademacher"),  # r = 1024: one channel per pass
+    ("f16-few-vectors-wide-groups", "f16", 4, 80, 8, 8, 8, 3, 1, 1, 4, "rademacher"),  # r = 4: groups of 64 and 16 channels
+    ("f32-two-vectors", "f32", 3, 150, 6, 6, 6, 3, 1, 1, 2, "gaussian"),               # r = 2: groups of 128 and 22 channels
 ]
 
 
