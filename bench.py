@@ -392,6 +392,58 @@ def measure_network(steps, warmup, dev, layers=12, B=128, C=64, HW=32, r=16, dty
     return out
 
 
+def measure_accuracy(cfg, dev, rs=(4, 8, 16, 32, 64), seeds=8):
+    """Relative error ||dW_est - dW_exact|| / ||dW_exact|| of one draw (root mean square over `seeds` draws) against
+    the number of probing vectors, for the three probing modes on one layer (the paper's gradient-error-against-r
+    experiment on synthetic tensors); the exact gradient is xconv_dw_exact."""
+    import dataclasses
+    import torch
+    from paper_2106_06998_amd import binding as xb
+    from paper_2106_06998_amd import synth
+    X, dY = synth.make_layer(cfg)
+    Xd, dYd = xb.to_device(X, cfg.dtype, dev), xb.to_device(dY, cfg.dtype, dev)
+    dW = torch.empty((cfg.C_out, cfg.C_in, cfg.k, cfg.k), dtype=torch.float32, device=dev)
+    d0 = xb.desc_from_config(cfg)
+    ex = torch.empty_like(dW)
+    xb.xconv_dw_exact(d0, dYd, Xd, ex, xb.alloc_ws(d0, xb.XCONV_OP_EXACT, dev))
+    ex = ex.double()
+    out = {"r": list(rs), "channel": [], "multi": [], "independent": [], "state_bytes": {"channel": [], "multi": [], "independent": []}}
+    for r in rs:
+        d = xb.desc_from_config(dataclasses.replace(cfg, r=r))
+        for mode in ("channel", "multi", "independent"):
+            if mode == "channel":
+                state = xb.alloc_xt(d, dev)
+                wsp, wse = xb.alloc_ws(d, xb.XCONV_OP_PROBE, dev), xb.alloc_ws(d, xb.XCONV_OP_ESTIMATE, dev)
+                nbytes = cfg.B * r * cfg.H * cfg.W * elem_bytes(cfg.dtype)
+            else:
+                ind = mode == "independent"
+                nbytes = (xb.xconv_pixel_indep_xbar_bytes if ind else xb.xconv_pixel_xbar_bytes)(d)
+                wsb = xb.xconv_pixel_indep_workspace_bytes if ind else xb.xconv_pixel_workspace_bytes
+                state = torch.empty(max(nbytes // 4, 1), dtype=torch.float32, device=dev)
+                wsp, wse = xb.alloc_bytes(wsb(d, xb.XCONV_OP_PROBE), dev), xb.alloc_bytes(wsb(d, xb.XCONV_OP_ESTIMATE), dev)
+            if nbytes == 0:
+                out[mode].append(None)
+                out["state_bytes"][mode].append(None)
+                continue
+            acc = 0.0
+            for s in range(seeds):
+                d.seed = 910000 + 97 * r + s
+                if mode == "channel":
+                    xb.xconv_probe_fwd(d, Xd, state, None, wsp)
+                    xb.xconv_dw_estimate(d, dYd, state, None, dW, wse)
+                elif mode == "multi":
+                    xb.xconv_pixel_probe_fwd(d, Xd, state, wsp)
+                    xb.xconv_pixel_dw_estimate(d, dYd, state, dW, wse)
+                else:
+                    xb.xconv_pixel_indep_probe_fwd(d, Xd, state, wsp)
+                    xb.xconv_pixel_indep_dw_estimate(d, dYd, state, dW, wse)
+                acc += float(((dW.double() - ex).norm() / ex.norm()) ** 2)
+            out[mode].append((acc / seeds) ** 0.5)
+            out["state_bytes"][mode].append(nbytes)
+    out["act_bytes"] = cfg.B * cfg.C_in * cfg.H * cfg.W * elem_bytes(cfg.dtype)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -409,6 +461,8 @@ def main():
     ap.add_argument("--independent", action="store_true",
                     help="with --pixel-probe: independent probing (xconv_pixel_indep_*), r probing vectors per input channel")
     ap.add_argument("--r", type=int, default=0, help="with --pixel-probe: number of probing vectors instead of the layer's own")
+    ap.add_argument("--accuracy", action="store_true",
+                    help="error of the dW estimate against the number of probing vectors for the three probing modes on --config")
     ap.add_argument("--network", action="store_true",
                     help="forward + backward of a stack of convolutions and ReLUs, torch's layers against XConv2d + SignReLU")
     ap.add_argument("--net-probe", default="gaussian", choices=["gaussian", "rademacher"], help="with --network: probe distribution")
@@ -456,6 +510,20 @@ def main():
         torch.cuda.empty_cache()
         r2, _, _ = measure_volume("V2", max(args.steps // 2, 10), max(args.warmup // 2, 3), dev, False, not args.no_exact)
         line["per_config"] = [r2]
+        print(json.dumps(line))
+        return 0
+    if args.accuracy:
+        cfg = synth.CONFIGS[args.config]
+        res = measure_accuracy(cfg, dev)
+        i16 = res["r"].index(16)
+        line = {
+            "metric": "relative error of one draw of the dW estimate at r=16 (channel probes), 1 GPU", "value": res["channel"][i16],
+            "unit": "relative L2 error", "n_gpus": 1, "steps": 8, "warmup": 0, "ms_per_step": None, "higher_is_better": False,
+            "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+            "config": {"workload": "%s: B=%d C_in=%d C_out=%d H=W=%d k=%d stride=%d pad=%d, %s probes, %s storage, r swept" % (
+                cfg.name, cfg.B, cfg.C_in, cfg.C_out, cfg.H, cfg.k, cfg.stride, cfg.pad, cfg.probe, cfg.dtype)},
+            "detail": res,
+        }
         print(json.dumps(line))
         return 0
     if args.network:
