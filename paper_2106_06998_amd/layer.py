@@ -28,19 +28,24 @@ def _pair(v):
     return (v, v) if isinstance(v, int) else tuple(v)
 
 
+def _aligned(t):
+    """The library takes 16-byte aligned tensors; a view into the middle of a storage may not be."""
+    return t if t.data_ptr() % 16 == 0 else t.clone(memory_format=torch.preserve_format)
+
+
 def _layout_of(x):
     """(layout code, tensor whose memory is in that layout)."""
     if x.is_contiguous():
-        return xb.XCONV_NCHW, x
+        return xb.XCONV_NCHW, _aligned(x)
     if x.is_contiguous(memory_format=torch.channels_last):
-        return xb.XCONV_NHWC, x
+        return xb.XCONV_NHWC, _aligned(x)
     return xb.XCONV_NCHW, x.contiguous()
 
 
 def _as_layout(t, layout):
     if layout == xb.XCONV_NHWC:
-        return t.contiguous(memory_format=torch.channels_last)
-    return t.contiguous()
+        return _aligned(t.contiguous(memory_format=torch.channels_last))
+    return _aligned(t.contiguous())
 
 
 class _XConvFunction(torch.autograd.Function):
@@ -152,6 +157,7 @@ class _SignReLUFunction(torch.autograd.Function):
         if not (xs.is_contiguous() or xs.is_contiguous(memory_format=torch.channels_last)
                 or (xs.dim() == 5 and xs.is_contiguous(memory_format=torch.channels_last_3d))):
             xs = xs.contiguous()
+        xs = _aligned(xs)
         y = torch.empty_like(xs)          # same strides as xs
         n = xs.numel()
         mask = torch.empty(max(xb.xconv_relu_mask_bytes(n) // 8, 1), dtype=torch.int64, device=x.device)
@@ -207,6 +213,7 @@ class _XConv3dFunction(torch.autograd.Function):
                 layout = xb.XCONV_NHWC
             else:
                 xs = xs.contiguous()
+        xs = _aligned(xs)
         B, C_in, D, H, W = x.shape
         v = xb.make_desc3d(B, C_in, weight.shape[0], D, H, W, tuple(weight.shape[2:]), stride, padding, r, _DTYPE[x.dtype], probe,
                            seed, 0, layout)
@@ -231,7 +238,7 @@ class _XConv3dFunction(torch.autograd.Function):
         if ctx.has_state and ctx.needs_input_grad[1]:
             state, v, dev = saved[1], ctx.desc, dy.device
             dys = dy.to(ctx.x_dtype)
-            dys = dys.contiguous(memory_format=torch.channels_last_3d) if ctx.layout == xb.XCONV_NHWC else dys.contiguous()
+            dys = _aligned(dys.contiguous(memory_format=torch.channels_last_3d) if ctx.layout == xb.XCONV_NHWC else dys.contiguous())
             dw32 = torch.empty(weight.shape, dtype=torch.float32, device=dev)
             with torch.cuda.device(dev):
                 xb.xconv3d_dw_estimate(v, dys, state, None, dw32, xb.alloc_bytes(xb.xconv3d_workspace_bytes(v, xb.XCONV_OP_ESTIMATE), dev))

@@ -242,3 +242,30 @@ def test_converted_volumetric_network_runs_and_matches_the_plain_input_gradient(
     assert torch.allclose(plain[0].bias.grad, conv[0].bias.grad, rtol=1e-3, atol=1e-4)
     assert torch.isfinite(conv[0].weight.grad).all() and float(conv[0].weight.grad.abs().max()) > 0
 
+
+def test_layers_take_views_that_start_in_the_middle_of_a_storage():
+    # views that start one fp16 value past the beginning of their storage: 2 bytes past a 16-byte boundary
+    torch.manual_seed(4)
+    x = torch.randn(1 + 2 * 32 * 5 * 5, device=DEV, dtype=torch.float16)[1:].view(2, 32, 5, 5)
+    assert x.data_ptr() % 16 != 0 and x.is_contiguous()
+    layer = XConv2d(32, 8, 3, r=8, padding=1).to(DEV).half()
+    xr = x.detach().clone().requires_grad_(True)
+    xv = x.detach().requires_grad_(True)
+    act = SignReLU()
+    g = torch.randn(1 + 2 * 8 * 5 * 5, device=DEV, dtype=torch.float16)[1:].view(2, 8, 5, 5)
+    assert g.data_ptr() % 16 != 0
+    y = layer(act(xv))
+    y.backward(g)
+    seed = layer.last_seed
+    w1 = layer.weight.grad.clone()
+    layer.zero_grad()
+    # the same call on aligned copies, with the probes of the first call
+    import paper_2106_06998_amd.layer as L
+    import itertools
+    L._calls = itertools.count(seed - layer.base_seed * 0x9E3779B1)
+    y2 = layer(act(xr))
+    y2.backward(g.clone())
+    torch.cuda.synchronize()
+    assert layer.last_seed == seed
+    assert torch.equal(y, y2) and torch.equal(w1, layer.weight.grad) and torch.equal(xv.grad, xr.grad)
+
