@@ -263,7 +263,7 @@ xconv_status xconv_pixel_indep_dw_estimate(const xconv_desc *desc, const void *d
 
 /* ---- ReLU that keeps signs only --------------------------------------------------
  * A ReLU in front of a convolution used to find its output stored by that convolution;
- * with the layers above the convolution keeps the probe output instead, so the ReLU
+ * with the entry points above, the convolution keeps the probe output instead, so the ReLU
  * keeps one bit per element (Sec. 5, "Overall effective memory savings").
  *
  *   forward   Y[i] = max(X[i], 0);  bit i%64 of the 64-bit word i/64 of mask = (X[i] > 0)
