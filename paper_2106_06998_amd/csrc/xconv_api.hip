@@ -770,7 +770,7 @@ xconv_status pixel_geom(const xconv_desc *d, bool indep, PixelGeom &g)
         else if (w > g.exact_ws) g.exact_ws = w;
     }
     // rows of one channel are contiguous in NCHW only, and the product wants them in whole 16-byte vectors
-    g.per_channel = indep && d->layout == XCONV_NCHW && pixel_fwd_ok(d->dtype, (long long)d->H * d->W, nullptr);
+    g.per_channel = indep && d->layout == XCONV_NCHW && d->C_in <= kMaxGridZ && pixel_fwd_ok(d->dtype, (long long)d->H * d->W, nullptr);   // (one grid row per channel)
     g.zimg_c = align_up((size_t)d->r * g.K * eb, 256);
     return XCONV_OK;
 }
