@@ -83,3 +83,27 @@ def test_captured_graph_replays_give_the_eager_result(e):
         torch.cuda.synchronize()
         assert torch.equal(L.dW, want), salt
         assert bool(torch.isfinite(L.dW).all())
+
+
+def test_two_layers_on_two_streams_at_once():
+    # the library keeps no state between calls: layers with buffers of their own, enqueued alternately on two
+    # streams, give what each gives alone
+    say("two streams at once")
+    a, b = Layer(LAYERS[0]), Layer(LAYERS[1])
+    a.step()
+    b.step()
+    torch.cuda.synchronize()
+    want_a, want_b = a.dW.clone(), b.dW.clone()
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    for rep in range(4):
+        a.dW.fill_(float("nan"))
+        b.dW.fill_(float("nan"))
+        torch.cuda.synchronize()
+        xb.xconv_probe_fwd(a.d, a.X, a.Xt, None, a.wsp, sa)
+        xb.xconv_probe_fwd(b.d, b.X, b.Xt, None, b.wsp, sb)
+        xb.xconv_dw_estimate(a.d, a.dY, a.Xt, None, a.dW, a.wse, sa)
+        xb.xconv_dw_estimate(b.d, b.dY, b.Xt, None, b.dW, b.wse, sb)
+        sa.synchronize()
+        sb.synchronize()
+        assert torch.equal(a.dW, want_a) and torch.equal(b.dW, want_b), rep
+
