@@ -324,3 +324,39 @@ def test_sign_relu_sizes_and_argument_checks():
     assert L.xconv_relu_bwd(1, one, None, one, 8, None) == xb.XCONV_EINVAL
     assert L.xconv_relu_bwd(2, one, one, one, (1 << 40) + 1, None) == xb.XCONV_EUNSUPPORTED
 
+
+def test_host_planning_is_thread_safe():
+    # size and plan queries from several threads at once (an autograd backward thread beside the forward thread)
+    # agree with the answers of one thread
+    import threading
+    rng = np.random.default_rng(99)
+    descs = []
+    while len(descs) < 64:
+        k = int(rng.integers(1, 6))
+        d = xb.make_desc(int(rng.integers(1, 64)), int(rng.integers(1, 200)), int(rng.integers(1, 200)), int(rng.integers(k, 60)),
+                         int(rng.integers(k, 60)), k, int(rng.integers(1, 3)), int(rng.integers(0, k)), int(rng.integers(1, 100)),
+                         ["f32", "bf16", "f16"][rng.integers(3)])
+        if xb.xconv_check_desc(d) == xb.XCONV_OK:
+            descs.append(d)
+
+    def answers(order):
+        out = {}
+        for i in order:
+            d = descs[i]
+            out[i] = (xb.xconv_xt_bytes(d), xb.xconv_workspace_bytes(d, xb.XCONV_OP_ESTIMATE), xb.xconv_workspace_bytes(d, xb.XCONV_OP_EXACT),
+                      tuple(sorted(xb.xconv_plan_info(d, xb.XCONV_OP_ESTIMATE).items())), xb.xconv_pixel_workspace_bytes(d, xb.XCONV_OP_ESTIMATE))
+        return out
+
+    results = [None] * 8
+
+    def work(t):
+        results[t] = answers(np.random.default_rng(t).permutation(len(descs)))
+
+    threads = [threading.Thread(target=work, args=(t,)) for t in range(8)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    want = answers(range(len(descs)))
+    assert all(r == want for r in results)
+
