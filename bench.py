@@ -173,22 +173,45 @@ def measure_config(cfg, steps, warmup, dev, with_exact=False, nhwc=False):
     return out, L
 
 
-def cpu_baseline(cfg, host, budget_s=12.0):
-    """The CPU oracle, as it stands, on the same layer (single thread)."""
+def host_cpu():
+    """(logical cores of the host, CPU model string), read at run time."""
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    return os.cpu_count() or 0, model
+
+
+def cpu_baseline(cfg, host, budget_s=15.0):
+    """The CPU oracle, as it stands (plain C, one thread), on a bounded sample of the same layer: the
+    first `Bs` images of the batch, `Bs` chosen from a one-image trial so that the sample takes about
+    `budget_s` seconds (the oracle's work is linear in the batch), the time scaled to the whole batch."""
     from oracle import xconv_oracle as xo
     X, dY = host
     Z = xo.probe_matrix({"rademacher": xo.RADEMACHER, "gaussian": xo.GAUSSIAN}[cfg.probe], cfg.seeds[2], cfg.C_in, cfg.r)
     dt = {"f32": xo.F32, "bf16": xo.BF16, "f16": xo.F16}[cfg.dtype]
     st, pd = (cfg.stride, cfg.stride), (cfg.pad, cfg.pad)
-    reps, t_total = 0, 0.0
-    while reps < 1 or (t_total < budget_s and reps < 16):
+
+    def run(nb):
         t0 = time.perf_counter()
-        Xt = xo.probe_fwd(X, Z, dt)
-        xo.dw_from_xt(dY, Xt, Z, cfg.k, cfg.k, st, pd)
-        t_total += time.perf_counter() - t0
-        reps += 1
-    return dict(value=t_total / reps * 1e3, unit="ms/layer", cores=1, kind="oracle",
-                sample="full %s layer (probe_fwd + dw_from_xt), %d repetition(s), plain C -O2, one thread" % (cfg.name, reps))
+        Xt = xo.probe_fwd(X[:nb], Z, dt)
+        xo.dw_from_xt(dY[:nb], Xt, Z, cfg.k, cfg.k, st, pd)
+        return time.perf_counter() - t0
+
+    t1 = run(1)
+    Bs = max(1, min(cfg.B, int(budget_s / max(t1, 1e-6))))
+    t = run(Bs)
+    ncores, model = host_cpu()
+    return dict(value=t * cfg.B / Bs * 1e3, unit="ms/layer", cores=1, kind="oracle", host_cores=ncores, host_cpu=model,
+                sample_seconds=t, sample_images=Bs,
+                sample="images 0..%d of the %d of layer %s (probe_fwd + dw_from_xt), one repetition of %.1f s, plain C -O2, one "
+                       "thread of the host's %d; value = that time scaled by %d/%d (the oracle's work is linear in the batch)" % (
+                           Bs - 1, cfg.B, cfg.name, t, ncores, cfg.B, Bs))
 
 
 # Volumetric layers (3x3x3 kernels on cubic patches, the regime of the paper's volumetric
@@ -317,7 +340,7 @@ def measure_pixel(cfg, steps, warmup, dev, with_cpu, indep=False):
         Z = xo.pixel_probe_matrix({"rademacher": xo.RADEMACHER, "gaussian": xo.GAUSSIAN}[cfg.probe], cfg.seeds[2], cfg.C_in, cfg.H,
                                   cfg.W, cfg.r)
         xbar = xo.pixel_indep_probe_fwd(X, Z)
-        xo.pixel_indep_dw_estimate(dY, xbar, Z, cfg.C_in, cfg.H, cfg.W, cfg.k, cfg.k, (cfg.stride, cfg.stride), (cfg.pad, cfg.pad), dt)
+        xo.pixel_indep_dw_estimate(dY, xbar, Z, cfg.C_in, cfg.H, cfg.W, cfg.k, cfg.k, (cfg.stride, cfg.stride), (cfg.pad, cfg.pad))
         t = time.perf_counter() - t0
         out["cpu_baseline"] = dict(value=t * 1e3, unit="ms/layer", cores=1, kind="oracle",
                                    sample="full %s layer (pixel_probe_matrix + pixel_indep_probe_fwd + pixel_indep_dw_estimate), "
@@ -329,7 +352,7 @@ def measure_pixel(cfg, steps, warmup, dev, with_cpu, indep=False):
         Z = xo.pixel_probe_matrix({"rademacher": xo.RADEMACHER, "gaussian": xo.GAUSSIAN}[cfg.probe], cfg.seeds[2], cfg.C_in, cfg.H,
                                   cfg.W, cfg.r)
         xbar = xo.pixel_probe_fwd(X, Z)
-        xo.pixel_dw_estimate(dY, xbar, Z, cfg.C_in, cfg.H, cfg.W, cfg.k, cfg.k, (cfg.stride, cfg.stride), (cfg.pad, cfg.pad), dt)
+        xo.pixel_dw_estimate(dY, xbar, Z, cfg.C_in, cfg.H, cfg.W, cfg.k, cfg.k, (cfg.stride, cfg.stride), (cfg.pad, cfg.pad))
         t = time.perf_counter() - t0
         out["cpu_baseline"] = dict(value=t * 1e3, unit="ms/layer", cores=1, kind="oracle",
                                    sample="full %s layer (pixel_probe_matrix + pixel_probe_fwd + pixel_dw_estimate), 1 repetition, "
@@ -444,13 +467,47 @@ def measure_accuracy(cfg, dev, rs=(4, 8, 16, 32, 64), seeds=8):
     return out
 
 
+def workload_string(cfg, nhwc):
+    return "%s: B=%d C_in=%d C_out=%d H=W=%d k=%d stride=%d pad=%d r=%d %s probes, %s storage, %s" % (
+        cfg.name, cfg.B, cfg.C_in, cfg.C_out, cfg.H, cfg.k, cfg.stride, cfg.pad, cfg.r, cfg.probe, cfg.dtype,
+        "NHWC" if nhwc else "NCHW")
+
+
+CORR_KERNEL_NAMES = {0: "corr_kernel", 1: "corr_ws_kernel", 2: "corr_ws32_kernel"}
+
+
+def roofline_of(cfg, res):
+    """Roofline object of the correlation launch (the dominant kernel of every layer): the matrix-core peak
+    of the storage type, or HBM when the layer's algorithmic bytes take longer at 8 TB/s than its flops at
+    that peak.  `achieved` = algorithmic flops (bytes) of the one launch / its event-timed duration."""
+    alg = algorithmic(cfg)
+    c = res["corr"]
+    kname = CORR_KERNEL_NAMES[res["plan"].get("ws", 0)]
+    mfma_bound = (alg["corr_flops"] / (PEAK_MFMA_TFLOPS[cfg.dtype] * 1e12)) >= (alg["corr_bytes"] / (PEAK_HBM_GBS * 1e9))
+    if mfma_bound:
+        ach = c["gflops"] / 1e3
+        roof = dict(bound="mfma", achieved=ach, peak=PEAK_MFMA_TFLOPS[cfg.dtype], unit="TFLOP/s", frac=ach / PEAK_MFMA_TFLOPS[cfg.dtype])
+    else:
+        roof = dict(bound="hbm", achieved=c["gbps"], peak=PEAK_HBM_GBS, unit="GB/s", frac=c["gbps"] / PEAK_HBM_GBS)
+    roof.update(kernel=kname, kernel_ms=c["ms"], traffic=MEASURED_TRAFFIC.get((cfg.name, kname)),
+                mfma_frac=c["mfma_frac"], hbm_frac=c["hbm_frac"])
+    return roof
+
+
+def probe_roofline_of(cfg, res):
+    p = res["probe"]
+    return dict(bound="hbm", achieved=p["gbps"], peak=PEAK_HBM_GBS, unit="GB/s", frac=p["hbm_frac"], kernel="probe_kernel",
+                kernel_ms=p["ms"], traffic=MEASURED_TRAFFIC.get((cfg.name, "probe_kernel")))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", default="C2", help="layer the headline value is quoted on (default: configs[1])")
-    ap.add_argument("--all", action="store_true", help="also measure the other benchmark layers (extra field per_config)")
+    ap.add_argument("--config", default="C5",
+                    help="layer the headline value is quoted on (default: C5, the largest layer, the one the roofline bars are stated on)")
+    ap.add_argument("--headline-only", action="store_true", help="do not measure the other four benchmark layers (field per_config)")
     ap.add_argument("--nhwc", action="store_true", help="hand X and dY over channels-last (layout XCONV_NHWC) instead of NCHW")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--no-exact", action="store_true", help="skip timing xconv_dw_exact (for clean per-kernel profiles)")
@@ -563,50 +620,32 @@ def main():
     cfg = synth.CONFIGS[args.config]
     res, L = measure_config(cfg, args.steps, args.warmup, dev, with_exact=not args.no_exact, nhwc=args.nhwc)
     alg = algorithmic(cfg)
-
-    # roofline of the dominant kernel of the step
-    dom = "corr" if res.get("corr", {}).get("ms", 0) >= res.get("probe", {}).get("ms", 0) else "probe"
-    if dom == "corr":
-        mfma_bound = (alg["corr_flops"] / (PEAK_MFMA_TFLOPS[cfg.dtype] * 1e12)) >= (alg["corr_bytes"] / (PEAK_HBM_GBS * 1e9))
-        if mfma_bound:
-            ach = res["corr"]["gflops"] / 1e3
-            roof = dict(bound="mfma", achieved=ach, peak=PEAK_MFMA_TFLOPS[cfg.dtype], unit="TFLOP/s",
-                        frac=ach / PEAK_MFMA_TFLOPS[cfg.dtype])
-        else:
-            ach = res["corr"]["gbps"]
-            roof = dict(bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS)
-        roof["kernel"] = {0: "corr_kernel", 1: "corr_ws_kernel", 2: "corr_ws32_kernel"}[res["plan"].get("ws", 0)]
-        roof["kernel_ms"] = res["corr"]["ms"]
-    else:
-        ach = res["probe"]["gbps"]
-        roof = dict(bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS,
-                    kernel="probe_kernel", kernel_ms=res["probe"]["ms"])
-    roof["traffic"] = MEASURED_TRAFFIC.get((cfg.name, roof["kernel"]))
-
     line = {
         "metric": "ms/layer for the XConv dW estimate (xconv_probe_fwd + xconv_dw_estimate), 1 GPU",
         "value": res["ms_per_layer"], "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": res["ms_per_layer"], "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": "%s: B=%d C_in=%d C_out=%d H=W=%d k=%d stride=%d pad=%d r=%d %s probes, %s storage, %s" % (
-            cfg.name, cfg.B, cfg.C_in, cfg.C_out, cfg.H, cfg.k, cfg.stride, cfg.pad, cfg.r, cfg.probe, cfg.dtype,
-            "NHWC" if args.nhwc else "NCHW")},
+        "config": {"workload": workload_string(cfg, args.nhwc)},
         "gbps": (alg["probe_bytes"] + alg["corr_bytes"]) / res["ms_per_layer"] / 1e6,
         "gflops": (alg["probe_flops"] + alg["corr_flops"]) / res["ms_per_layer"] / 1e6,
-        "roofline": roof,
+        "roofline": roofline_of(cfg, res),
+        "probe_roofline": probe_roofline_of(cfg, res),
         "detail": res,
     }
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(cfg, L.host)
     del L
-    if args.all:
+    if not args.headline_only:
         per = []
         for name, c in synth.CONFIGS.items():
             if name == cfg.name:
                 continue
             torch.cuda.empty_cache()
-            r, Lc = measure_config(c, max(args.steps // 2, 10), max(args.warmup // 2, 3), dev, with_exact=(name == "C5" and not args.no_exact))
+            r, Lc = measure_config(c, max(args.steps // 2, 10), max(args.warmup // 2, 3), dev, with_exact=False)
             del Lc
+            r["workload"] = workload_string(c, False)
+            r["roofline"] = roofline_of(c, r)
+            r["probe_roofline"] = probe_roofline_of(c, r)
             per.append(r)
         line["per_config"] = per
     print(json.dumps(line))

@@ -387,15 +387,15 @@ void xo_round_array(float *v, size_t n, int dtype)
 /* The estimator as the paper states it: probing vectors over the stacked     */
 /* pixel x channel space (Sec. 3 multi-channel case, Eq. (6); Algorithm 1).    */
 /* Z is [C_in*N, r] with row (n, q) = n*N + q (N = H*W pixels), entries in the */
-/* storage type (the products run in it).                                       */
-/*   forward   Xbar[b,j] = sum_{n,q} Z[(n,q),j] X[b,n,q]          (fp32 kept)   */
-/*   backward  L[j,m,p]  = (1/r) sum_b Xbar[b,j] dY[b,m,p], rounded once to     */
-/*                         the storage type (it is the operand of the shifted   */
-/*                         product that follows)                                 */
-/*             dw[m,n,ky,kx] = sum_j sum_{oy,ox} L[j,m,oy,ox]                    */
+/* storage type.  Algorithm 1 saves Xbar (and the seed) and nothing else, so   */
+/* Xbar is the only rounded quantity: L is a transient of the backward pass    */
+/* and stays in double, and the factor 1/r comes once, at the end of step 4.   */
+/*   forward   Xbar[b,j] = sum_{n,q} Z[(n,q),j] X[b,n,q]   (saved, fp32)        */
+/*   backward  L[j,m,p]  = sum_b Xbar[b,j] dY[b,m,p]             (bwd step 3)  */
+/*             dw[m,n,ky,kx] = (1/r) sum_j sum_{oy,ox} L[j,m,oy,ox]             */
 /*                                 * Z[(n, (oy*sh+ky-ph, ox*sw+kx-pw)), j]       */
-/* which is dw_i = (1/r) tr(L T_{-k(i)} Z) with zero padding in place of the    */
-/* circular shift.                                                               */
+/* which is dw_i = (1/r) tr(L T_{-k(i)} Z) (bwd step 4) with zero padding in   */
+/* place of the circular shift.                                                 */
 /* ------------------------------------------------------------------------- */
 void xo_pixel_probe_fwd(const float *X, const float *Z, float *Xbar, int B, int C_in, int H, int W, int r)
 {
@@ -410,21 +410,17 @@ void xo_pixel_probe_fwd(const float *X, const float *Z, float *Xbar, int B, int 
 
 void xo_pixel_dw_estimate(const float *dY, const float *Xbar, const float *Z, double *dW,
                           int B, int C_in, int C_out, int H, int W, int r,
-                          int kH, int kW, int sh, int sw, int ph, int pw, int dtype)
+                          int kH, int kW, int sh, int sw, int ph, int pw)
 {
     int Ho = xo_out_extent(H, kH, sh, ph);
     int Wo = xo_out_extent(W, kW, sw, pw);
     size_t P = (size_t)C_out * Ho * Wo, N = (size_t)H * W;
-    float *L = (float *)malloc((size_t)r * P * sizeof(float));
+    double *L = (double *)malloc((size_t)r * P * sizeof(double));
     for (int j = 0; j < r; ++j)
         for (size_t p = 0; p < P; ++p) {
             double s = 0.0;
-            for (int b = 0; b < B; ++b) {
-                /* the scaled coefficient Xbar / r is formed in single precision, as the stored state is */
-                float c = Xbar[(size_t)b * r + j] * (1.0f / (float)r);
-                s += (double)c * (double)dY[(size_t)b * P + p];
-            }
-            L[(size_t)j * P + p] = (float)xo_round_storage(s, dtype);
+            for (int b = 0; b < B; ++b) s += (double)Xbar[(size_t)b * r + j] * (double)dY[(size_t)b * P + p];
+            L[(size_t)j * P + p] = s;
         }
     for (int m = 0; m < C_out; ++m)
       for (int n = 0; n < C_in; ++n)
@@ -443,7 +439,7 @@ void xo_pixel_dw_estimate(const float *dY, const float *Xbar, const float *Z, do
                         s += l * z;
                     }
                 }
-              dW[(((size_t)m * C_in + n) * kH + ky) * kW + kx] = s;
+              dW[(((size_t)m * C_in + n) * kH + ky) * kW + kx] = s / (double)r;
           }
     free(L);
 }

@@ -75,7 +75,7 @@ def lib():
         L.xo_pixel_probe_fwd.restype = None
         L.xo_pixel_probe_fwd.argtypes = [_c_f32p, _c_f32p, _c_f32p] + [ctypes.c_int] * 5
         L.xo_pixel_dw_estimate.restype = None
-        L.xo_pixel_dw_estimate.argtypes = [_c_f32p, _c_f32p, _c_f32p, _c_f64p] + [ctypes.c_int] * 13
+        L.xo_pixel_dw_estimate.argtypes = [_c_f32p, _c_f32p, _c_f32p, _c_f64p] + [ctypes.c_int] * 12
         L.xo_conv_fwd.argtypes = [_c_f32p, _c_f64p, _c_f64p] + [ctypes.c_int] * 11
         _LIB = L
     return _LIB
@@ -342,8 +342,8 @@ def pixel_probe_fwd(X, Z):
     return Xbar
 
 
-def pixel_dw_estimate(dY, Xbar, Z, C_in, H, W, kH, kW, stride=(1, 1), pad=(0, 0), dtype=F32, nnz_norm=False):
-    """dw_i = (1/r) tr(L T_{-k(i)} Z), L = Xbar^T dY rounded to the storage type (Alg. 1 backward).
+def pixel_dw_estimate(dY, Xbar, Z, C_in, H, W, kH, kW, stride=(1, 1), pad=(0, 0), nnz_norm=False):
+    """dw_i = (1/r) tr(L T_{-k(i)} Z), L = Xbar^T dY (Alg. 1 backward steps 3 and 4; nothing but the saved Xbar is rounded).
     nnz_norm: the estimate of input channel n is scaled by 1 / nnz(Z_n) instead of 1 / r (Eq. (8)); a channel
     without any block gives zeros."""
     dY, dYp = _f32(dY)
@@ -355,7 +355,7 @@ def pixel_dw_estimate(dY, Xbar, Z, C_in, H, W, kH, kW, stride=(1, 1), pad=(0, 0)
     assert Ho == out_extent(H, kH, stride[0], pad[0]) and Wo == out_extent(W, kW, stride[1], pad[1])
     dW = np.empty((C_out, C_in, kH, kW), dtype=np.float64)
     lib().xo_pixel_dw_estimate(dYp, Xbp, Zp, dW.ctypes.data_as(_c_f64p), B, C_in, C_out, H, W, r,
-                               kH, kW, stride[0], stride[1], pad[0], pad[1], dtype)
+                               kH, kW, stride[0], stride[1], pad[0], pad[1])
     if nnz_norm:
         nnz = pixel_block_counts(Z, C_in)
         dW *= np.where(nnz > 0, r / np.maximum(nnz, 1), 0.0).reshape(1, C_in, 1, 1)
@@ -377,7 +377,7 @@ def pixel_indep_probe_fwd(X, Z):
     return Xbar
 
 
-def pixel_indep_dw_estimate(dY, Xbar, Z, C_in, H, W, kH, kW, stride=(1, 1), pad=(0, 0), dtype=F32):
+def pixel_indep_dw_estimate(dY, Xbar, Z, C_in, H, W, kH, kW, stride=(1, 1), pad=(0, 0)):
     """Independent probing, backward: the trace estimate of every (input, output) channel pair uses the
     probes of its own input channel only, so column n of dW is the single-channel estimate (Alg. 1
     backward with C_in = 1) from Xbar[:, n] and Z_n; no term mixes two input channels."""
@@ -388,7 +388,7 @@ def pixel_indep_dw_estimate(dY, Xbar, Z, C_in, H, W, kH, kW, stride=(1, 1), pad=
     assert Xbar.shape[1] == C_in and Z.shape[0] == C_in * N
     dW = np.empty((C_out, C_in, kH, kW), dtype=np.float64)
     for n in range(C_in):
-        dW[:, n:n + 1] = pixel_dw_estimate(dY, Xbar[:, n, :], Z[n * N:(n + 1) * N], 1, H, W, kH, kW, stride, pad, dtype)
+        dW[:, n:n + 1] = pixel_dw_estimate(dY, Xbar[:, n, :], Z[n * N:(n + 1) * N], 1, H, W, kH, kW, stride, pad)
     return dW
 
 

@@ -30,6 +30,15 @@ __global__ __launch_bounds__(kThreads) void gen_z_kernel(float *__restrict__ Z, 
     Z[i] = probe_entry(probe_gen(dist, seed), (uint64_t)i);
 }
 
+// Workgroups are handed to the chip's 8 dies in turn (workgroup b runs on die b % 8, each with an L2 of
+// its own).  With a grid that is a multiple of 8 this gives the workgroups of one die neighbouring
+// tiles, so that a cache line which straddles two tiles (planes are not line-aligned) is fetched
+// from memory once, by one L2, instead of once by each of two.
+__device__ inline int xcd_block(int b, int grid)
+{
+    return (grid & 7) == 0 ? (b & 7) * (grid >> 3) + (b >> 3) : b;
+}
+
 // Row i of MFMA tile jt holds probe column j0 + jmap: lane group g = i/4 then
 // owns the 4*JT consecutive columns g*4*JT .. (g+1)*4*JT-1 of the 16*JT block.
 __device__ inline int jmap(int jt, int i, int JT) { return (i >> 2) * (4 * JT) + jt * 4 + (i & 3); }
@@ -192,7 +201,7 @@ __global__ __launch_bounds__(kThreads, (JT == 1 ? 4 : 2)) void probe_f32_kernel(
     };
 
     // The first tile's loads are in flight while the Z fragments are staged.
-    int tile = blockIdx.x * 4 + wave;
+    int tile = xcd_block(blockIdx.x, gridDim.x) * 4 + wave;
     const int tile_step = gridDim.x * 4;
     Tile cur;
     Staged rg[D];
@@ -396,7 +405,7 @@ __global__ __launch_bounds__(kThreads, 2) void probe_16_kernel(const uint16_t *_
     };
 
     // The first tile's loads are in flight while the Z fragments are staged.
-    int tile = blockIdx.x * 4 + wave;
+    int tile = xcd_block(blockIdx.x, gridDim.x) * 4 + wave;
     const int tile_step = gridDim.x * 4;
     Tile cur;
     Staged rg[D];
@@ -642,12 +651,16 @@ template <typename K> static hipError_t set_lds(K kernel, size_t bytes)
     return hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
 
-static int probe_grid(int ntiles)
+// 4 tiles (one per wave) per workgroup pass.  The grid is what is resident at once (256 compute
+// units x `wgs_per_cu`) or less, sized so that every workgroup makes the same number of passes: a
+// grid of 784 on 512 slots would run a second round that is half empty, 392 workgroups of two
+// passes each keep the whole chip loading until the end.  Rounded up to a multiple of 8 (see xcd_block).
+static int probe_grid(int ntiles, int wgs_per_cu)
 {
-    // 4 tiles (one per wave) per workgroup pass; cap the grid so that the
-    // per-workgroup Z staging is amortised over several tiles on large inputs.
     const int want = ceil_div(ntiles, 4);
-    return want < 2048 ? want : 2048;
+    const int slots = 256 * wgs_per_cu;
+    const int rounds = ceil_div(want, slots);
+    return round_up(ceil_div(want, rounds), 8);
 }
 
 template <int JT, bool NHWC>
@@ -660,7 +673,7 @@ static hipError_t launch_probe_f32_jt(const float *X, const float *Z, const floa
     const size_t lds = (size_t)ceil_div(C_in, 16) * 4 * JT * 64 * sizeof(float);
     hipError_t e = set_lds(probe_f32_kernel<JT, NHWC>, lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((probe_f32_kernel<JT, NHWC>), dim3(probe_grid(ntiles)), dim3(kThreads), lds, st, X, Z, zpack, Xt, C_in, HW, r,
+    hipLaunchKernelGGL((probe_f32_kernel<JT, NHWC>), dim3(probe_grid(ntiles, JT == 1 ? 4 : 2)), dim3(kThreads), lds, st, X, Z, zpack, Xt, C_in, HW, r,
                        CS, j0, ngroups, ntiles, sm, dist, seed);
     return hipGetLastError();
 }
@@ -674,7 +687,7 @@ static hipError_t launch_probe_16_cfg(const uint16_t *X, const float *Z, const u
     const size_t lds = (size_t)(SPLIT ? 2 : 1) * ceil_div(C_in, 32) * JT * 64 * sizeof(uint4);
     hipError_t e = set_lds(probe_16_kernel<DT, JT, PT, SPLIT, NHWC>, lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((probe_16_kernel<DT, JT, PT, SPLIT, NHWC>), dim3(probe_grid(ntiles)), dim3(kThreads), lds, st, X, Z, zpack,
+    hipLaunchKernelGGL((probe_16_kernel<DT, JT, PT, SPLIT, NHWC>), dim3(probe_grid(ntiles, 2)), dim3(kThreads), lds, st, X, Z, zpack,
                        Xt, C_in, HW, r, CS, j0, ngroups, ntiles, sm, dist, seed);
     return hipGetLastError();
 }

@@ -2,8 +2,11 @@
 // the optional per-kernel event timing.  Declarations and their contracts are
 // in include/xconv.h.
 #include <cstdlib>
+#include <cstring>
 #include <mutex>
 #include <vector>
+
+extern char **environ;
 
 #include "common.h"
 #include "launch.h"
@@ -78,10 +81,23 @@ struct PlanEntry {
 std::mutex g_plan_mu;
 std::vector<PlanEntry> g_plans;
 
+// The plan functions read XCONV_* overrides from the environment, so the overrides in force are part of
+// the cache key: a plan made under one setting is never handed out under another.
+int plan_override_hash()
+{
+    uint32_t h = 2166136261u;
+    for (char **e = environ; e && *e; ++e) {
+        if (strncmp(*e, "XCONV_", 6) != 0) continue;
+        for (const char *c = *e; *c; ++c) h = (h ^ (uint8_t)*c) * 16777619u;
+        h = (h ^ 0xffu) * 16777619u;
+    }
+    return (int)h;
+}
+
 bool get_plan(PlanEntry &out, int dtype, int B, int C_out, int H, int W, int kH, int kW, int sh, int sw, int ph, int pw, int CS,
               bool dy_aligned)
 {
-    PlanKey k{{dtype, B, C_out, H, W, kH, kW, sh, sw, ph, pw, CS, dy_aligned ? 1 : 0, 0}};
+    PlanKey k{{dtype, B, C_out, H, W, kH, kW, sh, sw, ph, pw, CS, dy_aligned ? 1 : 0, plan_override_hash()}};
     {
         std::lock_guard<std::mutex> lk(g_plan_mu);
         for (const PlanEntry &e : g_plans)

@@ -449,48 +449,41 @@ def test_estimate_is_deterministic_and_overwrites():
 # ---------------------------------------------------------------------------
 # the five layers at full size, in the launch configuration the bench times
 # ---------------------------------------------------------------------------
-@pytest.mark.parametrize("name", ["C1", "C2"])
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
 def test_full_size_complete(name):
-    full_parity(synth.CONFIGS[name], seed_path=True, check_exact=(name == "C1"))
+    # Every entry of the stored probe output and of the estimate against the oracle, Z drawn from the seed on both
+    # sides, in the launch configuration the bench times (the oracle needs about half a minute for the largest layer).
+    full_parity(synth.CONFIGS[name], seed_path=True, check_exact=(name in ("C1", "C2")))
 
 
 @pytest.mark.parametrize("name", ["C3", "C4", "C5"])
-def test_full_size_sampled(name):
-    # The oracle computes the probe output in full and the gradient at sampled
-    # entries (each one a sum over all B*H'*W' pixels and all r probes).
+def test_full_size_exact_rows(name):
+    # Exact gradient at full size: whole rows dW[m, :, :, :] for one output channel out of every 16, so that every
+    # (output-channel tile x input-channel block x kernel offset) of the running plan is compared, a sixteenth of all
+    # entries.  The estimate must also equal those oracle rows mixed by Z Z^T / r (holds at any size).
     cfg = synth.CONFIGS[name]
-    say("%s full size, sampled entries" % name)
+    say("%s full size, exact gradient, one output channel in 16" % name)
     X, dY = synth.make_layer(cfg)
     Z = xo.probe_matrix(OPROBE[cfg.probe], cfg.seeds[2], cfg.C_in, cfg.r)
     st, pd = (cfg.stride, cfg.stride), (cfg.pad, cfg.pad)
-    d, Xt, Xt_g = run_probe(cfg, X, None, seed_path=True)
-    got = run_estimate(cfg, d, dY, Xt, None)
-    got_x = run_exact(cfg, d, dY, X) if name == "C5" else None
-    assert np.all(np.isfinite(got))
-    say("%s oracle probe" % name)
-    Xt_o = xo.probe_fwd(X, Z, ODT[cfg.dtype])
-    check_probe_output(cfg, Xt_g, Xt_o)
+    d = xb.desc_from_config(cfg)
+    got_x = run_exact(cfg, d, dY, X)
+    assert np.all(np.isfinite(got_x))
     rng = np.random.default_rng(5)
-    n = 48
-    idx = np.stack([rng.integers(0, cfg.C_out, n), rng.integers(0, cfg.C_in, n),
-                    rng.integers(0, cfg.k, n), rng.integers(0, cfg.k, n)], axis=1).astype(np.int32)
-    idx[0] = (0, 0, 0, 0)
-    idx[1] = (cfg.C_out - 1, cfg.C_in - 1, cfg.k - 1, cfg.k - 1)
-    say("%s oracle samples" % name)
-    want = xo.dw_from_xt_at(dY, Xt_o, Z, idx, cfg.k, cfg.k, st, pd)
-    g = np.array([got[tuple(i)] for i in idx])
-    scale = np.max(np.abs(got))          # the largest entry of the full result bounds the oracle's largest sampled one
-    assert np.max(np.abs(want)) <= 1.05 * scale
-    assert np.max(np.abs(g - want)) <= GRAD_TOL[cfg.dtype] * np.max(np.abs(want)), (np.max(np.abs(g - want)), np.max(np.abs(want)))
-    if got_x is not None:
-        wx = xo.dw_exact_at(dY, X, idx, cfg.k, cfg.k, st, pd)
-        gx = np.array([got_x[tuple(i)] for i in idx])
-        assert np.max(np.abs(gx - wx)) <= GRAD_TOL[cfg.dtype] * np.max(np.abs(wx))
-    # property that holds at any size: the estimate is the exact gradient mixed by Z Z^T / r
-    if got_x is not None:
-        G = Z.astype(np.float64) @ Z.astype(np.float64).T / cfg.r
-        mixed = np.einsum("nq,mqyx->mnyx", G, got_x)
-        assert rel_max(got, mixed) <= 2 * GRAD_TOL[cfg.dtype]
+    rows = np.array([16 * t + int(rng.integers(0, 16)) for t in range(cfg.C_out // 16)])
+    rows[0], rows[-1] = 0, cfg.C_out - 1
+    idx = np.array([(m, n, ky, kx) for m in rows for n in range(cfg.C_in) for ky in range(cfg.k) for kx in range(cfg.k)], dtype=np.int32)
+    say("%s oracle rows (%d entries)" % (name, len(idx)))
+    wx = xo.dw_exact_at(dY, X, idx, cfg.k, cfg.k, st, pd).reshape(len(rows), cfg.C_in, cfg.k, cfg.k)
+    gx = got_x[rows]
+    scale = np.max(np.abs(wx))
+    assert np.max(np.abs(got_x)) <= 1.5 * scale          # no stray large entry in the rows that are not compared
+    assert np.max(np.abs(gx - wx)) <= GRAD_TOL[cfg.dtype] * scale, (np.max(np.abs(gx - wx)), scale)
+    _, Xt, _ = run_probe(cfg, X, None, seed_path=True)
+    got = run_estimate(cfg, d, dY, Xt, None)
+    G = Z.astype(np.float64) @ Z.astype(np.float64).T / cfg.r
+    mixed = np.einsum("nq,mqyx->mnyx", G, wx)
+    assert np.max(np.abs(got[rows] - mixed)) <= 2 * GRAD_TOL[cfg.dtype] * np.max(np.abs(mixed))
 
 
 def test_byte_offsets_beyond_4_gib():

@@ -75,7 +75,7 @@ def run_indep(e, nhwc=False):
     got_xbar = xbar.cpu().numpy()
     assert np.max(np.abs(got_xbar - want_xbar)) <= 1e-5 * np.max(np.abs(want_xbar)), rel_max(got_xbar, want_xbar)
     # backward from the oracle's projections, so that both sides start from the same stored state
-    want = xo.pixel_indep_dw_estimate(dY, want_xbar, Z, C_in, H, W, k, k, (st, st), (pad, pad), ODT[dtype])
+    want = xo.pixel_indep_dw_estimate(dY, want_xbar, Z, C_in, H, W, k, k, (st, st), (pad, pad))
     got = gpu_bwd(d, dYd, torch.from_numpy(want_xbar).to(DEV), (C_out, C_in, k, k))
     assert np.all(np.isfinite(got))
     err = rel_max(got, want)

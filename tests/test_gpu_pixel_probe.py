@@ -62,7 +62,7 @@ def run_pixel(e, nhwc=False):
     got_xbar = xbar.cpu().numpy()
     assert np.max(np.abs(got_xbar - want_xbar)) <= 1e-5 * np.max(np.abs(want_xbar)), rel_max(got_xbar, want_xbar)
     # backward from the oracle's projections, so that both sides start from the same stored state
-    want = xo.pixel_dw_estimate(dY, want_xbar, Z, C_in, H, W, k, k, (st, st), (pad, pad), ODT[dtype], nnz_norm=keep != 0)
+    want = xo.pixel_dw_estimate(dY, want_xbar, Z, C_in, H, W, k, k, (st, st), (pad, pad), nnz_norm=keep != 0)
     dW = torch.full((C_out, C_in, k, k), float("nan"), dtype=torch.float32, device=DEV)
     ws2 = xb.alloc_bytes(xb.xconv_pixel_workspace_bytes(d, xb.XCONV_OP_ESTIMATE), DEV)
     ws2.fill_(0x7f)

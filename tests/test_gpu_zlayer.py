@@ -32,8 +32,8 @@ def oracle_dw(mode, X, dY, seed, C_in, H, W, k, st, pad, r, probe, dtype):
         return xo.dw_from_xt(dY, xo.probe_fwd(X, Z, ODT[dtype]), Z, k, k, (st, st), (pad, pad))
     Z = xo.pixel_probe_matrix(OPROBE[probe], seed, C_in, H, W, r, ODT[dtype])
     if mode == "multi":
-        return xo.pixel_dw_estimate(dY, xo.pixel_probe_fwd(X, Z), Z, C_in, H, W, k, k, (st, st), (pad, pad), ODT[dtype])
-    return xo.pixel_indep_dw_estimate(dY, xo.pixel_indep_probe_fwd(X, Z), Z, C_in, H, W, k, k, (st, st), (pad, pad), ODT[dtype])
+        return xo.pixel_dw_estimate(dY, xo.pixel_probe_fwd(X, Z), Z, C_in, H, W, k, k, (st, st), (pad, pad))
+    return xo.pixel_indep_dw_estimate(dY, xo.pixel_indep_probe_fwd(X, Z), Z, C_in, H, W, k, k, (st, st), (pad, pad))
 
 
 @pytest.mark.parametrize("e", CASES, ids=["%s-%s%s" % (e[0], e[11], "-cl" if e[12] else "") for e in CASES])
