@@ -473,7 +473,7 @@ def workload_string(cfg, nhwc):
         "NHWC" if nhwc else "NCHW")
 
 
-CORR_KERNEL_NAMES = {0: "corr_kernel", 1: "corr_ws_kernel", 2: "corr_ws32_kernel"}
+CORR_KERNEL_NAMES = {0: "corr_kernel", 1: "corr_ws_kernel", 2: "corr_ws32_kernel", 3: "corr_row_kernel"}
 
 
 def roofline_of(cfg, res):

@@ -80,6 +80,12 @@ bool plan_corr_ws(WsParams &P, int dtype, int B, int C_out, int H, int W, int kH
 size_t corr_ws_lds_bytes(const WsParams &P);
 hipError_t launch_corr_ws(int dtype, const WsParams &P, hipStream_t st);
 
+// corr_row_kernels.hip: producer/consumer kernel for 16-bit storage, 3x3 kernels at unit stride and short output rows
+// (a multiple of 4 columns, as many as the ring of staged rows leaves room for in LDS: 28 with 64 probe columns) that a workgroup sweeps whole; plan_corr_row returns false for everything else
+bool plan_corr_row(WsParams &P, int dtype, int B, int C_out, int H, int W, int kH, int kW, int sh, int sw, int ph, int pw, int CS);
+size_t corr_row_lds_bytes(const WsParams &P);
+hipError_t launch_corr_row(int dtype, const WsParams &P, hipStream_t st);
+
 // corr_ws32_kernels.hip: the producer/consumer kernel for fp32 storage (same plan structure)
 bool plan_corr_ws32(WsParams &P, int dtype, int B, int C_out, int H, int W, int kH, int kW, int sh, int sw, int ph, int pw, int CS);
 size_t corr_ws32_lds_bytes(const WsParams &P);

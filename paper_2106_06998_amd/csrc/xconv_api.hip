@@ -74,7 +74,7 @@ struct PlanKey {
 struct PlanEntry {
     PlanKey key;
     CorrParams P;   // launch plan of corr_kernel; with `ws` only the fields the reduction and expansion read
-    WsParams Wp;    // launch plan of corr_ws_kernel (ws == 1, 16-bit storage) or corr_ws32_kernel (ws == 2, fp32)
+    WsParams Wp;    // launch plan of corr_ws_kernel (ws == 1, 16-bit storage), corr_ws32_kernel (ws == 2, fp32) or corr_row_kernel (ws == 3)
     int ws;
     bool ok;
 };
@@ -94,10 +94,12 @@ int plan_override_hash()
     return (int)h;
 }
 
+// allow_row: the row-sweep kernel may be chosen (2-D layers; the volumetric entry points, which hand the kernels
+// depth slices through an offset table, keep to the kernels that know that table)
 bool get_plan(PlanEntry &out, int dtype, int B, int C_out, int H, int W, int kH, int kW, int sh, int sw, int ph, int pw, int CS,
-              bool dy_aligned)
+              bool dy_aligned, bool allow_row = true)
 {
-    PlanKey k{{dtype, B, C_out, H, W, kH, kW, sh, sw, ph, pw, CS, dy_aligned ? 1 : 0, plan_override_hash()}};
+    PlanKey k{{dtype, B, C_out, H, W, kH, kW, sh, sw, ph, pw, CS, (dy_aligned ? 1 : 0) | (allow_row ? 2 : 0), plan_override_hash()}};
     {
         std::lock_guard<std::mutex> lk(g_plan_mu);
         for (const PlanEntry &e : g_plans)
@@ -111,7 +113,8 @@ bool get_plan(PlanEntry &out, int dtype, int B, int C_out, int H, int W, int kH,
     e.P = CorrParams{};
     e.Wp = WsParams{};
     // the producer/consumer kernel reads dY in place, so the caller's planes must be usable as they are
-    e.ws = (dy_aligned && plan_corr_ws(e.Wp, dtype, B, C_out, H, W, kH, kW, sh, sw, ph, pw, CS)) ? 1 : 0;
+    e.ws = (dy_aligned && allow_row && plan_corr_row(e.Wp, dtype, B, C_out, H, W, kH, kW, sh, sw, ph, pw, CS)) ? 3 : 0;
+    if (!e.ws && dy_aligned && plan_corr_ws(e.Wp, dtype, B, C_out, H, W, kH, kW, sh, sw, ph, pw, CS)) e.ws = 1;
     if (!e.ws && dy_aligned && plan_corr_ws32(e.Wp, dtype, B, C_out, H, W, kH, kW, sh, sw, ph, pw, CS)) e.ws = 2;
     if (e.ws) {
         e.ok = true;
@@ -127,6 +130,12 @@ bool get_plan(PlanEntry &out, int dtype, int B, int C_out, int H, int W, int kH,
     if (g_plans.size() >= 64) g_plans.erase(g_plans.begin());
     g_plans.push_back(e);
     return e.ok;
+}
+
+hipError_t launch_ws_plan(int dtype, const PlanEntry &E, hipStream_t st)
+{
+    if (E.ws == 3) return launch_corr_row(dtype, E.Wp, st);
+    return E.ws == 2 ? launch_corr_ws32(E.Wp, st) : launch_corr_ws(dtype, E.Wp, st);
 }
 
 // distribution and keep probability in the form the generator takes
@@ -339,7 +348,7 @@ bool vol_plan(PlanEntry &E, const xconv3d_desc *v, int CS)
     const xconv_desc *d = &v->l;
     const Vol g = vol_of(v);
     if (g.B2 > 0x7fffffffLL) return false;
-    return get_plan(E, d->dtype, (int)g.B2, d->C_out, d->H, d->W, d->kH, d->kW, d->stride_h, d->stride_w, d->pad_h, d->pad_w, CS, true);
+    return get_plan(E, d->dtype, (int)g.B2, d->C_out, d->H, d->W, d->kH, d->kW, d->stride_h, d->stride_w, d->pad_h, d->pad_w, CS, true, false);
 }
 
 }  // namespace
@@ -396,7 +405,7 @@ xconv_status xconv_dw_estimate(const xconv_desc *d, const void *dY_dev, const vo
         E.Wp.dY = P.dY;
         E.Wp.A = Xt_dev;
         E.Wp.part = P.part;
-        XC_LAUNCH(K_CORR, st, E.ws == 2 ? launch_corr_ws32(E.Wp, st) : launch_corr_ws(d->dtype, E.Wp, st));
+        XC_LAUNCH(K_CORR, st, launch_ws_plan(d->dtype, E, st));
     } else {
         XC_LAUNCH(K_CORR, st, launch_corr(d->dtype, P, st));
     }
@@ -457,7 +466,7 @@ xconv_status exact_impl(const xconv_desc *d, const void *dY_dev, const void *X_d
         E.Wp.dY = P.dY;
         E.Wp.A = A;
         E.Wp.part = P.part;
-        XC_LAUNCH(K_CORR, st, E.ws == 2 ? launch_corr_ws32(E.Wp, st) : launch_corr_ws(d->dtype, E.Wp, st));
+        XC_LAUNCH(K_CORR, st, launch_ws_plan(d->dtype, E, st));
     } else {
         XC_LAUNCH(K_CORR, st, launch_corr(d->dtype, P, st));
     }
@@ -487,7 +496,7 @@ xconv_status xconv_plan_info(const xconv_desc *d, int op, int32_t *out)
         return XCONV_EUNSUPPORTED;
     if (E.ws) {
         const WsParams &Q = E.Wp;
-        const int32_t v[16] = {Q.S, Q.NS, 1, Q.CW, Q.WM, Q.WJ, 1, Q.M_WG, Q.J_WG, (int32_t)(E.ws == 2 ? corr_ws32_lds_bytes(Q) : corr_ws_lds_bytes(Q)),
+        const int32_t v[16] = {Q.S, Q.NS, 1, Q.CW, Q.WM, Q.WJ, 1, Q.M_WG, Q.J_WG, (int32_t)(E.ws == 3 ? corr_row_lds_bytes(Q) : E.ws == 2 ? corr_ws32_lds_bytes(Q) : corr_ws_lds_bytes(Q)),
                                Q.NTM, Q.NTJ, Q.NOG, Q.CS, Q.NSUB, E.ws};
         for (int i = 0; i < 16; ++i) out[i] = v[i];
         return XCONV_OK;
@@ -617,7 +626,7 @@ xconv_status xconv3d_dw_estimate(const xconv3d_desc *v, const void *dY_dev, cons
             E.Wp.dY = P.dY;
             E.Wp.A = A;
             E.Wp.part = P.part;
-            XC_LAUNCH(K_CORR, st, E.ws == 2 ? launch_corr_ws32(E.Wp, st) : launch_corr_ws(d->dtype, E.Wp, st));
+            XC_LAUNCH(K_CORR, st, launch_ws_plan(d->dtype, E, st));
         } else {
             XC_LAUNCH(K_CORR, st, launch_corr(d->dtype, P, st));
         }
@@ -679,7 +688,7 @@ xconv_status xconv3d_dw_exact(const xconv3d_desc *v, const void *dY_dev, const v
             E.Wp.dY = P.dY;
             E.Wp.A = A;
             E.Wp.part = P.part;
-            XC_LAUNCH(K_CORR, st, E.ws == 2 ? launch_corr_ws32(E.Wp, st) : launch_corr_ws(d->dtype, E.Wp, st));
+            XC_LAUNCH(K_CORR, st, launch_ws_plan(d->dtype, E, st));
         } else {
             XC_LAUNCH(K_CORR, st, launch_corr(d->dtype, P, st));
         }

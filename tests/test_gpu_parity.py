@@ -221,19 +221,51 @@ WS_EDGE = [
 
 
 @pytest.mark.parametrize("e", WS_EDGE, ids=[e[0] for e in WS_EDGE])
-def test_producer_consumer_kernel_shapes(e):
-    import os
+def test_producer_consumer_kernel_shapes(e, monkeypatch):
     name, B, C_in, C_out, H, W, k, stride, pad, r, probe, dtype = e
     d = xb.make_desc(B, C_in, C_out, H, W, k, stride, pad, r, dtype, probe, 13)
+    monkeypatch.setenv("XCONV_CORR_ROW", "0")        # (the row-sweep kernel would take some of these shapes: see below)
     if name.startswith("ws-runs"):
-        os.environ["XCONV_WS_SPLITS"] = "4"      # read when the launch plan of this shape is made
-    try:
-        op = xb.XCONV_OP_EXACT if name.startswith("ws-exact") else xb.XCONV_OP_ESTIMATE
-        plan = xb.xconv_plan_info(d, op)
-    finally:
-        os.environ.pop("XCONV_WS_SPLITS", None)
+        monkeypatch.setenv("XCONV_WS_SPLITS", "4")   # the overrides in force are part of the key of the plan cache
+    op = xb.XCONV_OP_EXACT if name.startswith("ws-exact") else xb.XCONV_OP_ESTIMATE
+    plan = xb.xconv_plan_info(d, op)
     assert plan["ws"] == 1, plan
     if name.startswith("ws-runs"):
+        assert plan["S"] == 4 and plan["NS"] == 30, plan
+    run_edge(e)
+
+
+# Shapes that the row-sweep kernel takes (16-bit storage, 3x3 kernels at unit stride, output rows of 4..28 columns, a
+# multiple of 4, probe columns a multiple of 32): rows of 2..16 k-steps in one or two sub-steps with every position
+# the sliding window can have at the end of a row, partial groups of 8 images, output channels that do not fill a
+# tile, paddings 0 and 2, two tiles along the probe columns, the exact gradient, and a split of the reduction whose
+# ranges cross from one group of images into the next.
+ROW_EDGE = [
+    ("row-w4-f16", 8, 16, 32, 6, 4, 3, 1, 1, 32, "rademacher", "f16"),
+    ("row-w8-nopad-f16", 8, 16, 32, 10, 10, 3, 1, 0, 32, "gaussian", "f16"),
+    ("row-w12-partial-group-f16", 11, 16, 40, 12, 12, 3, 1, 1, 32, "rademacher", "f16"),
+    ("row-w12-pad2-bf16", 8, 16, 32, 8, 10, 3, 1, 2, 32, "rademacher", "bf16"),
+    ("row-w16-r64-bf16", 9, 24, 70, 10, 16, 3, 1, 1, 64, "rademacher", "bf16"),
+    ("row-w20-f16", 8, 16, 64, 7, 20, 3, 1, 1, 64, "rademacher", "f16"),
+    ("row-w24-bf16", 10, 16, 33, 9, 24, 3, 1, 1, 64, "gaussian", "bf16"),
+    ("row-w28-f16", 16, 32, 96, 28, 28, 3, 1, 1, 64, "rademacher", "f16"),
+    ("row-r128-f16", 8, 16, 32, 8, 8, 3, 1, 1, 128, "rademacher", "f16"),
+    ("row-exact-cin64-f16", 8, 64, 32, 8, 8, 3, 1, 1, 16, "rademacher", "f16"),
+    ("row-runs-f16", 40, 16, 32, 6, 8, 3, 1, 1, 32, "rademacher", "f16"),        # 4 ranges over 5 groups x 6 rows
+    ("row-runs-two-tiles-bf16", 20, 16, 48, 5, 28, 3, 1, 1, 64, "rademacher", "bf16"),
+]
+
+
+@pytest.mark.parametrize("e", ROW_EDGE, ids=[e[0] for e in ROW_EDGE])
+def test_row_sweep_kernel_shapes(e, monkeypatch):
+    name, B, C_in, C_out, H, W, k, stride, pad, r, probe, dtype = e
+    d = xb.make_desc(B, C_in, C_out, H, W, k, stride, pad, r, dtype, probe, 13)
+    if "runs" in name:
+        monkeypatch.setenv("XCONV_ROW_SPLITS", "4" if name == "row-runs-f16" else "3")
+    op = xb.XCONV_OP_EXACT if name.startswith("row-exact") else xb.XCONV_OP_ESTIMATE
+    plan = xb.xconv_plan_info(d, op)
+    assert plan["ws"] == 3, plan
+    if name == "row-runs-f16":
         assert plan["S"] == 4 and plan["NS"] == 30, plan
     run_edge(e)
 
@@ -277,6 +309,20 @@ def test_producer_consumer_kernel_is_deterministic():
     dY = synth.draw((B, C_out, H, W), 32, "normal", 1e-2, dtype)
     d = xb.make_desc(B, C_in, C_out, H, W, k, stride, pad, r, dtype, probe, 33)
     assert xb.xconv_plan_info(d, xb.XCONV_OP_ESTIMATE)["ws"] == 1
+    _three_runs_agree(d, X, dY, dtype, C_out, C_in)
+
+
+def test_row_sweep_kernel_is_deterministic():
+    say("determinism, row-sweep kernel")
+    name, B, C_in, C_out, H, W, k, stride, pad, r, probe, dtype = ROW_EDGE[7]
+    X = synth.draw((B, C_in, H, W), 31, "relu_normal", 1.0, dtype)
+    dY = synth.draw((B, C_out, H, W), 32, "normal", 1e-2, dtype)
+    d = xb.make_desc(B, C_in, C_out, H, W, k, stride, pad, r, dtype, probe, 33)
+    assert xb.xconv_plan_info(d, xb.XCONV_OP_ESTIMATE)["ws"] == 3
+    _three_runs_agree(d, X, dY, dtype, C_out, C_in)
+
+
+def _three_runs_agree(d, X, dY, dtype, C_out, C_in):
     Xd, dYd = xb.to_device(X, dtype, DEV), xb.to_device(dY, dtype, DEV)
     Xt = xb.alloc_xt(d, DEV)
     xb.xconv_probe_fwd(d, Xd, Xt, None, xb.alloc_ws(d, xb.XCONV_OP_PROBE, DEV))
