@@ -28,6 +28,13 @@
 #include "launch.h"
 #include "ws_pos.h"
 
+// Timing experiments only (never defined in the shipped build): bit 0 consumers issue no MFMA, bit 1 no
+// fragment reads, bit 3 producers issue no global loads, bit 4 no LDS writes or transposes, bit 5 the first
+// consumer wave leaves time stamps in its partial tile.
+#ifndef XCONV_ROW_DBG
+#define XCONV_ROW_DBG 0
+#endif
+
 namespace xc {
 
 namespace {
@@ -59,6 +66,8 @@ __global__ __launch_bounds__(kWsThreads) void corr_row_kernel(const WsParams P)
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    unsigned long long ts_[8];
+    if constexpr (XCONV_ROW_DBG & 32) { ts_[0] = __builtin_amdgcn_s_memrealtime(); ts_[1] = __builtin_readcyclecounter(); }
     int tm, tj;
     fast_divmod((int)blockIdx.y, P.NTM, frcp(P.NTM), tj, tm);
     const int m0 = tm * P.M_WG;
@@ -102,6 +111,7 @@ __global__ __launch_bounds__(kWsThreads) void corr_row_kernel(const WsParams P)
                 return b_wave + (uint32_t)__builtin_amdgcn_readfirstlane(slot * P.b_row_units) * 16u;
             };
             auto lds_read = [](u32x4r &dst, uint32_t addr, auto off) {
+                if constexpr (XCONV_ROW_DBG & 2) return;
                 asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(decltype(off)::value) : "memory");
             };
             // requests return in order: at most N younger ones may be in flight behind x, y, z
@@ -114,6 +124,7 @@ __global__ __launch_bounds__(kWsThreads) void corr_row_kernel(const WsParams P)
             uint32_t pa, pb3[3];
             auto mma = [&](auto phc, auto oc, const u32x4r &bf) {
                 constexpr int o = decltype(oc)::value;
+                if constexpr (XCONV_ROW_DBG & 1) return;
                 acc[o] = mfma32r<DT>(af[decltype(phc)::value], bf, acc[o]);
             };
 
@@ -121,6 +132,7 @@ __global__ __launch_bounds__(kWsThreads) void corr_row_kernel(const WsParams P)
 #pragma unroll
             for (int ky = 0; ky < 3; ++ky) pb3[ky] = b_addr(pc.rowmod, ky);
             ws_barrier();  // the first dY tile and the rows of the first row-step are in LDS
+            if constexpr (XCONV_ROW_DBG & 32) { ts_[2] = __builtin_amdgcn_s_memrealtime(); ts_[3] = __builtin_readcyclecounter(); }
             lds_read(af[0], pa, IC<0>{});
             ws_static_for<0, 9>([&](auto oc) {   // window register w <- column w, kernel rows inside
                 constexpr int o = decltype(oc)::value;
@@ -277,6 +289,7 @@ __global__ __launch_bounds__(kWsThreads) void corr_row_kernel(const WsParams P)
             }
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         }
+        if constexpr (XCONV_ROW_DBG & 32) { ts_[4] = __builtin_amdgcn_s_memrealtime(); ts_[5] = __builtin_readcyclecounter(); }
 
         // D tile: lane (l32, g) holds column l32 and rows 8v + 4g .. 8v + 4g + 3 (v = 0..3)
         const int jcol = jb + wj * 32 + l32;
@@ -286,6 +299,14 @@ __global__ __launch_bounds__(kWsThreads) void corr_row_kernel(const WsParams P)
 #pragma unroll
             for (int v = 0; v < 4; ++v)
                 *reinterpret_cast<f32x4 *>(dst + 8 * v) = f32x4{acc[o][4 * v], acc[o][4 * v + 1], acc[o][4 * v + 2], acc[o][4 * v + 3]};
+        }
+        if constexpr (XCONV_ROW_DBG & 32) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            ts_[6] = __builtin_amdgcn_s_memrealtime(); ts_[7] = __builtin_readcyclecounter();
+            if (wave == 0 && lane == 0) {
+                unsigned long long *d = reinterpret_cast<unsigned long long *>(P.part + (((size_t)blockIdx.x * P.K2) * P.JP + jb) * P.MP + m0);
+                for (int q = 0; q < 8; ++q) d[q] = ts_[q];
+            }
         }
     } else {
         // =========================== producers ===========================
@@ -335,6 +356,7 @@ __global__ __launch_bounds__(kWsThreads) void corr_row_kernel(const WsParams P)
         };
         // loads are opaque to the compiler and waited for by hand (see corr_ws_kernel)
         auto buf16_async = [](u32x4r &dst, i32x4r r, uint32_t voff) {
+            if constexpr (XCONV_ROW_DBG & 8) return;
             asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(dst) : "v"(voff), "s"(r) : "memory");
         };
         auto wait8 = [](auto nc, u32x4r (&r)[8]) {
@@ -345,6 +367,7 @@ __global__ __launch_bounds__(kWsThreads) void corr_row_kernel(const WsParams P)
         };
         // 8 images x 8 columns -> 8 units, in place
         auto transpose = [](u32x4r (&r)[8]) {
+            if constexpr (XCONV_ROW_DBG & 16) return;
             uint32_t rows[8][4];
 #pragma unroll
             for (int q = 0; q < 8; ++q) { rows[q][0] = r[q].x; rows[q][1] = r[q].y; rows[q][2] = r[q].z; rows[q][3] = r[q].w; }
@@ -376,6 +399,7 @@ __global__ __launch_bounds__(kWsThreads) void corr_row_kernel(const WsParams P)
         };
         // ---- the pieces of sub-step u of a row (transposed registers) -> dY tile `buf`
         auto write_dy = [&](int u, int buf, const u32x4r (&r)[8]) {
+            if constexpr (XCONV_ROW_DBG & 16) return;
             if (d_on && du == u) {
                 uint4 *dst = lds_a + buf * P.a_units + d_lds;
 #pragma unroll
@@ -385,6 +409,7 @@ __global__ __launch_bounds__(kWsThreads) void corr_row_kernel(const WsParams P)
         };
         // ---- the added row of row-step ps (transposed registers) -> its ring slot
         auto write_xt = [&](const WsPos &ps, const u32x4r (&r)[8]) {
+            if constexpr (XCONV_ROW_DBG & 16) return;
             if (x_on && ps.y > 0) {
                 int slot = ps.rowmod + P.kH - 1;
                 slot = slot >= P.NRING ? slot - P.NRING : slot;
