@@ -130,6 +130,21 @@ xconv_status xconv_dw_estimate(const xconv_desc *desc, const void *dY_dev, const
                                const float *Z_dev, float *dW_dev,
                                void *ws_dev, size_t ws_bytes, void *stream);
 
+/* xconv_dw_estimate for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): no workspace argument.
+ * The scratch is a device array inside the library, XCONV_STATIC_SCRATCH_BYTES per GPU the
+ * library runs on, held until the process ends; its address is looked up once per device, on
+ * the first call with that device current.  The call allocates and frees nothing.  Arguments,
+ * result and status as xconv_dw_estimate; XCONV_EWORKSPACE when
+ * xconv_workspace_bytes(desc, XCONV_OP_ESTIMATE) exceeds XCONV_STATIC_SCRATCH_BYTES (nothing is
+ * launched then), XCONV_EHIP when the runtime does not give the array's address.  All calls on
+ * one GPU share the one array: calls that overlap in time on a GPU (two streams, two threads)
+ * race on it, so issue them on one stream or order them with events. */
+#define XCONV_STATIC_SCRATCH_BYTES (40u * 1024u * 1024u)
+size_t xconv_static_scratch_bytes(void);
+xconv_status xconv_dw_estimate_static(const xconv_desc *desc, const void *dY_dev, const void *Xt_dev,
+                                      const float *Z_dev, float *dW_dev, void *stream);
+
 /* Exact weight gradient (Eq. (2)/(5)), for comparison with the estimate: same
  * correlation kernel with the C_in real channels in place of the r probed
  * ones.  X_dev: [B,C_in,H,W] (XCONV_NHWC: X and dY channels-last); dY_dev 16-byte aligned; dW_dev: [C_out,C_in,kH,kW] fp32, overwritten.

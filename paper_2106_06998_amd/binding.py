@@ -71,6 +71,10 @@ def lib():
         L.xconv_dw_estimate.argtypes = [P, vp, vp, vp, vp, vp, sz, vp]
         L.xconv_dw_exact.restype = i32
         L.xconv_dw_exact.argtypes = [P, vp, vp, vp, vp, sz, vp]
+        L.xconv_dw_estimate_static.restype = i32
+        L.xconv_dw_estimate_static.argtypes = [P, vp, vp, vp, vp, vp]
+        L.xconv_static_scratch_bytes.restype = sz
+        L.xconv_static_scratch_bytes.argtypes = []
         L.xconv_plan_info.restype = i32
         L.xconv_plan_info.argtypes = [P, i32, vp]
         L.xconv_xt_unpack.restype = i32
@@ -200,6 +204,15 @@ def xconv_probe_fwd(desc, X_dev, Xt_dev, Z_dev=None, ws_dev=None, stream=None):
 def xconv_dw_estimate(desc, dY_dev, Xt_dev, Z_dev, dW_dev, ws_dev, stream=None):
     _check(lib().xconv_dw_estimate(ctypes.byref(desc), _ptr(dY_dev), _ptr(Xt_dev), _ptr(Z_dev), _ptr(dW_dev),
                                    _ptr(ws_dev), _nbytes(ws_dev), _stream(stream)), "xconv_dw_estimate")
+
+
+def xconv_dw_estimate_static(desc, dY_dev, Xt_dev, Z_dev, dW_dev, stream=None):
+    _check(lib().xconv_dw_estimate_static(ctypes.byref(desc), _ptr(dY_dev), _ptr(Xt_dev), _ptr(Z_dev), _ptr(dW_dev),
+                                          _stream(stream)), "xconv_dw_estimate_static")
+
+
+def xconv_static_scratch_bytes():
+    return int(lib().xconv_static_scratch_bytes())
 
 
 def xconv_dw_exact(desc, dY_dev, X_dev, dW_dev, ws_dev, stream=None):

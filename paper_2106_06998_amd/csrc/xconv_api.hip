@@ -416,6 +416,54 @@ xconv_status xconv_dw_estimate(const xconv_desc *d, const void *dY_dev, const vo
 
 }  // extern "C"
 
+// ---- the estimate without a workspace argument --------------------------------------------------
+// Scratch of xconv_dw_estimate_static: a device array of the library itself, one copy per GPU, alive until the
+// process ends.  Its name is a host-side stand-in here; the address on a device comes from hipGetSymbolAddress,
+// asked for once per device with that device current, and only that address is ever handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[XCONV_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// address of `scratch` on the current device (nullptr: the runtime would not say)
+void *static_scratch()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t xconv_static_scratch_bytes(void) { return XCONV_STATIC_SCRATCH_BYTES; }
+
+xconv_status xconv_dw_estimate_static(const xconv_desc *d, const void *dY_dev, const void *Xt_dev, const float *Z_dev, float *dW_dev,
+                                      void *stream)
+{
+    xconv_status s = xconv_check_desc(d);
+    if (s != XCONV_OK) return s;
+    const size_t need = xconv_workspace_bytes(d, XCONV_OP_ESTIMATE);
+    if (need == 0) return XCONV_EUNSUPPORTED;
+    if (need > (size_t)XCONV_STATIC_SCRATCH_BYTES) return XCONV_EWORKSPACE;
+    void *ws = static_scratch();
+    if (!ws) return XCONV_EHIP;
+    // every partial sum the kernels read from the scratch is written earlier in the same call: nothing to clear
+    return xconv_dw_estimate(d, dY_dev, Xt_dev, Z_dev, dW_dev, ws, XCONV_STATIC_SCRATCH_BYTES, stream);
+}
+
+}  // extern "C"
+
 namespace {
 
 // Exact-gradient path.  A_ready != nullptr: the activation is already channels-last [B, H, W, C_in rounded up

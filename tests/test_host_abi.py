@@ -308,7 +308,19 @@ def test_launch_plans_stay_within_the_device_limits_on_random_layers():
             assert plan["CS"] % 16 == 0 and plan["CS"] >= (d.r if op == xb.XCONV_OP_ESTIMATE else d.C_in)
             assert plan["NTM"] * plan["M_WG"] >= d.C_out and plan["NTJ"] * plan["J_WG"] == plan["CS"]
             assert ws < 2 ** 34
-    assert seen == {0, 1, 2}          # all three correlation kernels get layers
+    assert seen == {0, 1, 2, 3}       # all four correlation kernels get layers
+
+
+def test_static_scratch_entry_point_checks_before_it_touches_a_device():
+    # xconv_dw_estimate_static: descriptor and size checks come first and need no GPU
+    L = xb.lib()
+    assert xb.xconv_static_scratch_bytes() == 40 * 1024 * 1024
+    d = _good()
+    d.r = 0
+    assert L.xconv_dw_estimate_static(ctypes.byref(d), 16, 16, None, 16, None) == xb.XCONV_EINVAL
+    big = xb.make_desc(64, 256, 512, 28, 28, 3, 1, 1, 256, "f16", "rademacher", 1)
+    assert xb.xconv_workspace_bytes(big, xb.XCONV_OP_ESTIMATE) > xb.xconv_static_scratch_bytes()
+    assert L.xconv_dw_estimate_static(ctypes.byref(big), 16, 16, None, 16, None) == xb.XCONV_EWORKSPACE
 
 
 def test_sign_relu_sizes_and_argument_checks():
