@@ -211,6 +211,11 @@ struct CorrParams {
     int dy_plane;      // elements between consecutive (image, channel) planes of dY as the kernel reads it (whole 16-byte vectors)
     int a_units, b_units;  // LDS units of the two staging tiles
     int AL;            // every staged row segment of dY starts on a 16-byte vector
+    // Z[s] for the expansion that follows (Alg. 1 backward step 2): when zout is set, the launch's workgroups
+    // each draw a slice of its nz entries from (zdist, zseed) before they start on the correlation
+    float *zout;
+    int nz, zdist;
+    uint64_t zseed;
 };
 
 
@@ -238,6 +243,21 @@ struct WsParams {
     // slot i % vol_period of volume i / vol_period, a zero image when the slot is >= vol_Do.  0: plain dY.
     int vol_period, vol_Do;
     uint32_t vol_bytes;     // bytes of the whole dY tensor (below 2^30)
+    // Z[s] for the expansion that follows, drawn by this launch (see CorrParams)
+    float *zout;
+    int nz, zdist;
+    uint64_t zseed;
 };
+
+// Entries wg*threads + tid, + (workgroups * threads), ... of Z[s], drawn by the calling thread (Alg. 1 backward
+// step 2: the probing matrix is regenerated from the seed, never stored between the passes).
+__device__ inline void draw_z_slice(float *zout, int nz, int dist, uint64_t seed)
+{
+    if (!zout) return;
+    const int nwg = gridDim.x * gridDim.y * gridDim.z;
+    const int wg = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    const ProbeGen gen = probe_gen(dist, seed);
+    for (int i = wg * (int)blockDim.x + (int)threadIdx.x; i < nz; i += nwg * (int)blockDim.x) zout[i] = probe_entry(gen, (uint64_t)i);
+}
 
 }  // namespace xc

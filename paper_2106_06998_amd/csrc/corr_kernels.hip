@@ -127,6 +127,7 @@ __device__ inline StepPos next_step(const CorrParams &P, StepPos s)
 template <int DT, int MT, int NA, int NB, int NOFF, bool AL>
 __global__ __launch_bounds__(kThreads, ((DT == XCONV_F32 && MT <= 2) ? 2 : 1)) void corr_kernel(const CorrParams P)
 {
+    draw_z_slice(P.zout, P.nz, P.zdist, P.zseed);
     constexpr bool F32 = (DT == XCONV_F32);
     constexpr int BI = F32 ? 1 : 8;   // images per LDS unit
     constexpr int EPV = F32 ? 4 : 8;  // elements per 16-byte global vector
@@ -471,21 +472,27 @@ __global__ __launch_bounds__(kThreads, ((DT == XCONV_F32 && MT <= 2) ? 2 : 1)) v
                 pb[o] = b_base + (uint32_t)u * US;
             }
         };
-        auto tie = [](frag_t &r) { asm volatile("" : "+v"(r)); };
-        frag_t a[MT], an[MT], b[NOFF];
-        auto a_arrived = [&]() {  // the A fragments are the oldest of the MT + NOFF requests of a k-step
-            asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(NOFF) : "memory");
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) tie(an[mt]);
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) a[mt] = an[mt];
+        // A wait names the registers it guards as operands, and no fragment is ever copied: the A fragments
+        // alternate between two register sets (k-step i multiplies from set i & 1 and requests the next one into
+        // the other set).  A copy "a = a_next" behind the wait would be the compiler's to place, and it has been seen
+        // in front of the wait, reading registers whose data had not arrived yet.
+        frag_t a2[2][MT], b[NOFF];
+        auto a_arrived = [&](auto parc) {  // the A fragments are the oldest of the MT + NOFF requests of a k-step
+            constexpr int par = decltype(parc)::value;
+            if constexpr (MT == 1)
+                asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a2[par][0]) : "n"(NOFF) : "memory");
+            else if constexpr (MT == 2)
+                asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a2[par][0]), "+v"(a2[par][1]) : "n"(NOFF) : "memory");
+            else
+                asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a2[par][0]), "+v"(a2[par][1]), "+v"(a2[par][2]), "+v"(a2[par][3]) : "n"(NOFF) : "memory");
+            static_assert(MT == 1 || MT == 2 || MT == 4, "a_arrived names MT registers");
         };
         set_row(0);
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) lds_read(an[mt], pa[mt]);
+        for (int mt = 0; mt < MT; ++mt) lds_read(a2[0][mt], pa[mt]);
 #pragma unroll
         for (int o = 0; o < NOFF; ++o) lds_read(b[o], pb[o]);
-        a_arrived();
+        a_arrived(std::integral_constant<int, 0>{});
 
         // One k-step: its MFMAs and the requests for the fragments at (pa, pb).  Requests in
         // issue order: A (MT), then B of offset o-1 right after the MFMAs of offset o, B of the
@@ -493,33 +500,35 @@ __global__ __launch_bounds__(kThreads, ((DT == XCONV_F32 && MT <= 2) ? 2 : 1)) v
         // k-step's requests up to offset o+2 must be done: at that point the younger ones are
         // the rest of the previous k-step, this k-step's A and its B up to offset o-2.
         constexpr int WG3 = (NOFF % 3 == 0) ? 3 : 1;
-        auto kstep = [&]() {
+        auto kstep = [&](auto parc) {
+            constexpr int par = decltype(parc)::value;
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) lds_read(an[mt], pa[mt]);
+            for (int mt = 0; mt < MT; ++mt) lds_read(a2[par ^ 1][mt], pa[mt]);
             ws_for<0, NOFF>([&](auto oc) {
                 constexpr int o = decltype(oc)::value;
                 if constexpr (o % WG3 == 0) {
                     constexpr int younger = (NOFF - WG3 - o) + MT + (o >= 2 ? o - 1 : 0);
-                    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(younger) : "memory");
-#pragma unroll
-                    for (int q = 0; q < WG3; ++q) tie(b[o + q]);
+                    if constexpr (WG3 == 3)
+                        asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(b[o]), "+v"(b[o + WG3 - 2]), "+v"(b[o + WG3 - 1]) : "n"(younger) : "memory");
+                    else
+                        asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(b[o]) : "n"(younger) : "memory");
                 }
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
-                    if constexpr (F32) acc[mt][o] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[mt], b[o], acc[mt][o], 0, 0, 0);
-                    else acc[mt][o] = mfma16<DT>(__builtin_bit_cast(uint4, a[mt]), __builtin_bit_cast(uint4, b[o]), acc[mt][o]);
+                    if constexpr (F32) acc[mt][o] = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[par][mt], b[o], acc[mt][o], 0, 0, 0);
+                    else acc[mt][o] = mfma16<DT>(__builtin_bit_cast(uint4, a2[par][mt]), __builtin_bit_cast(uint4, b[o]), acc[mt][o]);
                 }
                 if constexpr (o >= 1) lds_read(b[o - 1], pb[o - 1]);
             });
             lds_read(b[NOFF - 1], pb[NOFF - 1]);
-            a_arrived();
+            a_arrived(std::integral_constant<int, par ^ 1>{});
             __builtin_amdgcn_sched_barrier(0);
         };
 
         int i_row = 0, rb = 0;
-        for (int i = 0; i < total; ++i) {
-            // addresses of the k-step after this one (after the last one: unchanged, the requests repeat)
+        // addresses of the k-step after the current one (after the last one: unchanged, the requests repeat)
+        auto advance = [&]() {
             if (++i_row == n_row) {
                 i_row = 0;
                 ++rb;
@@ -532,7 +541,17 @@ __global__ __launch_bounds__(kThreads, ((DT == XCONV_F32 && MT <= 2) ? 2 : 1)) v
 #pragma unroll
                 for (int o = 0; o < NOFF; ++o) pb[o] += step_b;
             }
-            kstep();
+        };
+        int i = 0;
+        for (; i + 1 < total; i += 2) {
+            advance();
+            kstep(std::integral_constant<int, 0>{});
+            advance();
+            kstep(std::integral_constant<int, 1>{});
+        }
+        if (i < total) {
+            advance();
+            kstep(std::integral_constant<int, 0>{});
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     };
@@ -710,6 +729,119 @@ __global__ __launch_bounds__(64) void expand_kernel(const float *__restrict__ T,
 #pragma unroll
                 for (int o = 0; o < OG; ++o)
                     if (o0 + o < K2) dst[o] = acc[o][v] * inv_r;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Second pass in one launch (Algorithm 1 backward step 4, Eq. (6) step (iii), on the partial sums of
+// step 3): a workgroup owns 16 output channels of one kernel offset.  It first sums the S partial
+// tiles of its slab T[og, j0 .. j0+JC, m0 .. m0+16) in a fixed order (s = 0, 1, 2, ... in four
+// interleaved chains, chains and groups combined in a fixed tree: the result does not depend on
+// timing) into LDS, then multiplies the slab by Z on the 16x16x4 matrix instruction,
+//   dW[m,n,og] = (1/r) sum_j Z[n,j] T[og,j,m],
+// its four waves taking the tiles of 16 input channels in turn.  MODE 0: Z from memory (the caller's,
+// or the one the workgroups of the correlation launch redrew from the seed, Alg. 1 backward step 2);
+// MODE 2: exact gradient, dW[m,n,og] = T[og,n,m] (then grid.z cuts the input channels into chunks
+// of JC).  Offsets are counted over `nsets` sets of partial tiles stored back to back (volumetric
+// layers: one set per kernel-depth offset), og = set * K2 + o, K2T = nsets * K2.
+// ---------------------------------------------------------------------------
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void reduce_expand_kernel(const float *__restrict__ part, const float *__restrict__ Z,
+                                                                 float *__restrict__ dW, int S, int K2, int K2T, int JP, int MP,
+                                                                 int JC, int C_out, int C_in, int r, int nnz_norm)
+{
+    extern __shared__ f32x4 re_lds[];   // slab [JC][4] float4, then (few elements only) the groups' sums [NG][NE]
+    const int tid = threadIdx.x;
+    const int m0 = blockIdx.x * 16;
+    const int og = blockIdx.y, set = og / K2, o = og - set * K2;
+    const int j0 = blockIdx.z * JC;
+    const int NE = JC * 4;   // float4 elements of the slab: (j, four output channels)
+    const size_t tile = (size_t)K2 * JP * MP;   // floats of one partial tile
+    const float *base = part + (size_t)set * S * tile + ((size_t)o * JP + j0) * MP + m0;
+
+    // ---- fixed-order sum over the S partial tiles.  An element's tiles are taken in 16 interleaved chains (16
+    // loads in flight per thread: the tiles were written by other compute units and come from beyond the L2);
+    // few-element slabs also spread the tiles of an element over NG groups of threads.
+    const int NG = NE >= kThreads ? 1 : kThreads / NE;   // groups of threads that share the tiles of an element
+    f32x4 *red = re_lds + NE;
+    auto chain_sum = [&](const float *p, int first, int step) {
+        f32x4 c[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) c[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+        int k = first;
+        for (; k + 15 * step < S; k += 16 * step) {   // 16 tiles per trip, every load issued before the first sum
+            f32x4 v[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) v[i] = *reinterpret_cast<const f32x4 *>(p + (size_t)(k + i * step) * tile);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) c[i] += v[i];
+        }
+        for (int i = 0; k < S; k += step, ++i) c[i & 15] += *reinterpret_cast<const f32x4 *>(p + (size_t)k * tile);
+#pragma unroll
+        for (int w = 8; w >= 1; w >>= 1)
+#pragma unroll
+            for (int i = 0; i < w; ++i) c[i] += c[i + w];
+        return c[0];
+    };
+    if (NG == 1) {
+        for (int e = tid; e < NE; e += kThreads) re_lds[e] = chain_sum(base + (size_t)(e >> 2) * MP + 4 * (e & 3), 0, 1);
+    } else {
+        const int gi = tid / NE, e = tid - gi * NE;
+        if (gi < NG) red[gi * NE + e] = chain_sum(base + (size_t)(e >> 2) * MP + 4 * (e & 3), gi, NG);
+        __syncthreads();
+        if (tid < NE) {
+            f32x4 t = red[tid];
+            for (int q = 1; q < NG; ++q) t += red[q * NE + tid];
+            re_lds[tid] = t;
+        }
+    }
+    __syncthreads();
+    const float *slab = reinterpret_cast<const float *>(re_lds);   // [JC][16]
+
+    if constexpr (MODE == 2) {
+        // exact gradient: the slab is dW[m0.., j0.., og] transposed
+        for (int e = tid; e < JC * 16; e += kThreads) {
+            const int mi = e & 15, j = e >> 4;
+            const int m = m0 + mi, n = j0 + j;
+            if (m < C_out && n < C_in) dW[((size_t)m * C_in + n) * K2T + og] = slab[j * 16 + mi];
+        }
+    } else {
+        const int lane = tid & 63, wave = tid >> 6, l16 = lane & 15, g = lane >> 4;
+        const int NTN = (C_in + 15) >> 4;
+        for (int nt = wave; nt < NTN; nt += 4) {
+            const int ncol = nt * 16 + l16;
+            const int nc = ncol < C_in ? ncol : C_in - 1;
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            int cnt = 0;
+            for (int jj = 0; jj < r; jj += 16) {
+                float bv[4], av[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int j = jj + 4 * u + g;
+                    const int jc = j < r ? j : r - 1;
+                    const float zv = Z[(size_t)nc * r + jc];
+                    bv[u] = j < r ? zv : 0.f;
+                    cnt += bv[u] != 0.0f ? 1 : 0;
+                    av[u] = slab[jc * 16 + l16];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u], bv[u], acc, 0, 0, 0);
+            }
+            float inv_r = 1.0f / (float)r;
+            if (nnz_norm) {
+                // non-zero entries of row n of Z: the four lane groups of a column hold every fourth probe
+                cnt += __shfl_xor(cnt, 16);
+                cnt += __shfl_xor(cnt, 32);
+                inv_r = cnt > 0 ? 1.0f / (float)cnt : 0.0f;
+            }
+            if (ncol < C_in) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int m = m0 + 4 * g + v;
+                    if (m < C_out) dW[((size_t)m * C_in + ncol) * K2T + og] = acc[v] * inv_r;
+                }
             }
         }
     }
@@ -1007,6 +1139,43 @@ hipError_t launch_reduce_raw(const float *part, float *T, int S, int E4, hipStre
 {
     hipLaunchKernelGGL(reduce_partials_kernel, dim3(ceil_div(E4, 16), nsets), dim3(kThreads), 0, st, reinterpret_cast<const f32x4 *>(part),
                        reinterpret_cast<f32x4 *>(T), S, E4, nullptr, 0, 0, 0, (uint64_t)0);
+    return hipGetLastError();
+}
+
+bool reduce_expand_fused(const CorrParams &P, bool have_z, bool exact, int C_in, int r, int dist)
+{
+    // One workgroup per (offset, 16 output channels) reads all S partial tiles of its slab: that is K2 * MP / 16
+    // workgroups, 36 on a 64-channel 3x3 layer, and a compute unit turns memory requests around at a limited rate
+    // (measured: 18-30 us on the benchmark layers against 13-16 us for reduce_partials_kernel, which spreads the
+    // same bytes over the whole chip, plus expand_kernel).  The single launch wins where launch cost dominates:
+    // small layers, up to a few MB of partial sums.
+    const int mode = env_int("XCONV_FUSED_PASS2", -1);   // tests: 0 never, 1 whenever the kernel can take the layer
+    if (mode == 0) return false;
+    if (P.MP % 16 != 0 || P.JP % 16 != 0) return false;
+    if (!exact && P.JP > 1024) return false;   // (the slab of all probe columns sits in LDS: 64 KB at most)
+    if (mode == 1) return true;
+    return (size_t)P.S * P.K2 * P.JP * P.MP * sizeof(float) <= ((size_t)3 << 20);
+}
+
+hipError_t launch_reduce_expand(const CorrParams &P, const float *Z, bool exact, float *dW, int C_in, int r, bool nnz_norm, int dist,
+                                uint64_t seed, int nsets, hipStream_t st)
+{
+    // slab of JC probe columns (or input channels) x 16 output channels per workgroup; the estimate needs all columns
+    int JC = P.JP;
+    if (exact)   // chunks of at most 256 input channels that divide the padded channel count (a multiple of 16)
+        for (JC = P.JP < 256 ? P.JP : 256; P.JP % JC != 0; JC -= 16) {}
+    const int NE = JC * 4;
+    const int NG = NE >= kThreads ? 1 : kThreads / NE;
+    const size_t lds = (size_t)NE * 16 + (NG > 1 ? (size_t)NG * NE * 16 : 0);
+    const dim3 grid((unsigned)(P.MP / 16), (unsigned)(nsets * P.K2), (unsigned)(exact ? ceil_div(P.JP, JC) : 1));
+    const int K2T = nsets * P.K2;
+    if (exact) {
+        hipLaunchKernelGGL(reduce_expand_kernel<2>, grid, dim3(kThreads), lds, st, P.part, nullptr, dW, P.S, P.K2, K2T, P.JP, P.MP, JC,
+                           P.C_out, C_in, r, 0);
+    } else {
+        hipLaunchKernelGGL(reduce_expand_kernel<0>, grid, dim3(kThreads), lds, st, P.part, Z, dW, P.S, P.K2, K2T, P.JP, P.MP, JC, P.C_out,
+                           C_in, r, nnz_norm ? 1 : 0);
+    }
     return hipGetLastError();
 }
 

@@ -60,6 +60,7 @@ template <int N> using IC = std::integral_constant<int, N>;
 template <int DT, int REM, int CB>
 __global__ __launch_bounds__(kWsThreads) void corr_row_kernel(const WsParams P)
 {
+    draw_z_slice(P.zout, P.nz, P.zdist, P.zseed);
     extern __shared__ uint4 row_lds[];
     uint4 *lds_a = row_lds;                    // two dY tiles [lane group][slot][M_WG]
     uint4 *lds_b = row_lds + 2 * P.a_units;    // ring of A rows [slot][column][BSTR]

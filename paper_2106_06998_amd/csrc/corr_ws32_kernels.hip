@@ -31,6 +31,7 @@ namespace xc {
 template <int NOFF, int NTASK, int D, int OCC, bool VOL>
 __global__ __launch_bounds__(kWsThreads, 2 * OCC) void corr_ws32_kernel(const WsParams P)
 {
+    draw_z_slice(P.zout, P.nz, P.zdist, P.zseed);
     extern __shared__ uint4 ws32_lds[];
     uint4 *lds_a = ws32_lds;                    // two dY tiles [slot][M_WG]
     uint4 *lds_b = ws32_lds + 2 * P.a_units;    // ring of A rows [slot][column][BSTR]

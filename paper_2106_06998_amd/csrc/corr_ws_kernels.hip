@@ -53,6 +53,7 @@ template <int DT> __device__ inline f32x16 mfma32(const uint4 &a, const uint4 &b
 template <int DT, int NOFF, int NTASK, int D, int CB, bool RU, bool VOL>
 __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
 {
+    draw_z_slice(P.zout, P.nz, P.zdist, P.zseed);
     extern __shared__ uint4 ws_lds[];
     uint4 *lds_a = ws_lds;                    // two dY tiles [slot][M_WG]
     uint4 *lds_b = ws_lds + 2 * P.a_units;    // ring of A rows [slot][column][BSTR]

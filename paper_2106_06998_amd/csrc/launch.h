@@ -67,6 +67,12 @@ hipError_t launch_repack_planes(int dtype, const void *src, void *dst, long long
 hipError_t launch_reduce(const CorrParams &P, hipStream_t st, float *Zout = nullptr, int nz = 0, int dist = 0, uint64_t seed = 0,
                          float *T = nullptr, int nsets = 1);
 hipError_t launch_reduce_raw(const float *part, float *T, int S, int E4, hipStream_t st, int nsets = 1);
+// The second pass in one launch: fixed-order sum of the S partial tiles and the expansion by Z / r or, for the exact
+// gradient, the transposed store, straight into dW [C_out, C_in, nsets*K2].  reduce_expand_fused says whether this launch applies (otherwise launch_reduce
+// followed by launch_expand do the same in two).
+bool reduce_expand_fused(const CorrParams &P, bool have_z, bool exact, int C_in, int r, int dist);
+hipError_t launch_reduce_expand(const CorrParams &P, const float *Z, bool exact, float *dW, int C_in, int r, bool nnz_norm, int dist,
+                                uint64_t seed, int nsets, hipStream_t st);
 // dW[m,n,o] = (1/r) * sum_j Z[n,j] * T[o,j,m]   (Z != nullptr)
 // dW[m,n,o] = T[o,n,m]                          (Z == nullptr, exact path)
 // T != nullptr: K2 tiles [K2, JP, MP] are read from there (volumetric layers: kD * kH * kW offsets).

@@ -401,6 +401,14 @@ xconv_status xconv_dw_estimate(const xconv_desc *d, const void *dY_dev, const vo
     }
     P.A = Xt_dev;
     P.part = reinterpret_cast<float *>(static_cast<char *>(ws_dev) + zb);
+    // one launch for the second pass: Z[s], if it has to be redrawn, is drawn by the workgroups of the correlation launch
+    const bool fused = reduce_expand_fused(P, Z_dev != nullptr, false, d->C_in, d->r, probe_code(d));
+    if (fused && zw) {
+        P.zout = E.Wp.zout = zw;
+        P.nz = E.Wp.nz = d->C_in * d->r;
+        P.zdist = E.Wp.zdist = probe_code(d);
+        P.zseed = E.Wp.zseed = d->seed;
+    }
     if (E.ws) {
         E.Wp.dY = P.dY;
         E.Wp.A = Xt_dev;
@@ -408,6 +416,10 @@ xconv_status xconv_dw_estimate(const xconv_desc *d, const void *dY_dev, const vo
         XC_LAUNCH(K_CORR, st, launch_ws_plan(d->dtype, E, st));
     } else {
         XC_LAUNCH(K_CORR, st, launch_corr(d->dtype, P, st));
+    }
+    if (fused) {
+        XC_LAUNCH(K_REDUCE, st, launch_reduce_expand(P, Z, false, dW_dev, d->C_in, d->r, d->keep_q15 != 0, probe_code(d), d->seed, 1, st));
+        return XCONV_OK;
     }
     XC_LAUNCH(K_REDUCE, st, launch_reduce(P, st, zw, d->C_in * d->r, probe_code(d), d->seed));
     XC_LAUNCH(K_EXPAND, st, launch_expand(P, Z, dW_dev, d->C_in, d->r, st, d->keep_q15 != 0));
@@ -517,6 +529,10 @@ xconv_status exact_impl(const xconv_desc *d, const void *dY_dev, const void *X_d
         XC_LAUNCH(K_CORR, st, launch_ws_plan(d->dtype, E, st));
     } else {
         XC_LAUNCH(K_CORR, st, launch_corr(d->dtype, P, st));
+    }
+    if (reduce_expand_fused(P, false, true, d->C_in, d->r, 0)) {
+        XC_LAUNCH(K_REDUCE, st, launch_reduce_expand(P, nullptr, true, dW_dev, d->C_in, d->r, false, 0, 0, 1, st));
+        return XCONV_OK;
     }
     XC_LAUNCH(K_REDUCE, st, launch_reduce(P, st));
     XC_LAUNCH(K_EXPAND, st, launch_expand(P, nullptr, dW_dev, d->C_in, d->r, st));
@@ -666,7 +682,13 @@ xconv_status xconv3d_dw_estimate(const xconv3d_desc *v, const void *dY_dev, cons
         P.dY = dy_slices;
     }
     float *part0 = reinterpret_cast<float *>(ws + zb);
+    const bool fused = reduce_expand_fused(P, Z_dev != nullptr, false, d->C_in, d->r, probe_code(d));
     for (int kz = 0; kz < v->kD; ++kz) {
+        // (the first correlation launch also redraws Z[s] for the fused second pass)
+        P.zout = E.Wp.zout = (fused && zw && kz == 0) ? zw : nullptr;
+        P.nz = E.Wp.nz = d->C_in * d->r;
+        P.zdist = E.Wp.zdist = probe_code(d);
+        P.zseed = E.Wp.zseed = d->seed;
         const void *A = static_cast<const char *>(Xt_dev) + vol_offset_slices(g, kz) * g.slice_bytes;
         P.A = A;
         P.part = part0 + (size_t)kz * P.S * (tile / sizeof(float));
@@ -681,6 +703,10 @@ xconv_status xconv3d_dw_estimate(const xconv3d_desc *v, const void *dY_dev, cons
     }
     // one reduction for all kernel-depth offsets; its spare workgroups redraw Z[s] for the expansion
     P.part = part0;
+    if (fused) {
+        XC_LAUNCH(K_REDUCE, st, launch_reduce_expand(P, Z, false, dW_dev, d->C_in, d->r, d->keep_q15 != 0, probe_code(d), d->seed, v->kD, st));
+        return XCONV_OK;
+    }
     XC_LAUNCH(K_REDUCE, st, launch_reduce(P, st, zw, d->C_in * d->r, probe_code(d), d->seed, T3, v->kD));
     XC_LAUNCH(K_EXPAND, st, launch_expand(P, Z, dW_dev, d->C_in, d->r, st, d->keep_q15 != 0, T3, v->kD * P.K2));
     return XCONV_OK;
@@ -742,6 +768,10 @@ xconv_status xconv3d_dw_exact(const xconv3d_desc *v, const void *dY_dev, const v
         }
     }
     P.part = part0;
+    if (reduce_expand_fused(P, false, true, d->C_in, d->r, 0)) {
+        XC_LAUNCH(K_REDUCE, st, launch_reduce_expand(P, nullptr, true, dW_dev, d->C_in, d->r, false, 0, 0, v->kD, st));
+        return XCONV_OK;
+    }
     XC_LAUNCH(K_REDUCE, st, launch_reduce(P, st, nullptr, 0, 0, 0, T3, v->kD));
     XC_LAUNCH(K_EXPAND, st, launch_expand(P, nullptr, dW_dev, d->C_in, d->r, st, false, T3, v->kD * P.K2));
     return XCONV_OK;

@@ -335,6 +335,19 @@ def _three_runs_agree(d, X, dY, dtype, C_out, C_in):
     assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
 
 
+# The second pass (sum of the split partial tiles, then Z / r or 1/nnz, Alg. 1 backward step 4) runs as one launch on
+# small layers and as two on large ones: both routes on the same layers, whatever their size.
+@pytest.mark.parametrize("fused", ["0", "1"], ids=["two-launches", "one-launch"])
+def test_second_pass_routes(fused, monkeypatch):
+    monkeypatch.setenv("XCONV_FUSED_PASS2", fused)
+    for e in (EDGE[0], WS_EDGE[1], ROW_EDGE[7], WS32_EDGE[4], ("c2-like", 16, 64, 64, 32, 32, 3, 1, 1, 16, "gaussian", "f32"),
+              ("wide-cin-exact", 4, 300, 40, 8, 8, 3, 1, 1, 24, "rademacher", "f16")):
+        run_edge(e)
+    for e in SPARSE[:2]:
+        test_block_sparse_probes(e, False)
+        test_block_sparse_probes(e, True)
+
+
 # ---------------------------------------------------------------------------
 # block-sparse probing vectors with the 1/nnz scaling (Eq. (7), Eq. (8))
 # ---------------------------------------------------------------------------
@@ -479,6 +492,31 @@ def test_full_rank_hadamard_probe_gives_exact_gradient_on_gpu():
     torch.cuda.synchronize()
     exact = xo.dw_exact(dY, X, 3, 3, (1, 1), (1, 1))
     assert rel_max(dW.cpu().numpy().astype(np.float64), exact) <= 1e-5
+
+
+def test_generic_kernel_repeats_its_result_300_times():
+    # A layer of the generic correlation kernel (fp32, 1x1 kernel, two 16-row tiles per wave, odd output width) whose
+    # result used to differ about once in a hundred launches: a register copy had been scheduled in front of the wait
+    # for the LDS read that fills it.  300 launches, every result equal to the first bit for bit, the first checked
+    # against the oracle.
+    say("generic kernel, 300 launches")
+    B, C_in, C_out, H, W, r = 12, 64, 64, 9, 36, 32
+    X = synth.draw((B, C_in, H, W), 6041, "relu_normal", 1.0, "f32")
+    dY = synth.draw((B, C_out, 11, 19), 7041, "normal", 1e-2, "f32")
+    d = xb.make_desc(B, C_in, C_out, H, W, (1, 1), (1, 2), (1, 1), r, "f32", "rademacher", 8041)
+    assert xb.xconv_plan_info(d, xb.XCONV_OP_EXACT)["ws"] == 0
+    Xd, dYd = xb.to_device(X, "f32", DEV), xb.to_device(dY, "f32", DEV)
+    ws = xb.alloc_ws(d, xb.XCONV_OP_EXACT, DEV)
+    first = None
+    for it in range(300):
+        dW = torch.full((C_out, C_in, 1, 1), float("nan"), dtype=torch.float32, device=DEV)
+        xb.xconv_dw_exact(d, dYd, Xd, dW, ws)
+        if first is None:
+            first = dW
+        else:
+            assert torch.equal(dW, first), it
+    want = xo.dw_exact(dY, X, 1, 1, (1, 2), (1, 1))
+    assert rel_max(first.cpu().numpy().astype(np.float64), want) <= 1e-4
 
 
 def test_estimate_is_deterministic_and_overwrites():

@@ -115,6 +115,13 @@ def test_volumetric_layers_through_the_dy_copy(e, monkeypatch):
     assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("fused", ["0", "1"], ids=["two-launches", "one-launch"])
+def test_volumetric_second_pass_routes(fused, monkeypatch):
+    monkeypatch.setenv("XCONV_FUSED_PASS2", fused)
+    for e in VOL[:4]:
+        run_volume(e)
+
+
 def test_volumetric_estimate_is_deterministic():
     _, a = run_volume(VOL[2])
     _, b = run_volume(VOL[2])
