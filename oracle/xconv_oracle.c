@@ -549,3 +549,41 @@ void xo_conv_fwd(const float *X, const double *Wt, double *Y,
               }
           }
 }
+
+/* ------------------------------------------------------------------------ */
+/* Input gradient of the layer (Sec. 2: standard backpropagation is kept for  */
+/* everything but the weight gradient, so dX is the exact transposed          */
+/* convolution):                                                              */
+/*   dX[b,n,iy,ix] = sum_{m,ky,kx} dY[b,m,oy,ox] W[m,n,ky,kx]                 */
+/* over the (oy, ox) with oy*sh + ky - ph = iy and ox*sw + kx - pw = ix.      */
+/* Written as a gather over the outputs of every input pixel, so that it      */
+/* shares no loop structure with xo_conv_fwd (a scatter over the inputs); the */
+/* two are tied together by <dX, V> = <dY, conv(V, W)> in the tests.           */
+/* dY [B,C_out,Ho,Wo], Wt [C_out,C_in,kH,kW] (double), dX [B,C_in,H,W] (double) */
+/* ------------------------------------------------------------------------ */
+void xo_dx(const float *dY, const double *Wt, double *dX,
+           int B, int C_in, int C_out, int H, int W,
+           int kH, int kW, int sh, int sw, int ph, int pw)
+{
+    int Ho = xo_out_extent(H, kH, sh, ph);
+    int Wo = xo_out_extent(W, kW, sw, pw);
+    for (int b = 0; b < B; ++b)
+      for (int n = 0; n < C_in; ++n)
+        for (int iy = 0; iy < H; ++iy)
+          for (int ix = 0; ix < W; ++ix) {
+              double s = 0.0;
+              for (int ky = 0; ky < kH; ++ky) {
+                  int ty = iy + ph - ky;
+                  if (ty < 0 || ty % sh != 0 || ty / sh >= Ho) continue;
+                  for (int kx = 0; kx < kW; ++kx) {
+                      int tx = ix + pw - kx;
+                      if (tx < 0 || tx % sw != 0 || tx / sw >= Wo) continue;
+                      for (int m = 0; m < C_out; ++m)
+                          s += (double)dY[(((size_t)b * C_out + m) * Ho + ty / sh) * Wo + tx / sw] *
+                               Wt[(((size_t)m * C_in + n) * kH + ky) * kW + kx];
+                  }
+              }
+              dX[(((size_t)b * C_in + n) * H + iy) * W + ix] = s;
+          }
+}
+

@@ -77,6 +77,8 @@ def lib():
         L.xo_pixel_dw_estimate.restype = None
         L.xo_pixel_dw_estimate.argtypes = [_c_f32p, _c_f32p, _c_f32p, _c_f64p] + [ctypes.c_int] * 12
         L.xo_conv_fwd.argtypes = [_c_f32p, _c_f64p, _c_f64p] + [ctypes.c_int] * 11
+        L.xo_dx.restype = None
+        L.xo_dx.argtypes = [_c_f32p, _c_f64p, _c_f64p] + [ctypes.c_int] * 11
         _LIB = L
     return _LIB
 
@@ -223,6 +225,18 @@ def dw_exact_at(dY, X, idx, kH, kW, stride=(1, 1), pad=(0, 0)):
                          out.ctypes.data_as(_c_f64p), B, C_in, C_out, H, W,
                          kH, kW, stride[0], stride[1], pad[0], pad[1])
     return out
+
+
+def dx(dY, Wt, H, W, stride=(1, 1), pad=(0, 0)):
+    """Exact input gradient dX [B, C_in, H, W] of the layer (transposed convolution of dY with the weights)."""
+    dY, dYp = _f32(dY)
+    Wt, Wp = _f64(Wt)
+    B, C_out, Ho, Wo = dY.shape
+    _, C_in, kH, kW = Wt.shape
+    assert Wt.shape[0] == C_out and Ho == out_extent(H, kH, stride[0], pad[0]) and Wo == out_extent(W, kW, stride[1], pad[1])
+    dX = np.empty((B, C_in, H, W), dtype=np.float64)
+    lib().xo_dx(dYp, Wp, dX.ctypes.data_as(_c_f64p), B, C_in, C_out, H, W, kH, kW, stride[0], stride[1], pad[0], pad[1])
+    return dX
 
 
 def conv_fwd(X, Wt, stride=(1, 1), pad=(0, 0)):

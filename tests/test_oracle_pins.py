@@ -204,6 +204,56 @@ def test_dw_exact_adjoint_identity():
         assert abs(lhs - rhs) < 1e-9 * max(1.0, abs(lhs))
 
 
+# ---------------------------------------------------------------------------
+# input gradient (Sec. 2: backpropagation through the layer stays exact; only dW is estimated)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("case", TINY + [(3, 5, 4, 9, 11, 3, 3, (2, 2), (1, 1)), (2, 4, 6, 12, 12, 3, 3, (1, 1), (1, 1)),
+                                         (2, 3, 4, 10, 9, 3, 3, (3, 2), (0, 1))])
+def test_dx_against_torch_autograd(case):
+    B, C_in, C_out, H, W, kH, kW, stride, pad = case
+    rng = np.random.default_rng(31)
+    Ho, Wo = xo.out_extent(H, kH, stride[0], pad[0]), xo.out_extent(W, kW, stride[1], pad[1])
+    dY = rng.standard_normal((B, C_out, Ho, Wo)).astype(np.float32)
+    Wt = rng.standard_normal((C_out, C_in, kH, kW))
+    x = torch.zeros((B, C_in, H, W), dtype=torch.float64, requires_grad=True)
+    y = F.conv2d(x, torch.from_numpy(Wt), stride=stride, padding=pad)
+    y.backward(torch.from_numpy(dY).double())
+    assert np.allclose(xo.dx(dY, Wt, H, W, stride, pad), x.grad.numpy(), atol=1e-11)
+
+
+def test_dx_adjoint_identity_with_the_forward_convolution():
+    # <dX, V> = <dY, conv(V, W)> for any V: the transposed convolution is the adjoint of the forward one, which is
+    # written as a scatter over the inputs and pinned by brute force above
+    rng = np.random.default_rng(32)
+    B, C_in, C_out, H, W, k = 3, 4, 5, 10, 9, 3
+    for stride, pad in (((1, 1), (1, 1)), ((2, 2), (1, 1)), ((1, 2), (0, 1)), ((3, 3), (2, 2))):
+        V = rng.standard_normal((B, C_in, H, W)).astype(np.float32)
+        Wt = rng.standard_normal((C_out, C_in, k, k))
+        Y = xo.conv_fwd(V, Wt, stride, pad)
+        dY = rng.standard_normal(Y.shape).astype(np.float32)
+        lhs = np.sum(xo.dx(dY, Wt, H, W, stride, pad) * V.astype(np.float64))
+        rhs = np.sum(dY.astype(np.float64) * Y)
+        assert abs(lhs - rhs) < 1e-9 * max(1.0, abs(rhs))
+
+
+def test_dx_special_cases():
+    rng = np.random.default_rng(33)
+    # k = 1, stride 1: dX[b,n,p] = sum_m W[m,n] dY[b,m,p]
+    B, C_in, C_out, H, W = 2, 3, 4, 5, 6
+    dY = rng.standard_normal((B, C_out, H, W)).astype(np.float32)
+    Wt = rng.standard_normal((C_out, C_in, 1, 1))
+    want = np.einsum("mn,bmyx->bnyx", Wt[:, :, 0, 0], dY.astype(np.float64))
+    assert np.allclose(xo.dx(dY, Wt, H, W), want, atol=1e-12)
+    # a single non-zero residual at (oy, ox) with stride 2: dX is the kernel stamped at (oy*2 - p, ox*2 - p)
+    dY = np.zeros((1, 1, 4, 4), dtype=np.float32)
+    dY[0, 0, 1, 2] = 2.0
+    Wt = rng.standard_normal((1, 2, 3, 3))
+    got = xo.dx(dY, Wt, 8, 8, (2, 2), (1, 1))
+    want = np.zeros((1, 2, 8, 8))
+    want[0, :, 1:4, 3:6] = 2.0 * Wt[0]
+    assert np.allclose(got, want, atol=1e-12)
+
+
 def test_dw_exact_special_cases():
     rng = np.random.default_rng(5)
     # k = 1: the gradient is the plain matrix product  sum_{b,p} dY[b,m,p] X[b,n,p]
