@@ -157,6 +157,19 @@ def measure_config(cfg, steps, warmup, dev, with_exact=False, nhwc=False):
         out["exact_ms"] = ms_x
         out["exact_gflops"] = alg["exact_flops"] / ms_x / 1e6
         out["estimate_vs_exact_speedup"] = ms_x / ms_step
+        # the rest of the layer on the library's own kernels (forward convolution, exact input gradient)
+        if not nhwc:
+            import torch
+            td = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[cfg.dtype]
+            Wd = (torch.randn(cfg.C_out, cfg.C_in, cfg.k, cfg.k, device=dev) / (cfg.C_in * cfg.k * cfg.k) ** 0.5).to(td)
+            Yd = torch.empty((cfg.B, cfg.C_out, cfg.Ho, cfg.Wo), dtype=td, device=dev)
+            dXd = torch.empty((cfg.B, cfg.C_in, cfg.H, cfg.W), dtype=td, device=dev)
+            n_fast = max(steps // 10, 3)
+            ms_f = time_region(lambda i: xb.xconv_conv_fwd(L.desc, L.sets[i % len(L.sets)]["X"], Wd, Yd), n_fast, 2)
+            ms_b = time_region(lambda i: xb.xconv_dx_exact(L.desc, L.sets[i % len(L.sets)]["dY"], Wd, dXd), n_fast, 2)
+            out["conv_fwd_ms"], out["dx_exact_ms"] = ms_f, ms_b
+            out["conv_fwd_gflops"] = alg["exact_flops"] / ms_f / 1e6
+            out["dx_exact_gflops"] = alg["exact_flops"] / ms_b / 1e6
         # the framework's own exact weight gradient on the same tensors (MIOpen through torch), for context only
         if not nhwc:
             try:

@@ -152,6 +152,22 @@ xconv_status xconv_dw_estimate_static(const xconv_desc *desc, const void *dY_dev
 xconv_status xconv_dw_exact(const xconv_desc *desc, const void *dY_dev, const void *X_dev,
                             float *dW_dev, void *ws_dev, size_t ws_bytes, void *stream);
 
+/* The rest of the layer (Sec. 2: the forward pass and the backpropagation through the layer
+ * stay exact, only the weight gradient is estimated; Alg. 1 forward step 1), so that a layer can
+ * run on this library alone:
+ *
+ *   xconv_conv_fwd   Y[b,m,oy,ox]  = sum_{n,ky,kx} W[m,n,ky,kx] X[b,n, oy*sh+ky-ph, ox*sw+kx-pw]
+ *   xconv_dx_exact   dX[b,n,iy,ix] = sum_{m,ky,kx} W[m,n,ky,kx] dY[b,m,oy,ox]
+ *                                    over the (oy, ox) with oy*sh+ky-ph = iy, ox*sw+kx-pw = ix
+ *
+ * (zero padding, cross-correlation, no bias).  X, Y, dY, dX in desc->dtype and desc->layout
+ * ([B,C,H,W] or [B,H,W,C]); W_dev: [C_out,C_in,kH,kW] in desc->dtype, row-major, for both layouts.
+ * Sums are fp32, the output is rounded once (nearest even) and overwritten.  No scratch; one
+ * kernel launch each; desc->r, probe and seed are ignored.  Pointers aligned to the element size.
+ * XCONV_EUNSUPPORTED when an image of X or Y has more than 2^31-1 elements. */
+xconv_status xconv_conv_fwd(const xconv_desc *desc, const void *X_dev, const void *W_dev, void *Y_dev, void *stream);
+xconv_status xconv_dx_exact(const xconv_desc *desc, const void *dY_dev, const void *W_dev, void *dX_dev, void *stream);
+
 /* Launch plan of the correlation kernel for op XCONV_OP_ESTIMATE or
  * XCONV_OP_EXACT, for reports and tests (host only).  Fills out[0..15] with
  * K-splits S, steps NS, rows per step RB, columns per step CW, waves along

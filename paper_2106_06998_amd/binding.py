@@ -71,6 +71,10 @@ def lib():
         L.xconv_dw_estimate.argtypes = [P, vp, vp, vp, vp, vp, sz, vp]
         L.xconv_dw_exact.restype = i32
         L.xconv_dw_exact.argtypes = [P, vp, vp, vp, vp, sz, vp]
+        L.xconv_conv_fwd.restype = i32
+        L.xconv_conv_fwd.argtypes = [P, vp, vp, vp, vp]
+        L.xconv_dx_exact.restype = i32
+        L.xconv_dx_exact.argtypes = [P, vp, vp, vp, vp]
         L.xconv_dw_estimate_static.restype = i32
         L.xconv_dw_estimate_static.argtypes = [P, vp, vp, vp, vp, vp]
         L.xconv_static_scratch_bytes.restype = sz
@@ -204,6 +208,14 @@ def xconv_probe_fwd(desc, X_dev, Xt_dev, Z_dev=None, ws_dev=None, stream=None):
 def xconv_dw_estimate(desc, dY_dev, Xt_dev, Z_dev, dW_dev, ws_dev, stream=None):
     _check(lib().xconv_dw_estimate(ctypes.byref(desc), _ptr(dY_dev), _ptr(Xt_dev), _ptr(Z_dev), _ptr(dW_dev),
                                    _ptr(ws_dev), _nbytes(ws_dev), _stream(stream)), "xconv_dw_estimate")
+
+
+def xconv_conv_fwd(desc, X_dev, W_dev, Y_dev, stream=None):
+    _check(lib().xconv_conv_fwd(ctypes.byref(desc), _ptr(X_dev), _ptr(W_dev), _ptr(Y_dev), _stream(stream)), "xconv_conv_fwd")
+
+
+def xconv_dx_exact(desc, dY_dev, W_dev, dX_dev, stream=None):
+    _check(lib().xconv_dx_exact(ctypes.byref(desc), _ptr(dY_dev), _ptr(W_dev), _ptr(dX_dev), _stream(stream)), "xconv_dx_exact")
 
 
 def xconv_dw_estimate_static(desc, dY_dev, Xt_dev, Z_dev, dW_dev, stream=None):

@@ -31,7 +31,8 @@ enum KernelId {
     K_SCALE = 12,
     K_PIXEL_FWD = 13,
     K_RELU = 14,
-    K_COUNT = 15
+    K_CONV = 15,
+    K_COUNT = 16
 };
 
 // Where the probe output of a voxel goes in Xt.  sd == 0: plain order, pixel `first` of the
@@ -259,5 +260,21 @@ __device__ inline void draw_z_slice(float *zout, int nz, int dist, uint64_t seed
     const ProbeGen gen = probe_gen(dist, seed);
     for (int i = wg * (int)blockDim.x + (int)threadIdx.x; i < nz; i += nwg * (int)blockDim.x) zout[i] = probe_entry(gen, (uint64_t)i);
 }
+
+// ---- forward convolution / exact input gradient as one implicit GEMM (conv_kernels.hip) ----
+struct ConvGemmParams {
+    const void *in;    // activation-like tensor the contraction runs over (X, or dY for the input gradient)
+    const void *w;     // weights [C_out, C_in, kH, kW] in the storage type
+    void *out;         // Y, or dX
+    int Cin, Cout;     // contraction channels and output channels of this product
+    int Hi, Wi;        // extent of `in`
+    int Ho, Wo;        // extent of `out`
+    int kH, kW, sh, sw, ph, pw;
+    int transposed;    // 0: src = (y*sh + ky - ph, x*sw + kx - pw); 1: src = ((y + ph - ky) / sh, ...) where that divides
+    long long npix;    // B * Ho * Wo
+    long long in_sb, out_sb;                              // element strides: image,
+    int in_sc, in_sy, in_sx, out_sc, out_sy, out_sx;      // channel, row, column
+    int w_sco, w_sci;                                     // weights: output channel of the product, contraction channel
+};
 
 }  // namespace xc

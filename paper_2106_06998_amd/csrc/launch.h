@@ -97,6 +97,9 @@ bool plan_corr_ws32(WsParams &P, int dtype, int B, int C_out, int H, int W, int 
 size_t corr_ws32_lds_bytes(const WsParams &P);
 hipError_t launch_corr_ws32(const WsParams &P, hipStream_t st);
 
+// conv_kernels.hip: forward convolution and exact input gradient (one implicit-GEMM kernel, see ConvGemmParams)
+hipError_t launch_conv_gemm(int dtype, const ConvGemmParams &P, hipStream_t st);
+
 // pixel_kernels.hip: Xbar[b, j] = sum_k X[b, k] Zimg[j, k] (forward product of the pixel x channel probes)
 bool pixel_fwd_ok(int dtype, long long K, const void *X);
 size_t pixel_fwd_partial_bytes(int dtype, long long K, int B, int r);

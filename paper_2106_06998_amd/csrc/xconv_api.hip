@@ -549,6 +549,61 @@ xconv_status xconv_dw_exact(const xconv_desc *d, const void *dY_dev, const void 
     return exact_impl(d, dY_dev, X_dev, nullptr, dW_dev, ws_dev, ws_bytes, stream);
 }
 
+// ---- forward convolution and exact input gradient (Sec. 2; Alg. 1 forward step 1) ----
+static void conv_strides(int layout, int C, int H, int W, long long &sb, int &sc, int &sy, int &sx)
+{
+    if (layout == XCONV_NHWC) { sb = (long long)H * W * C; sc = 1; sy = W * C; sx = C; }
+    else { sb = (long long)C * H * W; sc = H * W; sy = W; sx = 1; }
+}
+
+xconv_status xconv_conv_fwd(const xconv_desc *d, const void *X_dev, const void *W_dev, void *Y_dev, void *stream)
+{
+    xconv_status s = xconv_check_desc(d);
+    if (s != XCONV_OK) return s;
+    if (!X_dev || !W_dev || !Y_dev) return XCONV_EINVAL;
+    const uintptr_t em = elem_bytes(d->dtype) - 1;
+    if ((reinterpret_cast<uintptr_t>(X_dev) & em) || (reinterpret_cast<uintptr_t>(W_dev) & em) || (reinterpret_cast<uintptr_t>(Y_dev) & em)) return XCONV_EINVAL;
+    const int Ho = out_extent(d->H, d->kH, d->stride_h, d->pad_h), Wo = out_extent(d->W, d->kW, d->stride_w, d->pad_w);
+    if ((long long)d->C_in * d->H * d->W > 0x7fffffffLL || (long long)d->C_out * Ho * Wo > 0x7fffffffLL) return XCONV_EUNSUPPORTED;
+    ConvGemmParams P{};
+    P.in = X_dev; P.w = W_dev; P.out = Y_dev;
+    P.Cin = d->C_in; P.Cout = d->C_out; P.Hi = d->H; P.Wi = d->W; P.Ho = Ho; P.Wo = Wo;
+    P.kH = d->kH; P.kW = d->kW; P.sh = d->stride_h; P.sw = d->stride_w; P.ph = d->pad_h; P.pw = d->pad_w;
+    P.transposed = 0;
+    P.npix = (long long)d->B * Ho * Wo;
+    conv_strides(d->layout, d->C_in, d->H, d->W, P.in_sb, P.in_sc, P.in_sy, P.in_sx);
+    conv_strides(d->layout, d->C_out, Ho, Wo, P.out_sb, P.out_sc, P.out_sy, P.out_sx);
+    P.w_sco = d->C_in * d->kH * d->kW;
+    P.w_sci = d->kH * d->kW;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    XC_LAUNCH(K_CONV, st, launch_conv_gemm(d->dtype, P, st));
+    return XCONV_OK;
+}
+
+xconv_status xconv_dx_exact(const xconv_desc *d, const void *dY_dev, const void *W_dev, void *dX_dev, void *stream)
+{
+    xconv_status s = xconv_check_desc(d);
+    if (s != XCONV_OK) return s;
+    if (!dY_dev || !W_dev || !dX_dev) return XCONV_EINVAL;
+    const uintptr_t em = elem_bytes(d->dtype) - 1;
+    if ((reinterpret_cast<uintptr_t>(dY_dev) & em) || (reinterpret_cast<uintptr_t>(W_dev) & em) || (reinterpret_cast<uintptr_t>(dX_dev) & em)) return XCONV_EINVAL;
+    const int Ho = out_extent(d->H, d->kH, d->stride_h, d->pad_h), Wo = out_extent(d->W, d->kW, d->stride_w, d->pad_w);
+    if ((long long)d->C_in * d->H * d->W > 0x7fffffffLL || (long long)d->C_out * Ho * Wo > 0x7fffffffLL) return XCONV_EUNSUPPORTED;
+    ConvGemmParams P{};
+    P.in = dY_dev; P.w = W_dev; P.out = dX_dev;
+    P.Cin = d->C_out; P.Cout = d->C_in; P.Hi = Ho; P.Wi = Wo; P.Ho = d->H; P.Wo = d->W;
+    P.kH = d->kH; P.kW = d->kW; P.sh = d->stride_h; P.sw = d->stride_w; P.ph = d->pad_h; P.pw = d->pad_w;
+    P.transposed = 1;
+    P.npix = (long long)d->B * d->H * d->W;
+    conv_strides(d->layout, d->C_out, Ho, Wo, P.in_sb, P.in_sc, P.in_sy, P.in_sx);
+    conv_strides(d->layout, d->C_in, d->H, d->W, P.out_sb, P.out_sc, P.out_sy, P.out_sx);
+    P.w_sco = d->kH * d->kW;                 // the product's output channel is the layer's input channel n
+    P.w_sci = d->C_in * d->kH * d->kW;       // and it contracts over the layer's output channels m
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    XC_LAUNCH(K_CONV, st, launch_conv_gemm(d->dtype, P, st));
+    return XCONV_OK;
+}
+
 xconv_status xconv_plan_info(const xconv_desc *d, int op, int32_t *out)
 {
     xconv_status s = xconv_check_desc(d);
@@ -1098,6 +1153,7 @@ const char *xconv_prof_kernel_name(int id)
     case K_UNPACK: return "unpack_kernel";
     case K_REPACK: return "repack_planes_kernel";
     case K_PACK_Z: return "pack_z_kernel";
+    case K_CONV: return "conv_gemm_kernel";
     case K_ZERO_GAPS: return "zero_gap_slices_kernel";
     case K_GEN_ZIMG: return "gen_zimg_kernel";
     case K_SCALE: return "scale_kernel";

@@ -6,8 +6,11 @@ What the layer changes is what is kept between the forward and the backward pass
 instead of the input X it stores the probe output, r/C_in of X for probes over the channels
 (mode "channel"), B*r numbers for probes over pixels and channels (mode "multi", Eq. (6)), B*C_in*r
 for independent probing (mode "independent"); the weight gradient then comes from the matching
-estimate entry point of the library.  The forward convolution, the input gradient and the bias
-gradient are the framework's own operators and are exact; they are not part of this library.
+estimate entry point of the library.  For 2-D layers the forward convolution and the input gradient
+are exact and run on the library's own kernels as well (xconv_conv_fwd, xconv_dx_exact;
+engine="library", the default), or on the framework's operators (engine="framework"); the bias is
+added, and its gradient summed, by the framework.  Volumetric layers use the framework's forward
+convolution and input gradient.
 
 Z is drawn from a seed that changes with every forward call (Algorithm 1: seed and probing matrix
 are redrawn for each layer and iteration); nothing but the seed is kept of it.
@@ -48,10 +51,34 @@ def _as_layout(t, layout):
     return _aligned(t.contiguous())
 
 
+def _library_conv_ok(x, weight):
+    return x.is_cuda and x.dtype in _DTYPE and weight.dtype == x.dtype and weight.device == x.device
+
+
+def _empty_like_layout(shape, dtype, device, layout):
+    return torch.empty(shape, dtype=dtype, device=device,
+                       memory_format=torch.channels_last if layout == xb.XCONV_NHWC else torch.contiguous_format)
+
+
 class _XConvFunction(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, x, weight, bias, stride, padding, r, probe, mode, seed):
-        y = F.conv2d(x, weight, bias, stride, padding)
+    def forward(ctx, x, weight, bias, stride, padding, r, probe, mode, seed, engine):
+        ctx.own = engine == "library" and _library_conv_ok(x, weight)
+        if ctx.own:
+            # forward convolution on the library's kernel (Alg. 1 forward step 1)
+            lay, xs0 = _layout_of(x.detach())
+            B, C_in, H, W = x.shape
+            d0 = xb.make_desc(B, C_in, weight.shape[0], H, W, tuple(weight.shape[2:]), stride, padding, 1, _DTYPE[x.dtype],
+                              "rademacher", 0, lay)
+            Ho = (H + 2 * padding[0] - weight.shape[2]) // stride[0] + 1
+            Wo = (W + 2 * padding[1] - weight.shape[3]) // stride[1] + 1
+            y = _empty_like_layout((B, weight.shape[0], Ho, Wo), x.dtype, x.device, lay)
+            with torch.cuda.device(x.device):
+                xb.xconv_conv_fwd(d0, xs0, weight.detach().contiguous(), y)
+            if bias is not None:
+                y += bias.detach().view(1, -1, 1, 1)
+        else:
+            y = F.conv2d(x, weight, bias, stride, padding)
         ctx.has_state = False
         ctx.stride, ctx.padding, ctx.x_shape = stride, padding, x.shape
         ctx.has_bias = bias is not None
@@ -91,7 +118,17 @@ class _XConvFunction(torch.autograd.Function):
         weight = saved[0]
         dx = dw = db = None
         if ctx.needs_input_grad[0]:
-            dx = torch.nn.grad.conv2d_input(ctx.x_shape, weight, dy, stride=ctx.stride, padding=ctx.padding)
+            if ctx.own and dy.dtype == weight.dtype:
+                # exact input gradient on the library's kernel (Sec. 2: backpropagation through the layer stays exact)
+                lay, dys0 = _layout_of(dy.detach())
+                B, C_in, H, W = ctx.x_shape
+                d0 = xb.make_desc(B, C_in, weight.shape[0], H, W, tuple(weight.shape[2:]), ctx.stride, ctx.padding, 1,
+                                  _DTYPE[dy.dtype], "rademacher", 0, lay)
+                dx = _empty_like_layout(tuple(ctx.x_shape), dy.dtype, dy.device, lay)
+                with torch.cuda.device(dy.device):
+                    xb.xconv_dx_exact(d0, dys0, weight.detach().contiguous(), dx)
+            else:
+                dx = torch.nn.grad.conv2d_input(ctx.x_shape, weight, dy, stride=ctx.stride, padding=ctx.padding)
         if ctx.has_state and ctx.needs_input_grad[1]:
             state, d, dev = saved[1], ctx.desc, dy.device
             dys = _as_layout(dy.to(ctx.x_dtype), ctx.layout)
@@ -109,7 +146,7 @@ class _XConvFunction(torch.autograd.Function):
             dw = dw32.to(weight.dtype)
         if ctx.has_bias and ctx.needs_input_grad[2]:
             db = dy.sum(dim=(0, 2, 3))
-        return dx, dw, db, None, None, None, None, None, None
+        return dx, dw, db, None, None, None, None, None, None, None
 
 
 class XConv2d(torch.nn.Conv2d):
@@ -120,11 +157,12 @@ class XConv2d(torch.nn.Conv2d):
     and channels, Eq. (6), state B*r numbers) or "independent" (every input channel on its own).
     Supported: dilation 1, groups 1, zero padding given as numbers.  In eval mode, or when the
     weight needs no gradient, it is a plain convolution.  `last_seed` is the seed of the latest
-    training forward call.
+    training forward call.  engine: "library" runs the forward convolution and the exact input
+    gradient on this library's kernels too, "framework" on torch's operators.
     """
 
     def __init__(self, in_channels, out_channels, kernel_size, r=16, stride=1, padding=0, bias=True, probe="rademacher",
-                 mode="channel", base_seed=0, **kw):
+                 mode="channel", base_seed=0, engine="library", **kw):
         super().__init__(in_channels, out_channels, kernel_size, stride=stride, padding=padding, bias=bias, **kw)
         if _pair(self.dilation) != (1, 1) or self.groups != 1 or self.padding_mode != "zeros" or isinstance(self.padding, str):
             raise ValueError("XConv2d: dilation 1, groups 1 and numeric zero padding only")
@@ -132,14 +170,17 @@ class XConv2d(torch.nn.Conv2d):
             raise ValueError("XConv2d: mode must be one of %s" % (MODES,))
         if probe not in ("rademacher", "gaussian"):
             raise ValueError("XConv2d: probe must be 'rademacher' or 'gaussian'")
+        if engine not in ("library", "framework"):
+            raise ValueError("XConv2d: engine must be 'library' or 'framework'")
         self.r, self.probe, self.mode, self.base_seed, self.last_seed = int(r), probe, mode, int(base_seed), None
+        self.engine = engine
 
     def forward(self, x):
         if not (self.training and torch.is_grad_enabled() and self.weight.requires_grad):
             return super().forward(x)
         self.last_seed = (self.base_seed * 0x9E3779B1 + next(_calls)) & 0x7FFFFFFFFFFFFFFF
         return _XConvFunction.apply(x, self.weight, self.bias, _pair(self.stride), _pair(self.padding), self.r, self.probe,
-                                    self.mode, self.last_seed)
+                                    self.mode, self.last_seed, self.engine)
 
     def extra_repr(self):
         return super().extra_repr() + ", r=%d, probe=%s, mode=%s" % (self.r, self.probe, self.mode)
@@ -273,7 +314,7 @@ class XConv3d(torch.nn.Conv3d):
         return super().extra_repr() + ", r=%d, probe=%s" % (self.r, self.probe)
 
 
-def convert_net(model, r=16, probe="rademacher", mode="channel", min_in_channels=None, relu=False):
+def convert_net(model, r=16, probe="rademacher", mode="channel", min_in_channels=None, relu=False, engine="library"):
     """Replaces, in place, every torch.nn.Conv2d (and, in mode "channel", torch.nn.Conv3d) of `model` that the layer supports (dilation 1,
     groups 1, zero padding, and at least `min_in_channels` input channels; default: more than r in
     mode "channel", where fewer channels than probing vectors save nothing) by an XConv2d that
@@ -306,7 +347,7 @@ def convert_net(model, r=16, probe="rademacher", mode="channel", min_in_channels
                     or child.in_channels < min_in_channels):
                 continue
             new = XConv2d(child.in_channels, child.out_channels, child.kernel_size, r=r, stride=child.stride, padding=child.padding,
-                          bias=child.bias is not None, probe=probe, mode=mode, base_seed=n + 1,
+                          bias=child.bias is not None, probe=probe, mode=mode, base_seed=n + 1, engine=engine,
                           device=child.weight.device, dtype=child.weight.dtype)
             new.weight, new.bias = child.weight, child.bias
             new.train(child.training)
