@@ -62,6 +62,15 @@ struct SliceMap {
 __host__ __device__ inline int round_up(int a, int b) { return (a + b - 1) / b * b; }
 __host__ __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
+// Layout of one fp32 tile of correlation sums (a K-split's partial tile, or the reduced tile): [K2][MP/4][JP][4].
+// Four consecutive output channels of one (offset, column) are a 16-byte element, and the JP columns of such a
+// channel quad are contiguous: the lanes of a matrix-instruction result (one column each, four rows per register
+// group) store runs of 16-byte elements, and the second pass reads a quad's columns as one run.
+__host__ __device__ inline size_t tile_index(int o, int j, int m, int JP, int MP)
+{
+    return ((((size_t)o * (size_t)(MP >> 2) + (size_t)(m >> 2)) * (size_t)JP + (size_t)j) << 2) + (size_t)(m & 3);
+}
+
 // ---- storage-type conversions (device) ------------------------------------
 __device__ inline uint16_t f32_to_bf16_rne(float f)
 {
@@ -191,7 +200,7 @@ __host__ __device__ inline float probe_value(const ProbeGen &g, uint64_t idx)
 struct CorrParams {
     const void *dY;    // [B, C_out, Ho, Wo] storage dtype
     const void *A;     // channels-last activation-like tensor [B, H, W, CS] storage dtype (Xt, or X for the exact path)
-    float *part;       // [S, K2, JP, MP] fp32 partial sums
+    float *part;       // [S] partial tiles of fp32 sums, each in the layout of tile_index()
     int B, C_out, H, W, Ho, Wo;
     int kH, kW, sh, sw, ph, pw;
     int CS;            // channel stride of A (multiple of 16)
@@ -224,7 +233,7 @@ struct CorrParams {
 struct WsParams {
     const void *dY;    // [B, C_out, Ho, Wo] storage dtype
     const void *A;     // channels-last [B, H, W, CS] storage dtype
-    float *part;       // [S, K2, JP, MP] fp32 partial sums
+    float *part;       // [S] partial tiles of fp32 sums, each in the layout of tile_index()
     int B, C_out, H, W, Ho, Wo;
     int kH, kW, sh, sw, ph, pw;
     int CS, NBG;            // channel stride of A; groups of 8 images

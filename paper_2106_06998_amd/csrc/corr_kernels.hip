@@ -615,9 +615,9 @@ __global__ __launch_bounds__(kThreads, ((DT == XCONV_F32 && MT <= 2) ? 2 : 1)) v
 #pragma unroll
         for (int o = 0; o < NOFF; ++o) {
             if (o < noff) {
-                float *dst = P.part + (((size_t)blockIdx.x * P.K2 + (o_first + o)) * P.JP + jcol) * P.MP + m0 + (wm * MT) * 16 + 4 * g;
+                float *dst = P.part + (size_t)blockIdx.x * P.K2 * P.JP * P.MP + tile_index(o_first + o, jcol, m0 + (wm * MT) * 16 + 4 * g, P.JP, P.MP);
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) *reinterpret_cast<f32x4 *>(dst + mt * 16) = acc[mt][o];
+                for (int mt = 0; mt < MT; ++mt) *reinterpret_cast<f32x4 *>(dst + (size_t)16 * mt * P.JP) = acc[mt][o];   // 16 rows = four channel quads
             }
         }
     }
@@ -671,7 +671,7 @@ __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const f32x4 *
 //   dW[m,n,o] = (1/r) sum_j Z[n,j] T[o,j,m],
 // one small fp32 GEMM per offset (rows m, columns n, contraction over the r probes) on the
 // 16x16x4 matrix instruction.  One wave owns a 16 x 16 tile of (m, n) and OG consecutive
-// offsets: the A operand (T, channel-contiguous) and the B operand (Z rows) are read straight
+// offsets: the A operand (T, in the layout of tile_index) and the B operand (Z rows) are read straight
 // from global memory, and a lane ends up with all OG offsets of its (m, n) pairs, which are
 // adjacent in dW.
 // ---------------------------------------------------------------------------
@@ -691,26 +691,28 @@ __global__ __launch_bounds__(64) void expand_kernel(const float *__restrict__ T,
 #pragma unroll
     for (int o = 0; o < OG; ++o) {
         const int oo = (o0 + o < K2) ? o0 + o : K2 - 1;  // offsets past the end repeat the last one and are not stored
-        tcol[o] = T + (size_t)oo * JP * MP + mt * 16 + l16;
+        tcol[o] = T + tile_index(oo, 0, mt * 16 + l16, JP, MP);
     }
     f32x4 acc[OG];
 #pragma unroll
     for (int o = 0; o < OG; ++o) acc[o] = f32x4{0.f, 0.f, 0.f, 0.f};
-    // four k-steps per trip, all loads issued before the first use; probes past r are clamped
-    // to the last one and enter with a zero B operand
-    for (int j0 = 0; j0 < r; j0 += 16) {
-        float bv[4], av[4][OG];
+    // NU k-steps (4 probes each) per trip, all loads issued before the first use: with few offsets per wave a trip
+    // covers 64 probes, so that a wave waits for memory once; probes past r are clamped to the last one and enter
+    // with a zero B operand
+    constexpr int NU = OG >= 9 ? 4 : 16;
+    for (int j0 = 0; j0 < r; j0 += 4 * NU) {
+        float bv[NU], av[NU][OG];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < NU; ++u) {
             const int j = j0 + 4 * u + g;
             const int jc = j < r ? j : r - 1;
             const float zv = zrow[jc];
             bv[u] = j < r ? zv : 0.f;
 #pragma unroll
-            for (int o = 0; o < OG; ++o) av[u][o] = tcol[o][(size_t)jc * MP];
+            for (int o = 0; o < OG; ++o) av[u][o] = tcol[o][(size_t)jc * 4];
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < NU; ++u)
 #pragma unroll
             for (int o = 0; o < OG; ++o) acc[o] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][o], bv[u], acc[o], 0, 0, 0);
     }
@@ -736,37 +738,83 @@ __global__ __launch_bounds__(64) void expand_kernel(const float *__restrict__ T,
 
 // ---------------------------------------------------------------------------
 // Second pass in one launch (Algorithm 1 backward step 4, Eq. (6) step (iii), on the partial sums of
-// step 3): a workgroup owns 16 output channels of one kernel offset.  It first sums the S partial
-// tiles of its slab T[og, j0 .. j0+JC, m0 .. m0+16) in a fixed order (s = 0, 1, 2, ... in four
-// interleaved chains, chains and groups combined in a fixed tree: the result does not depend on
-// timing) into LDS, then multiplies the slab by Z on the 16x16x4 matrix instruction,
-//   dW[m,n,og] = (1/r) sum_j Z[n,j] T[og,j,m],
-// its four waves taking the tiles of 16 input channels in turn.  MODE 0: Z from memory (the caller's,
-// or the one the workgroups of the correlation launch redrew from the seed, Alg. 1 backward step 2);
-// MODE 2: exact gradient, dW[m,n,og] = T[og,n,m] (then grid.z cuts the input channels into chunks
-// of JC).  Offsets are counted over `nsets` sets of partial tiles stored back to back (volumetric
-// layers: one set per kernel-depth offset), og = set * K2 + o, K2T = nsets * K2.
+// step 3): a workgroup owns four consecutive output channels (one 16-byte element per column) of one
+// kernel offset.  It first sums the S partial tiles of its slab T[og, j0 .. j0+JC, 4mq .. 4mq+3] in a
+// fixed order (16 interleaved chains per thread, chains and thread groups combined in a fixed tree: the
+// result does not depend on timing) into LDS; the slab of a tile is one run of JC elements, so a wave
+// reads whole cache lines.  Then
+//   dW[m,n,og] = (1/r) sum_j Z[n,j] T[og,j,m]
+// on the vector ALUs: Z goes through LDS in tiles of 128 input channels x 64 probes (read with
+// coalesced loads, rows padded so that a lane can read its row 16 bytes at a time without bank
+// conflicts), a thread owns one input channel and two of the four output channels.  MODE 0: Z from
+// memory (the caller's, or the one the workgroups of the correlation launch redrew from the seed,
+// Alg. 1 backward step 2); MODE 2: exact gradient, dW[m,n,og] = T[og,n,m] (then grid.z cuts the input
+// channels into chunks of JC).  Offsets are counted over `nsets` sets of partial tiles stored back to
+// back (volumetric layers: one set per kernel-depth offset), og = set * K2 + o, K2T = nsets * K2.
+// The grid's first extent is a multiple of 8, so the workgroups that write the K2T offsets of one
+// (m, n) run of dW share an L2, which merges their 4-byte stores.
 // ---------------------------------------------------------------------------
+constexpr int kP2Rows = 128;          // input channels per Z tile
+constexpr int kP2Cols = 64;           // probes per Z tile
+constexpr int kP2Stride = kP2Cols + 4;  // floats per staged row: 4 * odd, rows of 16-byte reads fall on distinct banks
+
 template <int MODE>
-__global__ __launch_bounds__(kThreads) void reduce_expand_kernel(const float *__restrict__ part, const float *__restrict__ Z,
-                                                                 float *__restrict__ dW, int S, int K2, int K2T, int JP, int MP,
-                                                                 int JC, int C_out, int C_in, int r, int nnz_norm)
+__global__ __launch_bounds__(kThreads) void pass2_kernel(const f32x4 *__restrict__ part, const float *__restrict__ Z,
+                                                         float *__restrict__ dW, int S, int K2, int K2T, int JP, int MQ, int JC,
+                                                         int C_out, int C_in, int r, int nnz_norm, int z_vec)
 {
-    extern __shared__ f32x4 re_lds[];   // slab [JC][4] float4, then (few elements only) the groups' sums [NG][NE]
+    extern __shared__ f32x4 p2_lds[];   // slab [JC], then the thread groups' sums [NG][NE] (few-element slabs only), then the Z tile
     const int tid = threadIdx.x;
-    const int m0 = blockIdx.x * 16;
+    const int mq = blockIdx.x;
+    if (mq >= MQ) return;   // (the grid is padded to a multiple of 8 workgroups per offset)
     const int og = blockIdx.y, set = og / K2, o = og - set * K2;
     const int j0 = blockIdx.z * JC;
-    const int NE = JC * 4;   // float4 elements of the slab: (j, four output channels)
-    const size_t tile = (size_t)K2 * JP * MP;   // floats of one partial tile
-    const float *base = part + (size_t)set * S * tile + ((size_t)o * JP + j0) * MP + m0;
+    const int NE = JC;
+    const size_t tile = (size_t)K2 * MQ * JP;   // 16-byte elements of one partial tile
+    const f32x4 *base = part + (size_t)set * S * tile + ((size_t)o * MQ + mq) * JP + j0;
+    const int NG = NE >= kThreads ? 1 : kThreads / NE;   // groups of threads that share the tiles of an element
+    f32x4 *red = p2_lds + NE;
+    float *zs = reinterpret_cast<float *>(red + (NG > 1 ? NG * NE : 0));
+
+    // ---- Z tile (n0 .., jb ..) -> registers (8 x 16 bytes per thread) -> LDS; entries past C_in or r are zero
+    const int nl = tid & (kP2Rows - 1), h = tid >> 7;   // phase 2: input channel inside the tile, pair of output channels
+    f32x4 zr[8];
+    auto load_z = [&](int n0, int jb) {
+        if constexpr (MODE != 0) return;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int e = q * kThreads + tid;         // element (row, 4 probes) of the tile
+            const int row = e >> 4, c4 = (e & 15) * 4;
+            const int n = n0 + row, j = jb + c4;
+            f32x4 v = {0.f, 0.f, 0.f, 0.f};
+            if (n < C_in) {
+                const float *src = Z + (size_t)n * r + j;
+                if (z_vec && j + 3 < r) {
+                    v = *reinterpret_cast<const f32x4 *>(src);
+                } else {
+                    if (j < r) v[0] = src[0];
+                    if (j + 1 < r) v[1] = src[1];
+                    if (j + 2 < r) v[2] = src[2];
+                    if (j + 3 < r) v[3] = src[3];
+                }
+            }
+            zr[q] = v;
+        }
+    };
+    auto store_z = [&]() {
+        if constexpr (MODE != 0) return;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int e = q * kThreads + tid;
+            *reinterpret_cast<f32x4 *>(zs + (e >> 4) * kP2Stride + (e & 15) * 4) = zr[q];
+        }
+    };
+    load_z(0, 0);   // in flight while the partial tiles are summed
 
     // ---- fixed-order sum over the S partial tiles.  An element's tiles are taken in 16 interleaved chains (16
     // loads in flight per thread: the tiles were written by other compute units and come from beyond the L2);
     // few-element slabs also spread the tiles of an element over NG groups of threads.
-    const int NG = NE >= kThreads ? 1 : kThreads / NE;   // groups of threads that share the tiles of an element
-    f32x4 *red = re_lds + NE;
-    auto chain_sum = [&](const float *p, int first, int step) {
+    auto chain_sum = [&](const f32x4 *p, int first, int step) {
         f32x4 c[16];
 #pragma unroll
         for (int i = 0; i < 16; ++i) c[i] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -774,11 +822,17 @@ __global__ __launch_bounds__(kThreads) void reduce_expand_kernel(const float *__
         for (; k + 15 * step < S; k += 16 * step) {   // 16 tiles per trip, every load issued before the first sum
             f32x4 v[16];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) v[i] = *reinterpret_cast<const f32x4 *>(p + (size_t)(k + i * step) * tile);
+            for (int i = 0; i < 16; ++i) v[i] = p[(size_t)(k + i * step) * tile];
 #pragma unroll
             for (int i = 0; i < 16; ++i) c[i] += v[i];
         }
-        for (int i = 0; k < S; k += step, ++i) c[i & 15] += *reinterpret_cast<const f32x4 *>(p + (size_t)k * tile);
+        if (k < S) {   // the last, shorter trip (chain i keeps taking tile k + i * step)
+            f32x4 v[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) v[i] = (k + i * step < S) ? p[(size_t)(k + i * step) * tile] : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int i = 0; i < 16; ++i) c[i] += v[i];
+        }
 #pragma unroll
         for (int w = 8; w >= 1; w >>= 1)
 #pragma unroll
@@ -786,62 +840,60 @@ __global__ __launch_bounds__(kThreads) void reduce_expand_kernel(const float *__
         return c[0];
     };
     if (NG == 1) {
-        for (int e = tid; e < NE; e += kThreads) re_lds[e] = chain_sum(base + (size_t)(e >> 2) * MP + 4 * (e & 3), 0, 1);
+        for (int e = tid; e < NE; e += kThreads) p2_lds[e] = chain_sum(base + e, 0, 1);
     } else {
         const int gi = tid / NE, e = tid - gi * NE;
-        if (gi < NG) red[gi * NE + e] = chain_sum(base + (size_t)(e >> 2) * MP + 4 * (e & 3), gi, NG);
+        if (gi < NG) red[gi * NE + e] = chain_sum(base + e, gi, NG);
         __syncthreads();
         if (tid < NE) {
             f32x4 t = red[tid];
             for (int q = 1; q < NG; ++q) t += red[q * NE + tid];
-            re_lds[tid] = t;
+            p2_lds[tid] = t;
         }
     }
+    store_z();
     __syncthreads();
-    const float *slab = reinterpret_cast<const float *>(re_lds);   // [JC][16]
+    const float *slab = reinterpret_cast<const float *>(p2_lds);   // [JC][4]
 
     if constexpr (MODE == 2) {
-        // exact gradient: the slab is dW[m0.., j0.., og] transposed
-        for (int e = tid; e < JC * 16; e += kThreads) {
-            const int mi = e & 15, j = e >> 4;
-            const int m = m0 + mi, n = j0 + j;
-            if (m < C_out && n < C_in) dW[((size_t)m * C_in + n) * K2T + og] = slab[j * 16 + mi];
+        // exact gradient: the slab is dW[4mq .. 4mq+3, j0.., og] transposed
+        for (int e = tid; e < JC * 4; e += kThreads) {
+            const int mi = e & 3, j = e >> 2;
+            const int m = 4 * mq + mi, n = j0 + j;
+            if (m < C_out && n < C_in) dW[((size_t)m * C_in + n) * K2T + og] = slab[e];
         }
     } else {
-        const int lane = tid & 63, wave = tid >> 6, l16 = lane & 15, g = lane >> 4;
-        const int NTN = (C_in + 15) >> 4;
-        for (int nt = wave; nt < NTN; nt += 4) {
-            const int ncol = nt * 16 + l16;
-            const int nc = ncol < C_in ? ncol : C_in - 1;
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        const int m = 4 * mq + 2 * h;
+        for (int n0 = 0; n0 < C_in; n0 += kP2Rows) {
+            float acc0 = 0.f, acc1 = 0.f;
             int cnt = 0;
-            for (int jj = 0; jj < r; jj += 16) {
-                float bv[4], av[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int j = jj + 4 * u + g;
-                    const int jc = j < r ? j : r - 1;
-                    const float zv = Z[(size_t)nc * r + jc];
-                    bv[u] = j < r ? zv : 0.f;
-                    cnt += bv[u] != 0.0f ? 1 : 0;
-                    av[u] = slab[jc * 16 + l16];
+            for (int jb = 0; jb < r; jb += kP2Cols) {
+                if (n0 + jb > 0) {   // (the first tile is already there)
+                    load_z(n0, jb);
+                    __syncthreads();   // every thread is done with the tile before
+                    store_z();
+                    __syncthreads();
                 }
+                const int jn = r - jb < kP2Cols ? r - jb : kP2Cols;
+                const float *zrow = zs + nl * kP2Stride;
+                for (int j = 0; j < jn; j += 4) {   // (a row's entries past r are zero)
+                    const f32x4 z = *reinterpret_cast<const f32x4 *>(zrow + j);
 #pragma unroll
-                for (int u = 0; u < 4; ++u) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u], bv[u], acc, 0, 0, 0);
+                    for (int q = 0; q < 4; ++q) {
+                        const float *t = slab + (size_t)(jb + j + q) * 4 + 2 * h;   // same address in every lane of a half
+                        const float tq0 = (j + q < jn) ? t[0] : 0.f, tq1 = (j + q < jn) ? t[1] : 0.f;
+                        acc0 = fmaf(z[q], tq0, acc0);
+                        acc1 = fmaf(z[q], tq1, acc1);
+                        cnt += z[q] != 0.0f ? 1 : 0;
+                    }
+                }
             }
             float inv_r = 1.0f / (float)r;
-            if (nnz_norm) {
-                // non-zero entries of row n of Z: the four lane groups of a column hold every fourth probe
-                cnt += __shfl_xor(cnt, 16);
-                cnt += __shfl_xor(cnt, 32);
-                inv_r = cnt > 0 ? 1.0f / (float)cnt : 0.0f;
-            }
-            if (ncol < C_in) {
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int m = m0 + 4 * g + v;
-                    if (m < C_out) dW[((size_t)m * C_in + ncol) * K2T + og] = acc[v] * inv_r;
-                }
+            if (nnz_norm) inv_r = cnt > 0 ? 1.0f / (float)cnt : 0.0f;
+            const int n = n0 + nl;
+            if (n < C_in) {
+                if (m < C_out) dW[((size_t)m * C_in + n) * K2T + og] = acc0 * inv_r;
+                if (m + 1 < C_out) dW[((size_t)(m + 1) * C_in + n) * K2T + og] = acc1 * inv_r;
             }
         }
     }
@@ -857,7 +909,7 @@ __global__ __launch_bounds__(kThreads) void untile_kernel(const float *__restric
     const int o = (int)(i % K2);
     const long long mn = i / K2;
     const int n = (int)(mn % C_in), m = (int)(mn / C_in);
-    dW[i] = T[((size_t)o * JP + n) * MP + m];
+    dW[i] = T[tile_index(o, n, m, JP, MP)];
 }
 
 // dY planes whose size is not a whole number of 16-byte vectors are copied once into planes
@@ -1144,37 +1196,41 @@ hipError_t launch_reduce_raw(const float *part, float *T, int S, int E4, hipStre
 
 bool reduce_expand_fused(const CorrParams &P, bool have_z, bool exact, int C_in, int r, int dist)
 {
-    // One workgroup per (offset, 16 output channels) reads all S partial tiles of its slab: that is K2 * MP / 16
-    // workgroups, 36 on a 64-channel 3x3 layer, and a compute unit turns memory requests around at a limited rate
-    // (measured: 18-30 us on the benchmark layers against 13-16 us for reduce_partials_kernel, which spreads the
-    // same bytes over the whole chip, plus expand_kernel).  The single launch wins where launch cost dominates:
-    // small layers, up to a few MB of partial sums.
-    const int mode = env_int("XCONV_FUSED_PASS2", -1);   // tests: 0 never, 1 whenever the kernel can take the layer
+    // One workgroup per (offset, four output channels) reads the S partial tiles of its slab, K2 * MP / 4 workgroups in
+    // all.
+    const int mode = env_int("XCONV_FUSED_PASS2", -1);   // tests: 0 takes the two-launch route (launch_reduce, launch_expand)
     if (mode == 0) return false;
-    if (P.MP % 16 != 0 || P.JP % 16 != 0) return false;
-    if (!exact && P.JP > 1024) return false;   // (the slab of all probe columns sits in LDS: 64 KB at most)
+    if (P.MP % 4 != 0) return false;
+    if (!exact && P.JP > 1024) return false;   // (the slab of all probe columns sits in LDS: 16 KB at most)
     if (mode == 1) return true;
-    return (size_t)P.S * P.K2 * P.JP * P.MP * sizeof(float) <= ((size_t)3 << 20);
+    // Every workgroup also reads the whole of Z, and a compute unit turns memory requests around at a limited rate:
+    // with more slabs than compute units the busiest unit sets the time (measured on 576 slabs: 27 us against 18 us for
+    // the two launches, whose many small workgroups spread evenly).
+    return (long long)P.K2 * (P.MP / 4) <= 256;
 }
 
 hipError_t launch_reduce_expand(const CorrParams &P, const float *Z, bool exact, float *dW, int C_in, int r, bool nnz_norm, int dist,
                                 uint64_t seed, int nsets, hipStream_t st)
 {
-    // slab of JC probe columns (or input channels) x 16 output channels per workgroup; the estimate needs all columns
+    // slab of JC probe columns (or input channels) x 4 output channels per workgroup; the estimate needs all columns
     int JC = P.JP;
     if (exact)   // chunks of at most 256 input channels that divide the padded channel count (a multiple of 16)
         for (JC = P.JP < 256 ? P.JP : 256; P.JP % JC != 0; JC -= 16) {}
-    const int NE = JC * 4;
+    const int NE = JC;
     const int NG = NE >= kThreads ? 1 : kThreads / NE;
-    const size_t lds = (size_t)NE * 16 + (NG > 1 ? (size_t)NG * NE * 16 : 0);
-    const dim3 grid((unsigned)(P.MP / 16), (unsigned)(nsets * P.K2), (unsigned)(exact ? ceil_div(P.JP, JC) : 1));
+    const size_t lds = (size_t)NE * 16 + (NG > 1 ? (size_t)NG * NE * 16 : 0) + (exact ? 0 : (size_t)kP2Rows * kP2Stride * sizeof(float));
+    const int MQ = P.MP / 4;
+    const dim3 grid((unsigned)round_up(MQ, 8), (unsigned)(nsets * P.K2), (unsigned)(exact ? P.JP / JC : 1));
     const int K2T = nsets * P.K2;
+    const f32x4 *part = reinterpret_cast<const f32x4 *>(P.part);
     if (exact) {
-        hipLaunchKernelGGL(reduce_expand_kernel<2>, grid, dim3(kThreads), lds, st, P.part, nullptr, dW, P.S, P.K2, K2T, P.JP, P.MP, JC,
-                           P.C_out, C_in, r, 0);
+        hipLaunchKernelGGL(pass2_kernel<2>, grid, dim3(kThreads), lds, st, part, nullptr, dW, P.S, P.K2, K2T, P.JP, MQ, JC, P.C_out, C_in,
+                           r, 0, 0);
     } else {
-        hipLaunchKernelGGL(reduce_expand_kernel<0>, grid, dim3(kThreads), lds, st, P.part, Z, dW, P.S, P.K2, K2T, P.JP, P.MP, JC, P.C_out,
-                           C_in, r, nnz_norm ? 1 : 0);
+        // rows of Z are read 16 bytes at a time where every row starts on such a boundary
+        const int z_vec = (r % 4 == 0 && (reinterpret_cast<uintptr_t>(Z) & 15u) == 0) ? 1 : 0;
+        hipLaunchKernelGGL(pass2_kernel<0>, grid, dim3(kThreads), lds, st, part, Z, dW, P.S, P.K2, K2T, P.JP, MQ, JC, P.C_out, C_in, r,
+                           nnz_norm ? 1 : 0, z_vec);
     }
     return hipGetLastError();
 }
@@ -1189,7 +1245,7 @@ hipError_t launch_expand(const CorrParams &P, const float *Z, float *dW, int C_i
         // few tiles: split the offsets over more waves; many tiles: a lane writes whole runs of offsets
         const int NTM16 = ceil_div(P.C_out, 16), NTN = ceil_div(C_in, 16);
         const long long tiles = (long long)NTM16 * NTN;
-        int og = K2 == 1 ? 1 : (tiles * ceil_div(K2, 9) >= 2048 ? 9 : (tiles * ceil_div(K2, 3) >= 2048 ? 3 : 1));
+        int og = K2 == 1 ? 1 : (tiles * ceil_div(K2, 9) >= 2048 ? 9 : (tiles * ceil_div(K2, 3) >= 512 ? 3 : 1));
         og = env_int("XCONV_EXPAND_OG", og);
         const dim3 grid((unsigned)tiles, (unsigned)ceil_div(K2, og));
         if (og == 9)

@@ -296,16 +296,16 @@ __global__ __launch_bounds__(kWsThreads) void corr_row_kernel(const WsParams P)
         const int jcol = jb + wj * 32 + l32;
 #pragma unroll
         for (int o = 0; o < 9; ++o) {
-            float *dst = P.part + (((size_t)blockIdx.x * P.K2 + o) * P.JP + jcol) * P.MP + m0 + wm * 32 + 4 * g;
+            float *dst = P.part + (size_t)blockIdx.x * P.K2 * P.JP * P.MP + tile_index(o, jcol, m0 + wm * 32 + 4 * g, P.JP, P.MP);
 #pragma unroll
-            for (int v = 0; v < 4; ++v)
-                *reinterpret_cast<f32x4 *>(dst + 8 * v) = f32x4{acc[o][4 * v], acc[o][4 * v + 1], acc[o][4 * v + 2], acc[o][4 * v + 3]};
+            for (int v = 0; v < 4; ++v)   // rows 8v + 4g ..: two channel quads further on
+                *reinterpret_cast<f32x4 *>(dst + (size_t)8 * v * P.JP) = f32x4{acc[o][4 * v], acc[o][4 * v + 1], acc[o][4 * v + 2], acc[o][4 * v + 3]};
         }
         if constexpr (XCONV_ROW_DBG & 32) {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             ts_[6] = __builtin_amdgcn_s_memrealtime(); ts_[7] = __builtin_readcyclecounter();
             if (wave == 0 && lane == 0) {
-                unsigned long long *d = reinterpret_cast<unsigned long long *>(P.part + (((size_t)blockIdx.x * P.K2) * P.JP + jb) * P.MP + m0);
+                unsigned long long *d = reinterpret_cast<unsigned long long *>(P.part + (size_t)blockIdx.x * P.K2 * P.JP * P.MP + tile_index(0, jb, m0, P.JP, P.MP));
                 for (int q = 0; q < 8; ++q) d[q] = ts_[q];
             }
         }

@@ -178,7 +178,7 @@ __global__ __launch_bounds__(kWsThreads, 2 * OCC) void corr_ws32_kernel(const Ws
 #pragma unroll
         for (int o = 0; o < NOFF; ++o) {
             if (o < noff) {
-                float *dst = P.part + (((size_t)blockIdx.x * P.K2 + (o_first + o)) * P.JP + jcol) * P.MP + m0 + wm * 16 + 4 * g;
+                float *dst = P.part + (size_t)blockIdx.x * P.K2 * P.JP * P.MP + tile_index(o_first + o, jcol, m0 + wm * 16 + 4 * g, P.JP, P.MP);
                 *reinterpret_cast<f32x4 *>(dst) = acc[o];
             }
         }

@@ -419,10 +419,10 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
 #pragma unroll
         for (int o = 0; o < NOFF; ++o) {
             if (o < noff) {
-                float *dst = P.part + (((size_t)blockIdx.x * P.K2 + (o_first + o)) * P.JP + jcol) * P.MP + m0 + wm * 32 + 4 * g;
+                float *dst = P.part + (size_t)blockIdx.x * P.K2 * P.JP * P.MP + tile_index(o_first + o, jcol, m0 + wm * 32 + 4 * g, P.JP, P.MP);
 #pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    *reinterpret_cast<f32x4 *>(dst + 8 * v) = f32x4{acc[o][4 * v], acc[o][4 * v + 1], acc[o][4 * v + 2], acc[o][4 * v + 3]};
+                for (int v = 0; v < 4; ++v)   // rows 8v + 4g ..: two channel quads further on
+                    *reinterpret_cast<f32x4 *>(dst + (size_t)8 * v * P.JP) = f32x4{acc[o][4 * v], acc[o][4 * v + 1], acc[o][4 * v + 2], acc[o][4 * v + 3]};
             }
         }
     } else {
