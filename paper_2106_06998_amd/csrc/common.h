@@ -112,18 +112,21 @@ template <int DT> __device__ inline f32x4 mfma16(const uint4 &a, const uint4 &b,
 // gets the eight row values packed in q order.
 template <int NW> __device__ inline void transpose_rows8(const uint32_t (&rows)[8][NW], uint4 (&cols)[2 * NW])
 {
+    // One byte-permute per output word: v_perm_b32 picks its four bytes from the pair {second, first} operand
+    // (selector values 0-3: bytes of the second operand, 4-7: bytes of the first).
+    constexpr uint32_t kLow = 0x05040100u;    // low halves:  a.b0 a.b1 b.b0 b.b1
+    constexpr uint32_t kHigh = 0x07060302u;   // high halves: a.b2 a.b3 b.b2 b.b3
 #pragma unroll
     for (int w = 0; w < NW; ++w) {
         // even column: low halves of each row pair; odd column: high halves
-        // (plain shifts and masks; the compiler folds each into one byte-permute)
-        cols[2 * w].x = (rows[0][w] & 0xffffu) | (rows[1][w] << 16);
-        cols[2 * w].y = (rows[2][w] & 0xffffu) | (rows[3][w] << 16);
-        cols[2 * w].z = (rows[4][w] & 0xffffu) | (rows[5][w] << 16);
-        cols[2 * w].w = (rows[6][w] & 0xffffu) | (rows[7][w] << 16);
-        cols[2 * w + 1].x = (rows[0][w] >> 16) | (rows[1][w] & 0xffff0000u);
-        cols[2 * w + 1].y = (rows[2][w] >> 16) | (rows[3][w] & 0xffff0000u);
-        cols[2 * w + 1].z = (rows[4][w] >> 16) | (rows[5][w] & 0xffff0000u);
-        cols[2 * w + 1].w = (rows[6][w] >> 16) | (rows[7][w] & 0xffff0000u);
+        cols[2 * w].x = __builtin_amdgcn_perm(rows[1][w], rows[0][w], kLow);
+        cols[2 * w].y = __builtin_amdgcn_perm(rows[3][w], rows[2][w], kLow);
+        cols[2 * w].z = __builtin_amdgcn_perm(rows[5][w], rows[4][w], kLow);
+        cols[2 * w].w = __builtin_amdgcn_perm(rows[7][w], rows[6][w], kLow);
+        cols[2 * w + 1].x = __builtin_amdgcn_perm(rows[1][w], rows[0][w], kHigh);
+        cols[2 * w + 1].y = __builtin_amdgcn_perm(rows[3][w], rows[2][w], kHigh);
+        cols[2 * w + 1].z = __builtin_amdgcn_perm(rows[5][w], rows[4][w], kHigh);
+        cols[2 * w + 1].w = __builtin_amdgcn_perm(rows[7][w], rows[6][w], kHigh);
     }
 }
 
