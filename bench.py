@@ -27,8 +27,12 @@ PEAK_MFMA_TFLOPS = {"f32": 157.3, "bf16": 2500.0, "f16": 2500.0}
 # (FETCH_SIZE, WRITE_SIZE scaled by a copy kernel of known size; see
 # profiles/).  bytes, or None where not measured yet.
 MEASURED_TRAFFIC = {
-    ("C2", "corr_ws32_kernel"): 64.7e6, ("C2", "probe_kernel"): 42.1e6,  # profiles/xconv_kernels_C2.txt
-    ("C5", "corr_ws_kernel"): 202.5e6, ("C5", "probe_kernel"): 154.3e6,  # profiles/xconv_kernels_C5.txt
+    # (FETCH_SIZE * 2 + WRITE_SIZE) KiB per launch, profiles/xconv_kernels_<config>.txt
+    ("C1", "corr_ws32_kernel"): 3.8e6, ("C1", "probe_kernel"): 0.7e6,
+    ("C2", "corr_ws32_kernel"): 66.9e6, ("C2", "probe_kernel"): 42.1e6,
+    ("C3", "corr_kernel"): 122.9e6, ("C3", "probe_kernel"): 64.5e6,
+    ("C4", "corr_ws32_kernel"): 193.2e6, ("C4", "probe_kernel"): 167.9e6,
+    ("C5", "corr_row_kernel"): 219.1e6, ("C5", "probe_kernel"): 129.5e6,
 }
 
 

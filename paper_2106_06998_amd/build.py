@@ -14,6 +14,13 @@ OBJDIR = os.path.join(HERE, "_build")
 SOURCES = ["xconv_api.hip", "probe_kernels.hip", "corr_kernels.hip", "corr_ws_kernels.hip", "corr_row_kernels.hip", "corr_ws32_kernels.hip", "pixel_kernels.hip", "relu_kernels.hip", "conv_kernels.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+# XCONV_SANITIZE_HOST=1: a second library whose host code (descriptor checks, plans, size arithmetic) is built under
+# AddressSanitizer and UndefinedBehaviorSanitizer; the device code is the same.  tests/run_host_sanitizers.py uses it.
+SANITIZE_HOST = os.environ.get("XCONV_SANITIZE_HOST", "0") == "1"
+if SANITIZE_HOST:
+    LIB = os.path.join(HERE, "libxconv_san.so")
+    OBJDIR = os.path.join(HERE, "_build_san")
+SAN_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
     # packed fp32 vector ops are kept off for all device code
@@ -23,7 +30,7 @@ FLAGS = [
 
 def _compile(src):
     obj = os.path.join(OBJDIR, src.replace(".hip", ".o"))
-    cmd = [HIPCC] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC] + FLAGS + (SAN_FLAGS if SANITIZE_HOST else []) + ["-c", os.path.join(CSRC, src), "-o", obj]
     p = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     out = "\n".join(l for l in p.stdout.splitlines() if "packed-fp32-ops' is not a recognized feature" not in l)
     if p.returncode != 0:
@@ -38,6 +45,8 @@ def build(verbose=True):
     with ThreadPoolExecutor(max_workers=min(9, len(SOURCES))) as ex:
         objs = list(ex.map(_compile, SOURCES))
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
+    if SANITIZE_HOST:
+        cmd += ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined"]
     subprocess.run(cmd, check=True)
     if verbose:
         print("built", LIB)

@@ -34,6 +34,13 @@
 #ifndef XCONV_ROW_DBG
 #define XCONV_ROW_DBG 0
 #endif
+// wave priorities of the two roles
+#ifndef XCONV_ROW_CPRIO
+#define XCONV_ROW_CPRIO 3
+#endif
+#ifndef XCONV_ROW_PPRIO
+#define XCONV_ROW_PPRIO 0
+#endif
 
 namespace xc {
 
@@ -85,7 +92,7 @@ __global__ __launch_bounds__(kWsThreads) void corr_row_kernel(const WsParams P)
 
     if (wave < 4) {
         // =========================== consumers ===========================
-        __builtin_amdgcn_s_setprio(3);
+        __builtin_amdgcn_s_setprio(XCONV_ROW_CPRIO);
         const int l32 = lane & 31, g = lane >> 5;
         const int wm = wave & (P.WM - 1), wj = wave >> __builtin_ctz((unsigned)P.WM);
         const int G = 2 * wj + (l32 >> 4);  // 16-column group of this lane's column
@@ -311,7 +318,7 @@ __global__ __launch_bounds__(kWsThreads) void corr_row_kernel(const WsParams P)
         }
     } else {
         // =========================== producers ===========================
-        __builtin_amdgcn_s_setprio(0);
+        __builtin_amdgcn_s_setprio(XCONV_ROW_PPRIO);
         const int p = tid - kProducers;
         const uint16_t *dY = static_cast<const uint16_t *>(P.dY);
         const uint16_t *Ag = static_cast<const uint16_t *>(P.A);
