@@ -311,6 +311,33 @@ def test_launch_plans_stay_within_the_device_limits_on_random_layers():
     assert seen == {0, 1, 2, 3}       # all four correlation kernels get layers
 
 
+def test_plan_overrides_are_part_of_the_plan_cache_key(monkeypatch):
+    # A plan made under one setting of an XCONV_* override is never handed out under another: the fp32
+    # producer/consumer plan of one layer, asked for with one and then with two workgroups per compute unit (the
+    # second request would hit the cached first plan if the key were the shape alone), and back again.
+    d = xb.make_desc(128, 64, 64, 32, 32, 3, 1, 1, 16, "f32", "gaussian", 13)
+    monkeypatch.setenv("XCONV_WS32_OCC", "1")
+    one = xb.xconv_plan_info(d, xb.XCONV_OP_ESTIMATE)
+    monkeypatch.setenv("XCONV_WS32_OCC", "2")
+    two = xb.xconv_plan_info(d, xb.XCONV_OP_ESTIMATE)
+    monkeypatch.setenv("XCONV_WS32_OCC", "1")
+    again = xb.xconv_plan_info(d, xb.XCONV_OP_ESTIMATE)
+    assert one["ws"] == 2 and two["ws"] == 2
+    assert again == one
+    assert 2 * two["lds_bytes"] <= 160 * 1024          # two workgroups share a compute unit's LDS
+    assert two != one and two["S"] > one["S"]          # and the K-split counts both of them
+    # the same for a split-count override of the 16-bit kernel
+    h = xb.make_desc(9, 64, 64, 14, 14, 3, 1, 1, 64, "f16", "rademacher", 13)
+    base = xb.xconv_plan_info(h, xb.XCONV_OP_ESTIMATE)
+    monkeypatch.setenv("XCONV_ROW_SPLITS", "3")
+    monkeypatch.setenv("XCONV_WS_SPLITS", "3")
+    forced = xb.xconv_plan_info(h, xb.XCONV_OP_ESTIMATE)
+    monkeypatch.delenv("XCONV_ROW_SPLITS")
+    monkeypatch.delenv("XCONV_WS_SPLITS")
+    assert forced["S"] == 3 and base["S"] != 3
+    assert xb.xconv_plan_info(h, xb.XCONV_OP_ESTIMATE) == base
+
+
 def test_static_scratch_entry_point_checks_before_it_touches_a_device():
     # xconv_dw_estimate_static: descriptor and size checks come first and need no GPU
     L = xb.lib()
