@@ -39,6 +39,20 @@ __device__ inline int xcd_block(int b, int grid)
     return (grid & 7) == 0 ? (b & 7) * (grid >> 3) + (b >> 3) : b;
 }
 
+// Tile number `it` (0, 1, ...) of wave w out of NW waves, or ntiles when the wave is done.  Every wave takes
+// ntiles / NW tiles, and the remaining ones go to waves spread evenly over the grid (not to the first so many), so that every
+// compute unit, which holds the same number of waves, moves the same number of bytes to within a tile.
+__device__ inline int wave_tile(int w, int it, int NW, int ntiles)
+{
+    const int Q = ntiles / NW, R = ntiles - Q * NW;
+    if (it < Q) return it * NW + w;
+    if (it == Q) {
+        const int a = (int)((long long)w * R / NW), b = (int)((long long)(w + 1) * R / NW);
+        if (b > a) return Q * NW + a;
+    }
+    return ntiles;
+}
+
 // Row i of MFMA tile jt holds probe column j0 + jmap: lane group g = i/4 then
 // owns the 4*JT consecutive columns g*4*JT .. (g+1)*4*JT-1 of the 16*JT block.
 __device__ inline int jmap(int jt, int i, int JT) { return (i >> 2) * (4 * JT) + jt * 4 + (i & 3); }
@@ -201,8 +215,9 @@ __global__ __launch_bounds__(kThreads, (JT == 1 ? 4 : 2)) void probe_f32_kernel(
     };
 
     // The first tile's loads are in flight while the Z fragments are staged.
-    int tile = xcd_block(blockIdx.x, gridDim.x) * 4 + wave;
-    const int tile_step = gridDim.x * 4;
+    const int wv = xcd_block(blockIdx.x, gridDim.x) * 4 + wave, NWV = gridDim.x * 4;
+    int it = 0;
+    int tile = wave_tile(wv, 0, NWV, ntiles);
     Tile cur;
     Staged rg[D];
     if (tile < ntiles) {
@@ -259,7 +274,7 @@ __global__ __launch_bounds__(kThreads, (JT == 1 ? 4 : 2)) void probe_f32_kernel(
 
         // the next tile's first loads go out before this tile's stores
         const Tile done = cur;
-        tile += tile_step;
+        tile = wave_tile(wv, ++it, NWV, ntiles);
         if (tile < ntiles) {
             locate(cur, tile);
             prefetch(rg, cur);
@@ -405,8 +420,9 @@ __global__ __launch_bounds__(kThreads, 2) void probe_16_kernel(const uint16_t *_
     };
 
     // The first tile's loads are in flight while the Z fragments are staged.
-    int tile = xcd_block(blockIdx.x, gridDim.x) * 4 + wave;
-    const int tile_step = gridDim.x * 4;
+    const int wv = xcd_block(blockIdx.x, gridDim.x) * 4 + wave, NWV = gridDim.x * 4;
+    int it = 0;
+    int tile = wave_tile(wv, 0, NWV, ntiles);
     Tile cur;
     Staged rg[D];
     if (tile < ntiles) {
@@ -456,7 +472,7 @@ __global__ __launch_bounds__(kThreads, 2) void probe_16_kernel(const uint16_t *_
 
         // the next tile's first loads go out before this tile's stores
         const Tile done = cur;
-        tile += tile_step;
+        tile = wave_tile(wv, ++it, NWV, ntiles);
         if (tile < ntiles) {
             locate(cur, tile);
             prefetch(rg, cur);
@@ -652,15 +668,13 @@ template <typename K> static hipError_t set_lds(K kernel, size_t bytes)
 }
 
 // 4 tiles (one per wave) per workgroup pass.  The grid is what is resident at once (256 compute
-// units x `wgs_per_cu`) or less, sized so that every workgroup makes the same number of passes: a
-// grid of 784 on 512 slots would run a second round that is half empty, 392 workgroups of two
-// passes each keep the whole chip loading until the end.  Rounded up to a multiple of 8 (see xcd_block).
+// units x `wgs_per_cu`), or fewer workgroups when there are fewer tiles; wave_tile hands the tiles out so that every
+// compute unit gets the same number to within one.  A multiple of 8 (see xcd_block).
 static int probe_grid(int ntiles, int wgs_per_cu)
 {
-    const int want = ceil_div(ntiles, 4);
+    const int want = round_up(ceil_div(ntiles, 4), 8);
     const int slots = 256 * wgs_per_cu;
-    const int rounds = ceil_div(want, slots);
-    return round_up(ceil_div(want, rounds), 8);
+    return want < slots ? want : slots;
 }
 
 template <int JT, bool NHWC>
