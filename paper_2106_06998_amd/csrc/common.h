@@ -32,7 +32,8 @@ enum KernelId {
     K_PIXEL_FWD = 13,
     K_RELU = 14,
     K_CONV = 15,
-    K_COUNT = 16
+    K_PASS2 = 16,
+    K_COUNT = 17
 };
 
 // Where the probe output of a voxel goes in Xt.  sd == 0: plain order, pixel `first` of the

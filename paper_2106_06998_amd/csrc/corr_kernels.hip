@@ -736,34 +736,63 @@ __global__ __launch_bounds__(64) void expand_kernel(const float *__restrict__ T,
     }
 }
 
-// ---------------------------------------------------------------------------
-// Second pass in one launch (Algorithm 1 backward step 4, Eq. (6) step (iii), on the partial sums of
-// step 3): a workgroup owns four consecutive output channels (one 16-byte element per column) of one
-// kernel offset.  It first sums the S partial tiles of its slab T[og, j0 .. j0+JC, 4mq .. 4mq+3] in a
-// fixed order (16 interleaved chains per thread, chains and thread groups combined in a fixed tree: the
-// result does not depend on timing) into LDS; the slab of a tile is one run of JC elements, so a wave
-// reads whole cache lines.  Then
-//   dW[m,n,og] = (1/r) sum_j Z[n,j] T[og,j,m]
-// on the vector ALUs: Z goes through LDS in tiles of 128 input channels x 64 probes (read with
-// coalesced loads, rows padded so that a lane can read its row 16 bytes at a time without bank
-// conflicts), a thread owns one input channel and two of the four output channels.  MODE 0: Z from
-// memory (the caller's, or the one the workgroups of the correlation launch redrew from the seed,
-// Alg. 1 backward step 2); MODE 2: exact gradient, dW[m,n,og] = T[og,n,m] (then grid.z cuts the input
-// channels into chunks of JC).  Offsets are counted over `nsets` sets of partial tiles stored back to
-// back (volumetric layers: one set per kernel-depth offset), og = set * K2 + o, K2T = nsets * K2.
-// The grid's first extent is a multiple of 8, so the workgroups that write the K2T offsets of one
-// (m, n) run of dW share an L2, which merges their 4-byte stores.
-// ---------------------------------------------------------------------------
-constexpr int kP2Rows = 128;          // input channels per Z tile
-constexpr int kP2Cols = 64;           // probes per Z tile
-constexpr int kP2Stride = kP2Cols + 4;  // floats per staged row: 4 * odd, rows of 16-byte reads fall on distinct banks
-
-template <int MODE>
-__global__ __launch_bounds__(kThreads) void pass2_kernel(const f32x4 *__restrict__ part, const float *__restrict__ Z,
-                                                         float *__restrict__ dW, int S, int K2, int K2T, int JP, int MQ, int JC,
-                                                         int C_out, int C_in, int r, int nnz_norm, int z_vec)
+// Fixed-order sum of the tiles first, first + step, ... < S of one 16-byte element (p points at the element in
+// tile 0, tiles are `tile` elements apart): NC interleaved chains (NC loads in flight per thread: the tiles were
+// written by other compute units and come from beyond the L2), combined in a fixed tree.
+template <int NC> __device__ inline f32x4 chain_sum(const f32x4 *p, int first, int step, int S, size_t tile)
 {
-    extern __shared__ f32x4 p2_lds[];   // slab [JC], then the thread groups' sums [NG][NE] (few-element slabs only), then the Z tile
+    f32x4 c[NC];
+#pragma unroll
+    for (int i = 0; i < NC; ++i) c[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    int k = first;
+    for (; k + (NC - 1) * step < S; k += NC * step) {   // NC tiles per trip, every load issued before the first sum
+        f32x4 v[NC];
+#pragma unroll
+        for (int i = 0; i < NC; ++i) v[i] = p[(size_t)(k + i * step) * tile];
+#pragma unroll
+        for (int i = 0; i < NC; ++i) c[i] += v[i];
+    }
+    if (k < S) {   // the last, shorter trip (chain i keeps taking tile k + i * step)
+        f32x4 v[NC];
+#pragma unroll
+        for (int i = 0; i < NC; ++i) v[i] = (k + i * step < S) ? p[(size_t)(k + i * step) * tile] : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < NC; ++i) c[i] += v[i];
+    }
+#pragma unroll
+    for (int w = NC / 2; w >= 1; w >>= 1)
+#pragma unroll
+        for (int i = 0; i < w; ++i) c[i] += c[i + w];
+    return c[0];
+}
+
+// The same for an element with at most NC tiles to take: one trip, no running sums
+template <int NC> __device__ inline f32x4 once_sum(const f32x4 *p, int first, int step, int S, size_t tile)
+{
+    f32x4 v[NC];
+#pragma unroll
+    for (int i = 0; i < NC; ++i) v[i] = (first + i * step < S) ? p[(size_t)(first + i * step) * tile] : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int w = NC / 2; w >= 1; w >>= 1)
+#pragma unroll
+        for (int i = 0; i < w; ++i) v[i] += v[i + w];
+    return v[0];
+}
+
+// ---------------------------------------------------------------------------
+// Second pass of the exact gradient in one launch: a workgroup owns four consecutive output channels (one
+// 16-byte element per column) of one kernel offset and JC input channels.  It sums the S partial tiles of its
+// slab T[og, j0 .. j0+JC, 4mq .. 4mq+3] in a fixed order (16 interleaved chains per thread, chains and thread
+// groups combined in a fixed tree: the result does not depend on timing) into LDS; the slab of a tile is one
+// run of JC elements, so a wave reads whole cache lines.  Then dW[m,n,og] = T[og,n,m], a transposed store.
+// Offsets are counted over `nsets` sets of partial tiles stored back to back (volumetric layers: one set per
+// kernel-depth offset), og = set * K2 + o, K2T = nsets * K2.  The grid's first extent is a multiple of 8, so
+// the workgroups that write the K2T offsets of one (m, n) run of dW share an L2, which merges their 4-byte stores.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void pass2_exact_kernel(const f32x4 *__restrict__ part, float *__restrict__ dW, int S, int K2,
+                                                               int K2T, int JP, int MQ, int JC, int C_out, int C_in)
+{
+    extern __shared__ f32x4 p2_lds[];   // slab [JC], then the thread groups' sums [NG][NE] (few-element slabs only)
     const int tid = threadIdx.x;
     const int mq = blockIdx.x;
     if (mq >= MQ) return;   // (the grid is padded to a multiple of 8 workgroups per offset)
@@ -774,20 +803,74 @@ __global__ __launch_bounds__(kThreads) void pass2_kernel(const f32x4 *__restrict
     const f32x4 *base = part + (size_t)set * S * tile + ((size_t)o * MQ + mq) * JP + j0;
     const int NG = NE >= kThreads ? 1 : kThreads / NE;   // groups of threads that share the tiles of an element
     f32x4 *red = p2_lds + NE;
-    float *zs = reinterpret_cast<float *>(red + (NG > 1 ? NG * NE : 0));
 
-    // ---- Z tile (n0 .., jb ..) -> registers (8 x 16 bytes per thread) -> LDS; entries past C_in or r are zero
-    const int nl = tid & (kP2Rows - 1), h = tid >> 7;   // phase 2: input channel inside the tile, pair of output channels
-    f32x4 zr[8];
-    auto load_z = [&](int n0, int jb) {
-        if constexpr (MODE != 0) return;
+    if (NG == 1) {
+        for (int e = tid; e < NE; e += kThreads) p2_lds[e] = chain_sum<16>(base + e, 0, 1, S, tile);
+    } else {
+        const int gi = tid / NE, e = tid - gi * NE;
+        if (gi < NG) red[gi * NE + e] = chain_sum<16>(base + e, gi, NG, S, tile);
+        __syncthreads();
+        if (tid < NE) {
+            f32x4 t = red[tid];
+            for (int q = 1; q < NG; ++q) t += red[q * NE + tid];
+            p2_lds[tid] = t;
+        }
+    }
+    __syncthreads();
+    const float *slab = reinterpret_cast<const float *>(p2_lds);   // [JC][4]: dW[4mq .. 4mq+3, j0.., og] transposed
+    for (int e = tid; e < JC * 4; e += kThreads) {
+        const int mi = e & 3, j = e >> 2;
+        const int m = 4 * mq + mi, n = j0 + j;
+        if (m < C_out && n < C_in) dW[((size_t)m * C_in + n) * K2T + og] = slab[e];
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Second pass of the estimate in one launch, expansion on the matrix cores: a workgroup of 16 waves owns QW
+// consecutive quads of output channels of one kernel offset.  Its threads request a block of rows of Z (whole
+// rows, consecutive lanes consecutive 16 bytes), sum the S partial tiles of the slab
+// T[og, :, 4 QW mg .. + 4 QW - 1] in a fixed order (chain_sum<8>: with 1024 threads that is 128 KB in flight per
+// compute unit; the QW quads are one run of QW * JP elements of a tile) into LDS, put the rows of Z into LDS
+// (row pitch = 4 * odd words: the 64 lanes of a B operand, 16 rows x 4 consecutive probes, fall on distinct
+// banks), and each wave multiplies the slab (A operand of the 16x16x4 instruction, rows = output channels,
+// 16 - 4 QW of them zero) with its tiles of 16 input channels:
+//   dW[m,n,og] = (1/r) sum_j Z[n,j] T[og,j,m]      (or 1 / nnz(Z_n), Eq. (8))
+// A lane ends up with 4 output channels of one input channel.  Layers with more input channels than one block
+// of rows holds (NR rows, at most 4 x 16 bytes per thread) take further blocks in turn.  Grid: (quad groups
+// padded to a multiple of 8, offsets): the workgroups that write the K2T offsets of one (m, n) run of dW then
+// share an L2, which merges their 4-byte stores.
+// ---------------------------------------------------------------------------
+constexpr int kP2Threads = 1024;
+
+template <int QW>
+__global__ __launch_bounds__(kP2Threads) void pass2_mfma_kernel(const f32x4 *__restrict__ part, const float *__restrict__ Z,
+                                                                float *__restrict__ dW, int S, int K2, int K2T, int JP, int MQ,
+                                                                int C_out, int C_in, int r, int nnz_norm, int z_vec, int NR, int ZS)
+{
+    extern __shared__ f32x4 p2_lds[];   // slab [QW][JP], then the thread groups' sums [NG][NE] (few-element slabs only) and, after them, rows of Z [NR][ZS]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, q4 = lane >> 4;
+    const int mg = blockIdx.x;
+    if (mg * QW >= MQ) return;   // (padding of the grid)
+    const int og = blockIdx.y, set = og / K2, o = og - set * K2;
+    const int NE = QW * JP;
+    const size_t tile = (size_t)K2 * MQ * JP;   // 16-byte elements of one partial tile
+    const f32x4 *base = part + (size_t)set * S * tile + ((size_t)o * MQ + (size_t)mg * QW) * JP;
+    const int NG = NE >= kP2Threads ? 1 : kP2Threads / NE;
+    f32x4 *red = p2_lds + NE;
+    float *zs = reinterpret_cast<float *>(red);   // (the groups' sums are dead by then)
+    const int r4 = (r + 3) >> 2;   // 16-byte elements of a row of Z
+
+    // ---- rows n0 .. n0 + NR - 1 of Z -> registers -> LDS; entries past C_in or r are zero
+    f32x4 zr[4];
+    auto load_z = [&](int n0) {
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            const int e = q * kThreads + tid;         // element (row, 4 probes) of the tile
-            const int row = e >> 4, c4 = (e & 15) * 4;
-            const int n = n0 + row, j = jb + c4;
+        for (int q = 0; q < 4; ++q) {
+            const int e = q * kP2Threads + tid;
+            const int row = e / r4, j = (e - row * r4) * 4;
+            const int n = n0 + row;
             f32x4 v = {0.f, 0.f, 0.f, 0.f};
-            if (n < C_in) {
+            if (row < NR && n < C_in) {
                 const float *src = Z + (size_t)n * r + j;
                 if (z_vec && j + 3 < r) {
                     v = *reinterpret_cast<const f32x4 *>(src);
@@ -802,98 +885,76 @@ __global__ __launch_bounds__(kThreads) void pass2_kernel(const f32x4 *__restrict
         }
     };
     auto store_z = [&]() {
-        if constexpr (MODE != 0) return;
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            const int e = q * kThreads + tid;
-            *reinterpret_cast<f32x4 *>(zs + (e >> 4) * kP2Stride + (e & 15) * 4) = zr[q];
+        for (int q = 0; q < 4; ++q) {
+            const int e = q * kP2Threads + tid;
+            const int row = e / r4, j = (e - row * r4) * 4;
+            if (row < NR) *reinterpret_cast<f32x4 *>(zs + row * ZS + j) = zr[q];
         }
     };
-    load_z(0, 0);   // in flight while the partial tiles are summed
+    load_z(0);   // in flight while the partial tiles are summed
 
-    // ---- fixed-order sum over the S partial tiles.  An element's tiles are taken in 16 interleaved chains (16
-    // loads in flight per thread: the tiles were written by other compute units and come from beyond the L2);
-    // few-element slabs also spread the tiles of an element over NG groups of threads.
-    auto chain_sum = [&](const f32x4 *p, int first, int step) {
-        f32x4 c[16];
-#pragma unroll
-        for (int i = 0; i < 16; ++i) c[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-        int k = first;
-        for (; k + 15 * step < S; k += 16 * step) {   // 16 tiles per trip, every load issued before the first sum
-            f32x4 v[16];
-#pragma unroll
-            for (int i = 0; i < 16; ++i) v[i] = p[(size_t)(k + i * step) * tile];
-#pragma unroll
-            for (int i = 0; i < 16; ++i) c[i] += v[i];
-        }
-        if (k < S) {   // the last, shorter trip (chain i keeps taking tile k + i * step)
-            f32x4 v[16];
-#pragma unroll
-            for (int i = 0; i < 16; ++i) v[i] = (k + i * step < S) ? p[(size_t)(k + i * step) * tile] : f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int i = 0; i < 16; ++i) c[i] += v[i];
-        }
-#pragma unroll
-        for (int w = 8; w >= 1; w >>= 1)
-#pragma unroll
-            for (int i = 0; i < w; ++i) c[i] += c[i + w];
-        return c[0];
-    };
+    const bool once = (S + NG - 1) / NG <= 16;   // every thread's tiles fit one trip
     if (NG == 1) {
-        for (int e = tid; e < NE; e += kThreads) p2_lds[e] = chain_sum(base + e, 0, 1);
+        for (int e = tid; e < NE; e += kP2Threads)
+            p2_lds[e] = once ? once_sum<16>(base + e, 0, 1, S, tile) : chain_sum<8>(base + e, 0, 1, S, tile);
     } else {
         const int gi = tid / NE, e = tid - gi * NE;
-        if (gi < NG) red[gi * NE + e] = chain_sum(base + e, gi, NG);
+        if (gi < NG) red[gi * NE + e] = once ? once_sum<16>(base + e, gi, NG, S, tile) : chain_sum<8>(base + e, gi, NG, S, tile);
         __syncthreads();
         if (tid < NE) {
             f32x4 t = red[tid];
             for (int q = 1; q < NG; ++q) t += red[q * NE + tid];
             p2_lds[tid] = t;
         }
+        __syncthreads();   // the rows of Z go where the groups' sums were
     }
     store_z();
     __syncthreads();
-    const float *slab = reinterpret_cast<const float *>(p2_lds);   // [JC][4]
+    const float *slab = reinterpret_cast<const float *>(p2_lds);   // [QW][JP][4]
 
-    if constexpr (MODE == 2) {
-        // exact gradient: the slab is dW[4mq .. 4mq+3, j0.., og] transposed
-        for (int e = tid; e < JC * 4; e += kThreads) {
-            const int mi = e & 3, j = e >> 2;
-            const int m = 4 * mq + mi, n = j0 + j;
-            if (m < C_out && n < C_in) dW[((size_t)m * C_in + n) * K2T + og] = slab[e];
+    const bool a_on = l16 < 4 * QW;                                       // A operand: output channel l16 of the group
+    const int arow = ((a_on ? l16 >> 2 : 0) * JP) * 4 + (l16 & 3);
+    for (int n0 = 0; n0 < C_in; n0 += NR) {
+        if (n0 > 0) {
+            load_z(n0);
+            __syncthreads();   // every wave is done with the rows before
+            store_z();
+            __syncthreads();
         }
-    } else {
-        const int m = 4 * mq + 2 * h;
-        for (int n0 = 0; n0 < C_in; n0 += kP2Rows) {
-            float acc0 = 0.f, acc1 = 0.f;
+        for (int t = wave; t * 16 < NR && n0 + t * 16 < C_in; t += kP2Threads / 64) {
+            const float *zrow = zs + (t * 16 + l16) * ZS;
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
             int cnt = 0;
-            for (int jb = 0; jb < r; jb += kP2Cols) {
-                if (n0 + jb > 0) {   // (the first tile is already there)
-                    load_z(n0, jb);
-                    __syncthreads();   // every thread is done with the tile before
-                    store_z();
-                    __syncthreads();
-                }
-                const int jn = r - jb < kP2Cols ? r - jb : kP2Cols;
-                const float *zrow = zs + nl * kP2Stride;
-                for (int j = 0; j < jn; j += 4) {   // (a row's entries past r are zero)
-                    const f32x4 z = *reinterpret_cast<const f32x4 *>(zrow + j);
+            for (int jc = 0; jc < r; jc += 64) {
+                float at[16], bz[16];
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const float *t = slab + (size_t)(jb + j + q) * 4 + 2 * h;   // same address in every lane of a half
-                        const float tq0 = (j + q < jn) ? t[0] : 0.f, tq1 = (j + q < jn) ? t[1] : 0.f;
-                        acc0 = fmaf(z[q], tq0, acc0);
-                        acc1 = fmaf(z[q], tq1, acc1);
-                        cnt += z[q] != 0.0f ? 1 : 0;
-                    }
+                for (int k = 0; k < 16; ++k) {
+                    const int j = jc + 4 * k + q4;
+                    at[k] = (a_on && j < JP) ? slab[arow + j * 4] : 0.f;
+                    bz[k] = j < 4 * r4 ? zrow[j] : 0.f;
+                }
+#pragma unroll
+                for (int k = 0; k < 16; ++k) {
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(at[k], bz[k], acc, 0, 0, 0);
+                    cnt += bz[k] != 0.0f ? 1 : 0;
                 }
             }
+            // D tile: lane (n, g) holds output channels 4g .. 4g+3 of the group for input channel n
+            const int n = n0 + t * 16 + l16;
             float inv_r = 1.0f / (float)r;
-            if (nnz_norm) inv_r = cnt > 0 ? 1.0f / (float)cnt : 0.0f;
-            const int n = n0 + nl;
-            if (n < C_in) {
-                if (m < C_out) dW[((size_t)m * C_in + n) * K2T + og] = acc0 * inv_r;
-                if (m + 1 < C_out) dW[((size_t)(m + 1) * C_in + n) * K2T + og] = acc1 * inv_r;
+            if (nnz_norm) {   // non-zero entries of row n: the four lanes that share l16 hold a quarter of the row each
+                int c = cnt;
+                c += __shfl_xor(c, 16);
+                c += __shfl_xor(c, 32);
+                inv_r = c > 0 ? 1.0f / (float)c : 0.0f;
+            }
+            if (n < C_in && q4 < QW) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int m = 4 * (mg * QW + q4) + v;
+                    if (m < C_out) dW[((size_t)m * C_in + n) * K2T + og] = acc[v] * inv_r;
+                }
             }
         }
     }
@@ -1194,43 +1255,72 @@ hipError_t launch_reduce_raw(const float *part, float *T, int S, int E4, hipStre
     return hipGetLastError();
 }
 
+// Quads of output channels per workgroup of pass2_mfma_kernel: as many (of 4, 2, 1) as still leave half of the compute
+// units a workgroup (a workgroup reads the whole of Z; a compute unit holds one workgroup of 16 waves at a time)
+static int pass2_quads(int MQ, int K2T)
+{
+    for (int q = 4; q > 1; q >>= 1)
+        if (MQ % q == 0 && (long long)K2T * (MQ / q) >= 128) return q;
+    return 1;
+}
+
 bool reduce_expand_fused(const CorrParams &P, bool have_z, bool exact, int C_in, int r, int dist)
 {
-    // One workgroup per (offset, four output channels) reads the S partial tiles of its slab, K2 * MP / 4 workgroups in
-    // all.
     const int mode = env_int("XCONV_FUSED_PASS2", -1);   // tests: 0 takes the two-launch route (launch_reduce, launch_expand)
     if (mode == 0) return false;
     if (P.MP % 4 != 0) return false;
-    if (!exact && P.JP > 1024) return false;   // (the slab of all probe columns sits in LDS: 16 KB at most)
+    if (!exact && P.JP > 1024) return false;   // (the slab of all probe columns sits in LDS)
     if (mode == 1) return true;
-    // Every workgroup also reads the whole of Z, and a compute unit turns memory requests around at a limited rate:
-    // with more slabs than compute units the busiest unit sets the time (measured on 576 slabs: 27 us against 18 us for
-    // the two launches, whose many small workgroups spread evenly).
-    return (long long)P.K2 * (P.MP / 4) <= 256;
+    // One round of workgroups: a compute unit turns memory requests around at a limited rate, so with more workgroups
+    // than compute units the busiest unit sets the time and the two launches, whose many small workgroups spread
+    // evenly, win (measured on 576 workgroups: 25 us against 19 us).
+    const int MQ = P.MP / 4;
+    return (long long)P.K2 * (MQ / (exact ? 1 : pass2_quads(MQ, P.K2))) <= 256;
 }
 
 hipError_t launch_reduce_expand(const CorrParams &P, const float *Z, bool exact, float *dW, int C_in, int r, bool nnz_norm, int dist,
                                 uint64_t seed, int nsets, hipStream_t st)
 {
-    // slab of JC probe columns (or input channels) x 4 output channels per workgroup; the estimate needs all columns
-    int JC = P.JP;
-    if (exact)   // chunks of at most 256 input channels that divide the padded channel count (a multiple of 16)
-        for (JC = P.JP < 256 ? P.JP : 256; P.JP % JC != 0; JC -= 16) {}
-    const int NE = JC;
-    const int NG = NE >= kThreads ? 1 : kThreads / NE;
-    const size_t lds = (size_t)NE * 16 + (NG > 1 ? (size_t)NG * NE * 16 : 0) + (exact ? 0 : (size_t)kP2Rows * kP2Stride * sizeof(float));
     const int MQ = P.MP / 4;
-    const dim3 grid((unsigned)round_up(MQ, 8), (unsigned)(nsets * P.K2), (unsigned)(exact ? P.JP / JC : 1));
     const int K2T = nsets * P.K2;
     const f32x4 *part = reinterpret_cast<const f32x4 *>(P.part);
     if (exact) {
-        hipLaunchKernelGGL(pass2_kernel<2>, grid, dim3(kThreads), lds, st, part, nullptr, dW, P.S, P.K2, K2T, P.JP, MQ, JC, P.C_out, C_in,
-                           r, 0, 0);
+        // slab of JC input channels x 4 output channels per workgroup: chunks of at most 256 input channels that
+        // divide the padded channel count (a multiple of 16)
+        int JC = P.JP < 256 ? P.JP : 256;
+        for (; P.JP % JC != 0; JC -= 16) {}
+        const int NE = JC;
+        const int NG = NE >= kThreads ? 1 : kThreads / NE;
+        const size_t lds = (size_t)NE * 16 + (NG > 1 ? (size_t)NG * NE * 16 : 0);
+        const dim3 grid((unsigned)round_up(MQ, 8), (unsigned)K2T, (unsigned)(P.JP / JC));
+        hipLaunchKernelGGL(pass2_exact_kernel, grid, dim3(kThreads), lds, st, part, dW, P.S, P.K2, K2T, P.JP, MQ, JC, P.C_out, C_in);
     } else {
+        int QW = env_int("XCONV_PASS2_QW", pass2_quads(MQ, K2T));
+        if ((QW != 1 && QW != 2 && QW != 4) || MQ % QW != 0) QW = 1;
+        const int r4 = ceil_div(r, 4);
+        const int ZS = 4 * (r4 + (r4 % 2 == 0 ? 1 : 2));         // words per staged row of Z: 4 * odd
+        int NR = (4 * kP2Threads / r4) & ~15;                      // rows per block: 4 x 16 bytes per thread
+        if (NR > round_up(C_in, 16)) NR = round_up(C_in, 16);
+        const int NE = QW * P.JP, NG = NE >= kP2Threads ? 1 : kP2Threads / NE;
+        const size_t red = NG > 1 ? (size_t)NG * NE * 16 : 0, zs = (size_t)NR * ZS * sizeof(float);
+        const size_t lds = (size_t)NE * 16 + (red > zs ? red : zs);
         // rows of Z are read 16 bytes at a time where every row starts on such a boundary
         const int z_vec = (r % 4 == 0 && (reinterpret_cast<uintptr_t>(Z) & 15u) == 0) ? 1 : 0;
-        hipLaunchKernelGGL(pass2_kernel<0>, grid, dim3(kThreads), lds, st, part, Z, dW, P.S, P.K2, K2T, P.JP, MQ, JC, P.C_out, C_in, r,
-                           nnz_norm ? 1 : 0, z_vec);
+        const dim3 grid((unsigned)round_up(MQ / QW, 8), (unsigned)K2T);
+#define XC_P2M(Q)                                                                                                        \
+    {                                                                                                                    \
+        static bool done = false;                                                                                        \
+        if (!done) {                                                                                                     \
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pass2_mfma_kernel<Q>),                      \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);                  \
+            if (e != hipSuccess) return e;                                                                               \
+            done = true;                                                                                                 \
+        }                                                                                                                \
+        hipLaunchKernelGGL(pass2_mfma_kernel<Q>, grid, dim3(kP2Threads), lds, st, part, Z, dW, P.S, P.K2, K2T, P.JP, MQ, \
+                           P.C_out, C_in, r, nnz_norm ? 1 : 0, z_vec, NR, ZS);                                           \
+    }
+        if (QW == 4) XC_P2M(4) else if (QW == 2) XC_P2M(2) else XC_P2M(1)
+#undef XC_P2M
     }
     return hipGetLastError();
 }

@@ -418,7 +418,7 @@ xconv_status xconv_dw_estimate(const xconv_desc *d, const void *dY_dev, const vo
         XC_LAUNCH(K_CORR, st, launch_corr(d->dtype, P, st));
     }
     if (fused) {
-        XC_LAUNCH(K_REDUCE, st, launch_reduce_expand(P, Z, false, dW_dev, d->C_in, d->r, d->keep_q15 != 0, probe_code(d), d->seed, 1, st));
+        XC_LAUNCH(K_PASS2, st, launch_reduce_expand(P, Z, false, dW_dev, d->C_in, d->r, d->keep_q15 != 0, probe_code(d), d->seed, 1, st));
         return XCONV_OK;
     }
     XC_LAUNCH(K_REDUCE, st, launch_reduce(P, st, zw, d->C_in * d->r, probe_code(d), d->seed));
@@ -531,7 +531,7 @@ xconv_status exact_impl(const xconv_desc *d, const void *dY_dev, const void *X_d
         XC_LAUNCH(K_CORR, st, launch_corr(d->dtype, P, st));
     }
     if (reduce_expand_fused(P, false, true, d->C_in, d->r, 0)) {
-        XC_LAUNCH(K_REDUCE, st, launch_reduce_expand(P, nullptr, true, dW_dev, d->C_in, d->r, false, 0, 0, 1, st));
+        XC_LAUNCH(K_PASS2, st, launch_reduce_expand(P, nullptr, true, dW_dev, d->C_in, d->r, false, 0, 0, 1, st));
         return XCONV_OK;
     }
     XC_LAUNCH(K_REDUCE, st, launch_reduce(P, st));
@@ -759,7 +759,7 @@ xconv_status xconv3d_dw_estimate(const xconv3d_desc *v, const void *dY_dev, cons
     // one reduction for all kernel-depth offsets; its spare workgroups redraw Z[s] for the expansion
     P.part = part0;
     if (fused) {
-        XC_LAUNCH(K_REDUCE, st, launch_reduce_expand(P, Z, false, dW_dev, d->C_in, d->r, d->keep_q15 != 0, probe_code(d), d->seed, v->kD, st));
+        XC_LAUNCH(K_PASS2, st, launch_reduce_expand(P, Z, false, dW_dev, d->C_in, d->r, d->keep_q15 != 0, probe_code(d), d->seed, v->kD, st));
         return XCONV_OK;
     }
     XC_LAUNCH(K_REDUCE, st, launch_reduce(P, st, zw, d->C_in * d->r, probe_code(d), d->seed, T3, v->kD));
@@ -824,7 +824,7 @@ xconv_status xconv3d_dw_exact(const xconv3d_desc *v, const void *dY_dev, const v
     }
     P.part = part0;
     if (reduce_expand_fused(P, false, true, d->C_in, d->r, 0)) {
-        XC_LAUNCH(K_REDUCE, st, launch_reduce_expand(P, nullptr, true, dW_dev, d->C_in, d->r, false, 0, 0, v->kD, st));
+        XC_LAUNCH(K_PASS2, st, launch_reduce_expand(P, nullptr, true, dW_dev, d->C_in, d->r, false, 0, 0, v->kD, st));
         return XCONV_OK;
     }
     XC_LAUNCH(K_REDUCE, st, launch_reduce(P, st, nullptr, 0, 0, 0, T3, v->kD));
@@ -1149,6 +1149,7 @@ const char *xconv_prof_kernel_name(int id)
     case K_CORR: return "corr_kernel";
     case K_REDUCE: return "reduce_partials_kernel";
     case K_EXPAND: return "expand_kernel";
+    case K_PASS2: return "pass2_kernel";
     case K_TO_NHWC: return "to_nhwc_kernel";
     case K_UNPACK: return "unpack_kernel";
     case K_REPACK: return "repack_planes_kernel";

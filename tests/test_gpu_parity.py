@@ -348,6 +348,21 @@ def test_second_pass_routes(fused, monkeypatch):
         test_block_sparse_probes(e, True)
 
 
+# The one-launch second pass gives a workgroup 1, 2 or 4 quads of output channels (chosen by the layer's size) and takes Z
+# in blocks of rows: every width, a probe count that is not a multiple of 4 and more input channels than one block holds.
+@pytest.mark.parametrize("quads", ["1", "2", "4"])
+def test_second_pass_quad_widths(quads, monkeypatch):
+    monkeypatch.setenv("XCONV_FUSED_PASS2", "1")
+    monkeypatch.setenv("XCONV_PASS2_QW", quads)
+    for e in (("p2-blocks", 3, 136, 24, 8, 8, 3, 1, 1, 250, "gaussian", "f32"),
+              ("p2-odd-r", 5, 40, 72, 9, 12, 3, 1, 1, 13, "rademacher", "f32"),
+              WS_EDGE[1], ROW_EDGE[7]):
+        run_edge(e)
+    for e in (SPARSE[1], SPARSE[4]):
+        test_block_sparse_probes(e, False)
+        test_block_sparse_probes(e, True)
+
+
 # ---------------------------------------------------------------------------
 # block-sparse probing vectors with the 1/nnz scaling (Eq. (7), Eq. (8))
 # ---------------------------------------------------------------------------
