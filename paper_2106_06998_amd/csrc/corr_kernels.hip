@@ -39,6 +39,11 @@
 #include "common.h"
 #include "launch.h"
 
+// Timing experiments only (never defined in the shipped build): bit 5 leaves time stamps of the first thread in the partial tile.
+#ifndef XCONV_CORR_DBG
+#define XCONV_CORR_DBG 0
+#endif
+
 namespace xc {
 
 constexpr int kMaxOff = 9;
@@ -135,6 +140,8 @@ __global__ __launch_bounds__(kThreads, ((DT == XCONV_F32 && MT <= 2) ? 2 : 1)) v
     using elem_t = typename std::conditional<F32, float, uint16_t>::type;
 
 #define XC_TRACE()
+    unsigned long long ts_[8];
+    if constexpr (XCONV_CORR_DBG & 32) { ts_[0] = __builtin_amdgcn_s_memrealtime(); ts_[1] = __builtin_readcyclecounter(); }
     __builtin_amdgcn_s_setprio(2);
     extern __shared__ uint4 lds_raw[];
     unit_t *lds_a0 = reinterpret_cast<unit_t *>(lds_raw);          // dY tile
@@ -581,6 +588,7 @@ __global__ __launch_bounds__(kThreads, ((DT == XCONV_F32 && MT <= 2) ? 2 : 1)) v
         // starves the vector, LDS and load instructions of the other waves on its SIMD (those of
         // the second workgroup on the CU, which is staging while this one multiplies).  Everything
         // but the MFMA loop runs at a raised priority so that staging slips in between MFMAs.
+        if constexpr (XCONV_CORR_DBG & 32) { if (step == t_begin) { ts_[2] = __builtin_amdgcn_s_memrealtime(); ts_[3] = __builtin_readcyclecounter(); } }
         __builtin_amdgcn_s_setprio(0);
         compute_step(sp);
         __builtin_amdgcn_s_setprio(2);
@@ -588,6 +596,7 @@ __global__ __launch_bounds__(kThreads, ((DT == XCONV_F32 && MT <= 2) ? 2 : 1)) v
         sp = spn;
     }
     lds_barrier();
+    if constexpr (XCONV_CORR_DBG & 32) { ts_[4] = __builtin_amdgcn_s_memrealtime(); ts_[5] = __builtin_readcyclecounter(); }
 
     // ---- reduce the WK k-split waves through LDS, then write the partial tile --
     // One buffer per (wm, wj) group; waves wk = 1..WK-1 hand their tiles to wave
@@ -619,6 +628,14 @@ __global__ __launch_bounds__(kThreads, ((DT == XCONV_F32 && MT <= 2) ? 2 : 1)) v
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) *reinterpret_cast<f32x4 *>(dst + (size_t)16 * mt * P.JP) = acc[mt][o];   // 16 rows = four channel quads
             }
+        }
+    }
+    if constexpr (XCONV_CORR_DBG & 32) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        ts_[6] = __builtin_amdgcn_s_memrealtime(); ts_[7] = __builtin_readcyclecounter();
+        if (tid == 0 && t_begin < t_end) {
+            unsigned long long *d = reinterpret_cast<unsigned long long *>(P.part + (size_t)blockIdx.x * P.K2 * P.JP * P.MP + tile_index(o_first, jb, m0, P.JP, P.MP));
+            for (int q = 0; q < 8; ++q) d[q] = ts_[q];
         }
     }
 }
