@@ -1281,7 +1281,7 @@ static int pass2_quads(int MQ, int K2T)
     return 1;
 }
 
-bool reduce_expand_fused(const CorrParams &P, bool have_z, bool exact, int C_in, int r, int dist)
+bool reduce_expand_fused(const CorrParams &P, bool have_z, bool exact, int C_in, int r, int dist, int nsets)
 {
     const int mode = env_int("XCONV_FUSED_PASS2", -1);   // tests: 0 takes the two-launch route (launch_reduce, launch_expand)
     if (mode == 0) return false;
@@ -1291,8 +1291,8 @@ bool reduce_expand_fused(const CorrParams &P, bool have_z, bool exact, int C_in,
     // One round of workgroups: a compute unit turns memory requests around at a limited rate, so with more workgroups
     // than compute units the busiest unit sets the time and the two launches, whose many small workgroups spread
     // evenly, win (measured on 576 workgroups: 25 us against 19 us).
-    const int MQ = P.MP / 4;
-    return (long long)P.K2 * (MQ / (exact ? 1 : pass2_quads(MQ, P.K2))) <= 256;
+    const int MQ = P.MP / 4, K2T = nsets * P.K2;
+    return (long long)K2T * (MQ / (exact ? 1 : pass2_quads(MQ, K2T))) <= 256;
 }
 
 hipError_t launch_reduce_expand(const CorrParams &P, const float *Z, bool exact, float *dW, int C_in, int r, bool nnz_norm, int dist,

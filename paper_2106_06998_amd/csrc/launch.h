@@ -70,7 +70,7 @@ hipError_t launch_reduce_raw(const float *part, float *T, int S, int E4, hipStre
 // The second pass in one launch: fixed-order sum of the S partial tiles and the expansion by Z / r or, for the exact
 // gradient, the transposed store, straight into dW [C_out, C_in, nsets*K2].  reduce_expand_fused says whether this launch applies (otherwise launch_reduce
 // followed by launch_expand do the same in two).
-bool reduce_expand_fused(const CorrParams &P, bool have_z, bool exact, int C_in, int r, int dist);
+bool reduce_expand_fused(const CorrParams &P, bool have_z, bool exact, int C_in, int r, int dist, int nsets = 1);
 hipError_t launch_reduce_expand(const CorrParams &P, const float *Z, bool exact, float *dW, int C_in, int r, bool nnz_norm, int dist,
                                 uint64_t seed, int nsets, hipStream_t st);
 // dW[m,n,o] = (1/r) * sum_j Z[n,j] * T[o,j,m]   (Z != nullptr)

@@ -737,7 +737,7 @@ xconv_status xconv3d_dw_estimate(const xconv3d_desc *v, const void *dY_dev, cons
         P.dY = dy_slices;
     }
     float *part0 = reinterpret_cast<float *>(ws + zb);
-    const bool fused = reduce_expand_fused(P, Z_dev != nullptr, false, d->C_in, d->r, probe_code(d));
+    const bool fused = reduce_expand_fused(P, Z_dev != nullptr, false, d->C_in, d->r, probe_code(d), v->kD);
     for (int kz = 0; kz < v->kD; ++kz) {
         // (the first correlation launch also redraws Z[s] for the fused second pass)
         P.zout = E.Wp.zout = (fused && zw && kz == 0) ? zw : nullptr;
