@@ -131,6 +131,41 @@ def kernel_times(xb, fn, steps, warmup):
     return {k: v[0] / v[1] for k, v in acc.items()}, wall
 
 
+def machine_rates(xb, dev):
+    """What this machine delivers to plain reference kernels, next to the published peaks the fractions are stated against:
+    a 256 MiB device copy (bytes read + written per second), and the library's matrix-instruction issue loop
+    (xconv_diag_mfma_rate) for fp32 and fp16."""
+    import torch
+    src = torch.full((64 * 2 ** 20,), 1.0, dtype=torch.float32, device=dev)
+    dst = torch.empty_like(src)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    for _ in range(3):
+        dst.copy_(src)
+    ev[0].record()
+    for _ in range(10):
+        dst.copy_(src)
+    ev[1].record()
+    torch.cuda.synchronize()
+    copy_gbps = 10 * 2 * src.numel() * 4 / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9
+    del src, dst
+    out = {"hbm_copy_gbps": copy_gbps, "hbm_copy": "256 MiB torch device copy, read + written bytes, 10 copies"}
+    scratch = xb.alloc_bytes(xb.XCONV_DIAG_OUT_BYTES, dev)
+    for dt, iters in (("f16", 4000), ("f32", 2000)):
+        for _ in range(2):
+            xb.xconv_diag_mfma_rate(dt, iters, scratch)
+        torch.cuda.synchronize()
+        xb.xconv_prof_enable(True)
+        flops = 0.0
+        for _ in range(5):
+            flops = xb.xconv_diag_mfma_rate(dt, iters, scratch)
+        torch.cuda.synchronize()
+        xb.xconv_prof_enable(False)
+        ms = [m for kid, m in xb.xconv_prof_collect() if xb.xconv_prof_kernel_name(kid) == "mfma_rate_kernel"]
+        out["mfma_issue_tflops_" + dt] = flops / (sum(ms) / len(ms) * 1e-3) / 1e12
+    out["mfma_issue"] = "xconv_diag_mfma_rate: 4 independent 32x32 accumulators per wave, 2 waves per SIMD, random operand bits"
+    return out
+
+
 def nsets_for(cfg):
     s = elem_bytes(cfg.dtype)
     per_set = (cfg.B * cfg.C_in * cfg.H * cfg.W + cfg.B * cfg.C_out * cfg.Ho * cfg.Wo + cfg.B * cfg.r * cfg.H * cfg.W) * s
@@ -649,6 +684,17 @@ def main():
         "probe_roofline": probe_roofline_of(cfg, res),
         "detail": res,
     }
+    # the same fractions against what plain reference kernels reach on this machine (context: the headline fractions above are
+    # against the published peaks)
+    mr = machine_rates(xb, dev)
+    line["machine"] = mr
+
+    def against_measured(rf, pf, dtype):
+        ref = mr["hbm_copy_gbps"] if rf["bound"] == "hbm" else mr["mfma_issue_tflops_" + ("f32" if dtype == "f32" else "f16")]
+        rf["frac_of_measured"] = rf["achieved"] / ref
+        pf["frac_of_measured"] = pf["achieved"] / mr["hbm_copy_gbps"]
+
+    against_measured(line["roofline"], line["probe_roofline"], cfg.dtype)
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(cfg, L.host)
     del L
@@ -663,6 +709,7 @@ def main():
             r["workload"] = workload_string(c, False)
             r["roofline"] = roofline_of(c, r)
             r["probe_roofline"] = probe_roofline_of(c, r)
+            against_measured(r["roofline"], r["probe_roofline"], c.dtype)
             per.append(r)
         line["per_config"] = per
     print(json.dumps(line))

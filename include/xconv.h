@@ -310,6 +310,17 @@ size_t xconv_relu_mask_bytes(long long n);
 xconv_status xconv_relu_fwd(int dtype, const void *X_dev, void *Y_dev, void *mask_dev, long long n, void *stream);
 xconv_status xconv_relu_bwd(int dtype, const void *dY_dev, const void *mask_dev, void *dX_dev, long long n, void *stream);
 
+/* Reference measurement for the roofline figures (not part of the method): enqueues a loop of `iters` x 4
+ * independent 32x32 matrix instructions per wave (32x32x16 for the 16-bit types, 32x32x2 for fp32) on every
+ * SIMD of the device, with operands of random bits, and stores the number of floating-point operations of
+ * the launch in *flops (host; may be null).  Timed by the caller (xconv_prof_* or its own events), flops /
+ * time is the matrix-core rate the chip sustains at the clock it holds.  out_dev: device scratch of at least
+ * XCONV_DIAG_OUT_BYTES, 4-byte aligned, caller-owned (one float per wave is written; the values mean
+ * nothing).  XCONV_EINVAL for a bad dtype, iters outside 1 .. 2^24 or a null or misaligned pointer,
+ * XCONV_EWORKSPACE for too small a buffer. */
+#define XCONV_DIAG_OUT_BYTES 8192
+xconv_status xconv_diag_mfma_rate(int dtype, int iters, float *out_dev, size_t out_bytes, double *flops, void *stream);
+
 /* Per-kernel timing with HIP events recorded on the launch stream.  While
  * enabled, every kernel the library enqueues is bracketed by two events.
  * xconv_prof_collect synchronises those events, writes up to `max` records

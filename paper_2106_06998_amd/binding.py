@@ -120,6 +120,8 @@ def lib():
         L.xconv_pixel_indep_probe_fwd.argtypes = [P, vp, vp, vp, sz, vp]
         L.xconv_pixel_indep_dw_estimate.restype = i32
         L.xconv_pixel_indep_dw_estimate.argtypes = [P, vp, vp, vp, vp, sz, vp]
+        L.xconv_diag_mfma_rate.restype = i32
+        L.xconv_diag_mfma_rate.argtypes = [i32, i32, vp, sz, ctypes.POINTER(ctypes.c_double), vp]
         L.xconv_prof_enable.restype = None
         L.xconv_prof_enable.argtypes = [i32]
         L.xconv_prof_collect.restype = i32
@@ -305,6 +307,17 @@ def xconv_pixel_probe_fwd(desc, X_dev, Xbar_dev, ws_dev, stream=None):
 def xconv_pixel_dw_estimate(desc, dY_dev, Xbar_dev, dW_dev, ws_dev, stream=None):
     _check(lib().xconv_pixel_dw_estimate(ctypes.byref(desc), _ptr(dY_dev), _ptr(Xbar_dev), _ptr(dW_dev), _ptr(ws_dev),
                                          _nbytes(ws_dev), _stream(stream)), "xconv_pixel_dw_estimate")
+
+
+XCONV_DIAG_OUT_BYTES = 8192
+
+
+def xconv_diag_mfma_rate(dtype, iters, out_dev, stream=None):
+    """Enqueues the matrix-instruction issue loop; returns the floating-point operations of the launch."""
+    flops = ctypes.c_double(0.0)
+    _check(lib().xconv_diag_mfma_rate(int(DTYPES[dtype]) if isinstance(dtype, str) else int(dtype), int(iters), _ptr(out_dev),
+                                      _nbytes(out_dev), ctypes.byref(flops), _stream(stream)), "xconv_diag_mfma_rate")
+    return flops.value
 
 
 def xconv_prof_enable(on):

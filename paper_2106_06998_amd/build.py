@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libxconv.so")
 OBJDIR = os.path.join(HERE, "_build")
-SOURCES = ["xconv_api.hip", "probe_kernels.hip", "corr_kernels.hip", "corr_ws_kernels.hip", "corr_row_kernels.hip", "corr_ws32_kernels.hip", "pixel_kernels.hip", "relu_kernels.hip", "conv_kernels.hip"]
+SOURCES = ["xconv_api.hip", "probe_kernels.hip", "corr_kernels.hip", "corr_ws_kernels.hip", "corr_row_kernels.hip", "corr_ws32_kernels.hip", "pixel_kernels.hip", "relu_kernels.hip", "conv_kernels.hip", "diag_kernels.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # XCONV_SANITIZE_HOST=1: a second library whose host code (descriptor checks, plans, size arithmetic) is built under
@@ -42,7 +42,7 @@ def _compile(src):
 
 def build(verbose=True):
     os.makedirs(OBJDIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(9, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(_compile, SOURCES))
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     if SANITIZE_HOST:

@@ -33,7 +33,8 @@ enum KernelId {
     K_RELU = 14,
     K_CONV = 15,
     K_PASS2 = 16,
-    K_COUNT = 17
+    K_DIAG = 17,
+    K_COUNT = 18
 };
 
 // Where the probe output of a voxel goes in Xt.  sd == 0: plain order, pixel `first` of the

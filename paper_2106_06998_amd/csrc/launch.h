@@ -110,4 +110,9 @@ hipError_t launch_pixel_fwd_indep(int dtype, const void *X, const void *Zimg, fl
 hipError_t launch_pixel_fwd(int dtype, const void *X, const void *Zimg, float *part, float *Xbar, long long K, int B, int r,
                             hipStream_t st);
 
+// diag_kernels.hip: matrix-instruction issue loop (two workgroups per compute unit), one float per wave into `out`
+constexpr int kMfmaRateGrid = 512;
+double mfma_rate_flops(int dtype, int iters);
+hipError_t launch_mfma_rate(int dtype, float *out, int iters, hipStream_t st);
+
 }  // namespace xc

@@ -1116,6 +1116,17 @@ xconv_status xconv_relu_bwd(int dtype, const void *dY_dev, const void *mask_dev,
     return XCONV_OK;
 }
 
+xconv_status xconv_diag_mfma_rate(int dtype, int iters, float *out_dev, size_t out_bytes, double *flops, void *stream)
+{
+    if (dtype < XCONV_F32 || dtype > XCONV_F16 || iters < 1 || iters > (1 << 24) || !out_dev) return XCONV_EINVAL;
+    if (out_bytes < XCONV_DIAG_OUT_BYTES) return XCONV_EWORKSPACE;
+    if (reinterpret_cast<uintptr_t>(out_dev) & 3u) return XCONV_EINVAL;
+    if (flops) *flops = mfma_rate_flops(dtype, iters);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    XC_LAUNCH(K_DIAG, st, launch_mfma_rate(dtype, out_dev, iters, st));
+    return XCONV_OK;
+}
+
 void xconv_prof_enable(int on)
 {
     std::lock_guard<std::mutex> lk(g_prof_mu);
@@ -1150,6 +1161,7 @@ const char *xconv_prof_kernel_name(int id)
     case K_REDUCE: return "reduce_partials_kernel";
     case K_EXPAND: return "expand_kernel";
     case K_PASS2: return "pass2_kernel";
+    case K_DIAG: return "mfma_rate_kernel";
     case K_TO_NHWC: return "to_nhwc_kernel";
     case K_UNPACK: return "unpack_kernel";
     case K_REPACK: return "repack_planes_kernel";

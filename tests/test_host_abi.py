@@ -364,6 +364,18 @@ def test_sign_relu_sizes_and_argument_checks():
     assert L.xconv_relu_bwd(2, one, one, one, (1 << 40) + 1, None) == xb.XCONV_EUNSUPPORTED
 
 
+def test_matrix_rate_diagnostic_checks_its_arguments():
+    L = xb.lib()
+    one = ctypes.c_void_p(4096)          # never dereferenced: validation fails first
+    big = xb.XCONV_DIAG_OUT_BYTES
+    assert L.xconv_diag_mfma_rate(3, 10, one, big, None, None) == xb.XCONV_EINVAL          # dtype
+    assert L.xconv_diag_mfma_rate(0, 0, one, big, None, None) == xb.XCONV_EINVAL           # iters
+    assert L.xconv_diag_mfma_rate(0, (1 << 24) + 1, one, big, None, None) == xb.XCONV_EINVAL
+    assert L.xconv_diag_mfma_rate(2, 10, None, big, None, None) == xb.XCONV_EINVAL
+    assert L.xconv_diag_mfma_rate(2, 10, ctypes.c_void_p(4098), big, None, None) == xb.XCONV_EINVAL
+    assert L.xconv_diag_mfma_rate(2, 10, one, big - 1, None, None) == xb.XCONV_EWORKSPACE
+
+
 def test_host_planning_is_thread_safe():
     # size and plan queries from several threads at once (an autograd backward thread beside the forward thread)
     # agree with the answers of one thread
