@@ -30,7 +30,7 @@
 
 // Timing experiments only (never defined in the shipped build): bit 0 consumers issue no MFMA, bit 1 no
 // fragment reads, bit 3 producers issue no global loads, bit 4 no LDS writes or transposes, bit 5 the first
-// consumer wave leaves time stamps in its partial tile.
+// consumer wave and the first producer thread leave time stamps in the partial tile.
 #ifndef XCONV_ROW_DBG
 #define XCONV_ROW_DBG 0
 #endif
@@ -322,6 +322,8 @@ __global__ __launch_bounds__(kWsThreads) void corr_row_kernel(const WsParams P)
             if (wave == 0 && lane == 0) {
                 unsigned long long *d = reinterpret_cast<unsigned long long *>(P.part + (size_t)blockIdx.x * P.K2 * P.JP * P.MP + tile_index(0, jb, m0, P.JP, P.MP));
                 for (int q = 0; q < 8; ++q) d[q] = ts_[q];
+                const unsigned long long *l = reinterpret_cast<const unsigned long long *>(row_lds + 2 * P.a_units + P.NRING * P.b_row_units);
+                for (int q = 2; q < 7; ++q) d[8 + q] = l[q];   // cycle counter: producers' first loads issued .. first barrier passed
             }
         }
     } else {
@@ -491,8 +493,11 @@ __global__ __launch_bounds__(kWsThreads) void corr_row_kernel(const WsParams P)
             WsPos pr = ws_pos_of(P, t_begin);   // row-step whose tiles are written next
             pr.u = P.NSUB - 1;                  // (ws_advance then moves on to the next row)
             WsPos p1 = ws_advance(P, pr);       // the row-step after it
+            if constexpr (XCONV_ROW_DBG & 32) { ts_[2] = __builtin_readcyclecounter(); }
             issue_dy(pr, true, sdy[0]);
+            if constexpr (XCONV_ROW_DBG & 32) { ts_[3] = __builtin_readcyclecounter(); }
             prime(pr, IC<3>{});
+            if constexpr (XCONV_ROW_DBG & 32) { ts_[4] = __builtin_readcyclecounter(); }
             issue_xt(p1, nrows > 1, sxt);
             issue_dy(p1, nrows > 1, sdy[1]);
             // One barrier per dY tile: it hands tile (row, u) and whatever was written to the ring meanwhile to the
@@ -507,9 +512,17 @@ __global__ __launch_bounds__(kWsThreads) void corr_row_kernel(const WsParams P)
                 }
                 // first tile of the row: dY of this row is the oldest of the loads in flight
                 wait8(IC<16>{}, sd);
+                if constexpr (XCONV_ROW_DBG & 32) { if (row == 0) ts_[5] = __builtin_readcyclecounter(); }
                 transpose(sd);
                 write_dy(0, tile & 1, sd);
                 ws_barrier();
+                if constexpr (XCONV_ROW_DBG & 32) {
+                    if (row == 0 && p == 0) {   // producer stamps go through spare LDS words to the consumer that writes them out
+                        ts_[6] = __builtin_readcyclecounter();
+                        unsigned long long *l = reinterpret_cast<unsigned long long *>(row_lds + 2 * P.a_units + P.NRING * P.b_row_units);
+                        for (int q = 2; q < 7; ++q) l[q] = ts_[q];
+                    }
+                }
                 if (P.NSUB == 2) write_dy(1, (tile + 1) & 1, sd);
                 // the row that the next row-step adds to the ring (its slot was last read by the row-step before
                 // this one), then the loads two row-steps ahead into the registers that just became free
@@ -523,7 +536,7 @@ __global__ __launch_bounds__(kWsThreads) void corr_row_kernel(const WsParams P)
                 issue_dy(p2, row + 2 < nrows, sd);
                 pr = p1;
                 p1 = p2;
-                if (P.NSUB == 2) ws_barrier();
+                if (P.NSUB == 2) ws_barrier();   // (right behind write_dy(1) it was measured: the loop grows by 9 %)
             };
             for (int row = 0; row < nrows; row += 2) {
                 row_step(row, sdy[0]);
@@ -547,7 +560,7 @@ static const size_t kRowLdsLimit = 160 * 1024;
 
 size_t corr_row_lds_bytes(const WsParams &P)
 {
-    return ((size_t)2 * P.a_units + (size_t)P.NRING * P.b_row_units) * 16;
+    return ((size_t)2 * P.a_units + (size_t)P.NRING * P.b_row_units) * 16 + ((XCONV_ROW_DBG & 32) ? 64 : 0);
 }
 
 bool plan_corr_row(WsParams &P, int dtype, int B, int C_out, int H, int W, int kH, int kW, int sh, int sw, int ph, int pw, int CS)
