@@ -485,10 +485,10 @@ __global__ __launch_bounds__(kWsThreads) void corr_row_kernel(const WsParams P)
 
         if (NI > 0) {
             const int nrows = t_end - t_begin;
-            // Loads in flight per thread, oldest first, at the top of a row-step r (steady state):
-            //   dY of row r (set r & 1, waited for now), A of row r + 1, dY of row r + 1.
-            // The tile of the row's second sub-step is written half a row-step later together with the
-            // added row of row-step r + 1, after which A of row r + 2 and dY of row r + 2 go out.
+            // At the top of a row-step r (steady state) dY of row r sits transposed in set r & 1, and the loads in flight
+            // per thread are, oldest first, A of row r + 1 and dY of row r + 1 (set (r + 1) & 1).  After the row's first
+            // barrier the second sub-step's tile is written, then the added row of row-step r + 1, then dY of row r + 1 is
+            // transposed in its registers; behind the row's second barrier A and dY of row r + 2 go out.
             u32x4r sdy[2][8], sxt[8];
             WsPos pr = ws_pos_of(P, t_begin);   // row-step whose tiles are written next
             pr.u = P.NSUB - 1;                  // (ws_advance then moves on to the next row)
@@ -500,20 +500,20 @@ __global__ __launch_bounds__(kWsThreads) void corr_row_kernel(const WsParams P)
             if constexpr (XCONV_ROW_DBG & 32) { ts_[4] = __builtin_readcyclecounter(); }
             issue_xt(p1, nrows > 1, sxt);
             issue_dy(p1, nrows > 1, sdy[1]);
+            wait8(IC<16>{}, sdy[0]);
+            if constexpr (XCONV_ROW_DBG & 32) { ts_[5] = __builtin_readcyclecounter(); }
+            transpose(sdy[0]);
             // One barrier per dY tile: it hands tile (row, u) and whatever was written to the ring meanwhile to the
             // consumers, who pass it one k-step before they finish the tile before.  The two register sets of dY take
             // turns row by row; the loop body is written out once per set so that which registers a load lands in
             // never depends on a run-time choice (a copy between its issue and its wait would read them too early).
-            auto row_step = [&](int row, u32x4r (&sd)[8]) {
+            auto row_step = [&](int row, u32x4r (&sd)[8], u32x4r (&sn)[8]) {
                 const int tile = row * P.NSUB;
                 if (row > 0 && pr.y == 0) {
                     ws_barrier();  // the consumers have left the previous run: its ring rows are free
                     prime(pr, IC<1>{});
                 }
-                // first tile of the row: dY of this row is the oldest of the loads in flight
-                wait8(IC<16>{}, sd);
-                if constexpr (XCONV_ROW_DBG & 32) { if (row == 0) ts_[5] = __builtin_readcyclecounter(); }
-                transpose(sd);
+                // first tile of the row (its dY is in `sd`, transposed half a row-step ago)
                 write_dy(0, tile & 1, sd);
                 ws_barrier();
                 if constexpr (XCONV_ROW_DBG & 32) {
@@ -532,15 +532,23 @@ __global__ __launch_bounds__(kWsThreads) void corr_row_kernel(const WsParams P)
                 wait8(IC<8>{}, sxt);
                 transpose(sxt);
                 if (row + 1 < nrows) write_xt(p1, sxt);
+                // dY of the next row-step (the last load in flight): transposed here, in the longer half of the row-step,
+                // so that the path to the next row's first barrier is short
+                wait8(IC<0>{}, sn);
+                transpose(sn);
+                // The barrier of the row's second tile, then the loads two row-steps ahead.  Measured on the C5 layer,
+                // loop cycles per workgroup: loads issued in front of this barrier and dY transposed at the top of its own
+                // row-step 85.7K, loads behind the barrier 83.5K, that and the early transpose 81.9K; the barrier
+                // right behind write_dy(1) 93.4K, the A loads in front of it and the dY loads behind 83.8K.
+                if (P.NSUB == 2) ws_barrier();
                 issue_xt(p2, row + 2 < nrows, sxt);
                 issue_dy(p2, row + 2 < nrows, sd);
                 pr = p1;
                 p1 = p2;
-                if (P.NSUB == 2) ws_barrier();   // (right behind write_dy(1) it was measured: the loop grows by 9 %)
             };
             for (int row = 0; row < nrows; row += 2) {
-                row_step(row, sdy[0]);
-                if (row + 1 < nrows) row_step(row + 1, sdy[1]);
+                row_step(row, sdy[0], sdy[1]);
+                if (row + 1 < nrows) row_step(row + 1, sdy[1], sdy[0]);
             }
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the last (empty) prefetches
         }
