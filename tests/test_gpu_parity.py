@@ -348,6 +348,19 @@ def test_second_pass_routes(fused, monkeypatch):
         test_block_sparse_probes(e, True)
 
 
+# Reference measurement of the benchmark (not part of the method): the launch runs, counts its operations as documented
+# and leaves one finite value per wave.
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+def test_matrix_rate_diagnostic_runs(dtype):
+    say("mfma rate %s" % dtype)
+    out = torch.full((xb.XCONV_DIAG_OUT_BYTES // 4,), float("nan"), dtype=torch.float32, device=DEV)
+    flops = xb.xconv_diag_mfma_rate(dtype, 8, out)
+    torch.cuda.synchronize()
+    per = 2 * 32 * 32 * (2 if dtype == "f32" else 16)
+    assert flops == 512 * 4 * 8 * 4 * per
+    assert bool(torch.isfinite(out).all())
+
+
 # The one-launch second pass gives a workgroup 1, 2 or 4 quads of output channels (chosen by the layer's size) and takes Z
 # in blocks of rows: every width, a probe count that is not a multiple of 4 and more input channels than one block holds.
 @pytest.mark.parametrize("quads", ["1", "2", "4"])
