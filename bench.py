@@ -31,8 +31,8 @@ MEASURED_TRAFFIC = {
     ("C1", "corr_ws32_kernel"): 3.8e6, ("C1", "probe_kernel"): 0.7e6,
     ("C2", "corr_ws32_kernel"): 66.9e6, ("C2", "probe_kernel"): 42.1e6,
     ("C3", "corr_kernel"): 122.9e6, ("C3", "probe_kernel"): 64.5e6,
-    ("C4", "corr_ws32_kernel"): 193.2e6, ("C4", "probe_kernel"): 167.9e6,
-    ("C5", "corr_row_kernel"): 221.9e6, ("C5", "probe_kernel"): 129.7e6,
+    ("C4", "corr_ws32_kernel"): 193.2e6, ("C4", "probe_kernel"): 168.0e6,
+    ("C5", "corr_row_kernel"): 221.9e6, ("C5", "probe_kernel"): 138.9e6,
 }
 
 
