@@ -21,7 +21,10 @@ namespace xc {
 // caches could keep.  Measured event-timed per probe launch: C5 34.0 -> 32.9 us, C4 34.2 -> 31.3, C3 20.8 -> 17.2, C2 13.4 ->
 // 12.0.  The stores of Xt do not carry it: the correlation reads them next (with the hint on the stores as well the
 // correlation got slower); nor do the correlation's loads of dY, whose rows share cache lines with the rows of the next
-// row-step (with the hint the C5 correlation took 69.7 instead of 62.9 us).
+// row-step (with the hint the C5 correlation took 69.7 instead of 62.9 us).  On C5 the planes of 1568 bytes share cache
+// lines between neighbouring tiles and a hinted line is fetched by both (113 instead of 104 MB read); the hint on only
+// the channel rows that are whole lines made the probe another 1.1 us faster but the layer 2 us slower (the correlation
+// behind it pays), so every row takes it.
 __device__ inline uint4 load_x16(const void *p)
 {
     typedef unsigned int u32x4nt __attribute__((ext_vector_type(4)));
