@@ -71,8 +71,10 @@ uint64_t xo_stream_word(uint64_t seed, uint64_t ctr)
     return xo_fin(key + XO_GAMMA * (ctr + 1));
 }
 
-/* dist 0: Rademacher (+1/-1 with probability 1/2 each, from the top bit of
- *         word c*r+j);
+/* dist 0: Rademacher (+1/-1 with probability 1/2 each): entry number
+ *         i = c*r+j takes bit i mod 64 of word i div 64 of the stream, a set
+ *         bit meaning -1 (the 64 bits of a SplitMix64 output are
+ *         independent fair bits, so one word serves 64 entries);
  * dist 1: standard normal by the Box-Muller transform on two 53-bit uniforms
  *         (words 2(c*r+j) and 2(c*r+j)+1), evaluated in double and rounded
  *         to float.
@@ -84,7 +86,8 @@ int xo_probe_matrix(int dist, uint64_t seed, int C_in, int r, float *Z)
         for (int j = 0; j < r; ++j) {
             uint64_t idx = (uint64_t)c * (uint64_t)r + (uint64_t)j;
             if (dist == 0) {
-                Z[idx] = (xo_stream_word(seed, idx) >> 63) ? -1.0f : 1.0f;
+                uint64_t word = xo_stream_word(seed, idx / 64);
+                Z[idx] = ((word >> (idx % 64)) & 1u) ? -1.0f : 1.0f;
             } else if (dist == 1) {
                 uint64_t h1 = xo_stream_word(seed, 2 * idx);
                 uint64_t h2 = xo_stream_word(seed, 2 * idx + 1);

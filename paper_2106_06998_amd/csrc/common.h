@@ -194,7 +194,9 @@ __host__ __device__ inline float probe_entry(const ProbeGen &g, uint64_t idx)
 }
 __host__ __device__ inline float probe_value(const ProbeGen &g, uint64_t idx)
 {
-    if (g.dist == XCONV_RADEMACHER) return (stream_word(g.key, idx) >> 63) ? -1.0f : 1.0f;
+    // +-1: entry idx is bit idx % 64 of word idx / 64 (the bits of a SplitMix64 output are independent fair bits), so one
+    // generator word serves 64 entries and a workgroup can draw a whole matrix from a few hundred words
+    if (g.dist == XCONV_RADEMACHER) return ((stream_word(g.key, idx >> 6) >> (idx & 63)) & 1ull) ? -1.0f : 1.0f;
     // Box-Muller in double on two 53-bit uniforms, u1 in (0,1], u2 in [0,1)
     const double u1 = ((double)(stream_word(g.key, 2ull * idx) >> 11) + 1.0) * 0x1.0p-53;
     const double u2 = (double)(stream_word(g.key, 2ull * idx + 1ull) >> 11) * 0x1.0p-53;

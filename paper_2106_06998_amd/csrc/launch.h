@@ -9,6 +9,8 @@ void host_probe_matrix(int dist, uint64_t seed, int n, float *Z);
 hipError_t launch_gen_z(float *Z, int n, int dist, uint64_t seed, hipStream_t st);
 // nhwc: X is channels-last [B, H, W, C_in] instead of [B, C_in, H, W]
 bool probe_fast_path_ok(int dtype, int C_in, int HW, bool nhwc);
+// the 16-bit probe kernel draws this matrix from (dist, seed) itself, from one generator word per 64 entries
+bool probe_draws_words(int C_in, int r, int dist);
 size_t zpack_bytes(int dtype, int C_in, int r, bool z_exact16);
 hipError_t launch_pack_z(int dtype, const float *Z, void *out, int C_in, int r, bool z_exact16, int dist, uint64_t seed,
                          bool nhwc, hipStream_t st);

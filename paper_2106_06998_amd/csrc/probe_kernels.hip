@@ -325,15 +325,41 @@ template <int DT, int JT, int PT, bool SPLIT, bool NHWC>
 __global__ __launch_bounds__(kThreads, 2) void probe_16_kernel(const uint16_t *__restrict__ X, const float *__restrict__ Z,
                                                             const uint4 *__restrict__ zpack, uint16_t *__restrict__ Xt, int C_in,
                                                             int HW, int r, int CS, int j0, long long ngroups, int ntiles,
-                                                            SliceMap sm, int dist, uint64_t seed)
+                                                            SliceMap sm, int dist, uint64_t seed, int nword)
 {
-    extern __shared__ uint4 zf[];  // [SPLIT?2:1][KK][JT][64] A-operand fragments
+    extern __shared__ uint4 zf[];  // [SPLIT?2:1][KK][JT][64] A-operand fragments, then (nword > 0) the generator words of a +-1 matrix
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int KK = (C_in + 31) >> 5;
     const int nfrag = KK * JT * 64;
     auto stage_z = [&]() {
         if (zpack) {
             for (int e = tid; e < nfrag * (SPLIT ? 2 : 1); e += kThreads) zf[e] = zpack[e];
+        } else if (nword > 0) {
+            // dense +-1 matrix from the seed (Alg. 1 forward step 2): entry i is bit i % 64 of generator word i / 64, so the
+            // workgroup draws the nword words once into LDS and every fragment entry is a bit of one of them
+            const ProbeGen gen = probe_gen(dist, seed);
+            uint64_t *words = reinterpret_cast<uint64_t *>(zf + nfrag * (SPLIT ? 2 : 1));
+            for (int w = tid; w < nword; w += kThreads) words[w] = stream_word(gen.key, (uint64_t)w);
+            __syncthreads();
+            constexpr uint32_t one = DT == XCONV_F16 ? 0x3c00u : 0x3f80u;   // 1.0 in the storage type; the sign bit makes it -1.0
+            // (the table holds at most 2^17 entries: 32-bit entry numbers; bit i % 64 of word i / 64 is bit i % 32 of the
+            // 32-bit half i / 32 of the table)
+            const uint32_t *half = reinterpret_cast<const uint32_t *>(words);
+            for (int e = tid; e < nfrag; e += kThreads) {
+                const int l = e & 63, jt = (e >> 6) % JT, kk = (e >> 6) / JT;
+                const int j = j0 + jmap(jt, l & 15, JT);
+                const int c0 = kk * 32 + 8 * (l >> 4);
+                uint32_t i = (uint32_t)c0 * (uint32_t)r + (uint32_t)j;
+                uint32_t h[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q, i += (uint32_t)r) {
+                    const bool on = j < r && c0 + q < C_in;
+                    const uint32_t bit = (half[on ? (i >> 5) : 0u] >> (i & 31u)) & 1u;
+                    h[q] = on ? (one | (bit << 15)) : 0u;
+                }
+                zf[e] = uint4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+                if constexpr (SPLIT) zf[nfrag + e] = uint4{0u, 0u, 0u, 0u};   // (+-1 is exact in 16 bits: no residue)
+            }
         } else {
             // Z fragments: four entries (32 scalar loads) per thread in flight at a time
             for (int base = 0; base < nfrag; base += 4 * kThreads) {
@@ -719,11 +745,13 @@ static hipError_t launch_probe_16_cfg(const uint16_t *X, const float *Z, const u
 {
     const long long ngroups = NHWC ? npix : npix / PT;
     const int ntiles = (int)(NHWC ? (npix + 16 * PT - 1) / (16 * PT) : (ngroups + 15) / 16);
-    const size_t lds = (size_t)(SPLIT ? 2 : 1) * ceil_div(C_in, 32) * JT * 64 * sizeof(uint4);
+    // a dense +-1 matrix that comes from the seed and has no fragments in scratch is drawn by the workgroups from its generator words
+    const int nword = (!Z && !zpack && probe_draws_words(C_in, r, dist)) ? (int)(((long long)C_in * r + 63) / 64) : 0;
+    const size_t lds = (size_t)(SPLIT ? 2 : 1) * ceil_div(C_in, 32) * JT * 64 * sizeof(uint4) + (size_t)round_up(nword, 2) * 8;
     hipError_t e = set_lds(probe_16_kernel<DT, JT, PT, SPLIT, NHWC>, lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((probe_16_kernel<DT, JT, PT, SPLIT, NHWC>), dim3(probe_grid(ntiles, 2)), dim3(kThreads), lds, st, X, Z, zpack,
-                       Xt, C_in, HW, r, CS, j0, ngroups, ntiles, sm, dist, seed);
+                       Xt, C_in, HW, r, CS, j0, ngroups, ntiles, sm, dist, seed, nword);
     return hipGetLastError();
 }
 
@@ -744,6 +772,13 @@ static hipError_t launch_probe_16_jt(const uint16_t *X, const float *Z, const ui
     }
     if (split) return launch_probe_16_cfg<DT, JT, 4, true, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, sm, dist, seed, st);
     return launch_probe_16_cfg<DT, JT, 4, false, false>(X, Z, zpack, Xt, C_in, HW, r, CS, j0, npix, sm, dist, seed, st);
+}
+
+// Dense +-1 matrices whose generator words (one per 64 entries) fit 16 KB of LDS next to the fragments: the 16-bit probe
+// kernel draws them itself, whatever their size, and no fragment launch is needed.
+bool probe_draws_words(int C_in, int r, int dist)
+{
+    return (dist & 0xff) == XCONV_RADEMACHER && (dist >> 8) == 0 && ((long long)C_in * r + 63) / 64 <= 2048;
 }
 
 bool probe_fast_path_ok(int dtype, int C_in, int HW, bool nhwc)

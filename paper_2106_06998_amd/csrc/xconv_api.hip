@@ -260,6 +260,8 @@ xconv_status probe_impl(const xconv_desc *d, int HW, int HWv, SliceMap sm, const
             const char *v = getenv("XCONV_PROBE_DRAW");   // sweeps: largest Z drawn inside the probe kernel, Rademacher / Gaussian
             const long long lim_r = v ? atoll(v) : 1024, lim_g = v ? atoll(v) : 0;
             if (!Z_dev && (long long)d->C_in * d->r <= (d->probe == XCONV_RADEMACHER ? lim_r : lim_g)) zpack = nullptr;
+            // 16-bit storage: a dense +-1 matrix of any size the kernel's word table holds
+            if (!Z_dev && !v && d->dtype != XCONV_F32 && probe_draws_words(d->C_in, d->r, probe_code(d))) zpack = nullptr;
         }
         if (zpack) XC_LAUNCH(K_PACK_Z, st, launch_pack_z(d->dtype, Z_dev, zpack, d->C_in, d->r, z_exact16, probe_code(d), d->seed, nhwc, st));
         XC_LAUNCH(K_PROBE, st, launch_probe(d->dtype, X_dev, Z_dev, zpack, Xt_dev, d->B, d->C_in, HW, d->r, CS, z_exact16, nhwc, sm,

@@ -52,10 +52,19 @@ def test_rademacher_entries_and_balance():
     assert abs(Z.sum()) < 4.0 * np.sqrt(n)
     assert np.all(np.abs(Z.sum(axis=0)) < 4.5 * np.sqrt(Z.shape[0]))
     assert np.all(np.abs(Z.sum(axis=1)) < 4.5 * np.sqrt(Z.shape[1]))
-    # top bit of the stream word decides the sign
+    # entry number i = c*r + j is bit i mod 64 of stream word i div 64, a set bit meaning -1
     for (c, j) in [(0, 0), (3, 5), (255, 63)]:
-        w = xo.stream_word(3001, c * 64 + j)
-        assert Z[c, j] == (-1.0 if (w >> 63) else 1.0)
+        i = c * 64 + j
+        w = xo.stream_word(3001, i // 64)
+        assert Z[c, j] == (-1.0 if ((w >> (i % 64)) & 1) else 1.0)
+    # a probe count that is not a multiple of 64: words run across the rows
+    Z2 = xo.probe_matrix(xo.RADEMACHER, 77, 9, 24)
+    for i in (0, 23, 24, 63, 64, 100, 215):
+        w = xo.stream_word(77, i // 64)
+        assert Z2.reshape(-1)[i] == (-1.0 if ((w >> (i % 64)) & 1) else 1.0)
+    # no correlation between neighbouring entries, which now share a word: the lag-1 product averages to 0
+    flat = Z.reshape(-1).astype(np.float64)
+    assert abs(np.mean(flat[:-1] * flat[1:])) < 4.0 / np.sqrt(flat.size)
 
 
 def test_gaussian_moments():
