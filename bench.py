@@ -32,7 +32,7 @@ MEASURED_TRAFFIC = {
     ("C2", "corr_ws32_kernel"): 66.9e6, ("C2", "probe_kernel"): 42.1e6,
     ("C3", "corr_kernel"): 122.9e6, ("C3", "probe_kernel"): 64.5e6,
     ("C4", "corr_ws32_kernel"): 193.2e6, ("C4", "probe_kernel"): 168.0e6,
-    ("C5", "corr_row_kernel"): 221.9e6, ("C5", "probe_kernel"): 138.9e6,
+    ("C5", "corr_row_kernel"): 222.1e6, ("C5", "probe_kernel"): 129.5e6,
 }
 
 

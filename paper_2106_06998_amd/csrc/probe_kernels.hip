@@ -12,31 +12,45 @@
 // 16-row MFMA tile are assigned to probe indices so that a lane ends up holding
 // consecutive probe columns of one pixel, which makes the channels-last store a
 // run of 16-byte vectors.
+#include <type_traits>
+
 #include "common.h"
 #include "launch.h"
 
 namespace xc {
 
-// X is read once and never again: its loads carry the non-temporal hint, so that the lines do not displace what the
-// caches could keep.  Measured event-timed per probe launch: C5 34.0 -> 32.9 us, C4 34.2 -> 31.3, C3 20.8 -> 17.2, C2 13.4 ->
-// 12.0.  The stores of Xt do not carry it: the correlation reads them next (with the hint on the stores as well the
-// correlation got slower); nor do the correlation's loads of dY, whose rows share cache lines with the rows of the next
-// row-step (with the hint the C5 correlation took 69.7 instead of 62.9 us).  On C5 the planes of 1568 bytes share cache
-// lines between neighbouring tiles and a hinted line is fetched by both (113 instead of 104 MB read); the hint on only
-// the channel rows that are whole lines made the probe another 1.1 us faster but the layer 2 us slower (the correlation
-// behind it pays), so every row takes it.
-__device__ inline uint4 load_x16(const void *p)
+// X is read once and never again: where a wave's piece of a channel plane is whole cache lines, its loads carry the
+// non-temporal hint, so that the lines do not displace what the caches could keep.  Measured event-timed per probe
+// launch: C4 34.2 -> 31.3 us, C3 20.8 -> 17.2, C2 13.4 -> 12.0.  Planes that are not whole lines (C5: 1568 bytes) share
+// lines between neighbouring tiles, and a hinted line is fetched again by the neighbour (113-120 MB read instead of 104):
+// there the hint made the kernel 1 us faster at first and, once the workgroups drew Z themselves and started less evenly,
+// 1.3 us slower, so the 16-bit kernel loads such planes without it (`nt` = 0; the fp32 kernel always hints: a run-time
+// choice cost it 0.5 us on C2 and C4).  The
+// stores of Xt never carry it: the correlation reads them next (with the hint on the stores the correlation got slower);
+// nor do the correlation's loads of dY, whose rows share cache lines with the rows of the next row-step (with the hint
+// the C5 correlation took 69.7 instead of 62.9 us).
+template <bool NT> __device__ inline uint4 load_x16(const void *p)
 {
-    typedef unsigned int u32x4nt __attribute__((ext_vector_type(4)));
-    const u32x4nt v = __builtin_nontemporal_load(static_cast<const u32x4nt *>(p));
-    return uint4{v.x, v.y, v.z, v.w};
+    if constexpr (NT) {
+        typedef unsigned int u32x4nt __attribute__((ext_vector_type(4)));
+        const u32x4nt v = __builtin_nontemporal_load(static_cast<const u32x4nt *>(p));
+        return uint4{v.x, v.y, v.z, v.w};
+    } else {
+        return *static_cast<const uint4 *>(p);
+    }
 }
-__device__ inline uint2 load_x8(const void *p)
+template <bool NT> __device__ inline uint2 load_x8(const void *p)
 {
-    typedef unsigned int u32x2nt __attribute__((ext_vector_type(2)));
-    const u32x2nt v = __builtin_nontemporal_load(static_cast<const u32x2nt *>(p));
-    return uint2{v.x, v.y};
+    if constexpr (NT) {
+        typedef unsigned int u32x2nt __attribute__((ext_vector_type(2)));
+        const u32x2nt v = __builtin_nontemporal_load(static_cast<const u32x2nt *>(p));
+        return uint2{v.x, v.y};
+    } else {
+        return *static_cast<const uint2 *>(p);
+    }
 }
+// whether the planes of an NCHW tensor (pitch bytes apart) are whole cache lines; channels-last rows always take the hint
+static int probe_nt(bool nhwc, long long pitch_bytes) { return (nhwc || pitch_bytes % 128 == 0) ? 1 : 0; }
 
 void host_probe_matrix(int dist, uint64_t seed, int n, float *Z)
 {
@@ -221,11 +235,11 @@ __global__ __launch_bounds__(kThreads, (JT == 1 ? 4 : 2)) void probe_f32_kernel(
             if constexpr (NHWC) {
                 int c = c0 + 4 * g;
                 c = c < C_in ? c : C_in - 4;
-                sg.v[u] = __builtin_bit_cast(float4, load_x16(tl.xb[u] + c));
+                sg.v[u] = __builtin_bit_cast(float4, load_x16<true>(tl.xb[u] + c));
             } else {
                 int c = c0 + 4 * u + g;
                 c = c < C_in ? c : C_in - 1;
-                sg.v[u] = __builtin_bit_cast(float4, load_x16(tl.xb[0] + (size_t)c * HW));
+                sg.v[u] = __builtin_bit_cast(float4, load_x16<true>(tl.xb[0] + (size_t)c * HW));
             }
         }
     };
@@ -325,7 +339,7 @@ template <int DT, int JT, int PT, bool SPLIT, bool NHWC>
 __global__ __launch_bounds__(kThreads, 2) void probe_16_kernel(const uint16_t *__restrict__ X, const float *__restrict__ Z,
                                                             const uint4 *__restrict__ zpack, uint16_t *__restrict__ Xt, int C_in,
                                                             int HW, int r, int CS, int j0, long long ngroups, int ntiles,
-                                                            SliceMap sm, int dist, uint64_t seed, int nword)
+                                                            SliceMap sm, int dist, uint64_t seed, int nword, int nt)
 {
     extern __shared__ uint4 zf[];  // [SPLIT?2:1][KK][JT][64] A-operand fragments, then (nword > 0) the generator words of a +-1 matrix
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -444,20 +458,25 @@ __global__ __launch_bounds__(kThreads, 2) void probe_16_kernel(const uint16_t *_
             int c = kk * 32 + 8 * g;
             c = c < C_in ? c : C_in - 8;
 #pragma unroll
-            for (int t = 0; t < PT; ++t) sg.cols[t] = load_x16(tl.xb[t] + c);
+            for (int t = 0; t < PT; ++t) sg.cols[t] = load_x16<true>(tl.xb[t] + c);
         } else {
+            auto rows8 = [&](auto ntc) {
+                constexpr bool NT = decltype(ntc)::value;
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                int c = kk * 32 + 8 * g + q;
-                c = c < C_in ? c : C_in - 1;
-                if constexpr (PT == 8) {
-                    const uint4 v = load_x16(tl.xb[0] + (size_t)c * HW);
-                    sg.rows[q][0] = v.x; sg.rows[q][1] = v.y; sg.rows[q][2] = v.z; sg.rows[q][3] = v.w;
-                } else {
-                    const uint2 v = load_x8(tl.xb[0] + (size_t)c * HW);
-                    sg.rows[q][0] = v.x; sg.rows[q][1] = v.y;
+                for (int q = 0; q < 8; ++q) {
+                    int c = kk * 32 + 8 * g + q;
+                    c = c < C_in ? c : C_in - 1;
+                    if constexpr (PT == 8) {
+                        const uint4 v = load_x16<NT>(tl.xb[0] + (size_t)c * HW);
+                        sg.rows[q][0] = v.x; sg.rows[q][1] = v.y; sg.rows[q][2] = v.z; sg.rows[q][3] = v.w;
+                    } else {
+                        const uint2 v = load_x8<NT>(tl.xb[0] + (size_t)c * HW);
+                        sg.rows[q][0] = v.x; sg.rows[q][1] = v.y;
+                    }
                 }
-            }
+            };
+            if (nt) rows8(std::true_type{});
+            else rows8(std::false_type{});
         }
     };
     auto prefetch = [&](Staged (&rg)[D], const Tile &tl) {
@@ -751,7 +770,7 @@ static hipError_t launch_probe_16_cfg(const uint16_t *X, const float *Z, const u
     hipError_t e = set_lds(probe_16_kernel<DT, JT, PT, SPLIT, NHWC>, lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((probe_16_kernel<DT, JT, PT, SPLIT, NHWC>), dim3(probe_grid(ntiles, 2)), dim3(kThreads), lds, st, X, Z, zpack,
-                       Xt, C_in, HW, r, CS, j0, ngroups, ntiles, sm, dist, seed, nword);
+                       Xt, C_in, HW, r, CS, j0, ngroups, ntiles, sm, dist, seed, nword, probe_nt(NHWC, 2LL * (sm.sd ? sm.HWs : HW)));
     return hipGetLastError();
 }
 
