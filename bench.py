@@ -428,8 +428,12 @@ def measure_network(steps, warmup, dev, layers=12, B=128, C=64, HW=32, r=16, dty
     td = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[dtype]
     x = torch.randn(B, C, HW, HW, device=dev).relu_().to(td)
     out = {}
+    # "channel", "multi": everything on the library's kernels (engine="library": forward convolution, input gradient, probe,
+    # estimate); "*_framework_conv": the forward convolution and the input gradient on torch's operators instead
     for name, kw in (("torch", None), ("channel", dict(r=r, mode="channel", relu=True, probe=probe)),
-                     ("multi", dict(r=r, mode="multi", relu=True, probe=probe))):
+                     ("multi", dict(r=r, mode="multi", relu=True, probe=probe)),
+                     ("channel_framework_conv", dict(r=r, mode="channel", relu=True, probe=probe, engine="framework")),
+                     ("multi_framework_conv", dict(r=r, mode="multi", relu=True, probe=probe, engine="framework"))):
         net = build()
         if kw:
             net, n = convert_net(net, **kw)

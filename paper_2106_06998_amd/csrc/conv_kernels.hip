@@ -190,8 +190,11 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
 template <int DT> static hipError_t launch_conv_dt(const ConvGemmParams &P, hipStream_t st)
 {
     const long long tiles = (P.npix + 63) / 64;
-    if (P.Cout > 32) {
+    // tiles of 128, 64 or 32 output channels: the smallest that covers the channels with the fewest empty rows
+    if (P.Cout > 64 && (P.Cout % 128 == 0 || P.Cout % 128 > 64)) {
         hipLaunchKernelGGL((conv_gemm_kernel<DT, 4>), dim3((unsigned)tiles, (unsigned)ceil_div(P.Cout, 128)), dim3(kThreads), 0, st, P);
+    } else if (P.Cout > 32) {
+        hipLaunchKernelGGL((conv_gemm_kernel<DT, 2>), dim3((unsigned)tiles, (unsigned)ceil_div(P.Cout, 64)), dim3(kThreads), 0, st, P);
     } else {
         hipLaunchKernelGGL((conv_gemm_kernel<DT, 1>), dim3((unsigned)tiles, (unsigned)ceil_div(P.Cout, 32)), dim3(kThreads), 0, st, P);
     }
