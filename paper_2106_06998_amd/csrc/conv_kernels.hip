@@ -98,7 +98,12 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
 #pragma unroll
         for (int tp = 0; tp < 2; ++tp) acc[tm][tp] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    for (int o = 0; o < K2; ++o) {
+    // ---- in[ci, src(p, o)] and Wv[co, ci, o] of step (o, c0) -> registers (zero beyond the tensors).  The lanes of a weight
+    // load run along whichever of the two channel indices has the smaller stride in [C_out, C_in, kH, kW] (values 18 or 36
+    // bytes apart for a 3x3 kernel: a few cache lines per instruction; along the other index it would be one line per lane).
+    unit_t bu[UPT];
+    elem_t aw[NAW];
+    auto load_step = [&](int o, int c0) {
         const int ky = o / P.kW, kx = o - ky * P.kW;
         // source pixel of my staging pixel for this offset
         int sy, sx;
@@ -114,53 +119,55 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
         }
         ok = ok && (unsigned)sy < (unsigned)P.Hi && (unsigned)sx < (unsigned)P.Wi;
         const elem_t *src = in_b + (size_t)(ok ? sy : 0) * P.in_sy + (size_t)(ok ? sx : 0) * P.in_sx;
-        for (int c0 = 0; c0 < P.Cin; c0 += KC) {
-            // ---- in[ci, src(p, o)] -> Bs, Wv[co, ci, o] -> As (zero beyond the tensors).  The lanes of a weight load run
-            // along whichever of the two channel indices has the smaller stride in [C_out, C_in, kH, kW] (values 18 or
-            // 36 bytes apart for a 3x3 kernel: a few cache lines per instruction; along the other index it would be one
-            // line per lane).
-            unit_t bu[UPT];
-            elem_t aw[NAW];
 #pragma unroll
-            for (int i = 0; i < UPT; ++i) {
-                const int u = kg + 4 * i;
-                elem_t v[KP];
+        for (int i = 0; i < UPT; ++i) {
+            const int u = kg + 4 * i;
+            elem_t v[KP];
 #pragma unroll
-                for (int e = 0; e < KP; ++e) {
-                    const int c = c0 + u * KP + e;
-                    v[e] = (ok && c < P.Cin) ? src[(size_t)c * P.in_sc] : elem_t(0);
-                }
-                bu[i] = conv_pack<DT>(v);
+            for (int e = 0; e < KP; ++e) {
+                const int c = c0 + u * KP + e;
+                v[e] = (ok && c < P.Cin) ? src[(size_t)c * P.in_sc] : elem_t(0);
             }
+            bu[i] = conv_pack<DT>(v);
+        }
 #pragma unroll
-            for (int i = 0; i < NAW; ++i) {
-                const int idx = tid + kThreads * i;
-                const int cl = w_along_ci ? idx % KC : idx / TM, col = w_along_ci ? idx / KC : idx % TM;
-                const int c = c0 + cl, co = co0 + col;
-                aw[i] = (co < P.Cout && c < P.Cin) ? wv[(size_t)co * P.w_sco + (size_t)c * P.w_sci + o] : elem_t(0);
-            }
-            __syncthreads();   // the previous chunk's fragments have been read
+        for (int i = 0; i < NAW; ++i) {
+            const int idx = tid + kThreads * i;
+            const int cl = w_along_ci ? idx % KC : idx / TM, col = w_along_ci ? idx / KC : idx % TM;
+            const int c = c0 + cl, co = co0 + col;
+            aw[i] = (co < P.Cout && c < P.Cin) ? wv[(size_t)co * P.w_sco + (size_t)c * P.w_sci + o] : elem_t(0);
+        }
+    };
+
+    // Steps (offset, chunk of contraction channels) in turn: the loads of the next step are issued before the matrix
+    // instructions of the current one, whose operands are in LDS by then.
+    int o = 0, c0 = 0;
+    load_step(0, 0);
+    while (o < K2) {
+        __syncthreads();   // the previous step's fragments have been read
 #pragma unroll
-            for (int i = 0; i < UPT; ++i) Bs[kg + 4 * i][sl] = bu[i];
+        for (int i = 0; i < UPT; ++i) Bs[kg + 4 * i][sl] = bu[i];
 #pragma unroll
-            for (int i = 0; i < NAW; ++i) {
-                const int idx = tid + kThreads * i;
-                const int cl = w_along_ci ? idx % KC : idx / TM, col = w_along_ci ? idx / KC : idx % TM;
-                reinterpret_cast<elem_t *>(&As[0][0])[((cl / KP) * TM + col) * KP + cl % KP] = aw[i];
-            }
-            __syncthreads();
+        for (int i = 0; i < NAW; ++i) {
+            const int idx = tid + kThreads * i;
+            const int cl = w_along_ci ? idx % KC : idx / TM, col = w_along_ci ? idx / KC : idx % TM;
+            reinterpret_cast<elem_t *>(&As[0][0])[((cl / KP) * TM + col) * KP + cl % KP] = aw[i];
+        }
+        __syncthreads();
+        c0 += KC;
+        if (c0 >= P.Cin) { c0 = 0; ++o; }
+        if (o < K2) load_step(o, c0);
 #pragma unroll
-            for (int kk = 0; kk < NU / 4; ++kk) {
-                unit_t a[MT], b[2];
+        for (int kk = 0; kk < NU / 4; ++kk) {
+            unit_t a[MT], b[2];
 #pragma unroll
-                for (int tm = 0; tm < MT; ++tm) a[tm] = As[kk * 4 + g][wm * (16 * MT) + tm * 16 + l16];
+            for (int tm = 0; tm < MT; ++tm) a[tm] = As[kk * 4 + g][wm * (16 * MT) + tm * 16 + l16];
 #pragma unroll
-                for (int tp = 0; tp < 2; ++tp) b[tp] = Bs[kk * 4 + g][wp * 32 + tp * 16 + l16];
+            for (int tp = 0; tp < 2; ++tp) b[tp] = Bs[kk * 4 + g][wp * 32 + tp * 16 + l16];
 #pragma unroll
-                for (int tm = 0; tm < MT; ++tm)
+            for (int tm = 0; tm < MT; ++tm)
 #pragma unroll
-                    for (int tp = 0; tp < 2; ++tp) acc[tm][tp] = conv_mfma<DT>(a[tm], b[tp], acc[tm][tp]);
-            }
+                for (int tp = 0; tp < 2; ++tp) acc[tm][tp] = conv_mfma<DT>(a[tm], b[tp], acc[tm][tp]);
         }
     }
 
