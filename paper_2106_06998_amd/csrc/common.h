@@ -277,6 +277,16 @@ __device__ inline void draw_z_slice(float *zout, int nz, int dist, uint64_t seed
     for (int i = wg * (int)blockDim.x + (int)threadIdx.x; i < nz; i += nwg * (int)blockDim.x) zout[i] = probe_entry(gen, (uint64_t)i);
 }
 
+// Workgroups are handed to the chip's 8 dies in turn (workgroup b runs on die b % 8, each with an L2 of
+// its own).  With a grid whose first extent is a multiple of 8 this gives the workgroups of one die neighbouring
+// pieces of work (tiles of the probe, K-splits of the correlation: consecutive output rows of one group of images),
+// so that a cache line which straddles two pieces (planes and rows are not line-aligned) is fetched from memory
+// once, by one L2, instead of once by each of two.
+__device__ inline int xcd_block(int b, int grid)
+{
+    return (grid & 7) == 0 ? (b & 7) * (grid >> 3) + (b >> 3) : b;
+}
+
 // ---- forward convolution / exact input gradient as one implicit GEMM (conv_kernels.hip) ----
 struct ConvGemmParams {
     const void *in;    // activation-like tensor the contraction runs over (X, or dY for the input gradient)

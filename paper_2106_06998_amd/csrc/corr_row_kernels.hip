@@ -89,7 +89,7 @@ __global__ __launch_bounds__(kWsThreads) void corr_row_kernel(const WsParams P)
     const int m0 = tm * P.M_WG;
     const int jb = tj * P.J_WG;
 
-    const int bx = blockIdx.x;
+    const int bx = xcd_block(blockIdx.x, gridDim.x);   // K-split of this workgroup: neighbouring splits on one die (C5: no change)
     const int t_begin = bx * P.SQ + (bx < P.SR ? bx : P.SR);
     const int t_end = t_begin + P.SQ + (bx < P.SR ? 1 : 0);
     const int NI = (t_end - t_begin) * P.NSUB;  // sub-steps of this workgroup
@@ -311,7 +311,7 @@ __global__ __launch_bounds__(kWsThreads) void corr_row_kernel(const WsParams P)
         const int jcol = jb + wj * 32 + l32;
 #pragma unroll
         for (int o = 0; o < 9; ++o) {
-            float *dst = P.part + (size_t)blockIdx.x * P.K2 * P.JP * P.MP + tile_index(o, jcol, m0 + wm * 32 + 4 * g, P.JP, P.MP);
+            float *dst = P.part + (size_t)bx * P.K2 * P.JP * P.MP + tile_index(o, jcol, m0 + wm * 32 + 4 * g, P.JP, P.MP);
 #pragma unroll
             for (int v = 0; v < 4; ++v)   // rows 8v + 4g ..: two channel quads further on
                 *reinterpret_cast<f32x4 *>(dst + (size_t)8 * v * P.JP) = f32x4{acc[o][4 * v], acc[o][4 * v + 1], acc[o][4 * v + 2], acc[o][4 * v + 3]};
@@ -320,7 +320,7 @@ __global__ __launch_bounds__(kWsThreads) void corr_row_kernel(const WsParams P)
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             ts_[6] = __builtin_amdgcn_s_memrealtime(); ts_[7] = __builtin_readcyclecounter();
             if (wave == 0 && lane == 0) {
-                unsigned long long *d = reinterpret_cast<unsigned long long *>(P.part + (size_t)blockIdx.x * P.K2 * P.JP * P.MP + tile_index(0, jb, m0, P.JP, P.MP));
+                unsigned long long *d = reinterpret_cast<unsigned long long *>(P.part + (size_t)bx * P.K2 * P.JP * P.MP + tile_index(0, jb, m0, P.JP, P.MP));
                 for (int q = 0; q < 8; ++q) d[q] = ts_[q];
                 const unsigned long long *l = reinterpret_cast<const unsigned long long *>(row_lds + 2 * P.a_units + P.NRING * P.b_row_units);
                 for (int q = 2; q < 7; ++q) d[8 + q] = l[q];   // cycle counter: producers' first loads issued .. first barrier passed

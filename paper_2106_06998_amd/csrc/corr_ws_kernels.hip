@@ -67,7 +67,7 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
     const int o_first = blockIdx.z * NOFF;
     const int noff = (P.K2 - o_first) < NOFF ? (P.K2 - o_first) : NOFF;
 
-    const int bx = blockIdx.x;
+    const int bx = xcd_block(blockIdx.x, gridDim.x);   // K-split of this workgroup: neighbouring splits on one die (V2: 37.2 -> 34.0 us per launch)
     const int t_begin = bx * P.SQ + (bx < P.SR ? bx : P.SR);
     const int t_end = t_begin + P.SQ + (bx < P.SR ? 1 : 0);
     const int NI = (t_end - t_begin) * P.NSUB;  // sub-steps of this workgroup
@@ -419,7 +419,7 @@ __global__ __launch_bounds__(kWsThreads) void corr_ws_kernel(const WsParams P)
 #pragma unroll
         for (int o = 0; o < NOFF; ++o) {
             if (o < noff) {
-                float *dst = P.part + (size_t)blockIdx.x * P.K2 * P.JP * P.MP + tile_index(o_first + o, jcol, m0 + wm * 32 + 4 * g, P.JP, P.MP);
+                float *dst = P.part + (size_t)bx * P.K2 * P.JP * P.MP + tile_index(o_first + o, jcol, m0 + wm * 32 + 4 * g, P.JP, P.MP);
 #pragma unroll
                 for (int v = 0; v < 4; ++v)   // rows 8v + 4g ..: two channel quads further on
                     *reinterpret_cast<f32x4 *>(dst + (size_t)8 * v * P.JP) = f32x4{acc[o][4 * v], acc[o][4 * v + 1], acc[o][4 * v + 2], acc[o][4 * v + 3]};

@@ -65,15 +65,6 @@ __global__ __launch_bounds__(kThreads) void gen_z_kernel(float *__restrict__ Z, 
     Z[i] = probe_entry(probe_gen(dist, seed), (uint64_t)i);
 }
 
-// Workgroups are handed to the chip's 8 dies in turn (workgroup b runs on die b % 8, each with an L2 of
-// its own).  With a grid that is a multiple of 8 this gives the workgroups of one die neighbouring
-// tiles, so that a cache line which straddles two tiles (planes are not line-aligned) is fetched
-// from memory once, by one L2, instead of once by each of two.
-__device__ inline int xcd_block(int b, int grid)
-{
-    return (grid & 7) == 0 ? (b & 7) * (grid >> 3) + (b >> 3) : b;
-}
-
 // Tile number `it` (0, 1, ...) of wave w out of NW waves, or ntiles when the wave is done.  Every wave takes
 // ntiles / NW tiles, and the remaining ones go to waves spread evenly over the grid (not to the first so many), so that every
 // compute unit, which holds the same number of waves, moves the same number of bytes to within a tile.
