@@ -501,6 +501,11 @@ bool plan_corr_ws32(WsParams &P, int dtype, int B, int C_out, int H, int W, int 
     int target = ws32_env_int("XCONV_WS32_SPLITS", 0);
     if (target <= 0) {
         target = 256 * per_cu / ny;
+        // Two workgroups per compute unit overlap one's start with the other's loop, but with fewer than 8 steps each the
+        // starts and the partial tiles are most of the work: then one workgroup per unit with twice the steps
+        // (C2, 2048 steps: 512 splits 33.1 + 10.7 us for correlation + second pass, 256 splits 32.3 + 9.7 us;
+        // C4, 8192 steps: 95.2 against 103.7 us)
+        if (per_cu == 2 && target >= 2 && P.NS / target < 8) target /= 2;
         if (target < 1) target = 1;
         if (target > P.NS) target = P.NS;
         int bestS = target;

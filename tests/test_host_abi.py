@@ -315,7 +315,7 @@ def test_plan_overrides_are_part_of_the_plan_cache_key(monkeypatch):
     # A plan made under one setting of an XCONV_* override is never handed out under another: the fp32
     # producer/consumer plan of one layer, asked for with one and then with two workgroups per compute unit (the
     # second request would hit the cached first plan if the key were the shape alone), and back again.
-    d = xb.make_desc(128, 64, 64, 32, 32, 3, 1, 1, 16, "f32", "gaussian", 13)
+    d = xb.make_desc(8, 64, 64, 256, 256, 3, 1, 1, 16, "f32", "gaussian", 13)   # (many steps per split: both counts fill the units)
     monkeypatch.setenv("XCONV_WS32_OCC", "1")
     one = xb.xconv_plan_info(d, xb.XCONV_OP_ESTIMATE)
     monkeypatch.setenv("XCONV_WS32_OCC", "2")
