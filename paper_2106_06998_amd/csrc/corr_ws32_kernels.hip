@@ -512,7 +512,7 @@ bool plan_corr_ws32(WsParams &P, int dtype, int B, int C_out, int H, int W, int 
         double best_eff = 0.0;
         for (int S = target; S >= 1 && S >= target * 3 / 4; --S) {
             const double eff = (double)P.NS / ((double)S * ceil_div(P.NS, S)) * ((double)S / target);
-            if (eff > best_eff + 1e-9) { best_eff = eff; bestS = S; }
+            if (eff > best_eff - 1e-9) { best_eff = eff > best_eff ? eff : best_eff; bestS = S; }   // (ties go to the smaller count: as many steps per workgroup, fewer partial tiles)
         }
         target = bestS;
     }
