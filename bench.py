@@ -29,8 +29,8 @@ PEAK_MFMA_TFLOPS = {"f32": 157.3, "bf16": 2500.0, "f16": 2500.0}
 MEASURED_TRAFFIC = {
     # (FETCH_SIZE * 2 + WRITE_SIZE) KiB per launch, profiles/xconv_kernels_<config>.txt
     ("C1", "corr_ws32_kernel"): 3.8e6, ("C1", "probe_kernel"): 0.7e6,
-    ("C2", "corr_ws32_kernel"): 66.9e6, ("C2", "probe_kernel"): 42.1e6,
-    ("C3", "corr_kernel"): 86.4e6, ("C3", "probe_kernel"): 64.5e6,
+    ("C2", "corr_ws32_kernel"): 53.1e6, ("C2", "probe_kernel"): 42.1e6,
+    ("C3", "corr_kernel"): 73.1e6, ("C3", "probe_kernel"): 64.5e6,
     ("C4", "corr_ws32_kernel"): 218.0e6, ("C4", "probe_kernel"): 168.0e6,
     ("C5", "corr_row_kernel"): 218.2e6, ("C5", "probe_kernel"): 129.5e6,
 }
