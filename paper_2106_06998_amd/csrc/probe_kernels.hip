@@ -1159,11 +1159,82 @@ __global__ __launch_bounds__(kThreads) void gen_zimg_kernel(void *__restrict__ o
     else static_cast<uint16_t *>(out)[i] = f32_to_st16<DT>(z);
 }
 
+// The same images for dense +-1 vectors over all channels (indep == 0, n0 == 0), where entry i of Z is bit i % 64 of
+// generator word i / 64: a thread owns 8 consecutive values of an image (16 bytes of 16-bit storage; rows of Z that are
+// r entries apart) and walks the images j0 .. j0 + nj - 1, in which the entries of a row are consecutive bits, so that it
+// draws a word only when a row's bit position crosses into the next one: C5 8 + 8 words for 128 values where the kernel
+// above draws one per value.  LINE = 8 consecutive k (cl_cs == 0; K a multiple of 8) or the 8 channel slots 8s .. 8s + 7 of
+// one pixel (cl_cs > 0, a multiple of 8; slots from C_in on are zero).
+template <int DT>
+__global__ __launch_bounds__(kThreads) void gen_zimg_pm1_kernel(void *__restrict__ out, long long K, int r, int nimg, uint64_t seed,
+                                                                int C_in, int cl_cs, int nj)
+{
+    const long long N = K / C_in;
+    const long long t = (long long)blockIdx.x * kThreads + threadIdx.x;
+    const long long nline = cl_cs == 0 ? K / 8 : N * (cl_cs / 8);
+    if (t >= nline) return;
+    const int j0 = blockIdx.y * nj;
+    const ProbeGen gen = probe_gen(XCONV_RADEMACHER, seed);
+    uint64_t row[8];    // entry number of (k_q, 0), or ~0 for a slot without a channel
+    long long pix = 0;
+    int slot0 = 0;
+    if (cl_cs == 0) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) row[q] = (uint64_t)(8 * t + q) * (uint64_t)r;
+    } else {
+        const int spp = cl_cs / 8;
+        pix = t / spp;
+        slot0 = (int)(t - pix * spp) * 8;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) row[q] = slot0 + q < C_in ? (uint64_t)((long long)(slot0 + q) * N + pix) * (uint64_t)r : ~0ull;
+    }
+    uint64_t word[8], have[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) { have[q] = ~0ull; word[q] = 0; }
+    constexpr uint32_t one16 = DT == XCONV_F16 ? 0x3c00u : 0x3f80u;
+    for (int j = j0; j < j0 + nj && j < nimg; ++j) {
+        uint32_t v[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            v[q] = 0u;
+            if (j < r && row[q] != ~0ull) {
+                const uint64_t i = row[q] + (uint64_t)j;
+                if ((i >> 6) != have[q]) { have[q] = i >> 6; word[q] = stream_word(gen.key, have[q]); }
+                const uint32_t bit = (uint32_t)(word[q] >> (i & 63)) & 1u;
+                v[q] = DT == XCONV_F32 ? (0x3f800000u | (bit << 31)) : (one16 | (bit << 15));
+            }
+        }
+        const long long at = cl_cs == 0 ? (long long)j * K + 8 * t : ((long long)j * N + pix) * cl_cs + slot0;
+        if constexpr (DT == XCONV_F32) {
+            uint4 *o = reinterpret_cast<uint4 *>(static_cast<float *>(out) + at);
+            o[0] = uint4{v[0], v[1], v[2], v[3]};
+            o[1] = uint4{v[4], v[5], v[6], v[7]};
+        } else {
+            *reinterpret_cast<uint4 *>(static_cast<uint16_t *>(out) + at) =
+                uint4{v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16)};
+        }
+    }
+}
+
 // n0, nch: channel window of the images (0, C_in for all channels); with cl_cs > 0 an image has cl_cs channel slots
 // for the channels n0 .. n0 + nch - 1 and N = K / C_in pixels
 hipError_t launch_gen_zimg(int dtype, void *out, long long K, int r, int nimg, int dist, uint64_t seed, int C_in, int cl_cs,
                            int indep, int n0, int nch, hipStream_t st)
 {
+    // dense +-1 vectors over all channels, whole 16-byte lines: one generator word per 64 entries
+    if ((dist & 0xff) == XCONV_RADEMACHER && (dist >> 8) == 0 && !indep && n0 == 0 && nch == C_in &&
+        (cl_cs == 0 ? K % 8 == 0 : cl_cs % 8 == 0) && (reinterpret_cast<uintptr_t>(out) & 15u) == 0) {
+        const long long nline = cl_cs == 0 ? K / 8 : (K / C_in) * (cl_cs / 8);
+        const int nj = 16;   // images per thread: enough threads for the chip, few redrawn words
+        dim3 grid((unsigned)((nline + kThreads - 1) / kThreads), (unsigned)ceil_div(nimg, nj));
+        if (dtype == XCONV_F32)
+            hipLaunchKernelGGL(gen_zimg_pm1_kernel<XCONV_F32>, grid, dim3(kThreads), 0, st, out, K, r, nimg, seed, C_in, cl_cs, nj);
+        else if (dtype == XCONV_BF16)
+            hipLaunchKernelGGL(gen_zimg_pm1_kernel<XCONV_BF16>, grid, dim3(kThreads), 0, st, out, K, r, nimg, seed, C_in, cl_cs, nj);
+        else
+            hipLaunchKernelGGL(gen_zimg_pm1_kernel<XCONV_F16>, grid, dim3(kThreads), 0, st, out, K, r, nimg, seed, C_in, cl_cs, nj);
+        return hipGetLastError();
+    }
     const long long total = cl_cs ? (K / C_in) * nimg * cl_cs : K * nimg;
     dim3 grid((unsigned)((total + kThreads - 1) / kThreads));
     if (dtype == XCONV_F32)
