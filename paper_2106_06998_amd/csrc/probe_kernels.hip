@@ -1225,7 +1225,7 @@ hipError_t launch_gen_zimg(int dtype, void *out, long long K, int r, int nimg, i
     if ((dist & 0xff) == XCONV_RADEMACHER && (dist >> 8) == 0 && !indep && n0 == 0 && nch == C_in &&
         (cl_cs == 0 ? K % 8 == 0 : cl_cs % 8 == 0) && (reinterpret_cast<uintptr_t>(out) & 15u) == 0) {
         const long long nline = cl_cs == 0 ? K / 8 : (K / C_in) * (cl_cs / 8);
-        const int nj = 16;   // images per thread: enough threads for the chip, few redrawn words
+        const int nj = 8;    // images per thread: enough threads for the chip, few redrawn words (C5, 64 images: 13.4 us; 15.0 with 16, 15.4 with 2)
         dim3 grid((unsigned)((nline + kThreads - 1) / kThreads), (unsigned)ceil_div(nimg, nj));
         if (dtype == XCONV_F32)
             hipLaunchKernelGGL(gen_zimg_pm1_kernel<XCONV_F32>, grid, dim3(kThreads), 0, st, out, K, r, nimg, seed, C_in, cl_cs, nj);
