@@ -13,7 +13,7 @@ bool probe_fast_path_ok(int dtype, int C_in, int HW, bool nhwc);
 bool probe_draws_words(int C_in, int r, int dist);
 size_t zpack_bytes(int dtype, int C_in, int r, bool z_exact16);
 hipError_t launch_pack_z(int dtype, const float *Z, void *out, int C_in, int r, bool z_exact16, int dist, uint64_t seed,
-                         bool nhwc, hipStream_t st);
+                         bool nhwc, hipStream_t st, float zmul = 1.0f);
 // sm: where the output goes in Xt (SliceMap{} = plain order; volumetric layers: depth slices in slot order)
 // Z == nullptr and zpack == nullptr: every workgroup draws its fragments of Z from (dist, seed) itself
 hipError_t launch_probe(int dtype, const void *X, const float *Z, const void *zpack, void *Xt, int B, int C_in, int HW, int r,

@@ -100,7 +100,7 @@ __device__ inline int jmap(int jt, int i, int JT) { return (i >> 2) * (4 * JT) +
 __device__ inline int f32_frag_channel(int kq, int g, bool nhwc) { return nhwc ? 16 * (kq >> 2) + 4 * g + (kq & 3) : 4 * kq + g; }
 
 __global__ __launch_bounds__(kThreads) void pack_z_f32_kernel(const float *__restrict__ Z, float *__restrict__ out, int C_in, int r,
-                                                              int NTJ, int KQ4, int dist, uint64_t seed, int nhwc)
+                                                              int NTJ, int KQ4, int dist, uint64_t seed, int nhwc, float zmul)
 {
     const int e = blockIdx.x * kThreads + threadIdx.x;
     if (e >= KQ4 * NTJ * 64) return;
@@ -110,14 +110,14 @@ __global__ __launch_bounds__(kThreads) void pack_z_f32_kernel(const float *__res
     float z = 0.0f;
     if (c < C_in && j < r) {
         const size_t idx = (size_t)c * r + j;
-        z = Z ? Z[idx] : probe_entry(probe_gen(dist, seed), (uint64_t)idx);
+        z = Z ? Z[idx] * zmul : probe_entry(probe_gen(dist, seed), (uint64_t)idx);
     }
     out[(size_t)bi * KQ4 * 4 * 64 + (kq * JTb + jt) * 64 + l] = z;
 }
 
 template <int DT>
 __global__ __launch_bounds__(kThreads) void pack_z_16_kernel(const float *__restrict__ Z, uint4 *__restrict__ out, int C_in, int r,
-                                                             int NTJ, int KK, int split, int dist, uint64_t seed)
+                                                             int NTJ, int KK, int split, int dist, uint64_t seed, float zmul)
 {
     const int e = blockIdx.x * kThreads + threadIdx.x;
     if (e >= KK * NTJ * 64) return;
@@ -135,7 +135,7 @@ __global__ __launch_bounds__(kThreads) void pack_z_16_kernel(const float *__rest
             z[u] = 0.0f;
             if (c < C_in && j < r) {
                 const size_t idx = (size_t)c * r + j;
-                z[u] = Z ? Z[idx] : probe_entry(gen, (uint64_t)idx);
+                z[u] = Z ? Z[idx] * zmul : probe_entry(gen, (uint64_t)idx);
             }
         }
         const uint16_t h0 = f32_to_st16<DT>(z[0]), h1 = f32_to_st16<DT>(z[1]);
@@ -809,23 +809,24 @@ size_t zpack_bytes(int dtype, int C_in, int r, bool z_exact16)
     return (size_t)(z_exact16 ? 1 : 2) * ceil_div(C_in, 32) * ntj * 64 * sizeof(uint4);
 }
 
+// zmul: factor on the entries of a given Z (1 leaves them as they are)
 hipError_t launch_pack_z(int dtype, const float *Z, void *out, int C_in, int r, bool z_exact16, int dist, uint64_t seed,
-                         bool nhwc, hipStream_t st)
+                         bool nhwc, hipStream_t st, float zmul)
 {
     const int ntj = ceil_div(r, 16);
     if (dtype == XCONV_F32) {
         const int KQ4 = ceil_div(C_in, 16) * 4;
         hipLaunchKernelGGL(pack_z_f32_kernel, dim3(ceil_div(KQ4 * ntj * 64, kThreads)), dim3(kThreads), 0, st, Z,
-                           static_cast<float *>(out), C_in, r, ntj, KQ4, dist, seed, nhwc ? 1 : 0);
+                           static_cast<float *>(out), C_in, r, ntj, KQ4, dist, seed, nhwc ? 1 : 0, zmul);
     } else {
         const int KK = ceil_div(C_in, 32);
         const dim3 grid(ceil_div(KK * ntj * 64, kThreads));
         if (dtype == XCONV_BF16)
             hipLaunchKernelGGL(pack_z_16_kernel<XCONV_BF16>, grid, dim3(kThreads), 0, st, Z, static_cast<uint4 *>(out), C_in, r, ntj,
-                               KK, z_exact16 ? 0 : 1, dist, seed);
+                               KK, z_exact16 ? 0 : 1, dist, seed, zmul);
         else
             hipLaunchKernelGGL(pack_z_16_kernel<XCONV_F16>, grid, dim3(kThreads), 0, st, Z, static_cast<uint4 *>(out), C_in, r, ntj,
-                               KK, z_exact16 ? 0 : 1, dist, seed);
+                               KK, z_exact16 ? 0 : 1, dist, seed, zmul);
     }
     return hipGetLastError();
 }

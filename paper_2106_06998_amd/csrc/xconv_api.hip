@@ -234,8 +234,15 @@ namespace {
 
 // Forward probe over B images of HW pixels each; `sm` says where the output goes in Xt
 // (SliceMap{} for 2-D layers: plain order).  `HWv`: extent whose divisibility decides the vector loads.
+// zmul: factor on a given Z, applied where Z is brought into fragment order (callers that pass one check
+// probe_scales_z first)
+bool probe_scales_z(const xconv_desc *d, int HWv, const void *X_dev, const void *ws_dev)
+{
+    return ws_dev && probe_fast_path_ok(d->dtype, d->C_in, HWv, d->layout == XCONV_NHWC) && aligned16(X_dev);
+}
+
 xconv_status probe_impl(const xconv_desc *d, int HW, int HWv, SliceMap sm, const void *X_dev, void *Xt_dev, const float *Z_dev,
-                        void *ws_dev, size_t ws_bytes, hipStream_t st)
+                        void *ws_dev, size_t ws_bytes, hipStream_t st, float zmul = 1.0f)
 {
     if (!X_dev || !Xt_dev) return XCONV_EINVAL;
     if (!aligned16(Xt_dev) || (reinterpret_cast<uintptr_t>(X_dev) & (elem_bytes(d->dtype) - 1)) != 0) return XCONV_EINVAL;
@@ -251,6 +258,7 @@ xconv_status probe_impl(const xconv_desc *d, int HW, int HWv, SliceMap sm, const
     } else if (!Z_dev) {
         return XCONV_EINVAL;
     }
+    if (zmul != 1.0f && !(Z_dev && probe_scales_z(d, HWv, X_dev, ws_dev))) return XCONV_EINVAL;
     if (fast) {
         // With scratch, Z goes to the kernels in fragment order (drawn from the seed when no Z
         // is given); without it, every workgroup gathers its fragments from Z_dev.
@@ -263,7 +271,7 @@ xconv_status probe_impl(const xconv_desc *d, int HW, int HWv, SliceMap sm, const
             // 16-bit storage: a dense +-1 matrix of any size the kernel's word table holds
             if (!Z_dev && !v && d->dtype != XCONV_F32 && probe_draws_words(d->C_in, d->r, probe_code(d))) zpack = nullptr;
         }
-        if (zpack) XC_LAUNCH(K_PACK_Z, st, launch_pack_z(d->dtype, Z_dev, zpack, d->C_in, d->r, z_exact16, probe_code(d), d->seed, nhwc, st));
+        if (zpack) XC_LAUNCH(K_PACK_Z, st, launch_pack_z(d->dtype, Z_dev, zpack, d->C_in, d->r, z_exact16, probe_code(d), d->seed, nhwc, st, zmul));
         XC_LAUNCH(K_PROBE, st, launch_probe(d->dtype, X_dev, Z_dev, zpack, Xt_dev, d->B, d->C_in, HW, d->r, CS, z_exact16, nhwc, sm,
                                             probe_code(d), d->seed, st));
     } else {
@@ -1049,10 +1057,13 @@ xconv_status pixel_dw_estimate(const xconv_desc *d, bool indep, const void *dY_d
     // the images past r are zero like the matching images of L
     XC_LAUNCH(K_GEN_ZIMG, st, launch_gen_zimg(d->dtype, zimg, g.K, d->r, g.CS, probe_code(d), d->seed, d->C_in, round_up(d->C_in, 16),
                                               0, 0, d->C_in, st));
-    XC_LAUNCH(K_SCALE, st, launch_scale(Xbar_dev, xs, d->B * g.R, 1.0f / (float)d->r, st));
     // Lt[p, j] = sum_b dY[b, p] Xbar[b, j] / r, rounded to the storage type (Alg. 1 backward step 3); p runs over
-    // an image of dY in its own order, so the images of L come out in dY's layout
-    s = probe_impl(&g.probe, (int)g.P, (int)g.P, SliceMap{}, dY_dev, lt, xs, pws, g.probe_ws, st);
+    // an image of dY in its own order, so the images of L come out in dY's layout.  The factor 1/r goes on Xbar where
+    // the product brings it into fragment order, or in a launch of its own for the shapes that do not pass there
+    const float inv_r = 1.0f / (float)d->r;
+    const bool zfused = probe_scales_z(&g.probe, (int)g.P, dY_dev, pws);
+    if (!zfused) XC_LAUNCH(K_SCALE, st, launch_scale(Xbar_dev, xs, d->B * g.R, inv_r, st));
+    s = probe_impl(&g.probe, (int)g.P, (int)g.P, SliceMap{}, dY_dev, lt, zfused ? Xbar_dev : xs, pws, g.probe_ws, st, zfused ? inv_r : 1.0f);
     if (s != XCONV_OK) return s;
     XC_LAUNCH(K_REPACK, st, launch_to_nchw(d->dtype, lt, l, 1, g.CS, (int)g.P, (int)g.P, st));
     // dw_i = tr(L T_{-k(i)} Z) (Alg. 1 backward step 4; the factor 1/r is already in L)
